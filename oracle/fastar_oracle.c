@@ -1,0 +1,568 @@
+/*
+ * CPU oracle for the FAST-AR attention hot path.  TEST INFRASTRUCTURE ONLY.
+ *
+ * Plain, slow, step-by-step C.  fp64 accumulation for every floating-point result,
+ * integer arithmetic for every decision.  Nothing here is shared with the GPU
+ * library: no common header, helper, table or constant.  Only tests, the smoke
+ * check and the bench's cpu_baseline leg may call it.
+ *
+ * What each function follows:
+ *   oracle_encode              Sec. 5.1 "Attention as approximate nearest neighbour search":
+ *                              shared low-dimensional random projection (LSH paragraph) of
+ *                              low-bit quantised vectors (quantised-search paragraph, 8 bit).
+ *   oracle_tempcache_compress  Sec. 5.2 "KV cache compression using temporal correspondence":
+ *                              top-1 neighbour of every new token among cached keys, merge when
+ *                              the key similarity passes a threshold, keep the most recent key,
+ *                              mean value and multiplicity (Lemma 1; appendix Eqs. for the group
+ *                              mean value and the biased logit).
+ *   oracle_ann_select_self     Sec. 5.4 (AnnSA): keys a query block attends to, ranked by code score.
+ *   oracle_ann_select_cross    Sec. 5.3 (AnnCA): prompt tokens with a neighbouring query in the block.
+ *   oracle_sparse_attn_fwd     Eq. (1) restricted to the candidate set (Sec. 5.1 display), with the
+ *                              +log m_t logit shift of Lemma 1.
+ *   oracle_recall_density      attention recall / density as defined in the Metrics paragraph.
+ *
+ * Parity pins (tests/test_oracle_*.py): dense softmax attention written independently in
+ * numpy, Lemma 1 on exact duplicates, brute-force nearest neighbours and top-k, closed-form
+ * code values, identity merge, monotonicity in the threshold.  The eviction policy of
+ * oracle_tempcache_compress (what to do when the bounded cache is full) is not in the paper:
+ * it is checked by invariants only and is "parity unpinned".
+ *
+ * dtype: 0 = float32, 1 = bfloat16 stored as uint16 bit patterns.
+ * All arrays are dense row-major with the shapes given at each function.
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+/* ------------------------------------------------------------------ storage helpers */
+
+static float load_f32(const void *p, int dtype, int64_t idx) {
+    if (dtype == 0) return ((const float *)p)[idx];
+    uint32_t u = ((uint32_t)((const uint16_t *)p)[idx]) << 16;
+    float f;
+    memcpy(&f, &u, 4);
+    return f;
+}
+
+static uint16_t f32_to_bf16(float f) { /* nearest, ties to even */
+    uint32_t u;
+    memcpy(&u, &f, 4);
+    u += 0x7FFFu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+}
+
+static void store_val(void *p, int dtype, int64_t idx, double v) {
+    if (dtype == 0)
+        ((float *)p)[idx] = (float)v;
+    else
+        ((uint16_t *)p)[idx] = f32_to_bf16((float)v);
+}
+
+static void copy_row(void *dst, int64_t drow, const void *src, int64_t srow, int d, int dtype) {
+    size_t es = dtype == 0 ? 4 : 2;
+    memcpy((char *)dst + (size_t)drow * d * es, (const char *)src + (size_t)srow * d * es, (size_t)d * es);
+}
+
+static int64_t floor_div(int64_t a, int64_t b) { /* b > 0 */
+    int64_t q = a / b;
+    if (a % b != 0 && a < 0) q -= 1;
+    return q;
+}
+
+static int clampi(int64_t v, int lo, int hi) { return v < lo ? lo : (v > hi ? hi : (int)v); }
+
+/* ------------------------------------------------------------------ encode */
+
+/* Quantise one coordinate to 8 bits: one float32 multiply, round half to even, saturate. */
+static int quant8(float x, float qscale) {
+    volatile float prod = x * qscale; /* volatile: exactly one IEEE single-precision product */
+    float q = rintf(prod);
+    if (q > 127.0f) q = 127.0f;
+    if (q < -127.0f) q = -127.0f;
+    return (int)q;
+}
+
+/* Code of one vector: quantise, project on the +-1 matrix R[d][r], shift down with rounding, saturate. */
+static void encode_vec(const void *x, int dtype, int64_t base, int d, const int8_t *R, int r, float qscale,
+                       int shift, int8_t *code) {
+    for (int j = 0; j < r; ++j) {
+        int64_t y = 0;
+        for (int t = 0; t < d; ++t) y += (int64_t)R[(int64_t)t * r + j] * quant8(load_f32(x, dtype, base + t), qscale);
+        int64_t c = floor_div(y + ((int64_t)1 << (shift - 1)), (int64_t)1 << shift);
+        code[j] = (int8_t)clampi(c, -127, 127);
+    }
+}
+
+/* x [n_vec, d] -> code [n_vec, r] */
+int oracle_encode(const void *x, int dtype, int64_t n_vec, int d, const int8_t *R, int r, float qscale, int shift,
+                  int8_t *code) {
+    if (!x || !R || !code || d <= 0 || r <= 0 || shift < 1) return -1;
+#pragma omp parallel for schedule(static)
+    for (int64_t v = 0; v < n_vec; ++v) encode_vec(x, dtype, v * d, d, R, r, qscale, shift, code + v * r);
+    return 0;
+}
+
+static int64_t dot_i8(const int8_t *a, const int8_t *b, int r) {
+    int64_t s = 0;
+    for (int j = 0; j < r; ++j) s += (int64_t)a[j] * (int64_t)b[j];
+    return s;
+}
+
+/* ------------------------------------------------------------------ TempCache */
+
+/*
+ * One frame of new tokens is merged into the per-head caches, every decision taken against the
+ * cache as it was at entry.
+ *
+ * cache:   K, V [H,C,d] dtype; code [H,C,r]; cnt, stamp [H,C]; len [H]   (updated in place)
+ * new:     K_new, V_new [H,n_new,d]; P_new (probe, NULL => K_new) [H,n_new,d]
+ * cand:    [H,n_cand] slot ids searched for the match (ids outside [0,len) are ignored), NULL => all live
+ * metric:  0 => S = 2 cp.code_j - |code_j|^2 (nearest in code space), 1 => S = cp.code_j
+ * tau2_q16 = rint(tau^2 * 65536); merge iff dot > 0 and dot^2 * 65536 >= tau2_q16 * |a|^2 |b|^2 on the
+ *          8-bit quantised full-width keys a (new) and b (cached)
+ * out:     merge_map [H,n_new] destination slot or -1 (dropped); merged [H,n_new] 0/1;
+ *          stats [H,8] = len', n_merged, n_appended, n_evicted, n_dropped, 0, 0, 0
+ */
+int oracle_tempcache_compress(void *K, void *V, int8_t *code, int32_t *cnt, int32_t *stamp, int32_t *len, int H,
+                              int C, int d, int r, int dtype, const int8_t *R, float qscale, int shift,
+                              const void *K_new, const void *V_new, const void *P_new, int n_new,
+                              const int32_t *cand, int n_cand, int metric, int32_t tau2_q16, int32_t frame_id,
+                              int32_t *merge_map, uint8_t *merged, int32_t *stats) {
+    if (!K || !V || !code || !cnt || !stamp || !len || !R || !K_new || !V_new || !merge_map || !merged || !stats)
+        return -1;
+    if (H <= 0 || C <= 0 || d <= 0 || r <= 0 || n_new < 0 || (metric != 0 && metric != 1)) return -1;
+    if (!P_new) P_new = K_new;
+    int err = 0;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int h = 0; h < H; ++h) {
+        const int L = len[h];
+        const int64_t cb = (int64_t)h * C;     /* first slot of this head   */
+        const int64_t nb = (int64_t)h * n_new; /* first new token of this head */
+        int8_t *cp = malloc((size_t)(n_new > 0 ? n_new : 1) * r);
+        int8_t *ck = malloc((size_t)(n_new > 0 ? n_new : 1) * r);
+        uint8_t *is_cand = calloc((size_t)(L > 0 ? L : 1), 1);
+        int32_t *jstar = malloc(sizeof(int32_t) * (size_t)(n_new > 0 ? n_new : 1));
+        int64_t *sstar = malloc(sizeof(int64_t) * (size_t)(n_new > 0 ? n_new : 1));
+        int32_t *group = calloc((size_t)(L > 0 ? L : 1), sizeof(int32_t));  /* |M_j| */
+        int32_t *winner = malloc(sizeof(int32_t) * (size_t)(L > 0 ? L : 1));
+        uint8_t *victim = calloc((size_t)(L > 0 ? L : 1), 1);
+        if (!cp || !ck || !is_cand || !jstar || !sstar || !group || !winner || !victim) {
+#pragma omp atomic write
+            err = -5;
+            goto done;
+        }
+        /* step 1: codes of the probes and of the new keys */
+        for (int i = 0; i < n_new; ++i) {
+            encode_vec(P_new, dtype, (nb + i) * d, d, R, r, qscale, shift, cp + (int64_t)i * r);
+            encode_vec(K_new, dtype, (nb + i) * d, d, R, r, qscale, shift, ck + (int64_t)i * r);
+        }
+        /* step 2: candidate set and top-1 match (strict '>' keeps the smallest slot on ties) */
+        if (cand) {
+            for (int c = 0; c < n_cand; ++c) {
+                int32_t j = cand[(int64_t)h * n_cand + c];
+                if (j >= 0 && j < L) is_cand[j] = 1;
+            }
+        } else {
+            for (int j = 0; j < L; ++j) is_cand[j] = 1;
+        }
+        for (int i = 0; i < n_new; ++i) {
+            jstar[i] = -1;
+            sstar[i] = 0;
+            for (int j = 0; j < L; ++j) {
+                if (!is_cand[j]) continue;
+                const int8_t *cj = code + (cb + j) * r;
+                int64_t S = dot_i8(cp + (int64_t)i * r, cj, r);
+                if (metric == 0) S = 2 * S - dot_i8(cj, cj, r);
+                if (jstar[i] < 0 || S > sstar[i]) {
+                    jstar[i] = j;
+                    sstar[i] = S;
+                }
+            }
+        }
+        /* step 3: cosine test on the 8-bit quantised full-width keys, as an integer inequality */
+        int n_merged = 0;
+        for (int i = 0; i < n_new; ++i) {
+            merged[nb + i] = 0;
+            if (jstar[i] < 0) continue;
+            int64_t dot = 0, na = 0, nbb = 0;
+            for (int t = 0; t < d; ++t) {
+                int64_t a = quant8(load_f32(K_new, dtype, (nb + i) * d + t), qscale);
+                int64_t b = quant8(load_f32(K, dtype, (cb + jstar[i]) * d + t), qscale);
+                dot += a * b;
+                na += a * a;
+                nbb += b * b;
+            }
+            if (dot > 0 && dot * dot * 65536 >= (int64_t)tau2_q16 * na * nbb) {
+                merged[nb + i] = 1;
+                n_merged += 1;
+            }
+        }
+        /* step 4: members of every touched slot and its winner: the joiner closest to the slot in code
+         * space (metric 0: -|cp_i - code_j|^2 = S - |cp_i|^2; metric 1: S), then the smallest token index */
+        for (int i = 0; i < n_new; ++i) {
+            if (!merged[nb + i]) continue;
+            if (metric == 0) sstar[i] -= dot_i8(cp + (int64_t)i * r, cp + (int64_t)i * r, r);
+        }
+        for (int i = 0; i < n_new; ++i) {
+            if (!merged[nb + i]) continue;
+            int j = jstar[i];
+            if (group[j] == 0 || sstar[i] > sstar[winner[j]]) winner[j] = i;
+            group[j] += 1;
+        }
+        /* step 5: tokens to append, evictions needed, victims = oldest untouched live slots */
+        int n_unmerged = n_new - n_merged;
+        int e = L + n_unmerged - C;
+        if (e < 0) e = 0;
+        int n_victims = 0;
+        for (int pick = 0; pick < e; ++pick) { /* repeatedly take the smallest (stamp, slot) not yet taken */
+            int best = -1;
+            for (int j = 0; j < L; ++j) {
+                if (group[j] != 0 || victim[j]) continue;
+                if (best < 0 || stamp[cb + j] < stamp[cb + best]) best = j;
+            }
+            if (best < 0) break;
+            victim[best] = 1;
+            n_victims += 1;
+        }
+        int n_dropped = e - n_victims;
+        /* step 6a: merged groups: mean value with multiplicity, most recent key as representative */
+        {
+            /* value sums: cnt * V_old first, then the members' values in ascending token order */
+            double *acc = malloc(sizeof(double) * (size_t)(n_merged > 0 ? n_merged : 1) * d);
+            int32_t *row_of = malloc(sizeof(int32_t) * (size_t)(L > 0 ? L : 1)); /* slot -> row of acc */
+            int n_rows = 0;
+            for (int j = 0; j < L; ++j) row_of[j] = -1;
+            for (int i = 0; i < n_new; ++i) {
+                if (!merged[nb + i]) continue;
+                int j = jstar[i];
+                merge_map[nb + i] = j;
+                if (row_of[j] < 0) {
+                    row_of[j] = n_rows++;
+                    for (int t = 0; t < d; ++t)
+                        acc[(int64_t)row_of[j] * d + t] =
+                            (double)cnt[cb + j] * (double)load_f32(V, dtype, (cb + j) * d + t);
+                }
+                for (int t = 0; t < d; ++t)
+                    acc[(int64_t)row_of[j] * d + t] += (double)load_f32(V_new, dtype, (nb + i) * d + t);
+            }
+            for (int j = 0; j < L; ++j) {
+                if (group[j] == 0) continue;
+                for (int t = 0; t < d; ++t)
+                    store_val(V, dtype, (cb + j) * d + t,
+                              acc[(int64_t)row_of[j] * d + t] / (double)(cnt[cb + j] + group[j]));
+                cnt[cb + j] += group[j];
+                copy_row(K, cb + j, K_new, nb + winner[j], d, dtype);
+                memcpy(code + (cb + j) * r, ck + (int64_t)winner[j] * r, (size_t)r);
+                stamp[cb + j] = frame_id;
+            }
+            free(acc);
+            free(row_of);
+        }
+        /* step 6b: unmerged tokens in ascending order: first into the victims (ascending slot), then
+         * into fresh slots; the last n_dropped of them do not fit and are dropped */
+        int a = 0, next_victim = 0;
+        for (int i = 0; i < n_new; ++i) {
+            if (merged[nb + i]) continue;
+            int dst;
+            if (a >= n_unmerged - n_dropped) {
+                dst = -1;
+            } else if (a < n_victims) {
+                while (!victim[next_victim]) next_victim += 1;
+                dst = next_victim;
+                next_victim += 1;
+            } else {
+                dst = L + (a - n_victims);
+            }
+            merge_map[nb + i] = dst;
+            if (dst >= 0) {
+                copy_row(K, cb + dst, K_new, nb + i, d, dtype);
+                copy_row(V, cb + dst, V_new, nb + i, d, dtype);
+                memcpy(code + (cb + dst) * r, ck + (int64_t)i * r, (size_t)r);
+                cnt[cb + dst] = 1;
+                stamp[cb + dst] = frame_id;
+            }
+            a += 1;
+        }
+        {
+            int n_app = n_unmerged - n_dropped;
+            int newL = L + n_app - n_victims;
+            len[h] = newL;
+            int32_t *st = stats + (int64_t)h * 8;
+            st[0] = newL;
+            st[1] = n_merged;
+            st[2] = n_app;
+            st[3] = n_victims;
+            st[4] = n_dropped;
+            st[5] = st[6] = st[7] = 0;
+        }
+    done:
+        free(cp);
+        free(ck);
+        free(is_cand);
+        free(jstar);
+        free(sstar);
+        free(group);
+        free(winner);
+        free(victim);
+    }
+    return err;
+}
+
+/* ------------------------------------------------------------------ ANN selection */
+
+/* Pick the n_out largest scores (ties: smaller index), flag them; O(n_out * n) on purpose. */
+static void pick_top(const int64_t *score, int n, int n_out, uint8_t *picked) {
+    memset(picked, 0, (size_t)(n > 0 ? n : 1));
+    for (int t = 0; t < n_out; ++t) {
+        int best = -1;
+        for (int k = 0; k < n; ++k) {
+            if (picked[k]) continue;
+            if (best < 0 || score[k] > score[best]) best = k;
+        }
+        if (best < 0) break;
+        picked[best] = 1;
+    }
+}
+
+/*
+ * AnnSA.  qcode [H,n_q,r], kcode [H,C,r], len [H].
+ * Query block b (BQ queries) is summarised by n_rep mean codes, one per run of g = BQ/n_rep
+ * queries: rep = floor((sum of codes + floor(g/2)) / g)  (runs with no query are skipped).
+ * Score of key block kb (BK keys) = max over summaries and over its live keys of rep . code_k.
+ * The min(n_sel, ceil(len/BK)) best key blocks are written in ascending order to
+ * sel [H,n_qb,n_sel] (-1 padded), their number to nsel [H,n_qb].
+ */
+int oracle_ann_select_self(const int8_t *qcode, int n_q, const int8_t *kcode, const int32_t *len, int H, int C, int r,
+                           int BQ, int n_rep, int BK, int n_sel, int32_t *sel, int32_t *nsel) {
+    if (!qcode || !kcode || !len || !sel || !nsel) return -1;
+    if (H <= 0 || C <= 0 || r <= 0 || BQ <= 0 || n_rep <= 0 || BK <= 0 || n_sel <= 0 || BQ % n_rep != 0) return -1;
+    const int n_qb = (n_q + BQ - 1) / BQ;
+    const int g = BQ / n_rep;
+    const int n_kb_cap = (C + BK - 1) / BK;
+#pragma omp parallel for collapse(2) schedule(dynamic, 1)
+    for (int h = 0; h < H; ++h) {
+        for (int b = 0; b < n_qb; ++b) {
+            const int L = len[h];
+            const int n_kb = (L + BK - 1) / BK;
+            int64_t *rep = malloc(sizeof(int64_t) * (size_t)n_rep * r);
+            uint8_t *rep_ok = malloc((size_t)n_rep);
+            int64_t *score = malloc(sizeof(int64_t) * (size_t)(n_kb_cap > 0 ? n_kb_cap : 1));
+            uint8_t *picked = malloc((size_t)(n_kb_cap > 0 ? n_kb_cap : 1));
+            for (int u = 0; u < n_rep; ++u) {
+                int q0 = b * BQ + u * g, q1 = q0 + g;
+                if (q1 > n_q) q1 = n_q;
+                rep_ok[u] = q0 < n_q;
+                for (int j = 0; j < r; ++j) {
+                    int64_t s = 0;
+                    for (int q = q0; q < q1; ++q) s += qcode[((int64_t)h * n_q + q) * r + j];
+                    rep[(int64_t)u * r + j] = floor_div(s + g / 2, g);
+                }
+            }
+            for (int kb = 0; kb < n_kb; ++kb) {
+                int have = 0;
+                int64_t best = 0;
+                for (int k = kb * BK; k < (kb + 1) * BK && k < L; ++k) {
+                    const int8_t *ck = kcode + ((int64_t)h * C + k) * r;
+                    for (int u = 0; u < n_rep; ++u) {
+                        if (!rep_ok[u]) continue;
+                        int64_t s = 0;
+                        for (int j = 0; j < r; ++j) s += rep[(int64_t)u * r + j] * (int64_t)ck[j];
+                        if (!have || s > best) {
+                            best = s;
+                            have = 1;
+                        }
+                    }
+                }
+                score[kb] = best;
+            }
+            int n_out = n_sel < n_kb ? n_sel : n_kb;
+            pick_top(score, n_kb, n_out, picked);
+            int32_t *out = sel + ((int64_t)h * n_qb + b) * n_sel;
+            int w = 0;
+            for (int kb = 0; kb < n_kb; ++kb)
+                if (picked[kb]) out[w++] = kb;
+            nsel[(int64_t)h * n_qb + b] = w;
+            for (; w < n_sel; ++w) out[w] = -1;
+            free(rep);
+            free(rep_ok);
+            free(score);
+            free(picked);
+        }
+    }
+    return 0;
+}
+
+/*
+ * AnnCA.  qcode [H,n_q,r], pcode [H,n_p,r].
+ * Score of prompt token p for query block b = max over the block's queries of c_q . c_p (a token
+ * is kept when at least one query of the block is its neighbour).  The min(n_sel, n_p) best
+ * tokens go to sel [H,n_qb,n_sel] in ascending order (-1 padded), their number to nsel.
+ */
+int oracle_ann_select_cross(const int8_t *qcode, int n_q, const int8_t *pcode, int n_p, int H, int r, int BQ,
+                            int n_sel, int32_t *sel, int32_t *nsel) {
+    if (!qcode || !pcode || !sel || !nsel) return -1;
+    if (H <= 0 || n_p < 0 || r <= 0 || BQ <= 0 || n_sel <= 0) return -1;
+    const int n_qb = (n_q + BQ - 1) / BQ;
+#pragma omp parallel for collapse(2) schedule(dynamic, 1)
+    for (int h = 0; h < H; ++h) {
+        for (int b = 0; b < n_qb; ++b) {
+            int64_t *score = malloc(sizeof(int64_t) * (size_t)(n_p > 0 ? n_p : 1));
+            uint8_t *picked = malloc((size_t)(n_p > 0 ? n_p : 1));
+            int q0 = b * BQ, q1 = q0 + BQ;
+            if (q1 > n_q) q1 = n_q;
+            for (int p = 0; p < n_p; ++p) {
+                const int8_t *cpp = pcode + ((int64_t)h * n_p + p) * r;
+                int64_t best = 0;
+                for (int q = q0; q < q1; ++q) {
+                    int64_t s = dot_i8(qcode + ((int64_t)h * n_q + q) * r, cpp, r);
+                    if (q == q0 || s > best) best = s;
+                }
+                score[p] = best;
+            }
+            int n_out = n_sel < n_p ? n_sel : n_p;
+            pick_top(score, n_p, n_out, picked);
+            int32_t *out = sel + ((int64_t)h * n_qb + b) * n_sel;
+            int w = 0;
+            for (int p = 0; p < n_p; ++p)
+                if (picked[p]) out[w++] = p;
+            nsel[(int64_t)h * n_qb + b] = w;
+            for (; w < n_sel; ++w) out[w] = -1;
+            free(score);
+            free(picked);
+        }
+    }
+    return 0;
+}
+
+/* ------------------------------------------------------------------ sparse attention */
+
+/* Collect the live key indices of the key blocks listed for query block b. Returns their number. */
+static int gather_keys(const int32_t *sel_row, int n_listed, int BK, int L, int32_t *keys) {
+    int n = 0;
+    const int n_kb = (L + BK - 1) / BK;
+    for (int s = 0; s < n_listed; ++s) {
+        int kb = sel_row[s];
+        if (kb < 0 || kb >= n_kb) continue;
+        for (int k = kb * BK; k < (kb + 1) * BK && k < L; ++k) keys[n++] = k;
+    }
+    return n;
+}
+
+/*
+ * Q [H,n_q,d], K,V [H,C,d] (dtype), cnt [H,C] or NULL, len [H], sel [H,n_qb,n_sel], nsel [H,n_qb].
+ * For query i of block b over the live keys J of the listed key blocks:
+ *   l_j = scale * (q_i . k_j) + ln(cnt_j),  o_i = sum_j softmax(l)_j v_j,  lse_i = ln sum_j exp(l_j).
+ * O [H,n_q,d] and lse [H,n_q] are returned in fp64.  J empty => o = 0, lse = -inf.
+ */
+int oracle_sparse_attn_fwd(const void *Q, int n_q, const void *K, const void *V, const int32_t *cnt,
+                           const int32_t *len, int H, int C, int d, int dtype, const int32_t *sel,
+                           const int32_t *nsel, int BQ, int BK, int n_sel, double scale, double *O, double *lse) {
+    if (!Q || !K || !V || !len || !sel || !nsel || !O) return -1;
+    if (H <= 0 || C <= 0 || d <= 0 || BQ <= 0 || BK <= 0 || n_sel <= 0) return -1;
+    const int n_qb = (n_q + BQ - 1) / BQ;
+#pragma omp parallel for collapse(2) schedule(dynamic, 1)
+    for (int h = 0; h < H; ++h) {
+        for (int b = 0; b < n_qb; ++b) {
+            const int L = len[h];
+            const int32_t *row = sel + ((int64_t)h * n_qb + b) * n_sel;
+            int n_listed = nsel[(int64_t)h * n_qb + b];
+            if (n_listed > n_sel) n_listed = n_sel;
+            int32_t *keys = malloc(sizeof(int32_t) * ((size_t)n_sel * BK + 1));
+            double *logit = malloc(sizeof(double) * ((size_t)n_sel * BK + 1));
+            const int nk = gather_keys(row, n_listed, BK, L, keys);
+            for (int i = b * BQ; i < (b + 1) * BQ && i < n_q; ++i) {
+                const int64_t qb = ((int64_t)h * n_q + i) * d;
+                double mx = -INFINITY;
+                for (int a = 0; a < nk; ++a) {
+                    const int64_t kb = ((int64_t)h * C + keys[a]) * d;
+                    double s = 0.0;
+                    for (int t = 0; t < d; ++t) s += (double)load_f32(Q, dtype, qb + t) * (double)load_f32(K, dtype, kb + t);
+                    s *= scale;
+                    if (cnt) s += log((double)cnt[(int64_t)h * C + keys[a]]);
+                    logit[a] = s;
+                    if (s > mx) mx = s;
+                }
+                double den = 0.0;
+                for (int a = 0; a < nk; ++a) {
+                    logit[a] = exp(logit[a] - mx);
+                    den += logit[a];
+                }
+                for (int t = 0; t < d; ++t) {
+                    double acc = 0.0;
+                    for (int a = 0; a < nk; ++a)
+                        acc += logit[a] * (double)load_f32(V, dtype, ((int64_t)h * C + keys[a]) * d + t);
+                    O[qb + t] = nk > 0 ? acc / den : 0.0;
+                }
+                if (lse) lse[(int64_t)h * n_q + i] = nk > 0 ? mx + log(den) : -INFINITY;
+            }
+            free(keys);
+            free(logit);
+        }
+    }
+    return 0;
+}
+
+/*
+ * Attention recall and density of a selection, on every q_stride-th query:
+ *   recall  = mean over queries of (softmax mass of the dense attention over all live keys that
+ *             falls on the selected keys);
+ *   density = selected query-key pairs / all query-key pairs.
+ * Logits carry the ln(cnt) shift when cnt is given.  out[0] = recall, out[1] = density.
+ */
+int oracle_recall_density(const void *Q, int n_q, const void *K, const int32_t *cnt, const int32_t *len, int H, int C,
+                          int d, int dtype, const int32_t *sel, const int32_t *nsel, int BQ, int BK, int n_sel,
+                          double scale, int q_stride, double *out) {
+    if (!Q || !K || !len || !sel || !nsel || !out || q_stride <= 0) return -1;
+    const int n_qb = (n_q + BQ - 1) / BQ;
+    double recall_sum = 0.0, pairs_sel = 0.0, pairs_all = 0.0;
+    int64_t n_queries = 0;
+#pragma omp parallel for collapse(2) schedule(dynamic, 4) reduction(+ : recall_sum, pairs_sel, pairs_all, n_queries)
+    for (int h = 0; h < H; ++h) {
+        for (int i = 0; i < n_q; ++i) {
+            if (i % q_stride != 0) continue;
+            const int L = len[h];
+            if (L <= 0) continue;
+            const int b = i / BQ;
+            const int32_t *row = sel + ((int64_t)h * n_qb + b) * n_sel;
+            int n_listed = nsel[(int64_t)h * n_qb + b];
+            uint8_t *in_sel = calloc((size_t)L, 1);
+            double *logit = malloc(sizeof(double) * (size_t)L);
+            const int n_kb = (L + BK - 1) / BK;
+            for (int s = 0; s < n_listed && s < n_sel; ++s) {
+                int kb = row[s];
+                if (kb < 0 || kb >= n_kb) continue;
+                for (int k = kb * BK; k < (kb + 1) * BK && k < L; ++k) in_sel[k] = 1;
+            }
+            const int64_t qb = ((int64_t)h * n_q + i) * d;
+            double mx = -INFINITY;
+            for (int k = 0; k < L; ++k) {
+                double s = 0.0;
+                for (int t = 0; t < d; ++t)
+                    s += (double)load_f32(Q, dtype, qb + t) * (double)load_f32(K, dtype, ((int64_t)h * C + k) * d + t);
+                s *= scale;
+                if (cnt) s += log((double)cnt[(int64_t)h * C + k]);
+                logit[k] = s;
+                if (s > mx) mx = s;
+            }
+            double den = 0.0, kept = 0.0, nsel_keys = 0.0;
+            for (int k = 0; k < L; ++k) {
+                double e = exp(logit[k] - mx);
+                den += e;
+                if (in_sel[k]) {
+                    kept += e;
+                    nsel_keys += 1.0;
+                }
+            }
+            recall_sum += kept / den;
+            pairs_sel += nsel_keys;
+            pairs_all += (double)L;
+            n_queries += 1;
+            free(in_sel);
+            free(logit);
+        }
+    }
+    out[0] = n_queries ? recall_sum / (double)n_queries : 0.0;
+    out[1] = pairs_all > 0 ? pairs_sel / pairs_all : 0.0;
+    return 0;
+}
