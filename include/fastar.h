@@ -1,0 +1,172 @@
+/*
+ * libfastar: the attention hot path of FAST-AR on one MI355X (gfx950), as a C ABI.
+ *
+ * Four operations, as the method section of the paper states them, plus the code they share:
+ *   fastar_encode        shared low-dimensional 8-bit ANN code of queries / keys / prompt keys
+ *   tempcache_compress   merge one frame of new K/V into the bounded per-head cache (TempCache)
+ *   ann_select_self      key blocks each query block attends to (AnnSA)
+ *   ann_select_cross     prompt tokens each query block attends to (AnnCA)
+ *   sparse_attn_fwd      softmax attention over the selected keys only, with the log-multiplicity bias
+ *
+ * Conventions (all entry points):
+ *   - Every pointer is a DEVICE pointer unless it points to one of the small structs below, which
+ *     are read on the host at call time.  The caller owns every buffer; the library allocates
+ *     nothing, keeps no state and never synchronises with the host.
+ *   - `stream` is a hipStream_t passed as void*.  Work is enqueued on it and the call returns.
+ *   - Tensors are dense row-major: [H, N, d] means element (h, n, t) at (h*N + n)*d + t.  The
+ *     batch dimension is folded into H.  Rows of Q/K/V/O must be 16-byte aligned.
+ *   - dtype: FASTAR_F32 (float) or FASTAR_BF16 (bfloat16).  Q, K, V, O of one call share it.
+ *   - Return value: FASTAR_OK, or a negative code found on the host before anything is launched
+ *     (INVALID_ARG: null / negative / inconsistent argument; UNSUPPORTED: a shape the kernels are
+ *     not built for; WORKSPACE: workspace too small), or FASTAR_ERR_HIP when a launch failed.
+ *     Conditions only the device can see (a full cache dropping tokens) are reported through the
+ *     `stats` output, never through the return value.
+ *   - Index outputs are deterministic: every decision is taken on exact integer scores with ties
+ *     going to the lowest index, so repeated calls and other implementations of the same
+ *     definition give identical bits.
+ */
+#ifndef FASTAR_H
+#define FASTAR_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define FASTAR_OK 0
+#define FASTAR_ERR_INVALID_ARG (-1)
+#define FASTAR_ERR_UNSUPPORTED (-2)
+#define FASTAR_ERR_WORKSPACE (-3)
+#define FASTAR_ERR_HIP (-4)
+
+#define FASTAR_F32 0
+#define FASTAR_BF16 1
+
+#define FASTAR_OP_COMPRESS 1
+#define FASTAR_OP_SELECT_SELF 2
+#define FASTAR_OP_SELECT_CROSS 3
+
+/*
+ * Bounded per-head KV cache with multiplicities (Lemma 1 of the paper: a group of merged keys is
+ * kept as one representative key, the mean of the group's values and the group size m, which
+ * enters attention as a +log m logit shift).  Capacity C slots per head, len[h] <= C of them live.
+ */
+typedef struct {
+    void *K;        /* [H,C,d] dtype   representative = most recent key of each group            */
+    void *V;        /* [H,C,d] dtype   mean value of each group                                  */
+    int8_t *code;   /* [H,C,r]         ANN code of K                                             */
+    int32_t *cnt;   /* [H,C]           multiplicity m >= 1 of live slots                         */
+    int32_t *stamp; /* [H,C]           frame id of the slot's last refresh                       */
+    int32_t *len;   /* [H]             live slots                                                */
+    int32_t H, C, d, r, dtype;
+} fastar_cache;
+
+/*
+ * Definition of the ANN code (Sec. 5.1: shared low-dimensional random projection + low-bit
+ * quantisation, 8 bit by default), in integer arithmetic so that every score is exact:
+ *   xq[t] = clamp(rint(x[t] * qscale), -127, 127)           one float32 multiply, ties to even
+ *   y[j]  = sum_t R[t][j] * xq[t]                           int32
+ *   c[j]  = clamp(floor((y[j] + 2^(shift-1)) / 2^shift), -127, 127)
+ */
+typedef struct {
+    const int8_t *R; /* [d,r] device, entries -1 / +1 */
+    float qscale;
+    int32_t shift;   /* >= 1 */
+} fastar_codec;
+
+/* Library version string (host pointer, static storage). */
+const char *fastar_version(void);
+
+/* Human-readable name of a return code (host pointer, static storage). */
+const char *fastar_strerror(int code);
+
+/*
+ * Bytes of device workspace an operation needs (FASTAR_OP_*).  Arguments that an operation does
+ * not use are ignored.  COMPRESS: H, C, n_new (as n_q), r.  SELECT_SELF: H, n_q, C (as n_k), BQ,
+ * BK, n_rep, r.  SELECT_CROSS: H, n_q, n_p (as n_k), BQ.  Returns 0 for an unknown op.
+ */
+size_t fastar_workspace_bytes(int op, int H, int n_q, int n_k, int r, int BQ, int BK, int n_rep);
+
+/*
+ * ANN codes (Sec. 5.1) of n_vec vectors.
+ *   x        [n_vec, d] dtype (device), d in {64, 128}
+ *   codec    host struct; codec->R device [d, r], r in {32, 64}
+ *   code_out [n_vec, r] int8 (device)
+ */
+int fastar_encode(const void *x, int dtype, int64_t n_vec, int d, const fastar_codec *codec, int r,
+                  int8_t *code_out, void *stream);
+
+/*
+ * TempCache (Sec. 5.2 and Lemma 1): merge one frame of n_new tokens per head into the cache.  Every
+ * decision is taken against the cache as it is at entry; a chunk of several frames is several calls.
+ *   1. probe code cp_i = code(P_new[i]) (P_new NULL => K_new), key code ck_i = code(K_new[i]).
+ *   2. top-1 match among the candidate slots (cand [H,n_cand] slot ids, ids outside [0,len) are
+ *      skipped; cand NULL => every live slot): j*(i) = argmax_j S(i,j), ties to the smallest slot,
+ *      S = 2 cp_i.code_j - |code_j|^2 (metric 0, nearest in code space) or cp_i.code_j (metric 1).
+ *   3. similarity threshold on the 8-bit quantised full-width keys a = xq(K_new[i]), b = xq(K[j*]):
+ *      merged_i <=> a.b > 0 and (a.b)^2 * 65536 >= tau2_q16 * |a|^2 |b|^2, with
+ *      tau2_q16 = rint(tau^2 * 65536) in [0, 131072].
+ *   4. every slot keeps, of the tokens merged into it, the one closest in code space (metric 0:
+ *      S - |cp_i|^2, metric 1: S; ties to the smallest token) as its new representative key; its
+ *      value becomes the mean over the enlarged group and its multiplicity grows by the joiners.
+ *   5. unmerged tokens are appended in token order.  If the cache would exceed C, the live slots
+ *      that received no token in this call are evicted, smallest (stamp, slot) first, and refilled
+ *      in ascending slot order; if there are too few of those, the last unmerged tokens are dropped.
+ *   K_new, V_new, P_new [H,n_new,d] dtype;  frame_id is stored as the stamp of every written slot.
+ * Outputs:
+ *   merge_map [H,n_new] int32  destination slot of each token, -1 if dropped
+ *   merged    [H,n_new] uint8  1 if the token joined an existing slot
+ *   stats     [H,8]     int32  {len after, n_merged, n_appended, n_evicted, n_dropped, 0, 0, 0}
+ *   ws / ws_bytes              workspace of fastar_workspace_bytes(FASTAR_OP_COMPRESS, ...), 256-byte aligned
+ * The cache struct and the codec struct are host structs; cache->len is updated on the device.
+ */
+int tempcache_compress(const fastar_cache *cache, const fastar_codec *codec, const void *K_new,
+                       const void *V_new, const void *P_new, int n_new, const int32_t *cand, int n_cand,
+                       int metric, int32_t tau2_q16, int32_t frame_id, int32_t *merge_map, uint8_t *merged,
+                       int32_t *stats, void *ws, size_t ws_bytes, void *stream);
+
+/*
+ * AnnSA (Sec. 5.4 with the ANN goal of Sec. 5.1): for every head and every block of BQ queries,
+ * the n_out = min(n_sel, ceil(len/BK)) key blocks of BK keys with the largest code score.
+ *   Query block b is summarised by n_rep mean codes, one per run of g = BQ/n_rep queries:
+ *   rep = floor((sum of the run's codes + floor(g/2)) / g); runs without a query are skipped.
+ *   Score of key block kb = max over summaries and over the block's live keys k < len of rep.code_k.
+ *   Ties go to the smaller block index; the result is written in ascending block order.
+ *   qcode [H,n_q,r], kcode [H,C,r], len [H]
+ *   sel   [H,n_qb,n_sel] int32 out, padded with -1;  nsel [H,n_qb] int32 out;  n_qb = ceil(n_q/BQ)
+ * Supported: r in {32,64}; BQ a multiple of n_rep; n_rep in {1,2,4,8,16,32}; any BK >= 1.
+ */
+int ann_select_self(const int8_t *qcode, int n_q, const int8_t *kcode, const int32_t *len, int H, int C, int r,
+                    int BQ, int n_rep, int BK, int n_sel, int32_t *sel, int32_t *nsel, void *ws,
+                    size_t ws_bytes, void *stream);
+
+/*
+ * AnnCA (Sec. 5.3): for every head and every block of BQ queries, the min(n_sel, n_p) prompt tokens
+ * with the largest max over the block's queries of c_q.c_p (a token is kept when at least one query
+ * of the block is its neighbour).  Ties to the smaller token index, ascending output, -1 padding.
+ *   qcode [H,n_q,r], pcode [H,n_p,r];  sel [H,n_qb,n_sel], nsel [H,n_qb] out.
+ */
+int ann_select_cross(const int8_t *qcode, int n_q, const int8_t *pcode, int n_p, int H, int r, int BQ,
+                     int n_sel, int32_t *sel, int32_t *nsel, void *ws, size_t ws_bytes, void *stream);
+
+/*
+ * Block-sparse attention (Eq. 1 restricted to the candidate set of Sec. 5.1, logits shifted by
+ * +ln(cnt) as in Lemma 1).  For query i of query block b, over the live keys J of the key blocks
+ * sel[h][b][0 .. nsel[h][b]):  l_j = scale * q_i.k_j + ln(cnt_j);  o_i = sum_j softmax(l)_j v_j;
+ * lse_i = ln sum_j exp(l_j).  J empty => o_i = 0, lse_i = -inf.
+ *   Q [H,n_q,d], K,V [H,C,d] dtype;  cnt [H,C] or NULL (no bias);  len [H];
+ *   sel [H,n_qb,n_sel] (entries < 0 are padding), nsel [H,n_qb];
+ *   O [H,n_q,d] dtype out;  lse [H,n_q] float out or NULL.
+ * Supported: bf16 with d in {64,128}, BQ in {64,128}, BK a power of two <= 64 (MFMA path, fp32
+ * softmax and accumulation); fp32 with d in {64,128}, BQ <= 128, BK <= 64 (plain fp32 arithmetic).
+ */
+int sparse_attn_fwd(const void *Q, int n_q, const void *K, const void *V, const int32_t *cnt,
+                    const int32_t *len, int H, int C, int d, int dtype, const int32_t *sel, const int32_t *nsel,
+                    int BQ, int BK, int n_sel, float scale, void *O, float *lse, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FASTAR_H */

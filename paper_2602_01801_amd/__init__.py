@@ -1,0 +1,24 @@
+"""FAST-AR attention hot path for one MI355X: TempCache, AnnSA / AnnCA selection, block-sparse attention.
+
+The work is done by ``libfastar.so`` (hand-written HIP for gfx950, C ABI in ``include/fastar.h``);
+this package only marshals PyTorch device tensors into that ABI.
+"""
+from .binding import (  # noqa: F401
+    BF16,
+    EXPORTS,
+    F32,
+    LIB_PATH,
+    OP_COMPRESS,
+    OP_SELECT_CROSS,
+    OP_SELECT_SELF,
+    Cache,
+    Codec,
+    FastarError,
+    ann_select_cross,
+    ann_select_self,
+    encode,
+    lib,
+    sparse_attn_fwd,
+    tempcache_compress,
+    workspace_bytes,
+)

@@ -1,0 +1,264 @@
+"""ctypes front end of libfastar.so: argument marshalling only.
+
+Every step of the path runs in the library's HIP kernels; PyTorch supplies device memory and the
+stream.  Function names and argument meaning follow ``include/fastar.h``.  There is no fallback:
+if the library is missing or a call fails, an exception is raised.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from dataclasses import dataclass
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libfastar.so")
+
+F32, BF16 = 0, 1
+OP_COMPRESS, OP_SELECT_SELF, OP_SELECT_CROSS = 1, 2, 3
+
+_lib = None
+
+
+class FastarError(RuntimeError):
+    pass
+
+
+class _CacheStruct(ctypes.Structure):
+    _fields_ = [("K", ctypes.c_void_p), ("V", ctypes.c_void_p), ("code", ctypes.c_void_p), ("cnt", ctypes.c_void_p),
+                ("stamp", ctypes.c_void_p), ("len", ctypes.c_void_p), ("H", ctypes.c_int32), ("C", ctypes.c_int32),
+                ("d", ctypes.c_int32), ("r", ctypes.c_int32), ("dtype", ctypes.c_int32)]
+
+
+class _CodecStruct(ctypes.Structure):
+    _fields_ = [("R", ctypes.c_void_p), ("qscale", ctypes.c_float), ("shift", ctypes.c_int32)]
+
+
+def lib() -> ctypes.CDLL:
+    """Load libfastar.so (built in-tree by ``paper_2602_01801_amd.build``).  Fails loudly when absent."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise FastarError(f"{LIB_PATH} is missing: run `python -m paper_2602_01801_amd.build` "
+                              "(or __graft_entry__.build()) first; there is no fallback path")
+        L = ctypes.CDLL(LIB_PATH)
+        L.fastar_version.restype = ctypes.c_char_p
+        L.fastar_strerror.restype = ctypes.c_char_p
+        L.fastar_strerror.argtypes = [ctypes.c_int]
+        L.fastar_workspace_bytes.restype = ctypes.c_size_t
+        L.fastar_workspace_bytes.argtypes = [ctypes.c_int] * 8
+        L.fastar_encode.restype = ctypes.c_int
+        L.fastar_encode.argtypes = [ctypes.c_void_p, ctypes.c_int, ctypes.c_int64, ctypes.c_int,
+                                    ctypes.POINTER(_CodecStruct), ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p]
+        L.tempcache_compress.restype = ctypes.c_int
+        L.tempcache_compress.argtypes = [ctypes.POINTER(_CacheStruct), ctypes.POINTER(_CodecStruct), ctypes.c_void_p,
+                                         ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int, ctypes.c_void_p, ctypes.c_int,
+                                         ctypes.c_int, ctypes.c_int32, ctypes.c_int32, ctypes.c_void_p,
+                                         ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t,
+                                         ctypes.c_void_p]
+        L.ann_select_self.restype = ctypes.c_int
+        L.ann_select_self.argtypes = [ctypes.c_void_p, ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int,
+                                      ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int,
+                                      ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
+                                      ctypes.c_size_t, ctypes.c_void_p]
+        L.ann_select_cross.restype = ctypes.c_int
+        L.ann_select_cross.argtypes = [ctypes.c_void_p, ctypes.c_int, ctypes.c_void_p, ctypes.c_int, ctypes.c_int,
+                                       ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p,
+                                       ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
+        L.sparse_attn_fwd.restype = ctypes.c_int
+        L.sparse_attn_fwd.argtypes = [ctypes.c_void_p, ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
+                                      ctypes.c_void_p, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int,
+                                      ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int, ctypes.c_int, ctypes.c_int,
+                                      ctypes.c_float, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
+        _lib = L
+    return _lib
+
+
+EXPORTS = ("fastar_version", "fastar_strerror", "fastar_workspace_bytes", "fastar_encode", "tempcache_compress",
+           "ann_select_self", "ann_select_cross", "sparse_attn_fwd")
+
+
+def _check(rc: int, what: str):
+    if rc != 0:
+        raise FastarError(f"{what}: {lib().fastar_strerror(rc).decode()} ({rc})")
+
+
+def _stream() -> int:
+    return torch.cuda.current_stream().cuda_stream
+
+
+def _ptr(t):
+    return None if t is None else t.data_ptr()
+
+
+def _dtype_code(t: torch.Tensor) -> int:
+    if t.dtype == torch.float32:
+        return F32
+    if t.dtype == torch.bfloat16:
+        return BF16
+    raise TypeError(f"dtype must be float32 or bfloat16, got {t.dtype}")
+
+
+def _dev(t: torch.Tensor, dtype=None):
+    if not t.is_cuda or not t.is_contiguous():
+        raise ValueError("tensors must be contiguous device tensors")
+    if dtype is not None and t.dtype != dtype:
+        raise TypeError(f"expected {dtype}, got {t.dtype}")
+    return t
+
+
+def workspace_bytes(op: int, H: int, n_q: int, n_k: int, r: int = 32, BQ: int = 128, BK: int = 64,
+                    n_rep: int = 4) -> int:
+    return int(lib().fastar_workspace_bytes(op, H, n_q, n_k, r, BQ, BK, n_rep))
+
+
+def _workspace(ws, nbytes: int, device):
+    if ws is None:
+        ws = torch.empty(max(nbytes, 256), dtype=torch.uint8, device=device)
+    if ws.numel() * ws.element_size() < nbytes:
+        raise FastarError("workspace too small")
+    return ws
+
+
+@dataclass
+class Codec:
+    """Definition of the ANN code: +-1 projection R [d,r] (device int8), quantiser scale, requantise shift."""
+    R: torch.Tensor
+    qscale: float
+    shift: int
+
+    def struct(self) -> _CodecStruct:
+        _dev(self.R, torch.int8)
+        return _CodecStruct(self.R.data_ptr(), float(self.qscale), int(self.shift))
+
+
+@dataclass
+class Cache:
+    """Device buffers of the bounded per-head KV cache with multiplicities (capacity C slots per head)."""
+    K: torch.Tensor      # [H,C,d]
+    V: torch.Tensor      # [H,C,d]
+    code: torch.Tensor   # [H,C,r] int8
+    cnt: torch.Tensor    # [H,C] int32
+    stamp: torch.Tensor  # [H,C] int32
+    len: torch.Tensor    # [H] int32
+
+    @classmethod
+    def empty(cls, H: int, C: int, d: int, r: int, dtype: torch.dtype, device="cuda") -> "Cache":
+        z = lambda *s, dt: torch.zeros(*s, dtype=dt, device=device)
+        return cls(z(H, C, d, dt=dtype), z(H, C, d, dt=dtype), z(H, C, r, dt=torch.int8), z(H, C, dt=torch.int32),
+                   z(H, C, dt=torch.int32), z(H, dt=torch.int32))
+
+    @property
+    def shape(self):
+        H, C, d = self.K.shape
+        return H, C, d, self.code.shape[2]
+
+    def struct(self) -> _CacheStruct:
+        H, C, d, r = self.shape
+        for t in (self.K, self.V, self.code, self.cnt, self.stamp, self.len):
+            _dev(t)
+        return _CacheStruct(self.K.data_ptr(), self.V.data_ptr(), self.code.data_ptr(), self.cnt.data_ptr(),
+                            self.stamp.data_ptr(), self.len.data_ptr(), H, C, d, r, _dtype_code(self.K))
+
+    def nbytes(self) -> int:
+        return sum(t.numel() * t.element_size() for t in (self.K, self.V, self.code, self.cnt, self.stamp, self.len))
+
+
+def encode(x: torch.Tensor, codec: Codec, out: torch.Tensor | None = None) -> torch.Tensor:
+    """x [..., d] -> int8 codes [..., r]."""
+    _dev(x)
+    d, r = codec.R.shape
+    n_vec = x.numel() // d
+    if out is None:
+        out = torch.empty(x.shape[:-1] + (r,), dtype=torch.int8, device=x.device)
+    cs = codec.struct()
+    _check(lib().fastar_encode(x.data_ptr(), _dtype_code(x), n_vec, d, ctypes.byref(cs), r, out.data_ptr(), _stream()),
+           "fastar_encode")
+    return out
+
+
+def tempcache_compress(cache: Cache, codec: Codec, K_new, V_new, P_new=None, cand=None, metric: int = 0,
+                       tau2_q16: int = 53084, frame_id: int = 0, ws=None, out=None):
+    """Merge one frame into ``cache`` in place.  Returns (merge_map [H,n] int32, merged [H,n] uint8, stats [H,8])."""
+    H, C, d, r = cache.shape
+    _dev(K_new, cache.K.dtype)
+    _dev(V_new, cache.K.dtype)
+    n_new = K_new.shape[1]
+    if P_new is not None:
+        _dev(P_new, cache.K.dtype)
+    n_cand = 0
+    if cand is not None:
+        _dev(cand, torch.int32)
+        n_cand = cand.shape[1]
+    ws = _workspace(ws, workspace_bytes(OP_COMPRESS, H, n_new, C, r), K_new.device)
+    if out is None:
+        out = (torch.empty((H, n_new), dtype=torch.int32, device=K_new.device),
+               torch.empty((H, n_new), dtype=torch.uint8, device=K_new.device),
+               torch.empty((H, 8), dtype=torch.int32, device=K_new.device))
+    merge_map, merged, stats = out
+    cs, ks = cache.struct(), codec.struct()
+    _check(lib().tempcache_compress(ctypes.byref(cs), ctypes.byref(ks), K_new.data_ptr(), V_new.data_ptr(),
+                                    _ptr(P_new), n_new, _ptr(cand), n_cand, metric, tau2_q16, frame_id,
+                                    merge_map.data_ptr(), merged.data_ptr(), stats.data_ptr(), ws.data_ptr(),
+                                    ws.numel() * ws.element_size(), _stream()), "tempcache_compress")
+    return merge_map, merged, stats
+
+
+def ann_select_self(qcode, kcode, length, BQ: int, n_rep: int, BK: int, n_sel: int, ws=None, out=None):
+    """AnnSA: (sel [H,n_qb,n_sel] int32 ascending / -1 padded, nsel [H,n_qb] int32)."""
+    _dev(qcode, torch.int8)
+    _dev(kcode, torch.int8)
+    _dev(length, torch.int32)
+    H, n_q, r = qcode.shape
+    C = kcode.shape[1]
+    n_qb = (n_q + BQ - 1) // BQ
+    ws = _workspace(ws, workspace_bytes(OP_SELECT_SELF, H, n_q, C, r, BQ, BK, n_rep), qcode.device)
+    if out is None:
+        out = (torch.empty((H, n_qb, n_sel), dtype=torch.int32, device=qcode.device),
+               torch.empty((H, n_qb), dtype=torch.int32, device=qcode.device))
+    sel, nsel = out
+    _check(lib().ann_select_self(qcode.data_ptr(), n_q, kcode.data_ptr(), length.data_ptr(), H, C, r, BQ, n_rep, BK,
+                                 n_sel, sel.data_ptr(), nsel.data_ptr(), ws.data_ptr(),
+                                 ws.numel() * ws.element_size(), _stream()), "ann_select_self")
+    return sel, nsel
+
+
+def ann_select_cross(qcode, pcode, BQ: int, n_sel: int, ws=None, out=None):
+    """AnnCA: (sel [H,n_qb,n_sel] prompt-token ids ascending / -1 padded, nsel [H,n_qb])."""
+    _dev(qcode, torch.int8)
+    _dev(pcode, torch.int8)
+    H, n_q, r = qcode.shape
+    n_p = pcode.shape[1]
+    n_qb = (n_q + BQ - 1) // BQ
+    ws = _workspace(ws, workspace_bytes(OP_SELECT_CROSS, H, n_q, n_p, r, BQ), qcode.device)
+    if out is None:
+        out = (torch.empty((H, n_qb, n_sel), dtype=torch.int32, device=qcode.device),
+               torch.empty((H, n_qb), dtype=torch.int32, device=qcode.device))
+    sel, nsel = out
+    _check(lib().ann_select_cross(qcode.data_ptr(), n_q, pcode.data_ptr(), n_p, H, r, BQ, n_sel, sel.data_ptr(),
+                                  nsel.data_ptr(), ws.data_ptr(), ws.numel() * ws.element_size(), _stream()),
+           "ann_select_cross")
+    return sel, nsel
+
+
+def sparse_attn_fwd(Q, K, V, cnt, length, sel, nsel, BQ: int, BK: int, scale: float, out=None, want_lse: bool = True):
+    """Block-sparse attention.  Returns (O [H,n_q,d] in Q's dtype, lse [H,n_q] float32 or None)."""
+    _dev(Q)
+    _dev(K, Q.dtype)
+    _dev(V, Q.dtype)
+    _dev(length, torch.int32)
+    _dev(sel, torch.int32)
+    _dev(nsel, torch.int32)
+    if cnt is not None:
+        _dev(cnt, torch.int32)
+    H, n_q, d = Q.shape
+    C = K.shape[1]
+    n_sel = sel.shape[2]
+    if out is None:
+        out = (torch.empty_like(Q), torch.empty((H, n_q), dtype=torch.float32, device=Q.device) if want_lse else None)
+    O, lse = out
+    _check(lib().sparse_attn_fwd(Q.data_ptr(), n_q, K.data_ptr(), V.data_ptr(), _ptr(cnt), length.data_ptr(), H, C, d,
+                                 _dtype_code(Q), sel.data_ptr(), nsel.data_ptr(), BQ, BK, n_sel, float(scale),
+                                 O.data_ptr(), _ptr(lse), _stream()), "sparse_attn_fwd")
+    return O, lse

@@ -1,0 +1,88 @@
+// Shared device helpers of libfastar (gfx950 only): vector types, MFMA wrappers, bf16 handling,
+// the 8-bit quantiser and wave-level primitives.  Wavefronts are 64 lanes wide throughout.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/fastar.h"
+
+namespace fastar {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(2))) int i32x2;
+typedef __attribute__((ext_vector_type(4))) int i32x4;
+typedef __attribute__((ext_vector_type(16))) int i32x16;
+typedef __attribute__((ext_vector_type(2))) unsigned u32x2;
+typedef __attribute__((ext_vector_type(4))) unsigned u32x4;
+
+constexpr int WAVE = 64;
+
+// ---- MFMA ---------------------------------------------------------------------------------------
+// 32x32 tiles: lane l supplies row (A) / column (B) l%32 and the k-slots of half g = l/32; the
+// accumulator register v of lane l is element (row 8*(v/4) + 4*g + v%4, column l%32).
+// 16x16 tiles: lane l supplies row / column l%16 and the k-slots of quarter l/16; accumulator
+// register v is element (row 4*(l/16) + v, column l%16).
+// Which k a slot stands for is free as long as A and B agree, so operands are loaded with whatever
+// k order suits the memory layout.
+
+__device__ __forceinline__ f32x16 mfma_bf16_32x32x16(bf16x8 a, bf16x8 b, f32x16 c) {
+    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+}
+__device__ __forceinline__ i32x16 mfma_i8_32x32x32(i32x4 a, i32x4 b, i32x16 c) {
+    return __builtin_amdgcn_mfma_i32_32x32x32_i8(a, b, c, 0, 0, 0);
+}
+__device__ __forceinline__ i32x4 mfma_i8_16x16x64(i32x4 a, i32x4 b, i32x4 c) {
+    return __builtin_amdgcn_mfma_i32_16x16x64_i8(a, b, c, 0, 0, 0);
+}
+
+// ---- bf16 ---------------------------------------------------------------------------------------
+
+__device__ __forceinline__ float bf16_bits_to_f32(unsigned short b) { return __uint_as_float(((unsigned)b) << 16); }
+__device__ __forceinline__ float bf16_lo(unsigned w) { return __uint_as_float(w << 16); }
+__device__ __forceinline__ float bf16_hi(unsigned w) { return __uint_as_float(w & 0xFFFF0000u); }
+
+// float -> bfloat16 bits, nearest with ties to even (inputs are finite here).
+__device__ __forceinline__ unsigned f32_to_bf16_bits(float f) {
+    unsigned u = __float_as_uint(f);
+    u += 0x7FFFu + ((u >> 16) & 1u);
+    return u >> 16;
+}
+__device__ __forceinline__ unsigned pack_bf16x2(float lo, float hi) {
+    return f32_to_bf16_bits(lo) | (f32_to_bf16_bits(hi) << 16);
+}
+
+// ---- quantiser of the ANN code ----------------------------------------------------------------------
+// One float32 multiply, round half to even, saturate to [-127, 127].
+__device__ __forceinline__ int quant8(float x, float qscale) {
+    float p = __fmul_rn(x, qscale);
+    float q = rintf(p);
+    q = fminf(fmaxf(q, -127.0f), 127.0f);
+    return (int)q;
+}
+__device__ __forceinline__ unsigned pack_i8x4(int a, int b, int c, int d) {
+    return (unsigned)(a & 0xFF) | ((unsigned)(b & 0xFF) << 8) | ((unsigned)(c & 0xFF) << 16) | ((unsigned)(d & 0xFF) << 24);
+}
+
+// ---- wave primitives ------------------------------------------------------------------------------
+
+__device__ __forceinline__ int lane_id() { return threadIdx.x & (WAVE - 1); }
+
+template <typename T>
+__device__ __forceinline__ T shfl_xor(T v, int mask) {
+    return __shfl_xor(v, mask, WAVE);
+}
+
+__device__ __forceinline__ int dot4_i8(unsigned a, unsigned b, int acc) {
+    return __builtin_amdgcn_sdot4((int)a, (int)b, acc, false);
+}
+
+// Host-side launch check shared by the entry points.
+#define FASTAR_LAUNCH_CHECK()                          \
+    do {                                               \
+        if (hipGetLastError() != hipSuccess) return FASTAR_ERR_HIP; \
+    } while (0)
+
+}  // namespace fastar

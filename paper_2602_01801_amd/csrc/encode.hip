@@ -1,0 +1,141 @@
+// ANN codes (Sec. 5.1 of the paper: shared low-dimensional random projection + 8-bit quantisation).
+//
+//   xq = clamp(rint(x * qscale), +-127);  y = R^T xq (int32);  c = clamp((y + 2^(sh-1)) >> sh, +-127)
+//
+// HBM-bound: d*es bytes in, r bytes out per vector; the d x r contraction (2*d*r integer ops per
+// vector) runs on the int8 matrix cores so that it stays off the critical path.  One wavefront owns
+// 16 vectors at a time: B operand = their quantised coordinates (column = vector), A operand = R^T
+// (row = code coordinate), accumulator row 4*(lane/16)+v / column lane%16, so a lane ends up with 4
+// consecutive code bytes of one vector and stores them as one dword.
+#include "common.hpp"
+
+namespace fastar {
+
+// Coordinate t that k-slot e (0..15) of quarter g stands for in k-step ks.  Chosen so that each
+// 16-byte load of a lane is contiguous and the four quarters of a row tile the row.
+template <bool BF16>
+__device__ __forceinline__ int slot_coord(int ks, int g, int e) {
+    if (BF16) return ks * 64 + (e >> 3) * 32 + 8 * g + (e & 7);
+    return ks * 64 + (e >> 2) * 16 + 4 * g + (e & 3);
+}
+
+// Quantised coordinates of one vector for k-step ks, as the 16 int8 k-slots of this lane.
+template <bool BF16>
+__device__ __forceinline__ i32x4 load_quantised(const void *row, int ks, int g, float qscale) {
+    i32x4 out;
+    if (BF16) {
+        const unsigned short *p = (const unsigned short *)row;
+#pragma unroll
+        for (int m = 0; m < 2; ++m) {
+            u32x4 w = *(const u32x4 *)(p + ks * 64 + m * 32 + 8 * g);
+            int q[8];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                q[2 * e] = quant8(bf16_lo(w[e]), qscale);
+                q[2 * e + 1] = quant8(bf16_hi(w[e]), qscale);
+            }
+            out[2 * m] = (int)pack_i8x4(q[0], q[1], q[2], q[3]);
+            out[2 * m + 1] = (int)pack_i8x4(q[4], q[5], q[6], q[7]);
+        }
+    } else {
+        const float *p = (const float *)row;
+#pragma unroll
+        for (int m = 0; m < 4; ++m) {
+            f32x4 w = *(const f32x4 *)(p + ks * 64 + m * 16 + 4 * g);
+            out[m] = (int)pack_i8x4(quant8(w[0], qscale), quant8(w[1], qscale), quant8(w[2], qscale), quant8(w[3], qscale));
+        }
+    }
+    return out;
+}
+
+__device__ __forceinline__ int requant(int y, int shift) {
+    int c = (y + (1 << (shift - 1))) >> shift;  // arithmetic shift = floor division
+    return min(max(c, -127), 127);
+}
+
+template <bool BF16, int D, int R>
+__global__ __launch_bounds__(256) void encode_kernel(const void *__restrict__ x, int64_t n_vec,
+                                                     const int8_t *__restrict__ Rm, float qscale, int shift,
+                                                     int8_t *__restrict__ code, unsigned long long *zero_fill,
+                                                     int64_t zero_n) {
+    constexpr int KS = D / 64;   // k-steps of 64 coordinates
+    constexpr int CB = R / 16;   // blocks of 16 code coordinates
+    const int lane = lane_id();
+    const int col = lane & 15, g = lane >> 4;
+    const int64_t gtid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int64_t gthreads = (int64_t)gridDim.x * blockDim.x;
+    // optional: clear a 64-bit array for a later kernel of the same call
+    for (int64_t i = gtid; i < zero_n; i += gthreads) zero_fill[i] = 0ull;
+
+    // A operand: rows of R^T for every (k-step, code block), gathered once per wavefront
+    i32x4 a[KS][CB];
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks)
+#pragma unroll
+        for (int cb = 0; cb < CB; ++cb) {
+            int b[16];
+#pragma unroll
+            for (int e = 0; e < 16; ++e) b[e] = Rm[slot_coord<BF16>(ks, g, e) * R + cb * 16 + col];
+#pragma unroll
+            for (int m = 0; m < 4; ++m) a[ks][cb][m] = (int)pack_i8x4(b[4 * m], b[4 * m + 1], b[4 * m + 2], b[4 * m + 3]);
+        }
+
+    const int64_t wave = gtid >> 6, n_waves = gthreads >> 6;
+    const int64_t n_groups = (n_vec + 15) >> 4;
+    const size_t row_bytes = (size_t)D * (BF16 ? 2 : 4);
+    for (int64_t grp = wave; grp < n_groups; grp += n_waves) {
+        const int64_t vec = grp * 16 + col;
+        const int64_t vload = vec < n_vec ? vec : n_vec - 1;
+        const char *row = (const char *)x + (size_t)vload * row_bytes;
+        i32x4 b[KS];
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) b[ks] = load_quantised<BF16>(row, ks, g, qscale);
+#pragma unroll
+        for (int cb = 0; cb < CB; ++cb) {
+            i32x4 acc = {0, 0, 0, 0};
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) acc = mfma_i8_16x16x64(a[ks][cb], b[ks], acc);
+            unsigned w = pack_i8x4(requant(acc[0], shift), requant(acc[1], shift), requant(acc[2], shift),
+                                   requant(acc[3], shift));
+            if (vec < n_vec) *(unsigned *)(code + vec * R + cb * 16 + 4 * g) = w;
+        }
+    }
+}
+
+template <bool BF16, int D, int R>
+static void launch_encode(const void *x, int64_t n_vec, const fastar_codec *codec, int8_t *code,
+                          unsigned long long *zero_fill, int64_t zero_n, hipStream_t s) {
+    int64_t groups = (n_vec + 15) / 16;
+    int64_t blocks = (groups + 3) / 4;
+    if (blocks > 4096) blocks = 4096;
+    if (blocks < 1) blocks = 1;
+    hipLaunchKernelGGL((encode_kernel<BF16, D, R>), dim3((unsigned)blocks), dim3(256), 0, s, x, n_vec, codec->R,
+                       codec->qscale, codec->shift, code, zero_fill, zero_n);
+}
+
+// Internal launcher shared with tempcache_compress: encodes and optionally zero-fills an array.
+int encode_launch(const void *x, int dtype, int64_t n_vec, int d, const fastar_codec *codec, int r, int8_t *code,
+                  unsigned long long *zero_fill, int64_t zero_n, hipStream_t s) {
+    if (!x || !codec || !codec->R || !code || n_vec < 0) return FASTAR_ERR_INVALID_ARG;
+    if (dtype != FASTAR_F32 && dtype != FASTAR_BF16) return FASTAR_ERR_INVALID_ARG;
+    if (codec->shift < 1 || codec->shift > 16) return FASTAR_ERR_INVALID_ARG;
+    if ((d != 64 && d != 128) || (r != 32 && r != 64)) return FASTAR_ERR_UNSUPPORTED;
+    if (((uintptr_t)x & 15) || ((uintptr_t)code & 3)) return FASTAR_ERR_INVALID_ARG;
+    if (n_vec == 0 && zero_n == 0) return FASTAR_OK;
+#define FASTAR_ENC(B, DD, RR) launch_encode<B, DD, RR>(x, n_vec, codec, code, zero_fill, zero_n, s)
+    const bool bf = dtype == FASTAR_BF16;
+    if (d == 64 && r == 32) { if (bf) FASTAR_ENC(true, 64, 32); else FASTAR_ENC(false, 64, 32); }
+    else if (d == 64 && r == 64) { if (bf) FASTAR_ENC(true, 64, 64); else FASTAR_ENC(false, 64, 64); }
+    else if (d == 128 && r == 32) { if (bf) FASTAR_ENC(true, 128, 32); else FASTAR_ENC(false, 128, 32); }
+    else { if (bf) FASTAR_ENC(true, 128, 64); else FASTAR_ENC(false, 128, 64); }
+#undef FASTAR_ENC
+    FASTAR_LAUNCH_CHECK();
+    return FASTAR_OK;
+}
+
+}  // namespace fastar
+
+extern "C" int fastar_encode(const void *x, int dtype, int64_t n_vec, int d, const fastar_codec *codec, int r,
+                             int8_t *code_out, void *stream) {
+    return fastar::encode_launch(x, dtype, n_vec, d, codec, r, code_out, nullptr, 0, (hipStream_t)stream);
+}

@@ -1,0 +1,372 @@
+// ANN selection (Sec. 5.1 goal "keys with the largest dot products"; Sec. 5.4 AnnSA; Sec. 5.3 AnnCA).
+//
+// Three stages, all on exact integer scores so that the selected sets are reproducible bit for bit:
+//   rep_kernel          mean codes that summarise each query block (AnnSA only)
+//   score_*_kernel      int8 matrix-core scoring of summaries x key codes, reduced on the fly to one
+//                       int32 per (query block, key block) [AnnSA] or per (query block, prompt token)
+//                       [AnnCA]; HBM-bound: every key code is streamed exactly once
+//   topk_kernel         exact top-n_sel per row by radix select, ties to the lowest index, written in
+//                       ascending order by ballot + prefix-sum compaction
+#include <limits.h>
+
+#include "common.hpp"
+
+namespace fastar {
+
+constexpr int KB_PER_WG = 16;      // key blocks scored by one workgroup of score_self_kernel
+constexpr int COL_CHUNK = 8;       // summary column blocks (of 32) kept in registers at a time
+constexpr int TOPK_LDS_CAP = 8192; // row entries cached in LDS by topk_kernel
+
+static inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
+
+// ---- query-block summaries ------------------------------------------------------------------------
+// rep[h][b*n_rep + u][j] = floor((sum over the u-th run of g queries of block b of qcode[.][j] + g/2) / g)
+__global__ void rep_kernel(const int8_t *__restrict__ qcode, int n_q, int r, int BQ, int n_rep, int n_qb,
+                           int8_t *__restrict__ rep) {
+    const int b = blockIdx.x, h = blockIdx.y;
+    const int g = BQ / n_rep;
+    for (int t = threadIdx.x; t < n_rep * r; t += blockDim.x) {
+        const int u = t / r, j = t % r;
+        const int q0 = b * BQ + u * g;
+        const int q1 = min(q0 + g, n_q);
+        int s = 0;
+        for (int q = q0; q < q1; ++q) s += qcode[((size_t)h * n_q + q) * r + j];
+        s += g / 2;
+        int m = s / g;
+        if (s % g != 0 && s < 0) m -= 1;
+        rep[((size_t)h * n_qb * n_rep + (size_t)b * n_rep + u) * r + j] = (int8_t)m;
+    }
+}
+
+// ---- AnnSA scoring -----------------------------------------------------------------------------------
+// out[h][b][kb] = max over the summaries u of block b (whose run holds a query) and the live keys k of
+// key block kb of rep[b,u] . kcode[k].   D = A x B with A rows = 32 keys, B columns = 32 summaries.
+template <int R>
+__global__ __launch_bounds__(256) void score_self_kernel(const int8_t *__restrict__ kcode, const int32_t *__restrict__ len,
+                                                         const int8_t *__restrict__ rep, int C, int n_q, int BQ,
+                                                         int n_rep, int BK, int n_qb, int n_kb_cap,
+                                                         int32_t *__restrict__ out) {
+    constexpr int KS = R / 32;
+    extern __shared__ int32_t tile[];  // [n_qb][KB_PER_WG]
+    const int h = blockIdx.y;
+    const int L = min(len[h], C);
+    const int n_kb = (L + BK - 1) / BK;
+    const int kb0 = blockIdx.x * KB_PER_WG;
+    if (kb0 >= n_kb) return;  // whole workgroup beyond the live cache (uniform)
+    const int lane = lane_id(), wave = threadIdx.x >> 6;
+    const int col = lane & 31, g2 = lane >> 5;
+    const int NR = n_qb * n_rep;
+    const int NCB = (NR + 31) / 32;
+    const int g = BQ / n_rep;
+    const int8_t *kc = kcode + (size_t)h * C * R;
+    const int8_t *rp = rep + (size_t)h * NR * R;
+
+    for (int cb0 = 0; cb0 < NCB; cb0 += COL_CHUNK) {
+        i32x4 bfrag[COL_CHUNK][KS];
+#pragma unroll
+        for (int c = 0; c < COL_CHUNK; ++c) {
+            const int rc = min((cb0 + c) * 32 + col, NR - 1);
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) bfrag[c][ks] = *(const i32x4 *)(rp + (size_t)rc * R + ks * 32 + 16 * g2);
+        }
+        for (int kl = wave; kl < KB_PER_WG; kl += 4) {
+            const int kb = kb0 + kl;
+            if (kb >= n_kb) break;
+            int best[COL_CHUNK];
+#pragma unroll
+            for (int c = 0; c < COL_CHUNK; ++c) best[c] = INT_MIN;
+            for (int sg = 0; sg < BK; sg += 32) {
+                const int kbase = kb * BK + sg;
+                if (kbase >= L) break;
+                const int krow = min(kbase + col, C - 1);
+                i32x4 afrag[KS];
+#pragma unroll
+                for (int ks = 0; ks < KS; ++ks) afrag[ks] = *(const i32x4 *)(kc + (size_t)krow * R + ks * 32 + 16 * g2);
+                const bool partial = kbase + 32 > L || sg + 32 > BK;
+#pragma unroll
+                for (int c = 0; c < COL_CHUNK; ++c) {
+                    if (cb0 + c < NCB) {
+                        i32x16 acc = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+#pragma unroll
+                        for (int ks = 0; ks < KS; ++ks) acc = mfma_i8_32x32x32(afrag[ks], bfrag[c][ks], acc);
+                        int m = best[c];
+                        if (partial) {
+#pragma unroll
+                            for (int v = 0; v < 16; ++v) {
+                                const int kloc = 8 * (v >> 2) + 4 * g2 + (v & 3);
+                                if (kbase + kloc < L && sg + kloc < BK) m = max(m, acc[v]);
+                            }
+                        } else {
+#pragma unroll
+                            for (int v = 0; v < 16; ++v) m = max(m, acc[v]);
+                        }
+                        best[c] = m;
+                    }
+                }
+            }
+#pragma unroll
+            for (int c = 0; c < COL_CHUNK; ++c) {
+                if (cb0 + c < NCB) {
+                    int m = max(best[c], shfl_xor(best[c], 32));
+                    const int rc = (cb0 + c) * 32 + col;
+                    const int b = rc / n_rep, u = rc % n_rep;
+                    if (rc >= NR || b * BQ + u * g >= n_q) m = INT_MIN;
+                    for (int off = 1; off < n_rep; off <<= 1) m = max(m, shfl_xor(m, off));
+                    if (g2 == 0 && u == 0 && rc < NR) tile[b * KB_PER_WG + kl] = m;
+                }
+            }
+        }
+    }
+    __syncthreads();
+    const int n_here = min(KB_PER_WG, n_kb - kb0);
+    for (int t = threadIdx.x; t < n_qb * KB_PER_WG; t += blockDim.x) {
+        const int b = t / KB_PER_WG, kl = t % KB_PER_WG;
+        if (kl < n_here) out[((size_t)h * n_qb + b) * n_kb_cap + kb0 + kl] = tile[t];
+    }
+}
+
+// ---- AnnCA scoring -----------------------------------------------------------------------------------
+// out[h][b][p] = max over the queries q of block b of qcode[q] . pcode[p].
+// D = A x B with A rows = 32 queries, B columns = 32 prompt tokens.
+template <int R>
+__global__ __launch_bounds__(256) void score_cross_kernel(const int8_t *__restrict__ qcode, const int8_t *__restrict__ pcode,
+                                                          int n_q, int n_p, int BQ, int n_qb,
+                                                          int32_t *__restrict__ out) {
+    constexpr int KS = R / 32;
+    extern __shared__ int32_t smax[];  // [n_p]
+    const int b = blockIdx.x, h = blockIdx.y;
+    const int lane = lane_id(), wave = threadIdx.x >> 6;
+    const int col = lane & 31, g2 = lane >> 5;
+    for (int t = threadIdx.x; t < n_p; t += blockDim.x) smax[t] = INT_MIN;
+    __syncthreads();
+    const int q_end = min((b + 1) * BQ, n_q);
+    const int8_t *qc = qcode + (size_t)h * n_q * R;
+    const int8_t *pc = pcode + (size_t)h * n_p * R;
+    for (int qg = b * BQ + wave * 32; qg < q_end; qg += 4 * 32) {
+        const int qrow = min(qg + col, n_q - 1);
+        i32x4 afrag[KS];
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) afrag[ks] = *(const i32x4 *)(qc + (size_t)qrow * R + ks * 32 + 16 * g2);
+        const bool partial = qg + 32 > q_end;
+        for (int p0 = 0; p0 < n_p; p0 += 32) {
+            const int prow = min(p0 + col, n_p - 1);
+            i32x16 acc = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) {
+                i32x4 bfrag = *(const i32x4 *)(pc + (size_t)prow * R + ks * 32 + 16 * g2);
+                acc = mfma_i8_32x32x32(afrag[ks], bfrag, acc);
+            }
+            int m = INT_MIN;
+            if (partial) {
+#pragma unroll
+                for (int v = 0; v < 16; ++v)
+                    if (qg + 8 * (v >> 2) + 4 * g2 + (v & 3) < q_end) m = max(m, acc[v]);
+            } else {
+#pragma unroll
+                for (int v = 0; v < 16; ++v) m = max(m, acc[v]);
+            }
+            m = max(m, shfl_xor(m, 32));
+            if (g2 == 0 && p0 + col < n_p) atomicMax(&smax[p0 + col], m);
+        }
+    }
+    __syncthreads();
+    for (int t = threadIdx.x; t < n_p; t += blockDim.x) out[((size_t)h * n_qb + b) * n_p + t] = smax[t];
+}
+
+// ---- exact top-k per row ----------------------------------------------------------------------------
+// Row (h, b) of `score` holds n entries (n = ceil(len[h]/BK) when len is given, else n_fixed).  The
+// k = min(n_sel, n) largest are selected (ties: lowest index) and their indices written ascending to
+// sel[h][b][0..k), the rest of the row padded with -1; nsel[h][b] = k.
+__global__ __launch_bounds__(256) void topk_kernel(const int32_t *__restrict__ score, int row_stride,
+                                                   const int32_t *__restrict__ len, int len_cap, int BK, int n_fixed,
+                                                   int n_qb, int n_sel, int32_t *__restrict__ sel,
+                                                   int32_t *__restrict__ nsel) {
+    __shared__ unsigned keys[TOPK_LDS_CAP];
+    __shared__ unsigned hist[256];
+    __shared__ unsigned sh_bin, sh_remaining;
+    __shared__ unsigned wtot_a[4], wtot_b[4];
+    const int b = blockIdx.x, h = blockIdx.y, tid = threadIdx.x;
+    const int lane = lane_id(), wave = tid >> 6;
+    int n = n_fixed;
+    if (len) n = (min(len[h], len_cap) + BK - 1) / BK;
+    n = min(n, row_stride);
+    const int k = min(n_sel, n);
+    const int32_t *row = score + ((size_t)h * n_qb + b) * row_stride;
+    int32_t *out = sel + ((size_t)h * n_qb + b) * n_sel;
+    if (tid == 0) nsel[(size_t)h * n_qb + b] = k;
+    for (int t = k + tid; t < n_sel; t += 256) out[t] = -1;
+    if (k == 0) return;
+    if (k == n) {  // budget covers the row: everything, ascending
+        for (int t = tid; t < n; t += 256) out[t] = t;
+        return;
+    }
+    const bool cached = n <= TOPK_LDS_CAP;
+    if (cached)
+        for (int t = tid; t < n; t += 256) keys[t] = (unsigned)row[t] ^ 0x80000000u;
+    auto key_at = [&](int i) -> unsigned { return cached ? keys[i] : ((unsigned)row[i] ^ 0x80000000u); };
+
+    // radix select, most significant byte first: after the loop `prefix` is the k-th largest key and
+    // `remaining` the number of entries equal to it that belong to the selection
+    unsigned prefix = 0, mask = 0, remaining = (unsigned)k;
+    for (int shift = 24; shift >= 0; shift -= 8) {
+        hist[tid] = 0;
+        __syncthreads();
+        for (int t = tid; t < n; t += 256) {
+            const unsigned u = key_at(t);
+            if ((u & mask) == prefix) atomicAdd(&hist[(u >> shift) & 255u], 1u);
+        }
+        __syncthreads();
+        if (wave == 0) {
+            // lane l owns bins 255-4l .. 252-4l (descending); find where the running count reaches `remaining`
+            unsigned c[4], s = 0;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                c[e] = hist[255 - 4 * lane - e];
+                s += c[e];
+            }
+            unsigned incl = s;
+#pragma unroll
+            for (int off = 1; off < 64; off <<= 1) {
+                unsigned o = __shfl_up(incl, off, WAVE);
+                if (lane >= off) incl += o;
+            }
+            unsigned before = incl - s;
+            if (before < remaining && incl >= remaining) {
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    if (before < remaining && before + c[e] >= remaining) {
+                        sh_bin = 255 - 4 * lane - e;
+                        sh_remaining = remaining - before;
+                        before = 0xFFFFFFFFu;  // stop
+                    } else if (before != 0xFFFFFFFFu) {
+                        before += c[e];
+                    }
+                }
+            }
+        }
+        __syncthreads();
+        prefix |= sh_bin << shift;
+        mask |= 0xFFu << shift;
+        remaining = sh_remaining;
+    }
+    const unsigned T = prefix, need = remaining;
+
+    // ordered compaction
+    unsigned eq_before = 0, out_before = 0;
+    const unsigned long long lt_mask = (1ull << lane) - 1ull;
+    for (int base = 0; base < n; base += 256) {
+        const int i = base + tid;
+        const bool valid = i < n;
+        const unsigned u = valid ? key_at(i) : 0u;
+        const bool is_gt = valid && u > T, is_eq = valid && u == T;
+        const unsigned long long m_eq = __ballot(is_eq);
+        if (lane == 0) wtot_a[wave] = __popcll(m_eq);
+        __syncthreads();
+        unsigned eq_rank = eq_before + __popcll(m_eq & lt_mask), eq_total = 0;
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+            if (w < wave) eq_rank += wtot_a[w];
+            eq_total += wtot_a[w];
+        }
+        const bool take = is_gt || (is_eq && eq_rank < need);
+        const unsigned long long m_take = __ballot(take);
+        if (lane == 0) wtot_b[wave] = __popcll(m_take);
+        __syncthreads();
+        unsigned pos = out_before + __popcll(m_take & lt_mask), take_total = 0;
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+            if (w < wave) pos += wtot_b[w];
+            take_total += wtot_b[w];
+        }
+        if (take) out[pos] = i;
+        eq_before += eq_total;
+        out_before += take_total;
+        __syncthreads();  // wtot_a / wtot_b are rewritten by the next chunk
+    }
+}
+
+static bool pow2_le32(int v) { return v >= 1 && v <= 32 && (v & (v - 1)) == 0; }
+
+struct SelfWs {
+    size_t rep_off, score_off, total;
+};
+static SelfWs self_ws(int H, int n_q, int C, int r, int BQ, int BK, int n_rep) {
+    const int n_qb = (n_q + BQ - 1) / BQ;
+    const int n_kb_cap = (C + BK - 1) / BK;
+    SelfWs w;
+    w.rep_off = 0;
+    w.score_off = align256((size_t)H * n_qb * n_rep * r);
+    w.total = w.score_off + align256((size_t)H * n_qb * n_kb_cap * sizeof(int32_t));
+    return w;
+}
+
+size_t select_self_ws_bytes(int H, int n_q, int C, int r, int BQ, int BK, int n_rep) {
+    if (H <= 0 || n_q <= 0 || C <= 0 || r <= 0 || BQ <= 0 || BK <= 0 || n_rep <= 0) return 0;
+    return self_ws(H, n_q, C, r, BQ, BK, n_rep).total;
+}
+size_t select_cross_ws_bytes(int H, int n_q, int n_p, int BQ) {
+    if (H <= 0 || n_q <= 0 || n_p <= 0 || BQ <= 0) return 0;
+    const int n_qb = (n_q + BQ - 1) / BQ;
+    return align256((size_t)H * n_qb * n_p * sizeof(int32_t));
+}
+
+}  // namespace fastar
+
+using namespace fastar;
+
+extern "C" int ann_select_self(const int8_t *qcode, int n_q, const int8_t *kcode, const int32_t *len, int H, int C,
+                               int r, int BQ, int n_rep, int BK, int n_sel, int32_t *sel, int32_t *nsel, void *ws,
+                               size_t ws_bytes, void *stream) {
+    if (!qcode || !kcode || !len || !sel || !nsel || !ws) return FASTAR_ERR_INVALID_ARG;
+    if (H <= 0 || n_q <= 0 || C <= 0 || BQ <= 0 || n_rep <= 0 || BK <= 0 || n_sel <= 0) return FASTAR_ERR_INVALID_ARG;
+    if (BQ % n_rep != 0) return FASTAR_ERR_INVALID_ARG;
+    if (((uintptr_t)qcode & 15) || ((uintptr_t)kcode & 15) || ((uintptr_t)ws & 255)) return FASTAR_ERR_INVALID_ARG;
+    if ((r != 32 && r != 64) || !pow2_le32(n_rep) || BK % 32 != 0) return FASTAR_ERR_UNSUPPORTED;
+    const int n_qb = (n_q + BQ - 1) / BQ;
+    const int n_kb_cap = (C + BK - 1) / BK;
+    const size_t tile_bytes = (size_t)n_qb * KB_PER_WG * sizeof(int32_t);
+    if (tile_bytes > 64 * 1024) return FASTAR_ERR_UNSUPPORTED;
+    const SelfWs w = self_ws(H, n_q, C, r, BQ, BK, n_rep);
+    if (ws_bytes < w.total) return FASTAR_ERR_WORKSPACE;
+    hipStream_t s = (hipStream_t)stream;
+    int8_t *rep = (int8_t *)ws + w.rep_off;
+    int32_t *score = (int32_t *)((char *)ws + w.score_off);
+    hipLaunchKernelGGL(rep_kernel, dim3(n_qb, H), dim3(128), 0, s, qcode, n_q, r, BQ, n_rep, n_qb, rep);
+    FASTAR_LAUNCH_CHECK();
+    dim3 grid((n_kb_cap + KB_PER_WG - 1) / KB_PER_WG, H);
+    if (r == 32)
+        hipLaunchKernelGGL(score_self_kernel<32>, grid, dim3(256), tile_bytes, s, kcode, len, rep, C, n_q, BQ, n_rep,
+                           BK, n_qb, n_kb_cap, score);
+    else
+        hipLaunchKernelGGL(score_self_kernel<64>, grid, dim3(256), tile_bytes, s, kcode, len, rep, C, n_q, BQ, n_rep,
+                           BK, n_qb, n_kb_cap, score);
+    FASTAR_LAUNCH_CHECK();
+    hipLaunchKernelGGL(topk_kernel, dim3(n_qb, H), dim3(256), 0, s, score, n_kb_cap, len, C, BK, 0, n_qb, n_sel, sel,
+                       nsel);
+    FASTAR_LAUNCH_CHECK();
+    return FASTAR_OK;
+}
+
+extern "C" int ann_select_cross(const int8_t *qcode, int n_q, const int8_t *pcode, int n_p, int H, int r, int BQ,
+                                int n_sel, int32_t *sel, int32_t *nsel, void *ws, size_t ws_bytes, void *stream) {
+    if (!qcode || !pcode || !sel || !nsel || !ws) return FASTAR_ERR_INVALID_ARG;
+    if (H <= 0 || n_q <= 0 || n_p <= 0 || BQ <= 0 || n_sel <= 0) return FASTAR_ERR_INVALID_ARG;
+    if (((uintptr_t)qcode & 15) || ((uintptr_t)pcode & 15) || ((uintptr_t)ws & 255)) return FASTAR_ERR_INVALID_ARG;
+    if ((r != 32 && r != 64) || n_p > 12288) return FASTAR_ERR_UNSUPPORTED;
+    const int n_qb = (n_q + BQ - 1) / BQ;
+    if (ws_bytes < select_cross_ws_bytes(H, n_q, n_p, BQ)) return FASTAR_ERR_WORKSPACE;
+    hipStream_t s = (hipStream_t)stream;
+    int32_t *score = (int32_t *)ws;
+    const size_t lds = (size_t)n_p * sizeof(int32_t);
+    if (r == 32)
+        hipLaunchKernelGGL(score_cross_kernel<32>, dim3(n_qb, H), dim3(256), lds, s, qcode, pcode, n_q, n_p, BQ, n_qb,
+                           score);
+    else
+        hipLaunchKernelGGL(score_cross_kernel<64>, dim3(n_qb, H), dim3(256), lds, s, qcode, pcode, n_q, n_p, BQ, n_qb,
+                           score);
+    FASTAR_LAUNCH_CHECK();
+    hipLaunchKernelGGL(topk_kernel, dim3(n_qb, H), dim3(256), 0, s, score, n_p, (const int32_t *)nullptr, 0, 1, n_p,
+                       n_qb, n_sel, sel, nsel);
+    FASTAR_LAUNCH_CHECK();
+    return FASTAR_OK;
+}

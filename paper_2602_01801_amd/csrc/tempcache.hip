@@ -1,0 +1,565 @@
+// TempCache (Sec. 5.2 of the paper, Lemma 1): merge one frame of new keys/values into the bounded
+// per-head cache.  The steps, each a kernel on the caller's stream:
+//   encode        codes of the new keys (and of the probes when they differ)             -> encode.hip
+//   tc_match      top-1 candidate slot of every token on exact integer code scores (int8 matrix cores,
+//                 running arg-max per lane, 64-bit atomicMax across candidate chunks)
+//   tc_prep       unpack the match, clear the per-slot group records it will touch
+//   tc_verify     cosine test on the 8-bit quantised full-width keys as an int64 inequality; joiners
+//                 register in their slot's group record (count, best joiner)
+//   tc_plan       per head: ranks of the unmerged tokens (ballot + prefix sum), evictions needed,
+//                 victims = oldest untouched slots (radix select, ordered compaction), new length
+//   tc_apply      representative key, mean value, multiplicity, code, stamp of merged slots; appended
+//                 tokens into victims / fresh slots; merge map
+// All decisions are integer and order-independent (max / count), so the merge map is reproducible.
+#include "common.hpp"
+
+namespace fastar {
+
+int encode_launch(const void *x, int dtype, int64_t n_vec, int d, const fastar_codec *codec, int r, int8_t *code,
+                  unsigned long long *zero_fill, int64_t zero_n, hipStream_t s);
+
+constexpr int CAND_CHUNK = 512;          // candidate positions scanned by one workgroup of tc_match
+constexpr int SCORE_BIAS = 1 << 23;      // makes every score positive inside the packed arg-max key
+constexpr int HS_STRIDE = 8;             // per-head scalars: oldL, n_unmerged, e, n_victims, n_dropped, newL
+
+typedef unsigned long long u64;
+
+static inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
+
+struct CompressWs {
+    size_t ck, cp, best, jstar, sbest, rank, victims, hs, win, grp, total;
+};
+static CompressWs compress_ws(int H, int C, int n_new, int r) {
+    CompressWs w;
+    size_t o = 0;
+    const size_t T = (size_t)H * (n_new > 0 ? n_new : 1);
+    w.ck = o; o += align256(T * r);
+    w.cp = o; o += align256(T * r);
+    w.best = o; o += align256(T * 8);
+    w.jstar = o; o += align256(T * 4);
+    w.sbest = o; o += align256(T * 4);
+    w.rank = o; o += align256(T * 4);
+    w.victims = o; o += align256(T * 4);
+    w.hs = o; o += align256((size_t)H * HS_STRIDE * 4);
+    w.win = o; o += align256((size_t)H * C * 8);
+    w.grp = o; o += align256((size_t)H * C * 4);
+    w.total = o;
+    return w;
+}
+size_t compress_ws_bytes(int H, int C, int n_new, int r) {
+    if (H <= 0 || C <= 0 || n_new < 0 || r <= 0) return 0;
+    return compress_ws(H, C, n_new, r).total;
+}
+
+// ---- match -------------------------------------------------------------------------------------------
+// D = A x B: A rows = 32 candidate slots (codes gathered by slot id), B columns = 32 tokens (probe codes).
+// A lane therefore sees 16 candidates of one token per matrix instruction and keeps the best
+// (score, lowest slot) as one 64-bit key: (score + bias) << 32 | ~slot.
+template <int R>
+__global__ __launch_bounds__(256) void tc_match_kernel(const int8_t *__restrict__ code, const int32_t *__restrict__ len,
+                                                       int C, const int8_t *__restrict__ cp, int n_new,
+                                                       const int32_t *__restrict__ cand, int n_cand, int metric,
+                                                       u64 *__restrict__ best) {
+    constexpr int KS = R / 32;
+    __shared__ i32x2 cinfo[2][4][32];  // [parity][wave][candidate row] = {slot or -1, |code|^2}
+    const int h = blockIdx.z;
+    const int L = min(len[h], C);
+    const int n_pos = cand ? n_cand : L;
+    const int pos0 = blockIdx.y * CAND_CHUNK;
+    if (pos0 >= n_pos) return;  // uniform
+    const int pos1 = min(pos0 + CAND_CHUNK, n_pos);
+    const int lane = lane_id(), wave = threadIdx.x >> 6;
+    const int col = lane & 31, g2 = lane >> 5;
+    const int tok = blockIdx.x * 128 + wave * 32 + col;
+    const int8_t *cph = cp + (size_t)h * n_new * R;
+    const int8_t *ch = code + (size_t)h * C * R;
+    i32x4 bfrag[KS];
+    {
+        const int trow = min(tok, n_new - 1);
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) bfrag[ks] = *(const i32x4 *)(cph + (size_t)trow * R + ks * 32 + 16 * g2);
+    }
+    u64 mybest = 0;
+    int it = 0;
+    for (int p = pos0; p < pos1; p += 32, ++it) {
+        const int pos = p + col;
+        int slot = -1;
+        if (pos < pos1) {
+            slot = cand ? cand[(size_t)h * n_cand + pos] : pos;
+            if (slot < 0 || slot >= L) slot = -1;
+        }
+        i32x4 afrag[KS];
+        int nn = 0;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            i32x4 a = {0, 0, 0, 0};
+            if (slot >= 0) a = *(const i32x4 *)(ch + (size_t)slot * R + ks * 32 + 16 * g2);
+            afrag[ks] = a;
+#pragma unroll
+            for (int m = 0; m < 4; ++m) nn = dot4_i8((unsigned)a[m], (unsigned)a[m], nn);
+        }
+        nn += shfl_xor(nn, 32);
+        const int par = it & 1;
+        if (g2 == 0) {
+            i32x2 ci = {slot, nn};
+            cinfo[par][wave][col] = ci;
+        }
+        i32x16 acc = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) acc = mfma_i8_32x32x32(afrag[ks], bfrag[ks], acc);
+        __syncthreads();  // cinfo[par] visible; the other parity is free to be rewritten next iteration
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const i32x2 ci = cinfo[par][wave][8 * (v >> 2) + 4 * g2 + (v & 3)];
+            const int S = metric == 0 ? 2 * acc[v] - ci[1] : acc[v];
+            const u64 key = ((u64)(unsigned)(S + SCORE_BIAS) << 32) | (u64)(0xFFFFFFFFu - (unsigned)ci[0]);
+            if (ci[0] >= 0 && key > mybest) mybest = key;
+        }
+    }
+    {
+        const unsigned lo = shfl_xor((unsigned)mybest, 32), hi = shfl_xor((unsigned)(mybest >> 32), 32);
+        const u64 other = ((u64)hi << 32) | lo;
+        if (other > mybest) mybest = other;
+    }
+    if (g2 == 0 && tok < n_new && mybest != 0) atomicMax(&best[(size_t)h * n_new + tok], mybest);
+}
+
+// ---- prep ----------------------------------------------------------------------------------------------
+__global__ void tc_prep_kernel(const u64 *__restrict__ best, int n_new, int C, int32_t *__restrict__ jstar,
+                               int32_t *__restrict__ sbest, u64 *__restrict__ win, int32_t *__restrict__ grp) {
+    const int h = blockIdx.y;
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n_new) return;
+    const u64 key = best[(size_t)h * n_new + i];
+    int j = -1, S = 0;
+    if (key != 0) {
+        j = (int)(0xFFFFFFFFu - (unsigned)key);
+        S = (int)(unsigned)(key >> 32) - SCORE_BIAS;
+        win[(size_t)h * C + j] = 0;
+        grp[(size_t)h * C + j] = 0;
+    }
+    jstar[(size_t)h * n_new + i] = j;
+    sbest[(size_t)h * n_new + i] = S;
+}
+
+// ---- row pieces: 16 lanes share one row of D elements ----------------------------------------------------
+template <bool BF16, int D>
+struct RowPiece {
+    static constexpr int EPL = D / 16;  // elements per lane
+    __device__ static __forceinline__ void load(const void *base, size_t row, int l16, float *out) {
+        if (BF16) {
+            const unsigned short *p = (const unsigned short *)base + row * D + l16 * EPL;
+            if (EPL == 8) {
+                u32x4 w = *(const u32x4 *)p;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) { out[2 * e] = bf16_lo(w[e]); out[2 * e + 1] = bf16_hi(w[e]); }
+            } else {
+                u32x2 w = *(const u32x2 *)p;
+#pragma unroll
+                for (int e = 0; e < 2; ++e) { out[2 * e] = bf16_lo(w[e]); out[2 * e + 1] = bf16_hi(w[e]); }
+            }
+        } else {
+            const float *p = (const float *)base + row * D + l16 * EPL;
+#pragma unroll
+            for (int e = 0; e < EPL; e += 4) {
+                f32x4 w = *(const f32x4 *)(p + e);
+                out[e] = w[0]; out[e + 1] = w[1]; out[e + 2] = w[2]; out[e + 3] = w[3];
+            }
+        }
+    }
+    __device__ static __forceinline__ void store(void *base, size_t row, int l16, const float *v) {
+        if (BF16) {
+            unsigned short *p = (unsigned short *)base + row * D + l16 * EPL;
+            if (EPL == 8) {
+                u32x4 w;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) w[e] = pack_bf16x2(v[2 * e], v[2 * e + 1]);
+                *(u32x4 *)p = w;
+            } else {
+                u32x2 w;
+#pragma unroll
+                for (int e = 0; e < 2; ++e) w[e] = pack_bf16x2(v[2 * e], v[2 * e + 1]);
+                *(u32x2 *)p = w;
+            }
+        } else {
+            float *p = (float *)base + row * D + l16 * EPL;
+#pragma unroll
+            for (int e = 0; e < EPL; e += 4) {
+                f32x4 w = {v[e], v[e + 1], v[e + 2], v[e + 3]};
+                *(f32x4 *)(p + e) = w;
+            }
+        }
+    }
+    // bit copy of this lane's piece of a row
+    __device__ static __forceinline__ void copy(void *dst, size_t drow, const void *src, size_t srow, int l16) {
+        constexpr int BYTES = EPL * (BF16 ? 2 : 4);
+        const char *s = (const char *)src + (srow * D + (size_t)l16 * EPL) * (BF16 ? 2 : 4);
+        char *d = (char *)dst + (drow * D + (size_t)l16 * EPL) * (BF16 ? 2 : 4);
+        if (BYTES == 8) {
+            *(u32x2 *)d = *(const u32x2 *)s;
+        } else {
+#pragma unroll
+            for (int b = 0; b < BYTES; b += 16) *(u32x4 *)(d + b) = *(const u32x4 *)(s + b);
+        }
+    }
+};
+
+__device__ __forceinline__ int group16_sum(int v) {
+    v += shfl_xor(v, 1);
+    v += shfl_xor(v, 2);
+    v += shfl_xor(v, 4);
+    v += shfl_xor(v, 8);
+    return v;
+}
+
+// ---- verify --------------------------------------------------------------------------------------------
+template <bool BF16, int D>
+__global__ __launch_bounds__(256) void tc_verify_kernel(const void *__restrict__ K, const void *__restrict__ K_new,
+                                                        const int8_t *__restrict__ cp, int r, int C, int n_new,
+                                                        float qscale, int metric, int tau2_q16,
+                                                        const int32_t *__restrict__ jstar,
+                                                        const int32_t *__restrict__ sbest, u64 *__restrict__ win,
+                                                        int32_t *__restrict__ grp, uint8_t *__restrict__ merged) {
+    typedef RowPiece<BF16, D> RP;
+    const int h = blockIdx.y;
+    const int l16 = threadIdx.x & 15;
+    const int i = blockIdx.x * (blockDim.x / 16) + (threadIdx.x >> 4);
+    if (i >= n_new) return;  // whole 16-lane group leaves together
+    const size_t ti = (size_t)h * n_new + i;
+    const int j = jstar[ti];
+    bool is_merged = false;
+    if (j >= 0) {
+        float a[RP::EPL], b[RP::EPL];
+        RP::load(K_new, ti, l16, a);
+        RP::load(K, (size_t)h * C + j, l16, b);
+        int dot = 0, na = 0, nb = 0;
+#pragma unroll
+        for (int e = 0; e < RP::EPL; ++e) {
+            const int qa = quant8(a[e], qscale), qb = quant8(b[e], qscale);
+            dot += qa * qb;
+            na += qa * qa;
+            nb += qb * qb;
+        }
+        dot = group16_sum(dot);
+        na = group16_sum(na);
+        nb = group16_sum(nb);
+        is_merged = dot > 0 && (long long)dot * dot * 65536ll >= (long long)tau2_q16 * na * nb;
+        if (is_merged && l16 == 0) {
+            int W = sbest[ti];
+            if (metric == 0) {
+                const unsigned *c = (const unsigned *)(cp + ti * r);
+                int nn = 0;
+                for (int m = 0; m < r / 4; ++m) nn = dot4_i8(c[m], c[m], nn);
+                W -= nn;
+            }
+            const u64 key = ((u64)(unsigned)(W + SCORE_BIAS) << 32) | (u64)(0xFFFFFFFFu - (unsigned)i);
+            atomicMax(&win[(size_t)h * C + j], key);
+            atomicAdd(&grp[(size_t)h * C + j], 1);
+        }
+    }
+    if (l16 == 0) merged[ti] = is_merged ? 1 : 0;
+}
+
+// ---- plan ----------------------------------------------------------------------------------------------
+// One workgroup per head.  Block-wide ordered exclusive count of a predicate over one chunk of 256 items.
+struct BlockScan {
+    unsigned *wtot;  // [4] in LDS
+    __device__ __forceinline__ unsigned excl(bool flag, unsigned &total) {
+        const int lane = lane_id(), wave = threadIdx.x >> 6;
+        const unsigned long long m = __ballot(flag);
+        __syncthreads();  // previous use of wtot finished
+        if (lane == 0) wtot[wave] = __popcll(m);
+        __syncthreads();
+        unsigned pos = __popcll(m & ((1ull << lane) - 1ull));
+        total = 0;
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+            if (w < wave) pos += wtot[w];
+            total += wtot[w];
+        }
+        return pos;
+    }
+};
+
+__global__ __launch_bounds__(256) void tc_plan_kernel(int32_t *__restrict__ len, const int32_t *__restrict__ stamp, int C,
+                                                      int n_new, const int32_t *__restrict__ jstar,
+                                                      const uint8_t *__restrict__ merged, int32_t *__restrict__ rank,
+                                                      int32_t *__restrict__ victims, int32_t *__restrict__ hs,
+                                                      int32_t *__restrict__ stats) {
+    extern __shared__ unsigned touched[];  // bitmap over slots, ceil(C/32) words
+    __shared__ unsigned hist[256];
+    __shared__ unsigned wtot[4];
+    __shared__ unsigned sh_bin, sh_remaining;
+    const int h = blockIdx.x, tid = threadIdx.x, lane = lane_id(), wave = tid >> 6;
+    const int L = min(len[h], C);
+    BlockScan scan{wtot};
+    const size_t tb = (size_t)h * n_new;
+
+    // ranks of the unmerged tokens, ascending token order
+    unsigned n_unm = 0;
+    for (int base = 0; base < n_new; base += 256) {
+        const int i = base + tid;
+        const bool unm = i < n_new && merged[tb + i] == 0;
+        unsigned tot;
+        const unsigned pos = scan.excl(unm, tot);
+        if (i < n_new) rank[tb + i] = unm ? (int)(n_unm + pos) : -1;
+        n_unm += tot;
+    }
+    int e = L + (int)n_unm - C;
+    if (e < 0) e = 0;
+    int n_victims = 0;
+    if (e > 0) {  // uniform branch
+        const int n_words = (C + 31) / 32;
+        for (int w = tid; w < n_words; w += 256) touched[w] = 0;
+        __syncthreads();
+        for (int i = tid; i < n_new; i += 256)
+            if (merged[tb + i]) {
+                const int j = jstar[tb + i];
+                atomicOr(&touched[j >> 5], 1u << (j & 31));
+            }
+        __syncthreads();
+        const int32_t *st = stamp + (size_t)h * C;
+        // key: larger = older.  eligible slots: live and untouched
+        auto eligible = [&](int j) -> bool { return j < L && !((touched[j >> 5] >> (j & 31)) & 1u); };
+        auto key_at = [&](int j) -> unsigned { return ~((unsigned)st[j] ^ 0x80000000u); };
+        unsigned prefix = 0, mask = 0, remaining = (unsigned)e;
+        bool take_all = false;
+        for (int shift = 24; shift >= 0; shift -= 8) {
+            hist[tid] = 0;
+            __syncthreads();
+            for (int j = tid; j < L; j += 256) {
+                if (!eligible(j)) continue;
+                const unsigned u = key_at(j);
+                if ((u & mask) == prefix) atomicAdd(&hist[(u >> shift) & 255u], 1u);
+            }
+            __syncthreads();
+            if (wave == 0) {
+                unsigned c[4], s = 0;
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    c[q] = hist[255 - 4 * lane - q];
+                    s += c[q];
+                }
+                unsigned incl = s;
+#pragma unroll
+                for (int off = 1; off < 64; off <<= 1) {
+                    unsigned o = __shfl_up(incl, off, WAVE);
+                    if (lane >= off) incl += o;
+                }
+                unsigned before = incl - s;
+                const unsigned total = __shfl(incl, 63, WAVE);
+                if (lane == 0 && total < remaining) {  // fewer eligible slots than evictions needed
+                    sh_bin = 0x100u;
+                    sh_remaining = total;
+                }
+                if (total >= remaining && before < remaining && incl >= remaining) {
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        if (before != 0xFFFFFFFFu && before < remaining && before + c[q] >= remaining) {
+                            sh_bin = 255 - 4 * lane - q;
+                            sh_remaining = remaining - before;
+                            before = 0xFFFFFFFFu;
+                        } else if (before != 0xFFFFFFFFu) {
+                            before += c[q];
+                        }
+                    }
+                }
+            }
+            __syncthreads();
+            if (sh_bin == 0x100u) {  // can only happen in the first pass (uniform)
+                take_all = true;
+                n_victims = (int)sh_remaining;
+                break;
+            }
+            prefix |= sh_bin << shift;
+            mask |= 0xFFu << shift;
+            remaining = sh_remaining;
+        }
+        if (!take_all) n_victims = e;
+        const unsigned T = prefix, need = remaining;
+        unsigned eq_before = 0, out_before = 0;
+        for (int base = 0; base < L; base += 256) {
+            const int j = base + tid;
+            const bool el = j < L && eligible(j);
+            const unsigned u = el ? key_at(j) : 0u;
+            const bool is_gt = el && (take_all || u > T), is_eq = el && !take_all && u == T;
+            unsigned eq_tot, take_tot;
+            const unsigned eq_rank = eq_before + scan.excl(is_eq, eq_tot);
+            const bool take = is_gt || (is_eq && eq_rank < need);
+            const unsigned pos = out_before + scan.excl(take, take_tot);
+            if (take) victims[tb + pos] = j;
+            eq_before += eq_tot;
+            out_before += take_tot;
+        }
+    }
+    if (tid == 0) {
+        const int n_dropped = e - n_victims;
+        const int n_app = (int)n_unm - n_dropped;
+        const int newL = L + n_app - n_victims;
+        int32_t *o = hs + (size_t)h * HS_STRIDE;
+        o[0] = L; o[1] = (int)n_unm; o[2] = e; o[3] = n_victims; o[4] = n_dropped; o[5] = newL;
+        int32_t *s = stats + (size_t)h * 8;
+        s[0] = newL; s[1] = n_new - (int)n_unm; s[2] = n_app; s[3] = n_victims; s[4] = n_dropped;
+        s[5] = 0; s[6] = 0; s[7] = 0;
+        len[h] = newL;
+    }
+}
+
+// ---- apply ---------------------------------------------------------------------------------------------
+template <bool BF16, int D>
+__global__ __launch_bounds__(256) void tc_apply_kernel(void *__restrict__ K, void *__restrict__ V, int8_t *__restrict__ code,
+                                                       int32_t *__restrict__ cnt, int32_t *__restrict__ stamp, int C,
+                                                       int r, const void *__restrict__ K_new,
+                                                       const void *__restrict__ V_new, const int8_t *__restrict__ ck,
+                                                       int n_new, int frame_id, const int32_t *__restrict__ jstar,
+                                                       const uint8_t *__restrict__ merged, const u64 *__restrict__ win,
+                                                       const int32_t *__restrict__ grp, const int32_t *__restrict__ rank,
+                                                       const int32_t *__restrict__ victims, const int32_t *__restrict__ hs,
+                                                       int32_t *__restrict__ merge_map) {
+    typedef RowPiece<BF16, D> RP;
+    const int h = blockIdx.y;
+    const int l16 = threadIdx.x & 15;
+    const int sub = (threadIdx.x & 63) >> 4;  // which 16-lane group of the wavefront
+    const int i = blockIdx.x * (blockDim.x / 16) + (threadIdx.x >> 4);
+    if (i >= n_new) return;
+    const size_t tb = (size_t)h * n_new, ti = tb + i, cb = (size_t)h * C;
+    const int32_t *o = hs + (size_t)h * HS_STRIDE;
+    const int L = o[0], n_unm = o[1], n_victims = o[3], n_dropped = o[4];
+    int dst = -1;
+    bool write_kv_copy = false;
+    if (merged[ti]) {
+        const int j = jstar[ti];
+        dst = j;
+        const u64 wkey = win[cb + j];
+        const int widx = (int)(0xFFFFFFFFu - (unsigned)wkey);
+        if (widx == i) {  // this token represents the group: it refreshes the slot
+            const int gc = grp[cb + j];
+            const int m0 = cnt[cb + j];
+            float acc[RP::EPL], vn[RP::EPL];
+            RP::load(V, cb + j, l16, acc);
+#pragma unroll
+            for (int e = 0; e < RP::EPL; ++e) acc[e] *= (float)m0;
+            if (gc == 1) {
+                RP::load(V_new, ti, l16, vn);
+#pragma unroll
+                for (int e = 0; e < RP::EPL; ++e) acc[e] += vn[e];
+            } else {  // several joiners: add their values in ascending token order
+                for (int base = 0; base < n_new; base += 16) {
+                    const int t = base + l16;
+                    const bool member = t < n_new && merged[tb + t] && jstar[tb + t] == j;
+                    unsigned mm = (unsigned)((__ballot(member) >> (16 * sub)) & 0xFFFFull);
+                    while (mm) {
+                        const int bit = __ffs(mm) - 1;
+                        mm &= mm - 1;
+                        RP::load(V_new, tb + base + bit, l16, vn);
+#pragma unroll
+                        for (int e = 0; e < RP::EPL; ++e) acc[e] += vn[e];
+                    }
+                }
+            }
+#pragma unroll
+            for (int e = 0; e < RP::EPL; ++e) acc[e] = __fdiv_rn(acc[e], (float)(m0 + gc));
+            RP::store(V, cb + j, l16, acc);
+            RP::copy(K, cb + j, K_new, ti, l16);
+            if (l16 < r / 4) ((unsigned *)(code + (cb + j) * r))[l16] = ((const unsigned *)(ck + ti * r))[l16];
+            if (l16 == 0) {
+                cnt[cb + j] = m0 + gc;
+                stamp[cb + j] = frame_id;
+            }
+        }
+    } else {
+        const int a = rank[ti];
+        if (a < n_unm - n_dropped) {
+            dst = a < n_victims ? victims[tb + a] : L + (a - n_victims);
+            write_kv_copy = true;
+        }
+    }
+    if (write_kv_copy) {
+        RP::copy(K, cb + dst, K_new, ti, l16);
+        RP::copy(V, cb + dst, V_new, ti, l16);
+        if (l16 < r / 4) ((unsigned *)(code + (cb + dst) * r))[l16] = ((const unsigned *)(ck + ti * r))[l16];
+        if (l16 == 0) {
+            cnt[cb + dst] = 1;
+            stamp[cb + dst] = frame_id;
+        }
+    }
+    if (l16 == 0) merge_map[ti] = dst;
+}
+
+}  // namespace fastar
+
+using namespace fastar;
+
+extern "C" int tempcache_compress(const fastar_cache *cache, const fastar_codec *codec, const void *K_new,
+                                  const void *V_new, const void *P_new, int n_new, const int32_t *cand, int n_cand,
+                                  int metric, int32_t tau2_q16, int32_t frame_id, int32_t *merge_map,
+                                  uint8_t *merged, int32_t *stats, void *ws, size_t ws_bytes, void *stream) {
+    if (!cache || !codec || !codec->R || !K_new || !V_new || !merge_map || !merged || !stats || !ws)
+        return FASTAR_ERR_INVALID_ARG;
+    if (!cache->K || !cache->V || !cache->code || !cache->cnt || !cache->stamp || !cache->len)
+        return FASTAR_ERR_INVALID_ARG;
+    const int H = cache->H, C = cache->C, d = cache->d, r = cache->r, dtype = cache->dtype;
+    if (H <= 0 || C <= 0 || n_new <= 0 || (metric != 0 && metric != 1)) return FASTAR_ERR_INVALID_ARG;
+    if (tau2_q16 < 0 || tau2_q16 > 131072) return FASTAR_ERR_INVALID_ARG;
+    if (cand && n_cand <= 0) return FASTAR_ERR_INVALID_ARG;
+    if (dtype != FASTAR_F32 && dtype != FASTAR_BF16) return FASTAR_ERR_INVALID_ARG;
+    if ((d != 64 && d != 128) || (r != 32 && r != 64)) return FASTAR_ERR_UNSUPPORTED;
+    if ((size_t)((C + 31) / 32) * 4 > 48 * 1024) return FASTAR_ERR_UNSUPPORTED;  // eviction bitmap lives in LDS
+    if (((uintptr_t)cache->K & 15) || ((uintptr_t)cache->V & 15) || ((uintptr_t)cache->code & 15) ||
+        ((uintptr_t)K_new & 15) || ((uintptr_t)V_new & 15) || ((uintptr_t)P_new & 15) || ((uintptr_t)ws & 255))
+        return FASTAR_ERR_INVALID_ARG;
+    const CompressWs w = compress_ws(H, C, n_new, r);
+    if (ws_bytes < w.total) return FASTAR_ERR_WORKSPACE;
+    hipStream_t s = (hipStream_t)stream;
+    char *base = (char *)ws;
+    int8_t *ck = (int8_t *)(base + w.ck);
+    int8_t *cp = P_new ? (int8_t *)(base + w.cp) : ck;
+    u64 *best = (u64 *)(base + w.best);
+    int32_t *jstar = (int32_t *)(base + w.jstar), *sbest = (int32_t *)(base + w.sbest);
+    int32_t *rank = (int32_t *)(base + w.rank), *victims = (int32_t *)(base + w.victims);
+    int32_t *hs = (int32_t *)(base + w.hs);
+    u64 *win = (u64 *)(base + w.win);
+    int32_t *grp = (int32_t *)(base + w.grp);
+    const int64_t T = (int64_t)H * n_new;
+
+    int rc = encode_launch(K_new, dtype, T, d, codec, r, ck, best, T, s);
+    if (rc != FASTAR_OK) return rc;
+    if (P_new) {
+        rc = encode_launch(P_new, dtype, T, d, codec, r, cp, nullptr, 0, s);
+        if (rc != FASTAR_OK) return rc;
+    }
+    {
+        const int n_pos_cap = cand ? n_cand : C;
+        dim3 grid((n_new + 127) / 128, (n_pos_cap + CAND_CHUNK - 1) / CAND_CHUNK, H);
+        if (r == 32)
+            hipLaunchKernelGGL(tc_match_kernel<32>, grid, dim3(256), 0, s, cache->code, cache->len, C, cp, n_new, cand,
+                               n_cand, metric, best);
+        else
+            hipLaunchKernelGGL(tc_match_kernel<64>, grid, dim3(256), 0, s, cache->code, cache->len, C, cp, n_new, cand,
+                               n_cand, metric, best);
+        FASTAR_LAUNCH_CHECK();
+    }
+    hipLaunchKernelGGL(tc_prep_kernel, dim3((n_new + 255) / 256, H), dim3(256), 0, s, best, n_new, C, jstar, sbest, win,
+                       grp);
+    FASTAR_LAUNCH_CHECK();
+    const dim3 tgrid((n_new + 15) / 16, H);
+    const bool bf = dtype == FASTAR_BF16;
+#define FASTAR_TC(KERNEL, ...)                                                                          \
+    do {                                                                                                \
+        if (bf && d == 128) hipLaunchKernelGGL((KERNEL<true, 128>), tgrid, dim3(256), 0, s, __VA_ARGS__);      \
+        else if (bf) hipLaunchKernelGGL((KERNEL<true, 64>), tgrid, dim3(256), 0, s, __VA_ARGS__);               \
+        else if (d == 128) hipLaunchKernelGGL((KERNEL<false, 128>), tgrid, dim3(256), 0, s, __VA_ARGS__);       \
+        else hipLaunchKernelGGL((KERNEL<false, 64>), tgrid, dim3(256), 0, s, __VA_ARGS__);                       \
+    } while (0)
+    FASTAR_TC(tc_verify_kernel, cache->K, K_new, cp, r, C, n_new, codec->qscale, metric, tau2_q16, jstar, sbest, win, grp,
+              merged);
+    FASTAR_LAUNCH_CHECK();
+    hipLaunchKernelGGL(tc_plan_kernel, dim3(H), dim3(256), (size_t)((C + 31) / 32) * 4, s, cache->len, cache->stamp, C,
+                       n_new, jstar, merged, rank, victims, hs, stats);
+    FASTAR_LAUNCH_CHECK();
+    FASTAR_TC(tc_apply_kernel, cache->K, cache->V, cache->code, cache->cnt, cache->stamp, C, r, K_new, V_new, ck, n_new,
+              frame_id, jstar, merged, win, grp, rank, victims, hs, merge_map);
+    FASTAR_LAUNCH_CHECK();
+#undef FASTAR_TC
+    return FASTAR_OK;
+}

@@ -1,0 +1,274 @@
+"""GPU parity: every entry point of libfastar.so against the CPU oracle on the same seeded inputs.
+
+Index outputs (codes, merge maps, selections, cache bookkeeping) must match bit for bit; attention
+outputs within 2e-2 max-abs (bf16) / 1e-4 (fp32); running-mean values within a few units of the
+storage format's last place.
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2602_01801_amd as fa
+from workloads import CONFIGS, FrameStream, PromptSet, make_codec, to_f32, to_storage
+
+from gpu_util import assert_cache_equal, dev_cache, dev_codec, host_cache, storage_to_f64, to_dev, to_host
+
+pytestmark = pytest.mark.gpu
+
+TAU2 = lambda tau: int(round(tau * tau * 65536))
+ATOL = {"fp32": 1e-4, "bf16": 2e-2}
+VTOL = {"fp32": 1e-5, "bf16": 5e-2}
+
+
+def sync():
+    torch.cuda.synchronize()
+
+
+# ----------------------------------------------------------------------------------------- encode
+
+@pytest.mark.parametrize("dtype,d,r,n", [("fp32", 64, 32, 515), ("bf16", 128, 32, 4681), ("bf16", 64, 64, 33),
+                                         ("fp32", 128, 64, 1000), ("bf16", 128, 32, 1), ("fp32", 64, 32, 16)])
+def test_encode_bit_exact(dtype, d, r, n):
+    rng = np.random.default_rng(d * 1000 + r + n)
+    codec = make_codec(0, 7, d, r)
+    x = (rng.standard_normal((n, d)) * 1.3).astype(np.float32)
+    x[0, :4] = [100.0, -100.0, 0.0, 4.5]                       # saturation and exact grid points
+    xs = to_storage(x, dtype)
+    ref = oracle.encode(xs, codec.R, codec.qscale, codec.shift)
+    got = to_host(fa.encode(to_dev(xs), dev_codec(codec)))
+    assert np.array_equal(got, ref)
+
+
+def test_encode_rounding_half_cases_match():
+    # coordinates that land exactly on .5 after scaling (qscale = 2): ties must go to even on both sides
+    d, r = 64, 32
+    codec = make_codec(0, 8, d, r)
+    codec.qscale = np.float32(2.0)
+    rng = np.random.default_rng(5)
+    x = (rng.integers(-40, 41, size=(256, d)) * 0.25).astype(np.float32)
+    for dtype in ("fp32", "bf16"):
+        xs = to_storage(x, dtype)
+        ref = oracle.encode(xs, codec.R, codec.qscale, codec.shift)
+        assert np.array_equal(to_host(fa.encode(to_dev(xs), dev_codec(codec))), ref)
+
+
+# ----------------------------------------------------------------------------------------- selection
+
+def rand_codes(rng, lo, hi, *shape):
+    return rng.integers(lo, hi + 1, size=shape).astype(np.int8)
+
+
+@pytest.mark.parametrize("H,n_q,C,r,BQ,n_rep,BK,n_sel,lens,span", [
+    (2, 256, 1280, 32, 128, 4, 64, 5, [1280, 546], 60),          # cfg1-shaped
+    (3, 300, 64 * 40, 32, 128, 4, 64, 7, [2560, 2000, 0], 3),    # heavy ties, ragged tail, empty head
+    (2, 4680, 64 * 700, 32, 128, 4, 64, 70, [44800, 31111], 50), # rows longer than one scan chunk
+    (2, 200, 640, 64, 64, 8, 32, 4, [640, 333], 40),             # r = 64, BK = 32, n_rep = 8
+    (1, 130, 512, 32, 128, 1, 64, 20, [500], 30),                # one summary per block, budget > blocks
+    (1, 64, 256, 32, 32, 32, 64, 2, [256], 20),                  # per-query summaries
+])
+def test_ann_select_self_bit_exact(H, n_q, C, r, BQ, n_rep, BK, n_sel, lens, span):
+    rng = np.random.default_rng(n_q + C)
+    qc, kc = rand_codes(rng, -span, span, H, n_q, r), rand_codes(rng, -span, span, H, C, r)
+    length = np.array(lens, np.int32)
+    ref_sel, ref_nsel = oracle.ann_select_self(qc, kc, length, BQ, n_rep, BK, n_sel)
+    sel, nsel = fa.ann_select_self(to_dev(qc), to_dev(kc), to_dev(length), BQ, n_rep, BK, n_sel)
+    assert np.array_equal(to_host(nsel), ref_nsel)
+    assert np.array_equal(to_host(sel), ref_sel)
+
+
+@pytest.mark.parametrize("H,n_q,n_p,r,BQ,n_sel,span", [
+    (2, 256, 64, 32, 128, 16, 60), (2, 4680, 512, 32, 128, 64, 50), (1, 300, 2048, 32, 128, 64, 4),
+    (2, 100, 97, 64, 64, 10, 30), (1, 50, 20, 32, 128, 64, 30),
+])
+def test_ann_select_cross_bit_exact(H, n_q, n_p, r, BQ, n_sel, span):
+    rng = np.random.default_rng(n_q + n_p)
+    qc, pc = rand_codes(rng, -span, span, H, n_q, r), rand_codes(rng, -span, span, H, n_p, r)
+    ref_sel, ref_nsel = oracle.ann_select_cross(qc, pc, BQ, n_sel)
+    sel, nsel = fa.ann_select_cross(to_dev(qc), to_dev(pc), BQ, n_sel)
+    assert np.array_equal(to_host(nsel), ref_nsel)
+    assert np.array_equal(to_host(sel), ref_sel)
+
+
+def test_selection_is_deterministic_across_repeats():
+    rng = np.random.default_rng(11)
+    qc, kc = rand_codes(rng, -2, 2, 4, 1000, 32), rand_codes(rng, -2, 2, 4, 64 * 300, 32)
+    length = to_dev(np.array([19200, 19000, 64, 1], np.int32))
+    q, k = to_dev(qc), to_dev(kc)
+    first = fa.ann_select_self(q, k, length, 128, 4, 64, 30)
+    first = (first[0].clone(), first[1].clone())
+    for _ in range(10):
+        again = fa.ann_select_self(q, k, length, 128, 4, 64, 30)
+        assert torch.equal(again[0], first[0]) and torch.equal(again[1], first[1])
+
+
+# ----------------------------------------------------------------------------------------- attention
+
+def random_selection(rng, H, n_qb, n_sel, lens, BK, empty_some=True):
+    sel = np.full((H, n_qb, n_sel), -1, np.int32)
+    nsel = np.zeros((H, n_qb), np.int32)
+    for h in range(H):
+        n_kb = (lens[h] + BK - 1) // BK
+        for b in range(n_qb):
+            if n_kb == 0 or (empty_some and b == 1):
+                continue
+            m = int(rng.integers(1, min(n_sel, n_kb) + 1))
+            sel[h, b, :m] = np.sort(rng.choice(n_kb, size=m, replace=False))
+            nsel[h, b] = m
+    return sel, nsel
+
+
+def check_attention(Q, K, V, cnt, length, sel, nsel, BQ, BK, scale, dtype):
+    O_ref, lse_ref = oracle.sparse_attn_fwd(Q, K, V, cnt, length, sel, nsel, BQ, BK, scale)
+    O, lse = fa.sparse_attn_fwd(to_dev(Q), to_dev(K), to_dev(V), None if cnt is None else to_dev(cnt), to_dev(length),
+                                to_dev(sel), to_dev(nsel), BQ, BK, scale)
+    sync()
+    O = storage_to_f64(to_host(O))
+    lse = to_host(lse).astype(np.float64)
+    assert np.isfinite(O).all()
+    err = np.abs(O - O_ref).max()
+    assert err <= ATOL[dtype], f"max |O - O_ref| = {err}"
+    fin = np.isfinite(lse_ref)
+    assert np.array_equal(np.isneginf(lse), ~fin)
+    assert np.abs(lse[fin] - lse_ref[fin]).max(initial=0.0) <= (1e-4 if dtype == "fp32" else 2e-2)
+    return err
+
+
+@pytest.mark.parametrize("dtype,H,n_q,C,d,BQ,BK,n_sel,lens,use_cnt", [
+    ("fp32", 2, 256, 1280, 64, 128, 64, 6, [1280, 546], True),       # cfg1-shaped
+    ("fp32", 1, 100, 300, 128, 64, 16, 9, [291], False),
+    ("bf16", 3, 700, 64 * 50, 128, 128, 64, 12, [3200, 2011, 0], True),   # ragged query tail, ragged / empty caches
+    ("bf16", 2, 300, 2048, 128, 128, 1, 64, [2048, 1500], False),    # token-granular gather (cross-attention)
+    ("bf16", 2, 260, 1024, 64, 64, 64, 5, [1024, 1000], True),       # d = 64, BQ = 64
+    ("bf16", 1, 128, 512, 128, 64, 8, 40, [509], True),              # small key blocks
+    ("bf16", 2, 200, 640, 64, 128, 64, 10, [640, 600], False),
+])
+def test_sparse_attention_matches_oracle(dtype, H, n_q, C, d, BQ, BK, n_sel, lens, use_cnt):
+    rng = np.random.default_rng(n_q * 7 + C)
+    Q = to_storage(rng.standard_normal((H, n_q, d)).astype(np.float32), dtype)
+    K = to_storage(rng.standard_normal((H, C, d)).astype(np.float32), dtype)
+    V = to_storage(rng.standard_normal((H, C, d)).astype(np.float32), dtype)
+    length = np.array(lens, np.int32)
+    for h in range(H):                                               # poison dead slots: they must stay invisible
+        K[h, lens[h]:] = to_storage(np.full((C - lens[h], d), np.nan, np.float32), dtype)
+        V[h, lens[h]:] = to_storage(np.full((C - lens[h], d), np.inf, np.float32), dtype)
+    cnt = rng.integers(1, 9, size=(H, C)).astype(np.int32) if use_cnt else None
+    n_qb = (n_q + BQ - 1) // BQ
+    sel, nsel = random_selection(rng, H, n_qb, n_sel, lens, BK)
+    check_attention(Q, K, V, cnt, length, sel, nsel, BQ, BK, d ** -0.5, dtype)
+
+
+def test_dense_limit_on_clustered_data_fp32_and_bf16():
+    for name, dtype in (("cfg1", "fp32"), ("cfg1", "bf16")):
+        c = CONFIGS[name]
+        fs = FrameStream.from_config(name, dtype=dtype)
+        frames = [fs.next_frame() for _ in range(3)]
+        K = np.concatenate([k for k, _ in frames], axis=1)
+        V = np.concatenate([v for _, v in frames], axis=1)
+        Q = fs.queries(1)
+        length = np.full(c["H"], K.shape[1], np.int32)
+        sel, nsel = oracle.full_selection(c["H"], Q.shape[1], 128, length, 64)
+        check_attention(Q, K, V, None, length, sel, nsel, 128, 64, c["d"] ** -0.5, dtype)
+
+
+# ----------------------------------------------------------------------------------------- TempCache
+
+def run_rollout(name, n_frames, C, tau, dtype=None, H=None, windowed=True, metric=0, probe_queries=False):
+    over = {}
+    if dtype:
+        over["dtype"] = dtype
+    c = dict(CONFIGS[name]); c.update(over)
+    if H:
+        c["H"] = H
+    fs = FrameStream(c["seed"], c["cfg_id"], c["H"], c["d"], c["T"], c["n_c"], c["p"], c["sigma_d"], c["dtype"])
+    codec = make_codec(c["seed"], c["cfg_id"], c["d"], c["r"])
+    ref = oracle.Cache.empty(c["H"], C, c["d"], c["r"], c["dtype"])
+    gpu = dev_cache(ref)
+    dcodec = dev_codec(codec)
+    prev_ref, prev_gpu = None, None
+    for f in range(n_frames):
+        K, V = fs.next_frame()
+        P = fs.queries(1) if probe_queries else None
+        mm_r, mg_r, st_r = oracle.tempcache_compress(ref, codec.R, codec.qscale, codec.shift, K, V, P_new=P,
+                                                     cand=prev_ref if windowed else None, metric=metric,
+                                                     tau2_q16=TAU2(tau), frame_id=f)
+        mm_g, mg_g, st_g = fa.tempcache_compress(gpu, dcodec, to_dev(K), to_dev(V),
+                                                 P_new=None if P is None else to_dev(P),
+                                                 cand=prev_gpu if windowed else None, metric=metric,
+                                                 tau2_q16=TAU2(tau), frame_id=f)
+        sync()
+        assert np.array_equal(to_host(mg_g), mg_r), f"merged flags, frame {f}"
+        assert np.array_equal(to_host(mm_g), mm_r), f"merge map, frame {f}"
+        assert np.array_equal(to_host(st_g), st_r), f"stats, frame {f}"
+        assert_cache_equal(host_cache(gpu), ref, VTOL[c["dtype"]])
+        prev_ref, prev_gpu = mm_r, mm_g
+    return c, fs, codec, ref, gpu
+
+
+def test_tempcache_rollout_cfg1_bit_exact():
+    c, fs, codec, ref, gpu = run_rollout("cfg1", 6, 6 * 256, 0.98)
+    assert ref.len.max() < 6 * 256 and ref.cnt.max() > 1          # merging did happen
+
+
+def test_tempcache_eviction_and_drops_bit_exact():
+    c, fs, codec, ref, gpu = run_rollout("cfg1", 8, 2 * 256 + 40, 0.98)
+    run_rollout("cfg1", 2, 100, 2.0 ** 0.5)                            # capacity below one frame: drops
+
+
+def test_tempcache_whole_cache_match_and_inner_product_probe():
+    run_rollout("cfg1", 4, 5 * 256, 0.9, windowed=False)
+    run_rollout("cfg1", 4, 5 * 256, 0.9, windowed=True, metric=1, probe_queries=True)
+
+
+def test_tempcache_bf16_wan_shaped_heads():
+    # two heads of the Wan-shaped layer: 1560 tokens per frame (not a multiple of any tile), d = 128
+    c, fs, codec, ref, gpu = run_rollout("cfg2", 4, 4 * 1560, 0.98, H=2)
+    assert 0.7 < 1 - (ref.len[0] - 1560) / (3 * 1560) < 0.9            # about p = 0.8 of each frame merges
+
+
+def test_tempcache_then_select_then_attend_end_to_end_cfg1():
+    c, fs, codec, ref, gpu = run_rollout("cfg1", 5, 5 * 256, 0.98)
+    Q = fs.queries(1)
+    dcodec = dev_codec(codec)
+    qc_ref = oracle.encode(Q, codec.R, codec.qscale, codec.shift)
+    qc = fa.encode(to_dev(Q), dcodec)
+    assert np.array_equal(to_host(qc), qc_ref)
+    n_sel = 5
+    sel_r, nsel_r = oracle.ann_select_self(qc_ref, ref.code, ref.len, 128, 4, 64, n_sel)
+    sel, nsel = fa.ann_select_self(qc, gpu.code, gpu.len, 128, 4, 64, n_sel)
+    assert np.array_equal(to_host(sel), sel_r) and np.array_equal(to_host(nsel), nsel_r)
+    O_ref, _ = oracle.sparse_attn_fwd(Q, ref.K, ref.V, ref.cnt, ref.len, sel_r, nsel_r, 128, 64, c["d"] ** -0.5)
+    O, _ = fa.sparse_attn_fwd(to_dev(Q), gpu.K, gpu.V, gpu.cnt, gpu.len, sel, nsel, 128, 64, c["d"] ** -0.5)
+    assert np.abs(to_host(O).astype(np.float64) - O_ref).max() <= 1e-4
+    # cross-attention leg
+    ps = PromptSet(c["seed"], c["cfg_id"], fs.centreK, c["n_p"], c["n_pc"], c["n_near"], c["dtype"])
+    pc_ref = oracle.encode(ps.K, codec.R, codec.qscale, codec.shift)
+    pc = fa.encode(to_dev(ps.K), dcodec)
+    csel_r, cnsel_r = oracle.ann_select_cross(qc_ref, pc_ref, 128, c["n_sel_cross"])
+    csel, cnsel = fa.ann_select_cross(qc, pc, 128, c["n_sel_cross"])
+    assert np.array_equal(to_host(csel), csel_r) and np.array_equal(to_host(cnsel), cnsel_r)
+    n_p = c["n_p"]
+    plen = np.full(c["H"], n_p, np.int32)
+    O_ref, _ = oracle.sparse_attn_fwd(Q, ps.K, ps.V, None, plen, csel_r, cnsel_r, 128, 1, c["d"] ** -0.5)
+    O, _ = fa.sparse_attn_fwd(to_dev(Q), to_dev(ps.K), to_dev(ps.V), None, to_dev(plen), csel, cnsel, 128, 1,
+                              c["d"] ** -0.5)
+    assert np.abs(to_host(O).astype(np.float64) - O_ref).max() <= 1e-4
+
+
+# ----------------------------------------------------------------------------------------- argument checks
+
+def test_bad_arguments_are_rejected_on_the_host():
+    q = torch.zeros((1, 128, 32), dtype=torch.int8, device="cuda")
+    k = torch.zeros((1, 256, 32), dtype=torch.int8, device="cuda")
+    length = torch.full((1,), 256, dtype=torch.int32, device="cuda")
+    with pytest.raises(fa.FastarError, match="invalid"):
+        fa.ann_select_self(q, k, length, 128, 3, 64, 2)              # BQ not a multiple of n_rep
+    with pytest.raises(fa.FastarError, match="unsupported"):
+        fa.ann_select_self(q, k, length, 128, 4, 48, 2)              # BK not a multiple of 32
+    with pytest.raises(fa.FastarError, match="workspace"):
+        fa.ann_select_self(q, k, length, 128, 4, 64, 2, ws=torch.empty(256, dtype=torch.uint8, device="cuda"))
+    Q = torch.zeros((1, 128, 96), dtype=torch.bfloat16, device="cuda")
+    sel = torch.zeros((1, 1, 2), dtype=torch.int32, device="cuda")
+    nsel = torch.zeros((1, 1), dtype=torch.int32, device="cuda")
+    with pytest.raises(fa.FastarError, match="unsupported"):
+        fa.sparse_attn_fwd(Q, Q, Q, None, length, sel, nsel, 128, 64, 0.1)   # d = 96
