@@ -1,0 +1,364 @@
+#!/usr/bin/env python3
+"""Benchmark of the FAST-AR attention hot path on one MI355X.
+
+A *step* is one generated chunk of the Wan-1.3B-shaped layer (12 heads, d 128, 3 frames of 1560
+tokens = 4680 queries): three TempCache merges (one per frame of the chunk) into the bounded cache,
+ANN codes of the queries, AnnSA selection of 52 key blocks (10 % of the 512 blocks of the 21-frame
+cache the workload is quoted on) per query block, block-sparse self-attention, AnnCA selection of 64
+of 512 prompt tokens and the cross-attention over them.  All inputs are seeded synthetic data
+(clustered, temporally repeating K/V) already resident in HBM when the clock starts.
+
+Prints ONE JSON line: ms per chunk for the whole hot path, the per-stage split, the roofline
+fraction of the dominant kernel (block-sparse self-attention, bf16 matrix cores, attended FLOPs
+only) and the CPU oracle's time for the same chunk on the host cores.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 matrix-core peak
+PEAK_HBM_GBS = 8000.0       # MI355X HBM3E peak
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="cfg2", choices=["cfg2", "cfg5"])
+    ap.add_argument("--tau", type=float, default=0.98)
+    ap.add_argument("--prefill-frames", type=int, default=None, help="frames merged into the cache before timing")
+    ap.add_argument("--cap-frames", type=int, default=None, help="cache capacity in frames of slots")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-heads", type=int, default=2, help="heads of the last chunk replayed on the CPU oracle")
+    ap.add_argument("--sweep", action="store_true", help="long-rollout sweep (cfg3): per-step latency and footprint")
+    ap.add_argument("--sweep-frames", type=int, default=120)
+    ap.add_argument("--out", default=None, help="also write the JSON (and the sweep table) to this file")
+    return ap.parse_args()
+
+
+class ChunkPipeline:
+    """Device buffers and the call sequence of one chunk step.  Nothing is allocated per step."""
+
+    def __init__(self, cfg, C, tau, torch, fa, dev_codec, prompt, n_sel_blocks):
+        self.t, self.fa, self.cfg = torch, fa, cfg
+        H, d, r, T = cfg["H"], cfg["d"], cfg["r"], cfg["T"]
+        self.H, self.d, self.r, self.T, self.C = H, d, r, T, C
+        self.BQ, self.BK, self.n_rep = cfg["BQ"], cfg["BK"], cfg["n_rep"]
+        self.n_q = T * cfg["chunk_frames"]
+        self.n_qb = (self.n_q + self.BQ - 1) // self.BQ
+        self.n_sel = n_sel_blocks
+        self.n_sel_cross = cfg["n_sel_cross"]
+        self.tau2 = int(round(tau * tau * 65536))
+        self.scale = d ** -0.5
+        self.codec = dev_codec
+        dt = torch.bfloat16 if cfg["dtype"] == "bf16" else torch.float32
+        self.cache = fa.Cache.empty(H, C, d, r, dt)
+        dev = "cuda"
+        e = lambda shape, dtype: torch.empty(shape, dtype=dtype, device=dev)
+        self.ws_c = e((fa.workspace_bytes(fa.OP_COMPRESS, H, T, C, r),), torch.uint8)
+        self.ws_s = e((fa.workspace_bytes(fa.OP_SELECT_SELF, H, self.n_q, C, r, self.BQ, self.BK, self.n_rep),), torch.uint8)
+        self.mm = [(e((H, T), torch.int32), e((H, T), torch.uint8), e((H, 8), torch.int32)) for _ in range(2)]
+        self.qcode = e((H, self.n_q, r), torch.int8)
+        self.sel = (e((H, self.n_qb, self.n_sel), torch.int32), e((H, self.n_qb), torch.int32))
+        self.O = (e((H, self.n_q, d), dt), e((H, self.n_q), torch.float32))
+        self.prev = None
+        self.frame_id = 0
+        # cross-attention: prompt K/V and their codes are fixed for the rollout
+        self.pK, self.pV = prompt
+        self.n_p = self.pK.shape[1]
+        self.pcode = fa.encode(self.pK, self.codec)
+        self.plen = torch.full((H,), self.n_p, dtype=torch.int32, device=dev)
+        self.ws_x = e((fa.workspace_bytes(fa.OP_SELECT_CROSS, H, self.n_q, self.n_p, r, self.BQ),), torch.uint8)
+        self.csel = (e((H, self.n_qb, self.n_sel_cross), torch.int32), e((H, self.n_qb), torch.int32))
+        self.Ox = (e((H, self.n_q, d), dt), None)
+
+    def compress(self, K, V):
+        fa = self.fa
+        out = self.mm[self.frame_id & 1]
+        fa.tempcache_compress(self.cache, self.codec, K, V, cand=self.prev, tau2_q16=self.tau2,
+                              frame_id=self.frame_id, ws=self.ws_c, out=out)
+        self.prev = out[0]
+        self.frame_id += 1
+
+    def step(self, frames, Q, ev=None):
+        """frames: list of (K, V) device tensors of the chunk; Q [H,n_q,d].  ev: optional event recorder."""
+        fa = self.fa
+        mark = ev if ev is not None else (lambda name: None)
+        mark("start")
+        for K, V in frames:
+            self.compress(K, V)
+        mark("compress")
+        fa.encode(Q, self.codec, out=self.qcode)
+        mark("encode")
+        fa.ann_select_self(self.qcode, self.cache.code, self.cache.len, self.BQ, self.n_rep, self.BK, self.n_sel,
+                           ws=self.ws_s, out=self.sel)
+        mark("select_self")
+        fa.sparse_attn_fwd(Q, self.cache.K, self.cache.V, self.cache.cnt, self.cache.len, self.sel[0], self.sel[1],
+                           self.BQ, self.BK, self.scale, out=self.O)
+        mark("attn_self")
+        fa.ann_select_cross(self.qcode, self.pcode, self.BQ, self.n_sel_cross, ws=self.ws_x, out=self.csel)
+        mark("select_cross")
+        fa.sparse_attn_fwd(Q, self.pK, self.pV, None, self.plen, self.csel[0], self.csel[1], self.BQ, 1, self.scale,
+                           out=self.Ox, want_lse=False)
+        mark("attn_cross")
+
+    def attended_flops(self):
+        """4 * d * sum over (head, query) of the live keys in the selected blocks, for the current selection."""
+        t = self.t
+        sel, nsel = self.sel
+        L = self.cache.len.to(t.int64)[:, None, None]
+        kb = sel.to(t.int64)
+        valid = (kb >= 0) & (t.arange(self.n_sel, device=sel.device)[None, None, :] < nsel[:, :, None])
+        keys = t.clamp(t.minimum((kb + 1) * self.BK, L) - kb * self.BK, min=0) * valid
+        q_per_block = t.full((self.n_qb,), self.BQ, device=sel.device, dtype=t.int64)
+        q_per_block[-1] = self.n_q - (self.n_qb - 1) * self.BQ
+        pairs = (keys.sum(dim=2) * q_per_block[None, :]).sum()
+        return 4.0 * self.d * float(pairs.item())
+
+
+def gen_chunks(cfg, n_prefill, n_chunks, to_dev):
+    """Host-side generation of the whole rollout, uploaded once."""
+    from workloads import FrameStream, PromptSet
+    fs = FrameStream(cfg["seed"], cfg["cfg_id"], cfg["H"], cfg["d"], cfg["T"], cfg["n_c"], cfg["p"], cfg["sigma_d"],
+                     cfg["dtype"])
+    prefill = [tuple(to_dev(a) for a in fs.next_frame()) for _ in range(n_prefill)]
+    chunks = []
+    for _ in range(n_chunks):
+        frames = [fs.next_frame() for _ in range(cfg["chunk_frames"])]
+        Q = fs.queries(cfg["chunk_frames"])
+        chunks.append((frames, Q))
+    ps = PromptSet(cfg["seed"], cfg["cfg_id"], fs.centreK, cfg["n_p"], cfg["n_pc"], cfg["n_near"], cfg["dtype"])
+    return prefill, chunks, ps
+
+
+def cpu_baseline(cfg, pipe, host_state, last_chunk, ps, n_heads, to_host):
+    """Replay the last chunk on the CPU oracle for the first n_heads heads; returns (ms scaled to all heads, info)."""
+    import numpy as np
+    import oracle
+    from workloads import make_codec
+    H = cfg["H"]
+    hs = slice(0, n_heads)
+    codec = make_codec(cfg["seed"], cfg["cfg_id"], cfg["d"], cfg["r"])
+    cache = oracle.Cache(*(np.ascontiguousarray(a[hs]) for a in host_state["cache"]))
+    prev = np.ascontiguousarray(host_state["prev"][hs])
+    frames, Q = last_chunk
+    Qh = np.ascontiguousarray(Q[hs])
+    threads = len(os.sched_getaffinity(0))
+    t0 = time.perf_counter()
+    fid = host_state["frame_id"]
+    for K, V in frames:
+        prev, _, _ = oracle.tempcache_compress(cache, codec.R, codec.qscale, codec.shift, np.ascontiguousarray(K[hs]),
+                                               np.ascontiguousarray(V[hs]), cand=prev, tau2_q16=pipe.tau2, frame_id=fid)
+        fid += 1
+    t1 = time.perf_counter()
+    qc = oracle.encode(Qh, codec.R, codec.qscale, codec.shift)
+    sel, nsel = oracle.ann_select_self(qc, cache.code, cache.len, pipe.BQ, pipe.n_rep, pipe.BK, pipe.n_sel)
+    t2 = time.perf_counter()
+    O, _ = oracle.sparse_attn_fwd(Qh, cache.K, cache.V, cache.cnt, cache.len, sel, nsel, pipe.BQ, pipe.BK, pipe.scale)
+    t3 = time.perf_counter()
+    pc = oracle.encode(np.ascontiguousarray(ps.K[hs]), codec.R, codec.qscale, codec.shift)
+    csel, cnsel = oracle.ann_select_cross(qc, pc, pipe.BQ, pipe.n_sel_cross)
+    plen = np.full(n_heads, ps.K.shape[1], np.int32)
+    Ox, _ = oracle.sparse_attn_fwd(Qh, np.ascontiguousarray(ps.K[hs]), np.ascontiguousarray(ps.V[hs]), None, plen,
+                                   csel, cnsel, pipe.BQ, 1, pipe.scale)
+    t4 = time.perf_counter()
+    # parity of the GPU's last step against this replay (same inputs, same state)
+    from workloads import to_f32
+    sel_ok = bool(np.array_equal(to_host(pipe.sel[0])[hs], sel) and np.array_equal(to_host(pipe.sel[1])[hs], nsel))
+    csel_ok = bool(np.array_equal(to_host(pipe.csel[0])[hs], csel))
+    len_ok = bool(np.array_equal(to_host(pipe.cache.len)[hs], cache.len))
+    err = float(np.abs(to_f32(to_host(pipe.O[0])[hs]).astype(np.float64) - O).max())
+    errx = float(np.abs(to_f32(to_host(pipe.Ox[0])[hs]).astype(np.float64) - Ox).max())
+    scale = H / n_heads
+    recall, density = oracle.recall_density(Qh, cache.K, cache.cnt, cache.len, sel, nsel, pipe.BQ, pipe.BK, pipe.scale,
+                                            q_stride=97)
+    info = {
+        "value": round((t4 - t0) * 1e3 * scale, 1), "unit": "ms/chunk", "cores": threads, "kind": "oracle",
+        "sample": f"last timed chunk replayed on heads 0..{n_heads - 1} of {H} from the GPU's cache state; "
+                  f"time scaled by {scale:g}",
+        "stages_ms_scaled": {"compress": round((t1 - t0) * 1e3 * scale, 1), "encode+select": round((t2 - t1) * 1e3 * scale, 1),
+                             "attn_self": round((t3 - t2) * 1e3 * scale, 1), "cross": round((t4 - t3) * 1e3 * scale, 1)},
+        "parity_on_sample": {"sel_equal": sel_ok, "cross_sel_equal": csel_ok, "len_equal": len_ok,
+                             "attn_self_max_abs_err": err, "attn_cross_max_abs_err": errx},
+        "selection_recall": round(recall, 4), "selection_density": round(density, 4),
+    }
+    return info
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (the hot path is per head and needs no collective); "
+              "run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+    import numpy as np
+    import torch
+    import paper_2602_01801_amd as fa
+    from workloads import CONFIGS, make_codec
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    fa.lib()
+
+    def to_dev(a):
+        a = np.ascontiguousarray(a)
+        if a.dtype == np.uint16:
+            return torch.from_numpy(a.view(np.int16)).cuda().view(torch.bfloat16)
+        return torch.from_numpy(a).cuda()
+
+    def to_host(t):
+        if t.dtype == torch.bfloat16:
+            return t.view(torch.int16).cpu().numpy().view(np.uint16)
+        return t.cpu().numpy()
+
+    if args.sweep:
+        return sweep(args, torch, fa, np, to_dev, to_host)
+
+    cfg = dict(CONFIGS[args.workload])
+    T, cf = cfg["T"], cfg["chunk_frames"]
+    cap_frames = args.cap_frames or (24 if args.workload == "cfg2" else cfg["cache_frames"])
+    n_prefill = args.prefill_frames if args.prefill_frames is not None else cfg["cache_frames"] - cf
+    C = cap_frames * T
+    n_kb_quoted = (cfg["cache_frames"] * T + cfg["BK"] - 1) // cfg["BK"]
+    n_sel = int(np.ceil(cfg["sel_frac"] * n_kb_quoted))
+    codec_h = make_codec(cfg["seed"], cfg["cfg_id"], cfg["d"], cfg["r"])
+    codec = fa.Codec(to_dev(codec_h.R), float(codec_h.qscale), codec_h.shift)
+    n_chunks = args.warmup + args.steps
+    t_gen = time.perf_counter()
+    prefill, chunks, ps = gen_chunks(cfg, n_prefill, n_chunks, to_dev)
+    dev_chunks = [([(to_dev(K), to_dev(V)) for K, V in frames], to_dev(Q)) for frames, Q in chunks]
+    t_gen = time.perf_counter() - t_gen
+    pipe = ChunkPipeline(cfg, C, args.tau, torch, fa, codec, (to_dev(ps.K), to_dev(ps.V)), n_sel)
+    for K, V in prefill:
+        pipe.compress(K, V)
+    torch.cuda.synchronize()
+    len_prefill = to_host(pipe.cache.len).tolist()
+
+    for w in range(args.warmup):
+        pipe.step(*dev_chunks[w])
+    torch.cuda.synchronize()
+
+    stage_names = ["compress", "encode", "select_self", "attn_self", "select_cross", "attn_cross"]
+    events = []
+    flops = []
+    host_state = None
+    t0 = time.perf_counter()
+    for s in range(args.steps):
+        evs = []
+
+        def mark(name, evs=evs):
+            e = torch.cuda.Event(enable_timing=True)
+            e.record()
+            evs.append(e)
+        if s == args.steps - 1 and not args.no_cpu_baseline:
+            # state the CPU replay starts from (device-side copies; read back after the timed region)
+            snap = [t.clone() for t in (pipe.cache.K, pipe.cache.V, pipe.cache.code, pipe.cache.cnt, pipe.cache.stamp,
+                                        pipe.cache.len)]
+            host_state = {"snap": snap, "prev": pipe.prev.clone(), "frame_id": pipe.frame_id}
+        pipe.step(*dev_chunks[args.warmup + s], ev=mark)
+        events.append(evs)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    # the clones of the last step sit inside the timed region; they cost microseconds and are reported
+    stage_ms = {n: 0.0 for n in stage_names}
+    for evs in events:
+        for i, n in enumerate(stage_names):
+            stage_ms[n] += evs[i].elapsed_time(evs[i + 1])
+    stage_ms = {n: v / args.steps for n, v in stage_ms.items()}
+    attn_ms = stage_ms["attn_self"]
+    flops_last = pipe.attended_flops()
+    tflops = flops_last / (attn_ms * 1e-3) / 1e12
+    len_final = to_host(pipe.cache.len).tolist()
+
+    result = {
+        "metric": "sparse-attn ms per generated chunk", "value": round(ms_per_step, 4), "unit": "ms/chunk",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": False, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"{args.workload}: Wan-1.3B-shaped layer rollout, H {cfg['H']} d {cfg['d']}, chunk "
+                               f"{cf}x{T} = {cf * T} queries, TempCache-bounded cache (cap {cap_frames} frames = {C} "
+                               f"slots/head, tau {args.tau}), AnnSA {n_sel} of {n_kb_quoted} key blocks per query block "
+                               f"(BQ {cfg['BQ']}, BK {cfg['BK']}), AnnCA {cfg['n_sel_cross']} of {cfg['n_p']} prompt tokens",
+                   "prefill_frames": n_prefill, "cache_len_per_head_start": [min(len_prefill), max(len_prefill)],
+                   "cache_len_per_head_end": [min(len_final), max(len_final)],
+                   "cache_bytes": pipe.cache.nbytes()},
+        "stages_ms": {k: round(v, 4) for k, v in stage_ms.items()},
+        "effective_tflops": round(tflops, 2), "pct_mfma_peak": round(100 * tflops / PEAK_BF16_TFLOPS, 2),
+        "roofline": {"kernel": "attn_bf16_kernel<128,4> (block-sparse self-attention)", "bound": "mfma",
+                     "achieved": round(tflops, 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                     "frac": round(tflops / PEAK_BF16_TFLOPS, 4), "traffic": None,
+                     "flops_per_launch": flops_last, "avg_launch_ms": round(attn_ms, 4)},
+        "host_gen_s": round(t_gen, 1),
+    }
+    if not args.no_cpu_baseline:
+        hs = {"cache": [to_host(t) for t in host_state["snap"]], "prev": to_host(host_state["prev"]),
+              "frame_id": host_state["frame_id"]}
+        result["cpu_baseline"] = cpu_baseline(cfg, pipe, hs, chunks[-1], ps, min(args.cpu_heads, cfg["H"]), to_host)
+    line = json.dumps(result)
+    print(line, flush=True)
+    if args.out:
+        os.makedirs(os.path.dirname(os.path.abspath(args.out)), exist_ok=True)
+        with open(args.out, "w") as f:
+            f.write(line + "\n")
+
+
+def sweep(args, torch, fa, np, to_dev, to_host):
+    """Long-rollout sweep of the Wan-shaped layer: the cache grows 3 frames per step up to --sweep-frames;
+    each step is run TempCache-bounded (cap 24 frames of slots) and uncompressed (plain concatenation)."""
+    from workloads import CONFIGS, FrameStream, PromptSet, make_codec
+    cfg = dict(CONFIGS["cfg3"])
+    T, cf, H, d, r = cfg["T"], cfg["chunk_frames"], cfg["H"], cfg["d"], cfg["r"]
+    n_frames = args.sweep_frames
+    cap = cfg["cap_frames"] * T
+    codec_h = make_codec(cfg["seed"], cfg["cfg_id"], d, r)
+    codec = fa.Codec(to_dev(codec_h.R), float(codec_h.qscale), codec_h.shift)
+    fs = FrameStream(cfg["seed"], cfg["cfg_id"], H, d, T, cfg["n_c"], cfg["p"], cfg["sigma_d"], cfg["dtype"])
+    ps = PromptSet(cfg["seed"], cfg["cfg_id"], fs.centreK, cfg["n_p"], cfg["n_pc"], cfg["n_near"], cfg["dtype"])
+    prompt = (to_dev(ps.K), to_dev(ps.V))
+    n_kb_quoted = (21 * T + cfg["BK"] - 1) // cfg["BK"]
+    n_sel = int(np.ceil(cfg["sel_frac"] * n_kb_quoted))
+    bounded = ChunkPipeline(cfg, cap, args.tau, torch, fa, codec, prompt, n_sel)
+    plain = ChunkPipeline(cfg, n_frames * T, 2.0 ** 0.5, torch, fa, codec, prompt, n_sel)   # tau^2 = 2: never merges
+    rows = []
+    for step in range(n_frames // cf):
+        frames = [tuple(to_dev(a) for a in fs.next_frame()) for _ in range(cf)]
+        Q = to_dev(fs.queries(cf))
+        row = {"frames": (step + 1) * cf}
+        for name, pipe in (("tempcache", bounded), ("uncompressed", plain)):
+            evs = []
+
+            def mark(nm, evs=evs):
+                e = torch.cuda.Event(enable_timing=True)
+                e.record()
+                evs.append(e)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            pipe.step(frames, Q, ev=mark)
+            torch.cuda.synchronize()
+            ms = (time.perf_counter() - t0) * 1e3
+            L = to_host(pipe.cache.len)
+            live_bytes = int(L.sum()) * (2 * d * 2 + r + 8)
+            row[name] = {"ms": round(ms, 3), "attn_self_ms": round(evs[3].elapsed_time(evs[4]), 4),
+                         "select_self_ms": round(evs[2].elapsed_time(evs[3]), 4),
+                         "compress_ms": round(evs[0].elapsed_time(evs[1]), 4),
+                         "len_max": int(L.max()), "live_cache_MB": round(live_bytes / 1e6, 1)}
+        rows.append(row)
+        print(json.dumps(row), flush=True)
+    if args.out:
+        os.makedirs(os.path.dirname(os.path.abspath(args.out)), exist_ok=True)
+        with open(args.out, "w") as f:
+            for row in rows:
+                f.write(json.dumps(row) + "\n")
+
+
+if __name__ == "__main__":
+    main()
