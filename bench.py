@@ -42,6 +42,9 @@ def parse():
     ap.add_argument("--sweep", action="store_true", help="long-rollout sweep (cfg3): per-step latency and footprint")
     ap.add_argument("--sweep-frames", type=int, default=120)
     ap.add_argument("--out", default=None, help="also write the JSON (and the sweep table) to this file")
+    ap.add_argument("--calib-copy-mb", type=int, default=0,
+                    help="after the timed loop, run one plain device copy of this many MiB (a known-size "
+                         "reference for scaling the profiler's FETCH_SIZE / WRITE_SIZE counters)")
     return ap.parse_args()
 
 
@@ -269,6 +272,13 @@ def main():
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     ms_per_step = (t1 - t0) * 1e3 / args.steps
+    if args.calib_copy_mb > 0:
+        src = torch.ones(args.calib_copy_mb << 20, dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     # the clones of the last step sit inside the timed region; they cost microseconds and are reported
     stage_ms = {n: 0.0 for n in stage_names}
     for evs in events:

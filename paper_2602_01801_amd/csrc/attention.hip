@@ -367,6 +367,10 @@ __global__ __launch_bounds__(128) void attn_f32_kernel(const float *__restrict__
     }
 }
 
+int launch_attn_bf16_d128(const void *Q, int n_q, const void *K, const void *V, const int32_t *cnt, const int32_t *len,
+                          int H, int C, const int32_t *sel, const int32_t *nsel, int BQ, int bk_shift, int n_sel,
+                          float scale_log2, void *O, float *lse, hipStream_t s);
+
 }  // namespace fastar
 
 using namespace fastar;
@@ -393,9 +397,9 @@ extern "C" int sparse_attn_fwd(const void *Q, int n_q, const void *K, const void
     hipLaunchKernelGGL((attn_bf16_kernel<DD, NW>), grid, dim3(NW * 64), 0, s, (const unsigned short *)Q,          \
                        (const unsigned short *)K, (const unsigned short *)V, cnt, len, sel, nsel, n_q, C, bk_shift, \
                        n_sel, n_qb, H, scale_log2, (unsigned short *)O, lse)
-        if (d == 128 && BQ == 128) FASTAR_ATTN(128, 4);
-        else if (d == 128) FASTAR_ATTN(128, 2);
-        else if (BQ == 128) FASTAR_ATTN(64, 4);
+        if (d == 128)  // tuned path: direct-to-LDS tiles, LDS transpose loads
+            return launch_attn_bf16_d128(Q, n_q, K, V, cnt, len, H, C, sel, nsel, BQ, bk_shift, n_sel, scale_log2, O, lse, s);
+        if (BQ == 128) FASTAR_ATTN(64, 4);
         else FASTAR_ATTN(64, 2);
 #undef FASTAR_ATTN
     } else {

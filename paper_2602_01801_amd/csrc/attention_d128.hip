@@ -1,0 +1,288 @@
+// Block-sparse attention, bf16, head dimension 128: the tuned path of sparse_attn_fwd.
+//
+// Same mathematics and the same "transposed" formulation as the generic kernel in attention.hip
+// (S^T = K Q^T, O^T = V^T P^T, every per-query quantity in one lane), with a leaner data path:
+//   * K and V tiles (64 gathered rows x 256 bytes) go from global memory straight into LDS with
+//     16-byte direct loads: no staging registers, no VALU work, two LDS stages so that the loads
+//     of tile t+1 fly while tile t is consumed, one workgroup barrier per tile;
+//   * rows are stored unpadded and XOR-swizzled at 16-byte granularity (the swizzle is applied to
+//     the global address each lane fetches, so it costs nothing): K chunk c of row r sits at chunk
+//     c ^ (r & 15), V chunk c of row r at chunk c ^ (2 (r & 7)); both read patterns below are
+//     bank-conflict free;
+//   * the V^T operand is read from the row-major V tile with the LDS transpose load
+//     (ds_read_b64_tr_b16): in each group of 16 lanes, lane 4q+m receives element m of the 8-byte
+//     pieces addressed by lanes q, q+4, q+8, q+12, i.e. four consecutive keys of one value column;
+//   * masked rows (padding of the selection list, slots beyond len) fetch row 0 of the head, which
+//     is live, and carry a -inf bias, so they contribute exactly zero;
+//   * the running-maximum rescale of O is skipped when no lane of the wavefront saw a new maximum.
+#include "common.hpp"
+
+namespace fastar {
+
+namespace d128 {
+
+constexpr int D = 128;
+constexpr int TK = 64;                 // keys per tile
+constexpr int ROWB = D * 2;            // bytes per K/V row
+constexpr int TILEB = TK * ROWB;       // 16 KiB per tile
+constexpr float LN2 = 0.6931471805599453f;
+
+typedef __attribute__((ext_vector_type(4))) short s16x4;
+#define LDS_PTR(T, p) ((__attribute__((address_space(3))) T *)(p))
+
+struct __attribute__((aligned(16))) TileMeta {
+    int idx[TK];     // cache row of each tile position (masked positions: row 0)
+    float bias[TK];  // log2(cnt) of that row, -inf when masked
+};
+
+__device__ __forceinline__ void fill_meta(TileMeta &m, int t, const int32_t *__restrict__ sel_row, int n_listed,
+                                          int bk_shift, int L, const int32_t *__restrict__ cnt_h) {
+    const int p = threadIdx.x;
+    if (p < TK) {
+        const int listpos = t * TK + p;
+        const int entry = listpos >> bk_shift;
+        int key = -1;
+        if (entry < n_listed) {
+            const int kb = sel_row[entry];
+            if (kb >= 0) {
+                key = (kb << bk_shift) + (listpos & ((1 << bk_shift) - 1));
+                if (key >= L) key = -1;
+            }
+        }
+        float bias = -INFINITY;
+        if (key >= 0) bias = cnt_h ? __log2f((float)cnt_h[key]) : 0.0f;
+        m.idx[p] = key >= 0 ? key : 0;
+        m.bias[p] = bias;
+    }
+}
+
+// dynamic LDS layout: [K stage 0][K stage 1][V stage 0][V stage 1][meta x3]
+constexpr int LDS_BYTES = 4 * TILEB + 3 * (int)sizeof(TileMeta);
+
+template <int NW>
+__global__ __launch_bounds__(NW * 64, 2) void attn_bf16_d128_kernel(
+    const unsigned short *__restrict__ Q, const unsigned short *__restrict__ K, const unsigned short *__restrict__ V,
+    const int32_t *__restrict__ cnt, const int32_t *__restrict__ len, const int32_t *__restrict__ sel,
+    const int32_t *__restrict__ nsel, int n_q, int C, int bk_shift, int n_sel, int n_qb, int H, float scale_log2,
+    unsigned short *__restrict__ O, float *__restrict__ lse) {
+    extern __shared__ __attribute__((aligned(1024))) unsigned char lds[];
+    unsigned char *kbuf = lds;
+    unsigned char *vbuf = lds + 2 * TILEB;
+    TileMeta *meta = (TileMeta *)(lds + 4 * TILEB);
+    constexpr int IPW = (TK / 4) / NW;  // 1-KiB direct-load instructions per wavefront and tensor
+
+    // workgroup -> (head, query block): each XCD (workgroups are dealt round-robin to 8 of them) gets a
+    // contiguous range of (head, block) pairs, so neighbouring query blocks share one L2.
+    int h, b;
+    {
+        const int total = n_qb * H;
+        const int wg = blockIdx.x;
+        const int per = (total + 7) / 8;
+        const int item = (wg & 7) * per + (wg >> 3);
+        if (item >= total) return;
+        h = item / n_qb;
+        b = item % n_qb;
+    }
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int col = lane & 31, g = lane >> 5;
+    const int L = min(len[h], C);
+    const int n_listed = L > 0 ? min(nsel[(size_t)h * n_qb + b], n_sel) : 0;
+    const int32_t *sel_row = sel + ((size_t)h * n_qb + b) * n_sel;
+    const int32_t *cnt_h = cnt ? cnt + (size_t)h * C : nullptr;
+    const unsigned short *Kh = K + (size_t)h * C * D;
+    const unsigned short *Vh = V + (size_t)h * C * D;
+    const int nt = ((n_listed << bk_shift) + TK - 1) / TK;
+
+    const int q_idx = b * (NW * 32) + wave * 32 + col;
+    bf16x8 qf[D / 16];
+    {
+        const unsigned short *qrow = Q + ((size_t)h * n_q + min(q_idx, n_q - 1)) * D;
+#pragma unroll
+        for (int s = 0; s < D / 16; ++s) qf[s] = *(const bf16x8 *)(qrow + 16 * s + 8 * g);
+    }
+    f32x16 o_acc[D / 32];
+#pragma unroll
+    for (int db = 0; db < D / 32; ++db)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) o_acc[db][v] = 0.0f;
+    float m_run = -INFINITY, l_run = 0.0f;
+
+    // direct global -> LDS loads of one tile: instruction i of this wavefront covers tile rows
+    // 4*(wave*IPW+i) .. +3, lane l -> row +l/16, LDS chunk l%16, global chunk swizzled
+    const int lrow = lane >> 4, lchunk = lane & 15;
+    auto issue_loads = [&](const TileMeta &m, int stage) {
+#pragma unroll
+        for (int i = 0; i < IPW; ++i) {
+            const int inst = wave * IPW + i;
+            const int row = 4 * inst + lrow;
+            const int key = m.idx[row];
+            const unsigned short *ksrc = Kh + (size_t)key * D + ((lchunk ^ (row & 15)) << 3);
+            const unsigned short *vsrc = Vh + (size_t)key * D + ((lchunk ^ ((row & 7) << 1)) << 3);
+            __builtin_amdgcn_global_load_lds(ksrc, LDS_PTR(unsigned, kbuf + stage * TILEB + inst * 1024), 16, 0, 0);
+            __builtin_amdgcn_global_load_lds(vsrc, LDS_PTR(unsigned, vbuf + stage * TILEB + inst * 1024), 16, 0, 0);
+        }
+    };
+
+    if (nt > 0) {
+        fill_meta(meta[0], 0, sel_row, n_listed, bk_shift, L, cnt_h);
+        if (nt > 1) fill_meta(meta[1], 1, sel_row, n_listed, bk_shift, L, cnt_h);
+        __syncthreads();
+        issue_loads(meta[0], 0);
+    }
+    // per-lane LDS byte offsets that do not depend on the tile
+    //   K fragment (kb, s): row 32kb+col, logical chunk 2s+g  -> chunk (2s+g) ^ (row & 15); row & 15 = col & 15
+    //   V^T fragment (kstep, db): 16-lane group grp = lane/16 -> g = grp/2, column half = grp%2, s16 = lane%16;
+    //     row kbase + 4g + s16/4 (+8), logical chunk 4db + 2*(grp%2) + (s16%4)/2, byte (s16%2)*8
+    const int krow_off = col * ROWB;
+    const int kswz = col & 15;
+    const int s16 = lane & 15, grp = lane >> 4;
+    const int vrow_in = 4 * (grp >> 1) + (s16 >> 2);          // row within a 16-key step (first read)
+    const int vchunk_lo = 2 * (grp & 1) + ((s16 & 3) >> 1);   // logical chunk within the 4-chunk column block
+    const int vbyte = (s16 & 1) * 8;
+
+    for (int t = 0; t < nt; ++t) {
+        const int stage = t & 1;
+        __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): this wavefront's share of tile t has landed
+        __syncthreads();                     // ... and everyone else's; tile t-1 fully consumed
+        if (t + 1 < nt) issue_loads(meta[(t + 1) % 3], stage ^ 1);
+        if (t + 2 < nt) fill_meta(meta[(t + 2) % 3], t + 2, sel_row, n_listed, bk_shift, L, cnt_h);
+        const TileMeta &mt = meta[t % 3];
+        const unsigned char *kt = kbuf + stage * TILEB;
+        const unsigned char *vt = vbuf + stage * TILEB;
+
+        f32x16 s_acc[2];
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb) {
+#pragma unroll
+            for (int v = 0; v < 16; ++v) s_acc[kb][v] = 0.0f;
+#pragma unroll
+            for (int s = 0; s < D / 16; ++s) {
+                const bf16x8 a = *(const bf16x8 *)(kt + kb * 32 * ROWB + krow_off + (((2 * s + g) ^ kswz) << 4));
+                s_acc[kb] = mfma_bf16_32x32x16(a, qf[s], s_acc[kb]);
+            }
+        }
+        float mx = -INFINITY;
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+            for (int q4 = 0; q4 < 4; ++q4) {
+                const f32x4 bv = *(const f32x4 *)(&mt.bias[32 * kb + 8 * q4 + 4 * g]);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const float sv = fmaf(s_acc[kb][4 * q4 + e], scale_log2, bv[e]);
+                    s_acc[kb][4 * q4 + e] = sv;
+                    mx = fmaxf(mx, sv);
+                }
+            }
+        mx = fmaxf(mx, shfl_xor(mx, 32));
+        const float m_new = fmaxf(m_run, mx);
+        const float m_safe = m_new == -INFINITY ? 0.0f : m_new;
+        const bool grew = m_new > m_run;
+        const float alpha = __builtin_amdgcn_exp2f(m_run - m_safe);
+        float psum = 0.0f;
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const float p = __builtin_amdgcn_exp2f(s_acc[kb][v] - m_safe);
+                s_acc[kb][v] = p;
+                psum += p;
+            }
+        m_run = m_new;
+        if (__any(grew)) {  // wave-uniform: rescale only when some query of this wavefront saw a new maximum
+            l_run *= alpha;
+#pragma unroll
+            for (int db = 0; db < D / 32; ++db)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) o_acc[db][v] *= alpha;
+        }
+        l_run += psum;
+
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+            for (int half = 0; half < 2; ++half) {
+                bf16x8 pf;
+#pragma unroll
+                for (int e = 0; e < 8; ++e) pf[e] = (__bf16)s_acc[kb][8 * half + e];
+                const int kbase = 32 * kb + 16 * half;
+                const int r0 = kbase + vrow_in, r1 = r0 + 8;
+                const int sw0 = (r0 & 7) << 1, sw1 = (r1 & 7) << 1;
+#pragma unroll
+                for (int db = 0; db < D / 32; ++db) {
+                    const int lc = 4 * db + vchunk_lo;
+                    const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                        LDS_PTR(s16x4, vt + r0 * ROWB + ((lc ^ sw0) << 4) + vbyte));
+                    const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                        LDS_PTR(s16x4, vt + r1 * ROWB + ((lc ^ sw1) << 4) + vbyte));
+                    struct { s16x4 a, b; } pr = {lo, hi};
+                    bf16x8 a;
+                    __builtin_memcpy(&a, &pr, 16);
+                    o_acc[db] = mfma_bf16_32x32x16(a, pf, o_acc[db]);
+                }
+            }
+    }
+
+    // epilogue: normalise, transpose through LDS (K stages are free now), store rows coalesced
+    const float l_tot = l_run + shfl_xor(l_run, 32);
+    const float inv = l_tot > 0.0f ? 1.0f / l_tot : 0.0f;
+    __syncthreads();
+    constexpr int OSTR = D + 8;  // bf16 elements per staged row (16-byte pad)
+    unsigned short *Os = (unsigned short *)lds + (size_t)wave * 32 * OSTR;
+#pragma unroll
+    for (int db = 0; db < D / 32; ++db)
+#pragma unroll
+        for (int q4 = 0; q4 < 4; ++q4) {
+            bf16x8 dummy;
+            (void)dummy;
+            typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
+            bf16x4 w;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) w[e] = (__bf16)(o_acc[db][4 * q4 + e] * inv);
+            *(bf16x4 *)(Os + col * OSTR + 32 * db + 8 * q4 + 4 * g) = w;
+        }
+    __syncthreads();
+    {
+        const int rr = lane >> 4, cc = lane & 15;
+#pragma unroll
+        for (int it = 0; it < 8; ++it) {
+            const int r = it * 4 + rr;
+            const int qi = b * (NW * 32) + wave * 32 + r;
+            if (qi < n_q) *(u32x4 *)(O + ((size_t)h * n_q + qi) * D + cc * 8) = *(const u32x4 *)(Os + r * OSTR + cc * 8);
+        }
+    }
+    if (lse && g == 0 && q_idx < n_q)
+        lse[(size_t)h * n_q + q_idx] = l_tot > 0.0f ? (m_run + __log2f(l_tot)) * LN2 : -INFINITY;
+}
+
+}  // namespace d128
+
+// Launcher used by sparse_attn_fwd for bf16, d = 128.  BQ in {64, 128}.
+int launch_attn_bf16_d128(const void *Q, int n_q, const void *K, const void *V, const int32_t *cnt, const int32_t *len,
+                          int H, int C, const int32_t *sel, const int32_t *nsel, int BQ, int bk_shift, int n_sel,
+                          float scale_log2, void *O, float *lse, hipStream_t s) {
+    using namespace d128;
+    static bool attr_set = false;
+    if (!attr_set) {  // more than 64 KiB of LDS per workgroup has to be requested once per kernel
+        if (hipFuncSetAttribute((const void *)attn_bf16_d128_kernel<4>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                LDS_BYTES) != hipSuccess ||
+            hipFuncSetAttribute((const void *)attn_bf16_d128_kernel<2>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                LDS_BYTES) != hipSuccess)
+            return FASTAR_ERR_HIP;
+        attr_set = true;
+    }
+    const int n_qb = (n_q + BQ - 1) / BQ;
+    const dim3 grid((unsigned)(((n_qb * H + 7) / 8) * 8));
+    if (BQ == 128)
+        hipLaunchKernelGGL(attn_bf16_d128_kernel<4>, grid, dim3(256), LDS_BYTES, s, (const unsigned short *)Q,
+                           (const unsigned short *)K, (const unsigned short *)V, cnt, len, sel, nsel, n_q, C, bk_shift,
+                           n_sel, n_qb, H, scale_log2, (unsigned short *)O, lse);
+    else
+        hipLaunchKernelGGL(attn_bf16_d128_kernel<2>, grid, dim3(128), LDS_BYTES, s, (const unsigned short *)Q,
+                           (const unsigned short *)K, (const unsigned short *)V, cnt, len, sel, nsel, n_q, C, bk_shift,
+                           n_sel, n_qb, H, scale_log2, (unsigned short *)O, lse);
+    if (hipGetLastError() != hipSuccess) return FASTAR_ERR_HIP;
+    return FASTAR_OK;
+}
+
+}  // namespace fastar
