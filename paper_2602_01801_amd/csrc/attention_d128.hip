@@ -15,6 +15,8 @@
 //   * masked rows (padding of the selection list, slots beyond len) fetch row 0 of the head, which
 //     is live, and carry a -inf bias, so they contribute exactly zero;
 //   * the running-maximum rescale of O is skipped when no lane of the wavefront saw a new maximum.
+#include <type_traits>
+
 #include "common.hpp"
 
 namespace fastar {
@@ -56,6 +58,71 @@ __device__ __forceinline__ void fill_meta(TileMeta &m, int t, const int32_t *__r
     }
 }
 
+
+// LDS transpose load issued as inline assembly: the compiler then neither serialises it against the
+// direct-to-LDS tile loads in flight nor waits for it; wait_vt() below does, explicitly.
+template <int OFF>
+__device__ __forceinline__ s16x4 lds_read_tr16(unsigned addr) {
+    s16x4 r;
+    asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(r) : "v"(addr), "n"(OFF));
+    return r;
+}
+
+template <int OFF>
+__device__ __forceinline__ bf16x8 lds_read_b128(unsigned addr) {
+    bf16x8 r;
+    asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(r) : "v"(addr), "n"(OFF));
+    return r;
+}
+
+// K operands of 32 keys for the eight 16-coordinate steps.  BASE = byte offset of the first row inside the K region.
+template <int BASE>
+__device__ __forceinline__ void read_k(bf16x8 (&f)[D / 16], const unsigned (&kaddr)[D / 16]) {
+    f[0] = lds_read_b128<BASE>(kaddr[0]); f[1] = lds_read_b128<BASE>(kaddr[1]);
+    f[2] = lds_read_b128<BASE>(kaddr[2]); f[3] = lds_read_b128<BASE>(kaddr[3]);
+    f[4] = lds_read_b128<BASE>(kaddr[4]); f[5] = lds_read_b128<BASE>(kaddr[5]);
+    f[6] = lds_read_b128<BASE>(kaddr[6]); f[7] = lds_read_b128<BASE>(kaddr[7]);
+}
+__device__ __forceinline__ void wait_k(bf16x8 (&f)[D / 16]) {
+    asm volatile("s_waitcnt lgkmcnt(0)"
+                 : "+v"(f[0]), "+v"(f[1]), "+v"(f[2]), "+v"(f[3]), "+v"(f[4]), "+v"(f[5]), "+v"(f[6]), "+v"(f[7]));
+}
+
+// V^T operands of 32 keys (two steps of 16) for the four 32-column blocks: f[step][db][0|1] are the two
+// 4-key halves of one A operand.  BASE = byte offset of the first of the 32 rows inside the V region.
+template <int BASE>
+__device__ __forceinline__ void read_vt(s16x4 (&f)[2][D / 32][2], const unsigned (&vaddr)[D / 32]) {
+#define FASTAR_RD(ST, DB)                                                          \
+    f[ST][DB][0] = lds_read_tr16<BASE + (16 * ST) * ROWB>(vaddr[DB]);               \
+    f[ST][DB][1] = lds_read_tr16<BASE + (16 * ST + 8) * ROWB>(vaddr[DB]);
+    FASTAR_RD(0, 0) FASTAR_RD(0, 1) FASTAR_RD(0, 2) FASTAR_RD(0, 3)
+    FASTAR_RD(1, 0) FASTAR_RD(1, 1) FASTAR_RD(1, 2) FASTAR_RD(1, 3)
+#undef FASTAR_RD
+}
+
+// Wait until every LDS read issued so far has returned; the operands tie the wait to the fragments.
+__device__ __forceinline__ void wait_vt(s16x4 (&f)[2][D / 32][2]) {
+    asm volatile("s_waitcnt lgkmcnt(0)"
+                 : "+v"(f[0][0][0]), "+v"(f[0][0][1]), "+v"(f[0][1][0]), "+v"(f[0][1][1]), "+v"(f[0][2][0]),
+                   "+v"(f[0][2][1]), "+v"(f[0][3][0]), "+v"(f[0][3][1]), "+v"(f[1][0][0]), "+v"(f[1][0][1]),
+                   "+v"(f[1][1][0]), "+v"(f[1][1][1]), "+v"(f[1][2][0]), "+v"(f[1][2][1]), "+v"(f[1][3][0]),
+                   "+v"(f[1][3][1]));
+}
+
+// O^T += V^T P^T for 32 keys: two steps of 16 keys, four 32-column blocks each.
+__device__ __forceinline__ void pv_mfma(f32x16 (&o_acc)[D / 32], const s16x4 (&f)[2][D / 32][2],
+                                        const bf16x8 (&pf)[2]) {
+#pragma unroll
+    for (int st = 0; st < 2; ++st)
+#pragma unroll
+        for (int db = 0; db < D / 32; ++db) {
+            struct { s16x4 a, b; } pr = {f[st][db][0], f[st][db][1]};
+            bf16x8 a;
+            __builtin_memcpy(&a, &pr, 16);
+            o_acc[db] = mfma_bf16_32x32x16(a, pf[st], o_acc[db]);
+        }
+}
+
 // dynamic LDS layout: [K stage 0][K stage 1][V stage 0][V stage 1][meta x3]
 constexpr int LDS_BYTES = 4 * TILEB + 3 * (int)sizeof(TileMeta);
 
@@ -83,7 +150,8 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_bf16_d128_kernel(
         h = item / n_qb;
         b = item % n_qb;
     }
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform, kept in a scalar register
     const int col = lane & 31, g = lane >> 5;
     const int L = min(len[h], C);
     const int n_listed = L > 0 ? min(nsel[(size_t)h * n_qb + b], n_sel) : 0;
@@ -111,56 +179,94 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_bf16_d128_kernel(
     // 4*(wave*IPW+i) .. +3, lane l -> row +l/16, LDS chunk l%16, global chunk swizzled
     const int lrow = lane >> 4, lchunk = lane & 15;
     auto issue_loads = [&](const TileMeta &m, int stage) {
+        int keys[IPW];
+#pragma unroll
+        for (int i = 0; i < IPW; ++i) keys[i] = m.idx[4 * (wave * IPW + i) + lrow];
 #pragma unroll
         for (int i = 0; i < IPW; ++i) {
             const int inst = wave * IPW + i;
             const int row = 4 * inst + lrow;
-            const int key = m.idx[row];
-            const unsigned short *ksrc = Kh + (size_t)key * D + ((lchunk ^ (row & 15)) << 3);
-            const unsigned short *vsrc = Vh + (size_t)key * D + ((lchunk ^ ((row & 7) << 1)) << 3);
+            const unsigned short *ksrc = Kh + (size_t)keys[i] * D + ((lchunk ^ (row & 15)) << 3);
+            const unsigned short *vsrc = Vh + (size_t)keys[i] * D + ((lchunk ^ ((row & 7) << 1)) << 3);
             __builtin_amdgcn_global_load_lds(ksrc, LDS_PTR(unsigned, kbuf + stage * TILEB + inst * 1024), 16, 0, 0);
             __builtin_amdgcn_global_load_lds(vsrc, LDS_PTR(unsigned, vbuf + stage * TILEB + inst * 1024), 16, 0, 0);
         }
     };
 
+    // Row tables are built two tiles ahead by the first 64 threads.  Their two dependent global loads
+    // (selection entry, then multiplicity of the row it names) are split over two iterations and
+    // issued BEFORE the tile loads of the iteration, and consumed at its end: memory operations
+    // retire in order, so waiting for them any earlier would also wait for the tile in flight.
+    auto sel_entry = [&](int tile) -> int {
+        const int entry = (tile * TK + tid) >> bk_shift;
+        return (tid < TK && entry < n_listed) ? sel_row[entry] : -1;
+    };
+    auto key_of = [&](int kb, int tile) -> int {
+        int key = -1;
+        if (kb >= 0) {
+            key = (kb << bk_shift) + ((tile * TK + tid) & ((1 << bk_shift) - 1));
+            if (key >= L) key = -1;
+        }
+        return key;
+    };
+    int kb_ahead = -1;  // selection entry of this thread's position in tile t+2
     if (nt > 0) {
         fill_meta(meta[0], 0, sel_row, n_listed, bk_shift, L, cnt_h);
         if (nt > 1) fill_meta(meta[1], 1, sel_row, n_listed, bk_shift, L, cnt_h);
+        if (nt > 2) kb_ahead = sel_entry(2);
         __syncthreads();
         issue_loads(meta[0], 0);
     }
-    // per-lane LDS byte offsets that do not depend on the tile
-    //   K fragment (kb, s): row 32kb+col, logical chunk 2s+g  -> chunk (2s+g) ^ (row & 15); row & 15 = col & 15
+    // Per-lane LDS byte offsets that do not depend on the tile.  XOR with a per-lane constant permutes
+    // aligned groups of chunks, so every fragment address is (per-lane register) + (compile-time offset).
+    //   K fragment (kb, s): row 32kb+col, logical chunk 2s+g -> chunk (2s+g) ^ (col & 15)
     //   V^T fragment (kstep, db): 16-lane group grp = lane/16 -> g = grp/2, column half = grp%2, s16 = lane%16;
-    //     row kbase + 4g + s16/4 (+8), logical chunk 4db + 2*(grp%2) + (s16%4)/2, byte (s16%2)*8
-    const int krow_off = col * ROWB;
-    const int kswz = col & 15;
+    //     row kbase + 4g + s16/4 (+8), logical chunk 4db + 2*(grp%2) + (s16%4)/2, byte (s16%2)*8,
+    //     swizzle 2*(row & 7) = 2*((4g + s16/4) & 7) for both rows
+    const unsigned kbuf_lds = (unsigned)(size_t)LDS_PTR(unsigned char, kbuf);
+    unsigned kaddr[D / 16];
+#pragma unroll
+    for (int s = 0; s < D / 16; ++s) kaddr[s] = kbuf_lds + col * ROWB + (((2 * s + g) ^ (col & 15)) << 4);
     const int s16 = lane & 15, grp = lane >> 4;
-    const int vrow_in = 4 * (grp >> 1) + (s16 >> 2);          // row within a 16-key step (first read)
-    const int vchunk_lo = 2 * (grp & 1) + ((s16 & 3) >> 1);   // logical chunk within the 4-chunk column block
-    const int vbyte = (s16 & 1) * 8;
+    const int vrow_in = 4 * (grp >> 1) + (s16 >> 2);
+    const unsigned vbuf_lds = (unsigned)(size_t)LDS_PTR(unsigned char, vbuf);
+    unsigned vaddr[D / 32];
+#pragma unroll
+    for (int db = 0; db < D / 32; ++db)
+        vaddr[db] = vbuf_lds + vrow_in * ROWB +
+                    (((4 * db + 2 * (grp & 1) + ((s16 & 3) >> 1)) ^ ((vrow_in & 7) << 1)) << 4) + (s16 & 1) * 8;
 
-    for (int t = 0; t < nt; ++t) {
-        const int stage = t & 1;
+    auto tile_step = [&](int t, auto stage_c) {
+        constexpr int STAGE = decltype(stage_c)::value;
         __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): this wavefront's share of tile t has landed
         __syncthreads();                     // ... and everyone else's; tile t-1 fully consumed
-        if (t + 1 < nt) issue_loads(meta[(t + 1) % 3], stage ^ 1);
-        if (t + 2 < nt) fill_meta(meta[(t + 2) % 3], t + 2, sel_row, n_listed, bk_shift, L, cnt_h);
+        // row table of tile t+2, first half: issue its loads now
+        int key2 = -1, cnt2 = 1, kb3 = -1;
+        if (t + 2 < nt) {
+            key2 = key_of(kb_ahead, t + 2);
+            if (key2 >= 0 && cnt_h) cnt2 = cnt_h[key2];
+            if (t + 3 < nt) kb3 = sel_entry(t + 3);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        // K operands of keys 0..31: in flight while the next tile's loads are set up
+        bf16x8 ka[D / 16], kb2[D / 16];
+        read_k<STAGE * TILEB>(ka, kaddr);
+        if (t + 1 < nt) issue_loads(meta[(t + 1) % 3], STAGE ^ 1);
         const TileMeta &mt = meta[t % 3];
-        const unsigned char *kt = kbuf + stage * TILEB;
-        const unsigned char *vt = vbuf + stage * TILEB;
 
         f32x16 s_acc[2];
 #pragma unroll
-        for (int kb = 0; kb < 2; ++kb) {
+        for (int v = 0; v < 16; ++v) { s_acc[0][v] = 0.0f; s_acc[1][v] = 0.0f; }
+        wait_k(ka);
+        read_k<STAGE * TILEB + 32 * ROWB>(kb2, kaddr);  // keys 32..63, land during the first eight products
 #pragma unroll
-            for (int v = 0; v < 16; ++v) s_acc[kb][v] = 0.0f;
+        for (int s = 0; s < D / 16; ++s) s_acc[0] = mfma_bf16_32x32x16(ka[s], qf[s], s_acc[0]);
+        wait_k(kb2);
+        // V^T fragments of keys 0..31 of the tile: issued now, they land during the softmax arithmetic
+        s16x4 va[2][D / 32][2], vb[2][D / 32][2];
+        read_vt<STAGE * TILEB>(va, vaddr);
 #pragma unroll
-            for (int s = 0; s < D / 16; ++s) {
-                const bf16x8 a = *(const bf16x8 *)(kt + kb * 32 * ROWB + krow_off + (((2 * s + g) ^ kswz) << 4));
-                s_acc[kb] = mfma_bf16_32x32x16(a, qf[s], s_acc[kb]);
-            }
-        }
+        for (int s = 0; s < D / 16; ++s) s_acc[1] = mfma_bf16_32x32x16(kb2[s], qf[s], s_acc[1]);
         float mx = -INFINITY;
 #pragma unroll
         for (int kb = 0; kb < 2; ++kb)
@@ -197,30 +303,32 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_bf16_d128_kernel(
                 for (int v = 0; v < 16; ++v) o_acc[db][v] *= alpha;
         }
         l_run += psum;
-
+        bf16x8 pf[2][2];
 #pragma unroll
         for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-            for (int half = 0; half < 2; ++half) {
-                bf16x8 pf;
+            for (int half = 0; half < 2; ++half)
 #pragma unroll
-                for (int e = 0; e < 8; ++e) pf[e] = (__bf16)s_acc[kb][8 * half + e];
-                const int kbase = 32 * kb + 16 * half;
-                const int r0 = kbase + vrow_in, r1 = r0 + 8;
-                const int sw0 = (r0 & 7) << 1, sw1 = (r1 & 7) << 1;
-#pragma unroll
-                for (int db = 0; db < D / 32; ++db) {
-                    const int lc = 4 * db + vchunk_lo;
-                    const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                        LDS_PTR(s16x4, vt + r0 * ROWB + ((lc ^ sw0) << 4) + vbyte));
-                    const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                        LDS_PTR(s16x4, vt + r1 * ROWB + ((lc ^ sw1) << 4) + vbyte));
-                    struct { s16x4 a, b; } pr = {lo, hi};
-                    bf16x8 a;
-                    __builtin_memcpy(&a, &pr, 16);
-                    o_acc[db] = mfma_bf16_32x32x16(a, pf, o_acc[db]);
-                }
-            }
+                for (int e = 0; e < 8; ++e) pf[kb][half][e] = (__bf16)s_acc[kb][8 * half + e];
+
+        wait_vt(va);
+        read_vt<STAGE * TILEB + 32 * ROWB>(vb, vaddr);  // keys 32..63, land during the first eight products
+        pv_mfma(o_acc, va, pf[0]);
+        wait_vt(vb);
+        pv_mfma(o_acc, vb, pf[1]);
+
+        // row table of tile t+2, second half
+        __builtin_amdgcn_sched_barrier(0);
+        if (t + 2 < nt && tid < TK) {
+            TileMeta &m2 = meta[(t + 2) % 3];
+            m2.idx[tid] = key2 >= 0 ? key2 : 0;
+            m2.bias[tid] = key2 >= 0 ? (cnt_h ? __log2f((float)cnt2) : 0.0f) : -INFINITY;
+        }
+        kb_ahead = kb3;
+    };
+    for (int t = 0; t < nt; t += 2) {
+        tile_step(t, std::integral_constant<int, 0>{});
+        if (t + 1 < nt) tile_step(t + 1, std::integral_constant<int, 1>{});
     }
 
     // epilogue: normalise, transpose through LDS (K stages are free now), store rows coalesced
