@@ -13,6 +13,22 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-fast-math"
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wno-unused-command-line-argument"]
 
 
+def verify_asm_reads(hipcc: str, extra: list[str] | None = None) -> None:
+    """The tuned attention kernel reads LDS through inline assembly; check on the generated ISA that the
+    compiler kept its hands off those registers until the explicit wait (see asmcheck.py)."""
+    try:
+        from . import asmcheck
+    except ImportError:  # run as a script
+        import asmcheck
+    asm = os.path.join(CSRC, "attention_d128.s")
+    cmd = [hipcc, *FLAGS, *(extra or []), "-S", "--cuda-device-only", os.path.join(CSRC, "attention_d128.hip"), "-o", asm]
+    subprocess.run(cmd, check=True, stdout=subprocess.DEVNULL, stderr=subprocess.DEVNULL)
+    bad = asmcheck.check(asm, verbose=False)
+    os.remove(asm)
+    if bad:
+        raise RuntimeError(f"attention_d128: {bad} instruction(s) touch registers of an in-flight inline-asm LDS read")
+
+
 def build(verbose: bool = False, extra: list[str] | None = None) -> str:
     """Compile every kernel source and link the shared library.  Always recompiles."""
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
@@ -36,6 +52,7 @@ def build(verbose: bool = False, extra: list[str] | None = None) -> str:
             print(out)
     if failed:
         raise RuntimeError("hipcc failed")
+    verify_asm_reads(hipcc, extra)
     subprocess.run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs], check=True)
     return LIB
 
