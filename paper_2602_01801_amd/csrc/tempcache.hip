@@ -18,7 +18,7 @@ namespace fastar {
 int encode_launch(const void *x, int dtype, int64_t n_vec, int d, const fastar_codec *codec, int r, int8_t *code,
                   unsigned long long *zero_fill, int64_t zero_n, hipStream_t s);
 
-constexpr int CAND_CHUNK = 512;          // candidate positions scanned by one workgroup of tc_match
+constexpr int CAND_CHUNK = 256;          // candidate positions scanned by one workgroup of tc_match
 constexpr int SCORE_BIAS = 1 << 23;      // makes every score positive inside the packed arg-max key
 constexpr int HS_STRIDE = 8;             // per-head scalars: oldL, n_unmerged, e, n_victims, n_dropped, newL
 
@@ -61,7 +61,8 @@ __global__ __launch_bounds__(256) void tc_match_kernel(const int8_t *__restrict_
                                                        const int32_t *__restrict__ cand, int n_cand, int metric,
                                                        u64 *__restrict__ best) {
     constexpr int KS = R / 32;
-    __shared__ i32x2 cinfo[2][4][32];  // [parity][wave][candidate row] = {slot or -1, |code|^2}
+    constexpr int NIT = CAND_CHUNK / 32;  // groups of 32 candidates per workgroup
+    __shared__ i32x2 cinfo[4][CAND_CHUNK];  // [wave][candidate of the chunk] = {slot or -1, |code|^2}
     const int h = blockIdx.z;
     const int L = min(len[h], C);
     const int n_pos = cand ? n_cand : L;
@@ -79,38 +80,52 @@ __global__ __launch_bounds__(256) void tc_match_kernel(const int8_t *__restrict_
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) bfrag[ks] = *(const i32x4 *)(cph + (size_t)trow * R + ks * 32 + 16 * g2);
     }
-    u64 mybest = 0;
-    int it = 0;
-    for (int p = pos0; p < pos1; p += 32, ++it) {
-        const int pos = p + col;
-        int slot = -1;
+    // Two rounds of independent loads for the whole chunk (slot ids, then the codes they name) instead of
+    // one dependent pair per group: the chunk costs two memory round trips, not 2 * NIT.
+    int slot[NIT];
+#pragma unroll
+    for (int it = 0; it < NIT; ++it) {
+        const int pos = pos0 + it * 32 + col;
+        int sl = -1;
         if (pos < pos1) {
-            slot = cand ? cand[(size_t)h * n_cand + pos] : pos;
-            if (slot < 0 || slot >= L) slot = -1;
+            sl = cand ? cand[(size_t)h * n_cand + pos] : pos;
+            if (sl < 0 || sl >= L) sl = -1;
         }
-        i32x4 afrag[KS];
-        int nn = 0;
+        slot[it] = sl;
+    }
+    i32x4 afrag[NIT][KS];
+#pragma unroll
+    for (int it = 0; it < NIT; ++it)
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) {
             i32x4 a = {0, 0, 0, 0};
-            if (slot >= 0) a = *(const i32x4 *)(ch + (size_t)slot * R + ks * 32 + 16 * g2);
-            afrag[ks] = a;
+            if (slot[it] >= 0) a = *(const i32x4 *)(ch + (size_t)slot[it] * R + ks * 32 + 16 * g2);
+            afrag[it][ks] = a;
+        }
 #pragma unroll
-            for (int m = 0; m < 4; ++m) nn = dot4_i8((unsigned)a[m], (unsigned)a[m], nn);
-        }
+    for (int it = 0; it < NIT; ++it) {
+        int nn = 0;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks)
+#pragma unroll
+            for (int m = 0; m < 4; ++m) nn = dot4_i8((unsigned)afrag[it][ks][m], (unsigned)afrag[it][ks][m], nn);
         nn += shfl_xor(nn, 32);
-        const int par = it & 1;
         if (g2 == 0) {
-            i32x2 ci = {slot, nn};
-            cinfo[par][wave][col] = ci;
+            i32x2 ci = {slot[it], nn};
+            cinfo[wave][it * 32 + col] = ci;
         }
+    }
+    __syncthreads();  // every wavefront reads back only its own rows; the barrier orders write and read
+    u64 mybest = 0;
+#pragma unroll
+    for (int it = 0; it < NIT; ++it) {
+        if (pos0 + it * 32 >= pos1) break;  // uniform
         i32x16 acc = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
 #pragma unroll
-        for (int ks = 0; ks < KS; ++ks) acc = mfma_i8_32x32x32(afrag[ks], bfrag[ks], acc);
-        __syncthreads();  // cinfo[par] visible; the other parity is free to be rewritten next iteration
+        for (int ks = 0; ks < KS; ++ks) acc = mfma_i8_32x32x32(afrag[it][ks], bfrag[ks], acc);
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
-            const i32x2 ci = cinfo[par][wave][8 * (v >> 2) + 4 * g2 + (v & 3)];
+            const i32x2 ci = cinfo[wave][it * 32 + 8 * (v >> 2) + 4 * g2 + (v & 3)];
             const int S = metric == 0 ? 2 * acc[v] - ci[1] : acc[v];
             const u64 key = ((u64)(unsigned)(S + SCORE_BIAS) << 32) | (u64)(0xFFFFFFFFu - (unsigned)ci[0]);
             if (ci[0] >= 0 && key > mybest) mybest = key;
