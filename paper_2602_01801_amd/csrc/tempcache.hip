@@ -11,6 +11,8 @@
 //   tc_apply      representative key, mean value, multiplicity, code, stamp of merged slots; appended
 //                 tokens into victims / fresh slots; merge map
 // All decisions are integer and order-independent (max / count), so the merge map is reproducible.
+#include <limits.h>
+
 #include "common.hpp"
 
 namespace fastar {
@@ -62,7 +64,8 @@ __global__ __launch_bounds__(256) void tc_match_kernel(const int8_t *__restrict_
                                                        u64 *__restrict__ best) {
     constexpr int KS = R / 32;
     constexpr int NIT = CAND_CHUNK / 32;  // groups of 32 candidates per workgroup
-    __shared__ i32x2 cinfo[4][CAND_CHUNK];  // [wave][candidate of the chunk] = {slot or -1, |code|^2}
+    __shared__ __attribute__((aligned(16))) int cslot[4][CAND_CHUNK];  // [wave][candidate] slot id (-1: none)
+    __shared__ __attribute__((aligned(16))) int cpen[4][CAND_CHUNK];   // score penalty: |code|^2 (metric 0), 0 (metric 1), 2^30 (none)
     const int h = blockIdx.z;
     const int L = min(len[h], C);
     const int n_pos = cand ? n_cand : L;
@@ -111,26 +114,49 @@ __global__ __launch_bounds__(256) void tc_match_kernel(const int8_t *__restrict_
             for (int m = 0; m < 4; ++m) nn = dot4_i8((unsigned)afrag[it][ks][m], (unsigned)afrag[it][ks][m], nn);
         nn += shfl_xor(nn, 32);
         if (g2 == 0) {
-            i32x2 ci = {slot[it], nn};
-            cinfo[wave][it * 32 + col] = ci;
+            cslot[wave][it * 32 + col] = slot[it];
+            cpen[wave][it * 32 + col] = slot[it] >= 0 ? (metric == 0 ? nn : 0) : (1 << 30);
         }
     }
     __syncthreads();  // every wavefront reads back only its own rows; the barrier orders write and read
-    u64 mybest = 0;
+    // Running arg-max per lane: the 16 scores of a matrix instruction are reduced with plain 32-bit maxima;
+    // the slot ids are looked at only when that maximum reaches the best score seen so far.
+    const int mult = metric == 0 ? 2 : 1;
+    int best_s = INT_MIN, best_slot = INT_MAX;
 #pragma unroll
     for (int it = 0; it < NIT; ++it) {
         if (pos0 + it * 32 >= pos1) break;  // uniform
         i32x16 acc = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) acc = mfma_i8_32x32x32(afrag[it][ks], bfrag[ks], acc);
+        int m = INT_MIN;
 #pragma unroll
-        for (int v = 0; v < 16; ++v) {
-            const i32x2 ci = cinfo[wave][it * 32 + 8 * (v >> 2) + 4 * g2 + (v & 3)];
-            const int S = metric == 0 ? 2 * acc[v] - ci[1] : acc[v];
-            const u64 key = ((u64)(unsigned)(S + SCORE_BIAS) << 32) | (u64)(0xFFFFFFFFu - (unsigned)ci[0]);
-            if (ci[0] >= 0 && key > mybest) mybest = key;
+        for (int q4 = 0; q4 < 4; ++q4) {
+            const i32x4 pen = *(const i32x4 *)(&cpen[wave][it * 32 + 8 * q4 + 4 * g2]);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                acc[4 * q4 + e] = acc[4 * q4 + e] * mult - pen[e];
+                m = max(m, acc[4 * q4 + e]);
+            }
+        }
+        if (__any(m >= best_s && m > -(1 << 29))) {
+            int sl = INT_MAX;
+#pragma unroll
+            for (int q4 = 0; q4 < 4; ++q4) {
+                const i32x4 ids = *(const i32x4 *)(&cslot[wave][it * 32 + 8 * q4 + 4 * g2]);
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    if (acc[4 * q4 + e] == m) sl = min(sl, ids[e]);
+            }
+            if (m > -(1 << 29)) {  // at least one real candidate among the 16
+                if (m > best_s) { best_s = m; best_slot = sl; }
+                else if (m == best_s) best_slot = min(best_slot, sl);
+            }
         }
     }
+    u64 mybest = 0;
+    if (best_s != INT_MIN)
+        mybest = ((u64)(unsigned)(best_s + SCORE_BIAS) << 32) | (u64)(0xFFFFFFFFu - (unsigned)best_slot);
     {
         const unsigned lo = shfl_xor((unsigned)mybest, 32), hi = shfl_xor((unsigned)(mybest >> 32), 32);
         const u64 other = ((u64)hi << 32) | lo;
