@@ -1,0 +1,126 @@
+"""GPU parity at the benchmark's full shapes, in the launch configuration bench.py times.
+
+The GPU runs every head; the CPU oracle replays a subset of heads from the same inputs (heads are
+independent in every step of the method, so a head slice of the inputs gives exactly the head slice
+of the outputs).  Index outputs must match bit for bit, attention within 2e-2 max-abs (bf16).
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2602_01801_amd as fa
+from workloads import CONFIGS, FrameStream, PromptSet, make_codec, to_f32
+
+from gpu_util import dev_codec, storage_to_f64, to_dev, to_host
+
+pytestmark = pytest.mark.gpu
+
+TAU2 = lambda tau: int(round(tau * tau * 65536))
+
+
+def rollout(name, n_frames, cap_frames, heads, tau=0.98):
+    """Compress n_frames frames on the GPU (all heads) and in the oracle (`heads` only), checking every call."""
+    c = CONFIGS[name]
+    H, T, d, r = c["H"], c["T"], c["d"], c["r"]
+    fs = FrameStream.from_config(name)
+    codec = make_codec(c["seed"], c["cfg_id"], d, r)
+    dcodec = dev_codec(codec)
+    C = cap_frames * T
+    gpu = fa.Cache.empty(H, C, d, r, torch.bfloat16)
+    ref = oracle.Cache.empty(len(heads), C, d, r, "bf16")
+    prev_g = prev_r = None
+    ws = torch.empty(fa.workspace_bytes(fa.OP_COMPRESS, H, T, C, r), dtype=torch.uint8, device="cuda")
+    for f in range(n_frames):
+        K, V = fs.next_frame()
+        mm_g, mg_g, st_g = fa.tempcache_compress(gpu, dcodec, to_dev(K), to_dev(V), cand=prev_g, tau2_q16=TAU2(tau),
+                                                 frame_id=f, ws=ws)
+        mm_r, mg_r, st_r = oracle.tempcache_compress(ref, codec.R, codec.qscale, codec.shift,
+                                                     np.ascontiguousarray(K[heads]), np.ascontiguousarray(V[heads]),
+                                                     cand=prev_r, tau2_q16=TAU2(tau), frame_id=f)
+        assert np.array_equal(to_host(mm_g)[heads], mm_r), f"merge map, frame {f}"
+        assert np.array_equal(to_host(mg_g)[heads], mg_r), f"merged flags, frame {f}"
+        assert np.array_equal(to_host(st_g)[heads], st_r), f"stats, frame {f}"
+        prev_g, prev_r = mm_g.clone(), mm_r
+    # cache bookkeeping of the sampled heads
+    assert np.array_equal(to_host(gpu.len)[heads], ref.len)
+    for i, h in enumerate(heads):
+        L = int(ref.len[i])
+        assert np.array_equal(to_host(gpu.K[h, :L]), ref.K[i, :L])
+        assert np.array_equal(to_host(gpu.code[h, :L]), ref.code[i, :L])
+        assert np.array_equal(to_host(gpu.cnt[h, :L]), ref.cnt[i, :L])
+        assert np.array_equal(to_host(gpu.stamp[h, :L]), ref.stamp[i, :L])
+        dv = np.abs(storage_to_f64(to_host(gpu.V[h, :L])) - storage_to_f64(ref.V[i, :L])).max()
+        assert dv <= 5e-2, f"running-mean values, head {h}: {dv}"
+    return c, fs, codec, dcodec, gpu, ref
+
+
+def select_and_attend(c, fs, codec, dcodec, gpu, ref, heads, n_sel):
+    H, d = c["H"], c["d"]
+    BQ, BK, n_rep = c["BQ"], c["BK"], c["n_rep"]
+    Q = fs.queries(c["chunk_frames"])
+    qc = fa.encode(to_dev(Q), dcodec)
+    qc_r = oracle.encode(np.ascontiguousarray(Q[heads]), codec.R, codec.qscale, codec.shift)
+    assert np.array_equal(to_host(qc)[heads], qc_r)
+    sel, nsel = fa.ann_select_self(qc, gpu.code, gpu.len, BQ, n_rep, BK, n_sel)
+    sel_r, nsel_r = oracle.ann_select_self(qc_r, ref.code, ref.len, BQ, n_rep, BK, n_sel)
+    assert np.array_equal(to_host(nsel)[heads], nsel_r)
+    assert np.array_equal(to_host(sel)[heads], sel_r)
+    O, lse = fa.sparse_attn_fwd(to_dev(Q), gpu.K, gpu.V, gpu.cnt, gpu.len, sel, nsel, BQ, BK, d ** -0.5)
+    # the oracle attends over ITS cache state (values differ from the GPU's by bf16 rounding of the running mean)
+    O_r, lse_r = oracle.sparse_attn_fwd(np.ascontiguousarray(Q[heads]), ref.K, ref.V, ref.cnt, ref.len, sel_r, nsel_r,
+                                        BQ, BK, d ** -0.5)
+    err = np.abs(storage_to_f64(to_host(O))[heads] - O_r).max()
+    assert err <= 2e-2, f"max |O - O_ref| = {err}"
+    assert np.abs(to_host(lse)[heads].astype(np.float64) - lse_r).max() <= 2e-2
+    return Q, qc, qc_r
+
+
+def test_wan_shaped_layer_full_size():
+    # cfg2: 12 heads, d 128, 21 frames of 1560 tokens merged into a cache capped at 24 frames of slots,
+    # 52 of 512 key blocks per query block, 4680 queries
+    heads = [0, 7]
+    c, fs, codec, dcodec, gpu, ref = rollout("cfg2", 21, 24, heads)
+    n_kb = (c["cache_frames"] * c["T"] + c["BK"] - 1) // c["BK"]
+    n_sel = int(np.ceil(c["sel_frac"] * n_kb))
+    assert n_sel == 52
+    Q, qc, qc_r = select_and_attend(c, fs, codec, dcodec, gpu, ref, heads, n_sel)
+    # cross-attention legs (cfg4): 64 of 512 and of 2048 prompt tokens
+    for n_p in (c["n_p"], CONFIGS["cfg4"]["n_p_long"]):
+        ps = PromptSet(c["seed"], c["cfg_id"], fs.centreK, n_p, c["n_pc"], c["n_near"], c["dtype"])
+        pc = fa.encode(to_dev(ps.K), dcodec)
+        pc_r = oracle.encode(np.ascontiguousarray(ps.K[heads]), codec.R, codec.qscale, codec.shift)
+        assert np.array_equal(to_host(pc)[heads], pc_r)
+        csel, cnsel = fa.ann_select_cross(qc, pc, c["BQ"], c["n_sel_cross"])
+        csel_r, cnsel_r = oracle.ann_select_cross(qc_r, pc_r, c["BQ"], c["n_sel_cross"])
+        assert np.array_equal(to_host(csel)[heads], csel_r) and np.array_equal(to_host(cnsel)[heads], cnsel_r)
+        plen = np.full(c["H"], n_p, np.int32)
+        O, _ = fa.sparse_attn_fwd(to_dev(Q), to_dev(ps.K), to_dev(ps.V), None, to_dev(plen), csel, cnsel, c["BQ"], 1,
+                                  c["d"] ** -0.5)
+        O_r, _ = oracle.sparse_attn_fwd(np.ascontiguousarray(Q[heads]), np.ascontiguousarray(ps.K[heads]),
+                                        np.ascontiguousarray(ps.V[heads]), None, plen[: len(heads)], csel_r, cnsel_r,
+                                        c["BQ"], 1, c["d"] ** -0.5)
+        err = np.abs(storage_to_f64(to_host(O))[heads] - O_r).max()
+        assert err <= 2e-2, f"cross-attention n_p={n_p}: {err}"
+
+
+def test_bounded_cache_evicts_at_full_size():
+    # cfg3's cap reached quickly: capacity of 3 frames of slots, 8 frames pushed through
+    rollout("cfg2", 8, 3, [3])
+
+
+def test_world_model_shaped_layer():
+    # cfg5's shape (40 heads, 3600 tokens per frame, 128 clusters) on a short rollout
+    heads = [0, 39]
+    c, fs, codec, dcodec, gpu, ref = rollout("cfg5", 5, 5, heads)
+    select_and_attend(c, fs, codec, dcodec, gpu, ref, heads, 29)
+
+
+def test_dense_limit_uncompressed_wan_cache():
+    # plain concatenation of 4 frames (nothing merges at tau^2 = 2) and every block selected:
+    # the kernel must reproduce dense softmax attention over 6240 keys
+    heads = [5]
+    c, fs, codec, dcodec, gpu, ref = rollout("cfg2", 4, 4, heads, tau=2.0 ** 0.5)
+    assert int(ref.len[0]) == 4 * c["T"]
+    n_kb = (4 * c["T"] + c["BK"] - 1) // c["BK"]
+    select_and_attend(c, fs, codec, dcodec, gpu, ref, heads, n_kb)
