@@ -128,40 +128,55 @@ class ChunkPipeline:
         return 4.0 * self.d * float(pairs.item())
 
 
-def gen_chunks(cfg, n_prefill, n_chunks, to_dev):
-    """Host-side generation of the whole rollout, uploaded once."""
+def gen_chunks(cfg, n_prefill, n_chunks, to_dev, cpu_heads):
+    """Host-side generation of the whole rollout, uploaded once.  The first cpu_heads heads of the prefill
+    frames are kept on the host for the CPU oracle's own rollout."""
+    import numpy as np
     from workloads import FrameStream, PromptSet
     fs = FrameStream(cfg["seed"], cfg["cfg_id"], cfg["H"], cfg["d"], cfg["T"], cfg["n_c"], cfg["p"], cfg["sigma_d"],
                      cfg["dtype"])
-    prefill = [tuple(to_dev(a) for a in fs.next_frame()) for _ in range(n_prefill)]
+    prefill, prefill_host = [], []
+    for _ in range(n_prefill):
+        K, V = fs.next_frame()
+        prefill.append((to_dev(K), to_dev(V)))
+        prefill_host.append((np.ascontiguousarray(K[:cpu_heads]), np.ascontiguousarray(V[:cpu_heads])))
     chunks = []
     for _ in range(n_chunks):
         frames = [fs.next_frame() for _ in range(cfg["chunk_frames"])]
         Q = fs.queries(cfg["chunk_frames"])
         chunks.append((frames, Q))
     ps = PromptSet(cfg["seed"], cfg["cfg_id"], fs.centreK, cfg["n_p"], cfg["n_pc"], cfg["n_near"], cfg["dtype"])
-    return prefill, chunks, ps
+    return prefill, prefill_host, chunks, ps
 
 
-def cpu_baseline(cfg, pipe, host_state, last_chunk, ps, n_heads, to_host):
-    """Replay the last chunk on the CPU oracle for the first n_heads heads; returns (ms scaled to all heads, info)."""
+def cpu_baseline(cfg, pipe, prefill_host, chunks, ps, n_heads, to_host):
+    """The CPU oracle's own rollout on the first n_heads heads (same inputs, its own cache state from frame 0);
+    only its last chunk step is timed.  Returns the cpu_baseline record, time scaled to all heads."""
     import numpy as np
     import oracle
     from workloads import make_codec
     H = cfg["H"]
     hs = slice(0, n_heads)
     codec = make_codec(cfg["seed"], cfg["cfg_id"], cfg["d"], cfg["r"])
-    cache = oracle.Cache(*(np.ascontiguousarray(a[hs]) for a in host_state["cache"]))
-    prev = np.ascontiguousarray(host_state["prev"][hs])
-    frames, Q = last_chunk
-    Qh = np.ascontiguousarray(Q[hs])
+    cache = oracle.Cache.empty(n_heads, pipe.C, cfg["d"], cfg["r"], cfg["dtype"])
     threads = len(os.sched_getaffinity(0))
-    t0 = time.perf_counter()
-    fid = host_state["frame_id"]
-    for K, V in frames:
-        prev, _, _ = oracle.tempcache_compress(cache, codec.R, codec.qscale, codec.shift, np.ascontiguousarray(K[hs]),
-                                               np.ascontiguousarray(V[hs]), cand=prev, tau2_q16=pipe.tau2, frame_id=fid)
+    prev, fid = None, 0
+
+    def push(K, V):
+        nonlocal prev, fid
+        prev, _, _ = oracle.tempcache_compress(cache, codec.R, codec.qscale, codec.shift, K, V, cand=prev,
+                                               tau2_q16=pipe.tau2, frame_id=fid)
         fid += 1
+    for K, V in prefill_host:
+        push(K, V)
+    for frames, _ in chunks[:-1]:
+        for K, V in frames:
+            push(np.ascontiguousarray(K[hs]), np.ascontiguousarray(V[hs]))
+    frames, Q = chunks[-1]
+    Qh = np.ascontiguousarray(Q[hs])
+    t0 = time.perf_counter()
+    for K, V in frames:
+        push(np.ascontiguousarray(K[hs]), np.ascontiguousarray(V[hs]))
     t1 = time.perf_counter()
     qc = oracle.encode(Qh, codec.R, codec.qscale, codec.shift)
     sel, nsel = oracle.ann_select_self(qc, cache.code, cache.len, pipe.BQ, pipe.n_rep, pipe.BK, pipe.n_sel)
@@ -186,8 +201,8 @@ def cpu_baseline(cfg, pipe, host_state, last_chunk, ps, n_heads, to_host):
                                             q_stride=97)
     info = {
         "value": round((t4 - t0) * 1e3 * scale, 1), "unit": "ms/chunk", "cores": threads, "kind": "oracle",
-        "sample": f"last timed chunk replayed on heads 0..{n_heads - 1} of {H} from the GPU's cache state; "
-                  f"time scaled by {scale:g}",
+        "sample": f"heads 0..{n_heads - 1} of {H}: the oracle's own rollout of the same frames, its last chunk step "
+                  f"timed; time scaled by {scale:g}",
         "stages_ms_scaled": {"compress": round((t1 - t0) * 1e3 * scale, 1), "encode+select": round((t2 - t1) * 1e3 * scale, 1),
                              "attn_self": round((t3 - t2) * 1e3 * scale, 1), "cross": round((t4 - t3) * 1e3 * scale, 1)},
         "parity_on_sample": {"sel_equal": sel_ok, "cross_sel_equal": csel_ok, "len_equal": len_ok,
@@ -195,6 +210,20 @@ def cpu_baseline(cfg, pipe, host_state, last_chunk, ps, n_heads, to_host):
         "selection_recall": round(recall, 4), "selection_density": round(density, 4),
     }
     return info
+
+
+def profiled_traffic_bytes():
+    """HBM bytes per launch of the self-attention kernel as recorded in profiles/ (rocprofv3 FETCH_SIZE +
+    WRITE_SIZE, scaled by a copy of known size), or None when the summary is absent."""
+    path = os.path.join(ROOT, "profiles", "cfg2_chunk_step_hbm_traffic.txt")
+    try:
+        for line in open(path):
+            if "attn_bf16_d128_kernel<4> [large]" in line and not line.startswith("#"):
+                f = line.split()
+                return (float(f[-2]) + float(f[-1])) * 1e6
+    except OSError:
+        pass
+    return None
 
 
 def main():
@@ -237,7 +266,8 @@ def main():
     codec = fa.Codec(to_dev(codec_h.R), float(codec_h.qscale), codec_h.shift)
     n_chunks = args.warmup + args.steps
     t_gen = time.perf_counter()
-    prefill, chunks, ps = gen_chunks(cfg, n_prefill, n_chunks, to_dev)
+    n_cpu_heads = min(args.cpu_heads, cfg["H"])
+    prefill, prefill_host, chunks, ps = gen_chunks(cfg, n_prefill, n_chunks, to_dev, n_cpu_heads)
     dev_chunks = [([(to_dev(K), to_dev(V)) for K, V in frames], to_dev(Q)) for frames, Q in chunks]
     t_gen = time.perf_counter() - t_gen
     pipe = ChunkPipeline(cfg, C, args.tau, torch, fa, codec, (to_dev(ps.K), to_dev(ps.V)), n_sel)
@@ -253,7 +283,6 @@ def main():
     stage_names = ["compress", "encode", "select_self", "attn_self", "select_cross", "attn_cross"]
     events = []
     flops = []
-    host_state = None
     t0 = time.perf_counter()
     for s in range(args.steps):
         evs = []
@@ -262,11 +291,6 @@ def main():
             e = torch.cuda.Event(enable_timing=True)
             e.record()
             evs.append(e)
-        if s == args.steps - 1 and not args.no_cpu_baseline:
-            # state the CPU replay starts from (device-side copies; read back after the timed region)
-            snap = [t.clone() for t in (pipe.cache.K, pipe.cache.V, pipe.cache.code, pipe.cache.cnt, pipe.cache.stamp,
-                                        pipe.cache.len)]
-            host_state = {"snap": snap, "prev": pipe.prev.clone(), "frame_id": pipe.frame_id}
         pipe.step(*dev_chunks[args.warmup + s], ev=mark)
         events.append(evs)
     torch.cuda.synchronize()
@@ -279,7 +303,6 @@ def main():
         dst.copy_(src)
         torch.cuda.synchronize()
         del src, dst
-    # the clones of the last step sit inside the timed region; they cost microseconds and are reported
     stage_ms = {n: 0.0 for n in stage_names}
     for evs in events:
         for i, n in enumerate(stage_names):
@@ -303,16 +326,17 @@ def main():
                    "cache_bytes": pipe.cache.nbytes()},
         "stages_ms": {k: round(v, 4) for k, v in stage_ms.items()},
         "effective_tflops": round(tflops, 2), "pct_mfma_peak": round(100 * tflops / PEAK_BF16_TFLOPS, 2),
-        "roofline": {"kernel": "attn_bf16_kernel<128,4> (block-sparse self-attention)", "bound": "mfma",
+        "roofline": {"kernel": "attn_bf16_d128_kernel<4> (block-sparse self-attention)", "bound": "mfma",
                      "achieved": round(tflops, 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                     "frac": round(tflops / PEAK_BF16_TFLOPS, 4), "traffic": None,
+                     "frac": round(tflops / PEAK_BF16_TFLOPS, 4),
+                     "traffic": profiled_traffic_bytes() if args.workload == "cfg2" else None,
                      "flops_per_launch": flops_last, "avg_launch_ms": round(attn_ms, 4)},
         "host_gen_s": round(t_gen, 1),
     }
     if not args.no_cpu_baseline:
-        hs = {"cache": [to_host(t) for t in host_state["snap"]], "prev": to_host(host_state["prev"]),
-              "frame_id": host_state["frame_id"]}
-        result["cpu_baseline"] = cpu_baseline(cfg, pipe, hs, chunks[-1], ps, min(args.cpu_heads, cfg["H"]), to_host)
+        result["cpu_baseline"] = cpu_baseline(cfg, pipe, prefill_host, chunks, ps, n_cpu_heads, to_host)
+    result["peaks_measured"] = {"mfma_bf16_tflops": round(fa.probe_mfma_bf16(), 1),
+                                "stream_copy_gbs": round(fa.probe_copy(), 1)}
     line = json.dumps(result)
     print(line, flush=True)
     if args.out:

@@ -136,7 +136,8 @@ int tempcache_compress(const fastar_cache *cache, const fastar_codec *codec, con
  *   Ties go to the smaller block index; the result is written in ascending block order.
  *   qcode [H,n_q,r], kcode [H,C,r], len [H]
  *   sel   [H,n_qb,n_sel] int32 out, padded with -1;  nsel [H,n_qb] int32 out;  n_qb = ceil(n_q/BQ)
- * Supported: r in {32,64}; BQ a multiple of n_rep; n_rep in {1,2,4,8,16,32}; any BK >= 1.
+ * Supported: r in {32,64}; BQ a multiple of n_rep; n_rep in {1,2,4,8,16,32}; BK a multiple of 32;
+ *            at most 1024 query blocks per head.
  */
 int ann_select_self(const int8_t *qcode, int n_q, const int8_t *kcode, const int32_t *len, int H, int C, int r,
                     int BQ, int n_rep, int BK, int n_sel, int32_t *sel, int32_t *nsel, void *ws,
@@ -165,6 +166,18 @@ int ann_select_cross(const int8_t *qcode, int n_q, const int8_t *pcode, int n_p,
 int sparse_attn_fwd(const void *Q, int n_q, const void *K, const void *V, const int32_t *cnt,
                     const int32_t *len, int H, int C, int d, int dtype, const int32_t *sel, const int32_t *nsel,
                     int BQ, int BK, int n_sel, float scale, void *O, float *lse, void *stream);
+
+/*
+ * Measurement probes (not part of the method): what this chip reaches on the two rooflines the kernels
+ * are priced against, measured in the same process as the benchmark.
+ *   fastar_probe_mfma_bf16  register-resident bf16 32x32x16 matrix-instruction loop on every SIMD;
+ *                           *flops_out (host) receives the floating-point operations one launch performs;
+ *                           sink is a device float the kernel may write (never does in practice).
+ *   fastar_probe_copy       plain streaming copy of `bytes` (multiple of 16) from src to dst (device, 16-byte aligned).
+ * Both enqueue one kernel on `stream`; the caller times them.
+ */
+int fastar_probe_mfma_bf16(int iters, float *sink, double *flops_out, void *stream);
+int fastar_probe_copy(const void *src, void *dst, size_t bytes, void *stream);
 
 #ifdef __cplusplus
 }

@@ -18,6 +18,8 @@ from .binding import (  # noqa: F401
     ann_select_self,
     encode,
     lib,
+    probe_copy,
+    probe_mfma_bf16,
     sparse_attn_fwd,
     tempcache_compress,
     workspace_bytes,

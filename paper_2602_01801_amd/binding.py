@@ -71,12 +71,16 @@ def lib() -> ctypes.CDLL:
                                       ctypes.c_void_p, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int,
                                       ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int, ctypes.c_int, ctypes.c_int,
                                       ctypes.c_float, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
+        L.fastar_probe_mfma_bf16.restype = ctypes.c_int
+        L.fastar_probe_mfma_bf16.argtypes = [ctypes.c_int, ctypes.c_void_p, ctypes.POINTER(ctypes.c_double), ctypes.c_void_p]
+        L.fastar_probe_copy.restype = ctypes.c_int
+        L.fastar_probe_copy.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
         _lib = L
     return _lib
 
 
 EXPORTS = ("fastar_version", "fastar_strerror", "fastar_workspace_bytes", "fastar_encode", "tempcache_compress",
-           "ann_select_self", "ann_select_cross", "sparse_attn_fwd")
+           "ann_select_self", "ann_select_cross", "sparse_attn_fwd", "fastar_probe_mfma_bf16", "fastar_probe_copy")
 
 
 def _check(rc: int, what: str):
@@ -262,3 +266,32 @@ def sparse_attn_fwd(Q, K, V, cnt, length, sel, nsel, BQ: int, BK: int, scale: fl
                                  _dtype_code(Q), sel.data_ptr(), nsel.data_ptr(), BQ, BK, n_sel, float(scale),
                                  O.data_ptr(), _ptr(lse), _stream()), "sparse_attn_fwd")
     return O, lse
+
+
+def probe_mfma_bf16(iters: int = 20000) -> float:
+    """Measured register-resident bf16 matrix-core rate in TFLOP/s (times one probe launch with events)."""
+    sink = torch.zeros(1, dtype=torch.float32, device="cuda")
+    flops = ctypes.c_double(0.0)
+    _check(lib().fastar_probe_mfma_bf16(200, sink.data_ptr(), ctypes.byref(flops), _stream()), "fastar_probe_mfma_bf16")
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    _check(lib().fastar_probe_mfma_bf16(iters, sink.data_ptr(), ctypes.byref(flops), _stream()), "fastar_probe_mfma_bf16")
+    e1.record()
+    torch.cuda.synchronize()
+    return flops.value / (e0.elapsed_time(e1) * 1e-3) / 1e12
+
+
+def probe_copy(mib: int = 1024, reps: int = 5) -> float:
+    """Measured streaming-copy rate in GB/s (read + write bytes over time)."""
+    src = torch.ones(mib << 20, dtype=torch.uint8, device="cuda")
+    dst = torch.empty_like(src)
+    _check(lib().fastar_probe_copy(src.data_ptr(), dst.data_ptr(), src.numel(), _stream()), "fastar_probe_copy")
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(reps):
+        _check(lib().fastar_probe_copy(src.data_ptr(), dst.data_ptr(), src.numel(), _stream()), "fastar_probe_copy")
+    e1.record()
+    torch.cuda.synchronize()
+    return 2.0 * src.numel() * reps / (e0.elapsed_time(e1) * 1e-3) / 1e9

@@ -7,6 +7,53 @@ size_t select_self_ws_bytes(int H, int n_q, int C, int r, int BQ, int BK, int n_
 size_t select_cross_ws_bytes(int H, int n_q, int n_p, int BQ);
 }  // namespace fastar
 
+namespace fastar {
+
+// Register-resident matrix-core loop: four independent bf16 32x32x16 accumulators per wavefront, no memory traffic.
+__global__ __launch_bounds__(256) void probe_mfma_kernel(int iters, float *sink) {
+    bf16x8 a, b;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        a[i] = (__bf16)1.0f;
+        b[i] = (__bf16)0.5f;
+    }
+    f32x16 acc[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[j][v] = 0.0f;
+    for (int i = 0; i < iters; ++i) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) acc[j] = mfma_bf16_32x32x16(a, b, acc[j]);
+    }
+    if (acc[0][0] + acc[1][1] + acc[2][2] + acc[3][3] == 12345.0f) sink[0] = 1.0f;
+}
+
+// Plain streaming copy, 16 bytes per lane, grid-stride.
+__global__ __launch_bounds__(256) void probe_copy_kernel(const u32x4 *__restrict__ src, u32x4 *__restrict__ dst, size_t n16) {
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += (size_t)gridDim.x * blockDim.x)
+        dst[i] = src[i];
+}
+
+}  // namespace fastar
+
+extern "C" int fastar_probe_mfma_bf16(int iters, float *sink, double *flops_out, void *stream) {
+    if (iters <= 0 || !sink) return FASTAR_ERR_INVALID_ARG;
+    const int wgs = 256 * 8;
+    hipLaunchKernelGGL(fastar::probe_mfma_kernel, dim3(wgs), dim3(256), 0, (hipStream_t)stream, iters, sink);
+    if (hipGetLastError() != hipSuccess) return FASTAR_ERR_HIP;
+    if (flops_out) *flops_out = (double)wgs * 4.0 * (double)iters * 4.0 * 32768.0;
+    return FASTAR_OK;
+}
+
+extern "C" int fastar_probe_copy(const void *src, void *dst, size_t bytes, void *stream) {
+    if (!src || !dst || (bytes & 15) || ((uintptr_t)src & 15) || ((uintptr_t)dst & 15)) return FASTAR_ERR_INVALID_ARG;
+    hipLaunchKernelGGL(fastar::probe_copy_kernel, dim3(256 * 16), dim3(256), 0, (hipStream_t)stream,
+                       (const fastar::u32x4 *)src, (fastar::u32x4 *)dst, bytes / 16);
+    if (hipGetLastError() != hipSuccess) return FASTAR_ERR_HIP;
+    return FASTAR_OK;
+}
+
 extern "C" const char *fastar_version(void) { return "fastar-gfx950 0.1"; }
 
 extern "C" const char *fastar_strerror(int code) {
