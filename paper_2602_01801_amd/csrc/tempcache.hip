@@ -302,9 +302,14 @@ __global__ __launch_bounds__(256) void tc_verify_kernel(const void *__restrict__
 }
 
 // ---- plan ----------------------------------------------------------------------------------------------
-// One workgroup per head.  Block-wide ordered exclusive count of a predicate over one chunk of 256 items.
+// One workgroup of PLAN_THREADS threads per head.
+constexpr int PLAN_THREADS = 1024;
+constexpr int PLAN_WAVES = PLAN_THREADS / 64;
+constexpr int PLAN_CACHED = 40;  // slots per thread kept in registers by the eviction passes (C <= 40960)
+
+// Block-wide ordered exclusive count of a predicate over one chunk of PLAN_THREADS items.
 struct BlockScan {
-    unsigned *wtot;  // [4] in LDS
+    unsigned *wtot;  // [PLAN_WAVES] in LDS
     __device__ __forceinline__ unsigned excl(bool flag, unsigned &total) {
         const int lane = lane_id(), wave = threadIdx.x >> 6;
         const unsigned long long m = __ballot(flag);
@@ -314,22 +319,46 @@ struct BlockScan {
         unsigned pos = __popcll(m & ((1ull << lane) - 1ull));
         total = 0;
 #pragma unroll
-        for (int w = 0; w < 4; ++w) {
-            if (w < wave) pos += wtot[w];
-            total += wtot[w];
+        for (int w = 0; w < PLAN_WAVES; ++w) {
+            const unsigned c = wtot[w];
+            if (w < wave) pos += c;
+            total += c;
+        }
+        return pos;
+    }
+    // Same for a per-thread count instead of a flag (exclusive prefix sum in thread order).
+    __device__ __forceinline__ unsigned excl_sum(unsigned v, unsigned &total) {
+        const int lane = lane_id(), wave = threadIdx.x >> 6;
+        unsigned incl = v;
+#pragma unroll
+        for (int off = 1; off < 64; off <<= 1) {
+            const unsigned o = __shfl_up(incl, off, WAVE);
+            if (lane >= off) incl += o;
+        }
+        __syncthreads();
+        if (lane == 63) wtot[wave] = incl;
+        __syncthreads();
+        unsigned pos = incl - v;
+        total = 0;
+#pragma unroll
+        for (int w = 0; w < PLAN_WAVES; ++w) {
+            const unsigned c = wtot[w];
+            if (w < wave) pos += c;
+            total += c;
         }
         return pos;
     }
 };
 
-__global__ __launch_bounds__(256) void tc_plan_kernel(int32_t *__restrict__ len, const int32_t *__restrict__ stamp, int C,
-                                                      int n_new, const int32_t *__restrict__ jstar,
-                                                      const uint8_t *__restrict__ merged, int32_t *__restrict__ rank,
-                                                      int32_t *__restrict__ victims, int32_t *__restrict__ hs,
-                                                      int32_t *__restrict__ stats) {
+__global__ __launch_bounds__(PLAN_THREADS) void tc_plan_kernel(int32_t *__restrict__ len, const int32_t *__restrict__ stamp,
+                                                               int C, int n_new, const int32_t *__restrict__ jstar,
+                                                               const uint8_t *__restrict__ merged,
+                                                               int32_t *__restrict__ rank, int32_t *__restrict__ victims,
+                                                               int32_t *__restrict__ hs, int32_t *__restrict__ stats) {
     extern __shared__ unsigned touched[];  // bitmap over slots, ceil(C/32) words
     __shared__ unsigned hist[256];
-    __shared__ unsigned wtot[4];
+    __shared__ unsigned wtot[PLAN_WAVES];
+    __shared__ unsigned red_min[PLAN_WAVES], red_max[PLAN_WAVES], red_cnt[PLAN_WAVES];
     __shared__ unsigned sh_bin, sh_remaining;
     const int h = blockIdx.x, tid = threadIdx.x, lane = lane_id(), wave = tid >> 6;
     const int L = min(len[h], C);
@@ -338,7 +367,7 @@ __global__ __launch_bounds__(256) void tc_plan_kernel(int32_t *__restrict__ len,
 
     // ranks of the unmerged tokens, ascending token order
     unsigned n_unm = 0;
-    for (int base = 0; base < n_new; base += 256) {
+    for (int base = 0; base < n_new; base += PLAN_THREADS) {
         const int i = base + tid;
         const bool unm = i < n_new && merged[tb + i] == 0;
         unsigned tot;
@@ -349,89 +378,134 @@ __global__ __launch_bounds__(256) void tc_plan_kernel(int32_t *__restrict__ len,
     int e = L + (int)n_unm - C;
     if (e < 0) e = 0;
     int n_victims = 0;
-    if (e > 0) {  // uniform branch
+    if (e > 0) {  // uniform branch: the cache is full, evict the e oldest untouched slots
         const int n_words = (C + 31) / 32;
-        for (int w = tid; w < n_words; w += 256) touched[w] = 0;
+        for (int w = tid; w < n_words; w += PLAN_THREADS) touched[w] = 0;
         __syncthreads();
-        for (int i = tid; i < n_new; i += 256)
+        for (int i = tid; i < n_new; i += PLAN_THREADS)
             if (merged[tb + i]) {
                 const int j = jstar[tb + i];
                 atomicOr(&touched[j >> 5], 1u << (j & 31));
             }
         __syncthreads();
         const int32_t *st = stamp + (size_t)h * C;
-        // key: larger = older.  eligible slots: live and untouched
-        auto eligible = [&](int j) -> bool { return j < L && !((touched[j >> 5] >> (j & 31)) & 1u); };
-        auto key_at = [&](int j) -> unsigned { return ~((unsigned)st[j] ^ 0x80000000u); };
-        unsigned prefix = 0, mask = 0, remaining = (unsigned)e;
-        bool take_all = false;
-        for (int shift = 24; shift >= 0; shift -= 8) {
-            hist[tid] = 0;
-            __syncthreads();
-            for (int j = tid; j < L; j += 256) {
-                if (!eligible(j)) continue;
-                const unsigned u = key_at(j);
-                if ((u & mask) == prefix) atomicAdd(&hist[(u >> shift) & 255u], 1u);
-            }
-            __syncthreads();
-            if (wave == 0) {
-                unsigned c[4], s = 0;
+        // Every thread owns a contiguous run of `per` slots (a multiple of 4, so that runs are read with
+        // 16-byte loads).  Eligible = live and untouched; key: larger = older.  Up to PLAN_CACHED keys per
+        // thread are read once and kept in registers, every pass is then thread-local arithmetic plus one
+        // reduction or prefix sum over the workgroup.
+        const int per = (((L + PLAN_THREADS - 1) / PLAN_THREADS) + 3) & ~3;
+        const int j0 = tid * per;
+        const bool cached = per <= PLAN_CACHED;
+        const bool aligned16 = (((uintptr_t)st) & 15) == 0;  // runs start at multiples of 4 slots
+        unsigned kreg[PLAN_CACHED];
+        unsigned long long elig_mask = 0ull;
+        if (cached) {
 #pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    c[q] = hist[255 - 4 * lane - q];
-                    s += c[q];
-                }
-                unsigned incl = s;
+            for (int q = 0; q < PLAN_CACHED / 4; ++q) {
+                const int j = j0 + 4 * q;
+                i32x4 v = {0, 0, 0, 0};
+                if (4 * q < per && j + 3 < C && aligned16) {
+                    v = *(const i32x4 *)(st + j);
+                } else if (4 * q < per) {
 #pragma unroll
-                for (int off = 1; off < 64; off <<= 1) {
-                    unsigned o = __shfl_up(incl, off, WAVE);
-                    if (lane >= off) incl += o;
+                    for (int c = 0; c < 4; ++c)
+                        if (j + c < C) v[c] = st[j + c];
                 }
-                unsigned before = incl - s;
-                const unsigned total = __shfl(incl, 63, WAVE);
-                if (lane == 0 && total < remaining) {  // fewer eligible slots than evictions needed
-                    sh_bin = 0x100u;
-                    sh_remaining = total;
-                }
-                if (total >= remaining && before < remaining && incl >= remaining) {
 #pragma unroll
-                    for (int q = 0; q < 4; ++q) {
-                        if (before != 0xFFFFFFFFu && before < remaining && before + c[q] >= remaining) {
-                            sh_bin = 255 - 4 * lane - q;
-                            sh_remaining = remaining - before;
-                            before = 0xFFFFFFFFu;
-                        } else if (before != 0xFFFFFFFFu) {
-                            before += c[q];
-                        }
-                    }
-                }
+                for (int c = 0; c < 4; ++c) kreg[4 * q + c] = ~((unsigned)v[c] ^ 0x80000000u);
             }
-            __syncthreads();
-            if (sh_bin == 0x100u) {  // can only happen in the first pass (uniform)
-                take_all = true;
-                n_victims = (int)sh_remaining;
-                break;
+#pragma unroll
+            for (int k = 0; k < PLAN_CACHED; ++k) {
+                const int j = j0 + k;
+                if (k < per && j < L && !((touched[j >> 5] >> (j & 31)) & 1u)) elig_mask |= 1ull << k;
             }
-            prefix |= sh_bin << shift;
-            mask |= 0xFFu << shift;
-            remaining = sh_remaining;
         }
-        if (!take_all) n_victims = e;
-        const unsigned T = prefix, need = remaining;
-        unsigned eq_before = 0, out_before = 0;
-        for (int base = 0; base < L; base += 256) {
-            const int j = base + tid;
-            const bool el = j < L && eligible(j);
-            const unsigned u = el ? key_at(j) : 0u;
-            const bool is_gt = el && (take_all || u > T), is_eq = el && !take_all && u == T;
-            unsigned eq_tot, take_tot;
-            const unsigned eq_rank = eq_before + scan.excl(is_eq, eq_tot);
-            const bool take = is_gt || (is_eq && eq_rank < need);
-            const unsigned pos = out_before + scan.excl(take, take_tot);
-            if (take) victims[tb + pos] = j;
-            eq_before += eq_tot;
-            out_before += take_tot;
+        // visit(f): calls f(slot, key) for the eligible slots of this thread's run, ascending
+        auto visit = [&](auto &&f) {
+            if (cached) {
+#pragma unroll
+                for (int k = 0; k < PLAN_CACHED; ++k)
+                    if ((elig_mask >> k) & 1ull) f(j0 + k, kreg[k]);
+            } else {
+                for (int j = j0; j < min(j0 + per, L); ++j)
+                    if (!((touched[j >> 5] >> (j & 31)) & 1u)) f(j, ~((unsigned)st[j] ^ 0x80000000u));
+            }
+        };
+        // workgroup-wide sum of a per-thread count
+        auto block_sum = [&](unsigned c) -> unsigned {
+#pragma unroll
+            for (int off = 32; off >= 1; off >>= 1) c += shfl_xor(c, off);
+            __syncthreads();  // previous readers of red_cnt are done
+            if (lane == 0) red_cnt[wave] = c;
+            __syncthreads();
+            unsigned tot = 0;
+#pragma unroll
+            for (int w = 0; w < PLAN_WAVES; ++w) tot += red_cnt[w];
+            return tot;
+        };
+        // range of the keys and number of eligible slots
+        unsigned kmin = 0xFFFFFFFFu, kmax = 0u, cnt_el = 0u;
+        visit([&](int, unsigned u) {
+            kmin = min(kmin, u);
+            kmax = max(kmax, u);
+            cnt_el += 1;
+        });
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) {
+            kmin = min(kmin, shfl_xor(kmin, off));
+            kmax = max(kmax, shfl_xor(kmax, off));
         }
+        if (lane == 0) {
+            red_min[wave] = kmin;
+            red_max[wave] = kmax;
+        }
+        cnt_el = block_sum(cnt_el);  // its barriers also publish red_min / red_max
+        kmin = 0xFFFFFFFFu; kmax = 0u;
+#pragma unroll
+        for (int w = 0; w < PLAN_WAVES; ++w) {
+            kmin = min(kmin, red_min[w]);
+            kmax = max(kmax, red_max[w]);
+        }
+        const bool take_all = cnt_el <= (unsigned)e;  // fewer eligible slots than evictions needed: take them all
+        unsigned T = kmax, need = (unsigned)e;
+        if (take_all) {
+            n_victims = (int)cnt_el;
+        } else {
+            n_victims = e;
+            // e-th largest key by bisection on the key value (stamps repeat heavily: a histogram in LDS would
+            // serialise on a handful of bins).  Invariant: count(key >= lo) >= e.
+            unsigned lo = kmin, hi = kmax;
+            while (lo < hi) {  // uniform: lo, hi are the same in every thread
+                const unsigned mid = lo + ((hi - lo) >> 1) + 1u;
+                unsigned c = 0;
+                visit([&](int, unsigned u) { c += u >= mid ? 1u : 0u; });
+                if (block_sum(c) >= (unsigned)e) lo = mid;
+                else hi = mid - 1u;
+            }
+            T = lo;
+            unsigned c = 0;
+            visit([&](int, unsigned u) { c += u > T ? 1u : 0u; });
+            need = (unsigned)e - block_sum(c);
+        }
+        // ordered compaction, victims in ascending slot order: two prefix sums over the threads
+        unsigned c_gt = 0, c_eq = 0;
+        visit([&](int, unsigned u) {
+            c_gt += (take_all || u > T) ? 1u : 0u;
+            c_eq += (!take_all && u == T) ? 1u : 0u;
+        });
+        unsigned tot;
+        const unsigned eq_base = scan.excl_sum(c_eq, tot);
+        const unsigned eq_take = eq_base >= need ? 0u : min(c_eq, need - eq_base);  // ties this thread may take
+        unsigned pos = scan.excl_sum(c_gt + eq_take, tot);
+        unsigned eq_seen = 0;
+        visit([&](int j, unsigned u) {
+            bool take = take_all || u > T;
+            if (!take_all && u == T) {
+                take = eq_seen < eq_take;
+                eq_seen += 1;
+            }
+            if (take) victims[tb + pos++] = j;
+        });
     }
     if (tid == 0) {
         const int n_dropped = e - n_victims;
@@ -445,6 +519,9 @@ __global__ __launch_bounds__(256) void tc_plan_kernel(int32_t *__restrict__ len,
         len[h] = newL;
     }
 }
+
+// dynamic LDS of tc_plan_kernel: the touched bitmap
+static size_t plan_lds_bytes(int C) { return ((size_t)(C + 31) / 32) * 4; }
 
 // ---- apply ---------------------------------------------------------------------------------------------
 template <bool BF16, int D>
@@ -545,7 +622,7 @@ extern "C" int tempcache_compress(const fastar_cache *cache, const fastar_codec 
     if (cand && n_cand <= 0) return FASTAR_ERR_INVALID_ARG;
     if (dtype != FASTAR_F32 && dtype != FASTAR_BF16) return FASTAR_ERR_INVALID_ARG;
     if ((d != 64 && d != 128) || (r != 32 && r != 64)) return FASTAR_ERR_UNSUPPORTED;
-    if ((size_t)((C + 31) / 32) * 4 > 48 * 1024) return FASTAR_ERR_UNSUPPORTED;  // eviction bitmap lives in LDS
+    if (plan_lds_bytes(C) > 60 * 1024) return FASTAR_ERR_UNSUPPORTED;  // eviction bitmap and tables live in LDS
     if (((uintptr_t)cache->K & 15) || ((uintptr_t)cache->V & 15) || ((uintptr_t)cache->code & 15) ||
         ((uintptr_t)K_new & 15) || ((uintptr_t)V_new & 15) || ((uintptr_t)P_new & 15) || ((uintptr_t)ws & 255))
         return FASTAR_ERR_INVALID_ARG;
@@ -595,7 +672,7 @@ extern "C" int tempcache_compress(const fastar_cache *cache, const fastar_codec 
     FASTAR_TC(tc_verify_kernel, cache->K, K_new, cp, r, C, n_new, codec->qscale, metric, tau2_q16, jstar, sbest, win, grp,
               merged);
     FASTAR_LAUNCH_CHECK();
-    hipLaunchKernelGGL(tc_plan_kernel, dim3(H), dim3(256), (size_t)((C + 31) / 32) * 4, s, cache->len, cache->stamp, C,
+    hipLaunchKernelGGL(tc_plan_kernel, dim3(H), dim3(PLAN_THREADS), plan_lds_bytes(C), s, cache->len, cache->stamp, C,
                        n_new, jstar, merged, rank, victims, hs, stats);
     FASTAR_LAUNCH_CHECK();
     FASTAR_TC(tc_apply_kernel, cache->K, cache->V, cache->code, cache->cnt, cache->stamp, C, r, K_new, V_new, ck, n_new,

@@ -215,6 +215,37 @@ def test_tempcache_eviction_and_drops_bit_exact():
     run_rollout("cfg1", 2, 100, 2.0 ** 0.5)                            # capacity below one frame: drops
 
 
+@pytest.mark.parametrize("C,n_stamps", [(37440, 30), (37440, 1), (37440, 70000), (60000, 300), (1000, 5)])
+def test_tempcache_eviction_on_a_full_synthetic_cache(C, n_stamps):
+    # a full cache with random stamps (many ties, or several significant bytes): one call must evict exactly the
+    # oldest untouched slots, lowest slot first on ties, and refill them in ascending slot order
+    rng = np.random.default_rng(C + n_stamps)
+    H, d, r, T = 2, 64, 32, 300
+    codec = make_codec(0, 9, d, r)
+    ref = oracle.Cache.empty(H, C, d, r, "fp32")
+    ref.K[:] = rng.standard_normal((H, C, d)).astype(np.float32)
+    ref.V[:] = rng.standard_normal((H, C, d)).astype(np.float32)
+    ref.code[:] = oracle.encode(ref.K, codec.R, codec.qscale, codec.shift)
+    ref.cnt[:] = rng.integers(1, 4, size=(H, C))
+    ref.stamp[:] = rng.integers(0, n_stamps, size=(H, C)) - (n_stamps // 3)     # negative stamps too
+    ref.len[:] = [C, C - 17]
+    gpu = dev_cache(ref)
+    K_new = rng.standard_normal((H, T, d)).astype(np.float32)
+    K_new[:, :100] = ref.K[:, 5:105]                       # a third of the frame duplicates live slots: they merge
+    V_new = rng.standard_normal((H, T, d)).astype(np.float32)
+    cand = np.broadcast_to(np.arange(0, 400, dtype=np.int32), (H, 400)).copy()
+    mm_r, mg_r, st_r = oracle.tempcache_compress(ref, codec.R, codec.qscale, codec.shift, K_new, V_new, cand=cand,
+                                                 tau2_q16=TAU2(0.9), frame_id=10 ** 6)
+    mm_g, mg_g, st_g = fa.tempcache_compress(gpu, dev_codec(codec), to_dev(K_new), to_dev(V_new), cand=to_dev(cand),
+                                             tau2_q16=TAU2(0.9), frame_id=10 ** 6)
+    sync()
+    assert st_r[0, 3] > 100 and mg_r[:, :100].all()          # the case does evict and does merge
+    assert np.array_equal(to_host(st_g), st_r)
+    assert np.array_equal(to_host(mg_g), mg_r)
+    assert np.array_equal(to_host(mm_g), mm_r)
+    assert_cache_equal(host_cache(gpu), ref, VTOL["fp32"])
+
+
 def test_tempcache_whole_cache_match_and_inner_product_probe():
     run_rollout("cfg1", 4, 5 * 256, 0.9, windowed=False)
     run_rollout("cfg1", 4, 5 * 256, 0.9, windowed=True, metric=1, probe_queries=True)
