@@ -317,7 +317,7 @@ def main():
         "metric": "sparse-attn ms per generated chunk", "value": round(ms_per_step, 4), "unit": "ms/chunk",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
         "higher_is_better": False, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": f"{args.workload}: Wan-1.3B-shaped layer rollout, H {cfg['H']} d {cfg['d']}, chunk "
+        "config": {"workload": f"{args.workload}: {'Wan-1.3B-shaped' if args.workload == 'cfg2' else 'world-model-scale'} layer rollout, H {cfg['H']} d {cfg['d']}, chunk "
                                f"{cf}x{T} = {cf * T} queries, TempCache-bounded cache (cap {cap_frames} frames = {C} "
                                f"slots/head, tau {args.tau}), AnnSA {n_sel} of {n_kb_quoted} key blocks per query block "
                                f"(BQ {cfg['BQ']}, BK {cfg['BK']}), AnnCA {cfg['n_sel_cross']} of {cfg['n_p']} prompt tokens",
