@@ -326,7 +326,7 @@ def main():
                    "cache_bytes": pipe.cache.nbytes()},
         "stages_ms": {k: round(v, 4) for k, v in stage_ms.items()},
         "effective_tflops": round(tflops, 2), "pct_mfma_peak": round(100 * tflops / PEAK_BF16_TFLOPS, 2),
-        "roofline": {"kernel": "attn_bf16_d128_kernel<4> (block-sparse self-attention)", "bound": "mfma",
+        "roofline": {"kernel": "attn_bf16_d128_pp_kernel<4> (block-sparse self-attention)", "bound": "mfma",
                      "achieved": round(tflops, 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                      "frac": round(tflops / PEAK_BF16_TFLOPS, 4),
                      "traffic": profiled_traffic_bytes() if args.workload == "cfg2" else None,

@@ -162,6 +162,7 @@ int ann_select_cross(const int8_t *qcode, int n_q, const int8_t *pcode, int n_p,
  *   O [H,n_q,d] dtype out;  lse [H,n_q] float out or NULL.
  * Supported: bf16 with d in {64,128}, BQ in {64,128}, BK a power of two <= 64 (MFMA path, fp32
  * softmax and accumulation); fp32 with d in {64,128}, BQ <= 128, BK <= 64 (plain fp32 arithmetic).
+ * scale must be positive and finite (FASTAR_ERR_INVALID_ARG otherwise).
  */
 int sparse_attn_fwd(const void *Q, int n_q, const void *K, const void *V, const int32_t *cnt,
                     const int32_t *len, int H, int C, int d, int dtype, const int32_t *sel, const int32_t *nsel,

@@ -8,7 +8,9 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libfastar.so")
-SOURCES = ["api.hip", "encode.hip", "select.hip", "tempcache.hip", "attention.hip", "attention_d128.hip"]
+SOURCES = ["api.hip", "encode.hip", "select.hip", "tempcache.hip", "attention.hip", "attention_d128.hip",
+           "attention_d128_pp.hip"]
+ASM_CHECKED = ["attention_d128.hip", "attention_d128_pp.hip"]  # kernels that read LDS through inline assembly
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-fast-math", "-ffp-contract=on",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wno-unused-command-line-argument"]
 
@@ -20,13 +22,14 @@ def verify_asm_reads(hipcc: str, extra: list[str] | None = None) -> None:
         from . import asmcheck
     except ImportError:  # run as a script
         import asmcheck
-    asm = os.path.join(CSRC, "attention_d128.s")
-    cmd = [hipcc, *FLAGS, *(extra or []), "-S", "--cuda-device-only", os.path.join(CSRC, "attention_d128.hip"), "-o", asm]
-    subprocess.run(cmd, check=True, stdout=subprocess.DEVNULL, stderr=subprocess.DEVNULL)
-    bad = asmcheck.check(asm, verbose=False)
-    os.remove(asm)
-    if bad:
-        raise RuntimeError(f"attention_d128: {bad} instruction(s) touch registers of an in-flight inline-asm LDS read")
+    for src in ASM_CHECKED:
+        asm = os.path.join(CSRC, src.replace(".hip", ".s"))
+        cmd = [hipcc, *FLAGS, *(extra or []), "-S", "--cuda-device-only", os.path.join(CSRC, src), "-o", asm]
+        subprocess.run(cmd, check=True, stdout=subprocess.DEVNULL, stderr=subprocess.DEVNULL)
+        bad = asmcheck.check(asm, verbose=False)
+        os.remove(asm)
+        if bad:
+            raise RuntimeError(f"{src}: {bad} instruction(s) touch registers of an in-flight inline-asm LDS read")
 
 
 def build(verbose: bool = False, extra: list[str] | None = None) -> str:

@@ -370,6 +370,9 @@ __global__ __launch_bounds__(128) void attn_f32_kernel(const float *__restrict__
 int launch_attn_bf16_d128(const void *Q, int n_q, const void *K, const void *V, const int32_t *cnt, const int32_t *len,
                           int H, int C, const int32_t *sel, const int32_t *nsel, int BQ, int bk_shift, int n_sel,
                           float scale_log2, void *O, float *lse, hipStream_t s);
+int launch_attn_bf16_d128_pp(const void *Q, int n_q, const void *K, const void *V, const int32_t *cnt,
+                             const int32_t *len, int H, int C, const int32_t *sel, const int32_t *nsel, int bk_shift,
+                             int n_sel, float scale_log2, void *O, float *lse, hipStream_t s);
 
 }  // namespace fastar
 
@@ -382,6 +385,7 @@ extern "C" int sparse_attn_fwd(const void *Q, int n_q, const void *K, const void
     if (!Q || !K || !V || !len || !sel || !nsel || !O) return FASTAR_ERR_INVALID_ARG;
     if (H <= 0 || n_q <= 0 || C <= 0 || BQ <= 0 || BK <= 0 || n_sel <= 0) return FASTAR_ERR_INVALID_ARG;
     if (dtype != FASTAR_F32 && dtype != FASTAR_BF16) return FASTAR_ERR_INVALID_ARG;
+    if (!(scale > 0.0f) || !(scale < INFINITY)) return FASTAR_ERR_INVALID_ARG;
     if (((uintptr_t)Q & 15) || ((uintptr_t)K & 15) || ((uintptr_t)V & 15) || ((uintptr_t)O & 15))
         return FASTAR_ERR_INVALID_ARG;
     if (d != 64 && d != 128) return FASTAR_ERR_UNSUPPORTED;
@@ -397,6 +401,8 @@ extern "C" int sparse_attn_fwd(const void *Q, int n_q, const void *K, const void
     hipLaunchKernelGGL((attn_bf16_kernel<DD, NW>), grid, dim3(NW * 64), 0, s, (const unsigned short *)Q,          \
                        (const unsigned short *)K, (const unsigned short *)V, cnt, len, sel, nsel, n_q, C, bk_shift, \
                        n_sel, n_qb, H, scale_log2, (unsigned short *)O, lse)
+        if (d == 128 && BQ == 128)  // two query blocks per workgroup in anti-phase (matrix | vector) on each SIMD
+            return launch_attn_bf16_d128_pp(Q, n_q, K, V, cnt, len, H, C, sel, nsel, bk_shift, n_sel, scale_log2, O, lse, s);
         if (d == 128)  // tuned path: direct-to-LDS tiles, LDS transpose loads
             return launch_attn_bf16_d128(Q, n_q, K, V, cnt, len, H, C, sel, nsel, BQ, bk_shift, n_sel, scale_log2, O, lse, s);
         if (BQ == 128) FASTAR_ATTN(64, 4);

@@ -34,11 +34,12 @@ typedef __attribute__((ext_vector_type(4))) short s16x4;
 
 struct __attribute__((aligned(16))) TileMeta {
     int idx[TK];     // cache row of each tile position (masked positions: row 0)
-    float bias[TK];  // log2(cnt) of that row, -inf when masked
+    float bias[TK];  // log2(cnt) of that row in units of raw scores (divided by scale * log2 e), -inf when masked
 };
 
 __device__ __forceinline__ void fill_meta(TileMeta &m, int t, const int32_t *__restrict__ sel_row, int n_listed,
-                                          int bk_shift, int L, const int32_t *__restrict__ cnt_h) {
+                                          int bk_shift, int L, const int32_t *__restrict__ cnt_h,
+                                          float inv_scale_log2) {
     const int p = threadIdx.x;
     if (p < TK) {
         const int listpos = t * TK + p;
@@ -52,7 +53,7 @@ __device__ __forceinline__ void fill_meta(TileMeta &m, int t, const int32_t *__r
             }
         }
         float bias = -INFINITY;
-        if (key >= 0) bias = cnt_h ? __log2f((float)cnt_h[key]) : 0.0f;
+        if (key >= 0) bias = cnt_h ? __log2f((float)cnt_h[key]) * inv_scale_log2 : 0.0f;
         m.idx[p] = key >= 0 ? key : 0;
         m.bias[p] = bias;
     }
@@ -130,7 +131,7 @@ template <int NW>
 __global__ __launch_bounds__(NW * 64, 2) void attn_bf16_d128_kernel(
     const unsigned short *__restrict__ Q, const unsigned short *__restrict__ K, const unsigned short *__restrict__ V,
     const int32_t *__restrict__ cnt, const int32_t *__restrict__ len, const int32_t *__restrict__ sel,
-    const int32_t *__restrict__ nsel, int n_q, int C, int bk_shift, int n_sel, int n_qb, int H, float scale_log2,
+    const int32_t *__restrict__ nsel, int n_q, int C, int bk_shift, int n_sel, int n_qb, int H, float scale_log2, float inv_scale_log2,
     unsigned short *__restrict__ O, float *__restrict__ lse) {
     extern __shared__ __attribute__((aligned(1024))) unsigned char lds[];
     unsigned char *kbuf = lds;
@@ -173,7 +174,11 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_bf16_d128_kernel(
     for (int db = 0; db < D / 32; ++db)
 #pragma unroll
         for (int v = 0; v < 16; ++v) o_acc[db][v] = 0.0f;
-    float m_run = -INFINITY, l_run = 0.0f;
+    // running softmax state per query (lanes l and l+32 hold the two key halves of query column l%32):
+    // m_ref = reference maximum in raw score units, neg_ms = -m_ref * scale (0 while m_ref = -inf), l0/l1 = sums of P
+    float m_ref = -INFINITY, neg_ms = 0.0f, l0 = 0.0f, l1 = 0.0f;
+    const float tau_raw = 8.0f * inv_scale_log2;   // the reference may lag the true maximum by 8 octaves: P <= 256
+    typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
 
     // direct global -> LDS loads of one tile: instruction i of this wavefront covers tile rows
     // 4*(wave*IPW+i) .. +3, lane l -> row +l/16, LDS chunk l%16, global chunk swizzled
@@ -211,8 +216,8 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_bf16_d128_kernel(
     };
     int kb_ahead = -1;  // selection entry of this thread's position in tile t+2
     if (nt > 0) {
-        fill_meta(meta[0], 0, sel_row, n_listed, bk_shift, L, cnt_h);
-        if (nt > 1) fill_meta(meta[1], 1, sel_row, n_listed, bk_shift, L, cnt_h);
+        fill_meta(meta[0], 0, sel_row, n_listed, bk_shift, L, cnt_h, inv_scale_log2);
+        if (nt > 1) fill_meta(meta[1], 1, sel_row, n_listed, bk_shift, L, cnt_h, inv_scale_log2);
         if (nt > 2) kb_ahead = sel_entry(2);
         __syncthreads();
         issue_loads(meta[0], 0);
@@ -254,9 +259,17 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_bf16_d128_kernel(
         if (t + 1 < nt) issue_loads(meta[(t + 1) % 3], STAGE ^ 1);
         const TileMeta &mt = meta[t % 3];
 
+        // The score accumulators start from the keys' bias (register v is key row 8(v/4)+4g+v%4 of its half),
+        // in units of raw scores, so K Q^T lands on top of it: masking and multiplicity cost no vector instruction.
         f32x16 s_acc[2];
 #pragma unroll
-        for (int v = 0; v < 16; ++v) { s_acc[0][v] = 0.0f; s_acc[1][v] = 0.0f; }
+        for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+            for (int q4 = 0; q4 < 4; ++q4) {
+                const f32x4 bv = *(const f32x4 *)(&mt.bias[32 * kb + 8 * q4 + 4 * g]);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) s_acc[kb][4 * q4 + e] = bv[e];
+            }
         wait_k(ka);
         read_k<STAGE * TILEB + 32 * ROWB>(kb2, kaddr);  // keys 32..63, land during the first eight products
 #pragma unroll
@@ -267,49 +280,48 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_bf16_d128_kernel(
         read_vt<STAGE * TILEB>(va, vaddr);
 #pragma unroll
         for (int s = 0; s < D / 16; ++s) s_acc[1] = mfma_bf16_32x32x16(kb2[s], qf[s], s_acc[1]);
-        float mx = -INFINITY;
+        // P = exp2(scale * (S - m_ref)) with a lazily updated reference: O and the sums are rescaled only when
+        // some query of the wavefront exceeds its reference by more than tau, which after the first tiles is
+        // rare; any reference cancels in O / l, P just ranges up to 2^8 instead of 1.
+        float mx = s_acc[0][0];
 #pragma unroll
-        for (int kb = 0; kb < 2; ++kb)
+        for (int v = 1; v < 16; ++v) mx = fmaxf(mx, s_acc[0][v]);
 #pragma unroll
-            for (int q4 = 0; q4 < 4; ++q4) {
-                const f32x4 bv = *(const f32x4 *)(&mt.bias[32 * kb + 8 * q4 + 4 * g]);
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    const float sv = fmaf(s_acc[kb][4 * q4 + e], scale_log2, bv[e]);
-                    s_acc[kb][4 * q4 + e] = sv;
-                    mx = fmaxf(mx, sv);
-                }
-            }
+        for (int v = 0; v < 16; ++v) mx = fmaxf(mx, s_acc[1][v]);
         mx = fmaxf(mx, shfl_xor(mx, 32));
-        const float m_new = fmaxf(m_run, mx);
-        const float m_safe = m_new == -INFINITY ? 0.0f : m_new;
-        const bool grew = m_new > m_run;
-        const float alpha = __builtin_amdgcn_exp2f(m_run - m_safe);
-        float psum = 0.0f;
-#pragma unroll
-        for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const float p = __builtin_amdgcn_exp2f(s_acc[kb][v] - m_safe);
-                s_acc[kb][v] = p;
-                psum += p;
-            }
-        m_run = m_new;
-        if (__any(grew)) {  // wave-uniform: rescale only when some query of this wavefront saw a new maximum
-            l_run *= alpha;
+        if (__any(mx > m_ref + tau_raw)) {   // wave-uniform
+            const float m_new = fmaxf(m_ref, mx);
+            const float alpha = m_ref == -INFINITY ? 0.0f : __builtin_amdgcn_exp2f((m_ref - m_new) * scale_log2);
+            m_ref = m_new;
+            neg_ms = m_new == -INFINITY ? 0.0f : -m_new * scale_log2;
+            l0 *= alpha;
+            l1 *= alpha;
 #pragma unroll
             for (int db = 0; db < D / 32; ++db)
 #pragma unroll
                 for (int v = 0; v < 16; ++v) o_acc[db][v] *= alpha;
         }
-        l_run += psum;
+        bf16x2 ones;
+        ones[0] = (__bf16)1.0f;
+        ones[1] = (__bf16)1.0f;
         bf16x8 pf[2][2];
 #pragma unroll
         for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-            for (int half = 0; half < 2; ++half)
+            for (int hh = 0; hh < 2; ++hh) {
+                bf16x2 pr[4];
 #pragma unroll
-                for (int e = 0; e < 8; ++e) pf[kb][half][e] = (__bf16)s_acc[kb][8 * half + e];
+                for (int j = 0; j < 4; ++j) {
+                    const float p0 = __builtin_amdgcn_exp2f(fmaf(s_acc[kb][8 * hh + 2 * j], scale_log2, neg_ms));
+                    const float p1 = __builtin_amdgcn_exp2f(fmaf(s_acc[kb][8 * hh + 2 * j + 1], scale_log2, neg_ms));
+                    pr[j][0] = (__bf16)p0;
+                    pr[j][1] = (__bf16)p1;
+                    // the sums take the rounded P, the values the PV product sees
+                    if (j & 1) l1 = __builtin_amdgcn_fdot2_f32_bf16(pr[j], ones, l1, false);
+                    else l0 = __builtin_amdgcn_fdot2_f32_bf16(pr[j], ones, l0, false);
+                }
+                __builtin_memcpy(&pf[kb][hh], pr, 16);
+            }
 
         wait_vt(va);
         read_vt<STAGE * TILEB + 32 * ROWB>(vb, vaddr);  // keys 32..63, land during the first eight products
@@ -322,7 +334,7 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_bf16_d128_kernel(
         if (t + 2 < nt && tid < TK) {
             TileMeta &m2 = meta[(t + 2) % 3];
             m2.idx[tid] = key2 >= 0 ? key2 : 0;
-            m2.bias[tid] = key2 >= 0 ? (cnt_h ? __log2f((float)cnt2) : 0.0f) : -INFINITY;
+            m2.bias[tid] = key2 >= 0 ? (cnt_h ? __log2f((float)cnt2) * inv_scale_log2 : 0.0f) : -INFINITY;
         }
         kb_ahead = kb3;
     };
@@ -332,7 +344,8 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_bf16_d128_kernel(
     }
 
     // epilogue: normalise, transpose through LDS (K stages are free now), store rows coalesced
-    const float l_tot = l_run + shfl_xor(l_run, 32);
+    const float l_lane = l0 + l1;
+    const float l_tot = l_lane + shfl_xor(l_lane, 32);
     const float inv = l_tot > 0.0f ? 1.0f / l_tot : 0.0f;
     __syncthreads();
     constexpr int OSTR = D + 8;  // bf16 elements per staged row (16-byte pad)
@@ -360,7 +373,7 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_bf16_d128_kernel(
         }
     }
     if (lse && g == 0 && q_idx < n_q)
-        lse[(size_t)h * n_q + q_idx] = l_tot > 0.0f ? (m_run + __log2f(l_tot)) * LN2 : -INFINITY;
+        lse[(size_t)h * n_q + q_idx] = l_tot > 0.0f ? (m_ref * scale_log2 + __log2f(l_tot)) * LN2 : -INFINITY;
 }
 
 }  // namespace d128
@@ -384,11 +397,11 @@ int launch_attn_bf16_d128(const void *Q, int n_q, const void *K, const void *V, 
     if (BQ == 128)
         hipLaunchKernelGGL(attn_bf16_d128_kernel<4>, grid, dim3(256), LDS_BYTES, s, (const unsigned short *)Q,
                            (const unsigned short *)K, (const unsigned short *)V, cnt, len, sel, nsel, n_q, C, bk_shift,
-                           n_sel, n_qb, H, scale_log2, (unsigned short *)O, lse);
+                           n_sel, n_qb, H, scale_log2, 1.0f / scale_log2, (unsigned short *)O, lse);
     else
         hipLaunchKernelGGL(attn_bf16_d128_kernel<2>, grid, dim3(128), LDS_BYTES, s, (const unsigned short *)Q,
                            (const unsigned short *)K, (const unsigned short *)V, cnt, len, sel, nsel, n_q, C, bk_shift,
-                           n_sel, n_qb, H, scale_log2, (unsigned short *)O, lse);
+                           n_sel, n_qb, H, scale_log2, 1.0f / scale_log2, (unsigned short *)O, lse);
     if (hipGetLastError() != hipSuccess) return FASTAR_ERR_HIP;
     return FASTAR_OK;
 }

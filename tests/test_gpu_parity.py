@@ -142,6 +142,9 @@ def check_attention(Q, K, V, cnt, length, sel, nsel, BQ, BK, scale, dtype):
     ("bf16", 2, 260, 1024, 64, 64, 64, 5, [1024, 1000], True),       # d = 64, BQ = 64
     ("bf16", 1, 128, 512, 128, 64, 8, 40, [509], True),              # small key blocks
     ("bf16", 2, 200, 640, 64, 128, 64, 10, [640, 600], False),
+    ("bf16", 1, 300, 64 * 20, 128, 128, 64, 20, [1280], True),       # odd number of query blocks: a lone block in the last workgroup
+    ("bf16", 1, 100, 640, 128, 128, 32, 7, [640], True),             # a single query block
+    ("bf16", 5, 128, 64 * 9, 128, 128, 64, 9, [576, 64, 0, 576, 1], False),   # neighbours with 9 / 1 / 0 tiles
 ])
 def test_sparse_attention_matches_oracle(dtype, H, n_q, C, d, BQ, BK, n_sel, lens, use_cnt):
     rng = np.random.default_rng(n_q * 7 + C)
@@ -286,6 +289,29 @@ def test_tempcache_then_select_then_attend_end_to_end_cfg1():
     assert np.abs(to_host(O).astype(np.float64) - O_ref).max() <= 1e-4
 
 
+@pytest.mark.parametrize("BQ", [128, 64])
+def test_attention_with_logits_that_keep_growing_along_the_key_list(BQ):
+    """The bf16 d = 128 kernels follow the running maximum lazily (the reference of the exponentials moves only
+    when a score exceeds it by a margin); keys whose scores climb steadily, by less and by more than that margin
+    per tile, must give the same softmax as the oracle's plain definition."""
+    rng = np.random.default_rng(77)
+    H, n_q, C, d, BK = 2, 256, 64 * 24, 128, 64
+    base = rng.standard_normal((H, 1, d)).astype(np.float32)
+    Q = to_storage(base + 0.3 * rng.standard_normal((H, n_q, d)).astype(np.float32), "bf16")
+    ramp = np.linspace(0.0, 1.0, C, dtype=np.float32)[None, :, None]
+    ramp = np.where(np.arange(C)[None, :, None] < C // 2, 0.25 * ramp, ramp * ramp * 3.0)    # slow, then fast
+    K = to_storage(base * ramp + 0.3 * rng.standard_normal((H, C, d)).astype(np.float32), "bf16")
+    V = to_storage(rng.standard_normal((H, C, d)).astype(np.float32), "bf16")
+    length = np.full((H,), C, np.int32)
+    cnt = rng.integers(1, 5, size=(H, C)).astype(np.int32)
+    n_qb, n_sel = n_q // BQ, C // BK
+    sel = np.tile(np.arange(n_sel, dtype=np.int32), (H, n_qb, 1))
+    sel[1] = sel[1, :, ::-1]                                         # head 1 meets the largest scores first
+    nsel = np.full((H, n_qb), n_sel, np.int32)
+    for scale in (d ** -0.5, 4.0 * d ** -0.5):
+        check_attention(Q, K, V, cnt, length, sel, nsel, BQ, BK, scale, "bf16")
+
+
 # ----------------------------------------------------------------------------------------- argument checks
 
 def test_bad_arguments_are_rejected_on_the_host():
@@ -303,3 +329,7 @@ def test_bad_arguments_are_rejected_on_the_host():
     nsel = torch.zeros((1, 1), dtype=torch.int32, device="cuda")
     with pytest.raises(fa.FastarError, match="unsupported"):
         fa.sparse_attn_fwd(Q, Q, Q, None, length, sel, nsel, 128, 64, 0.1)   # d = 96
+    Q = torch.zeros((1, 128, 128), dtype=torch.bfloat16, device="cuda")
+    for bad_scale in (0.0, -0.1, float("inf"), float("nan")):
+        with pytest.raises(fa.FastarError, match="invalid"):
+            fa.sparse_attn_fwd(Q, Q, Q, None, length, sel, nsel, 128, 64, bad_scale)
