@@ -7,7 +7,7 @@
 //   tc_verify     cosine test on the 8-bit quantised full-width keys as an int64 inequality; joiners
 //                 register in their slot's group record (count, best joiner)
 //   tc_plan       per head: ranks of the unmerged tokens (ballot + prefix sum), evictions needed,
-//                 victims = oldest untouched slots (radix select, ordered compaction), new length
+//                 victims = oldest untouched slots (histogram select over several workgroups, ordered compaction)
 //   tc_apply      representative key, mean value, multiplicity, code, stamp of merged slots; appended
 //                 tokens into victims / fresh slots; merge map
 // All decisions are integer and order-independent (max / count), so the merge map is reproducible.
@@ -22,6 +22,7 @@ int encode_launch(const void *x, int dtype, int64_t n_vec, int d, const fastar_c
 
 constexpr int CAND_CHUNK = 256;          // candidate positions scanned by one workgroup of tc_match
 constexpr int SCORE_BIAS = 1 << 23;      // makes every score positive inside the packed arg-max key
+constexpr int PLAN_SCRATCH_WORDS = 64 + 3 * 1024;  // per-head scratch of tc_plan_kernel (PS_STRIDE)
 constexpr int HS_STRIDE = 8;             // per-head scalars: oldL, n_unmerged, e, n_victims, n_dropped, newL
 
 typedef unsigned long long u64;
@@ -29,7 +30,7 @@ typedef unsigned long long u64;
 static inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
 struct CompressWs {
-    size_t ck, cp, best, jstar, sbest, rank, victims, hs, win, grp, total;
+    size_t ck, cp, best, jstar, sbest, rank, victims, hs, ps, win, grp, total;
 };
 static CompressWs compress_ws(int H, int C, int n_new, int r) {
     CompressWs w;
@@ -38,6 +39,7 @@ static CompressWs compress_ws(int H, int C, int n_new, int r) {
     w.ck = o; o += align256(T * r);
     w.cp = o; o += align256(T * r);
     w.best = o; o += align256(T * 8);
+    w.ps = o; o += align256((size_t)H * PLAN_SCRATCH_WORDS * 4);   // directly behind best: one zero fill covers both
     w.jstar = o; o += align256(T * 4);
     w.sbest = o; o += align256(T * 4);
     w.rank = o; o += align256(T * 4);
@@ -166,21 +168,50 @@ __global__ __launch_bounds__(256) void tc_match_kernel(const int8_t *__restrict_
 }
 
 // ---- prep ----------------------------------------------------------------------------------------------
-__global__ void tc_prep_kernel(const u64 *__restrict__ best, int n_new, int C, int32_t *__restrict__ jstar,
-                               int32_t *__restrict__ sbest, u64 *__restrict__ win, int32_t *__restrict__ grp) {
+// Unpacks the match and clears the per-slot group records it will touch.  The same launch also leaves, per head, a
+// histogram of the live slots' ages (frame_id - stamp, 1024 bins, the last one collecting everything older) for
+// the eviction plan: a whole grid reads the stamps here, where the plan has few workgroups per head.
+constexpr int PREP_BINS = 1024;
+__global__ __launch_bounds__(256) void tc_prep_kernel(const u64 *__restrict__ best, int n_new, int C,
+                                                      int32_t *__restrict__ jstar, int32_t *__restrict__ sbest,
+                                                      u64 *__restrict__ win, int32_t *__restrict__ grp,
+                                                      const int32_t *__restrict__ len, const int32_t *__restrict__ stamp,
+                                                      int frame_id, unsigned *__restrict__ plan_scratch, int hist_word,
+                                                      int fut_word, int scratch_words) {
+    __shared__ unsigned lhist[PREP_BINS];
     const int h = blockIdx.y;
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
-    if (i >= n_new) return;
-    const u64 key = best[(size_t)h * n_new + i];
-    int j = -1, S = 0;
-    if (key != 0) {
-        j = (int)(0xFFFFFFFFu - (unsigned)key);
-        S = (int)(unsigned)(key >> 32) - SCORE_BIAS;
-        win[(size_t)h * C + j] = 0;
-        grp[(size_t)h * C + j] = 0;
+    if (i < n_new) {
+        const u64 key = best[(size_t)h * n_new + i];
+        int j = -1, S = 0;
+        if (key != 0) {
+            j = (int)(0xFFFFFFFFu - (unsigned)key);
+            S = (int)(unsigned)(key >> 32) - SCORE_BIAS;
+            win[(size_t)h * C + j] = 0;
+            grp[(size_t)h * C + j] = 0;
+        }
+        jstar[(size_t)h * n_new + i] = j;
+        sbest[(size_t)h * n_new + i] = S;
     }
-    jstar[(size_t)h * n_new + i] = j;
-    sbest[(size_t)h * n_new + i] = S;
+    const int L = min(len[h], C);
+    if (L + n_new <= C) return;  // uniform over the head: no eviction can be needed
+    for (int k = threadIdx.x; k < PREP_BINS; k += blockDim.x) lhist[k] = 0;
+    __syncthreads();
+    const int chunk = (L + gridDim.x - 1) / gridDim.x;
+    const int j0 = blockIdx.x * chunk, j1 = min(j0 + chunk, L);
+    const int32_t *st = stamp + (size_t)h * C;
+    bool future = false;
+    for (int j = j0 + threadIdx.x; j < j1; j += blockDim.x) {
+        const int sj = st[j];
+        if (sj > frame_id) future = true;
+        const unsigned age = (unsigned)frame_id - (unsigned)sj;
+        atomicAdd(&lhist[min(age, (unsigned)(PREP_BINS - 1))], 1u);
+    }
+    __syncthreads();
+    unsigned *ps = plan_scratch + (size_t)h * scratch_words;
+    for (int k = threadIdx.x; k < PREP_BINS; k += blockDim.x)
+        if (lhist[k]) atomicAdd(&ps[hist_word + k], lhist[k]);
+    if (__any(future) && lane_id() == 0) atomicOr(&ps[fut_word], 1u);
 }
 
 // ---- row pieces: 16 lanes share one row of D elements ----------------------------------------------------
@@ -302,12 +333,56 @@ __global__ __launch_bounds__(256) void tc_verify_kernel(const void *__restrict__
 }
 
 // ---- plan ----------------------------------------------------------------------------------------------
-// One workgroup of PLAN_THREADS threads per head.
-constexpr int PLAN_THREADS = 1024;
+// NB + 1 workgroups of PLAN_THREADS threads per head (grid (NB + 1) x H).  The last one ranks the unmerged tokens.
+// Each of the others counts the unmerged tokens and so knows e, the number of evictions needed.  When e > 0 they
+// split the slots into NB contiguous ranges and find the e oldest untouched slots together:
+//   threshold key T and the number of ties to take -> counts per workgroup -> ordered compaction, victims in
+//   ascending slot order.
+// T is normally read off the age histogram tc_prep_kernel left (no communication); otherwise: range of the keys ->
+// histogram over that range (1024 bins, a second one inside the threshold bin when the range is wider).
+// Between phases the workgroups of a head meet at a counter in global memory (head_barrier).  The grid is
+// kept small enough (NB * H <= PLAN_MAX_GRID workgroups of 256 threads) to be resident at once, and every wait
+// is bounded: a wait that runs out raises stats[7] and lets the kernel finish.
+constexpr int PLAN_THREADS = 256;
 constexpr int PLAN_WAVES = PLAN_THREADS / 64;
-constexpr int PLAN_CACHED = 40;  // slots per thread kept in registers by the eviction passes (C <= 40960)
+constexpr int PLAN_NB_MAX = 16;
+constexpr int PLAN_MAX_GRID = 1024;
+constexpr int PLAN_BINS = 1024;
+constexpr int PLAN_SPIN_LIMIT = 1 << 20;
+// per-head scratch in global memory (32-bit words), zeroed by tc_prep_kernel
+constexpr int PS_BAR = 0;                       // 4 arrival counters
+constexpr int PS_MAXK = 4, PS_MAXNK = 5;        // max key, max ~key
+constexpr int PS_TOT = 6, PS_ERR = 7;           // eligible slots, bounded wait ran out
+constexpr int PS_BLK = 8;                       // per workgroup, 64 bits: valid | count key > T | count key == T
+constexpr int PS_FUT = 40;                      // some live slot carries a stamp above this call's frame id
+constexpr int PS_HIST = 64;                     // histograms of PLAN_BINS: ages (from tc_prep_kernel), two select levels
+constexpr int PS_STRIDE = PS_HIST + 3 * PLAN_BINS;
+static_assert(PS_STRIDE == PLAN_SCRATCH_WORDS, "workspace layout");
 
-// Block-wide ordered exclusive count of a predicate over one chunk of PLAN_THREADS items.
+__device__ __forceinline__ unsigned ld_agent(const unsigned *p) {
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// All NB workgroups of a head arrive at counter *ctr; returns when all have (or the bounded wait ran out).
+__device__ __forceinline__ void head_barrier(unsigned *ctr, unsigned nb, unsigned *err) {
+    __syncthreads();
+    if (nb > 1 && threadIdx.x == 0) {
+        __threadfence();
+        atomicAdd(ctr, 1u);
+        int spins = 0;
+        while (ld_agent(ctr) < nb) {
+            if (++spins > PLAN_SPIN_LIMIT) {
+                atomicExch(err, 1u);
+                break;
+            }
+            __builtin_amdgcn_s_sleep(4);
+        }
+        __threadfence();
+    }
+    __syncthreads();
+}
+
+// Block-wide ordered exclusive prefix over the threads, for a flag or a per-thread count.
 struct BlockScan {
     unsigned *wtot;  // [PLAN_WAVES] in LDS
     __device__ __forceinline__ unsigned excl(bool flag, unsigned &total) {
@@ -326,7 +401,6 @@ struct BlockScan {
         }
         return pos;
     }
-    // Same for a per-thread count instead of a flag (exclusive prefix sum in thread order).
     __device__ __forceinline__ unsigned excl_sum(unsigned v, unsigned &total) {
         const int lane = lane_id(), wave = threadIdx.x >> 6;
         unsigned incl = v;
@@ -348,155 +422,327 @@ struct BlockScan {
         }
         return pos;
     }
+    __device__ __forceinline__ unsigned sum(unsigned v) {
+        unsigned tot;
+        excl_sum(v, tot);
+        return tot;
+    }
 };
 
-__global__ __launch_bounds__(PLAN_THREADS) void tc_plan_kernel(int32_t *__restrict__ len, const int32_t *__restrict__ stamp,
-                                                               int C, int n_new, const int32_t *__restrict__ jstar,
-                                                               const uint8_t *__restrict__ merged,
-                                                               int32_t *__restrict__ rank, int32_t *__restrict__ victims,
-                                                               int32_t *__restrict__ hs, int32_t *__restrict__ stats) {
-    extern __shared__ unsigned touched[];  // bitmap over slots, ceil(C/32) words
-    __shared__ unsigned hist[256];
-    __shared__ unsigned wtot[PLAN_WAVES];
-    __shared__ unsigned red_min[PLAN_WAVES], red_max[PLAN_WAVES], red_cnt[PLAN_WAVES];
-    __shared__ unsigned sh_bin, sh_remaining;
-    const int h = blockIdx.x, tid = threadIdx.x, lane = lane_id(), wave = tid >> 6;
-    const int L = min(len[h], C);
-    BlockScan scan{wtot};
-    const size_t tb = (size_t)h * n_new;
+constexpr int PLAN_PER_MAX = 16;  // slots per thread kept in registers (longer runs are re-read from memory)
+constexpr int PLAN_TOK_MAX = 8;   // tokens per thread kept in registers (n_new <= 2048; more are re-read)
 
-    // ranks of the unmerged tokens, ascending token order
-    unsigned n_unm = 0;
-    for (int base = 0; base < n_new; base += PLAN_THREADS) {
-        const int i = base + tid;
-        const bool unm = i < n_new && merged[tb + i] == 0;
-        unsigned tot;
-        const unsigned pos = scan.excl(unm, tot);
-        if (i < n_new) rank[tb + i] = unm ? (int)(n_unm + pos) : -1;
-        n_unm += tot;
+__global__ __launch_bounds__(PLAN_THREADS) void tc_plan_kernel(const int32_t *__restrict__ len,
+                                                               const int32_t *__restrict__ stamp, int C, int n_new,
+                                                               int frame_id, const int32_t *__restrict__ jstar,
+                                                               const uint8_t *__restrict__ merged,
+                                                               const u64 *__restrict__ win, int32_t *__restrict__ rank,
+                                                               int32_t *__restrict__ victims, int32_t *__restrict__ hs,
+                                                               int32_t *__restrict__ stats, unsigned *__restrict__ ps_all) {
+    extern __shared__ unsigned touched[];  // bitmap over this workgroup's slot range
+    __shared__ unsigned lhist[PLAN_BINS];
+    __shared__ unsigned wtot[PLAN_WAVES];
+    __shared__ unsigned red_a[PLAN_WAVES], red_b[PLAN_WAVES];
+    __shared__ unsigned sh_bin, sh_above;
+    __shared__ unsigned sh_blk[2 * PLAN_NB_MAX];
+    static_assert(PLAN_THREADS * 4 == PLAN_BINS, "one thread per four bins");
+    const int h = blockIdx.y, b = blockIdx.x, NB = gridDim.x - 1;  // the last workgroup of a head only ranks
+    const int tid = threadIdx.x, lane = lane_id(), wave = tid >> 6;
+    const int L = min(len[h], C);
+    unsigned *ps = ps_all + (size_t)h * PS_STRIDE;
+    BlockScan scan{wtot};
+    const size_t tb = (size_t)h * n_new, cb = (size_t)h * C;
+
+    // workgroup NB of every head only ranks the unmerged tokens, ascending token order
+    if (b == NB) {
+        unsigned done = 0;
+        for (int base = 0; base < n_new; base += PLAN_THREADS) {
+            const int i = base + tid;
+            const bool unm = i < n_new && merged[tb + i] == 0;
+            unsigned tot;
+            const unsigned pos = scan.excl(unm, tot);
+            if (i < n_new) rank[tb + i] = unm ? (int)(done + pos) : -1;
+            done += tot;
+        }
+        return;
     }
+    // First round of loads, all independent: the tokens' merge flags and slots (PLAN_TOK_MAX per thread in
+    // registers), this thread's run of stamps, four bins of the age histogram.
+    const int32_t *st = stamp + cb;
+    int tj[PLAN_TOK_MAX];  // slot a token merged into, -1: not merged (or beyond n_new)
+    const bool tok_cached = n_new <= PLAN_TOK_MAX * PLAN_THREADS;
+    unsigned n_unm;
+    {
+        unsigned c = 0;
+        if (tok_cached) {
+            unsigned char mg[PLAN_TOK_MAX];
+#pragma unroll
+            for (int k = 0; k < PLAN_TOK_MAX; ++k) {
+                const int i = tid + k * PLAN_THREADS;
+                mg[k] = i < n_new ? merged[tb + i] : 1;
+                tj[k] = i < n_new ? jstar[tb + i] : -1;
+            }
+#pragma unroll
+            for (int k = 0; k < PLAN_TOK_MAX; ++k) {
+                c += mg[k] == 0 ? 1u : 0u;
+                if (!mg[k] || tid + k * PLAN_THREADS >= n_new) tj[k] = -1;
+            }
+        } else {
+            for (int i = tid; i < n_new; i += PLAN_THREADS) c += merged[tb + i] == 0 ? 1u : 0u;
+        }
+        // the loads below do not depend on the count: issued before the reduction waits for the ones above
+        n_unm = c;
+    }
+    const int span = (L + NB - 1) / NB;
+    const int s0 = min(b * span, L), s1 = min(s0 + span, L);
+    const int per = (span + PLAN_THREADS - 1) / PLAN_THREADS;
+    const int j0 = min(s0 + tid * per, s1), j1 = min(j0 + per, s1);
+    const bool maybe = L + n_new > C;  // uniform: otherwise no eviction can be needed
+    const bool cached = per <= PLAN_PER_MAX;
+    int sreg[PLAN_PER_MAX];
+    unsigned hreg[4] = {0, 0, 0, 0};
+    if (maybe) {
+        if (cached) {
+#pragma unroll
+            for (int k = 0; k < PLAN_PER_MAX; ++k) sreg[k] = j0 + k < j1 ? st[j0 + k] : 0;
+        }
+#pragma unroll
+        for (int q = 0; q < 4; ++q) hreg[q] = ps[PS_HIST + 4 * tid + q];   // written by the previous kernel
+    }
+    n_unm = scan.sum(n_unm);
     int e = L + (int)n_unm - C;
     if (e < 0) e = 0;
     int n_victims = 0;
-    if (e > 0) {  // uniform branch: the cache is full, evict the e oldest untouched slots
-        const int n_words = (C + 31) / 32;
-        for (int w = tid; w < n_words; w += PLAN_THREADS) touched[w] = 0;
-        __syncthreads();
-        for (int i = tid; i < n_new; i += PLAN_THREADS)
-            if (merged[tb + i]) {
-                const int j = jstar[tb + i];
-                atomicOr(&touched[j >> 5], 1u << (j & 31));
+    if (e > 0) {  // uniform over the head's workgroups: the cache is full, evict the e oldest untouched slots
+        // visit_tok(f): f(token, slot) for the merged tokens this thread looks after
+        auto visit_tok = [&](auto &&f) {
+            if (tok_cached) {
+#pragma unroll
+                for (int k = 0; k < PLAN_TOK_MAX; ++k)
+                    if (tj[k] >= 0) f(tid + k * PLAN_THREADS, tj[k]);
+            } else {
+                for (int i = tid; i < n_new; i += PLAN_THREADS)
+                    if (merged[tb + i]) f(i, jstar[tb + i]);
             }
-        __syncthreads();
-        const int32_t *st = stamp + (size_t)h * C;
-        // Every thread owns a contiguous run of `per` slots (a multiple of 4, so that runs are read with
-        // 16-byte loads).  Eligible = live and untouched; key: larger = older.  Up to PLAN_CACHED keys per
-        // thread are read once and kept in registers, every pass is then thread-local arithmetic plus one
-        // reduction or prefix sum over the workgroup.
-        const int per = (((L + PLAN_THREADS - 1) / PLAN_THREADS) + 3) & ~3;
-        const int j0 = tid * per;
-        const bool cached = per <= PLAN_CACHED;
-        const bool aligned16 = (((uintptr_t)st) & 15) == 0;  // runs start at multiples of 4 slots
-        unsigned kreg[PLAN_CACHED];
-        unsigned long long elig_mask = 0ull;
-        if (cached) {
+        };
+        // second round of loads: for the merged tokens, the record of their slot's group and the slot's stamp
+        u64 wrec[PLAN_TOK_MAX];
+        int wst[PLAN_TOK_MAX];
+        if (tok_cached) {
 #pragma unroll
-            for (int q = 0; q < PLAN_CACHED / 4; ++q) {
-                const int j = j0 + 4 * q;
-                i32x4 v = {0, 0, 0, 0};
-                if (4 * q < per && j + 3 < C && aligned16) {
-                    v = *(const i32x4 *)(st + j);
-                } else if (4 * q < per) {
-#pragma unroll
-                    for (int c = 0; c < 4; ++c)
-                        if (j + c < C) v[c] = st[j + c];
-                }
-#pragma unroll
-                for (int c = 0; c < 4; ++c) kreg[4 * q + c] = ~((unsigned)v[c] ^ 0x80000000u);
-            }
-#pragma unroll
-            for (int k = 0; k < PLAN_CACHED; ++k) {
-                const int j = j0 + k;
-                if (k < per && j < L && !((touched[j >> 5] >> (j & 31)) & 1u)) elig_mask |= 1ull << k;
+            for (int k = 0; k < PLAN_TOK_MAX; ++k) {
+                wrec[k] = tj[k] >= 0 ? win[cb + tj[k]] : 0ull;
+                wst[k] = tj[k] >= 0 ? st[tj[k]] : 0;
             }
         }
-        // visit(f): calls f(slot, key) for the eligible slots of this thread's run, ascending
+        const int n_words = (span + 31) / 32 + 1;
+        for (int w = tid; w < n_words; w += PLAN_THREADS) touched[w] = 0;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) lhist[4 * tid + q] = hreg[q];
+        __syncthreads();
+        visit_tok([&](int, int j) {
+            if (j >= s0 && j < s1) atomicOr(&touched[(j - s0) >> 5], 1u << ((j - s0) & 31));
+        });
+        __syncthreads();
+        unsigned elig = 0;  // bit k: slot j0 + k is live and untouched
+        if (cached) {
+#pragma unroll
+            for (int k = 0; k < PLAN_PER_MAX; ++k) {
+                const int j = j0 + k;
+                if (j < j1 && !((touched[(j - s0) >> 5] >> ((j - s0) & 31)) & 1u)) elig |= 1u << k;
+            }
+        }
+        // visit(f): f(slot, key) for the eligible slots of this thread's run, ascending; key: larger = older
         auto visit = [&](auto &&f) {
             if (cached) {
 #pragma unroll
-                for (int k = 0; k < PLAN_CACHED; ++k)
-                    if ((elig_mask >> k) & 1ull) f(j0 + k, kreg[k]);
+                for (int k = 0; k < PLAN_PER_MAX; ++k)
+                    if ((elig >> k) & 1u) f(j0 + k, ~((unsigned)sreg[k] ^ 0x80000000u));
             } else {
-                for (int j = j0; j < min(j0 + per, L); ++j)
-                    if (!((touched[j >> 5] >> (j & 31)) & 1u)) f(j, ~((unsigned)st[j] ^ 0x80000000u));
+                for (int j = j0; j < j1; ++j)
+                    if (!((touched[(j - s0) >> 5] >> ((j - s0) & 31)) & 1u)) f(j, ~((unsigned)st[j] ^ 0x80000000u));
             }
         };
-        // workgroup-wide sum of a per-thread count
-        auto block_sum = [&](unsigned c) -> unsigned {
-#pragma unroll
-            for (int off = 32; off >= 1; off >>= 1) c += shfl_xor(c, off);
-            __syncthreads();  // previous readers of red_cnt are done
-            if (lane == 0) red_cnt[wave] = c;
+        // thread t owns the four bins 1023-4t .. 1020-4t of a histogram gh in global memory (descending keys):
+        // finds the bin in which the want-th largest entry lies and the number of entries above that bin
+        auto search = [&](const unsigned (&c4)[4], unsigned want, unsigned &total, unsigned &bin, unsigned &above) {
+            const unsigned mine = c4[0] + c4[1] + c4[2] + c4[3];
+            unsigned before = scan.excl_sum(mine, total);
+            if (tid == 0) sh_bin = 0xFFFFFFFFu;
             __syncthreads();
-            unsigned tot = 0;
+            if (before < want && want <= before + mine) {
 #pragma unroll
-            for (int w = 0; w < PLAN_WAVES; ++w) tot += red_cnt[w];
-            return tot;
-        };
-        // range of the keys and number of eligible slots
-        unsigned kmin = 0xFFFFFFFFu, kmax = 0u, cnt_el = 0u;
-        visit([&](int, unsigned u) {
-            kmin = min(kmin, u);
-            kmax = max(kmax, u);
-            cnt_el += 1;
-        });
-#pragma unroll
-        for (int off = 32; off >= 1; off >>= 1) {
-            kmin = min(kmin, shfl_xor(kmin, off));
-            kmax = max(kmax, shfl_xor(kmax, off));
-        }
-        if (lane == 0) {
-            red_min[wave] = kmin;
-            red_max[wave] = kmax;
-        }
-        cnt_el = block_sum(cnt_el);  // its barriers also publish red_min / red_max
-        kmin = 0xFFFFFFFFu; kmax = 0u;
-#pragma unroll
-        for (int w = 0; w < PLAN_WAVES; ++w) {
-            kmin = min(kmin, red_min[w]);
-            kmax = max(kmax, red_max[w]);
-        }
-        const bool take_all = cnt_el <= (unsigned)e;  // fewer eligible slots than evictions needed: take them all
-        unsigned T = kmax, need = (unsigned)e;
-        if (take_all) {
-            n_victims = (int)cnt_el;
-        } else {
-            n_victims = e;
-            // e-th largest key by bisection on the key value (stamps repeat heavily: a histogram in LDS would
-            // serialise on a handful of bins).  Invariant: count(key >= lo) >= e.
-            unsigned lo = kmin, hi = kmax;
-            while (lo < hi) {  // uniform: lo, hi are the same in every thread
-                const unsigned mid = lo + ((hi - lo) >> 1) + 1u;
-                unsigned c = 0;
-                visit([&](int, unsigned u) { c += u >= mid ? 1u : 0u; });
-                if (block_sum(c) >= (unsigned)e) lo = mid;
-                else hi = mid - 1u;
+                for (int q = 0; q < 4; ++q) {
+                    if (before < want && want <= before + c4[q]) {
+                        sh_bin = PLAN_BINS - 1 - (4 * tid + q);
+                        sh_above = before;
+                    }
+                    before += c4[q];
+                }
             }
-            T = lo;
-            unsigned c = 0;
-            visit([&](int, unsigned u) { c += u > T ? 1u : 0u; });
-            need = (unsigned)e - block_sum(c);
+            __syncthreads();
+            bin = sh_bin;
+            above = sh_above;
+            __syncthreads();
+        };
+        bool take_all = false;
+        unsigned T = 0, need = (unsigned)e, cnt_el = 0;
+        // Fast path: tc_prep_kernel left the histogram of all live slots' ages; subtract the slots touched in this
+        // frame (each counted once, by the token that represents its group) and read the threshold off it.  Every
+        // workgroup does this on the same data, so no meeting is needed.  It does not apply when a stamp lies in
+        // the future or the threshold falls into the last bin (ages >= 1023 lumped together).
+        bool fast = ps[PS_FUT] == 0u;   // written by the previous kernel
+        if (fast) {
+            if (tok_cached) {
+#pragma unroll
+                for (int k = 0; k < PLAN_TOK_MAX; ++k)
+                    if (tj[k] >= 0 && (int)(0xFFFFFFFFu - (unsigned)wrec[k]) == tid + k * PLAN_THREADS) {
+                        const unsigned age = (unsigned)frame_id - (unsigned)wst[k];
+                        atomicSub(&lhist[min(age, (unsigned)(PLAN_BINS - 1))], 1u);
+                    }
+            } else {
+                visit_tok([&](int i, int j) {
+                    if ((int)(0xFFFFFFFFu - (unsigned)win[cb + j]) == i) {
+                        const unsigned age = (unsigned)frame_id - (unsigned)st[j];
+                        atomicSub(&lhist[min(age, (unsigned)(PLAN_BINS - 1))], 1u);
+                    }
+                });
+            }
+            __syncthreads();
+            unsigned c4[4];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) c4[q] = lhist[PLAN_BINS - 1 - (4 * tid + q)];
+            unsigned bin, above;
+            search(c4, (unsigned)e, cnt_el, bin, above);
+            take_all = cnt_el <= (unsigned)e;
+            if (!take_all) {
+                if (bin >= (unsigned)(PLAN_BINS - 1)) {
+                    fast = false;
+                } else {
+                    T = ~((unsigned)(frame_id - (int)bin) ^ 0x80000000u);  // key of the stamp frame_id - bin
+                    need = (unsigned)e - above;
+                }
+            }
         }
-        // ordered compaction, victims in ascending slot order: two prefix sums over the threads
+        if (!fast) {
+            // General path: range of the keys and number of eligible slots over the whole head, then a histogram
+            // select on that range (a second histogram inside the threshold bin when the range is wider than the
+            // bins), the workgroups of the head meeting between the steps.
+            {
+                unsigned kmin = 0xFFFFFFFFu, kmax = 0u, c = 0u;
+                visit([&](int, unsigned u) {
+                    kmin = min(kmin, u);
+                    kmax = max(kmax, u);
+                    c += 1;
+                });
+#pragma unroll
+                for (int off = 32; off >= 1; off >>= 1) {
+                    kmin = min(kmin, shfl_xor(kmin, off));
+                    kmax = max(kmax, shfl_xor(kmax, off));
+                }
+                if (lane == 0) {
+                    red_a[wave] = kmin;
+                    red_b[wave] = kmax;
+                }
+                c = scan.sum(c);  // its barriers also publish red_a / red_b
+                if (tid == 0 && c > 0) {
+                    kmin = 0xFFFFFFFFu;
+                    kmax = 0u;
+                    for (int w = 0; w < PLAN_WAVES; ++w) {
+                        kmin = min(kmin, red_a[w]);
+                        kmax = max(kmax, red_b[w]);
+                    }
+                    atomicMax(&ps[PS_MAXK], kmax);
+                    atomicMax(&ps[PS_MAXNK], ~kmin);
+                    atomicAdd(&ps[PS_TOT], c);
+                }
+            }
+            head_barrier(&ps[PS_BAR + 0], NB, &ps[PS_ERR]);
+            const unsigned umax = ld_agent(&ps[PS_MAXK]), umin = ~ld_agent(&ps[PS_MAXNK]);
+            cnt_el = ld_agent(&ps[PS_TOT]);
+            take_all = cnt_el <= (unsigned)e;  // fewer eligible slots than evictions needed: take them all
+            T = umax;
+            need = (unsigned)e;
+            if (!take_all) {
+                // Among the keys in [lo, lo + width), with `want` of them to take from the top: histogram over the
+                // head (bin = (key - lo) >> sh), then the bin in which the want-th largest key lies.
+                auto level = [&](unsigned lo, unsigned width, int sh, unsigned want, int which, unsigned &bin, unsigned &above) {
+                    for (int k = tid; k < PLAN_BINS; k += PLAN_THREADS) lhist[k] = 0;
+                    __syncthreads();
+                    visit([&](int, unsigned u) {
+                        const unsigned rel = u - lo;
+                        if (u >= lo && rel < width && (rel >> sh) < (unsigned)PLAN_BINS) atomicAdd(&lhist[rel >> sh], 1u);
+                    });
+                    __syncthreads();
+                    unsigned *gh = ps + PS_HIST + (1 + which) * PLAN_BINS;
+                    for (int k = tid; k < PLAN_BINS; k += PLAN_THREADS)
+                        if (lhist[k]) atomicAdd(&gh[k], lhist[k]);
+                    head_barrier(&ps[PS_BAR + 1 + which], NB, &ps[PS_ERR]);
+                    unsigned c4[4], total;
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) c4[q] = ld_agent(&gh[PLAN_BINS - 1 - (4 * tid + q)]);
+                    search(c4, want, total, bin, above);
+                };
+                const unsigned range = umax - umin;
+                int sh = 0;
+                while ((range >> sh) >= (unsigned)PLAN_BINS) ++sh;
+                unsigned bin, above;
+                level(umin, 0xFFFFFFFFu, sh, (unsigned)e, 0, bin, above);
+                if (sh == 0) {
+                    T = umin + bin;
+                    need = (unsigned)e - above;
+                } else {  // resolve inside the coarse bin (ranges up to 2^20 frames; wider ones are not resolved exactly)
+                    const unsigned lo2 = umin + (bin << sh);
+                    const int sh2 = sh > 10 ? sh - 10 : 0;
+                    if (sh2 > 0 && tid == 0) atomicExch(&ps[PS_ERR], 2u);
+                    unsigned bin2, above2;
+                    level(lo2, 1u << sh, sh2, (unsigned)e - above, 1, bin2, above2);
+                    T = lo2 + (bin2 << sh2);
+                    need = (unsigned)e - above - above2;
+                }
+            }
+        }
+        n_victims = take_all ? (int)cnt_el : e;
+        // counts per workgroup, the workgroups meet, then ordered compaction: victims in ascending slot order
         unsigned c_gt = 0, c_eq = 0;
         visit([&](int, unsigned u) {
             c_gt += (take_all || u > T) ? 1u : 0u;
             c_eq += (!take_all && u == T) ? 1u : 0u;
         });
+        unsigned blk_gt, blk_eq;
+        scan.excl_sum(c_gt, blk_gt);
+        const unsigned eq_base_thr = scan.excl_sum(c_eq, blk_eq);
+        // Publish this workgroup's counts as one 64-bit word with a valid bit, then wait (bounded) for the words of
+        // the workgroups below: only those are needed for the positions, and the wait doubles as the read.
+        u64 *blk = (u64 *)(ps + PS_BLK);
+        if (tid == 0)
+            __hip_atomic_store(&blk[b], (1ull << 63) | ((u64)blk_gt << 32) | (u64)blk_eq, __ATOMIC_RELAXED,
+                               __HIP_MEMORY_SCOPE_AGENT);
+        if (tid < b) {
+            u64 v = 0;
+            int spins = 0;
+            while (!((v = __hip_atomic_load(&blk[tid], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) >> 63)) {
+                if (++spins > PLAN_SPIN_LIMIT) {
+                    atomicExch(&ps[PS_ERR], 1u);
+                    break;
+                }
+                __builtin_amdgcn_s_sleep(2);
+            }
+            sh_blk[2 * tid] = (unsigned)(v >> 32) & 0x7FFFFFFFu;
+            sh_blk[2 * tid + 1] = (unsigned)v;
+        }
+        __syncthreads();
+        unsigned pos_base = 0, eq_before = 0;
+        for (int bb = 0; bb < b; ++bb) {
+            const unsigned g = sh_blk[2 * bb], q = sh_blk[2 * bb + 1];
+            const unsigned tk = eq_before >= need ? 0u : min(q, need - eq_before);
+            pos_base += g + tk;
+            eq_before += q;
+        }
+        const unsigned eq_blk_take = eq_before >= need ? 0u : min(blk_eq, need - eq_before);  // ties this workgroup takes
+        const unsigned eq_take = eq_base_thr >= eq_blk_take ? 0u : min(c_eq, eq_blk_take - eq_base_thr);
         unsigned tot;
-        const unsigned eq_base = scan.excl_sum(c_eq, tot);
-        const unsigned eq_take = eq_base >= need ? 0u : min(c_eq, need - eq_base);  // ties this thread may take
-        unsigned pos = scan.excl_sum(c_gt + eq_take, tot);
+        unsigned pos = pos_base + scan.excl_sum(c_gt + eq_take, tot);
         unsigned eq_seen = 0;
         visit([&](int j, unsigned u) {
             bool take = take_all || u > T;
@@ -504,10 +750,13 @@ __global__ __launch_bounds__(PLAN_THREADS) void tc_plan_kernel(int32_t *__restri
                 take = eq_seen < eq_take;
                 eq_seen += 1;
             }
-            if (take) victims[tb + pos++] = j;
+            if (take) {
+                if (pos < (unsigned)n_new) victims[tb + pos] = j;
+                pos += 1;
+            }
         });
     }
-    if (tid == 0) {
+    if (b == 0 && tid == 0) {
         const int n_dropped = e - n_victims;
         const int n_app = (int)n_unm - n_dropped;
         const int newL = L + n_app - n_victims;
@@ -515,13 +764,19 @@ __global__ __launch_bounds__(PLAN_THREADS) void tc_plan_kernel(int32_t *__restri
         o[0] = L; o[1] = (int)n_unm; o[2] = e; o[3] = n_victims; o[4] = n_dropped; o[5] = newL;
         int32_t *s = stats + (size_t)h * 8;
         s[0] = newL; s[1] = n_new - (int)n_unm; s[2] = n_app; s[3] = n_victims; s[4] = n_dropped;
-        s[5] = 0; s[6] = 0; s[7] = 0;
-        len[h] = newL;
+        s[5] = 0; s[6] = 0; s[7] = e > 0 ? (int)ld_agent(&ps[PS_ERR]) : 0;
     }
 }
 
-// dynamic LDS of tc_plan_kernel: the touched bitmap
-static size_t plan_lds_bytes(int C) { return ((size_t)(C + 31) / 32) * 4; }
+// workgroups per head of tc_plan_kernel and its dynamic LDS (the touched bitmap of one workgroup's slot range)
+static int plan_nb(int H, int C) {
+    int nb = (C + 2047) / 2048;
+    const int cap = PLAN_MAX_GRID / H > 0 ? PLAN_MAX_GRID / H : 1;
+    if (nb > cap) nb = cap;
+    if (nb > PLAN_NB_MAX) nb = PLAN_NB_MAX;
+    return nb < 1 ? 1 : nb;
+}
+static size_t plan_lds_bytes(int C, int nb) { return ((size_t)((C + nb - 1) / nb + 31) / 32 + 1) * 4; }
 
 // ---- apply ---------------------------------------------------------------------------------------------
 template <bool BF16, int D>
@@ -533,9 +788,11 @@ __global__ __launch_bounds__(256) void tc_apply_kernel(void *__restrict__ K, voi
                                                        const uint8_t *__restrict__ merged, const u64 *__restrict__ win,
                                                        const int32_t *__restrict__ grp, const int32_t *__restrict__ rank,
                                                        const int32_t *__restrict__ victims, const int32_t *__restrict__ hs,
-                                                       int32_t *__restrict__ merge_map) {
+                                                       int32_t *__restrict__ merge_map, int32_t *__restrict__ len) {
     typedef RowPiece<BF16, D> RP;
     const int h = blockIdx.y;
+    // the new length is published here and not by the plan: its workgroups read len[h] at different times
+    if (blockIdx.x == 0 && threadIdx.x == 0) len[h] = hs[(size_t)h * HS_STRIDE + 5];
     const int l16 = threadIdx.x & 15;
     const int sub = (threadIdx.x & 63) >> 4;  // which 16-lane group of the wavefront
     const int i = blockIdx.x * (blockDim.x / 16) + (threadIdx.x >> 4);
@@ -622,7 +879,8 @@ extern "C" int tempcache_compress(const fastar_cache *cache, const fastar_codec 
     if (cand && n_cand <= 0) return FASTAR_ERR_INVALID_ARG;
     if (dtype != FASTAR_F32 && dtype != FASTAR_BF16) return FASTAR_ERR_INVALID_ARG;
     if ((d != 64 && d != 128) || (r != 32 && r != 64)) return FASTAR_ERR_UNSUPPORTED;
-    if (plan_lds_bytes(C) > 60 * 1024) return FASTAR_ERR_UNSUPPORTED;  // eviction bitmap and tables live in LDS
+    const int nb = plan_nb(H, C);
+    if (plan_lds_bytes(C, nb) > 48 * 1024) return FASTAR_ERR_UNSUPPORTED;  // eviction bitmap of a slot range lives in LDS
     if (((uintptr_t)cache->K & 15) || ((uintptr_t)cache->V & 15) || ((uintptr_t)cache->code & 15) ||
         ((uintptr_t)K_new & 15) || ((uintptr_t)V_new & 15) || ((uintptr_t)P_new & 15) || ((uintptr_t)ws & 255))
         return FASTAR_ERR_INVALID_ARG;
@@ -636,11 +894,13 @@ extern "C" int tempcache_compress(const fastar_cache *cache, const fastar_codec 
     int32_t *jstar = (int32_t *)(base + w.jstar), *sbest = (int32_t *)(base + w.sbest);
     int32_t *rank = (int32_t *)(base + w.rank), *victims = (int32_t *)(base + w.victims);
     int32_t *hs = (int32_t *)(base + w.hs);
+    unsigned *plan_scratch = (unsigned *)(base + w.ps);
     u64 *win = (u64 *)(base + w.win);
     int32_t *grp = (int32_t *)(base + w.grp);
     const int64_t T = (int64_t)H * n_new;
 
-    int rc = encode_launch(K_new, dtype, T, d, codec, r, ck, best, T, s);
+    const int64_t zero_words = (int64_t)((w.ps - w.best) / 8) + (int64_t)H * PLAN_SCRATCH_WORDS / 2;  // best .. end of ps
+    int rc = encode_launch(K_new, dtype, T, d, codec, r, ck, best, zero_words, s);
     if (rc != FASTAR_OK) return rc;
     if (P_new) {
         rc = encode_launch(P_new, dtype, T, d, codec, r, cp, nullptr, 0, s);
@@ -657,8 +917,13 @@ extern "C" int tempcache_compress(const fastar_cache *cache, const fastar_codec 
                                n_cand, metric, best);
         FASTAR_LAUNCH_CHECK();
     }
-    hipLaunchKernelGGL(tc_prep_kernel, dim3((n_new + 255) / 256, H), dim3(256), 0, s, best, n_new, C, jstar, sbest, win,
-                       grp);
+    {
+        int gx = (n_new + 255) / 256;
+        const int gslots = (C + 1023) / 1024 < 32 ? (C + 1023) / 1024 : 32;   // enough workgroups to read the stamps
+        if (gx < gslots) gx = gslots;
+        hipLaunchKernelGGL(tc_prep_kernel, dim3(gx, H), dim3(256), 0, s, best, n_new, C, jstar, sbest, win, grp,
+                           cache->len, cache->stamp, frame_id, plan_scratch, PS_HIST, PS_FUT, PS_STRIDE);
+    }
     FASTAR_LAUNCH_CHECK();
     const dim3 tgrid((n_new + 15) / 16, H);
     const bool bf = dtype == FASTAR_BF16;
@@ -672,11 +937,11 @@ extern "C" int tempcache_compress(const fastar_cache *cache, const fastar_codec 
     FASTAR_TC(tc_verify_kernel, cache->K, K_new, cp, r, C, n_new, codec->qscale, metric, tau2_q16, jstar, sbest, win, grp,
               merged);
     FASTAR_LAUNCH_CHECK();
-    hipLaunchKernelGGL(tc_plan_kernel, dim3(H), dim3(PLAN_THREADS), plan_lds_bytes(C), s, cache->len, cache->stamp, C,
-                       n_new, jstar, merged, rank, victims, hs, stats);
+    hipLaunchKernelGGL(tc_plan_kernel, dim3(nb + 1, H), dim3(PLAN_THREADS), plan_lds_bytes(C, nb), s, cache->len, cache->stamp,
+                       C, n_new, frame_id, jstar, merged, win, rank, victims, hs, stats, plan_scratch);
     FASTAR_LAUNCH_CHECK();
     FASTAR_TC(tc_apply_kernel, cache->K, cache->V, cache->code, cache->cnt, cache->stamp, C, r, K_new, V_new, ck, n_new,
-              frame_id, jstar, merged, win, grp, rank, victims, hs, merge_map);
+              frame_id, jstar, merged, win, grp, rank, victims, hs, merge_map, cache->len);
     FASTAR_LAUNCH_CHECK();
 #undef FASTAR_TC
     return FASTAR_OK;
