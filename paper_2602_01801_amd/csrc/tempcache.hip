@@ -20,7 +20,6 @@ namespace fastar {
 int encode_launch(const void *x, int dtype, int64_t n_vec, int d, const fastar_codec *codec, int r, int8_t *code,
                   unsigned long long *zero_fill, int64_t zero_n, hipStream_t s);
 
-constexpr int CAND_CHUNK = 256;          // candidate positions scanned by one workgroup of tc_match
 constexpr int SCORE_BIAS = 1 << 23;      // makes every score positive inside the packed arg-max key
 constexpr int PLAN_SCRATCH_WORDS = 64 + 3 * 1024;  // per-head scratch of tc_plan_kernel (PS_STRIDE)
 constexpr int HS_STRIDE = 8;             // per-head scalars: oldL, n_unmerged, e, n_victims, n_dropped, newL
@@ -59,7 +58,9 @@ size_t compress_ws_bytes(int H, int C, int n_new, int r) {
 // D = A x B: A rows = 32 candidate slots (codes gathered by slot id), B columns = 32 tokens (probe codes).
 // A lane therefore sees 16 candidates of one token per matrix instruction and keeps the best
 // (score, lowest slot) as one 64-bit key: (score + bias) << 32 | ~slot.
-template <int R>
+// CAND_CHUNK = candidate positions scanned by one workgroup: 64 for a windowed candidate list (more, lighter
+// workgroups hide the two dependent loads better), 256 for a scan of the whole cache (fewer atomics per token).
+template <int R, int CAND_CHUNK>
 __global__ __launch_bounds__(256) void tc_match_kernel(const int8_t *__restrict__ code, const int32_t *__restrict__ len,
                                                        int C, const int8_t *__restrict__ cp, int n_new,
                                                        const int32_t *__restrict__ cand, int n_cand, int metric,
@@ -908,13 +909,16 @@ extern "C" int tempcache_compress(const fastar_cache *cache, const fastar_codec 
     }
     {
         const int n_pos_cap = cand ? n_cand : C;
-        dim3 grid((n_new + 127) / 128, (n_pos_cap + CAND_CHUNK - 1) / CAND_CHUNK, H);
-        if (r == 32)
-            hipLaunchKernelGGL(tc_match_kernel<32>, grid, dim3(256), 0, s, cache->code, cache->len, C, cp, n_new, cand,
-                               n_cand, metric, best);
-        else
-            hipLaunchKernelGGL(tc_match_kernel<64>, grid, dim3(256), 0, s, cache->code, cache->len, C, cp, n_new, cand,
-                               n_cand, metric, best);
+        const int chunk = n_pos_cap <= 4096 ? 64 : 256;
+        dim3 grid((n_new + 127) / 128, (n_pos_cap + chunk - 1) / chunk, H);
+#define FASTAR_MATCH(RR, CH)                                                                                    \
+    hipLaunchKernelGGL((tc_match_kernel<RR, CH>), grid, dim3(256), 0, s, cache->code, cache->len, C, cp, n_new, cand, \
+                       n_cand, metric, best)
+        if (r == 32 && chunk == 64) FASTAR_MATCH(32, 64);
+        else if (r == 32) FASTAR_MATCH(32, 256);
+        else if (chunk == 64) FASTAR_MATCH(64, 64);
+        else FASTAR_MATCH(64, 256);
+#undef FASTAR_MATCH
         FASTAR_LAUNCH_CHECK();
     }
     {
