@@ -13,7 +13,7 @@
 
 namespace fastar {
 
-constexpr int KB_PER_WG = 16;      // key blocks scored by one workgroup of score_self_kernel
+constexpr int KB_PER_WG = 4;      // key blocks scored by one workgroup of score_self_kernel
 constexpr int COL_CHUNK = 8;       // summary column blocks (of 32) kept in registers at a time
 constexpr int TOPK_LDS_CAP = 8192; // row entries cached in LDS by topk_kernel
 
@@ -75,32 +75,49 @@ __global__ __launch_bounds__(256) void score_self_kernel(const int8_t *__restric
             int best[COL_CHUNK];
 #pragma unroll
             for (int c = 0; c < COL_CHUNK; ++c) best[c] = INT_MIN;
-            for (int sg = 0; sg < BK; sg += 32) {
-                const int kbase = kb * BK + sg;
-                if (kbase >= L) break;
-                const int krow = min(kbase + col, C - 1);
-                i32x4 afrag[KS];
+            // two groups of 32 keys per round: both loads are issued before the first product waits
+            for (int sg0 = 0; sg0 < BK; sg0 += 64) {
+                if (kb * BK + sg0 >= L) break;
+                i32x4 afrag[2][KS];
+                bool have[2], partial[2];
 #pragma unroll
-                for (int ks = 0; ks < KS; ++ks) afrag[ks] = *(const i32x4 *)(kc + (size_t)krow * R + ks * 32 + 16 * g2);
-                const bool partial = kbase + 32 > L || sg + 32 > BK;
+                for (int q = 0; q < 2; ++q) {
+                    const int sg = sg0 + 32 * q;
+                    const int kbase = kb * BK + sg;
+                    have[q] = sg < BK && kbase < L;
+                    partial[q] = kbase + 32 > L || sg + 32 > BK;
+                    const int krow = min(kbase + col, C - 1);
 #pragma unroll
-                for (int c = 0; c < COL_CHUNK; ++c) {
-                    if (cb0 + c < NCB) {
-                        i32x16 acc = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+                    for (int ks = 0; ks < KS; ++ks) {
+                        i32x4 a = {0, 0, 0, 0};
+                        if (have[q]) a = *(const i32x4 *)(kc + (size_t)krow * R + ks * 32 + 16 * g2);
+                        afrag[q][ks] = a;
+                    }
+                }
 #pragma unroll
-                        for (int ks = 0; ks < KS; ++ks) acc = mfma_i8_32x32x32(afrag[ks], bfrag[c][ks], acc);
-                        int m = best[c];
-                        if (partial) {
+                for (int q = 0; q < 2; ++q) {
+                    if (!have[q]) continue;   // uniform
+                    const int sg = sg0 + 32 * q;
+                    const int kbase = kb * BK + sg;
 #pragma unroll
-                            for (int v = 0; v < 16; ++v) {
-                                const int kloc = 8 * (v >> 2) + 4 * g2 + (v & 3);
-                                if (kbase + kloc < L && sg + kloc < BK) m = max(m, acc[v]);
+                    for (int c = 0; c < COL_CHUNK; ++c) {
+                        if (cb0 + c < NCB) {
+                            i32x16 acc = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+#pragma unroll
+                            for (int ks = 0; ks < KS; ++ks) acc = mfma_i8_32x32x32(afrag[q][ks], bfrag[c][ks], acc);
+                            int m = best[c];
+                            if (partial[q]) {
+#pragma unroll
+                                for (int v = 0; v < 16; ++v) {
+                                    const int kloc = 8 * (v >> 2) + 4 * g2 + (v & 3);
+                                    if (kbase + kloc < L && sg + kloc < BK) m = max(m, acc[v]);
+                                }
+                            } else {
+#pragma unroll
+                                for (int v = 0; v < 16; ++v) m = max(m, acc[v]);
                             }
-                        } else {
-#pragma unroll
-                            for (int v = 0; v < 16; ++v) m = max(m, acc[v]);
+                            best[c] = m;
                         }
-                        best[c] = m;
                     }
                 }
             }
