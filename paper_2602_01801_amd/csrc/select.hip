@@ -5,8 +5,9 @@
 //   score_*_kernel      int8 matrix-core scoring of summaries x key codes, reduced on the fly to one
 //                       int32 per (query block, key block) [AnnSA] or per (query block, prompt token)
 //                       [AnnCA]; HBM-bound: every key code is streamed exactly once
-//   topk_kernel         exact top-n_sel per row by radix select, ties to the lowest index, written in
-//                       ascending order by ballot + prefix-sum compaction
+//   topk                exact top-n_sel per row by radix select, ties to the lowest index, written in
+//                       ascending order by ballot + prefix-sum compaction (a kernel of its own for AnnSA,
+//                       the tail of the scoring kernel for AnnCA, where one workgroup owns a whole row)
 #include <limits.h>
 
 #include "common.hpp"
@@ -142,82 +143,27 @@ __global__ __launch_bounds__(256) void score_self_kernel(const int8_t *__restric
     }
 }
 
-// ---- AnnCA scoring -----------------------------------------------------------------------------------
-// out[h][b][p] = max over the queries q of block b of qcode[q] . pcode[p].
-// D = A x B with A rows = 32 queries, B columns = 32 prompt tokens.
-template <int R>
-__global__ __launch_bounds__(256) void score_cross_kernel(const int8_t *__restrict__ qcode, const int8_t *__restrict__ pcode,
-                                                          int n_q, int n_p, int BQ, int n_qb,
-                                                          int32_t *__restrict__ out) {
-    constexpr int KS = R / 32;
-    extern __shared__ int32_t smax[];  // [n_p]
-    const int b = blockIdx.x, h = blockIdx.y;
-    const int lane = lane_id(), wave = threadIdx.x >> 6;
-    const int col = lane & 31, g2 = lane >> 5;
-    for (int t = threadIdx.x; t < n_p; t += blockDim.x) smax[t] = INT_MIN;
-    __syncthreads();
-    const int q_end = min((b + 1) * BQ, n_q);
-    const int8_t *qc = qcode + (size_t)h * n_q * R;
-    const int8_t *pc = pcode + (size_t)h * n_p * R;
-    for (int qg = b * BQ + wave * 32; qg < q_end; qg += 4 * 32) {
-        const int qrow = min(qg + col, n_q - 1);
-        i32x4 afrag[KS];
-#pragma unroll
-        for (int ks = 0; ks < KS; ++ks) afrag[ks] = *(const i32x4 *)(qc + (size_t)qrow * R + ks * 32 + 16 * g2);
-        const bool partial = qg + 32 > q_end;
-        for (int p0 = 0; p0 < n_p; p0 += 32) {
-            const int prow = min(p0 + col, n_p - 1);
-            i32x16 acc = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
-#pragma unroll
-            for (int ks = 0; ks < KS; ++ks) {
-                i32x4 bfrag = *(const i32x4 *)(pc + (size_t)prow * R + ks * 32 + 16 * g2);
-                acc = mfma_i8_32x32x32(afrag[ks], bfrag, acc);
-            }
-            int m = INT_MIN;
-            if (partial) {
-#pragma unroll
-                for (int v = 0; v < 16; ++v)
-                    if (qg + 8 * (v >> 2) + 4 * g2 + (v & 3) < q_end) m = max(m, acc[v]);
-            } else {
-#pragma unroll
-                for (int v = 0; v < 16; ++v) m = max(m, acc[v]);
-            }
-            m = max(m, shfl_xor(m, 32));
-            if (g2 == 0 && p0 + col < n_p) atomicMax(&smax[p0 + col], m);
-        }
-    }
-    __syncthreads();
-    for (int t = threadIdx.x; t < n_p; t += blockDim.x) out[((size_t)h * n_qb + b) * n_p + t] = smax[t];
-}
-
 // ---- exact top-k per row ----------------------------------------------------------------------------
-// Row (h, b) of `score` holds n entries (n = ceil(len[h]/BK) when len is given, else n_fixed).  The
-// k = min(n_sel, n) largest are selected (ties: lowest index) and their indices written ascending to
-// sel[h][b][0..k), the rest of the row padded with -1; nsel[h][b] = k.
-__global__ __launch_bounds__(256) void topk_kernel(const int32_t *__restrict__ score, int row_stride,
-                                                   const int32_t *__restrict__ len, int len_cap, int BK, int n_fixed,
-                                                   int n_qb, int n_sel, int32_t *__restrict__ sel,
-                                                   int32_t *__restrict__ nsel) {
-    __shared__ unsigned keys[TOPK_LDS_CAP];
+// A row of n scores (row may point to global memory or to LDS).  The k = min(n_sel, n) largest are selected
+// (ties: lowest index) and their indices written ascending to out[0..k), the rest of out[0..n_sel) padded with
+// -1; *nsel_out = k.  Called by all 256 threads of a workgroup.
+// keys: LDS staging for up to TOPK_LDS_CAP entries of a row in global memory, or nullptr (row read in place).
+__device__ __forceinline__ void topk_row(const int32_t *row, int n, int n_sel, int32_t *__restrict__ out,
+                                         int32_t *__restrict__ nsel_out, unsigned *keys) {
     __shared__ unsigned hist[256];
     __shared__ unsigned sh_bin, sh_remaining;
     __shared__ unsigned wtot_a[4], wtot_b[4];
-    const int b = blockIdx.x, h = blockIdx.y, tid = threadIdx.x;
+    const int tid = threadIdx.x;
     const int lane = lane_id(), wave = tid >> 6;
-    int n = n_fixed;
-    if (len) n = (min(len[h], len_cap) + BK - 1) / BK;
-    n = min(n, row_stride);
     const int k = min(n_sel, n);
-    const int32_t *row = score + ((size_t)h * n_qb + b) * row_stride;
-    int32_t *out = sel + ((size_t)h * n_qb + b) * n_sel;
-    if (tid == 0) nsel[(size_t)h * n_qb + b] = k;
+    if (tid == 0) *nsel_out = k;
     for (int t = k + tid; t < n_sel; t += 256) out[t] = -1;
     if (k == 0) return;
     if (k == n) {  // budget covers the row: everything, ascending
         for (int t = tid; t < n; t += 256) out[t] = t;
         return;
     }
-    const bool cached = n <= TOPK_LDS_CAP;
+    const bool cached = keys != nullptr && n <= TOPK_LDS_CAP;
     if (cached)
         for (int t = tid; t < n; t += 256) keys[t] = (unsigned)row[t] ^ 0x80000000u;
     auto key_at = [&](int i) -> unsigned { return cached ? keys[i] : ((unsigned)row[i] ^ 0x80000000u); };
@@ -302,6 +248,70 @@ __global__ __launch_bounds__(256) void topk_kernel(const int32_t *__restrict__ s
     }
 }
 
+
+// ---- AnnCA scoring -----------------------------------------------------------------------------------
+// score[p] = max over the queries q of block b of qcode[q] . pcode[p], kept in LDS, then the top n_sel of the row.
+// D = A x B with A rows = 32 queries, B columns = 32 prompt tokens.
+template <int R>
+__global__ __launch_bounds__(256) void score_cross_kernel(const int8_t *__restrict__ qcode, const int8_t *__restrict__ pcode,
+                                                          int n_q, int n_p, int BQ, int n_qb, int n_sel,
+                                                          int32_t *__restrict__ sel, int32_t *__restrict__ nsel) {
+    constexpr int KS = R / 32;
+    extern __shared__ int32_t smax[];  // [n_p]
+    const int b = blockIdx.x, h = blockIdx.y;
+    const int lane = lane_id(), wave = threadIdx.x >> 6;
+    const int col = lane & 31, g2 = lane >> 5;
+    for (int t = threadIdx.x; t < n_p; t += blockDim.x) smax[t] = INT_MIN;
+    __syncthreads();
+    const int q_end = min((b + 1) * BQ, n_q);
+    const int8_t *qc = qcode + (size_t)h * n_q * R;
+    const int8_t *pc = pcode + (size_t)h * n_p * R;
+    for (int qg = b * BQ + wave * 32; qg < q_end; qg += 4 * 32) {
+        const int qrow = min(qg + col, n_q - 1);
+        i32x4 afrag[KS];
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) afrag[ks] = *(const i32x4 *)(qc + (size_t)qrow * R + ks * 32 + 16 * g2);
+        const bool partial = qg + 32 > q_end;
+        for (int p0 = 0; p0 < n_p; p0 += 32) {
+            const int prow = min(p0 + col, n_p - 1);
+            i32x16 acc = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) {
+                i32x4 bfrag = *(const i32x4 *)(pc + (size_t)prow * R + ks * 32 + 16 * g2);
+                acc = mfma_i8_32x32x32(afrag[ks], bfrag, acc);
+            }
+            int m = INT_MIN;
+            if (partial) {
+#pragma unroll
+                for (int v = 0; v < 16; ++v)
+                    if (qg + 8 * (v >> 2) + 4 * g2 + (v & 3) < q_end) m = max(m, acc[v]);
+            } else {
+#pragma unroll
+                for (int v = 0; v < 16; ++v) m = max(m, acc[v]);
+            }
+            m = max(m, shfl_xor(m, 32));
+            if (g2 == 0 && p0 + col < n_p) atomicMax(&smax[p0 + col], m);
+        }
+    }
+    __syncthreads();
+    // the workgroup owns the whole row: select from LDS right away
+    topk_row(smax, n_p, n_sel, sel + ((size_t)h * n_qb + b) * n_sel, nsel + (size_t)h * n_qb + b, nullptr);
+}
+
+// Row (h, b) of `score` holds n entries (n = ceil(len[h]/BK) when len is given, else n_fixed).
+__global__ __launch_bounds__(256) void topk_kernel(const int32_t *__restrict__ score, int row_stride,
+                                                   const int32_t *__restrict__ len, int len_cap, int BK, int n_fixed,
+                                                   int n_qb, int n_sel, int32_t *__restrict__ sel,
+                                                   int32_t *__restrict__ nsel) {
+    __shared__ unsigned keys[TOPK_LDS_CAP];
+    const int b = blockIdx.x, h = blockIdx.y;
+    int n = n_fixed;
+    if (len) n = (min(len[h], len_cap) + BK - 1) / BK;
+    n = min(n, row_stride);
+    topk_row(score + ((size_t)h * n_qb + b) * row_stride, n, n_sel, sel + ((size_t)h * n_qb + b) * n_sel,
+             nsel + (size_t)h * n_qb + b, keys);
+}
+
 static bool pow2_le32(int v) { return v >= 1 && v <= 32 && (v & (v - 1)) == 0; }
 
 struct SelfWs {
@@ -373,17 +383,13 @@ extern "C" int ann_select_cross(const int8_t *qcode, int n_q, const int8_t *pcod
     const int n_qb = (n_q + BQ - 1) / BQ;
     if (ws_bytes < select_cross_ws_bytes(H, n_q, n_p, BQ)) return FASTAR_ERR_WORKSPACE;
     hipStream_t s = (hipStream_t)stream;
-    int32_t *score = (int32_t *)ws;
     const size_t lds = (size_t)n_p * sizeof(int32_t);
     if (r == 32)
         hipLaunchKernelGGL(score_cross_kernel<32>, dim3(n_qb, H), dim3(256), lds, s, qcode, pcode, n_q, n_p, BQ, n_qb,
-                           score);
+                           n_sel, sel, nsel);
     else
         hipLaunchKernelGGL(score_cross_kernel<64>, dim3(n_qb, H), dim3(256), lds, s, qcode, pcode, n_q, n_p, BQ, n_qb,
-                           score);
-    FASTAR_LAUNCH_CHECK();
-    hipLaunchKernelGGL(topk_kernel, dim3(n_qb, H), dim3(256), 0, s, score, n_p, (const int32_t *)nullptr, 0, 1, n_p,
-                       n_qb, n_sel, sel, nsel);
+                           n_sel, sel, nsel);
     FASTAR_LAUNCH_CHECK();
     return FASTAR_OK;
 }
