@@ -298,6 +298,7 @@ __global__ __launch_bounds__(2 * NWG * 64, 1) void attn_bf16_d128_pp_kernel(
     float mx_tile = -INFINITY;   // per query: maximum of S(t) over the tile, handed from X(t) to Y(t)
     auto phase_x = [&](int t, auto pv_c, auto qk_c) __attribute__((always_inline)) {
         constexpr bool PV = decltype(pv_c)::value, QK = decltype(qk_c)::value;
+        __builtin_amdgcn_s_setprio(2);   // the wavefront feeding the matrix cores goes first on its SIMD
         s16x4 vb[2][D / 32][2];
         bf16x8 ka[D / 16], kb2[D / 16];
         if constexpr (PV) read_vt<32 * ROWB>(vb, vaddr);     // V(t-1), keys 32..63 (keys 0..31 are in va)
@@ -329,6 +330,7 @@ __global__ __launch_bounds__(2 * NWG * 64, 1) void attn_bf16_d128_pp_kernel(
             // all of it exists before the barrier: pure arithmetic would otherwise be free to sink past it
             asm volatile("" : "+v"(s_acc[0]), "+v"(s_acc[1]), "+v"(mx_tile));
         }
+        __builtin_amdgcn_s_setprio(0);
     };
     // Y(t), t = 0 .. nt-1: everything that is not a matrix instruction.  Row table of tile t+3; loads of K(t+2) and
     // V(t+1) into the stages X(t) has just consumed; P(t) = exp2(scale * (S(t) - m_ref)) as bf16 operands and the
