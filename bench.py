@@ -218,7 +218,7 @@ def profiled_traffic_bytes():
     path = os.path.join(ROOT, "profiles", "cfg2_chunk_step_hbm_traffic.txt")
     try:
         for line in open(path):
-            if "attn_bf16_d128_kernel<4> [large]" in line and not line.startswith("#"):
+            if "attn_bf16_d128_pp_kernel<4> [large]" in line and not line.startswith("#"):
                 f = line.split()
                 return (float(f[-2]) + float(f[-1])) * 1e6
     except OSError:
