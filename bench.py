@@ -212,6 +212,13 @@ def cpu_baseline(cfg, pipe, prefill_host, chunks, ps, n_heads, to_host):
     return info
 
 
+def attn_kernel_name(n_items):
+    """Which bf16 d = 128, BQ = 128 kernel sparse_attn_fwd launches for this many (head, query block) pairs."""
+    if n_items <= 512 or n_items % 512 == 0 or n_items % 512 >= 256:
+        return "attn_bf16_d128_pp_kernel<4>"
+    return "attn_bf16_d128_kernel<4>"
+
+
 def profiled_traffic_bytes():
     """HBM bytes per launch of the self-attention kernel as recorded in profiles/ (rocprofv3 FETCH_SIZE +
     WRITE_SIZE, scaled by a copy of known size), or None when the summary is absent."""
@@ -326,7 +333,7 @@ def main():
                    "cache_bytes": pipe.cache.nbytes()},
         "stages_ms": {k: round(v, 4) for k, v in stage_ms.items()},
         "effective_tflops": round(tflops, 2), "pct_mfma_peak": round(100 * tflops / PEAK_BF16_TFLOPS, 2),
-        "roofline": {"kernel": "attn_bf16_d128_pp_kernel<4> (block-sparse self-attention)", "bound": "mfma",
+        "roofline": {"kernel": attn_kernel_name(cfg["H"] * pipe.n_qb) + " (block-sparse self-attention)", "bound": "mfma",
                      "achieved": round(tflops, 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                      "frac": round(tflops / PEAK_BF16_TFLOPS, 4),
                      "traffic": profiled_traffic_bytes() if args.workload == "cfg2" else None,

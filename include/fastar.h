@@ -118,7 +118,10 @@ int fastar_encode(const void *x, int dtype, int64_t n_vec, int d, const fastar_c
  * Outputs:
  *   merge_map [H,n_new] int32  destination slot of each token, -1 if dropped
  *   merged    [H,n_new] uint8  1 if the token joined an existing slot
- *   stats     [H,8]     int32  {len after, n_merged, n_appended, n_evicted, n_dropped, 0, 0, 0}
+ *   stats     [H,8]     int32  {len after, n_merged, n_appended, n_evicted, n_dropped, 0, 0, status}
+ *                              status 0; 1 if a bounded wait inside the eviction plan ran out, 2 if the stamps of
+ *                              the evictable slots span 2^20 frames or more: the choice of victims is then not
+ *                              guaranteed to be the oldest-first one
  *   ws / ws_bytes              workspace of fastar_workspace_bytes(FASTAR_OP_COMPRESS, ...), 256-byte aligned
  * The cache struct and the codec struct are host structs; cache->len is updated on the device.
  */

@@ -401,7 +401,11 @@ extern "C" int sparse_attn_fwd(const void *Q, int n_q, const void *K, const void
     hipLaunchKernelGGL((attn_bf16_kernel<DD, NW>), grid, dim3(NW * 64), 0, s, (const unsigned short *)Q,          \
                        (const unsigned short *)K, (const unsigned short *)V, cnt, len, sel, nsel, n_q, C, bk_shift, \
                        n_sel, n_qb, H, scale_log2, (unsigned short *)O, lse)
-        if (d == 128 && BQ == 128)  // two query blocks per workgroup in anti-phase (matrix | vector) on each SIMD
+        // Two query blocks per workgroup in anti-phase (matrix | vector) on each SIMD; one workgroup fills a CU, so the
+        // work comes in rounds of 512 query blocks: when the last round would be less than half full, the kernel with
+        // one block per workgroup (two workgroups per CU, started as slots free up) finishes earlier.
+        const int n_items = n_qb * H;
+        if (d == 128 && BQ == 128 && (n_items <= 512 || n_items % 512 == 0 || n_items % 512 >= 256))
             return launch_attn_bf16_d128_pp(Q, n_q, K, V, cnt, len, H, C, sel, nsel, bk_shift, n_sel, scale_log2, O, lse, s);
         if (d == 128)  // tuned path: direct-to-LDS tiles, LDS transpose loads
             return launch_attn_bf16_d128(Q, n_q, K, V, cnt, len, H, C, sel, nsel, BQ, bk_shift, n_sel, scale_log2, O, lse, s);
