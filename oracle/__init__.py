@@ -37,7 +37,8 @@ def _load():
         build()
         _lib = ctypes.CDLL(_LIB)
         for name in ("oracle_encode", "oracle_tempcache_compress", "oracle_ann_select_self",
-                     "oracle_ann_select_cross", "oracle_sparse_attn_fwd", "oracle_recall_density"):
+                     "oracle_ann_select_cross", "oracle_sparse_attn_fwd", "oracle_recall_density",
+                     "oracle_encode_sign", "oracle_ann_select_lsh"):
             getattr(_lib, name).restype = ctypes.c_int
     return _lib
 
@@ -162,6 +163,36 @@ def ann_select_cross(qcode, pcode, BQ: int, n_sel: int):
     nsel = np.empty((H, n_qb), np.int32)
     rc = _load().oracle_ann_select_cross(_p(qcode), n_q, _p(pcode), n_p, H, r, BQ, n_sel, _p(sel), _p(nsel))
     _check(rc, "oracle_ann_select_cross")
+    return sel, nsel
+
+
+def encode_sign(x, R, qscale: float):
+    """x [..., d] storage form, R [d, n_bits] int8 (+-1) -> bits [..., n_bits/32] uint32 (Sec. 5.1, LSH paragraph)."""
+    x = _c(x)
+    R = _c(R, np.int8)
+    d, n_bits = R.shape
+    assert x.shape[-1] == d and n_bits % 32 == 0
+    n_vec = int(np.prod(x.shape[:-1]))
+    bits = np.empty(x.shape[:-1] + (n_bits // 32,), np.uint32)
+    rc = _load().oracle_encode_sign(_p(x), _dtype_code(x), ctypes.c_int64(n_vec), d, _p(R), n_bits,
+                                    ctypes.c_float(float(np.float32(qscale))), _p(bits))
+    _check(rc, "oracle_encode_sign")
+    return bits
+
+
+def ann_select_lsh(qbits, kbits, length, BQ: int, n_rep: int, BK: int, n_sel: int):
+    """qbits [H,n_q,W], kbits [H,C,W] uint32, length [H] -> (sel [H,n_qb,n_sel] ascending / -1 padded, nsel)."""
+    qbits = _c(qbits, np.uint32)
+    kbits = _c(kbits, np.uint32)
+    length = _c(length, np.int32)
+    H, n_q, W = qbits.shape
+    C = kbits.shape[1]
+    n_qb = (n_q + BQ - 1) // BQ
+    sel = np.empty((H, n_qb, n_sel), np.int32)
+    nsel = np.empty((H, n_qb), np.int32)
+    rc = _load().oracle_ann_select_lsh(_p(qbits), n_q, _p(kbits), _p(length), H, C, 32 * W, BQ, n_rep, BK, n_sel,
+                                       _p(sel), _p(nsel))
+    _check(rc, "oracle_ann_select_lsh")
     return sel, nsel
 
 

@@ -17,13 +17,17 @@
  *                              mean value and the biased logit).
  *   oracle_ann_select_self     Sec. 5.4 (AnnSA): keys a query block attends to, ranked by code score.
  *   oracle_ann_select_cross    Sec. 5.3 (AnnCA): prompt tokens with a neighbouring query in the block.
+ *   oracle_encode_sign         Sec. 5.1, LSH paragraph: one hash bit per random projection (its sign).
+ *   oracle_ann_select_lsh      Sec. 5.3 / 5.4 on those hash codes: candidates ranked by the number of hash
+ *                              bits they share with the query side (AnnSA with key blocks, AnnCA with BK = 1).
  *   oracle_sparse_attn_fwd     Eq. (1) restricted to the candidate set (Sec. 5.1 display), with the
  *                              +log m_t logit shift of Lemma 1.
  *   oracle_recall_density      attention recall / density as defined in the Metrics paragraph.
  *
  * Parity pins (tests/test_oracle_*.py): dense softmax attention written independently in
  * numpy, Lemma 1 on exact duplicates, brute-force nearest neighbours and top-k, closed-form
- * code values, identity merge, monotonicity in the threshold.  The eviction policy of
+ * code values, identity merge, monotonicity in the threshold; for the sign codes a worked example,
+ * sign-flip and scaling invariances, the 1 - angle/pi law of random hyperplanes, brute force in Python.  The eviction policy of
  * oracle_tempcache_compress (what to do when the bounded cache is full) is not in the paper:
  * it is checked by invariants only and is "parity unpinned".
  *
@@ -428,6 +432,108 @@ int oracle_ann_select_cross(const int8_t *qcode, int n_q, const int8_t *pcode, i
                 if (picked[p]) out[w++] = p;
             nsel[(int64_t)h * n_qb + b] = w;
             for (; w < n_sel; ++w) out[w] = -1;
+            free(score);
+            free(picked);
+        }
+    }
+    return 0;
+}
+
+/* ------------------------------------------------------------------ sign codes (LSH family) */
+
+/*
+ * x [n_vec, d] -> bits [n_vec, n_bits/32] (uint32 words, bit j of a vector in word j/32 at position j%32).
+ * Bit j = 1 iff sum_t R[t][j] * xq[t] >= 0, with xq the 8-bit quantisation of oracle_encode and R [d, n_bits]
+ * a +-1 matrix: the side of the j-th random hyperplane the (quantised) vector lies on.
+ */
+int oracle_encode_sign(const void *x, int dtype, int64_t n_vec, int d, const int8_t *R, int n_bits, float qscale,
+                       uint32_t *bits) {
+    if (!x || !R || !bits || d <= 0 || n_bits <= 0 || n_bits % 32 != 0) return -1;
+    const int W = n_bits / 32;
+#pragma omp parallel for schedule(static)
+    for (int64_t v = 0; v < n_vec; ++v) {
+        for (int w = 0; w < W; ++w) bits[v * W + w] = 0u;
+        for (int j = 0; j < n_bits; ++j) {
+            int64_t y = 0;
+            for (int t = 0; t < d; ++t)
+                y += (int64_t)R[(int64_t)t * n_bits + j] * quant8(load_f32(x, dtype, v * d + t), qscale);
+            if (y >= 0) bits[v * W + j / 32] |= (uint32_t)1 << (j % 32);
+        }
+    }
+    return 0;
+}
+
+static int equal_bits(const uint32_t *a, const uint32_t *b, int W) {
+    int n = 0;
+    for (int w = 0; w < W; ++w) {
+        uint32_t x = ~(a[w] ^ b[w]);
+        while (x) {
+            n += (int)(x & 1u);
+            x >>= 1;
+        }
+    }
+    return n;
+}
+
+/*
+ * Selection on sign codes.  qbits [H,n_q,W], kbits [H,C,W] (W = n_bits/32), len [H].
+ * Query block b (BQ queries) is summarised by n_rep majority codes, one per run of g = BQ/n_rep queries: bit j of a
+ * summary is 1 iff at least half of the run's queries have it set (2 * ones >= queries in the run; runs with no
+ * query are skipped).  Score of key block kb (BK keys) = max over summaries and over its live keys of the number
+ * of equal bits.  The min(n_sel, ceil(len/BK)) best key blocks (ties: lowest index) are written in ascending
+ * order to sel [H,n_qb,n_sel] (-1 padded), their number to nsel [H,n_qb].
+ * n_rep = BQ and BK = 1 give the cross-attention form: a key is scored by its best-matching query of the block.
+ */
+int oracle_ann_select_lsh(const uint32_t *qbits, int n_q, const uint32_t *kbits, const int32_t *len, int H, int C,
+                          int n_bits, int BQ, int n_rep, int BK, int n_sel, int32_t *sel, int32_t *nsel) {
+    if (!qbits || !kbits || !len || !sel || !nsel) return -1;
+    if (H <= 0 || C <= 0 || n_bits <= 0 || n_bits % 32 != 0 || BQ <= 0 || n_rep <= 0 || BK <= 0 || n_sel <= 0 ||
+        BQ % n_rep != 0)
+        return -1;
+    const int W = n_bits / 32;
+    const int n_qb = (n_q + BQ - 1) / BQ;
+    const int g = BQ / n_rep;
+    const int n_kb_cap = (C + BK - 1) / BK;
+#pragma omp parallel for collapse(2) schedule(dynamic, 1)
+    for (int h = 0; h < H; ++h) {
+        for (int b = 0; b < n_qb; ++b) {
+            const int L = len[h] < C ? len[h] : C;
+            const int n_kb = (L + BK - 1) / BK;
+            uint32_t *rep = calloc((size_t)n_rep * W, sizeof(uint32_t));
+            uint8_t *rep_ok = malloc((size_t)n_rep);
+            int64_t *score = malloc(sizeof(int64_t) * (size_t)(n_kb_cap > 0 ? n_kb_cap : 1));
+            uint8_t *picked = malloc((size_t)(n_kb_cap > 0 ? n_kb_cap : 1));
+            for (int u = 0; u < n_rep; ++u) {
+                int q0 = b * BQ + u * g, q1 = q0 + g;
+                if (q1 > n_q) q1 = n_q;
+                rep_ok[u] = q0 < n_q;
+                for (int j = 0; j < n_bits && rep_ok[u]; ++j) {
+                    int ones = 0;
+                    for (int q = q0; q < q1; ++q)
+                        ones += (int)((qbits[((int64_t)h * n_q + q) * W + j / 32] >> (j % 32)) & 1u);
+                    if (2 * ones >= q1 - q0) rep[(int64_t)u * W + j / 32] |= (uint32_t)1 << (j % 32);
+                }
+            }
+            for (int kb = 0; kb < n_kb; ++kb) {
+                int64_t best = -1;
+                for (int k = kb * BK; k < (kb + 1) * BK && k < L; ++k)
+                    for (int u = 0; u < n_rep; ++u) {
+                        if (!rep_ok[u]) continue;
+                        int64_t s = equal_bits(rep + (int64_t)u * W, kbits + ((int64_t)h * C + k) * W, W);
+                        if (s > best) best = s;
+                    }
+                score[kb] = best;
+            }
+            int n_out = n_sel < n_kb ? n_sel : n_kb;
+            pick_top(score, n_kb, n_out, picked);
+            int32_t *out = sel + ((int64_t)h * n_qb + b) * n_sel;
+            int w = 0;
+            for (int kb = 0; kb < n_kb; ++kb)
+                if (picked[kb]) out[w++] = kb;
+            nsel[(int64_t)h * n_qb + b] = w;
+            for (; w < n_sel; ++w) out[w] = -1;
+            free(rep);
+            free(rep_ok);
             free(score);
             free(picked);
         }
