@@ -47,6 +47,7 @@ extern "C" {
 #define FASTAR_OP_COMPRESS 1
 #define FASTAR_OP_SELECT_SELF 2
 #define FASTAR_OP_SELECT_CROSS 3
+#define FASTAR_OP_SELECT_LSH 4
 
 /*
  * Bounded per-head KV cache with multiplicities (Lemma 1 of the paper: a group of merged keys is
@@ -85,7 +86,8 @@ const char *fastar_strerror(int code);
 /*
  * Bytes of device workspace an operation needs (FASTAR_OP_*).  Arguments that an operation does
  * not use are ignored.  COMPRESS: H, C, n_new (as n_q), r.  SELECT_SELF: H, n_q, C (as n_k), BQ,
- * BK, n_rep, r.  SELECT_CROSS: H, n_q, n_p (as n_k), BQ.  Returns 0 for an unknown op.
+ * BK, n_rep, r.  SELECT_CROSS: H, n_q, n_p (as n_k), BQ.  SELECT_LSH: H, n_q, C (as n_k), n_bits (as r), BQ, BK,
+ * n_rep.  Returns 0 for an unknown op.
  */
 size_t fastar_workspace_bytes(int op, int H, int n_q, int n_k, int r, int BQ, int BK, int n_rep);
 
@@ -97,6 +99,30 @@ size_t fastar_workspace_bytes(int op, int H, int n_q, int n_k, int r, int BQ, in
  */
 int fastar_encode(const void *x, int dtype, int64_t n_vec, int d, const fastar_codec *codec, int r,
                   int8_t *code_out, void *stream);
+
+/*
+ * Sign codes, the hash of the LSH paragraph of Sec. 5.1: one bit per random projection, the side of the
+ * hyperplane the quantised vector lies on.  bit j = 1 iff sum_t R[t][j] * xq[t] >= 0, xq as in fastar_codec.
+ *   x        [n_vec, d] dtype (device), d in {64, 128}
+ *   R        [d, n_bits] int8 entries -1 / +1 (device), n_bits in {64, 128, 256}
+ *   bits_out [n_vec, n_bits/32] uint32 (device); bit j of a vector sits in word j/32 at position j%32
+ */
+int fastar_encode_sign(const void *x, int dtype, int64_t n_vec, int d, const int8_t *R, float qscale, int n_bits,
+                       uint32_t *bits_out, void *stream);
+
+/*
+ * Selection on sign codes (Sec. 5.3 / 5.4 with the LSH family of Sec. 5.1): candidates are ranked by the number of
+ * hash bits they share with the query side.  Query block b (BQ queries) is summarised by n_rep majority codes, one
+ * per run of BQ/n_rep queries (bit j = 1 iff at least half of the run's queries have it set); the score of key
+ * block kb (BK keys) is the largest number of equal bits between a summary and a live key of the block; the
+ * min(n_sel, ceil(len/BK)) best key blocks (ties: lowest index) are written ascending to sel, -1 padded.
+ * n_rep = BQ, BK = 1 is the cross-attention form (a prompt token is scored by its best-matching query).
+ *   qbits [H,n_q,W], kbits [H,C,W] uint32 (W = n_bits/32), len [H];  sel [H,n_qb,n_sel], nsel [H,n_qb] out.
+ * Supported: n_bits in {64,128,256}; BK a power of two <= 64 or a multiple of 64; BQ a multiple of n_rep.
+ */
+int ann_select_lsh(const uint32_t *qbits, int n_q, const uint32_t *kbits, const int32_t *len, int H, int C,
+                   int n_bits, int BQ, int n_rep, int BK, int n_sel, int32_t *sel, int32_t *nsel, void *ws,
+                   size_t ws_bytes, void *stream);
 
 /*
  * TempCache (Sec. 5.2 and Lemma 1): merge one frame of n_new tokens per head into the cache.  Every

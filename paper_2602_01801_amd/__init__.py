@@ -10,13 +10,16 @@ from .binding import (  # noqa: F401
     LIB_PATH,
     OP_COMPRESS,
     OP_SELECT_CROSS,
+    OP_SELECT_LSH,
     OP_SELECT_SELF,
     Cache,
     Codec,
     FastarError,
     ann_select_cross,
+    ann_select_lsh,
     ann_select_self,
     encode,
+    encode_sign,
     lib,
     probe_copy,
     probe_mfma_bf16,

@@ -16,7 +16,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libfastar.so")
 
 F32, BF16 = 0, 1
-OP_COMPRESS, OP_SELECT_SELF, OP_SELECT_CROSS = 1, 2, 3
+OP_COMPRESS, OP_SELECT_SELF, OP_SELECT_CROSS, OP_SELECT_LSH = 1, 2, 3, 4
 
 _lib = None
 
@@ -71,6 +71,12 @@ def lib() -> ctypes.CDLL:
                                       ctypes.c_void_p, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int,
                                       ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int, ctypes.c_int, ctypes.c_int,
                                       ctypes.c_float, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
+        L.fastar_encode_sign.restype = ctypes.c_int
+        L.fastar_encode_sign.argtypes = [ctypes.c_void_p, ctypes.c_int, ctypes.c_int64, ctypes.c_int, ctypes.c_void_p,
+                                         ctypes.c_float, ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p]
+        L.ann_select_lsh.restype = ctypes.c_int
+        L.ann_select_lsh.argtypes = [ctypes.c_void_p, ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p] + \
+            [ctypes.c_int] * 7 + [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
         L.fastar_probe_mfma_bf16.restype = ctypes.c_int
         L.fastar_probe_mfma_bf16.argtypes = [ctypes.c_int, ctypes.c_void_p, ctypes.POINTER(ctypes.c_double), ctypes.c_void_p]
         L.fastar_probe_copy.restype = ctypes.c_int
@@ -80,7 +86,8 @@ def lib() -> ctypes.CDLL:
 
 
 EXPORTS = ("fastar_version", "fastar_strerror", "fastar_workspace_bytes", "fastar_encode", "tempcache_compress",
-           "ann_select_self", "ann_select_cross", "sparse_attn_fwd", "fastar_probe_mfma_bf16", "fastar_probe_copy")
+           "ann_select_self", "ann_select_cross", "sparse_attn_fwd", "fastar_encode_sign", "ann_select_lsh",
+           "fastar_probe_mfma_bf16", "fastar_probe_copy")
 
 
 def _check(rc: int, what: str):
@@ -243,6 +250,40 @@ def ann_select_cross(qcode, pcode, BQ: int, n_sel: int, ws=None, out=None):
     _check(lib().ann_select_cross(qcode.data_ptr(), n_q, pcode.data_ptr(), n_p, H, r, BQ, n_sel, sel.data_ptr(),
                                   nsel.data_ptr(), ws.data_ptr(), ws.numel() * ws.element_size(), _stream()),
            "ann_select_cross")
+    return sel, nsel
+
+
+def encode_sign(x: torch.Tensor, R: torch.Tensor, qscale: float, out: torch.Tensor | None = None) -> torch.Tensor:
+    """x [..., d], R [d, n_bits] int8 (+-1) -> sign codes [..., n_bits/32] as int32 words (bit patterns)."""
+    _dev(x)
+    _dev(R, torch.int8)
+    d, n_bits = R.shape
+    if x.shape[-1] != d or not x.is_contiguous() or not R.is_contiguous():
+        raise ValueError("encode_sign: x must be contiguous [..., d] and R contiguous [d, n_bits]")
+    n_vec = x.numel() // d
+    if out is None:
+        out = torch.empty(x.shape[:-1] + (n_bits // 32,), dtype=torch.int32, device=x.device)
+    _check(lib().fastar_encode_sign(x.data_ptr(), _dtype_code(x), n_vec, d, R.data_ptr(), float(qscale), n_bits,
+                                    out.data_ptr(), _stream()), "fastar_encode_sign")
+    return out
+
+
+def ann_select_lsh(qbits, kbits, length, BQ: int, n_rep: int, BK: int, n_sel: int, ws=None, out=None):
+    """Selection on sign codes: (sel [H,n_qb,n_sel] int32 ascending / -1 padded, nsel [H,n_qb] int32)."""
+    _dev(qbits, torch.int32)
+    _dev(kbits, torch.int32)
+    _dev(length, torch.int32)
+    H, n_q, W = qbits.shape
+    C = kbits.shape[1]
+    n_qb = (n_q + BQ - 1) // BQ
+    ws = _workspace(ws, workspace_bytes(OP_SELECT_LSH, H, n_q, C, 32 * W, BQ, BK, n_rep), qbits.device)
+    if out is None:
+        out = (torch.empty((H, n_qb, n_sel), dtype=torch.int32, device=qbits.device),
+               torch.empty((H, n_qb), dtype=torch.int32, device=qbits.device))
+    sel, nsel = out
+    _check(lib().ann_select_lsh(qbits.data_ptr(), n_q, kbits.data_ptr(), length.data_ptr(), H, C, 32 * W, BQ, n_rep,
+                                BK, n_sel, sel.data_ptr(), nsel.data_ptr(), ws.data_ptr(),
+                                ws.numel() * ws.element_size(), _stream()), "ann_select_lsh")
     return sel, nsel
 
 

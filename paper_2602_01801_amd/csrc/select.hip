@@ -312,6 +312,100 @@ __global__ __launch_bounds__(256) void topk_kernel(const int32_t *__restrict__ s
              nsel + (size_t)h * n_qb + b, keys);
 }
 
+// ---- selection on sign codes (LSH family) -------------------------------------------------------------
+// Summaries: bit j of the summary of a run of g queries = majority of the run's bits (2 * ones >= queries).
+// One workgroup per (query block, head), one thread per hash bit; a wavefront's ballot is two words.
+__global__ __launch_bounds__(256) void lsh_summary_kernel(const uint32_t *__restrict__ qbits, int n_q, int W, int BQ,
+                                                          int n_rep, int n_qb, uint32_t *__restrict__ rep) {
+    const int b = blockIdx.x, h = blockIdx.y, j = threadIdx.x;
+    const int g = BQ / n_rep;
+    const int lane = lane_id(), wave = j >> 6;
+    const bool mine = j < 32 * W;
+    for (int u = 0; u < n_rep; ++u) {
+        const int q0 = b * BQ + u * g, q1 = min(q0 + g, n_q);
+        int ones = 0;
+        if (mine)
+            for (int q = q0; q < q1; ++q) ones += (int)((qbits[((size_t)h * n_q + q) * W + (j >> 5)] >> (j & 31)) & 1u);
+        const unsigned long long m = __ballot(mine && q1 > q0 && 2 * ones >= q1 - q0);
+        uint32_t *out = rep + ((size_t)h * n_qb * n_rep + (size_t)b * n_rep + u) * W;
+        if (lane == 0 && 2 * wave < W) out[2 * wave] = (uint32_t)m;
+        if (lane == 0 && 2 * wave + 1 < W) out[2 * wave + 1] = (uint32_t)(m >> 32);
+    }
+}
+
+// out[h][b][kb] = max over the summaries u of block b (whose run holds a query) and the live keys k of key block
+// kb of the number of equal bits.  A lane owns one key (its W words in registers) and walks all summaries (the
+// same for every lane: scalar loads); the maximum over a key block is a reduction over BK lanes (BK a power of two
+// <= 64) or over several 64-key rounds of a wavefront (BK a multiple of 64).
+template <int W>
+__global__ __launch_bounds__(256) void lsh_score_kernel(const uint32_t *__restrict__ kbits, const int32_t *__restrict__ len,
+                                                        const uint32_t *__restrict__ rep, int C, int n_q, int BQ,
+                                                        int n_rep, int BK, int n_qb, int n_kb_cap,
+                                                        int32_t *__restrict__ out) {
+    const int h = blockIdx.y;
+    const int L = min(len[h], C);
+    const int n_kb = (L + BK - 1) / BK;
+    const int lane = lane_id(), wave = threadIdx.x >> 6;
+    const int g = BQ / n_rep;
+    const uint32_t *kb_h = kbits + (size_t)h * C * W;
+    const uint32_t *rp = rep + (size_t)h * n_qb * n_rep * W;
+    const int rounds = BK > 64 ? BK / 64 : 1;             // 64-key rounds per key block
+    const int kb_per_round = BK >= 64 ? 1 : 64 / BK;      // key blocks covered by one round of 64 lanes
+    // unit = one round-set: kb_per_round key blocks (BK < 64) or one key block (BK >= 64)
+    const int n_units = (n_kb + kb_per_round - 1) / kb_per_round;
+    for (int unit = blockIdx.x * 4 + wave; unit < n_units; unit += gridDim.x * 4) {
+        uint32_t kw[W];   // this lane's key when a key block fits one round (re-read per round otherwise)
+        bool live = false;
+        if (rounds == 1) {
+            const int key = BK >= 64 ? unit * BK + lane : unit * 64 + lane;
+            live = key < L;
+#pragma unroll
+            for (int w = 0; w < W; ++w) kw[w] = live ? kb_h[(size_t)key * W + w] : 0u;
+        }
+        for (int b = 0; b < n_qb; ++b) {
+            int best = -1;
+            for (int rd = 0; rd < rounds; ++rd) {
+                if (rounds > 1) {
+                    const int key = unit * BK + rd * 64 + lane;
+                    live = key < L;
+#pragma unroll
+                    for (int w = 0; w < W; ++w) kw[w] = live ? kb_h[(size_t)key * W + w] : 0u;
+                }
+                for (int u = 0; u < n_rep; ++u) {
+                    if (b * BQ + u * g >= n_q) break;  // uniform: this run and the later ones hold no query
+                    const uint32_t *r = rp + ((size_t)b * n_rep + u) * W;
+                    int eq = 0;
+#pragma unroll
+                    for (int w = 0; w < W; ++w) eq += __popc(~(r[w] ^ kw[w]));
+                    if (live) best = max(best, eq);
+                }
+            }
+            // maximum over the lanes of a key block
+            const int span = BK >= 64 ? 64 : BK;
+            for (int off = 1; off < span; off <<= 1) best = max(best, shfl_xor(best, off));
+            const int kb = BK >= 64 ? unit : unit * kb_per_round + lane / BK;
+            if ((lane & (span - 1)) == 0 && kb < n_kb) out[((size_t)h * n_qb + b) * n_kb_cap + kb] = best;
+        }
+    }
+}
+
+struct LshWs {
+    size_t rep_off, score_off, total;
+};
+static LshWs lsh_ws(int H, int n_q, int C, int n_bits, int BQ, int BK, int n_rep) {
+    const int n_qb = (n_q + BQ - 1) / BQ;
+    const int n_kb_cap = (C + BK - 1) / BK;
+    LshWs w;
+    w.rep_off = 0;
+    w.score_off = align256((size_t)H * n_qb * n_rep * (n_bits / 8));
+    w.total = w.score_off + align256((size_t)H * n_qb * n_kb_cap * sizeof(int32_t));
+    return w;
+}
+size_t select_lsh_ws_bytes(int H, int n_q, int C, int n_bits, int BQ, int BK, int n_rep) {
+    if (H <= 0 || n_q <= 0 || C <= 0 || n_bits <= 0 || BQ <= 0 || BK <= 0 || n_rep <= 0) return 0;
+    return lsh_ws(H, n_q, C, n_bits, BQ, BK, n_rep).total;
+}
+
 static bool pow2_le32(int v) { return v >= 1 && v <= 32 && (v & (v - 1)) == 0; }
 
 struct SelfWs {
@@ -390,6 +484,43 @@ extern "C" int ann_select_cross(const int8_t *qcode, int n_q, const int8_t *pcod
     else
         hipLaunchKernelGGL(score_cross_kernel<64>, dim3(n_qb, H), dim3(256), lds, s, qcode, pcode, n_q, n_p, BQ, n_qb,
                            n_sel, sel, nsel);
+    FASTAR_LAUNCH_CHECK();
+    return FASTAR_OK;
+}
+
+extern "C" int ann_select_lsh(const uint32_t *qbits, int n_q, const uint32_t *kbits, const int32_t *len, int H, int C,
+                              int n_bits, int BQ, int n_rep, int BK, int n_sel, int32_t *sel, int32_t *nsel, void *ws,
+                              size_t ws_bytes, void *stream) {
+    if (!qbits || !kbits || !len || !sel || !nsel || !ws) return FASTAR_ERR_INVALID_ARG;
+    if (H <= 0 || n_q <= 0 || C <= 0 || BQ <= 0 || n_rep <= 0 || BK <= 0 || n_sel <= 0) return FASTAR_ERR_INVALID_ARG;
+    if (BQ % n_rep != 0 || ((uintptr_t)ws & 255)) return FASTAR_ERR_INVALID_ARG;
+    if (n_bits != 64 && n_bits != 128 && n_bits != 256) return FASTAR_ERR_UNSUPPORTED;
+    if (!((BK <= 64 && (BK & (BK - 1)) == 0) || BK % 64 == 0)) return FASTAR_ERR_UNSUPPORTED;
+    const int W = n_bits / 32;
+    const int n_qb = (n_q + BQ - 1) / BQ;
+    const int n_kb_cap = (C + BK - 1) / BK;
+    const LshWs w = lsh_ws(H, n_q, C, n_bits, BQ, BK, n_rep);
+    if (ws_bytes < w.total) return FASTAR_ERR_WORKSPACE;
+    hipStream_t s = (hipStream_t)stream;
+    uint32_t *rep = (uint32_t *)((char *)ws + w.rep_off);
+    int32_t *score = (int32_t *)((char *)ws + w.score_off);
+    hipLaunchKernelGGL(lsh_summary_kernel, dim3(n_qb, H), dim3(256), 0, s, qbits, n_q, W, BQ, n_rep, n_qb, rep);
+    FASTAR_LAUNCH_CHECK();
+    const int kb_per_round = BK >= 64 ? 1 : 64 / BK;
+    const int n_units = (n_kb_cap + kb_per_round - 1) / kb_per_round;
+    dim3 grid((n_units + 3) / 4, H);
+    if (W == 2)
+        hipLaunchKernelGGL(lsh_score_kernel<2>, grid, dim3(256), 0, s, kbits, len, rep, C, n_q, BQ, n_rep, BK, n_qb,
+                           n_kb_cap, score);
+    else if (W == 4)
+        hipLaunchKernelGGL(lsh_score_kernel<4>, grid, dim3(256), 0, s, kbits, len, rep, C, n_q, BQ, n_rep, BK, n_qb,
+                           n_kb_cap, score);
+    else
+        hipLaunchKernelGGL(lsh_score_kernel<8>, grid, dim3(256), 0, s, kbits, len, rep, C, n_q, BQ, n_rep, BK, n_qb,
+                           n_kb_cap, score);
+    FASTAR_LAUNCH_CHECK();
+    hipLaunchKernelGGL(topk_kernel, dim3(n_qb, H), dim3(256), 0, s, score, n_kb_cap, len, C, BK, 0, n_qb, n_sel, sel,
+                       nsel);
     FASTAR_LAUNCH_CHECK();
     return FASTAR_OK;
 }

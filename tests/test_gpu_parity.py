@@ -102,6 +102,83 @@ def test_selection_is_deterministic_across_repeats():
         assert torch.equal(again[0], first[0]) and torch.equal(again[1], first[1])
 
 
+# ----------------------------------------------------------------------------------------- sign codes (LSH)
+
+def as_u32(t):
+    return to_host(t).view(np.uint32)
+
+
+@pytest.mark.parametrize("dtype,d,n_bits,n", [("fp32", 64, 64, 515), ("bf16", 128, 128, 4681), ("bf16", 64, 256, 33),
+                                              ("fp32", 128, 256, 1000), ("bf16", 128, 64, 1), ("fp32", 64, 128, 16)])
+def test_encode_sign_bit_exact(dtype, d, n_bits, n):
+    rng = np.random.default_rng(d + n_bits + n)
+    R = rng.choice(np.array([-1, 1], np.int8), size=(d, n_bits))
+    x = rng.standard_normal((n, d)).astype(np.float32) * 1.5
+    x[::7] = np.round(x[::7])                                       # projections that land on zero happen
+    x[::11] = 0.0
+    xs = to_storage(x, dtype)
+    ref = oracle.encode_sign(xs, R, 127 / 4.5)
+    got = fa.encode_sign(to_dev(xs), to_dev(R), 127 / 4.5)
+    sync()
+    assert np.array_equal(as_u32(got), ref)
+
+
+@pytest.mark.parametrize("H,n_q,C,n_bits,BQ,n_rep,BK,n_sel,lens,flip", [
+    (2, 256, 1280, 128, 128, 4, 64, 5, [1280, 546], 0.3),            # cfg1-shaped
+    (3, 300, 64 * 40, 128, 128, 4, 64, 7, [2560, 2000, 0], 0.02),     # heavy ties, ragged tail, empty head
+    (2, 1000, 64 * 300, 64, 128, 4, 64, 40, [19200, 13111], 0.3),
+    (2, 200, 640, 256, 64, 8, 16, 9, [640, 333], 0.2),                # several key blocks per wavefront round
+    (1, 130, 1024, 128, 128, 1, 128, 3, [1000], 0.3),                 # key blocks of two rounds
+    (2, 300, 97, 128, 128, 128, 1, 20, [97, 50], 0.1),                # cross-attention form: BK = 1, n_rep = BQ
+])
+def test_ann_select_lsh_bit_exact(H, n_q, C, n_bits, BQ, n_rep, BK, n_sel, lens, flip):
+    rng = np.random.default_rng(n_q + C + n_bits)
+    W = n_bits // 32
+    # codes that cluster: a few prototypes with a fraction of their bits flipped, so that scores repeat and spread
+    proto = rng.integers(0, 2, size=(8, n_bits))
+    def draw(n):
+        b = proto[rng.integers(0, 8, size=n)] ^ (rng.random((n, n_bits)) < flip)
+        words = np.zeros((n, W), np.uint32)
+        for j in range(n_bits):
+            words[:, j // 32] |= (b[:, j].astype(np.uint32) << np.uint32(j % 32))
+        return words
+    qb = np.stack([draw(n_q) for _ in range(H)])
+    kb = np.stack([draw(C) for _ in range(H)])
+    length = np.array(lens, np.int32)
+    ref_sel, ref_nsel = oracle.ann_select_lsh(qb, kb, length, BQ, n_rep, BK, n_sel)
+    sel, nsel = fa.ann_select_lsh(to_dev(qb.view(np.int32)), to_dev(kb.view(np.int32)), to_dev(length), BQ, n_rep, BK,
+                                  n_sel)
+    sync()
+    assert np.array_equal(to_host(nsel), ref_nsel)
+    assert np.array_equal(to_host(sel), ref_sel)
+
+
+def test_sign_codes_select_then_attend_end_to_end():
+    """Hash the cache keys and the queries, select on shared bits, attend: the whole variant against the oracle."""
+    c = dict(CONFIGS["cfg1"])
+    fs = FrameStream(c["seed"], c["cfg_id"], c["H"], c["d"], c["T"], c["n_c"], c["p"], c["sigma_d"], c["dtype"])
+    frames = [fs.next_frame() for _ in range(4)]
+    K = np.concatenate([f[0] for f in frames], axis=1)
+    V = np.concatenate([f[1] for f in frames], axis=1)
+    Q = fs.queries(1)
+    rng = np.random.default_rng(2)
+    R = rng.choice(np.array([-1, 1], np.int8), size=(c["d"], 128))
+    q = 127 / 4.5
+    H, C = K.shape[0], K.shape[1]
+    length = np.full((H,), C, np.int32)
+    qb_r, kb_r = oracle.encode_sign(Q, R, q), oracle.encode_sign(K, R, q)
+    sel_r, nsel_r = oracle.ann_select_lsh(qb_r, kb_r, length, 128, 4, 64, 5)
+    O_r, _ = oracle.sparse_attn_fwd(Q, K, V, None, length, sel_r, nsel_r, 128, 64, c["d"] ** -0.5)
+    dQ, dK, dV, dR, dlen = to_dev(Q), to_dev(K), to_dev(V), to_dev(R), to_dev(length)
+    qb, kb = fa.encode_sign(dQ, dR, q), fa.encode_sign(dK, dR, q)
+    sel, nsel = fa.ann_select_lsh(qb, kb, dlen, 128, 4, 64, 5)
+    O, _ = fa.sparse_attn_fwd(dQ, dK, dV, None, dlen, sel, nsel, 128, 64, c["d"] ** -0.5)
+    sync()
+    assert np.array_equal(as_u32(qb), qb_r) and np.array_equal(as_u32(kb), kb_r)
+    assert np.array_equal(to_host(sel), sel_r) and np.array_equal(to_host(nsel), nsel_r)
+    assert np.abs(storage_to_f64(to_host(O)) - O_r).max() <= ATOL[c["dtype"]]
+
+
 # ----------------------------------------------------------------------------------------- attention
 
 def random_selection(rng, H, n_qb, n_sel, lens, BK, empty_some=True):
