@@ -31,6 +31,8 @@ PEAK_HBM_GBS = 8000.0       # MI355X HBM3E peak
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--ann", choices=["int8", "lsh"], default="int8",
+                    help="AnnSA code family: int8 projection codes (default) or 128-bit sign codes (LSH variant)")
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="cfg2", choices=["cfg2", "cfg5"])
@@ -51,7 +53,7 @@ def parse():
 class ChunkPipeline:
     """Device buffers and the call sequence of one chunk step.  Nothing is allocated per step."""
 
-    def __init__(self, cfg, C, tau, torch, fa, dev_codec, prompt, n_sel_blocks):
+    def __init__(self, cfg, C, tau, torch, fa, dev_codec, prompt, n_sel_blocks, sign_matrix=None):
         self.t, self.fa, self.cfg = torch, fa, cfg
         H, d, r, T = cfg["H"], cfg["d"], cfg["r"], cfg["T"]
         self.H, self.d, self.r, self.T, self.C = H, d, r, T, C
@@ -83,6 +85,14 @@ class ChunkPipeline:
         self.ws_x = e((fa.workspace_bytes(fa.OP_SELECT_CROSS, H, self.n_q, self.n_p, r, self.BQ),), torch.uint8)
         self.csel = (e((H, self.n_qb, self.n_sel_cross), torch.int32), e((H, self.n_qb), torch.int32))
         self.Ox = (e((H, self.n_q, d), dt), None)
+        # sign-code (LSH) variant of AnnSA: the cache keeps no hash bits, they are recomputed from K every chunk
+        self.Rb = sign_matrix
+        if sign_matrix is not None:
+            W = sign_matrix.shape[1] // 32
+            self.qbits = e((H, self.n_q, W), torch.int32)
+            self.kbits = e((H, C, W), torch.int32)
+            self.ws_l = e((fa.workspace_bytes(fa.OP_SELECT_LSH, H, self.n_q, C, 32 * W, self.BQ, self.BK, self.n_rep),),
+                          torch.uint8)
 
     def compress(self, K, V):
         fa = self.fa
@@ -101,9 +111,16 @@ class ChunkPipeline:
             self.compress(K, V)
         mark("compress")
         fa.encode(Q, self.codec, out=self.qcode)
+        if self.Rb is not None:
+            fa.encode_sign(Q, self.Rb, self.codec.qscale, out=self.qbits)
+            fa.encode_sign(self.cache.K, self.Rb, self.codec.qscale, out=self.kbits)
         mark("encode")
-        fa.ann_select_self(self.qcode, self.cache.code, self.cache.len, self.BQ, self.n_rep, self.BK, self.n_sel,
-                           ws=self.ws_s, out=self.sel)
+        if self.Rb is not None:
+            fa.ann_select_lsh(self.qbits, self.kbits, self.cache.len, self.BQ, self.n_rep, self.BK, self.n_sel,
+                              ws=self.ws_l, out=self.sel)
+        else:
+            fa.ann_select_self(self.qcode, self.cache.code, self.cache.len, self.BQ, self.n_rep, self.BK, self.n_sel,
+                               ws=self.ws_s, out=self.sel)
         mark("select_self")
         fa.sparse_attn_fwd(Q, self.cache.K, self.cache.V, self.cache.cnt, self.cache.len, self.sel[0], self.sel[1],
                            self.BQ, self.BK, self.scale, out=self.O)
@@ -149,7 +166,7 @@ def gen_chunks(cfg, n_prefill, n_chunks, to_dev, cpu_heads):
     return prefill, prefill_host, chunks, ps
 
 
-def cpu_baseline(cfg, pipe, prefill_host, chunks, ps, n_heads, to_host):
+def cpu_baseline(cfg, pipe, prefill_host, chunks, ps, n_heads, to_host, sign_matrix=None):
     """The CPU oracle's own rollout on the first n_heads heads (same inputs, its own cache state from frame 0);
     only its last chunk step is timed.  Returns the cpu_baseline record, time scaled to all heads."""
     import numpy as np
@@ -179,7 +196,12 @@ def cpu_baseline(cfg, pipe, prefill_host, chunks, ps, n_heads, to_host):
         push(np.ascontiguousarray(K[hs]), np.ascontiguousarray(V[hs]))
     t1 = time.perf_counter()
     qc = oracle.encode(Qh, codec.R, codec.qscale, codec.shift)
-    sel, nsel = oracle.ann_select_self(qc, cache.code, cache.len, pipe.BQ, pipe.n_rep, pipe.BK, pipe.n_sel)
+    if sign_matrix is not None:
+        qb = oracle.encode_sign(Qh, sign_matrix, codec.qscale)
+        kb = oracle.encode_sign(cache.K, sign_matrix, codec.qscale)
+        sel, nsel = oracle.ann_select_lsh(qb, kb, cache.len, pipe.BQ, pipe.n_rep, pipe.BK, pipe.n_sel)
+    else:
+        sel, nsel = oracle.ann_select_self(qc, cache.code, cache.len, pipe.BQ, pipe.n_rep, pipe.BK, pipe.n_sel)
     t2 = time.perf_counter()
     O, _ = oracle.sparse_attn_fwd(Qh, cache.K, cache.V, cache.cnt, cache.len, sel, nsel, pipe.BQ, pipe.BK, pipe.scale)
     t3 = time.perf_counter()
@@ -242,7 +264,7 @@ def main():
     import numpy as np
     import torch
     import paper_2602_01801_amd as fa
-    from workloads import CONFIGS, make_codec
+    from workloads import CONFIGS, make_codec, make_sign_matrix
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
@@ -277,7 +299,9 @@ def main():
     prefill, prefill_host, chunks, ps = gen_chunks(cfg, n_prefill, n_chunks, to_dev, n_cpu_heads)
     dev_chunks = [([(to_dev(K), to_dev(V)) for K, V in frames], to_dev(Q)) for frames, Q in chunks]
     t_gen = time.perf_counter() - t_gen
-    pipe = ChunkPipeline(cfg, C, args.tau, torch, fa, codec, (to_dev(ps.K), to_dev(ps.V)), n_sel)
+    sign_h = make_sign_matrix(cfg["seed"], cfg["cfg_id"], cfg["d"], 128) if args.ann == "lsh" else None
+    pipe = ChunkPipeline(cfg, C, args.tau, torch, fa, codec, (to_dev(ps.K), to_dev(ps.V)), n_sel,
+                         sign_matrix=None if sign_h is None else to_dev(sign_h))
     for K, V in prefill:
         pipe.compress(K, V)
     torch.cuda.synchronize()
@@ -328,6 +352,7 @@ def main():
                                f"{cf}x{T} = {cf * T} queries, TempCache-bounded cache (cap {cap_frames} frames = {C} "
                                f"slots/head, tau {args.tau}), AnnSA {n_sel} of {n_kb_quoted} key blocks per query block "
                                f"(BQ {cfg['BQ']}, BK {cfg['BK']}), AnnCA {cfg['n_sel_cross']} of {cfg['n_p']} prompt tokens",
+                   "ann": "int8 projection codes (r 32)" if args.ann == "int8" else "sign codes, 128 hash bits (LSH variant)",
                    "prefill_frames": n_prefill, "cache_len_per_head_start": [min(len_prefill), max(len_prefill)],
                    "cache_len_per_head_end": [min(len_final), max(len_final)],
                    "cache_bytes": pipe.cache.nbytes()},
@@ -341,7 +366,7 @@ def main():
         "host_gen_s": round(t_gen, 1),
     }
     if not args.no_cpu_baseline:
-        result["cpu_baseline"] = cpu_baseline(cfg, pipe, prefill_host, chunks, ps, n_cpu_heads, to_host)
+        result["cpu_baseline"] = cpu_baseline(cfg, pipe, prefill_host, chunks, ps, n_cpu_heads, to_host, sign_h)
     result["peaks_measured"] = {"mfma_bf16_tflops": round(fa.probe_mfma_bf16(), 1),
                                 "stream_copy_gbs": round(fa.probe_copy(), 1)}
     line = json.dumps(result)

@@ -317,15 +317,20 @@ __global__ __launch_bounds__(256) void topk_kernel(const int32_t *__restrict__ s
 // One workgroup per (query block, head), one thread per hash bit; a wavefront's ballot is two words.
 __global__ __launch_bounds__(256) void lsh_summary_kernel(const uint32_t *__restrict__ qbits, int n_q, int W, int BQ,
                                                           int n_rep, int n_qb, uint32_t *__restrict__ rep) {
+    extern __shared__ uint32_t qw[];  // the query block's codes, [BQ][W]
     const int b = blockIdx.x, h = blockIdx.y, j = threadIdx.x;
     const int g = BQ / n_rep;
     const int lane = lane_id(), wave = j >> 6;
     const bool mine = j < 32 * W;
+    const int q_lo = b * BQ, q_hi = min(q_lo + BQ, n_q);
+    // one round of loads for the whole block, then the votes are counted from LDS
+    for (int t = j; t < (q_hi - q_lo) * W; t += blockDim.x) qw[t] = qbits[((size_t)h * n_q + q_lo) * W + t];
+    __syncthreads();
     for (int u = 0; u < n_rep; ++u) {
-        const int q0 = b * BQ + u * g, q1 = min(q0 + g, n_q);
+        const int q0 = q_lo + u * g, q1 = min(q0 + g, n_q);
         int ones = 0;
         if (mine)
-            for (int q = q0; q < q1; ++q) ones += (int)((qbits[((size_t)h * n_q + q) * W + (j >> 5)] >> (j & 31)) & 1u);
+            for (int q = q0; q < q1; ++q) ones += (int)((qw[(q - q_lo) * W + (j >> 5)] >> (j & 31)) & 1u);
         const unsigned long long m = __ballot(mine && q1 > q0 && 2 * ones >= q1 - q0);
         uint32_t *out = rep + ((size_t)h * n_qb * n_rep + (size_t)b * n_rep + u) * W;
         if (lane == 0 && 2 * wave < W) out[2 * wave] = (uint32_t)m;
@@ -337,10 +342,12 @@ __global__ __launch_bounds__(256) void lsh_summary_kernel(const uint32_t *__rest
 // kb of the number of equal bits.  A lane owns one key (its W words in registers) and walks all summaries (the
 // same for every lane: scalar loads); the maximum over a key block is a reduction over BK lanes (BK a power of two
 // <= 64) or over several 64-key rounds of a wavefront (BK a multiple of 64).
+constexpr int LSH_QB = 8;  // query blocks whose scores a lane carries at a time
+
 template <int W>
 __global__ __launch_bounds__(256) void lsh_score_kernel(const uint32_t *__restrict__ kbits, const int32_t *__restrict__ len,
                                                         const uint32_t *__restrict__ rep, int C, int n_q, int BQ,
-                                                        int n_rep, int BK, int n_qb, int n_kb_cap,
+                                                        int n_rep, int BK, int n_qb, int n_kb_cap, int lds_words,
                                                         int32_t *__restrict__ out) {
     const int h = blockIdx.y;
     const int L = min(len[h], C);
@@ -349,6 +356,13 @@ __global__ __launch_bounds__(256) void lsh_score_kernel(const uint32_t *__restri
     const int g = BQ / n_rep;
     const uint32_t *kb_h = kbits + (size_t)h * C * W;
     const uint32_t *rp = rep + (size_t)h * n_qb * n_rep * W;
+    // the head's summaries are staged in LDS when they fit (lds_words > 0): every lane reads the same word
+    extern __shared__ uint32_t srep[];
+    if (lds_words > 0) {
+        for (int t = threadIdx.x; t < lds_words; t += blockDim.x) srep[t] = rp[t];
+        __syncthreads();
+        rp = srep;
+    }
     const int rounds = BK > 64 ? BK / 64 : 1;             // 64-key rounds per key block
     const int kb_per_round = BK >= 64 ? 1 : 64 / BK;      // key blocks covered by one round of 64 lanes
     // unit = one round-set: kb_per_round key blocks (BK < 64) or one key block (BK >= 64)
@@ -362,8 +376,11 @@ __global__ __launch_bounds__(256) void lsh_score_kernel(const uint32_t *__restri
 #pragma unroll
             for (int w = 0; w < W; ++w) kw[w] = live ? kb_h[(size_t)key * W + w] : 0u;
         }
-        for (int b = 0; b < n_qb; ++b) {
-            int best = -1;
+        // query blocks in batches of LSH_QB: the lane-exchange reductions of a batch are independent of each other
+        for (int b0 = 0; b0 < n_qb; b0 += LSH_QB) {
+            int best[LSH_QB];
+#pragma unroll
+            for (int i = 0; i < LSH_QB; ++i) best[i] = -1;
             for (int rd = 0; rd < rounds; ++rd) {
                 if (rounds > 1) {
                     const int key = unit * BK + rd * 64 + lane;
@@ -371,20 +388,32 @@ __global__ __launch_bounds__(256) void lsh_score_kernel(const uint32_t *__restri
 #pragma unroll
                     for (int w = 0; w < W; ++w) kw[w] = live ? kb_h[(size_t)key * W + w] : 0u;
                 }
-                for (int u = 0; u < n_rep; ++u) {
-                    if (b * BQ + u * g >= n_q) break;  // uniform: this run and the later ones hold no query
-                    const uint32_t *r = rp + ((size_t)b * n_rep + u) * W;
-                    int eq = 0;
 #pragma unroll
-                    for (int w = 0; w < W; ++w) eq += __popc(~(r[w] ^ kw[w]));
-                    if (live) best = max(best, eq);
+                for (int i = 0; i < LSH_QB; ++i) {
+                    const int b = b0 + i;
+                    if (b >= n_qb) break;  // uniform
+                    for (int u = 0; u < n_rep; ++u) {
+                        if (b * BQ + u * g >= n_q) break;  // uniform: this run and the later ones hold no query
+                        const uint32_t *r = rp + ((size_t)b * n_rep + u) * W;
+                        int eq = 0;
+#pragma unroll
+                        for (int w = 0; w < W; ++w) eq += __popc(~(r[w] ^ kw[w]));
+                        if (live) best[i] = max(best[i], eq);
+                    }
                 }
             }
             // maximum over the lanes of a key block
             const int span = BK >= 64 ? 64 : BK;
-            for (int off = 1; off < span; off <<= 1) best = max(best, shfl_xor(best, off));
+            for (int off = 1; off < span; off <<= 1) {
+#pragma unroll
+                for (int i = 0; i < LSH_QB; ++i) best[i] = max(best[i], shfl_xor(best[i], off));
+            }
             const int kb = BK >= 64 ? unit : unit * kb_per_round + lane / BK;
-            if ((lane & (span - 1)) == 0 && kb < n_kb) out[((size_t)h * n_qb + b) * n_kb_cap + kb] = best;
+            if ((lane & (span - 1)) == 0 && kb < n_kb) {
+#pragma unroll
+                for (int i = 0; i < LSH_QB; ++i)
+                    if (b0 + i < n_qb) out[((size_t)h * n_qb + b0 + i) * n_kb_cap + kb] = best[i];
+            }
         }
     }
 }
@@ -504,20 +533,25 @@ extern "C" int ann_select_lsh(const uint32_t *qbits, int n_q, const uint32_t *kb
     hipStream_t s = (hipStream_t)stream;
     uint32_t *rep = (uint32_t *)((char *)ws + w.rep_off);
     int32_t *score = (int32_t *)((char *)ws + w.score_off);
-    hipLaunchKernelGGL(lsh_summary_kernel, dim3(n_qb, H), dim3(256), 0, s, qbits, n_q, W, BQ, n_rep, n_qb, rep);
+    if ((size_t)BQ * W * 4 > 48 * 1024) return FASTAR_ERR_UNSUPPORTED;
+    hipLaunchKernelGGL(lsh_summary_kernel, dim3(n_qb, H), dim3(256), (size_t)BQ * W * 4, s, qbits, n_q, W, BQ, n_rep, n_qb,
+                       rep);
     FASTAR_LAUNCH_CHECK();
     const int kb_per_round = BK >= 64 ? 1 : 64 / BK;
     const int n_units = (n_kb_cap + kb_per_round - 1) / kb_per_round;
     dim3 grid((n_units + 3) / 4, H);
+    int lds_words = n_qb * n_rep * W;
+    if ((size_t)lds_words * 4 > 48 * 1024) lds_words = 0;  // too many summaries (per-query form): read them from memory
+    const size_t lds_bytes = (size_t)lds_words * 4;
     if (W == 2)
-        hipLaunchKernelGGL(lsh_score_kernel<2>, grid, dim3(256), 0, s, kbits, len, rep, C, n_q, BQ, n_rep, BK, n_qb,
-                           n_kb_cap, score);
+        hipLaunchKernelGGL(lsh_score_kernel<2>, grid, dim3(256), lds_bytes, s, kbits, len, rep, C, n_q, BQ, n_rep, BK,
+                           n_qb, n_kb_cap, lds_words, score);
     else if (W == 4)
-        hipLaunchKernelGGL(lsh_score_kernel<4>, grid, dim3(256), 0, s, kbits, len, rep, C, n_q, BQ, n_rep, BK, n_qb,
-                           n_kb_cap, score);
+        hipLaunchKernelGGL(lsh_score_kernel<4>, grid, dim3(256), lds_bytes, s, kbits, len, rep, C, n_q, BQ, n_rep, BK,
+                           n_qb, n_kb_cap, lds_words, score);
     else
-        hipLaunchKernelGGL(lsh_score_kernel<8>, grid, dim3(256), 0, s, kbits, len, rep, C, n_q, BQ, n_rep, BK, n_qb,
-                           n_kb_cap, score);
+        hipLaunchKernelGGL(lsh_score_kernel<8>, grid, dim3(256), lds_bytes, s, kbits, len, rep, C, n_q, BQ, n_rep, BK,
+                           n_qb, n_kb_cap, lds_words, score);
     FASTAR_LAUNCH_CHECK();
     hipLaunchKernelGGL(topk_kernel, dim3(n_qb, H), dim3(256), 0, s, score, n_kb_cap, len, C, BK, 0, n_qb, n_sel, sel,
                        nsel);

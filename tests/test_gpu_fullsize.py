@@ -85,6 +85,24 @@ def test_wan_shaped_layer_full_size():
     n_sel = int(np.ceil(c["sel_frac"] * n_kb))
     assert n_sel == 52
     Q, qc, qc_r = select_and_attend(c, fs, codec, dcodec, gpu, ref, heads, n_sel)
+    # the sign-code (LSH) selection on the same cache and queries: 128 hash bits, same budget
+    rng = np.random.default_rng(99)
+    Rb = rng.choice(np.array([-1, 1], np.int8), size=(c["d"], 128))
+    qb = fa.encode_sign(to_dev(Q), to_dev(Rb), codec.qscale)
+    kb = fa.encode_sign(gpu.K, to_dev(Rb), codec.qscale)
+    qb_r = oracle.encode_sign(np.ascontiguousarray(Q[heads]), Rb, codec.qscale)
+    kb_r = oracle.encode_sign(ref.K, Rb, codec.qscale)
+    assert np.array_equal(to_host(qb).view(np.uint32)[heads], qb_r)
+    for i, h in enumerate(heads):
+        L = int(ref.len[i])
+        assert np.array_equal(to_host(kb[h, :L]).view(np.uint32), kb_r[i, :L])
+    lsel, lnsel = fa.ann_select_lsh(qb, kb, gpu.len, c["BQ"], c["n_rep"], c["BK"], n_sel)
+    lsel_r, lnsel_r = oracle.ann_select_lsh(qb_r, kb_r, ref.len, c["BQ"], c["n_rep"], c["BK"], n_sel)
+    assert np.array_equal(to_host(lnsel)[heads], lnsel_r) and np.array_equal(to_host(lsel)[heads], lsel_r)
+    O, _ = fa.sparse_attn_fwd(to_dev(Q), gpu.K, gpu.V, gpu.cnt, gpu.len, lsel, lnsel, c["BQ"], c["BK"], c["d"] ** -0.5)
+    O_r, _ = oracle.sparse_attn_fwd(np.ascontiguousarray(Q[heads]), ref.K, ref.V, ref.cnt, ref.len, lsel_r, lnsel_r,
+                                    c["BQ"], c["BK"], c["d"] ** -0.5)
+    assert np.abs(storage_to_f64(to_host(O))[heads] - O_r).max() <= 2e-2
     # cross-attention legs (cfg4): 64 of 512 and of 2048 prompt tokens
     for n_p in (c["n_p"], CONFIGS["cfg4"]["n_p_long"]):
         ps = PromptSet(c["seed"], c["cfg_id"], fs.centreK, n_p, c["n_pc"], c["n_near"], c["dtype"])

@@ -11,6 +11,7 @@ from .synth import (  # noqa: F401
     bf16_bits_to_f32,
     f32_to_bf16_bits,
     make_codec,
+    make_sign_matrix,
     to_f32,
     to_storage,
 )

@@ -108,6 +108,12 @@ def make_codec(seed: int, cfg_id: int, d: int, r: int) -> Codec:
     return Codec(R=np.ascontiguousarray(R), qscale=np.float32(127.0 / CODEC_RANGE), shift=CODEC_SHIFT)
 
 
+def make_sign_matrix(seed: int, cfg_id: int, d: int, n_bits: int) -> np.ndarray:
+    """Random +-1 hyperplane matrix [d, n_bits] of the sign-code (LSH) variant; input data for oracle and GPU."""
+    rng = np.random.default_rng(np.random.SeedSequence([seed, cfg_id, 0x51C4]))
+    return np.ascontiguousarray((rng.integers(0, 2, size=(d, n_bits)).astype(np.int8) * 2 - 1).astype(np.int8))
+
+
 # --------------------------------------------------------------------------------------
 # frame stream
 # --------------------------------------------------------------------------------------
