@@ -33,6 +33,9 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--ann", choices=["int8", "lsh"], default="int8",
                     help="AnnSA code family: int8 projection codes (default) or 128-bit sign codes (LSH variant)")
+    ap.add_argument("--code-shift", type=int, default=None,
+                    help="right shift of the projected sums in the int8 code (default 4, about 8 significant bits; "
+                         "6 / 8 / 9 leave about 6 / 4 / 2): the bit-width ladder of the paper's quantisation ablation")
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="cfg2", choices=["cfg2", "cfg5"])
@@ -166,7 +169,7 @@ def gen_chunks(cfg, n_prefill, n_chunks, to_dev, cpu_heads):
     return prefill, prefill_host, chunks, ps
 
 
-def cpu_baseline(cfg, pipe, prefill_host, chunks, ps, n_heads, to_host, sign_matrix=None):
+def cpu_baseline(cfg, pipe, prefill_host, chunks, ps, n_heads, to_host, sign_matrix=None, code_shift=None):
     """The CPU oracle's own rollout on the first n_heads heads (same inputs, its own cache state from frame 0);
     only its last chunk step is timed.  Returns the cpu_baseline record, time scaled to all heads."""
     import numpy as np
@@ -175,6 +178,8 @@ def cpu_baseline(cfg, pipe, prefill_host, chunks, ps, n_heads, to_host, sign_mat
     H = cfg["H"]
     hs = slice(0, n_heads)
     codec = make_codec(cfg["seed"], cfg["cfg_id"], cfg["d"], cfg["r"])
+    if code_shift is not None:
+        codec.shift = code_shift
     cache = oracle.Cache.empty(n_heads, pipe.C, cfg["d"], cfg["r"], cfg["dtype"])
     threads = len(os.sched_getaffinity(0))
     prev, fid = None, 0
@@ -292,6 +297,8 @@ def main():
     n_kb_quoted = (cfg["cache_frames"] * T + cfg["BK"] - 1) // cfg["BK"]
     n_sel = int(np.ceil(cfg["sel_frac"] * n_kb_quoted))
     codec_h = make_codec(cfg["seed"], cfg["cfg_id"], cfg["d"], cfg["r"])
+    if args.code_shift is not None:
+        codec_h.shift = args.code_shift
     codec = fa.Codec(to_dev(codec_h.R), float(codec_h.qscale), codec_h.shift)
     n_chunks = args.warmup + args.steps
     t_gen = time.perf_counter()
@@ -352,7 +359,7 @@ def main():
                                f"{cf}x{T} = {cf * T} queries, TempCache-bounded cache (cap {cap_frames} frames = {C} "
                                f"slots/head, tau {args.tau}), AnnSA {n_sel} of {n_kb_quoted} key blocks per query block "
                                f"(BQ {cfg['BQ']}, BK {cfg['BK']}), AnnCA {cfg['n_sel_cross']} of {cfg['n_p']} prompt tokens",
-                   "ann": "int8 projection codes (r 32)" if args.ann == "int8" else "sign codes, 128 hash bits (LSH variant)",
+                   "ann": f"int8 projection codes (r 32, shift {codec_h.shift})" if args.ann == "int8" else "sign codes, 128 hash bits (LSH variant)",
                    "prefill_frames": n_prefill, "cache_len_per_head_start": [min(len_prefill), max(len_prefill)],
                    "cache_len_per_head_end": [min(len_final), max(len_final)],
                    "cache_bytes": pipe.cache.nbytes()},
@@ -366,7 +373,7 @@ def main():
         "host_gen_s": round(t_gen, 1),
     }
     if not args.no_cpu_baseline:
-        result["cpu_baseline"] = cpu_baseline(cfg, pipe, prefill_host, chunks, ps, n_cpu_heads, to_host, sign_h)
+        result["cpu_baseline"] = cpu_baseline(cfg, pipe, prefill_host, chunks, ps, n_cpu_heads, to_host, sign_h, args.code_shift)
     result["peaks_measured"] = {"mfma_bf16_tflops": round(fa.probe_mfma_bf16(), 1),
                                 "stream_copy_gbs": round(fa.probe_copy(), 1)}
     line = json.dumps(result)
