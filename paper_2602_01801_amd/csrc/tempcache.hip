@@ -263,6 +263,48 @@ struct RowPiece {
             }
         }
     }
+    // this lane's piece of a row as raw bits (held in registers between an early load and a late store)
+    struct Raw {
+        u32x4 w[(EPL * (BF16 ? 2 : 4) + 15) / 16];
+    };
+    __device__ static __forceinline__ Raw load_raw(const void *base, size_t row, int l16) {
+        constexpr int BYTES = EPL * (BF16 ? 2 : 4);
+        const char *s = (const char *)base + (row * D + (size_t)l16 * EPL) * (BF16 ? 2 : 4);
+        Raw r;
+        if (BYTES == 8) {
+            const u32x2 v = *(const u32x2 *)s;
+            r.w[0][0] = v[0]; r.w[0][1] = v[1]; r.w[0][2] = 0; r.w[0][3] = 0;
+        } else {
+#pragma unroll
+            for (int b = 0; b < BYTES; b += 16) r.w[b / 16] = *(const u32x4 *)(s + b);
+        }
+        return r;
+    }
+    __device__ static __forceinline__ void store_raw(void *base, size_t row, int l16, const Raw &r) {
+        constexpr int BYTES = EPL * (BF16 ? 2 : 4);
+        char *d = (char *)base + (row * D + (size_t)l16 * EPL) * (BF16 ? 2 : 4);
+        if (BYTES == 8) {
+            u32x2 v = {r.w[0][0], r.w[0][1]};
+            *(u32x2 *)d = v;
+        } else {
+#pragma unroll
+            for (int b = 0; b < BYTES; b += 16) *(u32x4 *)(d + b) = r.w[b / 16];
+        }
+    }
+    // raw bits -> float values of the piece
+    __device__ static __forceinline__ void unpack(const Raw &r, float *out) {
+        if (BF16) {
+#pragma unroll
+            for (int e = 0; e < EPL / 2; ++e) {
+                const unsigned w = r.w[e / 4][e % 4];
+                out[2 * e] = bf16_lo(w);
+                out[2 * e + 1] = bf16_hi(w);
+            }
+        } else {
+#pragma unroll
+            for (int e = 0; e < EPL; ++e) out[e] = __uint_as_float(r.w[e / 4][e % 4]);
+        }
+    }
     // bit copy of this lane's piece of a row
     __device__ static __forceinline__ void copy(void *dst, size_t drow, const void *src, size_t srow, int l16) {
         constexpr int BYTES = EPL * (BF16 ? 2 : 4);
@@ -299,11 +341,19 @@ __global__ __launch_bounds__(256) void tc_verify_kernel(const void *__restrict__
     const int i = blockIdx.x * (blockDim.x / 16) + (threadIdx.x >> 4);
     if (i >= n_new) return;  // whole 16-lane group leaves together
     const size_t ti = (size_t)h * n_new + i;
+    // everything addressed by the token first (one round trip), then the matched slot's key row
     const int j = jstar[ti];
+    float a[RP::EPL], b[RP::EPL];
+    RP::load(K_new, ti, l16, a);
+    int W = sbest[ti];
+    int nn = 0;
+    if (metric == 0 && l16 < r / 4) {
+        const unsigned c = ((const unsigned *)(cp + ti * r))[l16];
+        nn = dot4_i8(c, c, 0);
+    }
+    nn = group16_sum(nn);  // |probe code|^2 (r <= 64: at most 16 words)
     bool is_merged = false;
     if (j >= 0) {
-        float a[RP::EPL], b[RP::EPL];
-        RP::load(K_new, ti, l16, a);
         RP::load(K, (size_t)h * C + j, l16, b);
         int dot = 0, na = 0, nb = 0;
 #pragma unroll
@@ -318,13 +368,7 @@ __global__ __launch_bounds__(256) void tc_verify_kernel(const void *__restrict__
         nb = group16_sum(nb);
         is_merged = dot > 0 && (long long)dot * dot * 65536ll >= (long long)tau2_q16 * na * nb;
         if (is_merged && l16 == 0) {
-            int W = sbest[ti];
-            if (metric == 0) {
-                const unsigned *c = (const unsigned *)(cp + ti * r);
-                int nn = 0;
-                for (int m = 0; m < r / 4; ++m) nn = dot4_i8(c[m], c[m], nn);
-                W -= nn;
-            }
+            if (metric == 0) W -= nn;
             const u64 key = ((u64)(unsigned)(W + SCORE_BIAS) << 32) | (u64)(0xFFFFFFFFu - (unsigned)i);
             atomicMax(&win[(size_t)h * C + j], key);
             atomicAdd(&grp[(size_t)h * C + j], 1);
@@ -801,22 +845,28 @@ __global__ __launch_bounds__(256) void tc_apply_kernel(void *__restrict__ K, voi
     const size_t tb = (size_t)h * n_new, ti = tb + i, cb = (size_t)h * C;
     const int32_t *o = hs + (size_t)h * HS_STRIDE;
     const int L = o[0], n_unm = o[1], n_victims = o[3], n_dropped = o[4];
+    // First round of loads, all addressed by the token: flags, destination data, and the token's own rows (bit
+    // copies).  The second round (records and value row of the slot, or the victim slot) depends on them.
+    const bool mg = merged[ti] != 0;
+    const int j = jstar[ti];
+    const int a = rank[ti];
+    typename RP::Raw kraw = RP::load_raw(K_new, ti, l16), vraw = RP::load_raw(V_new, ti, l16);
+    unsigned cw = 0;
+    if (l16 < r / 4) cw = ((const unsigned *)(ck + ti * r))[l16];
     int dst = -1;
-    bool write_kv_copy = false;
-    if (merged[ti]) {
-        const int j = jstar[ti];
+    if (mg) {
         dst = j;
         const u64 wkey = win[cb + j];
+        const int gc = grp[cb + j];
+        const int m0 = cnt[cb + j];
         const int widx = (int)(0xFFFFFFFFu - (unsigned)wkey);
         if (widx == i) {  // this token represents the group: it refreshes the slot
-            const int gc = grp[cb + j];
-            const int m0 = cnt[cb + j];
             float acc[RP::EPL], vn[RP::EPL];
             RP::load(V, cb + j, l16, acc);
 #pragma unroll
             for (int e = 0; e < RP::EPL; ++e) acc[e] *= (float)m0;
             if (gc == 1) {
-                RP::load(V_new, ti, l16, vn);
+                RP::unpack(vraw, vn);
 #pragma unroll
                 for (int e = 0; e < RP::EPL; ++e) acc[e] += vn[e];
             } else {  // several joiners: add their values in ascending token order
@@ -836,24 +886,18 @@ __global__ __launch_bounds__(256) void tc_apply_kernel(void *__restrict__ K, voi
 #pragma unroll
             for (int e = 0; e < RP::EPL; ++e) acc[e] = __fdiv_rn(acc[e], (float)(m0 + gc));
             RP::store(V, cb + j, l16, acc);
-            RP::copy(K, cb + j, K_new, ti, l16);
-            if (l16 < r / 4) ((unsigned *)(code + (cb + j) * r))[l16] = ((const unsigned *)(ck + ti * r))[l16];
+            RP::store_raw(K, cb + j, l16, kraw);
+            if (l16 < r / 4) ((unsigned *)(code + (cb + j) * r))[l16] = cw;
             if (l16 == 0) {
                 cnt[cb + j] = m0 + gc;
                 stamp[cb + j] = frame_id;
             }
         }
-    } else {
-        const int a = rank[ti];
-        if (a < n_unm - n_dropped) {
-            dst = a < n_victims ? victims[tb + a] : L + (a - n_victims);
-            write_kv_copy = true;
-        }
-    }
-    if (write_kv_copy) {
-        RP::copy(K, cb + dst, K_new, ti, l16);
-        RP::copy(V, cb + dst, V_new, ti, l16);
-        if (l16 < r / 4) ((unsigned *)(code + (cb + dst) * r))[l16] = ((const unsigned *)(ck + ti * r))[l16];
+    } else if (a < n_unm - n_dropped) {
+        dst = a < n_victims ? victims[tb + a] : L + (a - n_victims);
+        RP::store_raw(K, cb + dst, l16, kraw);
+        RP::store_raw(V, cb + dst, l16, vraw);
+        if (l16 < r / 4) ((unsigned *)(code + (cb + dst) * r))[l16] = cw;
         if (l16 == 0) {
             cnt[cb + dst] = 1;
             stamp[cb + dst] = frame_id;
