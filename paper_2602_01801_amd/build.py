@@ -11,6 +11,9 @@ LIB = os.path.join(HERE, "libfastar.so")
 SOURCES = ["api.hip", "encode.hip", "select.hip", "tempcache.hip", "attention.hip", "attention_d128.hip",
            "attention_d128_pp.hip"]
 ASM_CHECKED = ["attention_d128.hip", "attention_d128_pp.hip"]  # kernels that read LDS through inline assembly
+# Integer matrix-core results that feed plain ALU epilogues (arg-max, top-k scores): keep them in ordinary vector
+# registers, not accumulation registers that every ALU instruction would first have to copy from.
+PER_SOURCE_FLAGS = {src: ["-mllvm", "-amdgpu-mfma-vgpr-form"] for src in ("tempcache.hip", "select.hip", "encode.hip")}
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-fast-math", "-ffp-contract=on",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wno-unused-command-line-argument"]
 
@@ -39,7 +42,7 @@ def build(verbose: bool = False, extra: list[str] | None = None) -> str:
     procs = []
     for src in SOURCES:
         obj = os.path.join(CSRC, src.replace(".hip", ".o"))
-        cmd = [hipcc, *FLAGS, *(extra or []), "-c", os.path.join(CSRC, src), "-o", obj]
+        cmd = [hipcc, *FLAGS, *PER_SOURCE_FLAGS.get(src, []), *(extra or []), "-c", os.path.join(CSRC, src), "-o", obj]
         if verbose:
             print(" ".join(cmd), flush=True)
         procs.append((src, subprocess.Popen(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)))

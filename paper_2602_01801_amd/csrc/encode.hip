@@ -7,51 +7,9 @@
 // 16 vectors at a time: B operand = their quantised coordinates (column = vector), A operand = R^T
 // (row = code coordinate), accumulator row 4*(lane/16)+v / column lane%16, so a lane ends up with 4
 // consecutive code bytes of one vector and stores them as one dword.
-#include "common.hpp"
+#include "encode_dev.hpp"
 
 namespace fastar {
-
-// Coordinate t that k-slot e (0..15) of quarter g stands for in k-step ks.  Chosen so that each
-// 16-byte load of a lane is contiguous and the four quarters of a row tile the row.
-template <bool BF16>
-__device__ __forceinline__ int slot_coord(int ks, int g, int e) {
-    if (BF16) return ks * 64 + (e >> 3) * 32 + 8 * g + (e & 7);
-    return ks * 64 + (e >> 2) * 16 + 4 * g + (e & 3);
-}
-
-// Quantised coordinates of one vector for k-step ks, as the 16 int8 k-slots of this lane.
-template <bool BF16>
-__device__ __forceinline__ i32x4 load_quantised(const void *row, int ks, int g, float qscale) {
-    i32x4 out;
-    if (BF16) {
-        const unsigned short *p = (const unsigned short *)row;
-#pragma unroll
-        for (int m = 0; m < 2; ++m) {
-            u32x4 w = *(const u32x4 *)(p + ks * 64 + m * 32 + 8 * g);
-            int q[8];
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                q[2 * e] = quant8(bf16_lo(w[e]), qscale);
-                q[2 * e + 1] = quant8(bf16_hi(w[e]), qscale);
-            }
-            out[2 * m] = (int)pack_i8x4(q[0], q[1], q[2], q[3]);
-            out[2 * m + 1] = (int)pack_i8x4(q[4], q[5], q[6], q[7]);
-        }
-    } else {
-        const float *p = (const float *)row;
-#pragma unroll
-        for (int m = 0; m < 4; ++m) {
-            f32x4 w = *(const f32x4 *)(p + ks * 64 + m * 16 + 4 * g);
-            out[m] = (int)pack_i8x4(quant8(w[0], qscale), quant8(w[1], qscale), quant8(w[2], qscale), quant8(w[3], qscale));
-        }
-    }
-    return out;
-}
-
-__device__ __forceinline__ int requant(int y, int shift) {
-    int c = (y + (1 << (shift - 1))) >> shift;  // arithmetic shift = floor division
-    return min(max(c, -127), 127);
-}
 
 template <bool BF16, int D, int R>
 __global__ __launch_bounds__(256) void encode_kernel(const void *__restrict__ x, int64_t n_vec,
@@ -68,17 +26,8 @@ __global__ __launch_bounds__(256) void encode_kernel(const void *__restrict__ x,
     for (int64_t i = gtid; i < zero_n; i += gthreads) zero_fill[i] = 0ull;
 
     // A operand: rows of R^T for every (k-step, code block), gathered once per wavefront
-    i32x4 a[KS][CB];
-#pragma unroll
-    for (int ks = 0; ks < KS; ++ks)
-#pragma unroll
-        for (int cb = 0; cb < CB; ++cb) {
-            int b[16];
-#pragma unroll
-            for (int e = 0; e < 16; ++e) b[e] = Rm[slot_coord<BF16>(ks, g, e) * R + cb * 16 + col];
-#pragma unroll
-            for (int m = 0; m < 4; ++m) a[ks][cb][m] = (int)pack_i8x4(b[4 * m], b[4 * m + 1], b[4 * m + 2], b[4 * m + 3]);
-        }
+    CodeMatrix<BF16, D, R> cm;
+    cm.load(Rm, lane);
 
     const int64_t wave = gtid >> 6, n_waves = gthreads >> 6;
     const int64_t n_groups = (n_vec + 15) >> 4;
@@ -92,11 +41,7 @@ __global__ __launch_bounds__(256) void encode_kernel(const void *__restrict__ x,
         for (int ks = 0; ks < KS; ++ks) b[ks] = load_quantised<BF16>(row, ks, g, qscale);
 #pragma unroll
         for (int cb = 0; cb < CB; ++cb) {
-            i32x4 acc = {0, 0, 0, 0};
-#pragma unroll
-            for (int ks = 0; ks < KS; ++ks) acc = mfma_i8_16x16x64(a[ks][cb], b[ks], acc);
-            unsigned w = pack_i8x4(requant(acc[0], shift), requant(acc[1], shift), requant(acc[2], shift),
-                                   requant(acc[3], shift));
+            const unsigned w = cm.code_word(b, cb, shift);
             if (vec < n_vec) *(unsigned *)(code + vec * R + cb * 16 + 4 * g) = w;
         }
     }

@@ -13,7 +13,7 @@
 // All decisions are integer and order-independent (max / count), so the merge map is reproducible.
 #include <limits.h>
 
-#include "common.hpp"
+#include "encode_dev.hpp"
 
 namespace fastar {
 
@@ -168,35 +168,250 @@ __global__ __launch_bounds__(256) void tc_match_kernel(const int8_t *__restrict_
     if (g2 == 0 && tok < n_new && mybest != 0) atomicMax(&best[(size_t)h * n_new + tok], mybest);
 }
 
-// ---- prep ----------------------------------------------------------------------------------------------
-// Unpacks the match and clears the per-slot group records it will touch.  The same launch also leaves, per head, a
-// histogram of the live slots' ages (frame_id - stamp, 1024 bins, the last one collecting everything older) for
-// the eviction plan: a whole grid reads the stamps here, where the plan has few workgroups per head.
-constexpr int PREP_BINS = 1024;
-__global__ __launch_bounds__(256) void tc_prep_kernel(const u64 *__restrict__ best, int n_new, int C,
-                                                      int32_t *__restrict__ jstar, int32_t *__restrict__ sbest,
-                                                      u64 *__restrict__ win, int32_t *__restrict__ grp,
-                                                      const int32_t *__restrict__ len, const int32_t *__restrict__ stamp,
-                                                      int frame_id, unsigned *__restrict__ plan_scratch, int hist_word,
-                                                      int fut_word, int scratch_words) {
-    __shared__ unsigned lhist[PREP_BINS];
+// ---- match against a candidate window held in LDS --------------------------------------------------------
+// For a candidate list short enough to stage in LDS (the previous frame's slots: n_cand * (R + 8) bytes), one
+// workgroup owns 64 tokens and sees every candidate, so the arg-max is final when it ends: no atomics, no packed
+// keys to unpack, and the group records of the matched slots are cleared right here.  The eight wavefronts are
+// (token half) x (quarter of the window): each takes every fourth step of 4 x 32 candidates, the partial arg-maxima
+// meet through LDS.  The epilogue per 32 x 32 scores is plain integer ALU work, so two wavefronts per SIMD (not
+// one) are what keeps the ALUs issuing.
+// LDS: codes chunk-major ([16-byte chunk][candidate], conflict-free A-operand reads), slot ids, penalties.
+// three-input minimum in one instruction (the compiler folds a select into each two-input minimum instead)
+__device__ __forceinline__ int min3_i32(int a, int b, int c) {
+    int r;
+    asm("v_min3_i32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
+    return r;
+}
+// With ENC the kernel also is the call's encode step for its 64 tokens (probe = new key): it quantises and projects
+// their rows while the window's loads are in flight, leaves the codes in ck for the apply step, and clears the
+// eviction plan's scratch words (ps_all) for the launches behind it.
+constexpr int WIN_THREADS = 512;
+template <int R, bool ENC, bool BF16, int D>
+__global__ __launch_bounds__(WIN_THREADS) void tc_match_window_kernel(const int8_t *__restrict__ code,
+                                                              const int32_t *__restrict__ len, int C,
+                                                              const int8_t *__restrict__ cp, int n_new,
+                                                              const int32_t *__restrict__ cand, int n_cand, int metric,
+                                                              int32_t *__restrict__ jstar, int32_t *__restrict__ sbest,
+                                                              u64 *__restrict__ win, int32_t *__restrict__ grp,
+                                                              const void *__restrict__ K_new,
+                                                              const int8_t *__restrict__ Rm, float qscale, int shift,
+                                                              int8_t *__restrict__ ck, unsigned *__restrict__ ps_all,
+                                                              int ps_words) {
+    constexpr int KS = R / 32;
+    constexpr int NCH = R / 16;  // 16-byte chunks per code
+    extern __shared__ __attribute__((aligned(16))) unsigned char wlds[];
+    const int n_pad = (n_cand + 31) & ~31;
+    i32x4 *ccode = (i32x4 *)wlds;                       // [NCH][n_pad]
+    int *cslot = (int *)(wlds + (size_t)NCH * n_pad * 16);  // [n_pad]
+    int *cpen = cslot + n_pad;                          // [n_pad]
+    constexpr int SPLIT = WIN_THREADS / 128;  // wavefronts sharing one group of 32 tokens, each on its share of the window
+    __shared__ u64 partbest[SPLIT][2][32];
     const int h = blockIdx.y;
-    const int i = blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < n_new) {
-        const u64 key = best[(size_t)h * n_new + i];
+    const int L = min(len[h], C);
+    const int tid = threadIdx.x, lane = lane_id(), wave = tid >> 6;
+    const int col = lane & 31, g2 = lane >> 5;
+    const int tg = wave & 1, ch = wave >> 1;
+    const int tok = blockIdx.x * 64 + tg * 32 + col;
+    const int8_t *ch_code = code + (size_t)h * C * R;
+    __shared__ __attribute__((aligned(16))) int8_t pcode[ENC ? 64 * R : 16];
+    i32x4 bfrag[KS];
+    CodeMatrix<BF16, D, R> cm;
+    i32x4 xq[D / 64];
+    const int etok = blockIdx.x * 64 + 16 * wave + (lane & 15);  // token this lane helps to encode
+    if (ENC)
+        for (int k = blockIdx.x * WIN_THREADS + tid; k < ps_words; k += gridDim.x * WIN_THREADS) ps_all[(size_t)h * ps_words + k] = 0u;
+    if (ENC && wave < 4) {  // 16 tokens per wavefront
+        cm.load(Rm, lane);
+        const char *row = (const char *)K_new + ((size_t)h * n_new + min(etok, n_new - 1)) * (size_t)D * (BF16 ? 2 : 4);
+#pragma unroll
+        for (int ks = 0; ks < D / 64; ++ks) xq[ks] = load_quantised<BF16>(row, ks, lane >> 4, qscale);
+    } else if (!ENC) {
+        // probe codes of this wavefront's 32 tokens (B operand), in flight while the window is staged
+        const int trow = min(tok, n_new - 1);
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) bfrag[ks] = *(const i32x4 *)(cp + ((size_t)h * n_new + trow) * R + ks * 32 + 16 * g2);
+    }
+    // Staging in batches of independent loads: the slot ids of a whole batch, then the code rows they name,
+    // so a batch costs two memory round trips however many candidates it holds.
+    constexpr int BATCH = 128 / R;  // candidates per thread and batch (32 code registers)
+    for (int p0 = 0; p0 < n_pad; p0 += WIN_THREADS * BATCH) {
+        int sl[BATCH];
+#pragma unroll
+        for (int u = 0; u < BATCH; ++u) {
+            const int p = p0 + u * WIN_THREADS + tid;
+            int v = -1;
+            if (p < n_cand) {
+                v = cand[(size_t)h * n_cand + p];
+                if (v < 0 || v >= L) v = -1;
+            }
+            sl[u] = v;
+        }
+        i32x4 row[BATCH][NCH];
+#pragma unroll
+        for (int u = 0; u < BATCH; ++u)
+#pragma unroll
+            for (int c = 0; c < NCH; ++c) {
+                i32x4 v = {0, 0, 0, 0};
+                if (sl[u] >= 0) v = *(const i32x4 *)(ch_code + (size_t)sl[u] * R + c * 16);
+                row[u][c] = v;
+            }
+#pragma unroll
+        for (int u = 0; u < BATCH; ++u) {
+            const int p = p0 + u * WIN_THREADS + tid;
+            if (p < n_pad) {
+                int nn = 0;
+#pragma unroll
+                for (int c = 0; c < NCH; ++c) {
+                    ccode[c * n_pad + p] = row[u][c];
+#pragma unroll
+                    for (int m = 0; m < 4; ++m) nn = dot4_i8((unsigned)row[u][c][m], (unsigned)row[u][c][m], nn);
+                }
+                cslot[p] = sl[u];
+                cpen[p] = sl[u] >= 0 ? (metric == 0 ? -nn : 0) : -(1 << 30);  // minus the penalty
+            }
+        }
+    }
+    if (ENC && wave < 4) {
+#pragma unroll
+        for (int cb = 0; cb < R / 16; ++cb) {
+            const unsigned w = cm.code_word(xq, cb, shift);
+            *(unsigned *)(pcode + (16 * wave + (lane & 15)) * R + cb * 16 + 4 * (lane >> 4)) = w;
+            if (etok < n_new) *(unsigned *)(ck + ((size_t)h * n_new + etok) * R + cb * 16 + 4 * (lane >> 4)) = w;
+        }
+    }
+    __syncthreads();
+    if (ENC) {
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) bfrag[ks] = *(const i32x4 *)(pcode + (tg * 32 + col) * R + ks * 32 + 16 * g2);
+    }
+    // running arg-max per lane, as in the chunked kernel: 32-bit maxima, slot ids only on a new or tied best
+    int best_s = INT_MIN, best_slot = INT_MAX;
+    const int n_groups = n_pad / 32;
+    // Four groups of 32 candidates per step, their operand reads and matrix instructions issued together
+    // (a group repeated at the ragged end changes nothing: maxima and minima are idempotent).
+    constexpr int UNR = 4;
+    for (int g0 = ch * UNR; g0 < n_groups; g0 += SPLIT * UNR) {
+        i32x4 afrag[UNR][KS];
+        i32x16 acc[UNR];
+#pragma unroll
+        for (int u = 0; u < UNR; ++u) {
+            const int gi = min(g0 + u, n_groups - 1);
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) afrag[u][ks] = ccode[(2 * ks + g2) * n_pad + gi * 32 + col];
+            // the accumulator starts from minus the penalty of its rows: the matrix unit does the subtraction
+#pragma unroll
+            for (int q4 = 0; q4 < 4; ++q4) {
+                const i32x4 np = *(const i32x4 *)(&cpen[gi * 32 + 8 * q4 + 4 * g2]);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) acc[u][4 * q4 + e] = np[e];
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < UNR; ++u) {
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) acc[u] = mfma_i8_32x32x32(afrag[u][ks], bfrag[ks], acc[u]);
+            if (metric == 0) {  // 2 * dot: the product is accumulated twice
+#pragma unroll
+                for (int ks = 0; ks < KS; ++ks) acc[u] = mfma_i8_32x32x32(afrag[u][ks], bfrag[ks], acc[u]);
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < UNR; ++u) {
+            const int gi = min(g0 + u, n_groups - 1);
+            int m = INT_MIN;
+#pragma unroll
+            for (int e = 0; e < 16; ++e) m = max(m, acc[u][e]);
+            if (__any(m >= best_s && m > -(1 << 29))) {
+                int sl = INT_MAX;
+#pragma unroll
+                for (int q4 = 0; q4 < 4; ++q4) {
+                    const i32x4 ids = *(const i32x4 *)(&cslot[gi * 32 + 8 * q4 + 4 * g2]);
+                    int t[4];
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) t[e] = acc[u][4 * q4 + e] == m ? ids[e] : INT_MAX;
+                    sl = min3_i32(min3_i32(sl, t[0], t[1]), t[2], t[3]);
+                }
+                if (m > -(1 << 29)) {
+                    if (m > best_s) { best_s = m; best_slot = sl; }
+                    else if (m == best_s) best_slot = min(best_slot, sl);
+                }
+            }
+        }
+    }
+    u64 mybest = 0;
+    if (best_s != INT_MIN)
+        mybest = ((u64)(unsigned)(best_s + SCORE_BIAS) << 32) | (u64)(0xFFFFFFFFu - (unsigned)best_slot);
+    {
+        const unsigned lo = shfl_xor((unsigned)mybest, 32), hi = shfl_xor((unsigned)(mybest >> 32), 32);
+        const u64 other = ((u64)hi << 32) | lo;
+        if (other > mybest) mybest = other;
+    }
+    if (g2 == 0) partbest[ch][tg][col] = mybest;
+    __syncthreads();
+    if (ch == 0 && g2 == 0 && tok < n_new) {
+#pragma unroll
+        for (int c = 1; c < SPLIT; ++c) {
+            const u64 other = partbest[c][tg][col];
+            if (other > mybest) mybest = other;
+        }
         int j = -1, S = 0;
-        if (key != 0) {
-            j = (int)(0xFFFFFFFFu - (unsigned)key);
-            S = (int)(unsigned)(key >> 32) - SCORE_BIAS;
+        if (mybest != 0) {
+            j = (int)(0xFFFFFFFFu - (unsigned)mybest);
+            S = (int)(unsigned)(mybest >> 32) - SCORE_BIAS;
             win[(size_t)h * C + j] = 0;
             grp[(size_t)h * C + j] = 0;
         }
-        jstar[(size_t)h * n_new + i] = j;
-        sbest[(size_t)h * n_new + i] = S;
+        jstar[(size_t)h * n_new + tok] = j;
+        sbest[(size_t)h * n_new + tok] = S;
     }
+}
+static size_t match_window_lds(int n_cand, int r) { return (size_t)((n_cand + 31) & ~31) * (size_t)(r + 8); }
+constexpr size_t WINDOW_LDS_MAX = 150 * 1024;
+template <int R, bool ENC, bool BF16, int D, typename... Args>
+static int launch_match_window(dim3 grid, size_t lds, hipStream_t s, Args... args) {
+    static bool attr_set = false;  // once per instantiation: allow more than the default 64 KB of dynamic LDS
+    if (!attr_set) {
+        if (hipFuncSetAttribute((const void *)tc_match_window_kernel<R, ENC, BF16, D>,
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)WINDOW_LDS_MAX) != hipSuccess)
+            return FASTAR_ERR_HIP;
+        attr_set = true;
+    }
+    hipLaunchKernelGGL((tc_match_window_kernel<R, ENC, BF16, D>), grid, dim3(WIN_THREADS), lds, s, args...);
+    FASTAR_LAUNCH_CHECK();
+    return FASTAR_OK;
+}
+
+// ---- prep (only behind the chunked match, which leaves packed arg-max keys) ---------------------------------
+// Unpacks the match and clears the per-slot group records it will touch.
+__global__ __launch_bounds__(256) void tc_prep_kernel(const u64 *__restrict__ best, int n_new, int C,
+                                                      int32_t *__restrict__ jstar, int32_t *__restrict__ sbest,
+                                                      u64 *__restrict__ win, int32_t *__restrict__ grp) {
+    const int h = blockIdx.y;
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n_new) return;
+    const u64 key = best[(size_t)h * n_new + i];
+    int j = -1, S = 0;
+    if (key != 0) {
+        j = (int)(0xFFFFFFFFu - (unsigned)key);
+        S = (int)(unsigned)(key >> 32) - SCORE_BIAS;
+        win[(size_t)h * C + j] = 0;
+        grp[(size_t)h * C + j] = 0;
+    }
+    jstar[(size_t)h * n_new + i] = j;
+    sbest[(size_t)h * n_new + i] = S;
+}
+
+// Per head, a histogram of the live slots' ages (frame_id - stamp, 1024 bins, the last one collecting everything
+// older) for the eviction plan: the verify launch, a whole grid, reads the stamps, where the plan has few
+// workgroups per head.  Every workgroup of the launch adds its slice of the slots.  Called by whole workgroups.
+constexpr int AGE_BINS = 1024;
+__device__ __forceinline__ void age_histogram_slice(const int32_t *__restrict__ len, const int32_t *__restrict__ stamp,
+                                                    int C, int n_new, int frame_id, unsigned *__restrict__ ps,
+                                                    int hist_word, int fut_word, unsigned *lhist) {
+    const int h = blockIdx.y;
     const int L = min(len[h], C);
     if (L + n_new <= C) return;  // uniform over the head: no eviction can be needed
-    for (int k = threadIdx.x; k < PREP_BINS; k += blockDim.x) lhist[k] = 0;
+    for (int k = threadIdx.x; k < AGE_BINS; k += blockDim.x) lhist[k] = 0;
     __syncthreads();
     const int chunk = (L + gridDim.x - 1) / gridDim.x;
     const int j0 = blockIdx.x * chunk, j1 = min(j0 + chunk, L);
@@ -206,11 +421,10 @@ __global__ __launch_bounds__(256) void tc_prep_kernel(const u64 *__restrict__ be
         const int sj = st[j];
         if (sj > frame_id) future = true;
         const unsigned age = (unsigned)frame_id - (unsigned)sj;
-        atomicAdd(&lhist[min(age, (unsigned)(PREP_BINS - 1))], 1u);
+        atomicAdd(&lhist[min(age, (unsigned)(AGE_BINS - 1))], 1u);
     }
     __syncthreads();
-    unsigned *ps = plan_scratch + (size_t)h * scratch_words;
-    for (int k = threadIdx.x; k < PREP_BINS; k += blockDim.x)
+    for (int k = threadIdx.x; k < AGE_BINS; k += blockDim.x)
         if (lhist[k]) atomicAdd(&ps[hist_word + k], lhist[k]);
     if (__any(future) && lane_id() == 0) atomicOr(&ps[fut_word], 1u);
 }
@@ -329,17 +543,43 @@ __device__ __forceinline__ int group16_sum(int v) {
 
 // ---- verify --------------------------------------------------------------------------------------------
 template <bool BF16, int D>
+__device__ __forceinline__ void verify_token(const void *__restrict__ K, const void *__restrict__ K_new,
+                                             const int8_t *__restrict__ cp, int r, int C, int n_new, float qscale,
+                                             int metric, int tau2_q16, const int32_t *__restrict__ jstar,
+                                             const int32_t *__restrict__ sbest, u64 *__restrict__ win,
+                                             int32_t *__restrict__ grp, uint8_t *__restrict__ merged, int h, int i,
+                                             int l16);
+
+template <bool BF16, int D>
 __global__ __launch_bounds__(256) void tc_verify_kernel(const void *__restrict__ K, const void *__restrict__ K_new,
                                                         const int8_t *__restrict__ cp, int r, int C, int n_new,
                                                         float qscale, int metric, int tau2_q16,
                                                         const int32_t *__restrict__ jstar,
                                                         const int32_t *__restrict__ sbest, u64 *__restrict__ win,
-                                                        int32_t *__restrict__ grp, uint8_t *__restrict__ merged) {
+                                                        int32_t *__restrict__ grp, uint8_t *__restrict__ merged,
+                                                        const int32_t *__restrict__ len,
+                                                        const int32_t *__restrict__ stamp, int frame_id,
+                                                        unsigned *__restrict__ plan_scratch, int hist_word,
+                                                        int fut_word, int scratch_words) {
     typedef RowPiece<BF16, D> RP;
+    __shared__ unsigned lhist[AGE_BINS];
     const int h = blockIdx.y;
     const int l16 = threadIdx.x & 15;
     const int i = blockIdx.x * (blockDim.x / 16) + (threadIdx.x >> 4);
-    if (i >= n_new) return;  // whole 16-lane group leaves together
+    if (i < n_new) verify_token<BF16, D>(K, K_new, cp, r, C, n_new, qscale, metric, tau2_q16, jstar, sbest, win, grp,
+                                         merged, h, i, l16);  // whole 16-lane groups
+    age_histogram_slice(len, stamp, C, n_new, frame_id, plan_scratch + (size_t)h * scratch_words, hist_word, fut_word,
+                        lhist);
+}
+
+template <bool BF16, int D>
+__device__ __forceinline__ void verify_token(const void *__restrict__ K, const void *__restrict__ K_new,
+                                             const int8_t *__restrict__ cp, int r, int C, int n_new, float qscale,
+                                             int metric, int tau2_q16, const int32_t *__restrict__ jstar,
+                                             const int32_t *__restrict__ sbest, u64 *__restrict__ win,
+                                             int32_t *__restrict__ grp, uint8_t *__restrict__ merged, int h, int i,
+                                             int l16) {
+    typedef RowPiece<BF16, D> RP;
     const size_t ti = (size_t)h * n_new + i;
     // everything addressed by the token first (one round trip), then the matched slot's key row
     const int j = jstar[ti];
@@ -383,7 +623,7 @@ __global__ __launch_bounds__(256) void tc_verify_kernel(const void *__restrict__
 // split the slots into NB contiguous ranges and find the e oldest untouched slots together:
 //   threshold key T and the number of ties to take -> counts per workgroup -> ordered compaction, victims in
 //   ascending slot order.
-// T is normally read off the age histogram tc_prep_kernel left (no communication); otherwise: range of the keys ->
+// T is normally read off the age histogram the verify launch left (no communication); otherwise: range of the keys ->
 // histogram over that range (1024 bins, a second one inside the threshold bin when the range is wider).
 // Between phases the workgroups of a head meet at a counter in global memory (head_barrier).  The grid is
 // kept small enough (NB * H <= PLAN_MAX_GRID workgroups of 256 threads) to be resident at once, and every wait
@@ -394,13 +634,13 @@ constexpr int PLAN_NB_MAX = 16;
 constexpr int PLAN_MAX_GRID = 1024;
 constexpr int PLAN_BINS = 1024;
 constexpr int PLAN_SPIN_LIMIT = 1 << 20;
-// per-head scratch in global memory (32-bit words), zeroed by tc_prep_kernel
+// per-head scratch in global memory (32-bit words), zeroed by the encode launch
 constexpr int PS_BAR = 0;                       // 4 arrival counters
 constexpr int PS_MAXK = 4, PS_MAXNK = 5;        // max key, max ~key
 constexpr int PS_TOT = 6, PS_ERR = 7;           // eligible slots, bounded wait ran out
 constexpr int PS_BLK = 8;                       // per workgroup, 64 bits: valid | count key > T | count key == T
 constexpr int PS_FUT = 40;                      // some live slot carries a stamp above this call's frame id
-constexpr int PS_HIST = 64;                     // histograms of PLAN_BINS: ages (from tc_prep_kernel), two select levels
+constexpr int PS_HIST = 64;                     // histograms of PLAN_BINS: ages (from the verify launch), two select levels
 constexpr int PS_STRIDE = PS_HIST + 3 * PLAN_BINS;
 static_assert(PS_STRIDE == PLAN_SCRATCH_WORDS, "workspace layout");
 
@@ -632,7 +872,7 @@ __global__ __launch_bounds__(PLAN_THREADS) void tc_plan_kernel(const int32_t *__
         };
         bool take_all = false;
         unsigned T = 0, need = (unsigned)e, cnt_el = 0;
-        // Fast path: tc_prep_kernel left the histogram of all live slots' ages; subtract the slots touched in this
+        // Fast path: the verify launch left the histogram of all live slots' ages; subtract the slots touched in this
         // frame (each counted once, by the token that represents its group) and read the threshold off it.  Every
         // workgroup does this on the same data, so no meeting is needed.  It does not apply when a stamp lies in
         // the future or the threshold falls into the last bin (ages >= 1023 lumped together).
@@ -922,6 +1162,7 @@ extern "C" int tempcache_compress(const fastar_cache *cache, const fastar_codec 
     if (H <= 0 || C <= 0 || n_new <= 0 || (metric != 0 && metric != 1)) return FASTAR_ERR_INVALID_ARG;
     if (tau2_q16 < 0 || tau2_q16 > 131072) return FASTAR_ERR_INVALID_ARG;
     if (cand && n_cand <= 0) return FASTAR_ERR_INVALID_ARG;
+    if (codec->shift < 1 || codec->shift > 16) return FASTAR_ERR_INVALID_ARG;
     if (dtype != FASTAR_F32 && dtype != FASTAR_BF16) return FASTAR_ERR_INVALID_ARG;
     if ((d != 64 && d != 128) || (r != 32 && r != 64)) return FASTAR_ERR_UNSUPPORTED;
     const int nb = plan_nb(H, C);
@@ -944,14 +1185,35 @@ extern "C" int tempcache_compress(const fastar_cache *cache, const fastar_codec 
     int32_t *grp = (int32_t *)(base + w.grp);
     const int64_t T = (int64_t)H * n_new;
 
-    const int64_t zero_words = (int64_t)((w.ps - w.best) / 8) + (int64_t)H * PLAN_SCRATCH_WORDS / 2;  // best .. end of ps
-    int rc = encode_launch(K_new, dtype, T, d, codec, r, ck, best, zero_words, s);
-    if (rc != FASTAR_OK) return rc;
-    if (P_new) {
-        rc = encode_launch(P_new, dtype, T, d, codec, r, cp, nullptr, 0, s);
+    const size_t win_lds = cand ? match_window_lds(n_cand, r) : 0;
+    const bool window = cand && win_lds <= WINDOW_LDS_MAX;
+    const bool fused_encode = window && !P_new;  // the match kernel encodes its own probes
+    if (!fused_encode) {
+        const int64_t zero_words = (int64_t)((w.ps - w.best) / 8) + (int64_t)H * PLAN_SCRATCH_WORDS / 2;  // best .. end of ps
+        int rc = encode_launch(K_new, dtype, T, d, codec, r, ck, best, zero_words, s);
         if (rc != FASTAR_OK) return rc;
+        if (P_new) {
+            rc = encode_launch(P_new, dtype, T, d, codec, r, cp, nullptr, 0, s);
+            if (rc != FASTAR_OK) return rc;
+        }
     }
-    {
+    if (window) {
+        // the whole candidate window fits one workgroup's LDS: final arg-max per token in one launch
+        const dim3 grid((n_new + 63) / 64, H);
+        const bool bf = dtype == FASTAR_BF16;
+        int rc = FASTAR_OK;
+#define FASTAR_WIN(RR, ENC, BF, DD)                                                                                  \
+    rc = launch_match_window<RR, ENC, BF, DD>(grid, win_lds, s, cache->code, cache->len, C, cp, n_new, cand, n_cand, \
+                                              metric, jstar, sbest, win, grp, K_new, codec->R, codec->qscale,         \
+                                              codec->shift, ck, plan_scratch, (int)PS_STRIDE)
+        if (!fused_encode) { if (r == 32) FASTAR_WIN(32, false, true, 128); else FASTAR_WIN(64, false, true, 128); }
+        else if (r == 32 && d == 128) { if (bf) FASTAR_WIN(32, true, true, 128); else FASTAR_WIN(32, true, false, 128); }
+        else if (r == 32) { if (bf) FASTAR_WIN(32, true, true, 64); else FASTAR_WIN(32, true, false, 64); }
+        else if (d == 128) { if (bf) FASTAR_WIN(64, true, true, 128); else FASTAR_WIN(64, true, false, 128); }
+        else { if (bf) FASTAR_WIN(64, true, true, 64); else FASTAR_WIN(64, true, false, 64); }
+#undef FASTAR_WIN
+        if (rc != FASTAR_OK) return rc;
+    } else {
         const int n_pos_cap = cand ? n_cand : C;
         const int chunk = n_pos_cap <= 4096 ? 64 : 256;
         dim3 grid((n_new + 127) / 128, (n_pos_cap + chunk - 1) / chunk, H);
@@ -964,15 +1226,10 @@ extern "C" int tempcache_compress(const fastar_cache *cache, const fastar_codec 
         else FASTAR_MATCH(64, 256);
 #undef FASTAR_MATCH
         FASTAR_LAUNCH_CHECK();
+        hipLaunchKernelGGL(tc_prep_kernel, dim3((n_new + 255) / 256, H), dim3(256), 0, s, best, n_new, C, jstar, sbest,
+                           win, grp);
+        FASTAR_LAUNCH_CHECK();
     }
-    {
-        int gx = (n_new + 255) / 256;
-        const int gslots = (C + 1023) / 1024 < 32 ? (C + 1023) / 1024 : 32;   // enough workgroups to read the stamps
-        if (gx < gslots) gx = gslots;
-        hipLaunchKernelGGL(tc_prep_kernel, dim3(gx, H), dim3(256), 0, s, best, n_new, C, jstar, sbest, win, grp,
-                           cache->len, cache->stamp, frame_id, plan_scratch, PS_HIST, PS_FUT, PS_STRIDE);
-    }
-    FASTAR_LAUNCH_CHECK();
     const dim3 tgrid((n_new + 15) / 16, H);
     const bool bf = dtype == FASTAR_BF16;
 #define FASTAR_TC(KERNEL, ...)                                                                          \
@@ -983,7 +1240,7 @@ extern "C" int tempcache_compress(const fastar_cache *cache, const fastar_codec 
         else hipLaunchKernelGGL((KERNEL<false, 64>), tgrid, dim3(256), 0, s, __VA_ARGS__);                       \
     } while (0)
     FASTAR_TC(tc_verify_kernel, cache->K, K_new, cp, r, C, n_new, codec->qscale, metric, tau2_q16, jstar, sbest, win, grp,
-              merged);
+              merged, cache->len, cache->stamp, frame_id, plan_scratch, PS_HIST, PS_FUT, PS_STRIDE);
     FASTAR_LAUNCH_CHECK();
     hipLaunchKernelGGL(tc_plan_kernel, dim3(nb + 1, H), dim3(PLAN_THREADS), plan_lds_bytes(C, nb), s, cache->len, cache->stamp,
                        C, n_new, frame_id, jstar, merged, win, rank, victims, hs, stats, plan_scratch);
