@@ -136,6 +136,25 @@ class ChunkPipeline:
                            out=self.Ox, want_lse=False)
         mark("attn_cross")
 
+    def dense_equivalent_ms(self, Q, reps=3):
+        """The same attention kernel with every live key block selected (the dense limit of the sparse call)."""
+        t = self.t
+        n_live = (int(self.cache.len.max().item()) + self.BK - 1) // self.BK
+        sel = t.arange(n_live, dtype=t.int32, device=Q.device).repeat(self.H, self.n_qb, 1).contiguous()
+        nsel = t.full((self.H, self.n_qb), n_live, dtype=t.int32, device=Q.device)
+        O = t.empty_like(Q)
+        lse = t.empty(Q.shape[:2], dtype=t.float32, device=Q.device)
+        self.fa.sparse_attn_fwd(Q, self.cache.K, self.cache.V, self.cache.cnt, self.cache.len, sel, nsel, self.BQ,
+                                self.BK, self.scale, out=(O, lse))
+        e0, e1 = t.cuda.Event(enable_timing=True), t.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            self.fa.sparse_attn_fwd(Q, self.cache.K, self.cache.V, self.cache.cnt, self.cache.len, sel, nsel, self.BQ,
+                                    self.BK, self.scale, out=(O, lse))
+        e1.record()
+        t.cuda.synchronize()
+        return e0.elapsed_time(e1) / reps, n_live
+
     def attended_flops(self):
         """4 * d * sum over (head, query) of the live keys in the selected blocks, for the current selection."""
         t = self.t
@@ -334,6 +353,7 @@ def main():
                 evs[name] = e
         pipe.step(*dev_chunks[args.warmup + s], ev=mark)
         attn_events.append(evs)
+    t_enqueued = time.perf_counter()
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     ms_per_step = (t1 - t0) * 1e3 / args.steps
@@ -368,6 +388,7 @@ def main():
     flops_last = flops_timed
     tflops = flops_last / (attn_ms * 1e-3) / 1e12
     len_final = to_host(pipe.cache.len).tolist()
+    dense_ms, dense_blocks = pipe.dense_equivalent_ms(dev_chunks[args.warmup + args.steps - 1][1])
 
     result = {
         "metric": "sparse-attn ms per generated chunk", "value": round(ms_per_step, 4), "unit": "ms/chunk",
@@ -389,7 +410,11 @@ def main():
                      "frac": round(tflops / PEAK_BF16_TFLOPS, 4),
                      "traffic": profiled_traffic_bytes() if args.workload == "cfg2" else None,
                      "flops_per_launch": flops_last, "avg_launch_ms": round(attn_ms, 4)},
+        "dense_equivalent": {"ms": round(dense_ms, 4), "key_blocks": dense_blocks,
+                             "speedup_of_sparse": round(dense_ms / attn_ms, 2),
+                             "note": "same kernel, every live key block of the final cache selected"},
         "host_gen_s": round(t_gen, 1),
+        "host_enqueue_ms_per_step": round((t_enqueued - t0) * 1e3 / args.steps, 4),
     }
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(cfg, pipe, prefill_host, chunks, ps, n_cpu_heads, to_host, sign_h, args.code_shift)

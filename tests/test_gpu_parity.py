@@ -326,6 +326,52 @@ def test_tempcache_eviction_on_a_full_synthetic_cache(C, n_stamps):
     assert_cache_equal(host_cache(gpu), ref, VTOL["fp32"])
 
 
+@pytest.mark.parametrize("dtype,d,r,n_cand,probe,metric", [
+    ("bf16", 128, 32, 700, False, 0), ("bf16", 128, 64, 700, False, 0), ("bf16", 64, 32, 37, False, 1),
+    ("bf16", 64, 64, 1000, False, 0), ("fp32", 128, 32, 1000, False, 0), ("fp32", 128, 64, 333, False, 1),
+    ("fp32", 64, 32, 2100, False, 0), ("fp32", 64, 64, 64, False, 0),          # window in LDS, probes encoded in-kernel
+    ("bf16", 128, 32, 700, True, 1), ("fp32", 64, 64, 1000, True, 0),          # window in LDS, separate probes
+    ("bf16", 128, 32, 4000, False, 0), ("fp32", 64, 64, 2500, True, 0),        # window too large for LDS: chunked match
+    ("bf16", 128, 64, 0, False, 0), ("fp32", 64, 32, 0, True, 1)])             # no list: every live slot
+def test_tempcache_every_match_path_bit_exact(dtype, d, r, n_cand, probe, metric):
+    # one call on a random cache: ragged token count, candidate lists with repeats, ids past the live length and -1
+    rng = np.random.default_rng(d + r + n_cand)
+    H, T, C = 2, 203, 2600
+    codec = make_codec(0, 9, d, r)
+    as_dt = lambda a: to_storage(a.astype(np.float32), dtype)
+    ref = oracle.Cache.empty(H, C, d, r, dtype)
+    ref.K[:] = as_dt(rng.standard_normal((H, C, d)))
+    ref.V[:] = as_dt(rng.standard_normal((H, C, d)))
+    ref.code[:] = oracle.encode(ref.K, codec.R, codec.qscale, codec.shift)
+    ref.cnt[:] = rng.integers(1, 4, size=(H, C))
+    ref.stamp[:] = rng.integers(0, 9, size=(H, C))
+    ref.len[:] = [2300, 1999]
+    gpu = dev_cache(ref)
+    K_new = as_dt(rng.standard_normal((H, T, d)))
+    src = rng.integers(0, 1900, size=(H, T))
+    for h in range(H):
+        K_new[h, :150] = ref.K[h, src[h, :150]]                  # most of the frame repeats live slots
+    V_new = as_dt(rng.standard_normal((H, T, d)))
+    P_new = as_dt(np.where(rng.random((H, T, 1)) < 0.8, to_f32(K_new), rng.standard_normal((H, T, d)))) if probe else None
+    cand = None
+    if n_cand:
+        cand = rng.integers(0, 2350, size=(H, n_cand)).astype(np.int32)   # some ids are past the live length
+        cand[:, : min(150, n_cand)] = src[:, : min(150, n_cand)]
+        cand[:, ::17] = -1
+        cand[:, 5::29] = cand[:, 4::29][:, : cand[:, 5::29].shape[1]]     # repeated ids
+    args = dict(cand=cand, metric=metric, tau2_q16=TAU2(0.9), frame_id=9)
+    mm_r, mg_r, st_r = oracle.tempcache_compress(ref, codec.R, codec.qscale, codec.shift, K_new, V_new, P_new=P_new, **args)
+    args["cand"] = None if cand is None else to_dev(cand)
+    mm_g, mg_g, st_g = fa.tempcache_compress(gpu, dev_codec(codec), to_dev(K_new), to_dev(V_new),
+                                             P_new=None if P_new is None else to_dev(P_new), **args)
+    sync()
+    assert mg_r.sum() > 50                                        # the case does merge
+    assert np.array_equal(to_host(mg_g), mg_r)
+    assert np.array_equal(to_host(mm_g), mm_r)
+    assert np.array_equal(to_host(st_g), st_r)
+    assert_cache_equal(host_cache(gpu), ref, VTOL[dtype])
+
+
 def test_tempcache_whole_cache_match_and_inner_product_probe():
     run_rollout("cfg1", 4, 5 * 256, 0.9, windowed=False)
     run_rollout("cfg1", 4, 5 * 256, 0.9, windowed=True, metric=1, probe_queries=True)
