@@ -45,6 +45,8 @@ def parse():
     ap.add_argument("--prefill-frames", type=int, default=None, help="frames merged into the cache before timing")
     ap.add_argument("--cap-frames", type=int, default=None, help="cache capacity in frames of slots")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-dense-equivalent", action="store_true",
+                    help="skip the leg that times the attention kernel with every live key block selected")
     ap.add_argument("--cpu-heads", type=int, default=2, help="heads of the last chunk replayed on the CPU oracle")
     ap.add_argument("--sweep", action="store_true", help="long-rollout sweep (cfg3): per-step latency and footprint")
     ap.add_argument("--sweep-frames", type=int, default=120)
@@ -388,7 +390,7 @@ def main():
     flops_last = flops_timed
     tflops = flops_last / (attn_ms * 1e-3) / 1e12
     len_final = to_host(pipe.cache.len).tolist()
-    dense_ms, dense_blocks = pipe.dense_equivalent_ms(dev_chunks[args.warmup + args.steps - 1][1])
+    dense = None if args.no_dense_equivalent else pipe.dense_equivalent_ms(dev_chunks[args.warmup + args.steps - 1][1])
 
     result = {
         "metric": "sparse-attn ms per generated chunk", "value": round(ms_per_step, 4), "unit": "ms/chunk",
@@ -410,9 +412,9 @@ def main():
                      "frac": round(tflops / PEAK_BF16_TFLOPS, 4),
                      "traffic": profiled_traffic_bytes() if args.workload == "cfg2" else None,
                      "flops_per_launch": flops_last, "avg_launch_ms": round(attn_ms, 4)},
-        "dense_equivalent": {"ms": round(dense_ms, 4), "key_blocks": dense_blocks,
-                             "speedup_of_sparse": round(dense_ms / attn_ms, 2),
-                             "note": "same kernel, every live key block of the final cache selected"},
+        "dense_equivalent": None if dense is None else {
+            "ms": round(dense[0], 4), "key_blocks": dense[1], "speedup_of_sparse": round(dense[0] / attn_ms, 2),
+            "note": "same kernel, every live key block of the final cache selected"},
         "host_gen_s": round(t_gen, 1),
         "host_enqueue_ms_per_step": round((t_enqueued - t0) * 1e3 / args.steps, 4),
     }

@@ -1,11 +1,12 @@
 // TempCache (Sec. 5.2 of the paper, Lemma 1): merge one frame of new keys/values into the bounded
 // per-head cache.  The steps, each a kernel on the caller's stream:
-//   encode        codes of the new keys (and of the probes when they differ)             -> encode.hip
-//   tc_match      top-1 candidate slot of every token on exact integer code scores (int8 matrix cores,
-//                 running arg-max per lane, 64-bit atomicMax across candidate chunks)
-//   tc_prep       unpack the match, clear the per-slot group records it will touch
+//   tc_match_window  (candidate list that fits LDS, probe = new key: the usual call) codes of the new keys AND the
+//                 top-1 candidate slot of every token on exact integer code scores (int8 matrix cores), final in
+//                 one launch; clears the group records of the matched slots
+//   otherwise     encode (encode.hip) -> tc_match (candidate chunks over many workgroups, 64-bit atomicMax) ->
+//                 tc_prep (unpack the match, clear the group records it will touch)
 //   tc_verify     cosine test on the 8-bit quantised full-width keys as an int64 inequality; joiners
-//                 register in their slot's group record (count, best joiner)
+//                 register in their slot's group record (count, best joiner); age histogram of the live slots
 //   tc_plan       per head: ranks of the unmerged tokens (ballot + prefix sum), evictions needed,
 //                 victims = oldest untouched slots (histogram select over several workgroups, ordered compaction)
 //   tc_apply      representative key, mean value, multiplicity, code, stamp of merged slots; appended
