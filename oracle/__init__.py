@@ -104,8 +104,9 @@ class Cache:
 
 
 def tempcache_compress(cache: Cache, R, qscale, shift, K_new, V_new, P_new=None, cand=None, metric: int = 0,
-                       tau2_q16: int = 53084, frame_id: int = 0):
-    """Merge one frame of tokens into ``cache`` in place.  Returns (merge_map, merged, stats)."""
+                       tau2_q16: int = 53084, frame_id: int = 0, rep_mode: int = 0):
+    """Merge one frame of tokens into ``cache`` in place.  Returns (merge_map, merged, stats).
+    rep_mode: 0 keeps the last key of a merged group, 1 its multiplicity-weighted mean key."""
     H, C, d = cache.K.shape
     r = cache.code.shape[2]
     K_new = _c(K_new)
@@ -131,7 +132,7 @@ def tempcache_compress(cache: Cache, R, qscale, shift, K_new, V_new, P_new=None,
         _p(cache.K), _p(cache.V), _p(cache.code), _p(cache.cnt), _p(cache.stamp), _p(cache.len), H, C, d, r,
         _dtype_code(cache.K), _p(R), ctypes.c_float(float(np.float32(qscale))), int(shift),
         _p(K_new), _p(V_new), _p(P_new), n_new, _p(cand), n_cand, int(metric), ctypes.c_int32(int(tau2_q16)),
-        ctypes.c_int32(int(frame_id)), _p(merge_map), _p(merged), _p(stats))
+        ctypes.c_int32(int(frame_id)), int(rep_mode), _p(merge_map), _p(merged), _p(stats))
     _check(rc, "oracle_tempcache_compress")
     return merge_map, merged, stats
 

@@ -14,7 +14,8 @@
  *                              top-1 neighbour of every new token among cached keys, merge when
  *                              the key similarity passes a threshold, keep the most recent key,
  *                              mean value and multiplicity (Lemma 1; appendix Eqs. for the group
- *                              mean value and the biased logit).
+ *                              mean value and the biased logit); rep_mode 1 keeps the mean key instead
+ *                              (appendix ablation "Representative selection in KV merging").
  *   oracle_ann_select_self     Sec. 5.4 (AnnSA): keys a query block attends to, ranked by code score.
  *   oracle_ann_select_cross    Sec. 5.3 (AnnCA): prompt tokens with a neighbouring query in the block.
  *   oracle_encode_sign         Sec. 5.1, LSH paragraph: one hash bit per random projection (its sign).
@@ -26,7 +27,8 @@
  *
  * Parity pins (tests/test_oracle_*.py): dense softmax attention written independently in
  * numpy, Lemma 1 on exact duplicates, brute-force nearest neighbours and top-k, closed-form
- * code values, identity merge, monotonicity in the threshold; for the sign codes a worked example,
+ * code values, identity merge, monotonicity in the threshold, a hand-computed mean key and its
+ * coincidence with the last key on exact duplicates; for the sign codes a worked example,
  * sign-flip and scaling invariances, the 1 - angle/pi law of random hyperplanes, brute force in Python.  The eviction policy of
  * oracle_tempcache_compress (what to do when the bounded cache is full) is not in the paper:
  * it is checked by invariants only and is "parity unpinned".
@@ -125,6 +127,12 @@ static int64_t dot_i8(const int8_t *a, const int8_t *b, int r) {
  * metric:  0 => S = 2 cp.code_j - |code_j|^2 (nearest in code space), 1 => S = cp.code_j
  * tau2_q16 = rint(tau^2 * 65536); merge iff dot > 0 and dot^2 * 65536 >= tau2_q16 * |a|^2 |b|^2 on the
  *          8-bit quantised full-width keys a (new) and b (cached)
+ * rep_mode: representative key of a merged group (appendix, "Representative selection in KV merging"):
+ *          0 => last key (the method's choice: the most recent member, here the group's winner of this frame),
+ *          1 => mean key: the multiplicity-weighted mean of the group's keys.  The stored mean feeds later integer
+ *               decisions (codes, the cosine test), so its arithmetic is fixed: float32, cnt * K_old first, then the
+ *               members' keys added in ascending token order, one float32 division, one rounding to the storage
+ *               type; the slot's code is the code of that stored key.
  * out:     merge_map [H,n_new] destination slot or -1 (dropped); merged [H,n_new] 0/1;
  *          stats [H,8] = len', n_merged, n_appended, n_evicted, n_dropped, 0, 0, 0
  */
@@ -132,10 +140,11 @@ int oracle_tempcache_compress(void *K, void *V, int8_t *code, int32_t *cnt, int3
                               int C, int d, int r, int dtype, const int8_t *R, float qscale, int shift,
                               const void *K_new, const void *V_new, const void *P_new, int n_new,
                               const int32_t *cand, int n_cand, int metric, int32_t tau2_q16, int32_t frame_id,
-                              int32_t *merge_map, uint8_t *merged, int32_t *stats) {
+                              int rep_mode, int32_t *merge_map, uint8_t *merged, int32_t *stats) {
     if (!K || !V || !code || !cnt || !stamp || !len || !R || !K_new || !V_new || !merge_map || !merged || !stats)
         return -1;
     if (H <= 0 || C <= 0 || d <= 0 || r <= 0 || n_new < 0 || (metric != 0 && metric != 1)) return -1;
+    if (rep_mode != 0 && rep_mode != 1) return -1;
     if (!P_new) P_new = K_new;
     int err = 0;
 #pragma omp parallel for schedule(dynamic, 1)
@@ -255,9 +264,23 @@ int oracle_tempcache_compress(void *K, void *V, int8_t *code, int32_t *cnt, int3
                 for (int t = 0; t < d; ++t)
                     store_val(V, dtype, (cb + j) * d + t,
                               acc[(int64_t)row_of[j] * d + t] / (double)(cnt[cb + j] + group[j]));
+                if (rep_mode == 0) {
+                    copy_row(K, cb + j, K_new, nb + winner[j], d, dtype);
+                    memcpy(code + (cb + j) * r, ck + (int64_t)winner[j] * r, (size_t)r);
+                } else {
+                    for (int t = 0; t < d; ++t) {
+                        volatile float ksum = (float)cnt[cb + j] * load_f32(K, dtype, (cb + j) * d + t);
+                        for (int i = 0; i < n_new; ++i)
+                            if (merged[nb + i] && jstar[i] == j) ksum = ksum + load_f32(K_new, dtype, (nb + i) * d + t);
+                        volatile float kmean = ksum / (float)(cnt[cb + j] + group[j]);
+                        if (dtype == 0)
+                            ((float *)K)[(cb + j) * d + t] = kmean;
+                        else
+                            ((uint16_t *)K)[(cb + j) * d + t] = f32_to_bf16(kmean);
+                    }
+                    encode_vec(K, dtype, (cb + j) * d, d, R, r, qscale, shift, code + (cb + j) * r);
+                }
                 cnt[cb + j] += group[j];
-                copy_row(K, cb + j, K_new, nb + winner[j], d, dtype);
-                memcpy(code + (cb + j) * r, ck + (int64_t)winner[j] * r, (size_t)r);
                 stamp[cb + j] = frame_id;
             }
             free(acc);

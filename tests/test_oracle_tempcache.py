@@ -173,6 +173,89 @@ def test_several_tokens_joining_one_slot_mean_value_count_and_last_key_represent
     assert mm[0].tolist() == [1, 0, 0] and cache2.cnt[0, :2].tolist() == [3, 2]
 
 
+def test_mean_key_representative_worked_example_and_multiplicity_weights():
+    # appendix, representative-selection ablation: mean-key averages the keys of the group.  Hand-computed values
+    # (all exactly representable, so float32 arithmetic is exact): slot 0 holds `base` with multiplicity 1.
+    d, r = 8, 4
+    R = np.array([[1, 1, 1, 1], [1, -1, 1, -1], [1, 1, -1, -1], [1, -1, -1, 1]] * 2, np.int8)
+    qscale, shift = 16.0, 1
+    base = np.array([1.0, 2.0, -1.0, 0.5, 3.0, -2.0, 1.5, 0.25], np.float32)
+    far = -base[::-1].copy()
+    K0 = np.stack([base, far])[None]
+    V0 = np.stack([np.full(d, 1.0), np.full(d, 10.0)])[None].astype(np.float32)
+    near = base + np.array([0.75, 0, 0, 0, 0, 0, -0.375, 0], np.float32)
+    other = np.array([-3.0, 0.1, 2.5, -1.0, 0.2, 0.3, -2.2, 1.7], np.float32)
+    K1 = np.stack([near, base, other])[None]
+    V1 = np.stack([np.full(d, 2.0), np.full(d, 6.0), np.full(d, -4.0)])[None].astype(np.float32)
+    last, mean = (oracle.Cache.empty(1, 8, d, r, "fp32") for _ in range(2))
+    outs = []
+    for cache, mode in ((last, 0), (mean, 1)):
+        oracle.tempcache_compress(cache, R, qscale, shift, K0, V0, tau2_q16=NEVER, frame_id=0, rep_mode=mode)
+        outs.append(oracle.tempcache_compress(cache, R, qscale, shift, K1, V1, tau2_q16=TAU2(0.9), frame_id=1,
+                                              rep_mode=mode))
+    # the mode changes what is stored, not what is decided in this call
+    for a, b in zip(outs[0], outs[1]):
+        assert np.array_equal(a, b)
+    assert outs[1][1][0].tolist() == [1, 1, 0]
+    expect = base + np.array([0.25, 0, 0, 0, 0, 0, -0.125, 0], np.float32)       # (base + near + base) / 3
+    assert np.array_equal(mean.K[0, 0], expect) and np.array_equal(last.K[0, 0], base)
+    assert np.array_equal(mean.code[0, 0], oracle.encode(expect[None], R, qscale, shift)[0])
+    for field in ("V", "cnt", "stamp", "len"):
+        assert np.array_equal(getattr(mean, field), getattr(last, field))
+    assert np.array_equal(mean.K[0, 1:3], last.K[0, 1:3]) and np.array_equal(mean.code[0, 1:3], last.code[0, 1:3])
+    # second frame: the stored mean counts three times: (3 * expect + k) / 4
+    k = expect + np.array([0, 1.0, 0, 0, 0, 0, 0, 0], np.float32)
+    oracle.tempcache_compress(mean, R, qscale, shift, k[None, None], V1[:, :1], tau2_q16=TAU2(0.9), frame_id=2,
+                              rep_mode=1)
+    assert mean.cnt[0, 0] == 4
+    assert np.array_equal(mean.K[0, 0], expect + np.array([0, 0.25, 0, 0, 0, 0, 0, 0], np.float32))
+
+
+@pytest.mark.parametrize("dtype", ["fp32", "bf16"])
+def test_mean_key_of_exact_duplicates_is_the_key_itself(dtype):
+    # drift 0: every group consists of bit-identical keys, so both representatives coincide for the whole rollout
+    # (m * k + k + ... over m + g is exact in float32 for these multiplicities) and so does everything derived
+    c, fs, codec = stream_cfg1(p=1.0, sigma_d=0.0, dtype=dtype)
+    H, T, d = c["H"], c["T"], c["d"]
+    caches = [oracle.Cache.empty(H, 2 * T, d, c["r"], dtype) for _ in range(2)]
+    K0, V0 = fs.next_frame()
+    prev = [None, None]
+    for f in range(4):
+        for m, cache in enumerate(caches):
+            mm, mg, st = compress(cache, codec, K0, V0, cand=prev[m], tau2_q16=TAU2(0.98), frame_id=f, rep_mode=m)
+            prev[m] = mm
+        assert (f == 0) or mg.all()
+    for field in ("K", "V", "code", "cnt", "stamp", "len"):
+        assert np.array_equal(getattr(caches[0], field), getattr(caches[1], field)), field
+    assert caches[1].cnt[:, :T].min() == 4
+
+
+def test_mean_key_stays_inside_the_hull_of_its_group_and_its_code_is_the_code_of_the_stored_key():
+    # drifting tokens: per coordinate the stored mean lies between the smallest and the largest member seen so far
+    # (up to one rounding), and the slot's code is always the code of what is stored
+    c, fs, codec = stream_cfg1(p=1.0, sigma_d=0.02)
+    H, T, d = c["H"], c["T"], c["d"]
+    cache = oracle.Cache.empty(H, 2 * T, d, c["r"], "fp32")
+    lo = hi = None
+    prev = None
+    for f in range(5):
+        K, V = fs.next_frame()
+        mm, mg, st = compress(cache, codec, K, V, cand=prev, tau2_q16=TAU2(0.98), frame_id=f, rep_mode=1)
+        prev = mm
+        if f == 0:
+            lo, hi = K.copy(), K.copy()
+            continue
+        assert mg.mean() > 0.9 and (mm[mg == 1] == np.broadcast_to(np.arange(T), (H, T))[mg == 1]).all()
+        for h in range(H):
+            idx = np.nonzero(mg[h])[0]
+            lo[h, idx] = np.minimum(lo[h, idx], K[h, idx])
+            hi[h, idx] = np.maximum(hi[h, idx], K[h, idx])
+        live = cache.K[:, :T]
+        assert (live >= lo - 1e-6).all() and (live <= hi + 1e-6).all()
+        assert np.array_equal(cache.code[:, :T], oracle.encode(live, codec.R, codec.qscale, codec.shift))
+    assert cache.cnt[:, :T].max() == 5
+
+
 def test_decisions_use_the_cache_as_it_was_at_entry():
     # two identical new tokens and an empty cache: nothing to match, both are appended (no merge inside a call)
     c, fs, codec = stream_cfg1()
