@@ -42,6 +42,8 @@ def parse():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="cfg2", choices=["cfg2", "cfg5"])
     ap.add_argument("--tau", type=float, default=0.98)
+    ap.add_argument("--rep", choices=["last", "mean"], default="last",
+                    help="representative key of a merged group: the last key (the method) or the mean key (its ablation)")
     ap.add_argument("--prefill-frames", type=int, default=None, help="frames merged into the cache before timing")
     ap.add_argument("--cap-frames", type=int, default=None, help="cache capacity in frames of slots")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -60,8 +62,9 @@ def parse():
 class ChunkPipeline:
     """Device buffers and the call sequence of one chunk step.  Nothing is allocated per step."""
 
-    def __init__(self, cfg, C, tau, torch, fa, dev_codec, prompt, n_sel_blocks, sign_matrix=None):
+    def __init__(self, cfg, C, tau, torch, fa, dev_codec, prompt, n_sel_blocks, sign_matrix=None, rep_mode=0):
         self.t, self.fa, self.cfg = torch, fa, cfg
+        self.rep_mode = rep_mode
         H, d, r, T = cfg["H"], cfg["d"], cfg["r"], cfg["T"]
         self.H, self.d, self.r, self.T, self.C = H, d, r, T, C
         self.BQ, self.BK, self.n_rep = cfg["BQ"], cfg["BK"], cfg["n_rep"]
@@ -105,7 +108,7 @@ class ChunkPipeline:
         fa = self.fa
         out = self.mm[self.frame_id & 1]
         fa.tempcache_compress(self.cache, self.codec, K, V, cand=self.prev, tau2_q16=self.tau2,
-                              frame_id=self.frame_id, ws=self.ws_c, out=out)
+                              frame_id=self.frame_id, rep_mode=self.rep_mode, ws=self.ws_c, out=out)
         self.prev = out[0]
         self.frame_id += 1
 
@@ -210,7 +213,7 @@ def cpu_baseline(cfg, pipe, prefill_host, chunks, ps, n_heads, to_host, sign_mat
     def push(K, V):
         nonlocal prev, fid
         prev, _, _ = oracle.tempcache_compress(cache, codec.R, codec.qscale, codec.shift, K, V, cand=prev,
-                                               tau2_q16=pipe.tau2, frame_id=fid)
+                                               tau2_q16=pipe.tau2, frame_id=fid, rep_mode=pipe.rep_mode)
         fid += 1
     for K, V in prefill_host:
         push(K, V)
@@ -331,7 +334,8 @@ def main():
     t_gen = time.perf_counter() - t_gen
     sign_h = make_sign_matrix(cfg["seed"], cfg["cfg_id"], cfg["d"], 128) if args.ann == "lsh" else None
     pipe = ChunkPipeline(cfg, C, args.tau, torch, fa, codec, (to_dev(ps.K), to_dev(ps.V)), n_sel,
-                         sign_matrix=None if sign_h is None else to_dev(sign_h))
+                         sign_matrix=None if sign_h is None else to_dev(sign_h),
+                         rep_mode=fa.REP_MEAN if args.rep == "mean" else fa.REP_LAST)
     for K, V in prefill:
         pipe.compress(K, V)
     torch.cuda.synchronize()
@@ -401,6 +405,7 @@ def main():
                                f"slots/head, tau {args.tau}), AnnSA {n_sel} of {n_kb_quoted} key blocks per query block "
                                f"(BQ {cfg['BQ']}, BK {cfg['BK']}), AnnCA {cfg['n_sel_cross']} of {cfg['n_p']} prompt tokens",
                    "ann": f"int8 projection codes (r 32, shift {codec_h.shift})" if args.ann == "int8" else "sign codes, 128 hash bits (LSH variant)",
+                   "representative": args.rep + " key",
                    "prefill_frames": n_prefill, "cache_len_per_head_start": [min(len_prefill), max(len_prefill)],
                    "cache_len_per_head_end": [min(len_final), max(len_final)],
                    "cache_bytes": pipe.cache.nbytes()},

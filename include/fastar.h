@@ -49,6 +49,10 @@ extern "C" {
 #define FASTAR_OP_SELECT_CROSS 3
 #define FASTAR_OP_SELECT_LSH 4
 
+/* representative key of a merged TempCache group (tempcache_compress, rep_mode) */
+#define FASTAR_REP_LAST 0
+#define FASTAR_REP_MEAN 1
+
 /*
  * Bounded per-head KV cache with multiplicities (Lemma 1 of the paper: a group of merged keys is
  * kept as one representative key, the mean of the group's values and the group size m, which
@@ -137,6 +141,10 @@ int ann_select_lsh(const uint32_t *qbits, int n_q, const uint32_t *kbits, const 
  *   4. every slot keeps, of the tokens merged into it, the one closest in code space (metric 0:
  *      S - |cp_i|^2, metric 1: S; ties to the smallest token) as its new representative key; its
  *      value becomes the mean over the enlarged group and its multiplicity grows by the joiners.
+ *      rep_mode FASTAR_REP_MEAN (appendix ablation "Representative selection in KV merging") stores the
+ *      multiplicity-weighted mean key instead: float32, multiplicity * old key, then the joiners' keys in
+ *      ascending token order, one division, one rounding to dtype; the slot's code is the code of the
+ *      stored key (one more launch).  FASTAR_REP_LAST is the method's own choice and the fast path.
  *   5. unmerged tokens are appended in token order.  If the cache would exceed C, the live slots
  *      that received no token in this call are evicted, smallest (stamp, slot) first, and refilled
  *      in ascending slot order; if there are too few of those, the last unmerged tokens are dropped.
@@ -153,8 +161,8 @@ int ann_select_lsh(const uint32_t *qbits, int n_q, const uint32_t *kbits, const 
  */
 int tempcache_compress(const fastar_cache *cache, const fastar_codec *codec, const void *K_new,
                        const void *V_new, const void *P_new, int n_new, const int32_t *cand, int n_cand,
-                       int metric, int32_t tau2_q16, int32_t frame_id, int32_t *merge_map, uint8_t *merged,
-                       int32_t *stats, void *ws, size_t ws_bytes, void *stream);
+                       int metric, int32_t tau2_q16, int32_t frame_id, int rep_mode, int32_t *merge_map,
+                       uint8_t *merged, int32_t *stats, void *ws, size_t ws_bytes, void *stream);
 
 /*
  * AnnSA (Sec. 5.4 with the ANN goal of Sec. 5.1): for every head and every block of BQ queries,

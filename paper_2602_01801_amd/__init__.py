@@ -11,6 +11,8 @@ from .binding import (  # noqa: F401
     OP_COMPRESS,
     OP_SELECT_CROSS,
     OP_SELECT_LSH,
+    REP_LAST,
+    REP_MEAN,
     OP_SELECT_SELF,
     Cache,
     Codec,

@@ -17,6 +17,7 @@ LIB_PATH = os.path.join(_HERE, "libfastar.so")
 
 F32, BF16 = 0, 1
 OP_COMPRESS, OP_SELECT_SELF, OP_SELECT_CROSS, OP_SELECT_LSH = 1, 2, 3, 4
+REP_LAST, REP_MEAN = 0, 1
 
 _lib = None
 
@@ -54,7 +55,7 @@ def lib() -> ctypes.CDLL:
         L.tempcache_compress.restype = ctypes.c_int
         L.tempcache_compress.argtypes = [ctypes.POINTER(_CacheStruct), ctypes.POINTER(_CodecStruct), ctypes.c_void_p,
                                          ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int, ctypes.c_void_p, ctypes.c_int,
-                                         ctypes.c_int, ctypes.c_int32, ctypes.c_int32, ctypes.c_void_p,
+                                         ctypes.c_int, ctypes.c_int32, ctypes.c_int32, ctypes.c_int, ctypes.c_void_p,
                                          ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t,
                                          ctypes.c_void_p]
         L.ann_select_self.restype = ctypes.c_int
@@ -190,8 +191,9 @@ def encode(x: torch.Tensor, codec: Codec, out: torch.Tensor | None = None) -> to
 
 
 def tempcache_compress(cache: Cache, codec: Codec, K_new, V_new, P_new=None, cand=None, metric: int = 0,
-                       tau2_q16: int = 53084, frame_id: int = 0, ws=None, out=None):
-    """Merge one frame into ``cache`` in place.  Returns (merge_map [H,n] int32, merged [H,n] uint8, stats [H,8])."""
+                       tau2_q16: int = 53084, frame_id: int = 0, rep_mode: int = 0, ws=None, out=None):
+    """Merge one frame into ``cache`` in place.  Returns (merge_map [H,n] int32, merged [H,n] uint8, stats [H,8]).
+    rep_mode: REP_LAST (0) keeps the last key of a merged group, REP_MEAN (1) its multiplicity-weighted mean."""
     H, C, d, r = cache.shape
     _dev(K_new, cache.K.dtype)
     _dev(V_new, cache.K.dtype)
@@ -211,7 +213,7 @@ def tempcache_compress(cache: Cache, codec: Codec, K_new, V_new, P_new=None, can
     cs, ks = cache.struct(), codec.struct()
     _check(lib().tempcache_compress(ctypes.byref(cs), ctypes.byref(ks), K_new.data_ptr(), V_new.data_ptr(),
                                     _ptr(P_new), n_new, _ptr(cand), n_cand, metric, tau2_q16, frame_id,
-                                    merge_map.data_ptr(), merged.data_ptr(), stats.data_ptr(), ws.data_ptr(),
+                                    int(rep_mode), merge_map.data_ptr(), merged.data_ptr(), stats.data_ptr(), ws.data_ptr(),
                                     ws.numel() * ws.element_size(), _stream()), "tempcache_compress")
     return merge_map, merged, stats
 

@@ -1074,7 +1074,8 @@ __global__ __launch_bounds__(256) void tc_apply_kernel(void *__restrict__ K, voi
                                                        const uint8_t *__restrict__ merged, const u64 *__restrict__ win,
                                                        const int32_t *__restrict__ grp, const int32_t *__restrict__ rank,
                                                        const int32_t *__restrict__ victims, const int32_t *__restrict__ hs,
-                                                       int32_t *__restrict__ merge_map, int32_t *__restrict__ len) {
+                                                       int32_t *__restrict__ merge_map, int32_t *__restrict__ len,
+                                                       int rep_mode) {
     typedef RowPiece<BF16, D> RP;
     const int h = blockIdx.y;
     // the new length is published here and not by the plan: its workgroups read len[h] at different times
@@ -1102,15 +1103,28 @@ __global__ __launch_bounds__(256) void tc_apply_kernel(void *__restrict__ K, voi
         const int m0 = cnt[cb + j];
         const int widx = (int)(0xFFFFFFFFu - (unsigned)wkey);
         if (widx == i) {  // this token represents the group: it refreshes the slot
-            float acc[RP::EPL], vn[RP::EPL];
+            // mean value; with rep_mode 1 also the mean key, whose stored bits feed later integer decisions: single
+            // float32 operations in a fixed order (multiplicity * old row, members in ascending token order, one division)
+            const bool mean_key = rep_mode == 1;
+            float acc[RP::EPL], vn[RP::EPL], kacc[RP::EPL], kn[RP::EPL];
             RP::load(V, cb + j, l16, acc);
+            if (mean_key) RP::load(K, cb + j, l16, kacc);
 #pragma unroll
             for (int e = 0; e < RP::EPL; ++e) acc[e] *= (float)m0;
+            if (mean_key) {
+#pragma unroll
+                for (int e = 0; e < RP::EPL; ++e) kacc[e] = __fmul_rn((float)m0, kacc[e]);
+            }
             if (gc == 1) {
                 RP::unpack(vraw, vn);
 #pragma unroll
                 for (int e = 0; e < RP::EPL; ++e) acc[e] += vn[e];
-            } else {  // several joiners: add their values in ascending token order
+                if (mean_key) {
+                    RP::unpack(kraw, kn);
+#pragma unroll
+                    for (int e = 0; e < RP::EPL; ++e) kacc[e] = __fadd_rn(kacc[e], kn[e]);
+                }
+            } else {  // several joiners: add their rows in ascending token order
                 for (int base = 0; base < n_new; base += 16) {
                     const int t = base + l16;
                     const bool member = t < n_new && merged[tb + t] && jstar[tb + t] == j;
@@ -1121,14 +1135,25 @@ __global__ __launch_bounds__(256) void tc_apply_kernel(void *__restrict__ K, voi
                         RP::load(V_new, tb + base + bit, l16, vn);
 #pragma unroll
                         for (int e = 0; e < RP::EPL; ++e) acc[e] += vn[e];
+                        if (mean_key) {
+                            RP::load(K_new, tb + base + bit, l16, kn);
+#pragma unroll
+                            for (int e = 0; e < RP::EPL; ++e) kacc[e] = __fadd_rn(kacc[e], kn[e]);
+                        }
                     }
                 }
             }
 #pragma unroll
             for (int e = 0; e < RP::EPL; ++e) acc[e] = __fdiv_rn(acc[e], (float)(m0 + gc));
             RP::store(V, cb + j, l16, acc);
-            RP::store_raw(K, cb + j, l16, kraw);
-            if (l16 < r / 4) ((unsigned *)(code + (cb + j) * r))[l16] = cw;
+            if (mean_key) {   // the slot's code follows in tc_recode_kernel, from the stored row
+#pragma unroll
+                for (int e = 0; e < RP::EPL; ++e) kacc[e] = __fdiv_rn(kacc[e], (float)(m0 + gc));
+                RP::store(K, cb + j, l16, kacc);
+            } else {
+                RP::store_raw(K, cb + j, l16, kraw);
+                if (l16 < r / 4) ((unsigned *)(code + (cb + j) * r))[l16] = cw;
+            }
             if (l16 == 0) {
                 cnt[cb + j] = m0 + gc;
                 stamp[cb + j] = frame_id;
@@ -1147,13 +1172,40 @@ __global__ __launch_bounds__(256) void tc_apply_kernel(void *__restrict__ K, voi
     if (l16 == 0) merge_map[ti] = dst;
 }
 
+// ---- codes of the slots whose key was replaced by a mean (rep_mode 1), from the rows tc_apply_kernel stored -----
+// One wavefront per 16 tokens, as in encode_kernel; every merged token encodes its slot (the joiners of one slot
+// write the same bytes).
+template <bool BF16, int D, int R>
+__global__ __launch_bounds__(256) void tc_recode_kernel(const void *__restrict__ K, int8_t *__restrict__ code, int C,
+                                                        int n_new, const int32_t *__restrict__ jstar,
+                                                        const uint8_t *__restrict__ merged,
+                                                        const int8_t *__restrict__ Rm, float qscale, int shift) {
+    const int h = blockIdx.y;
+    const int lane = lane_id();
+    const int col = lane & 15, g = lane >> 4;
+    const int i = blockIdx.x * 64 + (threadIdx.x >> 6) * 16 + col;
+    const bool act = i < n_new && merged[(size_t)h * n_new + i] != 0;
+    const int j = act ? jstar[(size_t)h * n_new + i] : 0;
+    CodeMatrix<BF16, D, R> cm;
+    cm.load(Rm, lane);
+    const char *row = (const char *)K + ((size_t)h * C + j) * (size_t)D * (BF16 ? 2 : 4);
+    i32x4 xq[D / 64];
+#pragma unroll
+    for (int ks = 0; ks < D / 64; ++ks) xq[ks] = load_quantised<BF16>(row, ks, g, qscale);
+#pragma unroll
+    for (int cb = 0; cb < R / 16; ++cb) {
+        const unsigned w = cm.code_word(xq, cb, shift);
+        if (act) *(unsigned *)(code + ((size_t)h * C + j) * R + cb * 16 + 4 * g) = w;
+    }
+}
+
 }  // namespace fastar
 
 using namespace fastar;
 
 extern "C" int tempcache_compress(const fastar_cache *cache, const fastar_codec *codec, const void *K_new,
                                   const void *V_new, const void *P_new, int n_new, const int32_t *cand, int n_cand,
-                                  int metric, int32_t tau2_q16, int32_t frame_id, int32_t *merge_map,
+                                  int metric, int32_t tau2_q16, int32_t frame_id, int rep_mode, int32_t *merge_map,
                                   uint8_t *merged, int32_t *stats, void *ws, size_t ws_bytes, void *stream) {
     if (!cache || !codec || !codec->R || !K_new || !V_new || !merge_map || !merged || !stats || !ws)
         return FASTAR_ERR_INVALID_ARG;
@@ -1161,6 +1213,7 @@ extern "C" int tempcache_compress(const fastar_cache *cache, const fastar_codec 
         return FASTAR_ERR_INVALID_ARG;
     const int H = cache->H, C = cache->C, d = cache->d, r = cache->r, dtype = cache->dtype;
     if (H <= 0 || C <= 0 || n_new <= 0 || (metric != 0 && metric != 1)) return FASTAR_ERR_INVALID_ARG;
+    if (rep_mode != FASTAR_REP_LAST && rep_mode != FASTAR_REP_MEAN) return FASTAR_ERR_INVALID_ARG;
     if (tau2_q16 < 0 || tau2_q16 > 131072) return FASTAR_ERR_INVALID_ARG;
     if (cand && n_cand <= 0) return FASTAR_ERR_INVALID_ARG;
     if (codec->shift < 1 || codec->shift > 16) return FASTAR_ERR_INVALID_ARG;
@@ -1247,8 +1300,20 @@ extern "C" int tempcache_compress(const fastar_cache *cache, const fastar_codec 
                        C, n_new, frame_id, jstar, merged, win, rank, victims, hs, stats, plan_scratch);
     FASTAR_LAUNCH_CHECK();
     FASTAR_TC(tc_apply_kernel, cache->K, cache->V, cache->code, cache->cnt, cache->stamp, C, r, K_new, V_new, ck, n_new,
-              frame_id, jstar, merged, win, grp, rank, victims, hs, merge_map, cache->len);
+              frame_id, jstar, merged, win, grp, rank, victims, hs, merge_map, cache->len, rep_mode);
     FASTAR_LAUNCH_CHECK();
 #undef FASTAR_TC
+    if (rep_mode == FASTAR_REP_MEAN) {
+        const dim3 rgrid((n_new + 63) / 64, H);
+#define FASTAR_RECODE(BF, DD, RR)                                                                                     \
+    hipLaunchKernelGGL((tc_recode_kernel<BF, DD, RR>), rgrid, dim3(256), 0, s, cache->K, cache->code, C, n_new, jstar, \
+                       merged, codec->R, codec->qscale, codec->shift)
+        if (bf && d == 128) { if (r == 32) FASTAR_RECODE(true, 128, 32); else FASTAR_RECODE(true, 128, 64); }
+        else if (bf) { if (r == 32) FASTAR_RECODE(true, 64, 32); else FASTAR_RECODE(true, 64, 64); }
+        else if (d == 128) { if (r == 32) FASTAR_RECODE(false, 128, 32); else FASTAR_RECODE(false, 128, 64); }
+        else { if (r == 32) FASTAR_RECODE(false, 64, 32); else FASTAR_RECODE(false, 64, 64); }
+#undef FASTAR_RECODE
+        FASTAR_LAUNCH_CHECK();
+    }
     return FASTAR_OK;
 }

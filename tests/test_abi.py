@@ -58,7 +58,7 @@ def test_null_and_inconsistent_arguments_return_error_codes_without_a_gpu(L):
     assert L.sparse_attn_fwd(null, 1, null, null, null, null, 1, 1, 128, 1, null, null, 128, 64, 1,
                              ctypes.c_float(1.0), null, null, null) == -1
     assert L.fastar_encode(null, 1, 16, 128, None, 32, null, null) == -1
-    assert L.tempcache_compress(None, None, null, null, null, 1, null, 0, 0, 0, 0, null, null, null, null, 0,
+    assert L.tempcache_compress(None, None, null, null, null, 1, null, 0, 0, 0, 0, 0, null, null, null, null, 0,
                                 null) == -1
 
 

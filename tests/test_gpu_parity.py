@@ -253,7 +253,7 @@ def test_dense_limit_on_clustered_data_fp32_and_bf16():
 
 # ----------------------------------------------------------------------------------------- TempCache
 
-def run_rollout(name, n_frames, C, tau, dtype=None, H=None, windowed=True, metric=0, probe_queries=False):
+def run_rollout(name, n_frames, C, tau, dtype=None, H=None, windowed=True, metric=0, probe_queries=False, rep_mode=0):
     over = {}
     if dtype:
         over["dtype"] = dtype
@@ -271,11 +271,11 @@ def run_rollout(name, n_frames, C, tau, dtype=None, H=None, windowed=True, metri
         P = fs.queries(1) if probe_queries else None
         mm_r, mg_r, st_r = oracle.tempcache_compress(ref, codec.R, codec.qscale, codec.shift, K, V, P_new=P,
                                                      cand=prev_ref if windowed else None, metric=metric,
-                                                     tau2_q16=TAU2(tau), frame_id=f)
+                                                     tau2_q16=TAU2(tau), frame_id=f, rep_mode=rep_mode)
         mm_g, mg_g, st_g = fa.tempcache_compress(gpu, dcodec, to_dev(K), to_dev(V),
                                                  P_new=None if P is None else to_dev(P),
                                                  cand=prev_gpu if windowed else None, metric=metric,
-                                                 tau2_q16=TAU2(tau), frame_id=f)
+                                                 tau2_q16=TAU2(tau), frame_id=f, rep_mode=rep_mode)
         sync()
         assert np.array_equal(to_host(mg_g), mg_r), f"merged flags, frame {f}"
         assert np.array_equal(to_host(mm_g), mm_r), f"merge map, frame {f}"
@@ -370,6 +370,21 @@ def test_tempcache_every_match_path_bit_exact(dtype, d, r, n_cand, probe, metric
     assert np.array_equal(to_host(mm_g), mm_r)
     assert np.array_equal(to_host(st_g), st_r)
     assert_cache_equal(host_cache(gpu), ref, VTOL[dtype])
+
+
+@pytest.mark.parametrize("name,dtype,H,frames,C", [("cfg1", None, None, 6, 6 * 256), ("cfg1", "bf16", None, 6, 3 * 256),
+                                                   ("cfg2", None, 2, 4, 3 * 1560)])
+def test_tempcache_mean_key_representative_bit_exact(name, dtype, H, frames, C):
+    # the stored mean key decides later codes, matches and cosine tests: every frame of the rollout must agree bit for
+    # bit (assert_cache_equal compares keys and codes exactly), through merges of several tokens per slot and evictions
+    c, fs, codec, ref, gpu = run_rollout(name, frames, C, 0.98, dtype=dtype, H=H, rep_mode=fa.REP_MEAN)
+    assert ref.cnt.max() >= 4
+
+
+def test_tempcache_mean_key_with_many_joiners_per_slot():
+    # low threshold on the clustered stream: whole clusters fold into single slots, so slots take many joiners per call
+    c, fs, codec, ref, gpu = run_rollout("cfg1", 4, 5 * 256, 0.5, rep_mode=fa.REP_MEAN)
+    assert ref.cnt.max() > 8
 
 
 def test_tempcache_whole_cache_match_and_inner_product_probe():
