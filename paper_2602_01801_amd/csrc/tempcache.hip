@@ -418,11 +418,27 @@ __device__ __forceinline__ void age_histogram_slice(const int32_t *__restrict__ 
     const int j0 = blockIdx.x * chunk, j1 = min(j0 + chunk, L);
     const int32_t *st = stamp + (size_t)h * C;
     bool future = false;
-    for (int j = j0 + threadIdx.x; j < j1; j += blockDim.x) {
-        const int sj = st[j];
-        if (sj > frame_id) future = true;
-        const unsigned age = (unsigned)frame_id - (unsigned)sj;
-        atomicAdd(&lhist[min(age, (unsigned)(AGE_BINS - 1))], 1u);
+    // Neighbouring slots were mostly written by the same frame: when all of a wavefront's slots fall into one bin, one
+    // lane adds their number (64 additions to one LDS word would be served one after the other).
+    for (int jb = j0; jb < j1; jb += blockDim.x) {   // uniform trip count
+        const int j = jb + threadIdx.x;
+        const bool act = j < j1;
+        unsigned bin = 0;
+        if (act) {
+            const int sj = st[j];
+            if (sj > frame_id) future = true;
+            bin = min((unsigned)frame_id - (unsigned)sj, (unsigned)(AGE_BINS - 1));
+        }
+        const u64 m = __ballot(act);
+        if (m) {
+            const int first = __ffsll((unsigned long long)m) - 1;
+            const unsigned fbin = (unsigned)__shfl((int)bin, first);
+            if (__all(!act || bin == fbin)) {
+                if (lane_id() == first) atomicAdd(&lhist[fbin], (unsigned)__popcll(m));
+            } else if (act) {
+                atomicAdd(&lhist[bin], 1u);
+            }
+        }
     }
     __syncthreads();
     for (int k = threadIdx.x; k < AGE_BINS; k += blockDim.x)
@@ -715,9 +731,11 @@ struct BlockScan {
     }
 };
 
-constexpr int PLAN_PER_MAX = 16;  // slots per thread kept in registers (longer runs are re-read from memory)
 constexpr int PLAN_TOK_MAX = 8;   // tokens per thread kept in registers (n_new <= 2048; more are re-read)
 
+// PLAN_PER_MAX: slots per thread kept in registers (longer runs are re-read from memory); 16 for caches up to
+// 16 * 256 * NB slots per head, 64 beyond (a 64-frame world-model cache: 57 slots per thread).
+template <int PLAN_PER_MAX>
 __global__ __launch_bounds__(PLAN_THREADS) void tc_plan_kernel(const int32_t *__restrict__ len,
                                                                const int32_t *__restrict__ stamp, int C, int n_new,
                                                                int frame_id, const int32_t *__restrict__ jstar,
@@ -779,16 +797,31 @@ __global__ __launch_bounds__(PLAN_THREADS) void tc_plan_kernel(const int32_t *__
         // the loads below do not depend on the count: issued before the reduction waits for the ones above
         n_unm = c;
     }
-    const int span = (L + NB - 1) / NB;
+    // Long runs (PLAN_PER_MAX 64) start on multiples of four slots so that their stamps can be read 16 bytes at a time:
+    // lanes of one load touch different cache lines either way, a quarter of the loads touches them a quarter as often.
+    constexpr bool QUADS = PLAN_PER_MAX > 16;
+    const int span = QUADS ? (((L + NB - 1) / NB + 3) & ~3) : (L + NB - 1) / NB;
     const int s0 = min(b * span, L), s1 = min(s0 + span, L);
-    const int per = (span + PLAN_THREADS - 1) / PLAN_THREADS;
+    const int per_raw = (span + PLAN_THREADS - 1) / PLAN_THREADS;
+    const int per = QUADS ? ((per_raw + 3) & ~3) : per_raw;
     const int j0 = min(s0 + tid * per, s1), j1 = min(j0 + per, s1);
     const bool maybe = L + n_new > C;  // uniform: otherwise no eviction can be needed
     const bool cached = per <= PLAN_PER_MAX;
     int sreg[PLAN_PER_MAX];
     unsigned hreg[4] = {0, 0, 0, 0};
     if (maybe) {
-        if (cached) {
+        if (cached && QUADS && (((uintptr_t)st & 15) == 0)) {
+#pragma unroll
+            for (int k = 0; k < PLAN_PER_MAX; k += 4) {
+                if (j0 + k + 3 < j1) {
+                    const i32x4 v = *(const i32x4 *)(st + j0 + k);
+                    sreg[k] = v[0]; sreg[k + 1] = v[1]; sreg[k + 2] = v[2]; sreg[k + 3] = v[3];
+                } else {
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) sreg[k + q] = j0 + k + q < j1 ? st[j0 + k + q] : 0;
+                }
+            }
+        } else if (cached) {
 #pragma unroll
             for (int k = 0; k < PLAN_PER_MAX; ++k) sreg[k] = j0 + k < j1 ? st[j0 + k] : 0;
         }
@@ -830,12 +863,12 @@ __global__ __launch_bounds__(PLAN_THREADS) void tc_plan_kernel(const int32_t *__
             if (j >= s0 && j < s1) atomicOr(&touched[(j - s0) >> 5], 1u << ((j - s0) & 31));
         });
         __syncthreads();
-        unsigned elig = 0;  // bit k: slot j0 + k is live and untouched
+        u64 elig = 0;  // bit k: slot j0 + k is live and untouched
         if (cached) {
 #pragma unroll
             for (int k = 0; k < PLAN_PER_MAX; ++k) {
                 const int j = j0 + k;
-                if (j < j1 && !((touched[(j - s0) >> 5] >> ((j - s0) & 31)) & 1u)) elig |= 1u << k;
+                if (j < j1 && !((touched[(j - s0) >> 5] >> ((j - s0) & 31)) & 1u)) elig |= 1ull << k;
             }
         }
         // visit(f): f(slot, key) for the eligible slots of this thread's run, ascending; key: larger = older
@@ -843,7 +876,7 @@ __global__ __launch_bounds__(PLAN_THREADS) void tc_plan_kernel(const int32_t *__
             if (cached) {
 #pragma unroll
                 for (int k = 0; k < PLAN_PER_MAX; ++k)
-                    if ((elig >> k) & 1u) f(j0 + k, ~((unsigned)sreg[k] ^ 0x80000000u));
+                    if ((elig >> k) & 1ull) f(j0 + k, ~((unsigned)sreg[k] ^ 0x80000000u));
             } else {
                 for (int j = j0; j < j1; ++j)
                     if (!((touched[(j - s0) >> 5] >> ((j - s0) & 31)) & 1u)) f(j, ~((unsigned)st[j] ^ 0x80000000u));
@@ -1062,7 +1095,7 @@ static int plan_nb(int H, int C) {
     if (nb > PLAN_NB_MAX) nb = PLAN_NB_MAX;
     return nb < 1 ? 1 : nb;
 }
-static size_t plan_lds_bytes(int C, int nb) { return ((size_t)((C + nb - 1) / nb + 31) / 32 + 1) * 4; }
+static size_t plan_lds_bytes(int C, int nb) { return ((size_t)((C + nb - 1) / nb + 3 + 31) / 32 + 2) * 4; }
 
 // ---- apply ---------------------------------------------------------------------------------------------
 template <bool BF16, int D>
@@ -1296,8 +1329,12 @@ extern "C" int tempcache_compress(const fastar_cache *cache, const fastar_codec 
     FASTAR_TC(tc_verify_kernel, cache->K, K_new, cp, r, C, n_new, codec->qscale, metric, tau2_q16, jstar, sbest, win, grp,
               merged, cache->len, cache->stamp, frame_id, plan_scratch, PS_HIST, PS_FUT, PS_STRIDE);
     FASTAR_LAUNCH_CHECK();
-    hipLaunchKernelGGL(tc_plan_kernel, dim3(nb + 1, H), dim3(PLAN_THREADS), plan_lds_bytes(C, nb), s, cache->len, cache->stamp,
-                       C, n_new, frame_id, jstar, merged, win, rank, victims, hs, stats, plan_scratch);
+    if (((C + nb - 1) / nb + PLAN_THREADS - 1) / PLAN_THREADS <= 16)
+        hipLaunchKernelGGL(tc_plan_kernel<16>, dim3(nb + 1, H), dim3(PLAN_THREADS), plan_lds_bytes(C, nb), s, cache->len,
+                           cache->stamp, C, n_new, frame_id, jstar, merged, win, rank, victims, hs, stats, plan_scratch);
+    else
+        hipLaunchKernelGGL(tc_plan_kernel<64>, dim3(nb + 1, H), dim3(PLAN_THREADS), plan_lds_bytes(C, nb), s, cache->len,
+                           cache->stamp, C, n_new, frame_id, jstar, merged, win, rank, victims, hs, stats, plan_scratch);
     FASTAR_LAUNCH_CHECK();
     FASTAR_TC(tc_apply_kernel, cache->K, cache->V, cache->code, cache->cnt, cache->stamp, C, r, K_new, V_new, ck, n_new,
               frame_id, jstar, merged, win, grp, rank, victims, hs, merge_map, cache->len, rep_mode);

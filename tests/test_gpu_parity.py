@@ -295,7 +295,8 @@ def test_tempcache_eviction_and_drops_bit_exact():
     run_rollout("cfg1", 2, 100, 2.0 ** 0.5)                            # capacity below one frame: drops
 
 
-@pytest.mark.parametrize("C,n_stamps", [(37440, 30), (37440, 1), (37440, 70000), (60000, 300), (1000, 5)])
+@pytest.mark.parametrize("C,n_stamps", [(37440, 30), (37440, 1), (37440, 70000), (60000, 300), (1000, 5),
+                                        (100000, 300), (100000, 2), (270000, 40)])   # 25 / 66 slots per planning thread
 def test_tempcache_eviction_on_a_full_synthetic_cache(C, n_stamps):
     # a full cache with random stamps (many ties, or several significant bytes): one call must evict exactly the
     # oldest untouched slots, lowest slot first on ties, and refill them in ascending slot order
