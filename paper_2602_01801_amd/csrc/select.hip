@@ -15,6 +15,7 @@
 namespace fastar {
 
 constexpr int KB_PER_WG = 4;      // key blocks scored by one workgroup of score_self_kernel
+constexpr int KB_PER_WG_LONG = 16; // the same for long caches (at least 2048 such workgroups)
 constexpr int COL_CHUNK = 8;       // summary column blocks (of 32) kept in registers at a time
 constexpr int TOPK_LDS_CAP = 8192; // row entries cached in LDS by topk_kernel
 
@@ -139,6 +140,128 @@ __global__ __launch_bounds__(256) void score_self_kernel(const int8_t *__restric
     const int n_here = min(KB_PER_WG, n_kb - kb0);
     for (int t = threadIdx.x; t < n_qb * KB_PER_WG; t += blockDim.x) {
         const int b = t / KB_PER_WG, kl = t % KB_PER_WG;
+        if (kl < n_here) out[((size_t)h * n_qb + b) * n_kb_cap + kb0 + kl] = tile[t];
+    }
+}
+
+// The same scores for long caches (at least 2048 workgroups of KBW = 16 key blocks): wavefront w streams blocks w, w+4,
+// ... with the codes of the next three rounds in flight while it scores the current one, and the workgroup writes
+// 64-byte pieces of the score rows.  CC: summary column blocks (of 32) kept in registers at a time.
+template <int R, int KBW, int CC>
+__global__ __launch_bounds__(256) void score_self_stream_kernel(const int8_t *__restrict__ kcode, const int32_t *__restrict__ len,
+                                                         const int8_t *__restrict__ rep, int C, int n_q, int BQ,
+                                                         int n_rep, int BK, int n_qb, int n_kb_cap,
+                                                         int32_t *__restrict__ out) {
+    constexpr int KS = R / 32;
+    extern __shared__ int32_t tile[];  // [n_qb][KBW]
+    const int h = blockIdx.y;
+    const int L = min(len[h], C);
+    const int n_kb = (L + BK - 1) / BK;
+    const int kb0 = blockIdx.x * KBW;
+    if (kb0 >= n_kb) return;  // whole workgroup beyond the live cache (uniform)
+    const int lane = lane_id(), wave = threadIdx.x >> 6;
+    const int col = lane & 31, g2 = lane >> 5;
+    const int NR = n_qb * n_rep;
+    const int NCB = (NR + 31) / 32;
+    const int g = BQ / n_rep;
+    const int8_t *kc = kcode + (size_t)h * C * R;
+    const int8_t *rp = rep + (size_t)h * NR * R;
+    // rounds of 64 keys (two groups of 32): key block wave + 4 * (it / rpk), keys 64 * (it % rpk) .. of it
+    const int rpk = (BK + 63) / 64;
+    const int n_it = ((KBW - wave + 3) / 4) * rpk;
+    auto load_round = [&](int it, i32x4 (&a)[2][KS]) __attribute__((always_inline)) {
+        const int kb = kb0 + wave + 4 * (it / rpk), sg0 = 64 * (it % rpk);
+#pragma unroll
+        for (int q = 0; q < 2; ++q) {
+            const int sg = sg0 + 32 * q;
+            const int kbase = kb * BK + sg;
+            // always loaded, from a clamped row: the number of loads in flight is then the same on every path and
+            // the compiler can wait for exactly the buffer it needs; rows past the block or the cache are never scored
+            const int krow = min(kbase + col, C - 1);
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) a[q][ks] = *(const i32x4 *)(kc + (size_t)krow * R + ks * 32 + 16 * g2);
+        }
+    };
+
+    for (int cb0 = 0; cb0 < NCB; cb0 += CC) {
+        i32x4 bfrag[CC][KS];
+#pragma unroll
+        for (int c = 0; c < CC; ++c) {
+            const int rc = min((cb0 + c) * 32 + col, NR - 1);
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) bfrag[c][ks] = *(const i32x4 *)(rp + (size_t)rc * R + ks * 32 + 16 * g2);
+        }
+        // Four operand buffers in rotation, three rounds ahead: 6 KB of codes per wavefront are in flight while a
+        // round is scored (the rotation is unrolled: copying a buffer would wait for its loads).
+        int best[CC];
+        auto score_round = [&](int it, const i32x4 (&cur)[2][KS]) __attribute__((always_inline)) {
+            const int kl = wave + 4 * (it / rpk), sg0 = 64 * (it % rpk);
+            const int kb = kb0 + kl;
+            if (it >= n_it || kb >= n_kb) return;   // uniform
+            if (sg0 == 0) {
+#pragma unroll
+                for (int c = 0; c < CC; ++c) best[c] = INT_MIN;
+            }
+#pragma unroll
+            for (int q = 0; q < 2; ++q) {
+                const int sg = sg0 + 32 * q;
+                const int kbase = kb * BK + sg;
+                if (!(sg < BK && kbase < L)) continue;   // uniform
+                const bool partial = kbase + 32 > L || sg + 32 > BK;
+#pragma unroll
+                for (int c = 0; c < CC; ++c) {
+                    if (cb0 + c < NCB) {
+                        i32x16 acc = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+#pragma unroll
+                        for (int ks = 0; ks < KS; ++ks) acc = mfma_i8_32x32x32(cur[q][ks], bfrag[c][ks], acc);
+                        int m = best[c];
+                        if (partial) {
+#pragma unroll
+                            for (int v = 0; v < 16; ++v) {
+                                const int kloc = 8 * (v >> 2) + 4 * g2 + (v & 3);
+                                if (kbase + kloc < L && sg + kloc < BK) m = max(m, acc[v]);
+                            }
+                        } else {
+#pragma unroll
+                            for (int v = 0; v < 16; ++v) m = max(m, acc[v]);
+                        }
+                        best[c] = m;
+                    }
+                }
+            }
+            if (it % rpk == rpk - 1) {   // the key block is complete
+#pragma unroll
+                for (int c = 0; c < CC; ++c) {
+                    if (cb0 + c < NCB) {
+                        int m = max(best[c], shfl_xor(best[c], 32));
+                        const int rc = (cb0 + c) * 32 + col;
+                        const int b = rc / n_rep, u = rc % n_rep;
+                        if (rc >= NR || b * BQ + u * g >= n_q) m = INT_MIN;
+                        for (int off = 1; off < n_rep; off <<= 1) m = max(m, shfl_xor(m, off));
+                        if (g2 == 0 && u == 0 && rc < NR) tile[b * KBW + kl] = m;
+                    }
+                }
+            }
+        };
+        i32x4 b0[2][KS], b1[2][KS], b2[2][KS], b3[2][KS];
+        load_round(0, b0);
+        load_round(1, b1);
+        load_round(2, b2);
+        for (int it = 0; it < n_it; it += 4) {
+            load_round(it + 3, b3);
+            score_round(it, b0);
+            load_round(it + 4, b0);
+            score_round(it + 1, b1);
+            load_round(it + 5, b1);
+            score_round(it + 2, b2);
+            load_round(it + 6, b2);
+            score_round(it + 3, b3);
+        }
+    }
+    __syncthreads();
+    const int n_here = min(KBW, n_kb - kb0);
+    for (int t = threadIdx.x; t < n_qb * KBW; t += blockDim.x) {
+        const int b = t / KBW, kl = t % KBW;
         if (kl < n_here) out[((size_t)h * n_qb + b) * n_kb_cap + kb0 + kl] = tile[t];
     }
 }
@@ -474,7 +597,8 @@ extern "C" int ann_select_self(const int8_t *qcode, int n_q, const int8_t *kcode
     if ((r != 32 && r != 64) || !pow2_le32(n_rep) || BK % 32 != 0) return FASTAR_ERR_UNSUPPORTED;
     const int n_qb = (n_q + BQ - 1) / BQ;
     const int n_kb_cap = (C + BK - 1) / BK;
-    const size_t tile_bytes = (size_t)n_qb * KB_PER_WG * sizeof(int32_t);
+    const int kbw = ((size_t)n_kb_cap * H >= (size_t)KB_PER_WG_LONG * 2048 && n_qb <= 1024) ? KB_PER_WG_LONG : KB_PER_WG;
+    const size_t tile_bytes = (size_t)n_qb * kbw * sizeof(int32_t);
     if (tile_bytes > 64 * 1024) return FASTAR_ERR_UNSUPPORTED;
     const SelfWs w = self_ws(H, n_q, C, r, BQ, BK, n_rep);
     if (ws_bytes < w.total) return FASTAR_ERR_WORKSPACE;
@@ -483,13 +607,24 @@ extern "C" int ann_select_self(const int8_t *qcode, int n_q, const int8_t *kcode
     int32_t *score = (int32_t *)((char *)ws + w.score_off);
     hipLaunchKernelGGL(rep_kernel, dim3(n_qb, H), dim3(128), 0, s, qcode, n_q, r, BQ, n_rep, n_qb, rep);
     FASTAR_LAUNCH_CHECK();
-    dim3 grid((n_kb_cap + KB_PER_WG - 1) / KB_PER_WG, H);
-    if (r == 32)
-        hipLaunchKernelGGL(score_self_kernel<32>, grid, dim3(256), tile_bytes, s, kcode, len, rep, C, n_q, BQ, n_rep,
-                           BK, n_qb, n_kb_cap, score);
-    else
-        hipLaunchKernelGGL(score_self_kernel<64>, grid, dim3(256), tile_bytes, s, kcode, len, rep, C, n_q, BQ, n_rep,
-                           BK, n_qb, n_kb_cap, score);
+    dim3 grid((n_kb_cap + kbw - 1) / kbw, H);
+#define FASTAR_SCORE(RR, CCC)                                                                                        \
+    hipLaunchKernelGGL((score_self_stream_kernel<RR, KB_PER_WG_LONG, CCC>), grid, dim3(256), tile_bytes, s, kcode, len, \
+                       rep, C, n_q, BQ, n_rep, BK, n_qb, n_kb_cap, score)
+    const bool few_cols = (n_qb * n_rep + 31) / 32 <= 4;   // all summaries fit four column blocks: fewer registers
+    if (kbw == KB_PER_WG) {
+        if (r == 32)
+            hipLaunchKernelGGL(score_self_kernel<32>, grid, dim3(256), tile_bytes, s, kcode, len, rep, C, n_q, BQ, n_rep,
+                               BK, n_qb, n_kb_cap, score);
+        else
+            hipLaunchKernelGGL(score_self_kernel<64>, grid, dim3(256), tile_bytes, s, kcode, len, rep, C, n_q, BQ, n_rep,
+                               BK, n_qb, n_kb_cap, score);
+    } else if (r == 32) {
+        if (few_cols) FASTAR_SCORE(32, 4); else FASTAR_SCORE(32, COL_CHUNK);
+    } else {
+        if (few_cols) FASTAR_SCORE(64, 4); else FASTAR_SCORE(64, COL_CHUNK);
+    }
+#undef FASTAR_SCORE
     FASTAR_LAUNCH_CHECK();
     hipLaunchKernelGGL(topk_kernel, dim3(n_qb, H), dim3(256), 0, s, score, n_kb_cap, len, C, BK, 0, n_qb, n_sel, sel,
                        nsel);
