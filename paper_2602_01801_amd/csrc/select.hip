@@ -297,9 +297,27 @@ __device__ __forceinline__ void topk_row(const int32_t *row, int n, int n_sel, i
     for (int shift = 24; shift >= 0; shift -= 8) {
         hist[tid] = 0;
         __syncthreads();
-        for (int t = tid; t < n; t += 256) {
-            const unsigned u = key_at(t);
-            if ((u & mask) == prefix) atomicAdd(&hist[(u >> shift) & 255u], 1u);
+        // The leading bytes of a row's scores are often all alike: when every candidate of a wavefront falls into one
+        // bin, one lane adds their number (64 additions to one LDS word are served one after the other).
+        for (int base = 0; base < n; base += 256) {   // uniform trip count
+            const int t = base + tid;
+            unsigned bin = 0;
+            bool act = false;
+            if (t < n) {
+                const unsigned u = key_at(t);
+                act = (u & mask) == prefix;
+                bin = (u >> shift) & 255u;
+            }
+            const unsigned long long m = __ballot(act);
+            if (m) {
+                const int first = __ffsll(m) - 1;
+                const unsigned fbin = (unsigned)__shfl((int)bin, first, WAVE);
+                if (__all(!act || bin == fbin)) {
+                    if (lane == first) atomicAdd(&hist[fbin], (unsigned)__popcll(m));
+                } else if (act) {
+                    atomicAdd(&hist[bin], 1u);
+                }
+            }
         }
         __syncthreads();
         if (wave == 0) {
