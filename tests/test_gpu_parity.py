@@ -390,6 +390,52 @@ def test_tempcache_mean_key_with_many_joiners_per_slot():
     assert ref.cnt.max() > 8
 
 
+@pytest.mark.parametrize("T,C,lens,n_cand,tau", [
+    (1, 300, [200, 0], 50, 0.9),           # a single token per head; one head still empty
+    (5000, 6000, [800, 799], 900, 0.9),    # more tokens than the plan keeps in registers, most of them appended
+    (300, 77, [77, 60], 64, 0.9),          # capacity far below one frame: evictions and drops
+    (64, 512, [300, 300], 128, 0.9),       # exactly one workgroup of tokens
+    (200, 512, [100, 250], -1, 0.9),       # every candidate id invalid: nothing can match
+    (200, 512, [0, 0], 100, 0.9),          # empty cache with a (stale) candidate list
+    (130, 4096, [4096, 4000], 3840, 0.5),  # the largest window that is staged in LDS, loose threshold: big groups
+])
+def test_tempcache_edge_shapes_bit_exact(T, C, lens, n_cand, tau):
+    rng = np.random.default_rng(T + C + n_cand)
+    H, d, r = 2, 64, 32
+    codec = make_codec(0, 9, d, r)
+    ref = oracle.Cache.empty(H, C, d, r, "fp32")
+    ref.K[:] = rng.standard_normal((H, C, d)).astype(np.float32)
+    ref.V[:] = rng.standard_normal((H, C, d)).astype(np.float32)
+    ref.code[:] = oracle.encode(ref.K, codec.R, codec.qscale, codec.shift)
+    ref.cnt[:] = rng.integers(1, 4, size=(H, C))
+    ref.stamp[:] = rng.integers(0, 5, size=(H, C))
+    ref.len[:] = lens
+    gpu = dev_cache(ref)
+    K_new = rng.standard_normal((H, T, d)).astype(np.float32)
+    lo = max(min(lens), 1)
+    src = rng.integers(0, lo, size=(H, T))
+    for h in range(H):
+        if lens[h] > 0:
+            K_new[h, : (2 * T) // 3] = ref.K[h, src[h, : (2 * T) // 3]] + 0.01 * rng.standard_normal(((2 * T) // 3, d)).astype(np.float32)
+    V_new = rng.standard_normal((H, T, d)).astype(np.float32)
+    if n_cand < 0:
+        cand = np.full((H, 40), -1, np.int32)
+        cand[:, ::2] = C + 5
+    else:
+        cand = rng.integers(0, max(max(lens), 1), size=(H, n_cand)).astype(np.int32)
+        k = min(n_cand, T)
+        cand[:, :k] = src[:, :k]
+    mm_r, mg_r, st_r = oracle.tempcache_compress(ref, codec.R, codec.qscale, codec.shift, K_new, V_new, cand=cand,
+                                                 tau2_q16=TAU2(tau), frame_id=7)
+    mm_g, mg_g, st_g = fa.tempcache_compress(gpu, dev_codec(codec), to_dev(K_new), to_dev(V_new), cand=to_dev(cand),
+                                             tau2_q16=TAU2(tau), frame_id=7)
+    sync()
+    assert np.array_equal(to_host(st_g), st_r)
+    assert np.array_equal(to_host(mg_g), mg_r)
+    assert np.array_equal(to_host(mm_g), mm_r)
+    assert_cache_equal(host_cache(gpu), ref, VTOL["fp32"])
+
+
 def test_tempcache_whole_cache_match_and_inner_product_probe():
     run_rollout("cfg1", 4, 5 * 256, 0.9, windowed=False)
     run_rollout("cfg1", 4, 5 * 256, 0.9, windowed=True, metric=1, probe_queries=True)
