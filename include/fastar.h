@@ -185,6 +185,8 @@ int ann_select_self(const int8_t *qcode, int n_q, const int8_t *kcode, const int
  * with the largest max over the block's queries of c_q.c_p (a token is kept when at least one query
  * of the block is its neighbour).  Ties to the smaller token index, ascending output, -1 padding.
  *   qcode [H,n_q,r], pcode [H,n_p,r];  sel [H,n_qb,n_sel], nsel [H,n_qb] out.
+ * BQ is free (it need not be sparse_attn_fwd's block size): BQ = tokens per frame gives the per-frame selection
+ * of Sec. 5.3, whose list the caller then shares among the query blocks of that frame's attention call.
  */
 int ann_select_cross(const int8_t *qcode, int n_q, const int8_t *pcode, int n_p, int H, int r, int BQ,
                      int n_sel, int32_t *sel, int32_t *nsel, void *ws, size_t ws_bytes, void *stream);

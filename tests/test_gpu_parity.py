@@ -82,6 +82,7 @@ def test_ann_select_self_bit_exact(H, n_q, C, r, BQ, n_rep, BK, n_sel, lens, spa
 @pytest.mark.parametrize("H,n_q,n_p,r,BQ,n_sel,span", [
     (2, 256, 64, 32, 128, 16, 60), (2, 4680, 512, 32, 128, 64, 50), (1, 300, 2048, 32, 128, 64, 4),
     (2, 100, 97, 64, 64, 10, 30), (1, 50, 20, 32, 128, 64, 30),
+    (2, 4680, 512, 32, 1560, 64, 50), (1, 3600, 2048, 64, 3600, 64, 20),   # one selection per frame (query block = frame)
 ])
 def test_ann_select_cross_bit_exact(H, n_q, n_p, r, BQ, n_sel, span):
     rng = np.random.default_rng(n_q + n_p)
@@ -179,6 +180,33 @@ def test_sign_codes_select_then_attend_end_to_end():
     assert np.array_equal(as_u32(qb), qb_r) and np.array_equal(as_u32(kb), kb_r)
     assert np.array_equal(to_host(sel), sel_r) and np.array_equal(to_host(nsel), nsel_r)
     assert np.abs(storage_to_f64(to_host(O)) - O_r).max() <= ATOL[c["dtype"]]
+
+
+def test_per_frame_prompt_selection_then_cross_attention_per_frame():
+    """AnnCA with the frame as the query block (Sec. 5.3 selects prompt tokens per frame): one selection per frame, its
+    list shared by the query blocks of that frame's attention call."""
+    c = dict(CONFIGS["cfg2"]); c["H"] = 2
+    fs = FrameStream(c["seed"], c["cfg_id"], c["H"], c["d"], c["T"], c["n_c"], c["p"], c["sigma_d"], c["dtype"])
+    ps = PromptSet(c["seed"], c["cfg_id"], fs.centreK, 512, 32, 3, c["dtype"])
+    codec = make_codec(c["seed"], c["cfg_id"], c["d"], c["r"])
+    T, H, n_sel = c["T"], c["H"], 64
+    fs.next_frame()
+    Q = fs.queries(2)                                             # two frames of queries
+    qc_r = oracle.encode(Q, codec.R, codec.qscale, codec.shift)
+    pc_r = oracle.encode(ps.K, codec.R, codec.qscale, codec.shift)
+    sel_r, nsel_r = oracle.ann_select_cross(qc_r, pc_r, T, n_sel)            # [H, 2 frames, n_sel]
+    dcodec = dev_codec(codec)
+    qc, pc = fa.encode(to_dev(Q), dcodec), fa.encode(to_dev(ps.K), dcodec)
+    sel, nsel = fa.ann_select_cross(qc, pc, T, n_sel)
+    sync()
+    assert np.array_equal(to_host(sel), sel_r) and np.array_equal(to_host(nsel), nsel_r)
+    plen = np.full((H,), 512, np.int32)
+    n_qb = (T + 127) // 128
+    for f in range(2):
+        Qf = np.ascontiguousarray(Q[:, f * T:(f + 1) * T])
+        sel_f = np.ascontiguousarray(np.repeat(sel_r[:, f:f + 1], n_qb, axis=1))
+        nsel_f = np.ascontiguousarray(np.repeat(nsel_r[:, f:f + 1], n_qb, axis=1))
+        check_attention(Qf, ps.K, ps.V, None, plen, sel_f, nsel_f, 128, 1, c["d"] ** -0.5, c["dtype"])
 
 
 # ----------------------------------------------------------------------------------------- attention
