@@ -133,7 +133,8 @@ int ann_select_lsh(const uint32_t *qbits, int n_q, const uint32_t *kbits, const 
  * decision is taken against the cache as it is at entry; a chunk of several frames is several calls.
  *   1. probe code cp_i = code(P_new[i]) (P_new NULL => K_new), key code ck_i = code(K_new[i]).
  *   2. top-1 match among the candidate slots (cand [H,n_cand] slot ids, ids outside [0,len) are
- *      skipped; cand NULL => every live slot): j*(i) = argmax_j S(i,j), ties to the smallest slot,
+ *      skipped; cand NULL => every live slot): j*(i) = argmax_j S(i,j), ties to the candidate listed
+ *      first (cand NULL: to the smallest slot),
  *      S = 2 cp_i.code_j - |code_j|^2 (metric 0, nearest in code space) or cp_i.code_j (metric 1).
  *   3. similarity threshold on the 8-bit quantised full-width keys a = xq(K_new[i]), b = xq(K[j*]):
  *      merged_i <=> a.b > 0 and (a.b)^2 * 65536 >= tau2_q16 * |a|^2 |b|^2, with

@@ -256,6 +256,25 @@ def test_mean_key_stays_inside_the_hull_of_its_group_and_its_code_is_the_code_of
     assert cache.cnt[:, :T].max() == 5
 
 
+def test_equally_scored_candidates_the_first_listed_wins():
+    # two cache slots hold the same key (same code, same score for any probe): the match goes to whichever the
+    # candidate list names first; without a list the slots are searched in ascending order
+    d, r = 8, 4
+    R = np.array([[1, 1, 1, 1], [1, -1, 1, -1], [1, 1, -1, -1], [1, -1, -1, 1]] * 2, np.int8)
+    qscale, shift = 16.0, 1
+    base = np.array([1.0, 2.0, -1.0, 0.5, 3.0, -2.0, 1.5, 0.25], np.float32)
+    other = np.array([-3.0, 0.1, 2.5, -1.0, 0.2, 0.3, -2.2, 1.7], np.float32)
+    K0 = np.stack([other, base, -other, base, base])[None]
+    V0 = np.zeros_like(K0)
+    for cand, expect in ((None, 1), ([[4, 1, 3]], 4), ([[0, 3, 3, 1, 4]], 3), ([[2, 7, -1, 1]], 1), ([[9, 4, 4]], 4)):
+        cache = oracle.Cache.empty(1, 8, d, r, "fp32")
+        oracle.tempcache_compress(cache, R, qscale, shift, K0, V0, tau2_q16=NEVER, frame_id=0)
+        mm, mg, _ = oracle.tempcache_compress(cache, R, qscale, shift, base[None, None], V0[:, :1],
+                                              cand=None if cand is None else np.array(cand, np.int32),
+                                              tau2_q16=TAU2(0.9), frame_id=1)
+        assert mg[0, 0] == 1 and mm[0, 0] == expect, (cand, mm)
+
+
 def test_decisions_use_the_cache_as_it_was_at_entry():
     # two identical new tokens and an empty cache: nothing to match, both are appended (no merge inside a call)
     c, fs, codec = stream_cfg1()
