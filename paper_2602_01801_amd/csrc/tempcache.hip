@@ -55,6 +55,38 @@ size_t compress_ws_bytes(int H, int C, int n_new, int r) {
     return compress_ws(H, C, n_new, r).total;
 }
 
+// Running arg-max of one lane over the 16 scores a 32x32 matrix instruction leaves it (rows 8(v/4) + 4(lane/32) + v%4
+// of a group of 32 candidates), with "first candidate in list order" among equal scores at no extra cost: a score
+// word carries its position among the 16 in its low four bits (one shift-add per score), so plain maxima pick
+// (highest score, then earliest row), and a later group only replaces the best on a strictly higher score.
+// Scores lie within +-2^21, missing candidates carry MATCH_NONE: both survive the shift by four.
+constexpr int MATCH_NONE = -(1 << 26);       // score word of a missing candidate (minus its "penalty")
+constexpr int MATCH_VALID = -(1 << 25);      // every real score is above, every missing one below
+struct LaneBest {
+    int s = INT_MIN, m = 0, g = 0;           // best score, its packed word, the group it came from
+    __device__ __forceinline__ void take(const i32x16 &acc, int group) {
+        int p[16];
+#pragma unroll
+        for (int v = 0; v < 16; ++v) p[v] = (int)(((unsigned)acc[v] << 4) + (unsigned)(15 - v));
+        int mx = p[0];
+#pragma unroll
+        for (int v = 1; v < 16; ++v) mx = max(mx, p[v]);
+        const int sc = mx >> 4;
+        if (sc > s) { s = sc; m = mx; g = group; }
+    }
+    // position of the best among the candidates (group * 32 + row), or -1 when no real candidate was seen
+    __device__ __forceinline__ int pos(int g2) const {
+        if (s <= MATCH_VALID) return -1;
+        const int v = 15 - (m & 15);
+        return g * 32 + 8 * (v >> 2) + 4 * g2 + (v & 3);
+    }
+    // (score, position) as one word ordered like the arg-max: higher score first, then the earlier position
+    __device__ __forceinline__ u64 key(int g2, int pos0) const {
+        const int p = pos(g2);
+        return p < 0 ? 0ull : ((u64)(unsigned)(s + SCORE_BIAS) << 32) | (u64)(0xFFFFFFFFu - (unsigned)(pos0 + p));
+    }
+};
+
 // ---- match -------------------------------------------------------------------------------------------
 // D = A x B: A rows = 32 candidate slots (codes gathered by slot id), B columns = 32 tokens (probe codes).
 // A lane therefore sees 16 candidates of one token per matrix instruction and keeps the best
@@ -68,8 +100,7 @@ __global__ __launch_bounds__(256) void tc_match_kernel(const int8_t *__restrict_
                                                        u64 *__restrict__ best) {
     constexpr int KS = R / 32;
     constexpr int NIT = CAND_CHUNK / 32;  // groups of 32 candidates per workgroup
-    __shared__ __attribute__((aligned(16))) int cslot[4][CAND_CHUNK];  // [wave][candidate] slot id (-1: none)
-    __shared__ __attribute__((aligned(16))) int cpen[4][CAND_CHUNK];   // score penalty: |code|^2 (metric 0), 0 (metric 1), 2^30 (none)
+    __shared__ __attribute__((aligned(16))) int cpen[4][CAND_CHUNK];   // minus the score penalty: -|code|^2 (metric 0), 0 (metric 1); MATCH_NONE: no candidate
     const int h = blockIdx.z;
     const int L = min(len[h], C);
     const int n_pos = cand ? n_cand : L;
@@ -117,50 +148,31 @@ __global__ __launch_bounds__(256) void tc_match_kernel(const int8_t *__restrict_
 #pragma unroll
             for (int m = 0; m < 4; ++m) nn = dot4_i8((unsigned)afrag[it][ks][m], (unsigned)afrag[it][ks][m], nn);
         nn += shfl_xor(nn, 32);
-        if (g2 == 0) {
-            cslot[wave][it * 32 + col] = slot[it];
-            cpen[wave][it * 32 + col] = slot[it] >= 0 ? (metric == 0 ? nn : 0) : (1 << 30);
-        }
+        if (g2 == 0) cpen[wave][it * 32 + col] = slot[it] >= 0 ? (metric == 0 ? -nn : 0) : MATCH_NONE;
     }
     __syncthreads();  // every wavefront reads back only its own rows; the barrier orders write and read
-    // Running arg-max per lane: the 16 scores of a matrix instruction are reduced with plain 32-bit maxima;
-    // the slot ids are looked at only when that maximum reaches the best score seen so far.
-    const int mult = metric == 0 ? 2 : 1;
-    int best_s = INT_MIN, best_slot = INT_MAX;
+    LaneBest lb;
 #pragma unroll
     for (int it = 0; it < NIT; ++it) {
         if (pos0 + it * 32 >= pos1) break;  // uniform
-        i32x16 acc = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
-#pragma unroll
-        for (int ks = 0; ks < KS; ++ks) acc = mfma_i8_32x32x32(afrag[it][ks], bfrag[ks], acc);
-        int m = INT_MIN;
+        // the accumulator starts from minus the penalty of its rows and takes the product twice for 2 * dot:
+        // the matrix unit does the arithmetic of the score
+        i32x16 acc;
 #pragma unroll
         for (int q4 = 0; q4 < 4; ++q4) {
-            const i32x4 pen = *(const i32x4 *)(&cpen[wave][it * 32 + 8 * q4 + 4 * g2]);
+            const i32x4 np = *(const i32x4 *)(&cpen[wave][it * 32 + 8 * q4 + 4 * g2]);
 #pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                acc[4 * q4 + e] = acc[4 * q4 + e] * mult - pen[e];
-                m = max(m, acc[4 * q4 + e]);
-            }
+            for (int e = 0; e < 4; ++e) acc[4 * q4 + e] = np[e];
         }
-        if (__any(m >= best_s && m > -(1 << 29))) {
-            int sl = INT_MAX;
 #pragma unroll
-            for (int q4 = 0; q4 < 4; ++q4) {
-                const i32x4 ids = *(const i32x4 *)(&cslot[wave][it * 32 + 8 * q4 + 4 * g2]);
+        for (int ks = 0; ks < KS; ++ks) acc = mfma_i8_32x32x32(afrag[it][ks], bfrag[ks], acc);
+        if (metric == 0) {
 #pragma unroll
-                for (int e = 0; e < 4; ++e)
-                    if (acc[4 * q4 + e] == m) sl = min(sl, ids[e]);
-            }
-            if (m > -(1 << 29)) {  // at least one real candidate among the 16
-                if (m > best_s) { best_s = m; best_slot = sl; }
-                else if (m == best_s) best_slot = min(best_slot, sl);
-            }
+            for (int ks = 0; ks < KS; ++ks) acc = mfma_i8_32x32x32(afrag[it][ks], bfrag[ks], acc);
         }
+        lb.take(acc, it);
     }
-    u64 mybest = 0;
-    if (best_s != INT_MIN)
-        mybest = ((u64)(unsigned)(best_s + SCORE_BIAS) << 32) | (u64)(0xFFFFFFFFu - (unsigned)best_slot);
+    u64 mybest = lb.key(g2, pos0);
     {
         const unsigned lo = shfl_xor((unsigned)mybest, 32), hi = shfl_xor((unsigned)(mybest >> 32), 32);
         const u64 other = ((u64)hi << 32) | lo;
@@ -177,12 +189,6 @@ __global__ __launch_bounds__(256) void tc_match_kernel(const int8_t *__restrict_
 // meet through LDS.  The epilogue per 32 x 32 scores is plain integer ALU work, so two wavefronts per SIMD (not
 // one) are what keeps the ALUs issuing.
 // LDS: codes chunk-major ([16-byte chunk][candidate], conflict-free A-operand reads), slot ids, penalties.
-// three-input minimum in one instruction (the compiler folds a select into each two-input minimum instead)
-__device__ __forceinline__ int min3_i32(int a, int b, int c) {
-    int r;
-    asm("v_min3_i32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
-    return r;
-}
 // With ENC the kernel also is the call's encode step for its 64 tokens (probe = new key): it quantises and projects
 // their rows while the window's loads are in flight, leaves the codes in ck for the apply step, and clears the
 // eviction plan's scratch words (ps_all) for the launches behind it.
@@ -268,7 +274,7 @@ __global__ __launch_bounds__(WIN_THREADS) void tc_match_window_kernel(const int8
                     for (int m = 0; m < 4; ++m) nn = dot4_i8((unsigned)row[u][c][m], (unsigned)row[u][c][m], nn);
                 }
                 cslot[p] = sl[u];
-                cpen[p] = sl[u] >= 0 ? (metric == 0 ? -nn : 0) : -(1 << 30);  // minus the penalty
+                cpen[p] = sl[u] >= 0 ? (metric == 0 ? -nn : 0) : MATCH_NONE;  // minus the penalty
             }
         }
     }
@@ -285,11 +291,10 @@ __global__ __launch_bounds__(WIN_THREADS) void tc_match_window_kernel(const int8
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) bfrag[ks] = *(const i32x4 *)(pcode + (tg * 32 + col) * R + ks * 32 + 16 * g2);
     }
-    // running arg-max per lane, as in the chunked kernel: 32-bit maxima, slot ids only on a new or tied best
-    int best_s = INT_MIN, best_slot = INT_MAX;
+    LaneBest lb;
     const int n_groups = n_pad / 32;
     // Four groups of 32 candidates per step, their operand reads and matrix instructions issued together
-    // (a group repeated at the ragged end changes nothing: maxima and minima are idempotent).
+    // (a group repeated at the ragged end changes nothing: only a strictly higher score replaces the best).
     constexpr int UNR = 4;
     for (int g0 = ch * UNR; g0 < n_groups; g0 += SPLIT * UNR) {
         i32x4 afrag[UNR][KS];
@@ -317,31 +322,9 @@ __global__ __launch_bounds__(WIN_THREADS) void tc_match_window_kernel(const int8
             }
         }
 #pragma unroll
-        for (int u = 0; u < UNR; ++u) {
-            const int gi = min(g0 + u, n_groups - 1);
-            int m = INT_MIN;
-#pragma unroll
-            for (int e = 0; e < 16; ++e) m = max(m, acc[u][e]);
-            if (__any(m >= best_s && m > -(1 << 29))) {
-                int sl = INT_MAX;
-#pragma unroll
-                for (int q4 = 0; q4 < 4; ++q4) {
-                    const i32x4 ids = *(const i32x4 *)(&cslot[gi * 32 + 8 * q4 + 4 * g2]);
-                    int t[4];
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) t[e] = acc[u][4 * q4 + e] == m ? ids[e] : INT_MAX;
-                    sl = min3_i32(min3_i32(sl, t[0], t[1]), t[2], t[3]);
-                }
-                if (m > -(1 << 29)) {
-                    if (m > best_s) { best_s = m; best_slot = sl; }
-                    else if (m == best_s) best_slot = min(best_slot, sl);
-                }
-            }
-        }
+        for (int u = 0; u < UNR; ++u) lb.take(acc[u], min(g0 + u, n_groups - 1));
     }
-    u64 mybest = 0;
-    if (best_s != INT_MIN)
-        mybest = ((u64)(unsigned)(best_s + SCORE_BIAS) << 32) | (u64)(0xFFFFFFFFu - (unsigned)best_slot);
+    u64 mybest = lb.key(g2, 0);
     {
         const unsigned lo = shfl_xor((unsigned)mybest, 32), hi = shfl_xor((unsigned)(mybest >> 32), 32);
         const u64 other = ((u64)hi << 32) | lo;
@@ -357,7 +340,7 @@ __global__ __launch_bounds__(WIN_THREADS) void tc_match_window_kernel(const int8
         }
         int j = -1, S = 0;
         if (mybest != 0) {
-            j = (int)(0xFFFFFFFFu - (unsigned)mybest);
+            j = cslot[(int)(0xFFFFFFFFu - (unsigned)mybest)];   // position in the window -> slot
             S = (int)(unsigned)(mybest >> 32) - SCORE_BIAS;
             win[(size_t)h * C + j] = 0;
             grp[(size_t)h * C + j] = 0;
@@ -385,6 +368,7 @@ static int launch_match_window(dim3 grid, size_t lds, hipStream_t s, Args... arg
 // ---- prep (only behind the chunked match, which leaves packed arg-max keys) ---------------------------------
 // Unpacks the match and clears the per-slot group records it will touch.
 __global__ __launch_bounds__(256) void tc_prep_kernel(const u64 *__restrict__ best, int n_new, int C,
+                                                      const int32_t *__restrict__ cand, int n_cand,
                                                       int32_t *__restrict__ jstar, int32_t *__restrict__ sbest,
                                                       u64 *__restrict__ win, int32_t *__restrict__ grp) {
     const int h = blockIdx.y;
@@ -393,7 +377,8 @@ __global__ __launch_bounds__(256) void tc_prep_kernel(const u64 *__restrict__ be
     const u64 key = best[(size_t)h * n_new + i];
     int j = -1, S = 0;
     if (key != 0) {
-        j = (int)(0xFFFFFFFFu - (unsigned)key);
+        const int pos = (int)(0xFFFFFFFFu - (unsigned)key);   // position in the candidate list (the slot without a list)
+        j = cand ? cand[(size_t)h * n_cand + pos] : pos;
         S = (int)(unsigned)(key >> 32) - SCORE_BIAS;
         win[(size_t)h * C + j] = 0;
         grp[(size_t)h * C + j] = 0;
@@ -1313,8 +1298,8 @@ extern "C" int tempcache_compress(const fastar_cache *cache, const fastar_codec 
         else FASTAR_MATCH(64, 256);
 #undef FASTAR_MATCH
         FASTAR_LAUNCH_CHECK();
-        hipLaunchKernelGGL(tc_prep_kernel, dim3((n_new + 255) / 256, H), dim3(256), 0, s, best, n_new, C, jstar, sbest,
-                           win, grp);
+        hipLaunchKernelGGL(tc_prep_kernel, dim3((n_new + 255) / 256, H), dim3(256), 0, s, best, n_new, C, cand, n_cand,
+                           jstar, sbest, win, grp);
         FASTAR_LAUNCH_CHECK();
     }
     const dim3 tgrid((n_new + 15) / 16, H);

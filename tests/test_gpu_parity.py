@@ -372,6 +372,8 @@ def test_tempcache_every_match_path_bit_exact(dtype, d, r, n_cand, probe, metric
     as_dt = lambda a: to_storage(a.astype(np.float32), dtype)
     ref = oracle.Cache.empty(H, C, d, r, dtype)
     ref.K[:] = as_dt(rng.standard_normal((H, C, d)))
+    ref.K[:, 1000:1400] = ref.K[:, 0:400]                        # repeated keys: equally scored candidates
+    ref.K[:, 1500:1600] = ref.K[:, 100:200]
     ref.V[:] = as_dt(rng.standard_normal((H, C, d)))
     ref.code[:] = oracle.encode(ref.K, codec.R, codec.qscale, codec.shift)
     ref.cnt[:] = rng.integers(1, 4, size=(H, C))
@@ -388,6 +390,10 @@ def test_tempcache_every_match_path_bit_exact(dtype, d, r, n_cand, probe, metric
     if n_cand:
         cand = rng.integers(0, 2350, size=(H, n_cand)).astype(np.int32)   # some ids are past the live length
         cand[:, : min(150, n_cand)] = src[:, : min(150, n_cand)]
+        if n_cand >= 700:                                         # both copies of repeated keys, in shuffled order
+            twins = np.concatenate([np.arange(0, 200), np.arange(1000, 1200), np.arange(1500, 1600)])
+            for h in range(H):
+                cand[h, 200:700] = rng.permutation(twins)
         cand[:, ::17] = -1
         cand[:, 5::29] = cand[:, 4::29][:, : cand[:, 5::29].shape[1]]     # repeated ids
     args = dict(cand=cand, metric=metric, tau2_q16=TAU2(0.9), frame_id=9)
