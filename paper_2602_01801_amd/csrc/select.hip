@@ -32,7 +32,17 @@ __global__ void rep_kernel(const int8_t *__restrict__ qcode, int n_q, int r, int
         const int q0 = b * BQ + u * g;
         const int q1 = min(q0 + g, n_q);
         int s = 0;
-        for (int q = q0; q < q1; ++q) s += qcode[((size_t)h * n_q + q) * r + j];
+        const int8_t *col = qcode + ((size_t)h * n_q + q0) * r + j;
+        const int n = q1 - q0;
+        int q = 0;
+        for (; q + 8 <= n; q += 8) {   // eight independent loads in flight
+            int v[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) v[e] = col[(size_t)(q + e) * r];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) s += v[e];
+        }
+        for (; q < n; ++q) s += col[(size_t)q * r];
         s += g / 2;
         int m = s / g;
         if (s % g != 0 && s < 0) m -= 1;
