@@ -283,6 +283,9 @@ __global__ __launch_bounds__(256) void score_self_stream_kernel(const int8_t *__
 // keys: LDS staging for up to TOPK_LDS_CAP entries of a row in global memory, or nullptr (row read in place).
 __device__ __forceinline__ void topk_row(const int32_t *row, int n, int n_sel, int32_t *__restrict__ out,
                                          int32_t *__restrict__ nsel_out, unsigned *keys) {
+    // Scores are sums of at most 64 products of 8-bit codes (or counts of equal hash bits): |score| < 2^21, and
+    // anything below (the INT_MIN of a block without a live key) is clamped there, so an order-preserving key has
+    // 22 bits: three passes over 8-bit digits (the first has 6 significant bits) select exactly.
     __shared__ unsigned hist[256];
     __shared__ unsigned sh_bin, sh_remaining;
     __shared__ unsigned wtot_a[4], wtot_b[4];
@@ -296,18 +299,19 @@ __device__ __forceinline__ void topk_row(const int32_t *row, int n, int n_sel, i
         for (int t = tid; t < n; t += 256) out[t] = t;
         return;
     }
+    auto to_key = [](int32_t sc) -> unsigned { return (unsigned)(max(sc, -(1 << 21)) + (1 << 21)); };
     const bool cached = keys != nullptr && n <= TOPK_LDS_CAP;
     if (cached)
-        for (int t = tid; t < n; t += 256) keys[t] = (unsigned)row[t] ^ 0x80000000u;
-    auto key_at = [&](int i) -> unsigned { return cached ? keys[i] : ((unsigned)row[i] ^ 0x80000000u); };
+        for (int t = tid; t < n; t += 256) keys[t] = to_key(row[t]);
+    auto key_at = [&](int i) -> unsigned { return cached ? keys[i] : to_key(row[i]); };
 
-    // radix select, most significant byte first: after the loop `prefix` is the k-th largest key and
+    // radix select, most significant digit first: after the loop `prefix` is the k-th largest key and
     // `remaining` the number of entries equal to it that belong to the selection
     unsigned prefix = 0, mask = 0, remaining = (unsigned)k;
-    for (int shift = 24; shift >= 0; shift -= 8) {
+    for (int shift = 16; shift >= 0; shift -= 8) {
         hist[tid] = 0;
         __syncthreads();
-        // The leading bytes of a row's scores are often all alike: when every candidate of a wavefront falls into one
+        // The leading digits of a row's scores are often all alike: when every candidate of a wavefront falls into one
         // bin, one lane adds their number (64 additions to one LDS word are served one after the other).
         for (int base = 0; base < n; base += 256) {   // uniform trip count
             const int t = base + tid;
@@ -423,25 +427,35 @@ __global__ __launch_bounds__(256) void score_cross_kernel(const int8_t *__restri
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) afrag[ks] = *(const i32x4 *)(qc + (size_t)qrow * R + ks * 32 + 16 * g2);
         const bool partial = qg + 32 > q_end;
-        for (int p0 = 0; p0 < n_p; p0 += 32) {
-            const int prow = min(p0 + col, n_p - 1);
-            i32x16 acc = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+        // eight groups of 32 prompt tokens per step: their codes are loaded together, then scored
+        constexpr int PB = 8;
+        for (int pb = 0; pb < n_p; pb += 32 * PB) {
+            i32x4 bfrag[PB][KS];
 #pragma unroll
-            for (int ks = 0; ks < KS; ++ks) {
-                i32x4 bfrag = *(const i32x4 *)(pc + (size_t)prow * R + ks * 32 + 16 * g2);
-                acc = mfma_i8_32x32x32(afrag[ks], bfrag, acc);
+            for (int u = 0; u < PB; ++u) {
+                const int prow = min(pb + 32 * u + col, n_p - 1);
+#pragma unroll
+                for (int ks = 0; ks < KS; ++ks) bfrag[u][ks] = *(const i32x4 *)(pc + (size_t)prow * R + ks * 32 + 16 * g2);
             }
-            int m = INT_MIN;
-            if (partial) {
 #pragma unroll
-                for (int v = 0; v < 16; ++v)
-                    if (qg + 8 * (v >> 2) + 4 * g2 + (v & 3) < q_end) m = max(m, acc[v]);
-            } else {
+            for (int u = 0; u < PB; ++u) {
+                const int p0 = pb + 32 * u;
+                if (p0 >= n_p) break;   // uniform
+                i32x16 acc = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
 #pragma unroll
-                for (int v = 0; v < 16; ++v) m = max(m, acc[v]);
+                for (int ks = 0; ks < KS; ++ks) acc = mfma_i8_32x32x32(afrag[ks], bfrag[u][ks], acc);
+                int m = INT_MIN;
+                if (partial) {
+#pragma unroll
+                    for (int v = 0; v < 16; ++v)
+                        if (qg + 8 * (v >> 2) + 4 * g2 + (v & 3) < q_end) m = max(m, acc[v]);
+                } else {
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) m = max(m, acc[v]);
+                }
+                m = max(m, shfl_xor(m, 32));
+                if (g2 == 0 && p0 + col < n_p) atomicMax(&smax[p0 + col], m);
             }
-            m = max(m, shfl_xor(m, 32));
-            if (g2 == 0 && p0 + col < n_p) atomicMax(&smax[p0 + col], m);
         }
     }
     __syncthreads();
