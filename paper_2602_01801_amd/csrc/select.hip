@@ -301,8 +301,21 @@ __device__ __forceinline__ void topk_row(const int32_t *row, int n, int n_sel, i
     }
     auto to_key = [](int32_t sc) -> unsigned { return (unsigned)(max(sc, -(1 << 21)) + (1 << 21)); };
     const bool cached = keys != nullptr && n <= TOPK_LDS_CAP;
-    if (cached)
-        for (int t = tid; t < n; t += 256) keys[t] = to_key(row[t]);
+    if (cached) {
+        for (int t0 = 0; t0 < n; t0 += 4 * 256) {   // four loads in flight per thread
+            int32_t v[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const int t = t0 + e * 256 + tid;
+                v[e] = t < n ? row[t] : 0;
+            }
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const int t = t0 + e * 256 + tid;
+                if (t < n) keys[t] = to_key(v[e]);
+            }
+        }
+    }
     auto key_at = [&](int i) -> unsigned { return cached ? keys[i] : to_key(row[i]); };
 
     // radix select, most significant digit first: after the loop `prefix` is the k-th largest key and
