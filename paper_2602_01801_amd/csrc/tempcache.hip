@@ -1116,17 +1116,19 @@ __global__ __launch_bounds__(256) void tc_apply_kernel(void *__restrict__ K, voi
     int dst = -1;
     if (mg) {
         dst = j;
+        // second round of loads, everything addressed by the slot at once: its records and multiplicity, and already
+        // its value row (and key row for the mean key), which only the group's representative goes on to use
+        const bool mean_key = rep_mode == 1;
+        float acc[RP::EPL], vn[RP::EPL], kacc[RP::EPL], kn[RP::EPL];
         const u64 wkey = win[cb + j];
         const int gc = grp[cb + j];
         const int m0 = cnt[cb + j];
+        RP::load(V, cb + j, l16, acc);
+        if (mean_key) RP::load(K, cb + j, l16, kacc);
         const int widx = (int)(0xFFFFFFFFu - (unsigned)wkey);
         if (widx == i) {  // this token represents the group: it refreshes the slot
             // mean value; with rep_mode 1 also the mean key, whose stored bits feed later integer decisions: single
             // float32 operations in a fixed order (multiplicity * old row, members in ascending token order, one division)
-            const bool mean_key = rep_mode == 1;
-            float acc[RP::EPL], vn[RP::EPL], kacc[RP::EPL], kn[RP::EPL];
-            RP::load(V, cb + j, l16, acc);
-            if (mean_key) RP::load(K, cb + j, l16, kacc);
 #pragma unroll
             for (int e = 0; e < RP::EPL; ++e) acc[e] *= (float)m0;
             if (mean_key) {
