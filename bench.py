@@ -42,6 +42,8 @@ def parse():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="cfg2", choices=["cfg2", "cfg5"])
     ap.add_argument("--tau", type=float, default=0.98)
+    ap.add_argument("--cross", choices=["fused", "separate"], default="fused",
+                    help="AnnCA as one launch (selection + attention) or as ann_select_cross followed by sparse_attn_fwd")
     ap.add_argument("--rep", choices=["last", "mean"], default="last",
                     help="representative key of a merged group: the last key (the method) or the mean key (its ablation)")
     ap.add_argument("--prefill-frames", type=int, default=None, help="frames merged into the cache before timing")
@@ -62,9 +64,11 @@ def parse():
 class ChunkPipeline:
     """Device buffers and the call sequence of one chunk step.  Nothing is allocated per step."""
 
-    def __init__(self, cfg, C, tau, torch, fa, dev_codec, prompt, n_sel_blocks, sign_matrix=None, rep_mode=0):
+    def __init__(self, cfg, C, tau, torch, fa, dev_codec, prompt, n_sel_blocks, sign_matrix=None, rep_mode=0,
+                 fused_cross=True):
         self.t, self.fa, self.cfg = torch, fa, cfg
         self.rep_mode = rep_mode
+        self.fused_cross = fused_cross
         H, d, r, T = cfg["H"], cfg["d"], cfg["r"], cfg["T"]
         self.H, self.d, self.r, self.T, self.C = H, d, r, T, C
         self.BQ, self.BK, self.n_rep = cfg["BQ"], cfg["BK"], cfg["n_rep"]
@@ -135,10 +139,15 @@ class ChunkPipeline:
         fa.sparse_attn_fwd(Q, self.cache.K, self.cache.V, self.cache.cnt, self.cache.len, self.sel[0], self.sel[1],
                            self.BQ, self.BK, self.scale, out=self.O)
         mark("attn_self")
-        fa.ann_select_cross(self.qcode, self.pcode, self.BQ, self.n_sel_cross, ws=self.ws_x, out=self.csel)
-        mark("select_cross")
-        fa.sparse_attn_fwd(Q, self.pK, self.pV, None, self.plen, self.csel[0], self.csel[1], self.BQ, 1, self.scale,
-                           out=self.Ox, want_lse=False)
+        if self.fused_cross:   # selection and attention over it in one launch; the stage is booked under select_cross
+            fa.ann_cross_attn_fwd(Q, self.qcode, self.pK, self.pV, self.pcode, self.BQ, self.n_sel_cross, self.scale,
+                                  out=(self.csel[0], self.csel[1], self.Ox[0]))
+            mark("select_cross")
+        else:
+            fa.ann_select_cross(self.qcode, self.pcode, self.BQ, self.n_sel_cross, ws=self.ws_x, out=self.csel)
+            mark("select_cross")
+            fa.sparse_attn_fwd(Q, self.pK, self.pV, None, self.plen, self.csel[0], self.csel[1], self.BQ, 1, self.scale,
+                               out=self.Ox, want_lse=False)
         mark("attn_cross")
 
     def dense_equivalent_ms(self, Q, reps=3):
@@ -335,7 +344,8 @@ def main():
     sign_h = make_sign_matrix(cfg["seed"], cfg["cfg_id"], cfg["d"], 128) if args.ann == "lsh" else None
     pipe = ChunkPipeline(cfg, C, args.tau, torch, fa, codec, (to_dev(ps.K), to_dev(ps.V)), n_sel,
                          sign_matrix=None if sign_h is None else to_dev(sign_h),
-                         rep_mode=fa.REP_MEAN if args.rep == "mean" else fa.REP_LAST)
+                         rep_mode=fa.REP_MEAN if args.rep == "mean" else fa.REP_LAST,
+                         fused_cross=args.cross == "fused")
     for K, V in prefill:
         pipe.compress(K, V)
     torch.cuda.synchronize()
@@ -406,6 +416,7 @@ def main():
                                f"(BQ {cfg['BQ']}, BK {cfg['BK']}), AnnCA {cfg['n_sel_cross']} of {cfg['n_p']} prompt tokens",
                    "ann": f"int8 projection codes (r 32, shift {codec_h.shift})" if args.ann == "int8" else "sign codes, 128 hash bits (LSH variant)",
                    "representative": args.rep + " key",
+                   "cross_attention": "one launch (ann_cross_attn_fwd)" if args.cross == "fused" else "ann_select_cross + sparse_attn_fwd",
                    "prefill_frames": n_prefill, "cache_len_per_head_start": [min(len_prefill), max(len_prefill)],
                    "cache_len_per_head_end": [min(len_final), max(len_final)],
                    "cache_bytes": pipe.cache.nbytes()},

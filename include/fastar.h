@@ -6,6 +6,7 @@
  *   tempcache_compress   merge one frame of new K/V into the bounded per-head cache (TempCache)
  *   ann_select_self      key blocks each query block attends to (AnnSA)
  *   ann_select_cross     prompt tokens each query block attends to (AnnCA)
+ *   ann_cross_attn_fwd   the same selection and the attention over it in one launch
  *   sparse_attn_fwd      softmax attention over the selected keys only, with the log-multiplicity bias
  *
  * Conventions (all entry points):
@@ -191,6 +192,20 @@ int ann_select_self(const int8_t *qcode, int n_q, const int8_t *kcode, const int
  */
 int ann_select_cross(const int8_t *qcode, int n_q, const int8_t *pcode, int n_p, int H, int r, int BQ,
                      int n_sel, int32_t *sel, int32_t *nsel, void *ws, size_t ws_bytes, void *stream);
+
+/*
+ * AnnCA in one launch (Sec. 5.3): the selection of ann_select_cross followed by the attention of sparse_attn_fwd
+ * over it (BK = 1, no multiplicities, every prompt token live), for callers that need both and no lse:
+ *   sel, nsel  exactly what ann_select_cross(qcode, pcode, BQ, n_sel) writes;
+ *   O          exactly what sparse_attn_fwd(Q, Kp, Vp, NULL, len = n_p, sel, nsel, BQ, 1, n_sel, scale) computes
+ *              (same arithmetic: bf16 products, fp32 softmax over the selected tokens in one piece).
+ *   Q [H,n_q,d], Kp, Vp [H,n_p,d] bf16;  qcode [H,n_q,r], pcode [H,n_p,r];  O [H,n_q,d] bf16 out.
+ * Supported: bf16, d = 128, BQ = 128, n_sel <= 64, r in {32,64}, n_p <= 12288; anything else is
+ * FASTAR_ERR_UNSUPPORTED and the two separate calls do the same work.  No workspace.
+ */
+int ann_cross_attn_fwd(const void *Q, const int8_t *qcode, int n_q, const void *Kp, const void *Vp,
+                       const int8_t *pcode, int n_p, int H, int d, int dtype, int r, int BQ, int n_sel, float scale,
+                       int32_t *sel, int32_t *nsel, void *O, void *stream);
 
 /*
  * Block-sparse attention (Eq. 1 restricted to the candidate set of Sec. 5.1, logits shifted by

@@ -17,6 +17,7 @@ from .binding import (  # noqa: F401
     Cache,
     Codec,
     FastarError,
+    ann_cross_attn_fwd,
     ann_select_cross,
     ann_select_lsh,
     ann_select_self,

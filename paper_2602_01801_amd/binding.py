@@ -58,6 +58,11 @@ def lib() -> ctypes.CDLL:
                                          ctypes.c_int, ctypes.c_int32, ctypes.c_int32, ctypes.c_int, ctypes.c_void_p,
                                          ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t,
                                          ctypes.c_void_p]
+        L.ann_cross_attn_fwd.restype = ctypes.c_int
+        L.ann_cross_attn_fwd.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p,
+                                         ctypes.c_void_p, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int,
+                                         ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_float, ctypes.c_void_p,
+                                         ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
         L.ann_select_self.restype = ctypes.c_int
         L.ann_select_self.argtypes = [ctypes.c_void_p, ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int,
                                       ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int,
@@ -87,6 +92,7 @@ def lib() -> ctypes.CDLL:
 
 
 EXPORTS = ("fastar_version", "fastar_strerror", "fastar_workspace_bytes", "fastar_encode", "tempcache_compress",
+           "ann_cross_attn_fwd",
            "ann_select_self", "ann_select_cross", "sparse_attn_fwd", "fastar_encode_sign", "ann_select_lsh",
            "fastar_probe_mfma_bf16", "fastar_probe_copy")
 
@@ -287,6 +293,26 @@ def ann_select_lsh(qbits, kbits, length, BQ: int, n_rep: int, BK: int, n_sel: in
                                 BK, n_sel, sel.data_ptr(), nsel.data_ptr(), ws.data_ptr(),
                                 ws.numel() * ws.element_size(), _stream()), "ann_select_lsh")
     return sel, nsel
+
+
+def ann_cross_attn_fwd(Q, qcode, Kp, Vp, pcode, BQ: int, n_sel: int, scale: float, out=None):
+    """AnnCA selection and the attention over it in one launch.  Returns (sel [H,n_qb,n_sel], nsel [H,n_qb], O)."""
+    _dev(Q)
+    _dev(Kp, Q.dtype)
+    _dev(Vp, Q.dtype)
+    _dev(qcode, torch.int8)
+    _dev(pcode, torch.int8)
+    H, n_q, d = Q.shape
+    n_p, r = pcode.shape[1], pcode.shape[2]
+    n_qb = (n_q + BQ - 1) // BQ
+    if out is None:
+        out = (torch.empty((H, n_qb, n_sel), dtype=torch.int32, device=Q.device),
+               torch.empty((H, n_qb), dtype=torch.int32, device=Q.device), torch.empty_like(Q))
+    sel, nsel, O = out
+    _check(lib().ann_cross_attn_fwd(Q.data_ptr(), qcode.data_ptr(), n_q, Kp.data_ptr(), Vp.data_ptr(), pcode.data_ptr(),
+                                    n_p, H, d, _dtype_code(Q), r, BQ, n_sel, float(scale), sel.data_ptr(),
+                                    nsel.data_ptr(), O.data_ptr(), _stream()), "ann_cross_attn_fwd")
+    return sel, nsel, O
 
 
 def sparse_attn_fwd(Q, K, V, cnt, length, sel, nsel, BQ: int, BK: int, scale: float, out=None, want_lse: bool = True):

@@ -420,20 +420,16 @@ __device__ __forceinline__ void topk_row(const int32_t *row, int n, int n_sel, i
 // ---- AnnCA scoring -----------------------------------------------------------------------------------
 // score[p] = max over the queries q of block b of qcode[q] . pcode[p], kept in LDS, then the top n_sel of the row.
 // D = A x B with A rows = 32 queries, B columns = 32 prompt tokens.
+// smax[p] = max over the queries of block b of qcode[q] . pcode[p], for all n_p prompt tokens; whole workgroup.
 template <int R>
-__global__ __launch_bounds__(256) void score_cross_kernel(const int8_t *__restrict__ qcode, const int8_t *__restrict__ pcode,
-                                                          int n_q, int n_p, int BQ, int n_qb, int n_sel,
-                                                          int32_t *__restrict__ sel, int32_t *__restrict__ nsel) {
+__device__ __forceinline__ void score_cross_block(const int8_t *__restrict__ qc, const int8_t *__restrict__ pc, int n_q,
+                                                  int n_p, int BQ, int b, int32_t *smax) {
     constexpr int KS = R / 32;
-    extern __shared__ int32_t smax[];  // [n_p]
-    const int b = blockIdx.x, h = blockIdx.y;
     const int lane = lane_id(), wave = threadIdx.x >> 6;
     const int col = lane & 31, g2 = lane >> 5;
     for (int t = threadIdx.x; t < n_p; t += blockDim.x) smax[t] = INT_MIN;
     __syncthreads();
     const int q_end = min((b + 1) * BQ, n_q);
-    const int8_t *qc = qcode + (size_t)h * n_q * R;
-    const int8_t *pc = pcode + (size_t)h * n_p * R;
     for (int qg = b * BQ + wave * 32; qg < q_end; qg += 4 * 32) {
         const int qrow = min(qg + col, n_q - 1);
         i32x4 afrag[KS];
@@ -472,8 +468,162 @@ __global__ __launch_bounds__(256) void score_cross_kernel(const int8_t *__restri
         }
     }
     __syncthreads();
+}
+
+template <int R>
+__global__ __launch_bounds__(256) void score_cross_kernel(const int8_t *__restrict__ qcode, const int8_t *__restrict__ pcode,
+                                                          int n_q, int n_p, int BQ, int n_qb, int n_sel,
+                                                          int32_t *__restrict__ sel, int32_t *__restrict__ nsel) {
+    extern __shared__ int32_t smax[];  // [n_p]
+    const int b = blockIdx.x, h = blockIdx.y;
+    score_cross_block<R>(qcode + (size_t)h * n_q * R, pcode + (size_t)h * n_p * R, n_q, n_p, BQ, b, smax);
     // the workgroup owns the whole row: select from LDS right away
     topk_row(smax, n_p, n_sel, sel + ((size_t)h * n_qb + b) * n_sel, nsel + (size_t)h * n_qb + b, nullptr);
+}
+
+// ---- AnnCA in one launch: selection and the attention over it (bf16, d = 128, blocks of 128 queries, up to 64 tokens) --
+// One workgroup = one query block: scores and exact top-n_sel as above (the list also goes to sel / nsel), then the
+// selected prompt rows are gathered into LDS once and the four wavefronts (32 queries each) attend to them:
+// S^T = K Q^T, softmax over the at most 64 tokens in one piece (no running maximum), O^T = V^T P^T.  V is stored
+// transposed ([d][token]) with the tokens of each 16 in the order the score accumulators hold them, so that the
+// accumulators, converted to bf16, are the second product's operand as they are.
+namespace fused {
+constexpr int D = 128, TK = 64;
+constexpr int KROW = D * 2 + 16;          // bytes per staged K row (padded: 16 consecutive rows hit 16 different bank groups)
+constexpr int VROW = TK * 2 + 16;         // bytes per staged V^T row
+constexpr int OROW = D * 2 + 16;          // bytes per staged output row
+constexpr int TILE_BYTES = TK * KROW + D * VROW;   // 17408 + 18432; the output staging (128 rows x OROW) reuses it
+static_assert(128 * OROW <= TILE_BYTES, "output staging fits the tile region");
+__host__ __device__ inline size_t lds_bytes(int n_p) { return ((size_t)n_p * 4 + 15) / 16 * 16 + TK * 4 + 16 + TILE_BYTES; }
+}  // namespace fused
+
+template <int R>
+__global__ __launch_bounds__(256) void cross_fused_kernel(const unsigned short *__restrict__ Q, const int8_t *__restrict__ qcode,
+                                                          const unsigned short *__restrict__ Kp,
+                                                          const unsigned short *__restrict__ Vp,
+                                                          const int8_t *__restrict__ pcode, int n_q, int n_p, int n_qb,
+                                                          int n_sel, float scale_log2, int32_t *__restrict__ sel,
+                                                          int32_t *__restrict__ nsel, unsigned short *__restrict__ O) {
+    using namespace fused;
+    extern __shared__ __attribute__((aligned(16))) unsigned char flds[];
+    int32_t *smax = (int32_t *)flds;
+    int32_t *lsel = (int32_t *)(flds + ((size_t)n_p * 4 + 15) / 16 * 16);   // [TK] selected tokens, ascending
+    int32_t *lcnt = lsel + TK;                                              // [1] how many
+    unsigned char *ktile = (unsigned char *)(lcnt + 4);
+    unsigned char *vtile = ktile + TK * KROW;
+    const int b = blockIdx.x, h = blockIdx.y;
+    const int tid = threadIdx.x, lane = lane_id(), wave = tid >> 6;
+    const int col = lane & 31, g = lane >> 5;
+    // this lane's query row as the second operand of K Q^T: in flight during the selection
+    const int q_idx = b * 128 + wave * 32 + col;
+    bf16x8 qf[D / 16];
+    {
+        const unsigned short *qrow = Q + ((size_t)h * n_q + min(q_idx, n_q - 1)) * D;
+#pragma unroll
+        for (int s = 0; s < D / 16; ++s) qf[s] = *(const bf16x8 *)(qrow + 16 * s + 8 * g);
+    }
+    score_cross_block<R>(qcode + (size_t)h * n_q * R, pcode + (size_t)h * n_p * R, n_q, n_p, 128, b, smax);
+    topk_row(smax, n_p, n_sel, lsel, lcnt, nullptr);
+    __syncthreads();
+    const int k = lcnt[0];
+    if (tid < n_sel) sel[((size_t)h * n_qb + b) * n_sel + tid] = lsel[tid];
+    if (tid == 0) nsel[(size_t)h * n_qb + b] = k;
+    // gather: K rows as they are, V rows transposed; slot p of the tile holds token lsel[p] (p >= k: token 0, masked below)
+    const unsigned short *Kh = Kp + (size_t)h * n_p * D, *Vh = Vp + (size_t)h * n_p * D;
+    {
+        u32x4 kv[4], vv[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const int idx = e * 256 + tid, p = idx >> 4, c = idx & 15;
+            const int tok = p < k ? lsel[p] : 0;
+            kv[e] = *(const u32x4 *)(Kh + (size_t)tok * D + 8 * c);
+            vv[e] = *(const u32x4 *)(Vh + (size_t)tok * D + 8 * c);
+        }
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const int idx = e * 256 + tid, p = idx >> 4, c = idx & 15;
+            *(u32x4 *)(ktile + p * KROW + c * 16) = kv[e];
+            // position of token slot p inside its 16: accumulator order (half g' = (o % 8) / 4 first, then o / 8, then o % 4)
+            const int o = p & 15;
+            const int pos = (p & ~15) + 8 * ((o & 7) >> 2) + 4 * (o >> 3) + (o & 3);
+#pragma unroll
+            for (int w = 0; w < 4; ++w) {
+                *(unsigned short *)(vtile + (8 * c + 2 * w) * VROW + pos * 2) = (unsigned short)(vv[e][w] & 0xFFFFu);
+                *(unsigned short *)(vtile + (8 * c + 2 * w + 1) * VROW + pos * 2) = (unsigned short)(vv[e][w] >> 16);
+            }
+        }
+    }
+    __syncthreads();
+    // S^T = K Q^T: rows = token slots (two blocks of 32), columns = this wavefront's 32 queries
+    f32x16 s_acc[2];
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb) {
+#pragma unroll
+        for (int v = 0; v < 16; ++v) s_acc[kb][v] = 0.0f;
+#pragma unroll
+        for (int s = 0; s < D / 16; ++s) {
+            const bf16x8 a = *(const bf16x8 *)(ktile + (32 * kb + col) * KROW + (16 * s + 8 * g) * 2);
+            s_acc[kb] = mfma_bf16_32x32x16(a, qf[s], s_acc[kb]);
+        }
+    }
+    // softmax over the k live slots (register v of block kb is slot 32 kb + 8 (v / 4) + 4 g + v % 4)
+    float mx = -INFINITY;
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int slot = 32 * kb + 8 * (v >> 2) + 4 * g + (v & 3);
+            if (slot >= k) s_acc[kb][v] = -INFINITY;
+            mx = fmaxf(mx, s_acc[kb][v]);
+        }
+    mx = fmaxf(mx, shfl_xor(mx, 32));
+    const float neg_ms = mx == -INFINITY ? 0.0f : -mx * scale_log2;
+    float l = 0.0f;
+    bf16x8 pf[2][2];
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+        for (int st = 0; st < 2; ++st)
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const float pv = __builtin_amdgcn_exp2f(fmaf(s_acc[kb][8 * st + j], scale_log2, neg_ms));
+                const __bf16 pb = (__bf16)pv;
+                pf[kb][st][j] = pb;
+                l += (float)pb;   // the sum takes the rounded P, the values the second product sees
+            }
+    l += shfl_xor(l, 32);
+    // O^T = V^T P^T: rows = 32 of the d coordinates per block, columns = queries
+    f32x16 o_acc[D / 32];
+#pragma unroll
+    for (int db = 0; db < D / 32; ++db) {
+#pragma unroll
+        for (int v = 0; v < 16; ++v) o_acc[db][v] = 0.0f;
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+            for (int st = 0; st < 2; ++st) {
+                const bf16x8 a = *(const bf16x8 *)(vtile + (32 * db + col) * VROW + (32 * kb + 16 * st + 8 * g) * 2);
+                o_acc[db] = mfma_bf16_32x32x16(a, pf[kb][st], o_acc[db]);
+            }
+    }
+    const float inv = l > 0.0f ? 1.0f / l : 0.0f;
+    __syncthreads();   // the tiles are dead: their LDS takes the output rows
+    unsigned char *orow = ktile + (size_t)(wave * 32 + col) * OROW;
+#pragma unroll
+    for (int db = 0; db < D / 32; ++db)
+#pragma unroll
+        for (int q4 = 0; q4 < 4; ++q4) {
+            u32x2 w;
+            w[0] = pack_bf16x2(o_acc[db][4 * q4] * inv, o_acc[db][4 * q4 + 1] * inv);
+            w[1] = pack_bf16x2(o_acc[db][4 * q4 + 2] * inv, o_acc[db][4 * q4 + 3] * inv);
+            *(u32x2 *)(orow + (32 * db + 8 * q4 + 4 * g) * 2) = w;
+        }
+    __syncthreads();
+    for (int idx = tid; idx < 128 * 16; idx += 256) {
+        const int r = idx >> 4, c = idx & 15;
+        const int qi = b * 128 + r;
+        if (qi < n_q) *(u32x4 *)(O + ((size_t)h * n_q + qi) * D + 8 * c) = *(const u32x4 *)(ktile + (size_t)r * OROW + c * 16);
+    }
 }
 
 // Row (h, b) of `score` holds n entries (n = ceil(len[h]/BK) when len is given, else n_fixed).
@@ -703,6 +853,42 @@ extern "C" int ann_select_cross(const int8_t *qcode, int n_q, const int8_t *pcod
     else
         hipLaunchKernelGGL(score_cross_kernel<64>, dim3(n_qb, H), dim3(256), lds, s, qcode, pcode, n_q, n_p, BQ, n_qb,
                            n_sel, sel, nsel);
+    FASTAR_LAUNCH_CHECK();
+    return FASTAR_OK;
+}
+
+extern "C" int ann_cross_attn_fwd(const void *Q, const int8_t *qcode, int n_q, const void *Kp, const void *Vp,
+                                  const int8_t *pcode, int n_p, int H, int d, int dtype, int r, int BQ, int n_sel,
+                                  float scale, int32_t *sel, int32_t *nsel, void *O, void *stream) {
+    if (!Q || !qcode || !Kp || !Vp || !pcode || !sel || !nsel || !O) return FASTAR_ERR_INVALID_ARG;
+    if (H <= 0 || n_q <= 0 || n_p <= 0 || n_sel <= 0) return FASTAR_ERR_INVALID_ARG;
+    if (!(scale > 0.0f) || !(scale < INFINITY)) return FASTAR_ERR_INVALID_ARG;
+    if (((uintptr_t)Q & 15) || ((uintptr_t)Kp & 15) || ((uintptr_t)Vp & 15) || ((uintptr_t)O & 15) ||
+        ((uintptr_t)qcode & 15) || ((uintptr_t)pcode & 15))
+        return FASTAR_ERR_INVALID_ARG;
+    if (dtype != FASTAR_BF16 || d != 128 || BQ != 128 || n_sel > fused::TK || (r != 32 && r != 64) || n_p > 12288)
+        return FASTAR_ERR_UNSUPPORTED;
+    const int n_qb = (n_q + 127) / 128;
+    const size_t lds = fused::lds_bytes(n_p);
+    hipStream_t s = (hipStream_t)stream;
+    const float scale_log2 = scale * 1.4426950408889634f;
+    static bool attr_set = false;   // more than 64 KB of LDS (long prompts) has to be allowed once per kernel
+    if (!attr_set) {
+        if (hipFuncSetAttribute((const void *)cross_fused_kernel<32>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                (int)fused::lds_bytes(12288)) != hipSuccess ||
+            hipFuncSetAttribute((const void *)cross_fused_kernel<64>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                (int)fused::lds_bytes(12288)) != hipSuccess)
+            return FASTAR_ERR_HIP;
+        attr_set = true;
+    }
+    if (r == 32)
+        hipLaunchKernelGGL(cross_fused_kernel<32>, dim3(n_qb, H), dim3(256), lds, s, (const unsigned short *)Q, qcode,
+                           (const unsigned short *)Kp, (const unsigned short *)Vp, pcode, n_q, n_p, n_qb, n_sel,
+                           scale_log2, sel, nsel, (unsigned short *)O);
+    else
+        hipLaunchKernelGGL(cross_fused_kernel<64>, dim3(n_qb, H), dim3(256), lds, s, (const unsigned short *)Q, qcode,
+                           (const unsigned short *)Kp, (const unsigned short *)Vp, pcode, n_q, n_p, n_qb, n_sel,
+                           scale_log2, sel, nsel, (unsigned short *)O);
     FASTAR_LAUNCH_CHECK();
     return FASTAR_OK;
 }

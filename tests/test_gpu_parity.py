@@ -209,6 +209,50 @@ def test_per_frame_prompt_selection_then_cross_attention_per_frame():
         check_attention(Qf, ps.K, ps.V, None, plen, sel_f, nsel_f, 128, 1, c["d"] ** -0.5, c["dtype"])
 
 
+@pytest.mark.parametrize("H,n_q,n_p,r,n_sel", [(2, 4680, 512, 32, 64), (1, 300, 2048, 64, 64), (2, 200, 40, 32, 64),
+                                               (3, 129, 97, 32, 17), (1, 128, 512, 32, 1)])
+def test_fused_prompt_selection_and_attention_matches_the_two_calls(H, n_q, n_p, r, n_sel):
+    """ann_cross_attn_fwd against the oracle's selection followed by its attention over that selection, and against the
+    library's own two-call path (ragged query tail, fewer prompt tokens than the budget, budgets below a full tile)."""
+    rng = np.random.default_rng(n_q + n_p + n_sel)
+    d = 128
+    codec = make_codec(0, 4, d, r)
+    Q = to_storage(rng.standard_normal((H, n_q, d)).astype(np.float32), "bf16")
+    Kp = to_storage(rng.standard_normal((H, n_p, d)).astype(np.float32), "bf16")
+    Vp = to_storage(rng.standard_normal((H, n_p, d)).astype(np.float32), "bf16")
+    qc_r = oracle.encode(Q, codec.R, codec.qscale, codec.shift)
+    pc_r = oracle.encode(Kp, codec.R, codec.qscale, codec.shift)
+    sel_r, nsel_r = oracle.ann_select_cross(qc_r, pc_r, 128, n_sel)
+    plen = np.full((H,), n_p, np.int32)
+    scale = d ** -0.5
+    O_r, _ = oracle.sparse_attn_fwd(Q, Kp, Vp, None, plen, sel_r, nsel_r, 128, 1, scale)
+    dQ, dK, dV = to_dev(Q), to_dev(Kp), to_dev(Vp)
+    dcodec = dev_codec(codec)
+    qc, pc = fa.encode(dQ, dcodec), fa.encode(dK, dcodec)
+    sel, nsel, O = fa.ann_cross_attn_fwd(dQ, qc, dK, dV, pc, 128, n_sel, scale)
+    sel2, nsel2 = fa.ann_select_cross(qc, pc, 128, n_sel)
+    O2, _ = fa.sparse_attn_fwd(dQ, dK, dV, None, to_dev(plen), sel2, nsel2, 128, 1, scale)
+    sync()
+    assert np.array_equal(to_host(sel), sel_r) and np.array_equal(to_host(nsel), nsel_r)
+    assert np.array_equal(to_host(sel2), sel_r)
+    Of = storage_to_f64(to_host(O))
+    assert np.isfinite(Of).all()
+    assert np.abs(Of - O_r).max() <= ATOL["bf16"]
+    assert np.abs(Of - storage_to_f64(to_host(O2))).max() <= ATOL["bf16"]
+
+
+def test_fused_prompt_attention_rejects_what_it_is_not_built_for():
+    Q = torch.zeros((1, 128, 64), dtype=torch.bfloat16, device="cuda")
+    code = torch.zeros((1, 128, 32), dtype=torch.int8, device="cuda")
+    with pytest.raises(fa.FastarError):
+        fa.ann_cross_attn_fwd(Q, code, Q, Q, code, 128, 16, 0.125)            # d = 64
+    Q = torch.zeros((1, 128, 128), dtype=torch.bfloat16, device="cuda")
+    with pytest.raises(fa.FastarError):
+        fa.ann_cross_attn_fwd(Q, code, Q, Q, code, 128, 65, 0.125)            # more than one tile of tokens
+    with pytest.raises(fa.FastarError):
+        fa.ann_cross_attn_fwd(Q, code, Q, Q, code, 64, 16, 0.125)             # query blocks of 64
+
+
 # ----------------------------------------------------------------------------------------- attention
 
 def random_selection(rng, H, n_qb, n_sel, lens, BK, empty_some=True):
