@@ -42,6 +42,9 @@ def parse():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="cfg2", choices=["cfg2", "cfg5"])
     ap.add_argument("--tau", type=float, default=0.98)
+    ap.add_argument("--ws", choices=["persistent", "scratch"], default="persistent",
+                    help="TempCache workspace: kept by the caller across calls (zero-filled once; one launch less per "
+                         "frame) or scratch that may hold anything")
     ap.add_argument("--cross", choices=["fused", "separate"], default="fused",
                     help="AnnCA as one launch (selection + attention) or as ann_select_cross followed by sparse_attn_fwd")
     ap.add_argument("--rep", choices=["last", "mean"], default="last",
@@ -65,8 +68,9 @@ class ChunkPipeline:
     """Device buffers and the call sequence of one chunk step.  Nothing is allocated per step."""
 
     def __init__(self, cfg, C, tau, torch, fa, dev_codec, prompt, n_sel_blocks, sign_matrix=None, rep_mode=0,
-                 fused_cross=True):
+                 fused_cross=True, ws_persistent=True):
         self.t, self.fa, self.cfg = torch, fa, cfg
+        self.ws_persistent = ws_persistent
         self.rep_mode = rep_mode
         self.fused_cross = fused_cross
         H, d, r, T = cfg["H"], cfg["d"], cfg["r"], cfg["T"]
@@ -83,7 +87,7 @@ class ChunkPipeline:
         self.cache = fa.Cache.empty(H, C, d, r, dt)
         dev = "cuda"
         e = lambda shape, dtype: torch.empty(shape, dtype=dtype, device=dev)
-        self.ws_c = e((fa.workspace_bytes(fa.OP_COMPRESS, H, T, C, r),), torch.uint8)
+        self.ws_c = torch.zeros((fa.workspace_bytes(fa.OP_COMPRESS, H, T, C, r),), dtype=torch.uint8, device=dev)
         self.ws_s = e((fa.workspace_bytes(fa.OP_SELECT_SELF, H, self.n_q, C, r, self.BQ, self.BK, self.n_rep),), torch.uint8)
         self.mm = [(e((H, T), torch.int32), e((H, T), torch.uint8), e((H, 8), torch.int32)) for _ in range(2)]
         self.qcode = e((H, self.n_q, r), torch.int8)
@@ -112,7 +116,8 @@ class ChunkPipeline:
         fa = self.fa
         out = self.mm[self.frame_id & 1]
         fa.tempcache_compress(self.cache, self.codec, K, V, cand=self.prev, tau2_q16=self.tau2,
-                              frame_id=self.frame_id, rep_mode=self.rep_mode, ws=self.ws_c, out=out)
+                              frame_id=self.frame_id, rep_mode=self.rep_mode, ws=self.ws_c, out=out,
+                              ws_persistent=self.ws_persistent)
         self.prev = out[0]
         self.frame_id += 1
 
@@ -347,7 +352,7 @@ def main():
     pipe = ChunkPipeline(cfg, C, args.tau, torch, fa, codec, (to_dev(ps.K), to_dev(ps.V)), n_sel,
                          sign_matrix=None if sign_h is None else to_dev(sign_h),
                          rep_mode=fa.REP_MEAN if args.rep == "mean" else fa.REP_LAST,
-                         fused_cross=args.cross == "fused")
+                         fused_cross=args.cross == "fused", ws_persistent=args.ws == "persistent")
     for K, V in prefill:
         pipe.compress(K, V)
     torch.cuda.synchronize()
@@ -418,6 +423,7 @@ def main():
                                f"(BQ {cfg['BQ']}, BK {cfg['BK']}), AnnCA {cfg['n_sel_cross']} of {cfg['n_p']} prompt tokens",
                    "ann": f"int8 projection codes (r 32, shift {codec_h.shift})" if args.ann == "int8" else "sign codes, 128 hash bits (LSH variant)",
                    "representative": args.rep + " key",
+                   "tempcache_workspace": args.ws,
                    "cross_attention": "one launch (ann_cross_attn_fwd)" if args.cross == "fused" else "ann_select_cross + sparse_attn_fwd",
                    "prefill_frames": n_prefill, "cache_len_per_head_start": [min(len_prefill), max(len_prefill)],
                    "cache_len_per_head_end": [min(len_final), max(len_final)],

@@ -158,13 +158,21 @@ int ann_select_lsh(const uint32_t *qbits, int n_q, const uint32_t *kbits, const 
  *                              status 0; 1 if a bounded wait inside the eviction plan ran out, 2 if the stamps of
  *                              the evictable slots span 2^20 frames or more: the choice of victims is then not
  *                              guaranteed to be the oldest-first one
+ *                              3 if ws_persistent was set for a workspace that is neither zero-filled nor left by
+ *                              a finished call
  *   ws / ws_bytes              workspace of fastar_workspace_bytes(FASTAR_OP_COMPRESS, ...), 256-byte aligned
+ *   ws_persistent              0: the workspace may hold anything (the call clears what it needs: one launch more).
+ *                              1: the caller zero-filled the workspace once and since then only calls of this
+ *                              function on this cache have written to it; every call leaves it as clean as a
+ *                              zero-filled one, so the match can go straight on to the threshold test (for candidate
+ *                              lists that fit LDS with P_new NULL; other calls ignore the flag).  The library still
+ *                              keeps no state of its own: the state is the caller's buffer.
  * The cache struct and the codec struct are host structs; cache->len is updated on the device.
  */
 int tempcache_compress(const fastar_cache *cache, const fastar_codec *codec, const void *K_new,
                        const void *V_new, const void *P_new, int n_new, const int32_t *cand, int n_cand,
                        int metric, int32_t tau2_q16, int32_t frame_id, int rep_mode, int32_t *merge_map,
-                       uint8_t *merged, int32_t *stats, void *ws, size_t ws_bytes, void *stream);
+                       uint8_t *merged, int32_t *stats, void *ws, size_t ws_bytes, int ws_persistent, void *stream);
 
 /*
  * AnnSA (Sec. 5.4 with the ANN goal of Sec. 5.1): for every head and every block of BQ queries,

@@ -57,7 +57,7 @@ def lib() -> ctypes.CDLL:
                                          ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int, ctypes.c_void_p, ctypes.c_int,
                                          ctypes.c_int, ctypes.c_int32, ctypes.c_int32, ctypes.c_int, ctypes.c_void_p,
                                          ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t,
-                                         ctypes.c_void_p]
+                                         ctypes.c_int, ctypes.c_void_p]
         L.ann_cross_attn_fwd.restype = ctypes.c_int
         L.ann_cross_attn_fwd.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p,
                                          ctypes.c_void_p, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int,
@@ -197,9 +197,13 @@ def encode(x: torch.Tensor, codec: Codec, out: torch.Tensor | None = None) -> to
 
 
 def tempcache_compress(cache: Cache, codec: Codec, K_new, V_new, P_new=None, cand=None, metric: int = 0,
-                       tau2_q16: int = 53084, frame_id: int = 0, rep_mode: int = 0, ws=None, out=None):
+                       tau2_q16: int = 53084, frame_id: int = 0, rep_mode: int = 0, ws=None, out=None,
+                       ws_persistent: bool = False):
     """Merge one frame into ``cache`` in place.  Returns (merge_map [H,n] int32, merged [H,n] uint8, stats [H,8]).
-    rep_mode: REP_LAST (0) keeps the last key of a merged group, REP_MEAN (1) its multiplicity-weighted mean."""
+    rep_mode: REP_LAST (0) keeps the last key of a merged group, REP_MEAN (1) its multiplicity-weighted mean.
+    ws_persistent: ``ws`` was zero-filled once and has since been written only by calls on this cache (one launch less)."""
+    if ws_persistent and ws is None:
+        raise ValueError("ws_persistent needs the caller's own workspace")
     H, C, d, r = cache.shape
     _dev(K_new, cache.K.dtype)
     _dev(V_new, cache.K.dtype)
@@ -220,7 +224,8 @@ def tempcache_compress(cache: Cache, codec: Codec, K_new, V_new, P_new=None, can
     _check(lib().tempcache_compress(ctypes.byref(cs), ctypes.byref(ks), K_new.data_ptr(), V_new.data_ptr(),
                                     _ptr(P_new), n_new, _ptr(cand), n_cand, metric, tau2_q16, frame_id,
                                     int(rep_mode), merge_map.data_ptr(), merged.data_ptr(), stats.data_ptr(), ws.data_ptr(),
-                                    ws.numel() * ws.element_size(), _stream()), "tempcache_compress")
+                                    ws.numel() * ws.element_size(), 1 if ws_persistent else 0, _stream()),
+           "tempcache_compress")
     return merge_map, merged, stats
 
 

@@ -23,7 +23,8 @@ int encode_launch(const void *x, int dtype, int64_t n_vec, int d, const fastar_c
 
 constexpr int SCORE_BIAS = 1 << 23;      // makes every score positive inside the packed arg-max key
 constexpr int PLAN_SCRATCH_WORDS = 64 + 3 * 1024;  // per-head scratch of tc_plan_kernel (PS_STRIDE)
-constexpr int HS_STRIDE = 8;             // per-head scalars: oldL, n_unmerged, e, n_victims, n_dropped, newL
+constexpr int HS_STRIDE = 8;             // per-head scalars: oldL, n_unmerged, e, n_victims, n_dropped, newL, -, clean mark
+constexpr int WS_CLEAN = 0x5A17C1EA;     // hs word 7 after a call: group records and plan scratch are all zero again
 
 typedef unsigned long long u64;
 
@@ -193,7 +194,25 @@ __global__ __launch_bounds__(256) void tc_match_kernel(const int8_t *__restrict_
 // their rows while the window's loads are in flight, leaves the codes in ck for the apply step, and clears the
 // eviction plan's scratch words (ps_all) for the launches behind it.
 constexpr int WIN_THREADS = 512;
-template <int R, bool ENC, bool BF16, int D>
+// What the fused tail of the window kernel needs from the verify step (defined further down).
+template <bool BF16, int D>
+struct VerifyRows;
+constexpr int AGE_BINS = 1024;
+__device__ __forceinline__ void age_histogram_slice(const int32_t *__restrict__ len, const int32_t *__restrict__ stamp,
+                                                    int C, int n_new, int frame_id, unsigned *__restrict__ ps,
+                                                    int hist_word, int fut_word, unsigned *lhist);
+struct VerifyArgs {   // the verify step's arguments, for the launch that runs it as its tail
+    const void *K;
+    int tau2_q16;
+    uint8_t *merged;
+    const int32_t *stamp;
+    int frame_id, hist_word, fut_word;
+};
+
+// With VERIFY (workspaces that every call leaves clean, see tempcache_compress) the kernel is the verify step too: once
+// the arg-max of its 64 tokens is final it runs the cosine test for them and registers the joiners; nothing is cleared
+// here (records and plan scratch are clean on entry), and every workgroup adds its slice of the age histogram.
+template <int R, bool ENC, bool BF16, int D, bool VERIFY>
 __global__ __launch_bounds__(WIN_THREADS) void tc_match_window_kernel(const int8_t *__restrict__ code,
                                                               const int32_t *__restrict__ len, int C,
                                                               const int8_t *__restrict__ cp, int n_new,
@@ -203,7 +222,8 @@ __global__ __launch_bounds__(WIN_THREADS) void tc_match_window_kernel(const int8
                                                               const void *__restrict__ K_new,
                                                               const int8_t *__restrict__ Rm, float qscale, int shift,
                                                               int8_t *__restrict__ ck, unsigned *__restrict__ ps_all,
-                                                              int ps_words) {
+                                                              int ps_words, VerifyArgs va) {
+    static_assert(!VERIFY || ENC, "the fused verify step reads the probe codes this kernel encoded");
     constexpr int KS = R / 32;
     constexpr int NCH = R / 16;  // 16-byte chunks per code
     extern __shared__ __attribute__((aligned(16))) unsigned char wlds[];
@@ -225,7 +245,7 @@ __global__ __launch_bounds__(WIN_THREADS) void tc_match_window_kernel(const int8
     CodeMatrix<BF16, D, R> cm;
     i32x4 xq[D / 64];
     const int etok = blockIdx.x * 64 + 16 * wave + (lane & 15);  // token this lane helps to encode
-    if (ENC)
+    if (ENC && !VERIFY)
         for (int k = blockIdx.x * WIN_THREADS + tid; k < ps_words; k += gridDim.x * WIN_THREADS) ps_all[(size_t)h * ps_words + k] = 0u;
     if (ENC && wave < 4) {  // 16 tokens per wavefront
         cm.load(Rm, lane);
@@ -332,35 +352,65 @@ __global__ __launch_bounds__(WIN_THREADS) void tc_match_window_kernel(const int8
     }
     if (g2 == 0) partbest[ch][tg][col] = mybest;
     __syncthreads();
-    if (ch == 0 && g2 == 0 && tok < n_new) {
-#pragma unroll
-        for (int c = 1; c < SPLIT; ++c) {
-            const u64 other = partbest[c][tg][col];
-            if (other > mybest) mybest = other;
-        }
+    __shared__ int vj[64], vs[64];
+    if (ch == 0 && g2 == 0) {
         int j = -1, S = 0;
-        if (mybest != 0) {
-            j = cslot[(int)(0xFFFFFFFFu - (unsigned)mybest)];   // position in the window -> slot
-            S = (int)(unsigned)(mybest >> 32) - SCORE_BIAS;
-            win[(size_t)h * C + j] = 0;
-            grp[(size_t)h * C + j] = 0;
+        if (tok < n_new) {
+#pragma unroll
+            for (int c = 1; c < SPLIT; ++c) {
+                const u64 other = partbest[c][tg][col];
+                if (other > mybest) mybest = other;
+            }
+            if (mybest != 0) {
+                j = cslot[(int)(0xFFFFFFFFu - (unsigned)mybest)];   // position in the window -> slot
+                S = (int)(unsigned)(mybest >> 32) - SCORE_BIAS;
+                if (!VERIFY) {
+                    win[(size_t)h * C + j] = 0;
+                    grp[(size_t)h * C + j] = 0;
+                }
+            }
+            jstar[(size_t)h * n_new + tok] = j;
+            sbest[(size_t)h * n_new + tok] = S;
         }
-        jstar[(size_t)h * n_new + tok] = j;
-        sbest[(size_t)h * n_new + tok] = S;
+        if (VERIFY) {
+            vj[tg * 32 + col] = j;
+            vs[tg * 32 + col] = S;
+        }
+    }
+    if constexpr (VERIFY) {
+        __shared__ unsigned lhist[AGE_BINS];
+        __syncthreads();
+        constexpr int NPASS = 64 * 16 / WIN_THREADS;   // tokens per 16-lane group
+        VerifyRows<BF16, D> vr[NPASS];
+#pragma unroll
+        for (int pass = 0; pass < NPASS; ++pass) {   // every row this group will need, in one round of loads
+            const int t = pass * (WIN_THREADS / 16) + (tid >> 4);
+            const int i = min(blockIdx.x * 64 + t, n_new - 1);
+            vr[pass].load(va.K, K_new, pcode + t * R, R, C, n_new, metric, h, i, tid & 15, vj[t]);
+        }
+#pragma unroll
+        for (int pass = 0; pass < NPASS; ++pass) {
+            const int t = pass * (WIN_THREADS / 16) + (tid >> 4);
+            const int i = blockIdx.x * 64 + t;
+            if (i < n_new)   // whole 16-lane groups
+                vr[pass].decide(C, n_new, qscale, metric, va.tau2_q16, win, grp, va.merged, h, i, tid & 15, vj[t], vs[t]);
+        }
+        age_histogram_slice(len, va.stamp, C, n_new, va.frame_id, ps_all + (size_t)h * ps_words, va.hist_word, va.fut_word,
+                            lhist);
     }
 }
 static size_t match_window_lds(int n_cand, int r) { return (size_t)((n_cand + 31) & ~31) * (size_t)(r + 8); }
 constexpr size_t WINDOW_LDS_MAX = 150 * 1024;
-template <int R, bool ENC, bool BF16, int D, typename... Args>
+template <int R, bool ENC, bool BF16, int D, bool VERIFY, typename... Args>
 static int launch_match_window(dim3 grid, size_t lds, hipStream_t s, Args... args) {
     static bool attr_set = false;  // once per instantiation: allow more than the default 64 KB of dynamic LDS
     if (!attr_set) {
-        if (hipFuncSetAttribute((const void *)tc_match_window_kernel<R, ENC, BF16, D>,
+        if (hipFuncSetAttribute((const void *)tc_match_window_kernel<R, ENC, BF16, D, VERIFY>,
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)WINDOW_LDS_MAX) != hipSuccess)
             return FASTAR_ERR_HIP;
         attr_set = true;
     }
-    hipLaunchKernelGGL((tc_match_window_kernel<R, ENC, BF16, D>), grid, dim3(WIN_THREADS), lds, s, args...);
+    hipLaunchKernelGGL((tc_match_window_kernel<R, ENC, BF16, D, VERIFY>), grid, dim3(WIN_THREADS), lds, s, args...);
     FASTAR_LAUNCH_CHECK();
     return FASTAR_OK;
 }
@@ -390,7 +440,6 @@ __global__ __launch_bounds__(256) void tc_prep_kernel(const u64 *__restrict__ be
 // Per head, a histogram of the live slots' ages (frame_id - stamp, 1024 bins, the last one collecting everything
 // older) for the eviction plan: the verify launch, a whole grid, reads the stamps, where the plan has few
 // workgroups per head.  Every workgroup of the launch adds its slice of the slots.  Called by whole workgroups.
-constexpr int AGE_BINS = 1024;
 __device__ __forceinline__ void age_histogram_slice(const int32_t *__restrict__ len, const int32_t *__restrict__ stamp,
                                                     int C, int n_new, int frame_id, unsigned *__restrict__ ps,
                                                     int hist_word, int fut_word, unsigned *lhist) {
@@ -574,6 +623,58 @@ __global__ __launch_bounds__(256) void tc_verify_kernel(const void *__restrict__
                         lhist);
 }
 
+// Token i of head h, matched to slot j with code score W (j < 0: no candidate); cprow = the token's probe code.
+// Two halves, so that a caller with several tokens per lane group can issue all their loads first.  Whole 16-lane groups.
+template <bool BF16, int D>
+struct VerifyRows {
+    float a[RowPiece<BF16, D>::EPL], b[RowPiece<BF16, D>::EPL];
+    unsigned cw;
+    __device__ __forceinline__ void load(const void *__restrict__ K, const void *__restrict__ K_new, const int8_t *cprow,
+                                         int r, int C, int n_new, int metric, int h, int i, int l16, int j) {
+        typedef RowPiece<BF16, D> RP;
+        RP::load(K_new, (size_t)h * n_new + i, l16, a);
+        cw = (metric == 0 && l16 < r / 4) ? ((const unsigned *)cprow)[l16] : 0u;
+        if (j >= 0) RP::load(K, (size_t)h * C + j, l16, b);
+    }
+    __device__ __forceinline__ void decide(int C, int n_new, float qscale, int metric, int tau2_q16, u64 *__restrict__ win,
+                                           int32_t *__restrict__ grp, uint8_t *__restrict__ merged, int h, int i,
+                                           int l16, int j, int W) const {
+        typedef RowPiece<BF16, D> RP;
+        const int nn = group16_sum(dot4_i8(cw, cw, 0));  // |probe code|^2 (r <= 64: at most 16 words)
+        bool is_merged = false;
+        if (j >= 0) {
+            int dot = 0, na = 0, nb = 0;
+#pragma unroll
+            for (int e = 0; e < RP::EPL; ++e) {
+                const int qa = quant8(a[e], qscale), qb = quant8(b[e], qscale);
+                dot += qa * qb;
+                na += qa * qa;
+                nb += qb * qb;
+            }
+            dot = group16_sum(dot);
+            na = group16_sum(na);
+            nb = group16_sum(nb);
+            is_merged = dot > 0 && (long long)dot * dot * 65536ll >= (long long)tau2_q16 * na * nb;
+            if (is_merged && l16 == 0) {
+                if (metric == 0) W -= nn;
+                const u64 key = ((u64)(unsigned)(W + SCORE_BIAS) << 32) | (u64)(0xFFFFFFFFu - (unsigned)i);
+                atomicMax(&win[(size_t)h * C + j], key);
+                atomicAdd(&grp[(size_t)h * C + j], 1);
+            }
+        }
+        if (l16 == 0) merged[(size_t)h * n_new + i] = is_merged ? 1 : 0;
+    }
+};
+template <bool BF16, int D>
+__device__ __forceinline__ void verify_core(const void *__restrict__ K, const void *__restrict__ K_new,
+                                            const int8_t *cprow, int r, int C, int n_new, float qscale, int metric,
+                                            int tau2_q16, u64 *__restrict__ win, int32_t *__restrict__ grp,
+                                            uint8_t *__restrict__ merged, int h, int i, int l16, int j, int W) {
+    VerifyRows<BF16, D> v;
+    v.load(K, K_new, cprow, r, C, n_new, metric, h, i, l16, j);
+    v.decide(C, n_new, qscale, metric, tau2_q16, win, grp, merged, h, i, l16, j, W);
+}
+
 template <bool BF16, int D>
 __device__ __forceinline__ void verify_token(const void *__restrict__ K, const void *__restrict__ K_new,
                                              const int8_t *__restrict__ cp, int r, int C, int n_new, float qscale,
@@ -581,42 +682,10 @@ __device__ __forceinline__ void verify_token(const void *__restrict__ K, const v
                                              const int32_t *__restrict__ sbest, u64 *__restrict__ win,
                                              int32_t *__restrict__ grp, uint8_t *__restrict__ merged, int h, int i,
                                              int l16) {
-    typedef RowPiece<BF16, D> RP;
-    const size_t ti = (size_t)h * n_new + i;
     // everything addressed by the token first (one round trip), then the matched slot's key row
-    const int j = jstar[ti];
-    float a[RP::EPL], b[RP::EPL];
-    RP::load(K_new, ti, l16, a);
-    int W = sbest[ti];
-    int nn = 0;
-    if (metric == 0 && l16 < r / 4) {
-        const unsigned c = ((const unsigned *)(cp + ti * r))[l16];
-        nn = dot4_i8(c, c, 0);
-    }
-    nn = group16_sum(nn);  // |probe code|^2 (r <= 64: at most 16 words)
-    bool is_merged = false;
-    if (j >= 0) {
-        RP::load(K, (size_t)h * C + j, l16, b);
-        int dot = 0, na = 0, nb = 0;
-#pragma unroll
-        for (int e = 0; e < RP::EPL; ++e) {
-            const int qa = quant8(a[e], qscale), qb = quant8(b[e], qscale);
-            dot += qa * qb;
-            na += qa * qa;
-            nb += qb * qb;
-        }
-        dot = group16_sum(dot);
-        na = group16_sum(na);
-        nb = group16_sum(nb);
-        is_merged = dot > 0 && (long long)dot * dot * 65536ll >= (long long)tau2_q16 * na * nb;
-        if (is_merged && l16 == 0) {
-            if (metric == 0) W -= nn;
-            const u64 key = ((u64)(unsigned)(W + SCORE_BIAS) << 32) | (u64)(0xFFFFFFFFu - (unsigned)i);
-            atomicMax(&win[(size_t)h * C + j], key);
-            atomicAdd(&grp[(size_t)h * C + j], 1);
-        }
-    }
-    if (l16 == 0) merged[ti] = is_merged ? 1 : 0;
+    const size_t ti = (size_t)h * n_new + i;
+    verify_core<BF16, D>(K, K_new, cp + ti * r, r, C, n_new, qscale, metric, tau2_q16, win, grp, merged, h, i, l16,
+                         jstar[ti], sbest[ti]);
 }
 
 // ---- plan ----------------------------------------------------------------------------------------------
@@ -727,7 +796,8 @@ __global__ __launch_bounds__(PLAN_THREADS) void tc_plan_kernel(const int32_t *__
                                                                const uint8_t *__restrict__ merged,
                                                                const u64 *__restrict__ win, int32_t *__restrict__ rank,
                                                                int32_t *__restrict__ victims, int32_t *__restrict__ hs,
-                                                               int32_t *__restrict__ stats, unsigned *__restrict__ ps_all) {
+                                                               int32_t *__restrict__ stats, unsigned *__restrict__ ps_all,
+                                                               int ws_persistent) {
     extern __shared__ unsigned touched[];  // bitmap over this workgroup's slot range
     __shared__ unsigned lhist[PLAN_BINS];
     __shared__ unsigned wtot[PLAN_WAVES];
@@ -1065,10 +1135,14 @@ __global__ __launch_bounds__(PLAN_THREADS) void tc_plan_kernel(const int32_t *__
         const int n_app = (int)n_unm - n_dropped;
         const int newL = L + n_app - n_victims;
         int32_t *o = hs + (size_t)h * HS_STRIDE;
+        const int mark = o[7];
         o[0] = L; o[1] = (int)n_unm; o[2] = e; o[3] = n_victims; o[4] = n_dropped; o[5] = newL;
         int32_t *s = stats + (size_t)h * 8;
         s[0] = newL; s[1] = n_new - (int)n_unm; s[2] = n_app; s[3] = n_victims; s[4] = n_dropped;
-        s[5] = 0; s[6] = 0; s[7] = e > 0 ? (int)ld_agent(&ps[PS_ERR]) : 0;
+        int status = e > 0 ? (int)ld_agent(&ps[PS_ERR]) : 0;
+        // a workspace declared persistent must be a zero-filled one or one a finished call left behind
+        if (ws_persistent && mark != 0 && mark != WS_CLEAN) status = 3;
+        s[5] = 0; s[6] = 0; s[7] = status;
     }
 }
 
@@ -1089,15 +1163,21 @@ __global__ __launch_bounds__(256) void tc_apply_kernel(void *__restrict__ K, voi
                                                        int r, const void *__restrict__ K_new,
                                                        const void *__restrict__ V_new, const int8_t *__restrict__ ck,
                                                        int n_new, int frame_id, const int32_t *__restrict__ jstar,
-                                                       const uint8_t *__restrict__ merged, const u64 *__restrict__ win,
-                                                       const int32_t *__restrict__ grp, const int32_t *__restrict__ rank,
-                                                       const int32_t *__restrict__ victims, const int32_t *__restrict__ hs,
+                                                       const uint8_t *__restrict__ merged, u64 *win, int32_t *grp,
+                                                       const int32_t *__restrict__ rank,
+                                                       const int32_t *__restrict__ victims, int32_t *hs,
                                                        int32_t *__restrict__ merge_map, int32_t *__restrict__ len,
-                                                       int rep_mode) {
+                                                       int rep_mode, unsigned *__restrict__ ps_all, int ps_words) {
     typedef RowPiece<BF16, D> RP;
     const int h = blockIdx.y;
     // the new length is published here and not by the plan: its workgroups read len[h] at different times
-    if (blockIdx.x == 0 && threadIdx.x == 0) len[h] = hs[(size_t)h * HS_STRIDE + 5];
+    if (blockIdx.x == 0 && threadIdx.x == 0) {
+        len[h] = hs[(size_t)h * HS_STRIDE + 5];
+        hs[(size_t)h * HS_STRIDE + 7] = WS_CLEAN;   // with the two clean-ups below: the workspace is left as a zero-filled one
+    }
+    // the plan is done with its scratch words: cleared for the next call that shares this workspace
+    for (int k = blockIdx.x * blockDim.x + threadIdx.x; k < ps_words; k += gridDim.x * blockDim.x)
+        ps_all[(size_t)h * ps_words + k] = 0u;
     const int l16 = threadIdx.x & 15;
     const int sub = (threadIdx.x & 63) >> 4;  // which 16-lane group of the wavefront
     const int i = blockIdx.x * (blockDim.x / 16) + (threadIdx.x >> 4);
@@ -1127,6 +1207,12 @@ __global__ __launch_bounds__(256) void tc_apply_kernel(void *__restrict__ K, voi
         if (mean_key) RP::load(K, cb + j, l16, kacc);
         const int widx = (int)(0xFFFFFFFFu - (unsigned)wkey);
         if (widx == i) {  // this token represents the group: it refreshes the slot
+            // ... and clears the group's records behind it: the other joiners only look for their own index in the
+            // record, which neither the old nor the cleared value shows them
+            if (l16 == 0) {
+                win[cb + j] = 0;
+                grp[cb + j] = 0;
+            }
             // mean value; with rep_mode 1 also the mean key, whose stored bits feed later integer decisions: single
             // float32 operations in a fixed order (multiplicity * old row, members in ascending token order, one division)
 #pragma unroll
@@ -1226,7 +1312,8 @@ using namespace fastar;
 extern "C" int tempcache_compress(const fastar_cache *cache, const fastar_codec *codec, const void *K_new,
                                   const void *V_new, const void *P_new, int n_new, const int32_t *cand, int n_cand,
                                   int metric, int32_t tau2_q16, int32_t frame_id, int rep_mode, int32_t *merge_map,
-                                  uint8_t *merged, int32_t *stats, void *ws, size_t ws_bytes, void *stream) {
+                                  uint8_t *merged, int32_t *stats, void *ws, size_t ws_bytes, int ws_persistent,
+                                  void *stream) {
     if (!cache || !codec || !codec->R || !K_new || !V_new || !merge_map || !merged || !stats || !ws)
         return FASTAR_ERR_INVALID_ARG;
     if (!cache->K || !cache->V || !cache->code || !cache->cnt || !cache->stamp || !cache->len)
@@ -1234,6 +1321,7 @@ extern "C" int tempcache_compress(const fastar_cache *cache, const fastar_codec 
     const int H = cache->H, C = cache->C, d = cache->d, r = cache->r, dtype = cache->dtype;
     if (H <= 0 || C <= 0 || n_new <= 0 || (metric != 0 && metric != 1)) return FASTAR_ERR_INVALID_ARG;
     if (rep_mode != FASTAR_REP_LAST && rep_mode != FASTAR_REP_MEAN) return FASTAR_ERR_INVALID_ARG;
+    if (ws_persistent != 0 && ws_persistent != 1) return FASTAR_ERR_INVALID_ARG;
     if (tau2_q16 < 0 || tau2_q16 > 131072) return FASTAR_ERR_INVALID_ARG;
     if (cand && n_cand <= 0) return FASTAR_ERR_INVALID_ARG;
     if (codec->shift < 1 || codec->shift > 16) return FASTAR_ERR_INVALID_ARG;
@@ -1262,6 +1350,7 @@ extern "C" int tempcache_compress(const fastar_cache *cache, const fastar_codec 
     const size_t win_lds = cand ? match_window_lds(n_cand, r) : 0;
     const bool window = cand && win_lds <= WINDOW_LDS_MAX;
     const bool fused_encode = window && !P_new;  // the match kernel encodes its own probes
+    const bool fused_verify = fused_encode && ws_persistent;   // ... and verifies its matches: nothing to clear first
     if (!fused_encode) {
         const int64_t zero_words = (int64_t)((w.ps - w.best) / 8) + (int64_t)H * PLAN_SCRATCH_WORDS / 2;  // best .. end of ps
         int rc = encode_launch(K_new, dtype, T, d, codec, r, ck, best, zero_words, s);
@@ -1275,16 +1364,23 @@ extern "C" int tempcache_compress(const fastar_cache *cache, const fastar_codec 
         // the whole candidate window fits one workgroup's LDS: final arg-max per token in one launch
         const dim3 grid((n_new + 63) / 64, H);
         const bool bf = dtype == FASTAR_BF16;
+        const VerifyArgs va = {cache->K, tau2_q16, merged, cache->stamp, frame_id, PS_HIST, PS_FUT};
         int rc = FASTAR_OK;
-#define FASTAR_WIN(RR, ENC, BF, DD)                                                                                  \
-    rc = launch_match_window<RR, ENC, BF, DD>(grid, win_lds, s, cache->code, cache->len, C, cp, n_new, cand, n_cand, \
-                                              metric, jstar, sbest, win, grp, K_new, codec->R, codec->qscale,         \
-                                              codec->shift, ck, plan_scratch, (int)PS_STRIDE)
-        if (!fused_encode) { if (r == 32) FASTAR_WIN(32, false, true, 128); else FASTAR_WIN(64, false, true, 128); }
-        else if (r == 32 && d == 128) { if (bf) FASTAR_WIN(32, true, true, 128); else FASTAR_WIN(32, true, false, 128); }
-        else if (r == 32) { if (bf) FASTAR_WIN(32, true, true, 64); else FASTAR_WIN(32, true, false, 64); }
-        else if (d == 128) { if (bf) FASTAR_WIN(64, true, true, 128); else FASTAR_WIN(64, true, false, 128); }
-        else { if (bf) FASTAR_WIN(64, true, true, 64); else FASTAR_WIN(64, true, false, 64); }
+#define FASTAR_WIN(RR, ENC, BF, DD, VER)                                                                                  \
+    rc = launch_match_window<RR, ENC, BF, DD, VER>(grid, win_lds, s, cache->code, cache->len, C, cp, n_new, cand, n_cand, \
+                                                   metric, jstar, sbest, win, grp, K_new, codec->R, codec->qscale,         \
+                                                   codec->shift, ck, plan_scratch, (int)PS_STRIDE, va)
+#define FASTAR_WIN_ENC(RR, BF, DD)                                                      \
+    do {                                                                                \
+        if (fused_verify) FASTAR_WIN(RR, true, BF, DD, true);                           \
+        else FASTAR_WIN(RR, true, BF, DD, false);                                       \
+    } while (0)
+        if (!fused_encode) { if (r == 32) FASTAR_WIN(32, false, true, 128, false); else FASTAR_WIN(64, false, true, 128, false); }
+        else if (r == 32 && d == 128) { if (bf) FASTAR_WIN_ENC(32, true, 128); else FASTAR_WIN_ENC(32, false, 128); }
+        else if (r == 32) { if (bf) FASTAR_WIN_ENC(32, true, 64); else FASTAR_WIN_ENC(32, false, 64); }
+        else if (d == 128) { if (bf) FASTAR_WIN_ENC(64, true, 128); else FASTAR_WIN_ENC(64, false, 128); }
+        else { if (bf) FASTAR_WIN_ENC(64, true, 64); else FASTAR_WIN_ENC(64, false, 64); }
+#undef FASTAR_WIN_ENC
 #undef FASTAR_WIN
         if (rc != FASTAR_OK) return rc;
     } else {
@@ -1313,18 +1409,23 @@ extern "C" int tempcache_compress(const fastar_cache *cache, const fastar_codec 
         else if (d == 128) hipLaunchKernelGGL((KERNEL<false, 128>), tgrid, dim3(256), 0, s, __VA_ARGS__);       \
         else hipLaunchKernelGGL((KERNEL<false, 64>), tgrid, dim3(256), 0, s, __VA_ARGS__);                       \
     } while (0)
-    FASTAR_TC(tc_verify_kernel, cache->K, K_new, cp, r, C, n_new, codec->qscale, metric, tau2_q16, jstar, sbest, win, grp,
-              merged, cache->len, cache->stamp, frame_id, plan_scratch, PS_HIST, PS_FUT, PS_STRIDE);
-    FASTAR_LAUNCH_CHECK();
+    if (!fused_verify) {
+        FASTAR_TC(tc_verify_kernel, cache->K, K_new, cp, r, C, n_new, codec->qscale, metric, tau2_q16, jstar, sbest, win,
+                  grp, merged, cache->len, cache->stamp, frame_id, plan_scratch, PS_HIST, PS_FUT, PS_STRIDE);
+        FASTAR_LAUNCH_CHECK();
+    }
     if (((C + nb - 1) / nb + PLAN_THREADS - 1) / PLAN_THREADS <= 16)
         hipLaunchKernelGGL(tc_plan_kernel<16>, dim3(nb + 1, H), dim3(PLAN_THREADS), plan_lds_bytes(C, nb), s, cache->len,
-                           cache->stamp, C, n_new, frame_id, jstar, merged, win, rank, victims, hs, stats, plan_scratch);
+                           cache->stamp, C, n_new, frame_id, jstar, merged, win, rank, victims, hs, stats, plan_scratch,
+                           ws_persistent);
     else
         hipLaunchKernelGGL(tc_plan_kernel<64>, dim3(nb + 1, H), dim3(PLAN_THREADS), plan_lds_bytes(C, nb), s, cache->len,
-                           cache->stamp, C, n_new, frame_id, jstar, merged, win, rank, victims, hs, stats, plan_scratch);
+                           cache->stamp, C, n_new, frame_id, jstar, merged, win, rank, victims, hs, stats, plan_scratch,
+                           ws_persistent);
     FASTAR_LAUNCH_CHECK();
     FASTAR_TC(tc_apply_kernel, cache->K, cache->V, cache->code, cache->cnt, cache->stamp, C, r, K_new, V_new, ck, n_new,
-              frame_id, jstar, merged, win, grp, rank, victims, hs, merge_map, cache->len, rep_mode);
+              frame_id, jstar, merged, win, grp, rank, victims, hs, merge_map, cache->len, rep_mode, plan_scratch,
+              (int)PS_STRIDE);
     FASTAR_LAUNCH_CHECK();
 #undef FASTAR_TC
     if (rep_mode == FASTAR_REP_MEAN) {

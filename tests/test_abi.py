@@ -59,7 +59,7 @@ def test_null_and_inconsistent_arguments_return_error_codes_without_a_gpu(L):
                              ctypes.c_float(1.0), null, null, null) == -1
     assert L.fastar_encode(null, 1, 16, 128, None, 32, null, null) == -1
     assert L.tempcache_compress(None, None, null, null, null, 1, null, 0, 0, 0, 0, 0, null, null, null, null, 0,
-                                null) == -1
+                                0, null) == -1
 
 
 def test_missing_library_fails_loudly(monkeypatch):

@@ -327,7 +327,8 @@ def test_dense_limit_on_clustered_data_fp32_and_bf16():
 
 # ----------------------------------------------------------------------------------------- TempCache
 
-def run_rollout(name, n_frames, C, tau, dtype=None, H=None, windowed=True, metric=0, probe_queries=False, rep_mode=0):
+def run_rollout(name, n_frames, C, tau, dtype=None, H=None, windowed=True, metric=0, probe_queries=False, rep_mode=0,
+                persistent=False):
     over = {}
     if dtype:
         over["dtype"] = dtype
@@ -340,6 +341,9 @@ def run_rollout(name, n_frames, C, tau, dtype=None, H=None, windowed=True, metri
     gpu = dev_cache(ref)
     dcodec = dev_codec(codec)
     prev_ref, prev_gpu = None, None
+    ws = None
+    if persistent:   # one workspace for the whole rollout, zero-filled once
+        ws = torch.zeros(fa.workspace_bytes(fa.OP_COMPRESS, c["H"], c["T"], C, c["r"]), dtype=torch.uint8, device="cuda")
     for f in range(n_frames):
         K, V = fs.next_frame()
         P = fs.queries(1) if probe_queries else None
@@ -349,7 +353,8 @@ def run_rollout(name, n_frames, C, tau, dtype=None, H=None, windowed=True, metri
         mm_g, mg_g, st_g = fa.tempcache_compress(gpu, dcodec, to_dev(K), to_dev(V),
                                                  P_new=None if P is None else to_dev(P),
                                                  cand=prev_gpu if windowed else None, metric=metric,
-                                                 tau2_q16=TAU2(tau), frame_id=f, rep_mode=rep_mode)
+                                                 tau2_q16=TAU2(tau), frame_id=f, rep_mode=rep_mode, ws=ws,
+                                                 ws_persistent=persistent)
         sync()
         assert np.array_equal(to_host(mg_g), mg_r), f"merged flags, frame {f}"
         assert np.array_equal(to_host(mm_g), mm_r), f"merge map, frame {f}"
@@ -512,6 +517,46 @@ def test_tempcache_edge_shapes_bit_exact(T, C, lens, n_cand, tau):
     assert np.array_equal(to_host(mg_g), mg_r)
     assert np.array_equal(to_host(mm_g), mm_r)
     assert_cache_equal(host_cache(gpu), ref, VTOL["fp32"])
+
+
+@pytest.mark.parametrize("name,dtype,H,frames,C,tau,rep", [
+    ("cfg1", None, None, 6, 6 * 256, 0.98, 0), ("cfg1", "bf16", None, 8, 2 * 256 + 40, 0.98, 0),
+    ("cfg2", None, 2, 5, 3 * 1560, 0.98, 0), ("cfg1", None, None, 4, 5 * 256, 0.5, 1), ("cfg1", None, None, 2, 100, 2.0 ** 0.5, 0)])
+def test_tempcache_rollout_on_a_persistent_workspace(name, dtype, H, frames, C, tau, rep):
+    # the workspace is zero-filled once and every call leaves it clean: the match launch goes straight on to the
+    # threshold test (no clearing launch); merges, big groups, evictions and drops must come out bit for bit the same
+    c, fs, codec, ref, gpu = run_rollout(name, frames, C, tau, dtype=dtype, H=H, rep_mode=rep, persistent=True)
+
+
+def test_tempcache_persistent_workspace_mixes_with_the_other_paths_and_reports_a_dirty_one():
+    # first frame without a candidate list (chunked match), then windowed frames, all on one persistent workspace
+    c = dict(CONFIGS["cfg1"])
+    fs = FrameStream(c["seed"], c["cfg_id"], c["H"], c["d"], c["T"], c["n_c"], c["p"], c["sigma_d"], c["dtype"])
+    codec = make_codec(c["seed"], c["cfg_id"], c["d"], c["r"])
+    C = 5 * c["T"]
+    ref = oracle.Cache.empty(c["H"], C, c["d"], c["r"], c["dtype"])
+    gpu = dev_cache(ref)
+    ws = torch.zeros(fa.workspace_bytes(fa.OP_COMPRESS, c["H"], c["T"], C, c["r"]), dtype=torch.uint8, device="cuda")
+    prev_r = prev_g = None
+    for f in range(4):
+        K, V = fs.next_frame()
+        P = fs.queries(1) if f == 2 else None                    # one frame with separate probes in between
+        mm_r, mg_r, st_r = oracle.tempcache_compress(ref, codec.R, codec.qscale, codec.shift, K, V, P_new=P, cand=prev_r,
+                                                     tau2_q16=TAU2(0.98), frame_id=f)
+        mm_g, mg_g, st_g = fa.tempcache_compress(gpu, dev_codec(codec), to_dev(K), to_dev(V),
+                                                 P_new=None if P is None else to_dev(P), cand=prev_g,
+                                                 tau2_q16=TAU2(0.98), frame_id=f, ws=ws, ws_persistent=True)
+        sync()
+        assert np.array_equal(to_host(mm_g), mm_r) and np.array_equal(to_host(st_g), st_r), f"frame {f}"
+        assert_cache_equal(host_cache(gpu), ref, VTOL[c["dtype"]])
+        prev_r, prev_g = mm_r, mm_g
+    # a workspace that is neither zero-filled nor left by a finished call is reported (cache far from full: no eviction)
+    K, V = fs.next_frame()
+    dirty = torch.full_like(ws, 0x5B)
+    _, _, st = fa.tempcache_compress(gpu, dev_codec(codec), to_dev(K), to_dev(V), cand=prev_g, tau2_q16=TAU2(0.98),
+                                     frame_id=9, ws=dirty, ws_persistent=True)
+    sync()
+    assert (to_host(st)[:, 7] == 3).all()
 
 
 def test_tempcache_whole_cache_match_and_inner_product_probe():
