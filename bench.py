@@ -472,6 +472,7 @@ def sweep(args, torch, fa, np, to_dev, to_host):
     bounded = ChunkPipeline(cfg, cap, args.tau, torch, fa, codec, prompt, n_sel)
     plain = ChunkPipeline(cfg, n_frames * T, 2.0 ** 0.5, torch, fa, codec, prompt, n_sel)   # tau^2 = 2: never merges
     rows = []
+    spacer = torch.zeros(64 << 20, dtype=torch.uint8, device="cuda")
     for step in range(n_frames // cf):
         frames = [tuple(to_dev(a) for a in fs.next_frame()) for _ in range(cf)]
         Q = to_dev(fs.queries(cf))
@@ -484,10 +485,13 @@ def sweep(args, torch, fa, np, to_dev, to_host):
                 e.record()
                 evs.append(e)
             torch.cuda.synchronize()
-            t0 = time.perf_counter()
+            # a spacer of plain device work in front: the step's launches are all enqueued while it runs, so the events
+            # time the GPU's work on a busy, clocked-up chip and not the host's launch rate on an idle one
+            for _ in range(12):
+                spacer.add_(1)
             pipe.step(frames, Q, ev=mark)
             torch.cuda.synchronize()
-            ms = (time.perf_counter() - t0) * 1e3
+            ms = evs[0].elapsed_time(evs[-1])
             L = to_host(pipe.cache.len)
             live_bytes = int(L.sum()) * (2 * d * 2 + r + 8)
             row[name] = {"ms": round(ms, 3), "attn_self_ms": round(evs[3].elapsed_time(evs[4]), 4),

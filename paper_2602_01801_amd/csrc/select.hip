@@ -15,7 +15,7 @@
 namespace fastar {
 
 constexpr int KB_PER_WG = 4;      // key blocks scored by one workgroup of score_self_kernel
-constexpr int KB_PER_WG_LONG = 16; // the same for long caches (at least 2048 such workgroups)
+constexpr int KB_PER_WG_LONG = 16; // the same for long caches (at least 4096 such workgroups)
 constexpr int COL_CHUNK = 8;       // summary column blocks (of 32) kept in registers at a time
 constexpr int TOPK_LDS_CAP = 8192; // row entries cached in LDS by topk_kernel
 
@@ -154,7 +154,7 @@ __global__ __launch_bounds__(256) void score_self_kernel(const int8_t *__restric
     }
 }
 
-// The same scores for long caches (at least 2048 workgroups of KBW = 16 key blocks): wavefront w streams blocks w, w+4,
+// The same scores for long caches (at least 4096 workgroups of KBW = 16 key blocks): wavefront w streams blocks w, w+4,
 // ... with the codes of the next three rounds in flight while it scores the current one, and the workgroup writes
 // 64-byte pieces of the score rows.  CC: summary column blocks (of 32) kept in registers at a time.
 template <int R, int KBW, int CC>
@@ -802,7 +802,10 @@ extern "C" int ann_select_self(const int8_t *qcode, int n_q, const int8_t *kcode
     if ((r != 32 && r != 64) || !pow2_le32(n_rep) || BK % 32 != 0) return FASTAR_ERR_UNSUPPORTED;
     const int n_qb = (n_q + BQ - 1) / BQ;
     const int n_kb_cap = (C + BK - 1) / BK;
-    const int kbw = ((size_t)n_kb_cap * H >= (size_t)KB_PER_WG_LONG * 2048 && n_qb <= 1024) ? KB_PER_WG_LONG : KB_PER_WG;
+    // the streaming kernel pays when there are thousands of its workgroups and the summaries fit four column blocks
+    // (measured: 121 against 126 us at 40 heads x 3600 blocks; with fewer, wider workgroups the plain kernel wins)
+    const bool few_cols = (n_qb * n_rep + 31) / 32 <= 4;
+    const int kbw = (few_cols && (size_t)n_kb_cap * H >= (size_t)KB_PER_WG_LONG * 4096) ? KB_PER_WG_LONG : KB_PER_WG;
     const size_t tile_bytes = (size_t)n_qb * kbw * sizeof(int32_t);
     if (tile_bytes > 64 * 1024) return FASTAR_ERR_UNSUPPORTED;
     const SelfWs w = self_ws(H, n_q, C, r, BQ, BK, n_rep);
@@ -816,7 +819,6 @@ extern "C" int ann_select_self(const int8_t *qcode, int n_q, const int8_t *kcode
 #define FASTAR_SCORE(RR, CCC)                                                                                        \
     hipLaunchKernelGGL((score_self_stream_kernel<RR, KB_PER_WG_LONG, CCC>), grid, dim3(256), tile_bytes, s, kcode, len, \
                        rep, C, n_q, BQ, n_rep, BK, n_qb, n_kb_cap, score)
-    const bool few_cols = (n_qb * n_rep + 31) / 32 <= 4;   // all summaries fit four column blocks: fewer registers
     if (kbw == KB_PER_WG) {
         if (r == 32)
             hipLaunchKernelGGL(score_self_kernel<32>, grid, dim3(256), tile_bytes, s, kcode, len, rep, C, n_q, BQ, n_rep,
@@ -825,9 +827,9 @@ extern "C" int ann_select_self(const int8_t *qcode, int n_q, const int8_t *kcode
             hipLaunchKernelGGL(score_self_kernel<64>, grid, dim3(256), tile_bytes, s, kcode, len, rep, C, n_q, BQ, n_rep,
                                BK, n_qb, n_kb_cap, score);
     } else if (r == 32) {
-        if (few_cols) FASTAR_SCORE(32, 4); else FASTAR_SCORE(32, COL_CHUNK);
+        FASTAR_SCORE(32, 4);
     } else {
-        if (few_cols) FASTAR_SCORE(64, 4); else FASTAR_SCORE(64, COL_CHUNK);
+        FASTAR_SCORE(64, 4);
     }
 #undef FASTAR_SCORE
     FASTAR_LAUNCH_CHECK();

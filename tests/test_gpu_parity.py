@@ -66,8 +66,9 @@ def rand_codes(rng, lo, hi, *shape):
     (2, 200, 640, 64, 64, 8, 32, 4, [640, 333], 40),             # r = 64, BK = 32, n_rep = 8
     (1, 130, 512, 32, 128, 1, 64, 20, [500], 30),                # one summary per block, budget > blocks
     (1, 64, 256, 32, 32, 32, 64, 2, [256], 20),                  # per-query summaries
-    (4, 300, 32 * 8200, 32, 128, 4, 32, 90, [262400, 262399, 131000, 40], 40),   # long caches: 16 key blocks per workgroup
-    (2, 200, 96 * 5500, 64, 64, 2, 96, 33, [528000, 300001], 40),                # the same, r = 64, three groups per block
+    (4, 300, 32 * 16400, 32, 128, 4, 32, 90, [524800, 524799, 131000, 40], 40),  # long caches: the streaming kernel
+    (2, 200, 96 * 33000, 64, 64, 2, 96, 33, [3168000, 300001], 40),              # the same, r = 64, three groups per block
+    (4, 300, 32 * 8200, 32, 128, 4, 32, 90, [262400, 262399, 131000, 40], 40),   # long caches below its threshold
 ])
 def test_ann_select_self_bit_exact(H, n_q, C, r, BQ, n_rep, BK, n_sel, lens, span):
     rng = np.random.default_rng(n_q + C)
