@@ -16,11 +16,11 @@ def check(path: str, verbose: bool = True) -> int:
 
 
 def _check_lines(lines, verbose):
-    def regs(tok):
-        m = re.match(r'v\[(\d+):(\d+)\]', tok)
-        if m: return set(range(int(m.group(1)), int(m.group(2)) + 1))
-        m = re.match(r'v(\d+)$', tok)
-        if m: return {int(m.group(1))}
+    def regs(tok):   # vector registers (v) and accumulation registers (a), as (file, index)
+        m = re.match(r'([va])\[(\d+):(\d+)\]', tok)
+        if m: return {(m.group(1), r) for r in range(int(m.group(2)), int(m.group(3)) + 1)}
+        m = re.match(r'([va])(\d+)$', tok)
+        if m: return {(m.group(1), int(m.group(2)))}
         return set()
     pending = {}   # reg -> (line of read, sequence number of that read)
     nread = 0      # inline-asm LDS reads seen so far
@@ -32,7 +32,7 @@ def _check_lines(lines, verbose):
         if t.startswith(';;#ASMEND'): in_asm = False; continue
         if not t or t.startswith((';', '.', '//')): continue
         if re.match(r'^\.?LBB', t): continue
-        ops = re.findall(r'v\[\d+:\d+\]|v\d+', t)
+        ops = re.findall(r'\b[va]\[\d+:\d+\]|\b[va]\d+\b', t)
         used = set().union(*[regs(o) for o in ops]) if ops else set()
         if in_asm and t.startswith('ds_read'):
             dst = regs(t.split()[1].rstrip(','))
