@@ -282,7 +282,7 @@ def cpu_baseline(cfg, pipe, prefill_host, chunks, ps, n_heads, to_host, sign_mat
 def attn_kernel_name(n_items):
     """Which bf16 d = 128, BQ = 128 kernel sparse_attn_fwd launches for this many (head, query block) pairs."""
     if n_items <= 512 or n_items % 512 == 0 or n_items % 512 >= 256:
-        return "attn_bf16_d128_pp_kernel<4>"
+        return "attn_bf16_d128_pp_kernel<4, true>"   # key blocks of 64 rows: tiles loaded by base address
     return "attn_bf16_d128_kernel<4>"
 
 
@@ -293,7 +293,7 @@ def profiled_traffic_bytes():
     best = None
     try:
         for line in open(path):
-            if "attn_bf16_d128_pp_kernel<4>" in line and not line.startswith("#"):
+            if "attn_bf16_d128_pp_kernel<4" in line and not line.startswith("#"):
                 f = line.split()
                 total = (float(f[-2]) + float(f[-1])) * 1e6
                 best = total if best is None else max(best, total)   # of several groups of launches: the self-attention ones

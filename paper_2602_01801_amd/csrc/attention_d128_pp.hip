@@ -12,6 +12,8 @@
 //     Y(t): softmax of S(t) -> P(t), running max / sum      (vector ALUs, about as long)
 // and the two groups are kept half a tile apart by a workgroup barrier per half step, so that on every
 // SIMD one wavefront is in X while the other is in Y.  K tiles run one tile ahead of V tiles.
+// Both phases are bound by what one wavefront can issue (a vector instruction every 5.4 cycles, measured), so
+// Y carries as few instructions as possible; with key blocks of 64 rows (CONTIG) it has no row table at all.
 #include <type_traits>
 
 #include "common.hpp"
@@ -19,6 +21,8 @@
 namespace fastar {
 
 namespace d128pp {
+
+#pragma clang diagnostic ignored "-Winline-asm"   // m0 is named as clobbered where the tile loads set it
 
 constexpr int D = 128;
 constexpr int TK = 64;                 // keys per tile
@@ -124,7 +128,13 @@ __device__ __forceinline__ void wg_barrier() {
     __builtin_amdgcn_sched_barrier(0);
 }
 
-template <int NWG>  // wavefronts per group; a group owns a query block of 32*NWG queries
+// NWG = wavefronts per group; a group owns a query block of 32*NWG queries.
+// CONTIG = key blocks of 64 rows (bk_shift = 6): a tile is one selection entry, 64 consecutive cache rows.  Then there
+// is no row table: every wavefront takes the entry from a register (one lane per entry of the list), a tile that lies
+// wholly below len is loaded from one uniform base address with the row and chunk in the instructions' immediate
+// offsets (any other tile row by row, rows at or beyond len redirected to row 0), and only the multiplicity bias
+// goes through LDS.
+template <int NWG, bool CONTIG>
 __global__ __launch_bounds__(2 * NWG * 64, 1) void attn_bf16_d128_pp_kernel(
     const unsigned short *__restrict__ Q, const unsigned short *__restrict__ K, const unsigned short *__restrict__ V,
     const int32_t *__restrict__ cnt, const int32_t *__restrict__ len, const int32_t *__restrict__ sel,
@@ -217,6 +227,73 @@ __global__ __launch_bounds__(2 * NWG * 64, 1) void attn_bf16_d128_pp_kernel(
         tile_keys(keys, m);
         issue_keys(base, dst, keys, is_v);
     };
+    // ---- CONTIG: selection entries in a register, tiles by base address -------------------------------------------
+    const unsigned lds_base = (unsigned)(size_t)LDS_PTR(unsigned char, lds);
+    int sel_chunk = 0;
+    int selv = -1;   // lane l: entry 64 * sel_chunk + l of the list
+    if constexpr (CONTIG) {
+        if (n_listed > 0) selv = sel_row[min(lane, n_listed - 1)];
+        asm volatile("s_waitcnt vmcnt(0)" : "+v"(selv)::"memory");
+    }
+    // first row of tile t (uniform; -1: no such tile or a negative entry); tiles are asked for in rising order
+    auto row0_of = [&](int t) __attribute__((always_inline)) -> int {
+        if (t >= nt) return -1;
+        if ((t >> 6) != sel_chunk) {
+            sel_chunk = t >> 6;
+            selv = sel_row[min(64 * sel_chunk + lane, n_listed - 1)];
+            // waited for here, once per 64 tiles, so that the common path carries no wait for it
+            asm volatile("s_waitcnt vmcnt(0)" : "+v"(selv)::"memory");
+        }
+        const int kb = __builtin_amdgcn_readlane(selv, t & 63);
+        return kb >= 0 ? kb * TK : -1;
+    };
+    unsigned koff[IPW], voff[2];   // per-lane parts of a tile load: row within the instruction's four, swizzled chunk
+#pragma unroll
+    for (int i = 0; i < IPW; ++i) koff[i] = ((unsigned)lrow << 8) | (kswz ^ (64u * i));
+#pragma unroll
+    for (int i = 0; i < 2; ++i) voff[i] = ((unsigned)lrow << 8) | (vswz ^ (128u * i));
+    // this wavefront's share (tile rows 16 gw .. 16 gw + 15) of the tile that starts at cache row row0
+    auto issue_tile = [&](const unsigned short *base, unsigned char *dst, int row0, auto is_v) __attribute__((always_inline)) {
+        constexpr bool IS_V = decltype(is_v)::value;
+        if (row0 >= 0 && row0 + TK <= L) {
+            // the immediate offset of a direct load moves the global and the LDS address alike: 1 KiB per instruction
+            const unsigned char *tb =
+                (const unsigned char *)base + ((size_t)(unsigned)(__builtin_amdgcn_readfirstlane(row0) + 4 * IPW * gw) << 8);
+            const unsigned d = lds_base + (unsigned)(dst - lds) + gw * IPW * 1024;
+            unsigned o0, o1, o2, o3;
+            if constexpr (IS_V) { o0 = voff[0]; o1 = voff[1]; o2 = voff[0]; o3 = voff[1]; }
+            else { o0 = koff[0]; o1 = koff[1]; o2 = koff[2]; o3 = koff[3]; }
+            asm volatile("s_mov_b32 m0, %[d]\n\t"
+                         "s_nop 0\n\t"
+                         "global_load_lds_dwordx4 %[o0], %[b]\n\t"
+                         "global_load_lds_dwordx4 %[o1], %[b] offset:1024\n\t"
+                         "global_load_lds_dwordx4 %[o2], %[b] offset:2048\n\t"
+                         "global_load_lds_dwordx4 %[o3], %[b] offset:3072"
+                         :
+                         : [d] "s"(d), [b] "s"(tb), [o0] "v"(o0), [o1] "v"(o1), [o2] "v"(o2), [o3] "v"(o3)
+                         : "memory", "m0");
+        } else {
+            int keys[IPW];
+#pragma unroll
+            for (int i = 0; i < IPW; ++i) {
+                const int row = row0 + 4 * (gw * IPW + i) + lrow;
+                keys[i] = (row0 >= 0 && row < L) ? row : 0;   // masked rows fetch row 0, which is live
+            }
+            issue_keys(base, dst, keys, is_v);
+        }
+    };
+    // bias row of tile t: log2 of the multiplicity c of tile position gtid (threads gtid < 64 of the group)
+    auto write_bias = [&](int t, int row0, int c) __attribute__((always_inline)) {
+        const int row = row0 + gtid;
+        const bool live = row0 >= 0 && row < L;
+        meta[t & (NMETA - 1)].bias[gtid] = live ? (cnt_h ? __log2f((float)c) * inv_scale_log2 : 0.0f) : -INFINITY;
+    };
+    auto cnt_of = [&](int row0) __attribute__((always_inline)) -> int {
+        const int row = row0 + gtid;
+        return (cnt_h && row0 >= 0 && row < L) ? cnt_h[row] : 1;
+    };
+    int r1 = -1, r2 = -1, r3 = -1;   // first rows of tiles t+1, t+2, t+3 as seen from Y(t)
+
     // row tables: position p of tile `tile` (threads gtid < 64 of the group)
     auto sel_entry = [&](int tile) __attribute__((always_inline)) -> int {
         const int entry = (tile * TK + gtid) >> bk_shift;
@@ -241,23 +318,42 @@ __global__ __launch_bounds__(2 * NWG * 64, 1) void attn_bf16_d128_pp_kernel(
     // Y(t-1) (their loads are covered by the wait at the head of every Y), and requests those of tile t+4.
     int key_n = -1, cnt_n = 1;   // row and multiplicity of this thread's position in the next table to write
     int kb_ahead = -1;           // selection entry of this thread's position in the table after that
-    if (nt > 0) {
+    if constexpr (CONTIG) {
+        const int r0 = row0_of(0);
+        r1 = row0_of(1);
+        r2 = row0_of(2);
+        r3 = row0_of(3);
+        if (nt > 0 && gw == 0) {
+            write_bias(0, r0, cnt_of(r0));
+            write_bias(1, r1, cnt_of(r1));
+            write_bias(2, r2, cnt_of(r2));
+            cnt_n = cnt_of(r3);
+        }
+        __syncthreads();
+        if (nt > 0) {   // K(0), K(1) -> K stages 0, 1; V(0) -> V stage 0
+            issue_tile(Kh, kbuf, r0, std::false_type{});
+            if (nt > 1) issue_tile(Kh, kbuf + TILEB, r1, std::false_type{});
+            issue_tile(Vh, vbuf, r0, std::true_type{});
+        }
+    } else {
+        if (nt > 0) {
 #pragma unroll
-        for (int tt = 0; tt < 3; ++tt) {
-            const int key = key_of(tt < nt ? sel_entry(tt) : -1, tt);
-            write_meta(tt, key, (key >= 0 && cnt_h) ? cnt_h[key] : 1);
+            for (int tt = 0; tt < 3; ++tt) {
+                const int key = key_of(tt < nt ? sel_entry(tt) : -1, tt);
+                write_meta(tt, key, (key >= 0 && cnt_h) ? cnt_h[key] : 1);
+            }
+            if (nt > 3) {
+                key_n = key_of(sel_entry(3), 3);
+                if (key_n >= 0 && cnt_h) cnt_n = cnt_h[key_n];
+                if (nt > 4) kb_ahead = sel_entry(4);
+            }
         }
-        if (nt > 3) {
-            key_n = key_of(sel_entry(3), 3);
-            if (key_n >= 0 && cnt_h) cnt_n = cnt_h[key_n];
-            if (nt > 4) kb_ahead = sel_entry(4);
+        __syncthreads();
+        if (nt > 0) {   // K(0), K(1) -> K stages 0, 1; V(0) -> V stage 0
+            issue_rows(Kh, kbuf, meta[0], std::false_type{});
+            if (nt > 1) issue_rows(Kh, kbuf + TILEB, meta[1], std::false_type{});
+            issue_rows(Vh, vbuf, meta[0], std::true_type{});
         }
-    }
-    __syncthreads();
-    if (nt > 0) {   // K(0), K(1) -> K stages 0, 1; V(0) -> V stage 0
-        issue_rows(Kh, kbuf, meta[0], std::false_type{});
-        if (nt > 1) issue_rows(Kh, kbuf + TILEB, meta[1], std::false_type{});
-        issue_rows(Vh, vbuf, meta[0], std::true_type{});
     }
 
     // per-lane LDS addresses (see attention_d128.hip), including the group's base
@@ -317,13 +413,17 @@ __global__ __launch_bounds__(2 * NWG * 64, 1) void attn_bf16_d128_pp_kernel(
 #pragma unroll
             for (int s = 0; s < D / 16; ++s) s_acc[0] = mfma_bf16_32x32x16(ka[s], qf[s], s_acc[0]);
             wait_k(kb2);
-#pragma unroll
-            for (int s = 0; s < D / 16; ++s) s_acc[1] = mfma_bf16_32x32x16(kb2[s], qf[s], s_acc[1]);
-#pragma unroll
-            for (int s = 0; s < D / 16; ++s) kaddr[s] += (t & 1) ? -TILEB : TILEB;   // K(t) -> K(t+1)
+            // the scores of keys 0..31 are complete: their maximum is taken under the products of keys 32..63
+            __builtin_amdgcn_sched_barrier(0);
             float mx = s_acc[0][0];
 #pragma unroll
-            for (int v = 1; v < 16; ++v) mx = fmaxf(mx, s_acc[0][v]);
+            for (int s = 0; s < D / 16; ++s) {
+                s_acc[1] = mfma_bf16_32x32x16(kb2[s], qf[s], s_acc[1]);
+                if (s > 0) mx = fmaxf(mx, s_acc[0][2 * s]);
+                mx = fmaxf(mx, s_acc[0][2 * s + 1]);
+                kaddr[s] += (t & 1) ? -TILEB : TILEB;   // K(t) -> K(t+1)
+            }
+            __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int v = 0; v < 16; ++v) mx = fmaxf(mx, s_acc[1][v]);
             mx_tile = max_across_halves(mx);
@@ -341,21 +441,29 @@ __global__ __launch_bounds__(2 * NWG * 64, 1) void attn_bf16_d128_pp_kernel(
     // (any reference cancels in O / l), P just ranges up to 2^8 instead of 1.
     typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
     auto phase_y = [&](int t) __attribute__((always_inline)) {
-        if (t + 3 < nt) write_meta(t + 3, key_n, cnt_n);
-        key_n = -1;
-        cnt_n = 1;
-        int kb_next = -1;
-        if (t + 4 < nt) {
-            key_n = key_of(kb_ahead, t + 4);
-            if (key_n >= 0 && cnt_h) cnt_n = cnt_h[key_n];
-            if (t + 5 < nt) kb_next = sel_entry(t + 5);
-        }
-        kb_ahead = kb_next;
-        // row lists of the two tiles to fetch: read now, used after the exponentials (their LDS round trip queues
-        // behind the other group's operand reads)
         int kk[IPW], vk[IPW];
-        tile_keys(kk, meta[(t + 2 < nt ? t + 2 : t) & (NMETA - 1)]);
-        tile_keys(vk, meta[(t + 1 < nt ? t + 1 : t) & (NMETA - 1)]);
+        int r4 = -1;
+        if constexpr (CONTIG) {
+            // bias row of tile t+3 from the multiplicities requested during Y(t-1); request those of tile t+4
+            if (gw == 0 && t + 3 < nt) write_bias(t + 3, r3, cnt_n);
+            r4 = row0_of(t + 4);
+            if (gw == 0) cnt_n = cnt_of(r4);
+        } else {
+            if (t + 3 < nt) write_meta(t + 3, key_n, cnt_n);
+            key_n = -1;
+            cnt_n = 1;
+            int kb_next = -1;
+            if (t + 4 < nt) {
+                key_n = key_of(kb_ahead, t + 4);
+                if (key_n >= 0 && cnt_h) cnt_n = cnt_h[key_n];
+                if (t + 5 < nt) kb_next = sel_entry(t + 5);
+            }
+            kb_ahead = kb_next;
+            // row lists of the two tiles to fetch: read now, used after the exponentials (their LDS round trip queues
+            // behind the other group's operand reads)
+            tile_keys(kk, meta[(t + 2 < nt ? t + 2 : t) & (NMETA - 1)]);
+            tile_keys(vk, meta[(t + 1 < nt ? t + 1 : t) & (NMETA - 1)]);
+        }
         const float mx = mx_tile;
         if (__any(mx > m_ref + tau_raw)) {   // wave-uniform
             const float m_new = fmaxf(m_ref, mx);
@@ -376,9 +484,14 @@ __global__ __launch_bounds__(2 * NWG * 64, 1) void attn_bf16_d128_pp_kernel(
         for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
             for (int hh = 0; hh < 2; ++hh) {
-                if (kb == 1 && hh == 0) {   // half way: the row lists have arrived by now
-                    if (t + 2 < nt) issue_keys(Kh, kbuf + (t & 1) * TILEB, kk, std::false_type{});
-                    if (t + 1 < nt) issue_keys(Vh, vbuf + ((t + 1) & 1) * TILEB, vk, std::true_type{});
+                if (kb == 1 && hh == 0) {   // half way (the row lists have arrived by now)
+                    if constexpr (CONTIG) {
+                        if (t + 2 < nt) issue_tile(Kh, kbuf + (t & 1) * TILEB, r2, std::false_type{});
+                        if (t + 1 < nt) issue_tile(Vh, vbuf + ((t + 1) & 1) * TILEB, r1, std::true_type{});
+                    } else {
+                        if (t + 2 < nt) issue_keys(Kh, kbuf + (t & 1) * TILEB, kk, std::false_type{});
+                        if (t + 1 < nt) issue_keys(Vh, vbuf + ((t + 1) & 1) * TILEB, vk, std::true_type{});
+                    }
                 }
                 bf16x2 pr[4];
 #pragma unroll
@@ -397,6 +510,11 @@ __global__ __launch_bounds__(2 * NWG * 64, 1) void attn_bf16_d128_pp_kernel(
         asm volatile("" : "+v"(pf[0][0]), "+v"(pf[0][1]), "+v"(pf[1][0]), "+v"(pf[1][1]), "+v"(l0), "+v"(l1));
         read_vt<0>(va, vaddr);           // V(t), keys 0..31, for X(t+1)
         wait_vt(va);
+        if constexpr (CONTIG) {
+            r1 = r2;
+            r2 = r3;
+            r3 = r4;
+        }
     };
 
     // Half steps.  A group with nt tiles runs X(0) Y(0) X(1) Y(1) ... Y(nt-1) X(nt), one workgroup barrier
@@ -468,17 +586,25 @@ int launch_attn_bf16_d128_pp(const void *Q, int n_q, const void *K, const void *
     using namespace d128pp;
     static bool attr_set = false;
     if (!attr_set) {  // more than 64 KiB of LDS per workgroup has to be requested once per kernel
-        if (hipFuncSetAttribute((const void *)attn_bf16_d128_pp_kernel<4>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                LDS_BYTES) != hipSuccess)
+        if (hipFuncSetAttribute((const void *)attn_bf16_d128_pp_kernel<4, false>,
+                                hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES) != hipSuccess ||
+            hipFuncSetAttribute((const void *)attn_bf16_d128_pp_kernel<4, true>,
+                                hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES) != hipSuccess)
             return FASTAR_ERR_HIP;
         attr_set = true;
     }
     const int n_qb = (n_q + 127) / 128;
     const int pairs = (n_qb * H + 1) / 2;
     const dim3 grid((unsigned)(((pairs + 7) / 8) * 8));
-    hipLaunchKernelGGL(attn_bf16_d128_pp_kernel<4>, grid, dim3(512), LDS_BYTES, s, (const unsigned short *)Q,
-                       (const unsigned short *)K, (const unsigned short *)V, cnt, len, sel, nsel, n_q, C, bk_shift,
-                       n_sel, n_qb, H, scale_log2, 1.0f / scale_log2, (unsigned short *)O, lse);
+    if (bk_shift == 6)   // key blocks of 64 rows: tiles by base address
+        hipLaunchKernelGGL((attn_bf16_d128_pp_kernel<4, true>), grid, dim3(512), LDS_BYTES, s, (const unsigned short *)Q,
+                           (const unsigned short *)K, (const unsigned short *)V, cnt, len, sel, nsel, n_q, C, bk_shift,
+                           n_sel, n_qb, H, scale_log2, 1.0f / scale_log2, (unsigned short *)O, lse);
+    else
+        hipLaunchKernelGGL((attn_bf16_d128_pp_kernel<4, false>), grid, dim3(512), LDS_BYTES, s,
+                           (const unsigned short *)Q, (const unsigned short *)K, (const unsigned short *)V, cnt, len, sel,
+                           nsel, n_q, C, bk_shift, n_sel, n_qb, H, scale_log2, 1.0f / scale_log2, (unsigned short *)O,
+                           lse);
     if (hipGetLastError() != hipSuccess) return FASTAR_ERR_HIP;
     return FASTAR_OK;
 }
