@@ -297,6 +297,7 @@ def check_attention(Q, K, V, cnt, length, sel, nsel, BQ, BK, scale, dtype):
     ("bf16", 1, 300, 64 * 20, 128, 128, 64, 20, [1280], True),       # odd number of query blocks: a lone block in the last workgroup
     ("bf16", 1, 100, 640, 128, 128, 32, 7, [640], True),             # a single query block
     ("bf16", 5, 128, 64 * 9, 128, 128, 64, 9, [576, 64, 0, 576, 1], False),   # neighbours with 9 / 1 / 0 tiles
+    ("bf16", 2, 384, 64 * 150, 128, 128, 64, 140, [9600, 9017], True),   # lists longer than 64 and 128 entries
 ])
 def test_sparse_attention_matches_oracle(dtype, H, n_q, C, d, BQ, BK, n_sel, lens, use_cnt):
     rng = np.random.default_rng(n_q * 7 + C)
@@ -311,6 +312,36 @@ def test_sparse_attention_matches_oracle(dtype, H, n_q, C, d, BQ, BK, n_sel, len
     n_qb = (n_q + BQ - 1) // BQ
     sel, nsel = random_selection(rng, H, n_qb, n_sel, lens, BK)
     check_attention(Q, K, V, cnt, length, sel, nsel, BQ, BK, d ** -0.5, dtype)
+
+
+def test_attention_skips_negative_and_dead_entries_inside_a_list():
+    """Entries that are negative or name a key block beyond len count as listed but contribute nothing."""
+    rng = np.random.default_rng(77)
+    H, n_q, C, d, BQ, BK, n_sel = 2, 256, 64 * 40, 128, 128, 64, 70
+    lens = [64 * 30 + 5, 64 * 12]
+    Q = to_storage(rng.standard_normal((H, n_q, d)).astype(np.float32), "bf16")
+    K = to_storage(rng.standard_normal((H, C, d)).astype(np.float32), "bf16")
+    V = to_storage(rng.standard_normal((H, C, d)).astype(np.float32), "bf16")
+    length = np.array(lens, np.int32)
+    for h in range(H):
+        K[h, lens[h]:] = to_storage(np.full((C - lens[h], d), np.nan, np.float32), "bf16")
+        V[h, lens[h]:] = to_storage(np.full((C - lens[h], d), np.inf, np.float32), "bf16")
+    cnt = rng.integers(1, 9, size=(H, C)).astype(np.int32)
+    n_qb = n_q // BQ
+    sel = np.full((H, n_qb, n_sel), -1, np.int32)
+    nsel = np.zeros((H, n_qb), np.int32)
+    for h in range(H):
+        n_kb = (lens[h] + BK - 1) // BK
+        for b in range(n_qb):
+            m = n_sel - 3 * b
+            row = rng.integers(0, C // BK, size=m).astype(np.int32)    # some of them name dead blocks
+            row[rng.random(m) < 0.2] = -1
+            row[0] = -1 if b == 0 else n_kb - 1                        # a list that starts with nothing / with the partial block
+            row[-1] = C // BK - 1
+            sel[h, b, :m] = row
+            nsel[h, b] = m
+    sel[1, 1, :nsel[1, 1]] = -1                                        # a list of nothing at all
+    check_attention(Q, K, V, cnt, length, sel, nsel, BQ, BK, d ** -0.5, "bf16")
 
 
 def test_dense_limit_on_clustered_data_fp32_and_bf16():
