@@ -32,6 +32,11 @@ def _check_lines(lines, verbose):
         if t.startswith(';;#ASMEND'): in_asm = False; continue
         if not t or t.startswith((';', '.', '//')): continue
         if re.match(r'^\.?LBB', t): continue
+        if t.startswith(('s_branch', 's_endpgm', 's_setpc')):
+            # straight-line approximation of the control flow: nothing falls through an unconditional jump, so
+            # what follows in the text is not reached with these reads in flight
+            pending = {}
+            continue
         ops = re.findall(r'\b[va]\[\d+:\d+\]|\b[va]\d+\b', t)
         used = set().union(*[regs(o) for o in ops]) if ops else set()
         if in_asm and t.startswith('ds_read'):

@@ -292,7 +292,7 @@ __global__ __launch_bounds__(2 * NWG * 64, 1) void attn_bf16_d128_pp_kernel(
         const int row = row0 + gtid;
         return (cnt_h && row0 >= 0 && row < L) ? cnt_h[row] : 1;
     };
-    int r1 = -1, r2 = -1, r3 = -1;   // first rows of tiles t+1, t+2, t+3 as seen from Y(t)
+    int r1 = -1, r2 = -1, r3 = -1, r4 = -1;   // first rows of tiles t+1 .. t+4 as seen from X(t) and Y(t)
 
     // row tables: position p of tile `tile` (threads gtid < 64 of the group)
     auto sel_entry = [&](int tile) __attribute__((always_inline)) -> int {
@@ -399,8 +399,15 @@ __global__ __launch_bounds__(2 * NWG * 64, 1) void attn_bf16_d128_pp_kernel(
         bf16x8 ka[D / 16], kb2[D / 16];
         if constexpr (PV) read_vt<32 * ROWB>(vb, vaddr);     // V(t-1), keys 32..63 (keys 0..31 are in va)
         if constexpr (QK) read_k<0>(ka, kaddr);              // K(t), keys 0..31
+        if constexpr (PV) pv_mfma(o_acc, va, pf[0]);
+        if constexpr (CONTIG && QK) {
+            // here rather than in Y, which is the longer phase: bias row of tile t+3 from the multiplicities requested
+            // during X(t-1); first row and multiplicities of tile t+4
+            if (gw == 0 && t + 3 < nt) write_bias(t + 3, r3, cnt_n);
+            r4 = row0_of(t + 4);
+            if (gw == 0) cnt_n = cnt_of(r4);
+        }
         if constexpr (PV) {
-            pv_mfma(o_acc, va, pf[0]);
             if constexpr (QK) wait_vt_but8(vb); else wait_vt(vb);
             pv_mfma(o_acc, vb, pf[1]);
 #pragma unroll
@@ -442,13 +449,7 @@ __global__ __launch_bounds__(2 * NWG * 64, 1) void attn_bf16_d128_pp_kernel(
     typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
     auto phase_y = [&](int t) __attribute__((always_inline)) {
         int kk[IPW], vk[IPW];
-        int r4 = -1;
-        if constexpr (CONTIG) {
-            // bias row of tile t+3 from the multiplicities requested during Y(t-1); request those of tile t+4
-            if (gw == 0 && t + 3 < nt) write_bias(t + 3, r3, cnt_n);
-            r4 = row0_of(t + 4);
-            if (gw == 0) cnt_n = cnt_of(r4);
-        } else {
+        if constexpr (!CONTIG) {
             if (t + 3 < nt) write_meta(t + 3, key_n, cnt_n);
             key_n = -1;
             cnt_n = 1;
