@@ -656,6 +656,112 @@ def test_attention_with_logits_that_keep_growing_along_the_key_list(BQ):
 
 # ----------------------------------------------------------------------------------------- argument checks
 
+# ----------------------------------------------------------------------------------------- HIP graph
+
+def test_selection_and_attention_replay_from_a_hip_graph():
+    """No entry point allocates, synchronises or clears memory with a memset, so a chunk's calls can be captured once
+    and replayed.  Every replay (different queries each time, eager work and synchronisations in between) must
+    reproduce the eager result bit for bit."""
+    H, n_q, C, d, r, BQ, BK, n_rep, n_sel, n_p, n_sel_x = 3, 640, 64 * 40, 128, 32, 128, 64, 4, 9, 256, 64
+    rng = np.random.default_rng(5)
+    codec = make_codec(11, 2, d, r)
+    dcodec = dev_codec(codec)
+    K = to_dev(to_storage(rng.standard_normal((H, C, d)).astype(np.float32), "bf16"))
+    V = to_dev(to_storage(rng.standard_normal((H, C, d)).astype(np.float32), "bf16"))
+    Kp = to_dev(to_storage(rng.standard_normal((H, n_p, d)).astype(np.float32), "bf16"))
+    Vp = to_dev(to_storage(rng.standard_normal((H, n_p, d)).astype(np.float32), "bf16"))
+    cnt = to_dev(rng.integers(1, 6, size=(H, C)).astype(np.int32))
+    length = to_dev(np.array([C, C - 100, 64 * 7 + 3], np.int32))
+    kcode = fa.encode(K, dcodec)
+    pcode = fa.encode(Kp, dcodec)
+    Qs = [to_dev(to_storage(rng.standard_normal((H, n_q, d)).astype(np.float32), "bf16")) for _ in range(3)]
+    n_qb = n_q // BQ
+    dev = "cuda"
+
+    def buffers():
+        e = lambda shape, dt: torch.empty(shape, dtype=dt, device=dev)
+        return dict(qcode=e((H, n_q, r), torch.int8), sel=(e((H, n_qb, n_sel), torch.int32), e((H, n_qb), torch.int32)),
+                    O=(e((H, n_q, d), torch.bfloat16), e((H, n_q), torch.float32)),
+                    X=(e((H, n_qb, n_sel_x), torch.int32), e((H, n_qb), torch.int32), e((H, n_q, d), torch.bfloat16)),
+                    ws=e((fa.workspace_bytes(fa.OP_SELECT_SELF, H, n_q, C, r, BQ, BK, n_rep),), torch.uint8))
+
+    def calls(Q, b):
+        fa.encode(Q, dcodec, out=b["qcode"])
+        fa.ann_select_self(b["qcode"], kcode, length, BQ, n_rep, BK, n_sel, ws=b["ws"], out=b["sel"])
+        fa.sparse_attn_fwd(Q, K, V, cnt, length, b["sel"][0], b["sel"][1], BQ, BK, d ** -0.5, out=b["O"])
+        fa.ann_cross_attn_fwd(Q, b["qcode"], Kp, Vp, pcode, BQ, n_sel_x, d ** -0.5, out=b["X"])
+
+    eager = []
+    for Q in Qs:
+        b = buffers()
+        calls(Q, b)
+        sync()
+        eager.append(b)
+    Qg = torch.empty_like(Qs[0])
+    g_buf = buffers()
+    Qg.copy_(Qs[0])
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):          # one run outside the capture, on a side stream
+        calls(Qg, g_buf)
+    torch.cuda.current_stream().wait_stream(side)
+    sync()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        calls(Qg, g_buf)
+    for rep in range(2):
+        for i, Q in enumerate(Qs):
+            Qg.copy_(Q)                      # eager work between the replays
+            for t in g_buf["O"] + g_buf["X"] + g_buf["sel"]:
+                t.zero_()
+            sync()
+            graph.replay()
+            sync()
+            ref = eager[i]
+            for name in ("sel", "O", "X"):
+                for a, b_ in zip(g_buf[name], ref[name]):
+                    assert torch.equal(a.view(torch.int16) if a.dtype == torch.bfloat16 else a,
+                                       b_.view(torch.int16) if b_.dtype == torch.bfloat16 else b_), (rep, i, name)
+
+
+def test_tempcache_frames_replayed_from_hip_graphs():
+    """Each frame's compress call captured in a graph of its own and run by replaying it (persistent workspace,
+    preallocated outputs): state and outputs as the oracle's, frame after frame, through merging and eviction."""
+    c = dict(CONFIGS["cfg1"])
+    C, tau, n_frames = 2 * c["T"] + 40, 0.98, 8
+    fs = FrameStream(c["seed"], c["cfg_id"], c["H"], c["d"], c["T"], c["n_c"], c["p"], c["sigma_d"], c["dtype"])
+    codec = make_codec(c["seed"], c["cfg_id"], c["d"], c["r"])
+    ref = oracle.Cache.empty(c["H"], C, c["d"], c["r"], c["dtype"])
+    gpu = dev_cache(ref)
+    dcodec = dev_codec(codec)
+    ws = torch.zeros(fa.workspace_bytes(fa.OP_COMPRESS, c["H"], c["T"], C, c["r"]), dtype=torch.uint8, device="cuda")
+    outs = [(torch.empty((c["H"], c["T"]), dtype=torch.int32, device="cuda"),
+             torch.empty((c["H"], c["T"]), dtype=torch.uint8, device="cuda"),
+             torch.empty((c["H"], 8), dtype=torch.int32, device="cuda")) for _ in range(2)]
+    prev_ref, prev_gpu = None, None
+    evicted = 0
+    for f in range(n_frames):
+        K, V = fs.next_frame()
+        mm_r, mg_r, st_r = oracle.tempcache_compress(ref, codec.R, codec.qscale, codec.shift, K, V, cand=prev_ref,
+                                                     tau2_q16=TAU2(tau), frame_id=f)
+        Kd, Vd = to_dev(K), to_dev(V)
+        out = outs[f & 1]
+        sync()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            fa.tempcache_compress(gpu, dcodec, Kd, Vd, cand=prev_gpu, tau2_q16=TAU2(tau), frame_id=f, ws=ws, out=out,
+                                  ws_persistent=True)
+        graph.replay()
+        sync()
+        assert np.array_equal(to_host(out[1]), mg_r), f"merged flags, frame {f}"
+        assert np.array_equal(to_host(out[0]), mm_r), f"merge map, frame {f}"
+        assert np.array_equal(to_host(out[2]), st_r), f"stats, frame {f}"
+        assert_cache_equal(host_cache(gpu), ref, VTOL[c["dtype"]])
+        evicted += int(st_r[:, 3].sum())
+        prev_ref, prev_gpu = mm_r, out[0]
+    assert evicted > 0, "the rollout was meant to reach eviction"
+
+
 def test_bad_arguments_are_rejected_on_the_host():
     q = torch.zeros((1, 128, 32), dtype=torch.int8, device="cuda")
     k = torch.zeros((1, 256, 32), dtype=torch.int8, device="cuda")
