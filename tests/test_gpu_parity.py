@@ -345,6 +345,40 @@ def test_attention_skips_negative_and_dead_entries_inside_a_list():
     check_attention(Q, K, V, cnt, length, sel, nsel, BQ, BK, d ** -0.5, "bf16")
 
 
+@pytest.mark.parametrize("seed", [1, 2, 3])
+def test_attention_on_seeded_random_shapes(seed):
+    """bf16, d 128, key blocks of 64 rows: a dozen random shapes per seed (ragged queries and caches, capacities that are
+    no multiple of the block, lists of 0..150 entries with repeats, negative and dead entries, with and without
+    multiplicities, query scales 0.3..3) against the oracle."""
+    rng = np.random.default_rng(seed)
+    d, BQ, BK = 128, 128, 64
+    for case in range(12):
+        H, n_q, C = int(rng.integers(1, 5)), int(rng.integers(1, 700)), int(rng.integers(64, 64 * 60))
+        n_sel = int(rng.integers(1, 150))
+        lens = [int(rng.integers(0, C + 1)) for _ in range(H)]
+        if rng.random() < 0.3:
+            lens[0] = C
+        Q = to_storage(rng.standard_normal((H, n_q, d)).astype(np.float32) * rng.choice([0.3, 1.0, 3.0]), "bf16")
+        K = to_storage(rng.standard_normal((H, C, d)).astype(np.float32), "bf16")
+        V = to_storage(rng.standard_normal((H, C, d)).astype(np.float32), "bf16")
+        for h in range(H):                                           # poison dead slots
+            K[h, lens[h]:] = to_storage(np.full((C - lens[h], d), np.nan, np.float32), "bf16")
+            V[h, lens[h]:] = to_storage(np.full((C - lens[h], d), np.inf, np.float32), "bf16")
+        cnt = rng.integers(1, 9, size=(H, C)).astype(np.int32) if rng.random() < 0.7 else None
+        n_qb = (n_q + BQ - 1) // BQ
+        sel = np.full((H, n_qb, n_sel), -1, np.int32)
+        nsel = np.zeros((H, n_qb), np.int32)
+        for h in range(H):
+            for b in range(n_qb):
+                m = int(rng.integers(0, n_sel + 1))
+                row = rng.integers(0, (C + BK - 1) // BK, size=m).astype(np.int32)
+                if m and rng.random() < 0.5:
+                    row[rng.random(m) < 0.15] = -1
+                sel[h, b, :m] = row
+                nsel[h, b] = m
+        check_attention(Q, K, V, cnt, np.array(lens, np.int32), sel, nsel, BQ, BK, d ** -0.5, "bf16")
+
+
 def test_dense_limit_on_clustered_data_fp32_and_bf16():
     for name, dtype in (("cfg1", "fp32"), ("cfg1", "bf16")):
         c = CONFIGS[name]
