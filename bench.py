@@ -279,10 +279,12 @@ def cpu_baseline(cfg, pipe, prefill_host, chunks, ps, n_heads, to_host, sign_mat
     return info
 
 
-def attn_kernel_name(n_items):
-    """Which bf16 d = 128, BQ = 128 kernel sparse_attn_fwd launches for this many (head, query block) pairs."""
+def attn_kernel_name(n_items, H, C, d=128):
+    """Which bf16 d = 128, BQ = 128, BK = 64 kernel sparse_attn_fwd launches for this many (head, query block) pairs
+    and this cache capacity (K and V of all heads within 256 MB: bias rows written in the matrix phase)."""
     if n_items <= 512 or n_items % 512 == 0 or n_items % 512 >= 256:
-        return "attn_bf16_d128_pp_kernel<4, true>"   # key blocks of 64 rows: tiles loaded by base address
+        resident = H * C * d * 2 * 2 <= (256 << 20)
+        return "attn_bf16_d128_pp_kernel<4, true, %s>" % ("true" if resident else "false")
     return "attn_bf16_d128_kernel<4>"
 
 
@@ -431,7 +433,7 @@ def main():
         "stages_ms": {k: round(v, 4) for k, v in stage_ms.items()},
         "stages_note": f"separate pass of {args.stage_steps} steps after the timed region, one event per stage",
         "effective_tflops": round(tflops, 2), "pct_mfma_peak": round(100 * tflops / PEAK_BF16_TFLOPS, 2),
-        "roofline": {"kernel": attn_kernel_name(cfg["H"] * pipe.n_qb) + " (block-sparse self-attention)", "bound": "mfma",
+        "roofline": {"kernel": attn_kernel_name(cfg["H"] * pipe.n_qb, cfg["H"], C) + " (block-sparse self-attention)", "bound": "mfma",
                      "achieved": round(tflops, 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                      "frac": round(tflops / PEAK_BF16_TFLOPS, 4),
                      "traffic": profiled_traffic_bytes() if args.workload == "cfg2" else None,

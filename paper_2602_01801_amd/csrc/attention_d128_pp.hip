@@ -134,7 +134,11 @@ __device__ __forceinline__ void wg_barrier() {
 // wholly below len is loaded from one uniform base address with the row and chunk in the instructions' immediate
 // offsets (any other tile row by row, rows at or beyond len redirected to row 0), and only the multiplicity bias
 // goes through LDS.
-template <int NWG, bool CONTIG>
+// BIAS_X (with CONTIG): the bias row of a tile is written in the matrix phase, one step after its multiplicities were
+// requested there, instead of at the head of the vector phase.  That shortens the vector phase (the longer one), but the
+// compiler's wait for the multiplicities then also waits for the tile loads the vector phase in between has issued:
+// good while those come from L2 / the memory-side cache, bad once the cache outgrows them.
+template <int NWG, bool CONTIG, bool BIAS_X>
 __global__ __launch_bounds__(2 * NWG * 64, 1) void attn_bf16_d128_pp_kernel(
     const unsigned short *__restrict__ Q, const unsigned short *__restrict__ K, const unsigned short *__restrict__ V,
     const int32_t *__restrict__ cnt, const int32_t *__restrict__ len, const int32_t *__restrict__ sel,
@@ -327,7 +331,8 @@ __global__ __launch_bounds__(2 * NWG * 64, 1) void attn_bf16_d128_pp_kernel(
             write_bias(0, r0, cnt_of(r0));
             write_bias(1, r1, cnt_of(r1));
             write_bias(2, r2, cnt_of(r2));
-            cnt_n = cnt_of(r3);
+            if constexpr (BIAS_X) cnt_n = cnt_of(r3);
+            else write_bias(3, r3, cnt_of(r3));
         }
         __syncthreads();
         if (nt > 0) {   // K(0), K(1) -> K stages 0, 1; V(0) -> V stage 0
@@ -401,9 +406,12 @@ __global__ __launch_bounds__(2 * NWG * 64, 1) void attn_bf16_d128_pp_kernel(
         if constexpr (QK) read_k<0>(ka, kaddr);              // K(t), keys 0..31
         if constexpr (PV) pv_mfma(o_acc, va, pf[0]);
         if constexpr (CONTIG && QK) {
-            // here rather than in Y, which is the longer phase: bias row of tile t+3 from the multiplicities requested
-            // during X(t-1); first row and multiplicities of tile t+4
-            if (gw == 0 && t + 3 < nt) write_bias(t + 3, r3, cnt_n);
+            // here rather than in Y, which is the longer phase: first row of tile t+4 and the request for its
+            // multiplicities (BIAS_X: after the bias row of tile t+3, whose multiplicities X(t-1) requested; otherwise
+            // the row of tile t+4 is written at the head of Y(t), behind the wait for every outstanding load that opens it)
+            if constexpr (BIAS_X) {
+                if (gw == 0 && t + 3 < nt) write_bias(t + 3, r3, cnt_n);
+            }
             r4 = row0_of(t + 4);
             if (gw == 0) cnt_n = cnt_of(r4);
         }
@@ -449,7 +457,11 @@ __global__ __launch_bounds__(2 * NWG * 64, 1) void attn_bf16_d128_pp_kernel(
     typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
     auto phase_y = [&](int t) __attribute__((always_inline)) {
         int kk[IPW], vk[IPW];
-        if constexpr (!CONTIG) {
+        if constexpr (CONTIG) {
+            if constexpr (!BIAS_X) {
+                if (gw == 0 && t + 4 < nt) write_bias(t + 4, r4, cnt_n);   // requested during X(t)
+            }
+        } else {
             if (t + 3 < nt) write_meta(t + 3, key_n, cnt_n);
             key_n = -1;
             cnt_n = 1;
@@ -587,25 +599,27 @@ int launch_attn_bf16_d128_pp(const void *Q, int n_q, const void *K, const void *
     using namespace d128pp;
     static bool attr_set = false;
     if (!attr_set) {  // more than 64 KiB of LDS per workgroup has to be requested once per kernel
-        if (hipFuncSetAttribute((const void *)attn_bf16_d128_pp_kernel<4, false>,
-                                hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES) != hipSuccess ||
-            hipFuncSetAttribute((const void *)attn_bf16_d128_pp_kernel<4, true>,
-                                hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES) != hipSuccess)
-            return FASTAR_ERR_HIP;
+        for (const void *f : {(const void *)attn_bf16_d128_pp_kernel<4, false, false>,
+                              (const void *)attn_bf16_d128_pp_kernel<4, true, false>,
+                              (const void *)attn_bf16_d128_pp_kernel<4, true, true>})
+            if (hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES) != hipSuccess)
+                return FASTAR_ERR_HIP;
         attr_set = true;
     }
     const int n_qb = (n_q + 127) / 128;
     const int pairs = (n_qb * H + 1) / 2;
     const dim3 grid((unsigned)(((pairs + 7) / 8) * 8));
-    if (bk_shift == 6)   // key blocks of 64 rows: tiles by base address
-        hipLaunchKernelGGL((attn_bf16_d128_pp_kernel<4, true>), grid, dim3(512), LDS_BYTES, s, (const unsigned short *)Q,
-                           (const unsigned short *)K, (const unsigned short *)V, cnt, len, sel, nsel, n_q, C, bk_shift,
-                           n_sel, n_qb, H, scale_log2, 1.0f / scale_log2, (unsigned short *)O, lse);
-    else
-        hipLaunchKernelGGL((attn_bf16_d128_pp_kernel<4, false>), grid, dim3(512), LDS_BYTES, s,
-                           (const unsigned short *)Q, (const unsigned short *)K, (const unsigned short *)V, cnt, len, sel,
-                           nsel, n_q, C, bk_shift, n_sel, n_qb, H, scale_log2, 1.0f / scale_log2, (unsigned short *)O,
-                           lse);
+#define FASTAR_PP(CONTIG, BIAS_X)                                                                                  \
+    hipLaunchKernelGGL((attn_bf16_d128_pp_kernel<4, CONTIG, BIAS_X>), grid, dim3(512), LDS_BYTES, s,                \
+                       (const unsigned short *)Q, (const unsigned short *)K, (const unsigned short *)V, cnt, len, sel, \
+                       nsel, n_q, C, bk_shift, n_sel, n_qb, H, scale_log2, 1.0f / scale_log2, (unsigned short *)O, lse)
+    // key blocks of 64 rows: tiles by base address; K and V of all heads within reach of the 256 MB memory-side cache:
+    // the bias rows are written in the matrix phase
+    const bool cache_resident = (size_t)H * (size_t)C * D * 2 * 2 <= ((size_t)256 << 20);
+    if (bk_shift == 6 && cache_resident) FASTAR_PP(true, true);
+    else if (bk_shift == 6) FASTAR_PP(true, false);
+    else FASTAR_PP(false, false);
+#undef FASTAR_PP
     if (hipGetLastError() != hipSuccess) return FASTAR_ERR_HIP;
     return FASTAR_OK;
 }

@@ -299,6 +299,7 @@ def check_attention(Q, K, V, cnt, length, sel, nsel, BQ, BK, scale, dtype):
     ("bf16", 5, 128, 64 * 9, 128, 128, 64, 9, [576, 64, 0, 576, 1], False),   # neighbours with 9 / 1 / 0 tiles
     ("bf16", 2, 384, 64 * 150, 128, 128, 64, 140, [9600, 9017], True),   # lists longer than 64 and 128 entries
     ("bf16", 2, 300, 1000, 128, 128, 64, 16, [1000, 777], True),     # capacity that is no multiple of the key block
+    ("bf16", 2, 384, 270000, 128, 128, 64, 20, [270000, 123457], True),   # K and V beyond the memory-side cache: other variant
 ])
 def test_sparse_attention_matches_oracle(dtype, H, n_q, C, d, BQ, BK, n_sel, lens, use_cnt):
     rng = np.random.default_rng(n_q * 7 + C)
