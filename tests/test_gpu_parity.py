@@ -94,6 +94,43 @@ def test_ann_select_cross_bit_exact(H, n_q, n_p, r, BQ, n_sel, span):
     assert np.array_equal(to_host(sel), ref_sel)
 
 
+@pytest.mark.parametrize("seed", [1, 2, 3])
+def test_selection_on_seeded_random_shapes(seed):
+    """AnnSA and AnnCA on a dozen random shapes per seed: both code widths, every summary count, key blocks of 32..128
+    rows, ragged query blocks and caches (an empty head now and then), budgets from one block to more than there are,
+    narrow code ranges (many ties) and wide ones.  Selections are bit-exact."""
+    rng = np.random.default_rng(100 + seed)
+    for case in range(12):
+        H, r = int(rng.integers(1, 5)), int(rng.choice([32, 64]))
+        n_rep = int(rng.choice([1, 2, 4, 8, 16, 32]))
+        BQ = n_rep * int(rng.integers(1, 128 // n_rep + 1))
+        BK = 32 * int(rng.integers(1, 5))
+        n_q, C = int(rng.integers(1, 900)), int(rng.integers(1, 6000))
+        n_blocks = (C + BK - 1) // BK
+        n_sel = int(rng.integers(1, n_blocks + 8))
+        lens = [int(rng.integers(0, C + 1)) for _ in range(H)]
+        if rng.random() < 0.3:
+            lens[0] = C
+        if rng.random() < 0.2:
+            lens[-1] = 0
+        span = int(rng.choice([1, 3, 40, 127]))
+        qc, kc = rand_codes(rng, -span, span, H, n_q, r), rand_codes(rng, -span, span, H, C, r)
+        length = np.array(lens, np.int32)
+        what = f"seed {seed} case {case}: H={H} r={r} n_rep={n_rep} BQ={BQ} BK={BK} n_q={n_q} C={C} n_sel={n_sel} lens={lens}"
+        ref_sel, ref_nsel = oracle.ann_select_self(qc, kc, length, BQ, n_rep, BK, n_sel)
+        sel, nsel = fa.ann_select_self(to_dev(qc), to_dev(kc), to_dev(length), BQ, n_rep, BK, n_sel)
+        assert np.array_equal(to_host(nsel), ref_nsel), what
+        assert np.array_equal(to_host(sel), ref_sel), what
+
+        n_p, BQc, n_selc = int(rng.integers(1, 1500)), int(rng.integers(1, 400)), int(rng.integers(1, 100))
+        pc = rand_codes(rng, -span, span, H, n_p, r)
+        what = f"seed {seed} case {case}: H={H} r={r} BQ={BQc} n_q={n_q} n_p={n_p} n_sel={n_selc}"
+        ref_sel, ref_nsel = oracle.ann_select_cross(qc, pc, BQc, n_selc)
+        sel, nsel = fa.ann_select_cross(to_dev(qc), to_dev(pc), BQc, n_selc)
+        assert np.array_equal(to_host(nsel), ref_nsel), what
+        assert np.array_equal(to_host(sel), ref_sel), what
+
+
 def test_selection_is_deterministic_across_repeats():
     rng = np.random.default_rng(11)
     qc, kc = rand_codes(rng, -2, 2, 4, 1000, 32), rand_codes(rng, -2, 2, 4, 64 * 300, 32)
