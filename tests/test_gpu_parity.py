@@ -624,6 +624,45 @@ def test_tempcache_edge_shapes_bit_exact(T, C, lens, n_cand, tau):
     assert_cache_equal(host_cache(gpu), ref, VTOL["fp32"])
 
 
+@pytest.mark.parametrize("seed", [1, 2, 3])
+def test_tempcache_on_seeded_random_shapes(seed):
+    """Eight random configurations per seed (storage type, head and code width, frame size, capacity from below one
+    frame to many, threshold, metric, representative, candidate list or whole cache), three frames each on one cache:
+    frames repeat earlier tokens with a little noise, so calls merge, append, evict and drop in mixtures.  Bookkeeping
+    bit-exact after every frame."""
+    rng = np.random.default_rng(200 + seed)
+    for case in range(8):
+        dtype, d, r = str(rng.choice(["fp32", "bf16"])), int(rng.choice([64, 128])), int(rng.choice([32, 64]))
+        H, T = int(rng.integers(1, 4)), int(rng.integers(1, 700))
+        C = int(rng.integers(max(T // 2, 1), 5 * T + 64))
+        tau, metric = float(rng.choice([0.5, 0.9, 0.98])), int(rng.integers(0, 2))
+        rep_mode = int(rng.integers(0, 2))
+        windowed = rng.random() < 0.7
+        what = f"seed {seed} case {case}: {dtype} d={d} r={r} H={H} T={T} C={C} tau={tau} metric={metric} rep={rep_mode} windowed={windowed}"
+        codec = make_codec(seed, case, d, r)
+        ref = oracle.Cache.empty(H, C, d, r, dtype)
+        gpu = dev_cache(ref)
+        dcodec = dev_codec(codec)
+        pool = rng.standard_normal((H, T, d)).astype(np.float32)            # the tokens every frame drifts from
+        prev_ref = prev_gpu = None
+        for f in range(3):
+            fresh = rng.random((H, T, 1)) < 0.3
+            K = np.where(fresh, rng.standard_normal((H, T, d)), pool + 0.02 * rng.standard_normal((H, T, d)))
+            K, V = to_storage(K.astype(np.float32), dtype), to_storage(rng.standard_normal((H, T, d)).astype(np.float32), dtype)
+            use = windowed and prev_ref is not None
+            mm_r, mg_r, st_r = oracle.tempcache_compress(ref, codec.R, codec.qscale, codec.shift, K, V,
+                                                         cand=prev_ref if use else None, metric=metric,
+                                                         tau2_q16=TAU2(tau), frame_id=f, rep_mode=rep_mode)
+            mm_g, mg_g, st_g = fa.tempcache_compress(gpu, dcodec, to_dev(K), to_dev(V), cand=prev_gpu if use else None,
+                                                     metric=metric, tau2_q16=TAU2(tau), frame_id=f, rep_mode=rep_mode)
+            sync()
+            assert np.array_equal(to_host(st_g), st_r), f"{what}: stats, frame {f}"
+            assert np.array_equal(to_host(mg_g), mg_r), f"{what}: merged flags, frame {f}"
+            assert np.array_equal(to_host(mm_g), mm_r), f"{what}: merge map, frame {f}"
+            assert_cache_equal(host_cache(gpu), ref, VTOL[dtype])
+            prev_ref, prev_gpu = mm_r, mm_g
+
+
 @pytest.mark.parametrize("name,dtype,H,frames,C,tau,rep", [
     ("cfg1", None, None, 6, 6 * 256, 0.98, 0), ("cfg1", "bf16", None, 8, 2 * 256 + 40, 0.98, 0),
     ("cfg2", None, 2, 5, 3 * 1560, 0.98, 0), ("cfg1", None, None, 4, 5 * 256, 0.5, 1), ("cfg1", None, None, 2, 100, 2.0 ** 0.5, 0)])
