@@ -417,6 +417,48 @@ def test_attention_on_seeded_random_shapes(seed):
         check_attention(Q, K, V, cnt, np.array(lens, np.int32), sel, nsel, BQ, BK, d ** -0.5, "bf16")
 
 
+@pytest.mark.parametrize("seed", [1, 2, 3])
+def test_attention_on_seeded_random_shapes_of_every_kernel(seed):
+    """The same over everything sparse_attn_fwd supports: fp32 (any query block up to 128, any key block up to 64) and
+    bf16 (query blocks of 64 / 128, key blocks 1 .. 64), both head widths, so that every kernel behind the entry point
+    sees ragged shapes, repeated / negative / dead entries and poisoned dead slots."""
+    rng = np.random.default_rng(300 + seed)
+    for case in range(16):
+        dtype, d = str(rng.choice(["fp32", "bf16"])), int(rng.choice([64, 128]))
+        if dtype == "bf16":
+            BQ, BK = int(rng.choice([64, 128])), int(rng.choice([1, 2, 4, 8, 16, 32, 64]))
+        else:
+            BQ, BK = int(rng.integers(1, 129)), int(rng.integers(1, 65))
+        H, n_q, C = int(rng.integers(1, 4)), int(rng.integers(1, 500)), int(rng.integers(BK, 3000))
+        n_sel = int(rng.integers(1, 100))
+        lens = [int(rng.integers(0, C + 1)) for _ in range(H)]
+        if rng.random() < 0.3:
+            lens[0] = C
+        Q = to_storage(rng.standard_normal((H, n_q, d)).astype(np.float32) * rng.choice([0.3, 1.0, 3.0]), dtype)
+        K = to_storage(rng.standard_normal((H, C, d)).astype(np.float32), dtype)
+        V = to_storage(rng.standard_normal((H, C, d)).astype(np.float32), dtype)
+        for h in range(H):                                           # poison dead slots
+            K[h, lens[h]:] = to_storage(np.full((C - lens[h], d), np.nan, np.float32), dtype)
+            V[h, lens[h]:] = to_storage(np.full((C - lens[h], d), np.inf, np.float32), dtype)
+        cnt = rng.integers(1, 9, size=(H, C)).astype(np.int32) if rng.random() < 0.7 else None
+        n_qb = (n_q + BQ - 1) // BQ
+        sel = np.full((H, n_qb, n_sel), -1, np.int32)
+        nsel = np.zeros((H, n_qb), np.int32)
+        for h in range(H):
+            for b in range(n_qb):
+                m = int(rng.integers(0, n_sel + 1))
+                row = rng.integers(0, (C + BK - 1) // BK, size=m).astype(np.int32)
+                if m and rng.random() < 0.5:
+                    row[rng.random(m) < 0.15] = -1
+                sel[h, b, :m] = row
+                nsel[h, b] = m
+        try:
+            check_attention(Q, K, V, cnt, np.array(lens, np.int32), sel, nsel, BQ, BK, d ** -0.5, dtype)
+        except AssertionError as e:
+            raise AssertionError(f"seed {seed} case {case}: {dtype} d={d} BQ={BQ} BK={BK} H={H} n_q={n_q} C={C} "
+                                 f"n_sel={n_sel} lens={lens} cnt={'yes' if cnt is not None else 'no'}: {e}") from e
+
+
 def test_dense_limit_on_clustered_data_fp32_and_bf16():
     for name, dtype in (("cfg1", "fp32"), ("cfg1", "bf16")):
         c = CONFIGS[name]
