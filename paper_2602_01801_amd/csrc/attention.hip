@@ -413,7 +413,7 @@ extern "C" int sparse_attn_fwd(const void *Q, int n_q, const void *K, const void
         else FASTAR_ATTN(64, 2);
 #undef FASTAR_ATTN
     } else {
-        if (BQ > 128) return FASTAR_ERR_UNSUPPORTED;
+        if (BQ > 128 || BK > 64) return FASTAR_ERR_UNSUPPORTED;
         const dim3 grid(n_qb, H);
         if (d == 128)
             hipLaunchKernelGGL(attn_f32_kernel<128>, grid, dim3(128), 0, s, (const float *)Q, (const float *)K,

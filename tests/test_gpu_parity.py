@@ -935,3 +935,12 @@ def test_bad_arguments_are_rejected_on_the_host():
     for bad_scale in (0.0, -0.1, float("inf"), float("nan")):
         with pytest.raises(fa.FastarError, match="invalid"):
             fa.sparse_attn_fwd(Q, Q, Q, None, length, sel, nsel, 128, 64, bad_scale)
+    with pytest.raises(fa.FastarError, match="unsupported"):
+        fa.sparse_attn_fwd(Q, Q, Q, None, length, sel, nsel, 128, 48, 0.1)    # bf16: BK no power of two
+    with pytest.raises(fa.FastarError, match="unsupported"):
+        fa.sparse_attn_fwd(Q, Q, Q, None, length, sel, nsel, 96, 64, 0.1)     # bf16: BQ neither 64 nor 128
+    Qf = torch.zeros((1, 128, 128), dtype=torch.float32, device="cuda")
+    with pytest.raises(fa.FastarError, match="unsupported"):
+        fa.sparse_attn_fwd(Qf, Qf, Qf, None, length, sel, nsel, 128, 96, 0.1)  # fp32: BK beyond 64
+    with pytest.raises(fa.FastarError, match="unsupported"):
+        fa.sparse_attn_fwd(Qf, Qf, Qf, None, length, sel, nsel, 256, 64, 0.1)  # fp32: BQ beyond 128
