@@ -168,6 +168,9 @@ int ann_select_lsh(const uint32_t *qbits, int n_q, const uint32_t *kbits, const 
  *                              lists that fit LDS with P_new NULL; other calls ignore the flag).  The library still
  *                              keeps no state of its own: the state is the caller's buffer.
  * The cache struct and the codec struct are host structs; cache->len is updated on the device.
+ * Supported: d in {64,128}, r in {32,64}; C up to about 393 000 * min(16, 1024 / H) slots per head (the eviction
+ *            plan runs on that many workgroups per head and each keeps a bitmap of its share of the slots in LDS):
+ *            6 million for up to 64 heads; FASTAR_ERR_UNSUPPORTED otherwise.
  */
 int tempcache_compress(const fastar_cache *cache, const fastar_codec *codec, const void *K_new,
                        const void *V_new, const void *P_new, int n_new, const int32_t *cand, int n_cand,
@@ -197,6 +200,7 @@ int ann_select_self(const int8_t *qcode, int n_q, const int8_t *kcode, const int
  *   qcode [H,n_q,r], pcode [H,n_p,r];  sel [H,n_qb,n_sel], nsel [H,n_qb] out.
  * BQ is free (it need not be sparse_attn_fwd's block size): BQ = tokens per frame gives the per-frame selection
  * of Sec. 5.3, whose list the caller then shares among the query blocks of that frame's attention call.
+ * Supported: r in {32,64}; n_p <= 12288 (the scores of one query block over the prompt live in LDS).
  */
 int ann_select_cross(const int8_t *qcode, int n_q, const int8_t *pcode, int n_p, int H, int r, int BQ,
                      int n_sel, int32_t *sel, int32_t *nsel, void *ws, size_t ws_bytes, void *stream);
