@@ -142,3 +142,42 @@ def test_dense_limit_uncompressed_wan_cache():
     assert int(ref.len[0]) == 4 * c["T"]
     n_kb = (4 * c["T"] + c["BK"] - 1) // c["BK"]
     select_and_attend(c, fs, codec, dcodec, gpu, ref, heads, n_kb)
+
+
+def test_world_model_attention_on_a_full_cache():
+    # cfg5 at the size bench.py --workload cfg5 reaches once its cache is full: 40 heads x 230400 live slots (64 frames
+    # of 3600), 3600 queries, 360 of 3600 key blocks per query block; 29 x 40 = 1160 query blocks, so the kernel with
+    # one block per workgroup is the one launched, on K and V far beyond the memory-side cache.  The cache is synthetic
+    # (seeded normal keys and values, multiplicities 1..6, two heads not quite full); the oracle recomputes three heads
+    # and, of each, the first, a middle and the ragged last query block.
+    c = CONFIGS["cfg5"]
+    H, d, BQ, BK = c["H"], c["d"], c["BQ"], c["BK"]
+    n_q, C, n_sel = c["T"], 64 * c["T"], 360
+    assert (H, d, BQ, BK, n_q) == (40, 128, 128, 64, 3600)
+    g = torch.Generator(device="cuda").manual_seed(20260205)
+    Q = torch.randn((H, n_q, d), device="cuda", generator=g).to(torch.bfloat16)
+    K = torch.randn((H, C, d), device="cuda", generator=g).to(torch.bfloat16)
+    V = torch.randn((H, C, d), device="cuda", generator=g).to(torch.bfloat16)
+    cnt = torch.randint(1, 7, (H, C), device="cuda", generator=g, dtype=torch.int32)
+    lens = np.full(H, C, np.int32)
+    lens[17], lens[39] = C - 41, C - 64 * 100 - 1
+    n_qb, n_kb = (n_q + BQ - 1) // BQ, C // BK
+    rng = np.random.default_rng(5)
+    sel = np.empty((H, n_qb, n_sel), np.int32)
+    for h in range(H):
+        for b in range(n_qb):
+            sel[h, b] = np.sort(rng.choice(n_kb, n_sel, replace=False))   # the last blocks of heads 17, 39: partly / wholly dead
+    nsel = np.full((H, n_qb), n_sel, np.int32)
+    O, lse = fa.sparse_attn_fwd(Q, K, V, cnt, to_dev(lens), to_dev(sel), to_dev(nsel), BQ, BK, d ** -0.5)
+    torch.cuda.synchronize()
+    assert bool(torch.isfinite(O.float()).all())
+    for h in (0, 17, 39):
+        Kh, Vh, ch = to_host(K[h:h + 1]), to_host(V[h:h + 1]), to_host(cnt[h:h + 1])
+        for b in (0, 13, n_qb - 1):
+            q0, q1 = b * BQ, min((b + 1) * BQ, n_q)
+            O_r, lse_r = oracle.sparse_attn_fwd(to_host(Q[h:h + 1, q0:q1]), Kh, Vh, ch, lens[h:h + 1],
+                                                np.ascontiguousarray(sel[h:h + 1, b:b + 1]), nsel[h:h + 1, b:b + 1],
+                                                BQ, BK, d ** -0.5)
+            err = np.abs(storage_to_f64(to_host(O[h:h + 1, q0:q1])) - O_r).max()
+            assert err <= 2e-2, f"head {h} block {b}: max |O - O_ref| = {err}"
+            assert np.abs(to_host(lse[h:h + 1, q0:q1]).astype(np.float64) - lse_r).max() <= 2e-2
