@@ -181,3 +181,23 @@ def test_world_model_attention_on_a_full_cache():
             err = np.abs(storage_to_f64(to_host(O[h:h + 1, q0:q1])) - O_r).max()
             assert err <= 2e-2, f"head {h} block {b}: max |O - O_ref| = {err}"
             assert np.abs(to_host(lse[h:h + 1, q0:q1]).astype(np.float64) - lse_r).max() <= 2e-2
+
+
+def test_world_model_selection_on_a_full_cache():
+    # AnnSA at the same size: 40 heads x 230400 live codes in blocks of 64, 3600 queries in blocks of 128 with 4 summaries,
+    # 360 of 3600 blocks kept: the streaming scoring kernel and the top-k over rows of 3600 scores, as bench.py times
+    # them.  Seeded random codes; the oracle replays three heads (one not quite full, one with 100 dead blocks).
+    c = CONFIGS["cfg5"]
+    H, r, BQ, BK, n_rep = c["H"], c["r"], c["BQ"], c["BK"], c["n_rep"]
+    n_q, C, n_sel = c["T"], 64 * c["T"], 360
+    g = torch.Generator(device="cuda").manual_seed(20260206)
+    qc = torch.randint(-40, 41, (H, n_q, r), device="cuda", generator=g, dtype=torch.int8)
+    kc = torch.randint(-40, 41, (H, C, r), device="cuda", generator=g, dtype=torch.int8)
+    lens = np.full(H, C, np.int32)
+    lens[17], lens[39] = C - 41, C - 64 * 100 - 1
+    sel, nsel = fa.ann_select_self(qc, kc, to_dev(lens), BQ, n_rep, BK, n_sel)
+    torch.cuda.synchronize()
+    heads = [0, 17, 39]
+    sel_r, nsel_r = oracle.ann_select_self(to_host(qc[heads]), to_host(kc[heads]), lens[heads], BQ, n_rep, BK, n_sel)
+    assert np.array_equal(to_host(nsel)[heads], nsel_r)
+    assert np.array_equal(to_host(sel)[heads], sel_r)
