@@ -201,3 +201,56 @@ def test_world_model_selection_on_a_full_cache():
     sel_r, nsel_r = oracle.ann_select_self(to_host(qc[heads]), to_host(kc[heads]), lens[heads], BQ, n_rep, BK, n_sel)
     assert np.array_equal(to_host(nsel)[heads], nsel_r)
     assert np.array_equal(to_host(sel)[heads], sel_r)
+
+
+def test_world_model_compress_on_a_full_cache():
+    # TempCache at the same size: one frame of 40 x 3600 tokens against a full cache of 230400 slots per head with a
+    # candidate window of 3600 slots (staged in LDS, as in bench.py --workload cfg5): a third of the tokens repeat live
+    # slots and merge, the rest need a slot each, so a full head evicts 2400 of its oldest untouched slots (63 stamp
+    # values over 230400 slots: long runs of ties).  Synthetic seeded cache; the oracle replays three heads, whose codes are
+    # its own encoding of their keys (the other heads carry random codes: their tokens match nothing and are all appended).
+    c = CONFIGS["cfg5"]
+    H, d, r, T = c["H"], c["d"], c["r"], c["T"]
+    C = 64 * T
+    codec = make_codec(c["seed"], c["cfg_id"], d, r)
+    g = torch.Generator(device="cuda").manual_seed(20260207)
+    gpu = fa.Cache.empty(H, C, d, r, torch.bfloat16)
+    gpu.K.copy_(torch.randn((H, C, d), device="cuda", generator=g))
+    gpu.V.copy_(torch.randn((H, C, d), device="cuda", generator=g))
+    gpu.code.copy_(torch.randint(-40, 41, (H, C, r), device="cuda", generator=g, dtype=torch.int8))
+    gpu.cnt.copy_(torch.randint(1, 4, (H, C), device="cuda", generator=g, dtype=torch.int32))
+    gpu.stamp.copy_(torch.randint(0, 63, (H, C), device="cuda", generator=g, dtype=torch.int32))
+    lens = np.full(H, C, np.int32)
+    lens[17], lens[39] = C - 41, C - 1001                     # 2400 / 2359 / 1399 evictions
+    gpu.len.copy_(to_dev(lens))
+    heads = [0, 17, 39]
+    K_h = to_host(gpu.K[heads])
+    code_h = oracle.encode(K_h, codec.R, codec.qscale, codec.shift)
+    gpu.code[heads] = to_dev(code_h)
+    ref = oracle.Cache(K=K_h, V=to_host(gpu.V[heads]), code=code_h, cnt=to_host(gpu.cnt[heads]),
+                       stamp=to_host(gpu.stamp[heads]), len=lens[heads].copy())
+    n_dup = T // 3
+    idx = torch.randint(0, C - 7000, (H, n_dup), device="cuda", generator=g)       # live in every head
+    K_new = torch.randn((H, T, d), device="cuda", generator=g).to(torch.bfloat16)
+    K_new[:, :n_dup] = torch.gather(gpu.K, 1, idx.unsqueeze(-1).expand(-1, -1, d))
+    V_new = torch.randn((H, T, d), device="cuda", generator=g).to(torch.bfloat16)
+    cand = torch.randint(0, C, (H, T), device="cuda", generator=g, dtype=torch.int32)   # some past the live length
+    cand[:, :n_dup] = idx.to(torch.int32)
+    K_new_h, V_new_h, cand_h = to_host(K_new[heads]), to_host(V_new[heads]), to_host(cand[heads])
+    mm_g, mg_g, st_g = fa.tempcache_compress(gpu, dev_codec(codec), K_new, V_new, cand=cand, tau2_q16=TAU2(0.98), frame_id=64)
+    torch.cuda.synchronize()
+    mm_r, mg_r, st_r = oracle.tempcache_compress(ref, codec.R, codec.qscale, codec.shift, K_new_h, V_new_h, cand=cand_h,
+                                                 tau2_q16=TAU2(0.98), frame_id=64)
+    assert mg_r[:, :n_dup].all() and (st_r[:, 3] > 1000).all() and (st_r[:, 7] == 0).all()   # merges and evictions
+    assert np.array_equal(to_host(st_g)[heads], st_r)
+    assert np.array_equal(to_host(mg_g)[heads], mg_r)
+    assert np.array_equal(to_host(mm_g)[heads], mm_r)
+    assert np.array_equal(to_host(gpu.len)[heads], ref.len)
+    for i, h in enumerate(heads):
+        L = int(ref.len[i])
+        assert np.array_equal(to_host(gpu.K[h, :L]), ref.K[i, :L]), f"K head {h}"
+        assert np.array_equal(to_host(gpu.code[h, :L]), ref.code[i, :L]), f"code head {h}"
+        assert np.array_equal(to_host(gpu.cnt[h, :L]), ref.cnt[i, :L]), f"cnt head {h}"
+        assert np.array_equal(to_host(gpu.stamp[h, :L]), ref.stamp[i, :L]), f"stamp head {h}"
+        dv = np.abs(storage_to_f64(to_host(gpu.V[h, :L])) - storage_to_f64(ref.V[i, :L])).max()
+        assert dv <= 5e-2, f"running-mean values, head {h}: {dv}"
