@@ -1,8 +1,15 @@
 /*
  * CPU oracle for the FAST-AR attention hot path.  TEST INFRASTRUCTURE ONLY.
  *
- * Plain, slow, step-by-step C.  fp64 accumulation for every floating-point result,
- * integer arithmetic for every decision.  Nothing here is shared with the GPU
+ * Plain, slow, step-by-step C.  fp64 accumulation for every floating-point result that is compared
+ * with a tolerance (attention outputs, lse, the running mean value), integer arithmetic for every
+ * decision.  One exception, by definition and not by accumulation error: the mean-key representative
+ * (rep_mode 1).  A stored mean key is re-quantised and re-encoded, so its bits decide later integers
+ * (codes, matches, the cosine test); its arithmetic is therefore part of the definition: IEEE float32,
+ * multiplicity * old key first, then the joiners' keys in ascending token order, one division, one
+ * rounding to the storage type.  tests/test_oracle_tempcache.py pins that order with values on which a
+ * float64 accumulation, or another order of the additions, gives different stored bits.
+ * Nothing here is shared with the GPU
  * library: no common header, helper, table or constant.  Only tests, the smoke
  * check and the bench's cpu_baseline leg may call it.
  *
@@ -123,8 +130,10 @@ static int64_t dot_i8(const int8_t *a, const int8_t *b, int r) {
  *
  * cache:   K, V [H,C,d] dtype; code [H,C,r]; cnt, stamp [H,C]; len [H]   (updated in place)
  * new:     K_new, V_new [H,n_new,d]; P_new (probe, NULL => K_new) [H,n_new,d]
- * cand:    [H,n_cand] slot ids searched for the match in this order (ids outside [0,len) are ignored; of
- *          equally scored candidates the first listed wins), NULL => all live slots in ascending order
+ * cand:    [H,n_cand] slot ids that form the candidate SET of the match (ids outside [0,len) are ignored, the
+ *          order of the list and repeated ids mean nothing), NULL => all live slots.  Of equally scored
+ *          candidates the smallest slot wins (Sec. 5.2 names no order among ties; every tie here goes to the
+ *          lowest index).
  * metric:  0 => S = 2 cp.code_j - |code_j|^2 (nearest in code space), 1 => S = cp.code_j
  * tau2_q16 = rint(tau^2 * 65536); merge iff dot > 0 and dot^2 * 65536 >= tau2_q16 * |a|^2 |b|^2 on the
  *          8-bit quantised full-width keys a (new) and b (cached)
@@ -155,12 +164,13 @@ int oracle_tempcache_compress(void *K, void *V, int8_t *code, int32_t *cnt, int3
         const int64_t nb = (int64_t)h * n_new; /* first new token of this head */
         int8_t *cp = malloc((size_t)(n_new > 0 ? n_new : 1) * r);
         int8_t *ck = malloc((size_t)(n_new > 0 ? n_new : 1) * r);
+        uint8_t *is_cand = calloc((size_t)(L > 0 ? L : 1), 1);
         int32_t *jstar = malloc(sizeof(int32_t) * (size_t)(n_new > 0 ? n_new : 1));
         int64_t *sstar = malloc(sizeof(int64_t) * (size_t)(n_new > 0 ? n_new : 1));
         int32_t *group = calloc((size_t)(L > 0 ? L : 1), sizeof(int32_t));  /* |M_j| */
         int32_t *winner = malloc(sizeof(int32_t) * (size_t)(L > 0 ? L : 1));
         uint8_t *victim = calloc((size_t)(L > 0 ? L : 1), 1);
-        if (!cp || !ck || !jstar || !sstar || !group || !winner || !victim) {
+        if (!cp || !ck || !is_cand || !jstar || !sstar || !group || !winner || !victim) {
 #pragma omp atomic write
             err = -5;
             goto done;
@@ -170,15 +180,21 @@ int oracle_tempcache_compress(void *K, void *V, int8_t *code, int32_t *cnt, int3
             encode_vec(P_new, dtype, (nb + i) * d, d, R, r, qscale, shift, cp + (int64_t)i * r);
             encode_vec(K_new, dtype, (nb + i) * d, d, R, r, qscale, shift, ck + (int64_t)i * r);
         }
-        /* step 2: top-1 match over the candidates in list order; the strict '>' keeps the first of equally scored
-         * candidates: the earliest entry of the list, or the smallest slot when every live slot is searched */
-        const int n_list = cand ? n_cand : L;
+        /* step 2: candidate set, then the top-1 match over it in ascending slot order: the strict '>' keeps the
+         * smallest slot among equally scored candidates */
+        if (cand) {
+            for (int c = 0; c < n_cand; ++c) {
+                const int32_t j = cand[(int64_t)h * n_cand + c];
+                if (j >= 0 && j < L) is_cand[j] = 1;
+            }
+        } else {
+            for (int j = 0; j < L; ++j) is_cand[j] = 1;
+        }
         for (int i = 0; i < n_new; ++i) {
             jstar[i] = -1;
             sstar[i] = 0;
-            for (int c = 0; c < n_list; ++c) {
-                const int j = cand ? cand[(int64_t)h * n_cand + c] : c;
-                if (j < 0 || j >= L) continue;
+            for (int j = 0; j < L; ++j) {
+                if (!is_cand[j]) continue;
                 const int8_t *cj = code + (cb + j) * r;
                 int64_t S = dot_i8(cp + (int64_t)i * r, cj, r);
                 if (metric == 0) S = 2 * S - dot_i8(cj, cj, r);
@@ -321,6 +337,7 @@ int oracle_tempcache_compress(void *K, void *V, int8_t *code, int32_t *cnt, int3
     done:
         free(cp);
         free(ck);
+        free(is_cand);
         free(jstar);
         free(sstar);
         free(group);

@@ -256,9 +256,9 @@ def test_mean_key_stays_inside_the_hull_of_its_group_and_its_code_is_the_code_of
     assert cache.cnt[:, :T].max() == 5
 
 
-def test_equally_scored_candidates_the_first_listed_wins():
-    # two cache slots hold the same key (same code, same score for any probe): the match goes to whichever the
-    # candidate list names first; without a list the slots are searched in ascending order
+def test_equally_scored_candidates_the_smallest_slot_wins():
+    # slots 1, 3 and 4 hold the same key (same code, same score for any probe): the match goes to the smallest of them
+    # that the candidate list names, whatever the order of the list and however often it repeats an id
     d, r = 8, 4
     R = np.array([[1, 1, 1, 1], [1, -1, 1, -1], [1, 1, -1, -1], [1, -1, -1, 1]] * 2, np.int8)
     qscale, shift = 16.0, 1
@@ -266,13 +266,86 @@ def test_equally_scored_candidates_the_first_listed_wins():
     other = np.array([-3.0, 0.1, 2.5, -1.0, 0.2, 0.3, -2.2, 1.7], np.float32)
     K0 = np.stack([other, base, -other, base, base])[None]
     V0 = np.zeros_like(K0)
-    for cand, expect in ((None, 1), ([[4, 1, 3]], 4), ([[0, 3, 3, 1, 4]], 3), ([[2, 7, -1, 1]], 1), ([[9, 4, 4]], 4)):
+    for cand, expect in ((None, 1), ([[4, 1, 3]], 1), ([[4, 3]], 3), ([[0, 3, 3, 1, 4]], 1), ([[2, 7, -1, 4, 3]], 3),
+                         ([[9, 4, 4]], 4), ([[4, 4, 0, 3, 3, 2]], 3)):
         cache = oracle.Cache.empty(1, 8, d, r, "fp32")
         oracle.tempcache_compress(cache, R, qscale, shift, K0, V0, tau2_q16=NEVER, frame_id=0)
         mm, mg, _ = oracle.tempcache_compress(cache, R, qscale, shift, base[None, None], V0[:, :1],
                                               cand=None if cand is None else np.array(cand, np.int32),
                                               tau2_q16=TAU2(0.9), frame_id=1)
         assert mg[0, 0] == 1 and mm[0, 0] == expect, (cand, mm)
+
+
+def test_match_over_shuffled_and_repeated_candidate_lists_is_the_brute_force_over_the_set():
+    # a cache in which many keys occur twice (ties at the top are the rule), candidate lists in random order with
+    # repeated, negative and dead ids: the match is the arg-max over the SET of valid ids, smallest slot among equals
+    c, fs, codec = stream_cfg1()
+    H, T, d = c["H"], c["T"], c["d"]
+    rng = np.random.default_rng(7)
+    K0, V0 = fs.next_frame()
+    K0[:, T // 2:] = K0[:, :T // 2][:, rng.permutation(T // 2)]          # second half repeats the first, permuted
+    K1, V1 = fs.next_frame()
+    K1[:, ::3] = K0[:, :T:3]                                             # a third of the new tokens are exact copies
+    for metric in (0, 1):
+        for trial in range(4):
+            cache = oracle.Cache.empty(H, 3 * T, d, c["r"], "fp32")
+            compress(cache, codec, K0, V0, tau2_q16=NEVER, frame_id=0)
+            n_cand = [T // 4, T, 2 * T, 5][trial]
+            cand = rng.integers(-2, T + 3, size=(H, n_cand)).astype(np.int32)
+            cand[:, n_cand // 2:] = cand[:, :n_cand - n_cand // 2]            # every id at least twice, far apart
+            cand = np.stack([row[rng.permutation(n_cand)] for row in cand])
+            old_code = cache.code.copy().astype(np.int64)
+            mm, mg, _ = compress(cache, codec, K1, V1, cand=cand, tau2_q16=ALWAYS, metric=metric, frame_id=1)
+            cp = oracle.encode(K1, codec.R, codec.qscale, codec.shift).astype(np.int64)
+            n_ties = 0
+            for h in range(H):
+                ids = np.unique(cand[h][(cand[h] >= 0) & (cand[h] < T)])     # ascending set of valid ids
+                for i in range(T):
+                    S = old_code[h, ids] @ cp[h, i]
+                    if metric == 0:
+                        S = 2 * S - (old_code[h, ids] ** 2).sum(axis=1)
+                    n_ties += int((S == S.max()).sum() > 1)
+                    if mg[h, i]:
+                        assert mm[h, i] == ids[int(np.argmax(S))], (metric, trial, h, i)   # first maximum = smallest id
+            assert trial == 3 or n_ties >= 16               # the case does exercise ties
+            assert mg.mean() > 0.5
+
+
+def test_mean_key_arithmetic_is_float32_in_token_order():
+    # the stored mean key decides later integers, so its arithmetic is part of the definition: float32,
+    # multiplicity * old key, joiners added in ascending token order, one division.  Values that float32 cannot
+    # represent exactly: on some coordinates a float64 accumulation (rounded once at the end) and the reverse order of
+    # the additions give other bits, and the oracle must show exactly the defined ones.
+    d, r = 8, 4
+    R = np.array([[1, 1, 1, 1], [1, -1, 1, -1], [1, 1, -1, -1], [1, -1, -1, 1]] * 2, np.int8)
+    qscale, shift = 16.0, 1
+    rng = np.random.default_rng(11)
+    far = np.array([-3.0, 0.1, 2.5, -1.0, 0.2, 0.3, -2.2, 1.7], np.float32)
+    differs64 = differs_rev = 0
+    for trial in range(40):
+        base = (rng.standard_normal(d) * 1.7 + 0.3).astype(np.float32)
+        joiners = (base[None] + 0.01 * rng.standard_normal((3, d))).astype(np.float32)
+        cache = oracle.Cache.empty(1, 8, d, r, "fp32")
+        K0 = np.stack([base, -base])[None]
+        V0 = np.zeros_like(K0)
+        oracle.tempcache_compress(cache, R, qscale, shift, K0, V0, tau2_q16=NEVER, frame_id=0, rep_mode=1)
+        cache.cnt[0, 0] = 3                                              # as if three keys had merged before
+        mm, mg, _ = oracle.tempcache_compress(cache, R, qscale, shift, joiners[None], np.zeros((1, 3, d), np.float32),
+                                              tau2_q16=TAU2(0.9), frame_id=1, rep_mode=1)
+        assert mg[0].tolist() == [1, 1, 1] and mm[0].tolist() == [0, 0, 0]
+        acc = np.float32(3.0) * base                                      # float32 throughout
+        for k in joiners:
+            acc = (acc + k).astype(np.float32)
+        want = (acc / np.float32(6.0)).astype(np.float32)
+        assert np.array_equal(cache.K[0, 0], want), trial
+        f64 = ((3.0 * base.astype(np.float64) + joiners.astype(np.float64).sum(axis=0)) / 6.0).astype(np.float32)
+        rev = np.float32(3.0) * base
+        for k in joiners[::-1]:
+            rev = (rev + k).astype(np.float32)
+        rev = (rev / np.float32(6.0)).astype(np.float32)
+        differs64 += int(not np.array_equal(want, f64))
+        differs_rev += int(not np.array_equal(want, rev))
+    assert differs64 >= 5 and differs_rev >= 5        # the pin can tell the definitions apart
 
 
 def test_decisions_use_the_cache_as_it_was_at_entry():
