@@ -12,10 +12,16 @@
  * Conventions (all entry points):
  *   - Every pointer is a DEVICE pointer unless it points to one of the small structs below, which
  *     are read on the host at call time.  The caller owns every buffer; the library allocates
- *     nothing, keeps no state and never synchronises with the host.
+ *     nothing and never synchronises with the host.  It keeps no state that a result depends on: the
+ *     only process-wide data are per-device marks that the one-time kernel set-up has been done
+ *     (fastar_init, or lazily and thread-safely by the first call that needs it).
  *   - `stream` is a hipStream_t passed as void*.  Work is enqueued on it and the call returns.
- *   - Tensors are dense row-major: [H, N, d] means element (h, n, t) at (h*N + n)*d + t.  The
- *     batch dimension is folded into H.  Rows of Q/K/V/O must be 16-byte aligned.
+ *   - Tensors are DENSE row-major: [H, N, d] means element (h, n, t) at (h*N + n)*d + t; there are no
+ *     stride arguments.  The key/value tiles of the attention kernels are fetched straight into LDS
+ *     from one base address per tile with fixed row pitch d * sizeof(element), and the cache arrays
+ *     K, V, code, cnt, stamp are indexed by one slot number; a strided view would put an address
+ *     computation per row back into those loops.  A caller that holds a strided view passes a
+ *     contiguous copy.  The batch dimension is folded into H.  Rows of Q/K/V/O must be 16-byte aligned.
  *   - dtype: FASTAR_F32 (float) or FASTAR_BF16 (bfloat16).  Q, K, V, O of one call share it.
  *   - Return value: FASTAR_OK, or a negative code found on the host before anything is launched
  *     (INVALID_ARG: null / negative / inconsistent argument; UNSUPPORTED: a shape the kernels are
@@ -82,6 +88,13 @@ typedef struct {
     int32_t shift;   /* >= 1 */
 } fastar_codec;
 
+/*
+ * One-time set-up for the CURRENT device: lets the kernels that stage large tiles use more than 64 KB of LDS.
+ * Optional: every entry point does the part it needs on its first call on a device (thread-safe).  Call it before
+ * capturing entry points into a HIP graph, so that no attribute call falls inside the capture.  Launches nothing.
+ */
+int fastar_init(void);
+
 /* Library version string (host pointer, static storage). */
 const char *fastar_version(void);
 
@@ -133,9 +146,9 @@ int ann_select_lsh(const uint32_t *qbits, int n_q, const uint32_t *kbits, const 
  * TempCache (Sec. 5.2 and Lemma 1): merge one frame of n_new tokens per head into the cache.  Every
  * decision is taken against the cache as it is at entry; a chunk of several frames is several calls.
  *   1. probe code cp_i = code(P_new[i]) (P_new NULL => K_new), key code ck_i = code(K_new[i]).
- *   2. top-1 match among the candidate slots (cand [H,n_cand] slot ids, ids outside [0,len) are
- *      skipped; cand NULL => every live slot): j*(i) = argmax_j S(i,j), ties to the candidate listed
- *      first (cand NULL: to the smallest slot),
+ *   2. top-1 match among the candidate slots (cand [H,n_cand] names a SET of slot ids: its order and
+ *      repeated ids mean nothing, ids outside [0,len) are skipped; cand NULL => every live slot):
+ *      j*(i) = argmax_j S(i,j), ties to the smallest slot,
  *      S = 2 cp_i.code_j - |code_j|^2 (metric 0, nearest in code space) or cp_i.code_j (metric 1).
  *   3. similarity threshold on the 8-bit quantised full-width keys a = xq(K_new[i]), b = xq(K[j*]):
  *      merged_i <=> a.b > 0 and (a.b)^2 * 65536 >= tau2_q16 * |a|^2 |b|^2, with
@@ -229,23 +242,12 @@ int ann_cross_attn_fwd(const void *Q, const int8_t *qcode, int n_q, const void *
  *   O [H,n_q,d] dtype out;  lse [H,n_q] float out or NULL.
  * Supported: bf16 with d in {64,128}, BQ in {64,128}, BK a power of two <= 64 (MFMA path, fp32
  * softmax and accumulation); fp32 with d in {64,128}, BQ <= 128, BK <= 64 (plain fp32 arithmetic).
- * scale must be positive and finite (FASTAR_ERR_INVALID_ARG otherwise).
+ * scale must be positive and finite (FASTAR_ERR_INVALID_ARG otherwise).  bf16: tile rows are addressed by 32-bit
+ * byte offsets inside a head, so C * d * 2 must stay below 2^32 (FASTAR_ERR_UNSUPPORTED otherwise).
  */
 int sparse_attn_fwd(const void *Q, int n_q, const void *K, const void *V, const int32_t *cnt,
                     const int32_t *len, int H, int C, int d, int dtype, const int32_t *sel, const int32_t *nsel,
                     int BQ, int BK, int n_sel, float scale, void *O, float *lse, void *stream);
-
-/*
- * Measurement probes (not part of the method): what this chip reaches on the two rooflines the kernels
- * are priced against, measured in the same process as the benchmark.
- *   fastar_probe_mfma_bf16  register-resident bf16 32x32x16 matrix-instruction loop on every SIMD;
- *                           *flops_out (host) receives the floating-point operations one launch performs;
- *                           sink is a device float the kernel may write (never does in practice).
- *   fastar_probe_copy       plain streaming copy of `bytes` (multiple of 16) from src to dst (device, 16-byte aligned).
- * Both enqueue one kernel on `stream`; the caller times them.
- */
-int fastar_probe_mfma_bf16(int iters, float *sink, double *flops_out, void *stream);
-int fastar_probe_copy(const void *src, void *dst, size_t bytes, void *stream);
 
 #ifdef __cplusplus
 }

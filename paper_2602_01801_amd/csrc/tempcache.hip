@@ -57,9 +57,10 @@ size_t compress_ws_bytes(int H, int C, int n_new, int r) {
 }
 
 // Running arg-max of one lane over the 16 scores a 32x32 matrix instruction leaves it (rows 8(v/4) + 4(lane/32) + v%4
-// of a group of 32 candidates), with "first candidate in list order" among equal scores at no extra cost: a score
-// word carries its position among the 16 in its low four bits (one shift-add per score), so plain maxima pick
-// (highest score, then earliest row), and a later group only replaces the best on a strictly higher score.
+// of a group of 32 candidates), with "earliest position" among equal scores at no extra cost: a score word carries
+// its position among the 16 in its low four bits (one shift-add per score), so plain maxima pick (highest score, then
+// earliest row), and a later group only replaces the best on a strictly higher score.  Callers present the
+// candidates in ascending slot order without repeats, which makes this the smallest-slot rule of the match.
 // Scores lie within +-2^21, missing candidates carry MATCH_NONE: both survive the shift by four.
 constexpr int MATCH_NONE = -(1 << 26);       // score word of a missing candidate (minus its "penalty")
 constexpr int MATCH_VALID = -(1 << 25);      // every real score is above, every missing one below
@@ -94,7 +95,10 @@ struct LaneBest {
 // (score, lowest slot) as one 64-bit key: (score + bias) << 32 | ~slot.
 // CAND_CHUNK = candidate positions scanned by one workgroup: 64 for a windowed candidate list (more, lighter
 // workgroups hide the two dependent loads better), 256 for a scan of the whole cache (fewer atomics per token).
-template <int R, int CAND_CHUNK>
+// Ties go to the smallest slot.  A scan of the whole cache (LIST false) visits the slots in ascending order, so the
+// cheap "earliest position" arg-max of LaneBest is that rule.  A candidate list too long for the LDS window (LIST)
+// comes in any order and may repeat ids: there every score is compared as the full (score, smallest slot) key.
+template <int R, int CAND_CHUNK, bool LIST>
 __global__ __launch_bounds__(256) void tc_match_kernel(const int8_t *__restrict__ code, const int32_t *__restrict__ len,
                                                        int C, const int8_t *__restrict__ cp, int n_new,
                                                        const int32_t *__restrict__ cand, int n_cand, int metric,
@@ -102,9 +106,10 @@ __global__ __launch_bounds__(256) void tc_match_kernel(const int8_t *__restrict_
     constexpr int KS = R / 32;
     constexpr int NIT = CAND_CHUNK / 32;  // groups of 32 candidates per workgroup
     __shared__ __attribute__((aligned(16))) int cpen[4][CAND_CHUNK];   // minus the score penalty: -|code|^2 (metric 0), 0 (metric 1); MATCH_NONE: no candidate
+    __shared__ __attribute__((aligned(16))) int cslotw[LIST ? 4 : 1][LIST ? CAND_CHUNK : 4];   // slot of every row (LIST)
     const int h = blockIdx.z;
     const int L = min(len[h], C);
-    const int n_pos = cand ? n_cand : L;
+    const int n_pos = LIST ? n_cand : L;
     const int pos0 = blockIdx.y * CAND_CHUNK;
     if (pos0 >= n_pos) return;  // uniform
     const int pos1 = min(pos0 + CAND_CHUNK, n_pos);
@@ -127,7 +132,7 @@ __global__ __launch_bounds__(256) void tc_match_kernel(const int8_t *__restrict_
         const int pos = pos0 + it * 32 + col;
         int sl = -1;
         if (pos < pos1) {
-            sl = cand ? cand[(size_t)h * n_cand + pos] : pos;
+            sl = LIST ? cand[(size_t)h * n_cand + pos] : pos;
             if (sl < 0 || sl >= L) sl = -1;
         }
         slot[it] = sl;
@@ -149,10 +154,14 @@ __global__ __launch_bounds__(256) void tc_match_kernel(const int8_t *__restrict_
 #pragma unroll
             for (int m = 0; m < 4; ++m) nn = dot4_i8((unsigned)afrag[it][ks][m], (unsigned)afrag[it][ks][m], nn);
         nn += shfl_xor(nn, 32);
-        if (g2 == 0) cpen[wave][it * 32 + col] = slot[it] >= 0 ? (metric == 0 ? -nn : 0) : MATCH_NONE;
+        if (g2 == 0) {
+            cpen[wave][it * 32 + col] = slot[it] >= 0 ? (metric == 0 ? -nn : 0) : MATCH_NONE;
+            if (LIST) cslotw[wave][it * 32 + col] = slot[it];
+        }
     }
     __syncthreads();  // every wavefront reads back only its own rows; the barrier orders write and read
     LaneBest lb;
+    u64 mybest = 0;
 #pragma unroll
     for (int it = 0; it < NIT; ++it) {
         if (pos0 + it * 32 >= pos1) break;  // uniform
@@ -171,9 +180,21 @@ __global__ __launch_bounds__(256) void tc_match_kernel(const int8_t *__restrict_
 #pragma unroll
             for (int ks = 0; ks < KS; ++ks) acc = mfma_i8_32x32x32(afrag[it][ks], bfrag[ks], acc);
         }
-        lb.take(acc, it);
+        if (LIST) {
+#pragma unroll
+            for (int q4 = 0; q4 < 4; ++q4) {
+                const i32x4 sl4 = *(const i32x4 *)(&cslotw[wave][it * 32 + 8 * q4 + 4 * g2]);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const u64 key = ((u64)(unsigned)(acc[4 * q4 + e] + SCORE_BIAS) << 32) | (u64)(0xFFFFFFFFu - (unsigned)sl4[e]);
+                    if (sl4[e] >= 0 && key > mybest) mybest = key;
+                }
+            }
+        } else {
+            lb.take(acc, it);
+        }
     }
-    u64 mybest = lb.key(g2, pos0);
+    if (!LIST) mybest = lb.key(g2, pos0);   // position = slot
     {
         const unsigned lo = shfl_xor((unsigned)mybest, 32), hi = shfl_xor((unsigned)(mybest >> 32), 32);
         const u64 other = ((u64)hi << 32) | lo;
@@ -258,20 +279,133 @@ __global__ __launch_bounds__(WIN_THREADS) void tc_match_window_kernel(const int8
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) bfrag[ks] = *(const i32x4 *)(cp + ((size_t)h * n_new + trow) * R + ks * 32 + 16 * g2);
     }
-    // Staging in batches of independent loads: the slot ids of a whole batch, then the code rows they name,
-    // so a batch costs two memory round trips however many candidates it holds.
+    // The candidate list is a SET of slots and ties go to the smallest slot, so the window is staged in ascending
+    // slot order without repeats: position order then is slot order, which is all the arg-max below needs.
+    //   1. every thread reads its entries of the list (ids outside [0, L) do not count) and whether the list already
+    //      ascends (then it is staged as it stands: equal neighbours are the same slot and change nothing);
+    //   2. otherwise the ids are sorted through a bitmap over the slot range they span, held where the codes will go
+    //      (several passes when the range is wider than that area): set bits, count per wavefront, expand in order;
+    //   3. the code rows of the sorted slots are gathered (one round of loads per batch, as before).
+    constexpr int CPT = 8;          // list entries per thread: the window holds at most 148 KB / (R + 8) < 3840 ids
+    constexpr int NOID = INT_MAX;   // key of an id that does not count
+    __shared__ int s_flag, s_min, s_max, s_wtot[WIN_THREADS / 64];
+    int ce[CPT];
+    {
+        bool descends = false;
+        int vmin = NOID, vmax = -1;
+        const int32_t *ch_cand = cand + (size_t)h * n_cand;
+#pragma unroll
+        for (int k = 0; k < CPT; ++k) {
+            const int p = k * WIN_THREADS + tid;
+            int v = NOID, before = -1;
+            if (p < n_cand) {
+                const int x = ch_cand[p];
+                if (x >= 0 && x < L) v = x;
+                if (p > 0) {
+                    const int y = ch_cand[p - 1];
+                    before = (y >= 0 && y < L) ? y : NOID;
+                }
+            }
+            ce[k] = v;
+            descends |= before > v;
+            if (v != NOID) {
+                vmin = min(vmin, v);
+                vmax = max(vmax, v);
+            }
+        }
+        if (tid == 0) {
+            s_flag = 0;
+            s_min = NOID;
+            s_max = -1;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) {
+            vmin = min(vmin, shfl_xor(vmin, off));
+            vmax = max(vmax, shfl_xor(vmax, off));
+        }
+        const bool any_desc = __any(descends);
+        if (lane == 0) {
+            if (any_desc) atomicOr(&s_flag, 1);
+            if (vmax >= 0) {
+                atomicMin(&s_min, vmin);
+                atomicMax(&s_max, vmax);
+            }
+        }
+        __syncthreads();
+    }
+    int n_u;   // staged candidates (positions 0 .. n_u-1 of cslot; uniform over the workgroup)
+    if (s_flag == 0) {
+#pragma unroll
+        for (int k = 0; k < CPT; ++k) {
+            const int p = k * WIN_THREADS + tid;
+            if (p < n_pad) cslot[p] = ce[k] == NOID ? -1 : ce[k];
+        }
+        n_u = n_cand;
+        __syncthreads();
+    } else {
+        unsigned *bm = (unsigned *)wlds;                    // the code area: R * n_pad bytes
+        const int bm_bits = 8 * R * n_pad;
+        const int lo0 = s_min & ~31, hi = s_max + 1;
+        int base = 0;
+        for (int lo = lo0; lo < hi; lo += bm_bits) {       // uniform
+            const int nbits = min(hi - lo, bm_bits);
+            const int nw = (nbits + 31) >> 5;
+            for (int w = tid; w < nw; w += WIN_THREADS) bm[w] = 0u;
+            __syncthreads();
+#pragma unroll
+            for (int k = 0; k < CPT; ++k) {
+                const int v = ce[k];
+                if (v != NOID && v >= lo && v - lo < nbits) atomicOr(&bm[(v - lo) >> 5], 1u << ((v - lo) & 31));
+            }
+            __syncthreads();
+            // a wavefront owns a contiguous run of words, its lanes take them 64 at a time
+            const int wpw = (nw + WIN_THREADS / 64 - 1) / (WIN_THREADS / 64);
+            const int w0 = min(wave * wpw, nw), w1 = min(w0 + wpw, nw);
+            int c = 0;
+            for (int w = w0 + lane; w < w1; w += 64) c += __popc(bm[w]);
+#pragma unroll
+            for (int off = 32; off >= 1; off >>= 1) c += shfl_xor(c, off);
+            if (lane == 0) s_wtot[wave] = c;
+            __syncthreads();
+            int pos = base, tot = 0;
+#pragma unroll
+            for (int ww = 0; ww < WIN_THREADS / 64; ++ww) {
+                const int t = s_wtot[ww];
+                if (ww < wave) pos += t;
+                tot += t;
+            }
+            for (int wb = w0; wb < w1; wb += 64) {         // uniform over the wavefront
+                const int w = wb + lane;
+                unsigned bits = w < w1 ? bm[w] : 0u;
+                const int mine = __popc(bits);
+                int incl = mine;
+#pragma unroll
+                for (int off = 1; off < 64; off <<= 1) {
+                    const int o = __shfl_up(incl, off, WAVE);
+                    if (lane >= off) incl += o;
+                }
+                int q = pos + incl - mine;
+                while (bits) {
+                    cslot[q++] = lo + 32 * w + (__ffs(bits) - 1);
+                    bits &= bits - 1;
+                }
+                pos += __shfl(incl, 63, WAVE);
+            }
+            base += tot;
+            __syncthreads();   // the bitmap may be cleared again; cslot is complete after the last pass
+        }
+        n_u = base;
+    }
+    const int n_stage = (n_u + 31) & ~31;   // <= n_pad
+    // Code rows in batches of independent loads, so a batch costs one memory round trip however many rows it holds.
     constexpr int BATCH = 128 / R;  // candidates per thread and batch (32 code registers)
-    for (int p0 = 0; p0 < n_pad; p0 += WIN_THREADS * BATCH) {
+    for (int p0 = 0; p0 < n_stage; p0 += WIN_THREADS * BATCH) {
         int sl[BATCH];
 #pragma unroll
         for (int u = 0; u < BATCH; ++u) {
             const int p = p0 + u * WIN_THREADS + tid;
-            int v = -1;
-            if (p < n_cand) {
-                v = cand[(size_t)h * n_cand + p];
-                if (v < 0 || v >= L) v = -1;
-            }
-            sl[u] = v;
+            sl[u] = p < n_u ? cslot[p] : -1;
         }
         i32x4 row[BATCH][NCH];
 #pragma unroll
@@ -285,7 +419,7 @@ __global__ __launch_bounds__(WIN_THREADS) void tc_match_window_kernel(const int8
 #pragma unroll
         for (int u = 0; u < BATCH; ++u) {
             const int p = p0 + u * WIN_THREADS + tid;
-            if (p < n_pad) {
+            if (p < n_stage) {
                 int nn = 0;
 #pragma unroll
                 for (int c = 0; c < NCH; ++c) {
@@ -293,7 +427,7 @@ __global__ __launch_bounds__(WIN_THREADS) void tc_match_window_kernel(const int8
 #pragma unroll
                     for (int m = 0; m < 4; ++m) nn = dot4_i8((unsigned)row[u][c][m], (unsigned)row[u][c][m], nn);
                 }
-                cslot[p] = sl[u];
+                if (p >= n_u) cslot[p] = -1;
                 cpen[p] = sl[u] >= 0 ? (metric == 0 ? -nn : 0) : MATCH_NONE;  // minus the penalty
             }
         }
@@ -312,7 +446,7 @@ __global__ __launch_bounds__(WIN_THREADS) void tc_match_window_kernel(const int8
         for (int ks = 0; ks < KS; ++ks) bfrag[ks] = *(const i32x4 *)(pcode + (tg * 32 + col) * R + ks * 32 + 16 * g2);
     }
     LaneBest lb;
-    const int n_groups = n_pad / 32;
+    const int n_groups = n_stage / 32;
     // Four groups of 32 candidates per step, their operand reads and matrix instructions issued together
     // (a group repeated at the ragged end changes nothing: only a strictly higher score replaces the best).
     constexpr int UNR = 4;
@@ -400,16 +534,36 @@ __global__ __launch_bounds__(WIN_THREADS) void tc_match_window_kernel(const int8
     }
 }
 static size_t match_window_lds(int n_cand, int r) { return (size_t)((n_cand + 31) & ~31) * (size_t)(r + 8); }
-constexpr size_t WINDOW_LDS_MAX = 150 * 1024;
+// dynamic LDS of the window kernel; with the static arrays of its largest instantiation (r = 64, fused verify: 10.6 KB)
+// it stays within the 160 KB of a compute unit
+constexpr size_t WINDOW_LDS_MAX = 148 * 1024;
+template <int R, bool ENC, bool BF16, int D, bool VERIFY>
+static int allow_window_lds() {
+    return hipFuncSetAttribute((const void *)tc_match_window_kernel<R, ENC, BF16, D, VERIFY>,
+                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)WINDOW_LDS_MAX) == hipSuccess
+               ? FASTAR_OK
+               : FASTAR_ERR_HIP;
+}
+// every instantiation of the window kernel may use more than the default 64 KB of dynamic LDS: requested once per device
+int tempcache_setup() {
+    static DeviceOnce once;
+    return once.run([](int) {
+        int rc = FASTAR_OK;
+#define FASTAR_ALLOW(RR, BF, DD)                                                       \
+    do {                                                                               \
+        if (rc == FASTAR_OK) rc = allow_window_lds<RR, true, BF, DD, true>();          \
+        if (rc == FASTAR_OK) rc = allow_window_lds<RR, true, BF, DD, false>();         \
+    } while (0)
+        FASTAR_ALLOW(32, true, 128); FASTAR_ALLOW(32, false, 128); FASTAR_ALLOW(32, true, 64); FASTAR_ALLOW(32, false, 64);
+        FASTAR_ALLOW(64, true, 128); FASTAR_ALLOW(64, false, 128); FASTAR_ALLOW(64, true, 64); FASTAR_ALLOW(64, false, 64);
+#undef FASTAR_ALLOW
+        if (rc == FASTAR_OK) rc = allow_window_lds<32, false, true, 128, false>();
+        if (rc == FASTAR_OK) rc = allow_window_lds<64, false, true, 128, false>();
+        return rc;
+    });
+}
 template <int R, bool ENC, bool BF16, int D, bool VERIFY, typename... Args>
 static int launch_match_window(dim3 grid, size_t lds, hipStream_t s, Args... args) {
-    static bool attr_set = false;  // once per instantiation: allow more than the default 64 KB of dynamic LDS
-    if (!attr_set) {
-        if (hipFuncSetAttribute((const void *)tc_match_window_kernel<R, ENC, BF16, D, VERIFY>,
-                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)WINDOW_LDS_MAX) != hipSuccess)
-            return FASTAR_ERR_HIP;
-        attr_set = true;
-    }
     hipLaunchKernelGGL((tc_match_window_kernel<R, ENC, BF16, D, VERIFY>), grid, dim3(WIN_THREADS), lds, s, args...);
     FASTAR_LAUNCH_CHECK();
     return FASTAR_OK;
@@ -427,8 +581,7 @@ __global__ __launch_bounds__(256) void tc_prep_kernel(const u64 *__restrict__ be
     const u64 key = best[(size_t)h * n_new + i];
     int j = -1, S = 0;
     if (key != 0) {
-        const int pos = (int)(0xFFFFFFFFu - (unsigned)key);   // position in the candidate list (the slot without a list)
-        j = cand ? cand[(size_t)h * n_cand + pos] : pos;
+        j = (int)(0xFFFFFFFFu - (unsigned)key);   // the low word counts down with the slot: ties went to the smallest
         S = (int)(unsigned)(key >> 32) - SCORE_BIAS;
         win[(size_t)h * C + j] = 0;
         grp[(size_t)h * C + j] = 0;
@@ -1362,6 +1515,7 @@ extern "C" int tempcache_compress(const fastar_cache *cache, const fastar_codec 
     }
     if (window) {
         // the whole candidate window fits one workgroup's LDS: final arg-max per token in one launch
+        if (const int rc0 = tempcache_setup(); rc0 != FASTAR_OK) return rc0;
         const dim3 grid((n_new + 63) / 64, H);
         const bool bf = dtype == FASTAR_BF16;
         const VerifyArgs va = {cache->K, tau2_q16, merged, cache->stamp, frame_id, PS_HIST, PS_FUT};
@@ -1387,9 +1541,15 @@ extern "C" int tempcache_compress(const fastar_cache *cache, const fastar_codec 
         const int n_pos_cap = cand ? n_cand : C;
         const int chunk = n_pos_cap <= 4096 ? 64 : 256;
         dim3 grid((n_new + 127) / 128, (n_pos_cap + chunk - 1) / chunk, H);
-#define FASTAR_MATCH(RR, CH)                                                                                    \
-    hipLaunchKernelGGL((tc_match_kernel<RR, CH>), grid, dim3(256), 0, s, cache->code, cache->len, C, cp, n_new, cand, \
-                       n_cand, metric, best)
+#define FASTAR_MATCH(RR, CH)                                                                                         \
+    do {                                                                                                             \
+        if (cand)                                                                                                    \
+            hipLaunchKernelGGL((tc_match_kernel<RR, CH, true>), grid, dim3(256), 0, s, cache->code, cache->len, C, cp, \
+                               n_new, cand, n_cand, metric, best);                                                   \
+        else                                                                                                         \
+            hipLaunchKernelGGL((tc_match_kernel<RR, CH, false>), grid, dim3(256), 0, s, cache->code, cache->len, C, cp, \
+                               n_new, cand, n_cand, metric, best);                                                   \
+    } while (0)
         if (r == 32 && chunk == 64) FASTAR_MATCH(32, 64);
         else if (r == 32) FASTAR_MATCH(32, 256);
         else if (chunk == 64) FASTAR_MATCH(64, 64);
