@@ -1,0 +1,29 @@
+/*
+ * Measurement probes of libfastar: NOT part of the method and not needed by any caller of fastar.h.
+ * The benchmark uses them to report what this chip reaches on the two rooflines the kernels are priced
+ * against, measured in the same process as the kernels.
+ */
+#ifndef FASTAR_PROBE_H
+#define FASTAR_PROBE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/*
+ *   fastar_probe_mfma_bf16  register-resident bf16 32x32x16 matrix-instruction loop on every SIMD;
+ *                           *flops_out (host) receives the floating-point operations one launch performs;
+ *                           sink is a device float the kernel may write (never does in practice).
+ *   fastar_probe_copy       plain streaming copy of `bytes` (multiple of 16) from src to dst (device, 16-byte aligned).
+ * Both enqueue one kernel on `stream`; the caller times them.
+ */
+int fastar_probe_mfma_bf16(int iters, float *sink, double *flops_out, void *stream);
+int fastar_probe_copy(const void *src, void *dst, size_t bytes, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FASTAR_PROBE_H */

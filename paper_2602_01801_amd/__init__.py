@@ -23,6 +23,7 @@ from .binding import (  # noqa: F401
     ann_select_self,
     encode,
     encode_sign,
+    init,
     lib,
     probe_copy,
     probe_mfma_bf16,

@@ -44,6 +44,8 @@ def lib() -> ctypes.CDLL:
             raise FastarError(f"{LIB_PATH} is missing: run `python -m paper_2602_01801_amd.build` "
                               "(or __graft_entry__.build()) first; there is no fallback path")
         L = ctypes.CDLL(LIB_PATH)
+        L.fastar_init.restype = ctypes.c_int
+        L.fastar_init.argtypes = []
         L.fastar_version.restype = ctypes.c_char_p
         L.fastar_strerror.restype = ctypes.c_char_p
         L.fastar_strerror.argtypes = [ctypes.c_int]
@@ -91,10 +93,15 @@ def lib() -> ctypes.CDLL:
     return _lib
 
 
-EXPORTS = ("fastar_version", "fastar_strerror", "fastar_workspace_bytes", "fastar_encode", "tempcache_compress",
+EXPORTS = ("fastar_init", "fastar_version", "fastar_strerror", "fastar_workspace_bytes", "fastar_encode", "tempcache_compress",
            "ann_cross_attn_fwd",
            "ann_select_self", "ann_select_cross", "sparse_attn_fwd", "fastar_encode_sign", "ann_select_lsh",
            "fastar_probe_mfma_bf16", "fastar_probe_copy")
+
+
+def init() -> None:
+    """fastar_init: one-time kernel set-up for the current device (optional; needed before graph capture)."""
+    _check(lib().fastar_init(), "fastar_init")
 
 
 def _check(rc: int, what: str):

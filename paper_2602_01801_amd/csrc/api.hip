@@ -55,6 +55,14 @@ extern "C" int fastar_probe_copy(const void *src, void *dst, size_t bytes, void 
     return FASTAR_OK;
 }
 
+extern "C" int fastar_init(void) {
+    int rc = fastar::attn_d128_pp_setup();
+    if (rc == FASTAR_OK) rc = fastar::attn_d128_setup();
+    if (rc == FASTAR_OK) rc = fastar::select_setup();
+    if (rc == FASTAR_OK) rc = fastar::tempcache_setup();
+    return rc;
+}
+
 extern "C" const char *fastar_version(void) { return "fastar-gfx950 0.1"; }
 
 extern "C" const char *fastar_strerror(int code) {

@@ -394,6 +394,7 @@ extern "C" int sparse_attn_fwd(const void *Q, int n_q, const void *K, const void
     const float scale_log2 = scale * LOG2E;
     if (dtype == FASTAR_BF16) {
         if ((BQ != 64 && BQ != 128) || BK > 64 || (BK & (BK - 1)) != 0) return FASTAR_ERR_UNSUPPORTED;
+        if ((unsigned long long)C * (unsigned long long)d * 2ull >= (1ull << 32)) return FASTAR_ERR_UNSUPPORTED;  // 32-bit row offsets
         int bk_shift = 0;
         while ((1 << bk_shift) < BK) ++bk_shift;
         const dim3 grid((unsigned)(((n_qb * H + 7) / 8) * 8));

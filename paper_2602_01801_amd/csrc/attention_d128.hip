@@ -378,20 +378,26 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_bf16_d128_kernel(
 
 }  // namespace d128
 
-// Launcher used by sparse_attn_fwd for bf16, d = 128.  BQ in {64, 128}.
-int launch_attn_bf16_d128(const void *Q, int n_q, const void *K, const void *V, const int32_t *cnt, const int32_t *len,
-                          int H, int C, const int32_t *sel, const int32_t *nsel, int BQ, int bk_shift, int n_sel,
-                          float scale_log2, void *O, float *lse, hipStream_t s) {
+// more than 64 KiB of LDS per workgroup has to be requested once per kernel and device
+int attn_d128_setup() {
     using namespace d128;
-    static bool attr_set = false;
-    if (!attr_set) {  // more than 64 KiB of LDS per workgroup has to be requested once per kernel
+    static DeviceOnce once;
+    return once.run([](int) {
         if (hipFuncSetAttribute((const void *)attn_bf16_d128_kernel<4>, hipFuncAttributeMaxDynamicSharedMemorySize,
                                 LDS_BYTES) != hipSuccess ||
             hipFuncSetAttribute((const void *)attn_bf16_d128_kernel<2>, hipFuncAttributeMaxDynamicSharedMemorySize,
                                 LDS_BYTES) != hipSuccess)
             return FASTAR_ERR_HIP;
-        attr_set = true;
-    }
+        return FASTAR_OK;
+    });
+}
+
+// Launcher used by sparse_attn_fwd for bf16, d = 128.  BQ in {64, 128}.
+int launch_attn_bf16_d128(const void *Q, int n_q, const void *K, const void *V, const int32_t *cnt, const int32_t *len,
+                          int H, int C, const int32_t *sel, const int32_t *nsel, int BQ, int bk_shift, int n_sel,
+                          float scale_log2, void *O, float *lse, hipStream_t s) {
+    using namespace d128;
+    if (const int rc = attn_d128_setup(); rc != FASTAR_OK) return rc;
     const int n_qb = (n_q + BQ - 1) / BQ;
     const dim3 grid((unsigned)(((n_qb * H + 7) / 8) * 8));
     if (BQ == 128)

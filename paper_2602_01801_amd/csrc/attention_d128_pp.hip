@@ -592,20 +592,26 @@ __global__ __launch_bounds__(2 * NWG * 64, 1) void attn_bf16_d128_pp_kernel(
 
 }  // namespace d128pp
 
-// Launcher used by sparse_attn_fwd for bf16, d = 128, BQ = 128.
-int launch_attn_bf16_d128_pp(const void *Q, int n_q, const void *K, const void *V, const int32_t *cnt,
-                             const int32_t *len, int H, int C, const int32_t *sel, const int32_t *nsel, int bk_shift,
-                             int n_sel, float scale_log2, void *O, float *lse, hipStream_t s) {
+// more than 64 KiB of LDS per workgroup has to be requested once per kernel and device
+int attn_d128_pp_setup() {
     using namespace d128pp;
-    static bool attr_set = false;
-    if (!attr_set) {  // more than 64 KiB of LDS per workgroup has to be requested once per kernel
+    static DeviceOnce once;
+    return once.run([](int) {
         for (const void *f : {(const void *)attn_bf16_d128_pp_kernel<4, false, false>,
                               (const void *)attn_bf16_d128_pp_kernel<4, true, false>,
                               (const void *)attn_bf16_d128_pp_kernel<4, true, true>})
             if (hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES) != hipSuccess)
                 return FASTAR_ERR_HIP;
-        attr_set = true;
-    }
+        return FASTAR_OK;
+    });
+}
+
+// Launcher used by sparse_attn_fwd for bf16, d = 128, BQ = 128.
+int launch_attn_bf16_d128_pp(const void *Q, int n_q, const void *K, const void *V, const int32_t *cnt,
+                             const int32_t *len, int H, int C, const int32_t *sel, const int32_t *nsel, int bk_shift,
+                             int n_sel, float scale_log2, void *O, float *lse, hipStream_t s) {
+    using namespace d128pp;
+    if (const int rc = attn_d128_pp_setup(); rc != FASTAR_OK) return rc;
     const int n_qb = (n_q + 127) / 128;
     const int pairs = (n_qb * H + 1) / 2;
     const dim3 grid((unsigned)(((pairs + 7) / 8) * 8));

@@ -5,6 +5,9 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <atomic>
+#include <mutex>
+
 #include "../../include/fastar.h"
 
 namespace fastar {
@@ -78,6 +81,34 @@ __device__ __forceinline__ T shfl_xor(T v, int mask) {
 __device__ __forceinline__ int dot4_i8(unsigned a, unsigned b, int acc) {
     return __builtin_amdgcn_sdot4((int)a, (int)b, acc, false);
 }
+
+// One-time set-up per device (kernel attributes, symbol addresses), safe to reach from several host threads: run(f)
+// calls f once per device ordinal, with that device current, and remembers a success.  It is the only process-wide data
+// the library keeps, and it never influences a result.
+struct DeviceOnce {
+    static constexpr int MAX_DEVICES = 64;
+    std::atomic<unsigned long long> done{0};
+    std::mutex mu;
+    template <class F>
+    int run(F &&f) {
+        int dev = 0;
+        if (hipGetDevice(&dev) != hipSuccess) return FASTAR_ERR_HIP;
+        if (dev < 0 || dev >= MAX_DEVICES) return FASTAR_ERR_UNSUPPORTED;
+        const unsigned long long bit = 1ull << dev;
+        if (done.load(std::memory_order_acquire) & bit) return FASTAR_OK;
+        std::lock_guard<std::mutex> lock(mu);
+        if (done.load(std::memory_order_relaxed) & bit) return FASTAR_OK;
+        const int rc = f(dev);
+        if (rc == FASTAR_OK) done.fetch_or(bit, std::memory_order_release);
+        return rc;
+    }
+};
+
+// Per-file set-up, all of it run by fastar_init() (api.hip) and each lazily by the first launch that needs it.
+int attn_d128_pp_setup();
+int attn_d128_setup();
+int select_setup();
+int tempcache_setup();
 
 // Host-side launch check shared by the entry points.
 #define FASTAR_LAUNCH_CHECK()                          \

@@ -788,6 +788,19 @@ size_t select_cross_ws_bytes(int H, int n_q, int n_p, int BQ) {
     return align256((size_t)H * n_qb * n_p * sizeof(int32_t));
 }
 
+// more than 64 KB of LDS (long prompts) has to be allowed once per kernel and device
+int select_setup() {
+    static DeviceOnce once;
+    return once.run([](int) {
+        if (hipFuncSetAttribute((const void *)cross_fused_kernel<32>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                (int)fused::lds_bytes(12288)) != hipSuccess ||
+            hipFuncSetAttribute((const void *)cross_fused_kernel<64>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                (int)fused::lds_bytes(12288)) != hipSuccess)
+            return FASTAR_ERR_HIP;
+        return FASTAR_OK;
+    });
+}
+
 }  // namespace fastar
 
 using namespace fastar;
@@ -874,15 +887,7 @@ extern "C" int ann_cross_attn_fwd(const void *Q, const int8_t *qcode, int n_q, c
     const size_t lds = fused::lds_bytes(n_p);
     hipStream_t s = (hipStream_t)stream;
     const float scale_log2 = scale * 1.4426950408889634f;
-    static bool attr_set = false;   // more than 64 KB of LDS (long prompts) has to be allowed once per kernel
-    if (!attr_set) {
-        if (hipFuncSetAttribute((const void *)cross_fused_kernel<32>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                (int)fused::lds_bytes(12288)) != hipSuccess ||
-            hipFuncSetAttribute((const void *)cross_fused_kernel<64>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                (int)fused::lds_bytes(12288)) != hipSuccess)
-            return FASTAR_ERR_HIP;
-        attr_set = true;
-    }
+    if (const int rc = select_setup(); rc != FASTAR_OK) return rc;
     if (r == 32)
         hipLaunchKernelGGL(cross_fused_kernel<32>, dim3(n_qb, H), dim3(256), lds, s, (const unsigned short *)Q, qcode,
                            (const unsigned short *)Kp, (const unsigned short *)Vp, pcode, n_q, n_p, n_qb, n_sel,

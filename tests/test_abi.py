@@ -7,7 +7,8 @@ import re
 import pytest
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
-HEADER = os.path.join(ROOT, "include", "fastar.h")
+HEADERS = [os.path.join(ROOT, "include", name) for name in sorted(os.listdir(os.path.join(ROOT, "include")))
+           if name.endswith(".h")]
 
 
 @pytest.fixture(scope="module")
@@ -20,7 +21,7 @@ def L():
 
 
 def declared_functions():
-    text = open(HEADER).read()
+    text = "\n".join(open(h).read() for h in HEADERS)
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     return sorted(set(re.findall(r"\b([a-z_0-9]+)\s*\([^;{]*\)\s*;", text)))
 
@@ -60,6 +61,16 @@ def test_null_and_inconsistent_arguments_return_error_codes_without_a_gpu(L):
     assert L.fastar_encode(null, 1, 16, 128, None, 32, null, null) == -1
     assert L.tempcache_compress(None, None, null, null, null, 1, null, 0, 0, 0, 0, 0, null, null, null, null, 0,
                                 0, null) == -1
+
+
+def test_cache_beyond_the_32_bit_row_offsets_is_rejected_before_any_launch(L):
+    # bf16 tiles are addressed by 32-bit byte offsets inside a head: C * d * 2 >= 2^32 must come back as unsupported
+    # (the pointers are never dereferenced: the check precedes every launch)
+    fake = ctypes.c_void_p(0x10000)
+    assert L.sparse_attn_fwd(fake, 128, fake, fake, None, fake, 1, 1 << 24, 128, 1, fake, fake, 128, 64, 1,
+                             ctypes.c_float(1.0), fake, None, None) == -2
+    assert L.sparse_attn_fwd(fake, 128, fake, fake, None, fake, 1, 1 << 25, 64, 1, fake, fake, 128, 64, 1,
+                             ctypes.c_float(1.0), fake, None, None) == -2
 
 
 def test_missing_library_fails_loudly(monkeypatch):
