@@ -47,6 +47,10 @@ extern "C" {
 #define FASTAR_ERR_UNSUPPORTED (-2)
 #define FASTAR_ERR_WORKSPACE (-3)
 #define FASTAR_ERR_HIP (-4)
+#define FASTAR_ERR_STATIC_SCRATCH (-5) /* the problem needs more than FASTAR_STATIC_SCRATCH_BYTES */
+
+/* size of the library's static device scratch (ann_select_self_static), held by every GPU the library runs on */
+#define FASTAR_STATIC_SCRATCH_BYTES (32 * 1024 * 1024)
 
 #define FASTAR_F32 0
 #define FASTAR_BF16 1
@@ -205,6 +209,22 @@ int tempcache_compress(const fastar_cache *cache, const fastar_codec *codec, con
 int ann_select_self(const int8_t *qcode, int n_q, const int8_t *kcode, const int32_t *len, int H, int C, int r,
                     int BQ, int n_rep, int BK, int n_sel, int32_t *sel, int32_t *nsel, void *ws,
                     size_t ws_bytes, void *stream);
+
+/*
+ * ann_select_self for callers that cannot allocate or bring a workspace: code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc.  Same arguments, same kernels and bit-identical outputs as ann_select_self,
+ * but the summaries and the score rows live in a static device array of FASTAR_STATIC_SCRATCH_BYTES inside the library
+ * (each GPU holds its own copy until the process ends; its address is looked up once per device, by fastar_init or by
+ * the first call).  The call allocates nothing: no hipMalloc / hipFree, no workspace argument.
+ *   - Problems that need more scratch than that (fastar_workspace_bytes(FASTAR_OP_SELECT_SELF, ...) is the amount;
+ *     the world-model layer with 40 heads x 29 query blocks x 3600 key blocks needs 16.8 MB) return
+ *     FASTAR_ERR_STATIC_SCRATCH and launch nothing.
+ *   - All calls on one GPU share the one array: calls that may overlap on a GPU (different streams, different host
+ *     threads) race on it.  Calls on one stream are ordered and safe.  Nothing in the array has to start from zero
+ *     and nothing of a previous call is read.
+ */
+int ann_select_self_static(const int8_t *qcode, int n_q, const int8_t *kcode, const int32_t *len, int H, int C, int r,
+                           int BQ, int n_rep, int BK, int n_sel, int32_t *sel, int32_t *nsel, void *stream);
 
 /*
  * AnnCA (Sec. 5.3): for every head and every block of BQ queries, the min(n_sel, n_p) prompt tokens

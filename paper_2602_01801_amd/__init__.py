@@ -21,6 +21,7 @@ from .binding import (  # noqa: F401
     ann_select_cross,
     ann_select_lsh,
     ann_select_self,
+    ann_select_self_static,
     encode,
     encode_sign,
     init,

@@ -70,6 +70,10 @@ def lib() -> ctypes.CDLL:
                                       ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int,
                                       ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
                                       ctypes.c_size_t, ctypes.c_void_p]
+        L.ann_select_self_static.restype = ctypes.c_int
+        L.ann_select_self_static.argtypes = [ctypes.c_void_p, ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int,
+                                             ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int,
+                                             ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
         L.ann_select_cross.restype = ctypes.c_int
         L.ann_select_cross.argtypes = [ctypes.c_void_p, ctypes.c_int, ctypes.c_void_p, ctypes.c_int, ctypes.c_int,
                                        ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p,
@@ -95,7 +99,7 @@ def lib() -> ctypes.CDLL:
 
 EXPORTS = ("fastar_init", "fastar_version", "fastar_strerror", "fastar_workspace_bytes", "fastar_encode", "tempcache_compress",
            "ann_cross_attn_fwd",
-           "ann_select_self", "ann_select_cross", "sparse_attn_fwd", "fastar_encode_sign", "ann_select_lsh",
+           "ann_select_self", "ann_select_self_static", "ann_select_cross", "sparse_attn_fwd", "fastar_encode_sign", "ann_select_lsh",
            "fastar_probe_mfma_bf16", "fastar_probe_copy")
 
 
@@ -252,6 +256,24 @@ def ann_select_self(qcode, kcode, length, BQ: int, n_rep: int, BK: int, n_sel: i
     _check(lib().ann_select_self(qcode.data_ptr(), n_q, kcode.data_ptr(), length.data_ptr(), H, C, r, BQ, n_rep, BK,
                                  n_sel, sel.data_ptr(), nsel.data_ptr(), ws.data_ptr(),
                                  ws.numel() * ws.element_size(), _stream()), "ann_select_self")
+    return sel, nsel
+
+
+def ann_select_self_static(qcode, kcode, length, BQ: int, n_rep: int, BK: int, n_sel: int, out):
+    """AnnSA on the library's static scratch: the call allocates nothing, so the outputs (sel, nsel) must be given."""
+    _dev(qcode, torch.int8)
+    _dev(kcode, torch.int8)
+    _dev(length, torch.int32)
+    H, n_q, r = qcode.shape
+    C = kcode.shape[1]
+    sel, nsel = out
+    _dev(sel, torch.int32)
+    _dev(nsel, torch.int32)
+    n_qb = (n_q + BQ - 1) // BQ
+    if tuple(sel.shape) != (H, n_qb, n_sel) or tuple(nsel.shape) != (H, n_qb):
+        raise ValueError("out must be (sel [H,n_qb,n_sel], nsel [H,n_qb])")
+    _check(lib().ann_select_self_static(qcode.data_ptr(), n_q, kcode.data_ptr(), length.data_ptr(), H, C, r, BQ, n_rep,
+                                        BK, n_sel, sel.data_ptr(), nsel.data_ptr(), _stream()), "ann_select_self_static")
     return sel, nsel
 
 

@@ -72,6 +72,7 @@ extern "C" const char *fastar_strerror(int code) {
         case FASTAR_ERR_UNSUPPORTED: return "unsupported shape or type";
         case FASTAR_ERR_WORKSPACE: return "workspace too small";
         case FASTAR_ERR_HIP: return "HIP launch error";
+        case FASTAR_ERR_STATIC_SCRATCH: return "problem larger than the library's static scratch";
         default: return "unknown error";
     }
 }

@@ -788,8 +788,12 @@ size_t select_cross_ws_bytes(int H, int n_q, int n_p, int BQ) {
     return align256((size_t)H * n_qb * n_p * sizeof(int32_t));
 }
 
-// more than 64 KB of LDS (long prompts) has to be allowed once per kernel and device
+int static_scratch_setup();
+
+// more than 64 KB of LDS (long prompts) has to be allowed once per kernel and device; fastar_init also resolves the
+// static scratch through this
 int select_setup() {
+    if (const int rc = static_scratch_setup(); rc != FASTAR_OK) return rc;
     static DeviceOnce once;
     return once.run([](int) {
         if (hipFuncSetAttribute((const void *)cross_fused_kernel<32>, hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -805,9 +809,9 @@ int select_setup() {
 
 using namespace fastar;
 
-extern "C" int ann_select_self(const int8_t *qcode, int n_q, const int8_t *kcode, const int32_t *len, int H, int C,
-                               int r, int BQ, int n_rep, int BK, int n_sel, int32_t *sel, int32_t *nsel, void *ws,
-                               size_t ws_bytes, void *stream) {
+static int select_self_impl(const int8_t *qcode, int n_q, const int8_t *kcode, const int32_t *len, int H, int C, int r,
+                            int BQ, int n_rep, int BK, int n_sel, int32_t *sel, int32_t *nsel, void *ws,
+                            size_t ws_bytes, void *stream) {
     if (!qcode || !kcode || !len || !sel || !nsel || !ws) return FASTAR_ERR_INVALID_ARG;
     if (H <= 0 || n_q <= 0 || C <= 0 || BQ <= 0 || n_rep <= 0 || BK <= 0 || n_sel <= 0) return FASTAR_ERR_INVALID_ARG;
     if (BQ % n_rep != 0) return FASTAR_ERR_INVALID_ARG;
@@ -850,6 +854,45 @@ extern "C" int ann_select_self(const int8_t *qcode, int n_q, const int8_t *kcode
                        nsel);
     FASTAR_LAUNCH_CHECK();
     return FASTAR_OK;
+}
+
+extern "C" int ann_select_self(const int8_t *qcode, int n_q, const int8_t *kcode, const int32_t *len, int H, int C,
+                               int r, int BQ, int n_rep, int BK, int n_sel, int32_t *sel, int32_t *nsel, void *ws,
+                               size_t ws_bytes, void *stream) {
+    return select_self_impl(qcode, n_q, kcode, len, H, C, r, BQ, n_rep, BK, n_sel, sel, nsel, ws, ws_bytes, stream);
+}
+
+// ---- the same selection on the library's own static scratch, for callers that cannot allocate ----------------------
+// `scratch` is device memory that every GPU the library runs on holds until the process ends.  In host code the name
+// is only a stand-in for the symbol: the device address is looked up once per device (with that device current) and
+// kept; kernels, and anything else on the host that needs the memory, use that pointer.
+static __device__ __align__(256) unsigned char scratch[FASTAR_STATIC_SCRATCH_BYTES];
+static void *scratch_ptr[DeviceOnce::MAX_DEVICES];
+
+namespace fastar {
+int static_scratch_setup() {
+    static DeviceOnce once;
+    return once.run([](int dev) {
+        void *p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || p == nullptr) return FASTAR_ERR_HIP;
+        scratch_ptr[dev] = p;
+        return FASTAR_OK;
+    });
+}
+}  // namespace fastar
+
+extern "C" int ann_select_self_static(const int8_t *qcode, int n_q, const int8_t *kcode, const int32_t *len, int H,
+                                      int C, int r, int BQ, int n_rep, int BK, int n_sel, int32_t *sel, int32_t *nsel,
+                                      void *stream) {
+    if (H <= 0 || n_q <= 0 || C <= 0 || r <= 0 || BQ <= 0 || n_rep <= 0 || BK <= 0) return FASTAR_ERR_INVALID_ARG;
+    if (self_ws(H, n_q, C, r, BQ, BK, n_rep).total > (size_t)FASTAR_STATIC_SCRATCH_BYTES) return FASTAR_ERR_STATIC_SCRATCH;
+    if (const int rc = static_scratch_setup(); rc != FASTAR_OK) return rc;
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return FASTAR_ERR_HIP;
+    // nothing in the scratch has to start from zero: the summaries and every score row that the top-k reads are
+    // written by this call's own launches before they are read
+    return select_self_impl(qcode, n_q, kcode, len, H, C, r, BQ, n_rep, BK, n_sel, sel, nsel, scratch_ptr[dev],
+                            (size_t)FASTAR_STATIC_SCRATCH_BYTES, stream);
 }
 
 extern "C" int ann_select_cross(const int8_t *qcode, int n_q, const int8_t *pcode, int n_p, int H, int r, int BQ,
