@@ -1,16 +1,23 @@
 #!/usr/bin/env python3
 """Benchmark of the FAST-AR attention hot path on one MI355X.
 
-A *step* is one generated chunk of the Wan-1.3B-shaped layer (12 heads, d 128, 3 frames of 1560
-tokens = 4680 queries): three TempCache merges (one per frame of the chunk) into the bounded cache,
-ANN codes of the queries, AnnSA selection of 52 key blocks (10 % of the 512 blocks of the 21-frame
-cache the workload is quoted on) per query block, block-sparse self-attention, AnnCA selection of 64
-of 512 prompt tokens and the cross-attention over them.  All inputs are seeded synthetic data
+A *step* is one generated chunk: TempCache merges of the chunk's frames into the bounded cache, ANN codes of
+the queries, AnnSA selection of 10 % of the key blocks per query block, block-sparse self-attention, AnnCA
+selection of 64 of 512 prompt tokens and the cross-attention over them.  All inputs are seeded synthetic data
 (clustered, temporally repeating K/V) already resident in HBM when the clock starts.
 
-Prints ONE JSON line: ms per chunk for the whole hot path, the per-stage split, the roofline
-fraction of the dominant kernel (block-sparse self-attention, bf16 matrix cores, attended FLOPs
-only) and the CPU oracle's time for the same chunk on the host cores.
+Workloads (--workload):
+  cfg5full  (default, the headline) the world-model-scale layer at its full size: 40 heads, d 128, one frame of
+            3600 tokens per chunk, a cache of 64 frames = 230 400 live slots per head (5.1 GB), filled by the seeded
+            device-side generator; every step merges about 90 % of its frame and evicts for the rest, AnnSA keeps 360
+            of 3600 key blocks.
+  cfg2      the Wan-1.3B-shaped layer (12 heads, 3 frames of 1560 tokens per chunk, cache capped at 24 frames).
+  cfg5      the world-model layer fed through TempCache from an empty cache (the cache stays small).
+The default run carries a short cfg2 leg and the two ends of the long-rollout sweep (cfg3) as extra keys.
+
+Prints ONE JSON line: ms per chunk for the whole hot path, the per-stage split with achieved GB/s of the
+bandwidth-bound stages, the roofline fraction of the dominant kernel (block-sparse self-attention, bf16 matrix
+cores, attended FLOPs only) and the CPU oracle's time for the same chunk on the host cores.
 """
 from __future__ import annotations
 
@@ -36,17 +43,23 @@ def parse():
     ap.add_argument("--code-shift", type=int, default=None,
                     help="right shift of the projected sums in the int8 code (default 4, about 8 significant bits; "
                          "6 / 8 / 9 leave about 6 / 4 / 2): the bit-width ladder of the paper's quantisation ablation")
-    ap.add_argument("--stage-steps", type=int, default=6,
+    ap.add_argument("--stage-steps", type=int, default=4,
                     help="extra steps after the timed region, instrumented with an event after every stage")
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="cfg2", choices=["cfg2", "cfg5"])
+    ap.add_argument("--workload", default="cfg5full", choices=["cfg5full", "cfg2", "cfg5"])
+    ap.add_argument("--no-extras", action="store_true",
+                    help="headline workload only: skip the short cfg2 leg and the sweep ends of the default run")
     ap.add_argument("--tau", type=float, default=0.98)
     ap.add_argument("--ws", choices=["persistent", "scratch"], default="persistent",
                     help="TempCache workspace: kept by the caller across calls (zero-filled once; one launch less per "
                          "frame) or scratch that may hold anything")
     ap.add_argument("--cross", choices=["fused", "separate"], default="fused",
                     help="AnnCA as one launch (selection + attention) or as ann_select_cross followed by sparse_attn_fwd")
+    ap.add_argument("--cand", choices=["as-is", "sorted"], default="as-is",
+                    help="candidate list handed to tempcache_compress: the previous call's merge map as it is (the "
+                         "kernel sorts it) or sorted ascending by the caller first (one torch sort per frame, untimed "
+                         "work it is not: it runs inside the step)")
     ap.add_argument("--rep", choices=["last", "mean"], default="last",
                     help="representative key of a merged group: the last key (the method) or the mean key (its ablation)")
     ap.add_argument("--prefill-frames", type=int, default=None, help="frames merged into the cache before timing")
@@ -71,6 +84,7 @@ class ChunkPipeline:
                  fused_cross=True, ws_persistent=True):
         self.t, self.fa, self.cfg = torch, fa, cfg
         self.ws_persistent = ws_persistent
+        self.sorted_cand = False
         self.rep_mode = rep_mode
         self.fused_cross = fused_cross
         H, d, r, T = cfg["H"], cfg["d"], cfg["r"], cfg["T"]
@@ -115,7 +129,10 @@ class ChunkPipeline:
     def compress(self, K, V):
         fa = self.fa
         out = self.mm[self.frame_id & 1]
-        fa.tempcache_compress(self.cache, self.codec, K, V, cand=self.prev, tau2_q16=self.tau2,
+        cand = self.prev
+        if self.sorted_cand and cand is not None:
+            cand = self.t.sort(cand, dim=1).values.contiguous()
+        fa.tempcache_compress(self.cache, self.codec, K, V, cand=cand, tau2_q16=self.tau2,
                               frame_id=self.frame_id, rep_mode=self.rep_mode, ws=self.ws_c, out=out,
                               ws_persistent=self.ws_persistent)
         self.prev = out[0]
@@ -188,57 +205,51 @@ class ChunkPipeline:
         return 4.0 * self.d * float(pairs.item())
 
 
-def gen_chunks(cfg, n_prefill, n_chunks, to_dev, cpu_heads):
-    """Host-side generation of the whole rollout, uploaded once.  The first cpu_heads heads of the prefill
-    frames are kept on the host for the CPU oracle's own rollout."""
-    import numpy as np
+def gen_chunks(cfg, n_prefill, n_chunks, cpu_heads):
+    """Host-side generation of the whole rollout (uploaded once by the caller).  Returns the prefill frames, the
+    chunks [(frames, Q)], the prompt set; host arrays in storage form."""
     from workloads import FrameStream, PromptSet
     fs = FrameStream(cfg["seed"], cfg["cfg_id"], cfg["H"], cfg["d"], cfg["T"], cfg["n_c"], cfg["p"], cfg["sigma_d"],
                      cfg["dtype"])
-    prefill, prefill_host = [], []
-    for _ in range(n_prefill):
-        K, V = fs.next_frame()
-        prefill.append((to_dev(K), to_dev(V)))
-        prefill_host.append((np.ascontiguousarray(K[:cpu_heads]), np.ascontiguousarray(V[:cpu_heads])))
+    prefill = [fs.next_frame() for _ in range(n_prefill)]
     chunks = []
     for _ in range(n_chunks):
         frames = [fs.next_frame() for _ in range(cfg["chunk_frames"])]
         Q = fs.queries(cfg["chunk_frames"])
         chunks.append((frames, Q))
     ps = PromptSet(cfg["seed"], cfg["cfg_id"], fs.centreK, cfg["n_p"], cfg["n_pc"], cfg["n_near"], cfg["dtype"])
-    return prefill, prefill_host, chunks, ps
+    return prefill, chunks, ps
 
 
-def cpu_baseline(cfg, pipe, prefill_host, chunks, ps, n_heads, to_host, sign_matrix=None, code_shift=None):
-    """The CPU oracle's own rollout on the first n_heads heads (same inputs, its own cache state from frame 0);
-    only its last chunk step is timed.  Returns the cpu_baseline record, time scaled to all heads."""
+def cpu_baseline(cfg, pipe, oracle_cache, oracle_prev, oracle_fid, host_chunks, ps_host, n_heads, to_host,
+                 sign_matrix=None, code_shift=None):
+    """The CPU oracle's own rollout on the first n_heads heads: from `oracle_cache` (its state before the first
+    chunk the GPU ran) it replays every chunk of host_chunks (same inputs as the GPU); only its last chunk step is
+    timed.  Returns the cpu_baseline record, time scaled to all heads."""
     import numpy as np
     import oracle
     from workloads import make_codec
     H = cfg["H"]
-    hs = slice(0, n_heads)
     codec = make_codec(cfg["seed"], cfg["cfg_id"], cfg["d"], cfg["r"])
     if code_shift is not None:
         codec.shift = code_shift
-    cache = oracle.Cache.empty(n_heads, pipe.C, cfg["d"], cfg["r"], cfg["dtype"])
+    cache = oracle_cache
     threads = len(os.sched_getaffinity(0))
-    prev, fid = None, 0
+    prev, fid = oracle_prev, oracle_fid
 
     def push(K, V):
         nonlocal prev, fid
-        prev, _, _ = oracle.tempcache_compress(cache, codec.R, codec.qscale, codec.shift, K, V, cand=prev,
-                                               tau2_q16=pipe.tau2, frame_id=fid, rep_mode=pipe.rep_mode)
+        prev, _, st = oracle.tempcache_compress(cache, codec.R, codec.qscale, codec.shift, K, V, cand=prev,
+                                                tau2_q16=pipe.tau2, frame_id=fid, rep_mode=pipe.rep_mode)
         fid += 1
-    for K, V in prefill_host:
-        push(K, V)
-    for frames, _ in chunks[:-1]:
+        return st
+    for frames, _ in host_chunks[:-1]:
         for K, V in frames:
-            push(np.ascontiguousarray(K[hs]), np.ascontiguousarray(V[hs]))
-    frames, Q = chunks[-1]
-    Qh = np.ascontiguousarray(Q[hs])
+            push(K, V)
+    frames, Qh = host_chunks[-1]
     t0 = time.perf_counter()
     for K, V in frames:
-        push(np.ascontiguousarray(K[hs]), np.ascontiguousarray(V[hs]))
+        st_last = push(K, V)
     t1 = time.perf_counter()
     qc = oracle.encode(Qh, codec.R, codec.qscale, codec.shift)
     if sign_matrix is not None:
@@ -250,30 +261,35 @@ def cpu_baseline(cfg, pipe, prefill_host, chunks, ps, n_heads, to_host, sign_mat
     t2 = time.perf_counter()
     O, _ = oracle.sparse_attn_fwd(Qh, cache.K, cache.V, cache.cnt, cache.len, sel, nsel, pipe.BQ, pipe.BK, pipe.scale)
     t3 = time.perf_counter()
-    pc = oracle.encode(np.ascontiguousarray(ps.K[hs]), codec.R, codec.qscale, codec.shift)
+    pK, pV = ps_host
+    pc = oracle.encode(pK, codec.R, codec.qscale, codec.shift)
     csel, cnsel = oracle.ann_select_cross(qc, pc, pipe.BQ, pipe.n_sel_cross)
-    plen = np.full(n_heads, ps.K.shape[1], np.int32)
-    Ox, _ = oracle.sparse_attn_fwd(Qh, np.ascontiguousarray(ps.K[hs]), np.ascontiguousarray(ps.V[hs]), None, plen,
-                                   csel, cnsel, pipe.BQ, 1, pipe.scale)
+    plen = np.full(n_heads, pK.shape[1], np.int32)
+    Ox, _ = oracle.sparse_attn_fwd(Qh, pK, pV, None, plen, csel, cnsel, pipe.BQ, 1, pipe.scale)
     t4 = time.perf_counter()
     # parity of the GPU's last step against this replay (same inputs, same state)
     from workloads import to_f32
+    hs = slice(0, n_heads)
     sel_ok = bool(np.array_equal(to_host(pipe.sel[0])[hs], sel) and np.array_equal(to_host(pipe.sel[1])[hs], nsel))
     csel_ok = bool(np.array_equal(to_host(pipe.csel[0])[hs], csel))
     len_ok = bool(np.array_equal(to_host(pipe.cache.len)[hs], cache.len))
-    err = float(np.abs(to_f32(to_host(pipe.O[0])[hs]).astype(np.float64) - O).max())
-    errx = float(np.abs(to_f32(to_host(pipe.Ox[0])[hs]).astype(np.float64) - Ox).max())
+    mm_ok = bool(np.array_equal(to_host(pipe.prev)[hs], prev))
+    err = float(np.abs(to_f32(to_host(pipe.O[0][hs])).astype(np.float64) - O).max())
+    errx = float(np.abs(to_f32(to_host(pipe.Ox[0][hs])).astype(np.float64) - Ox).max())
     scale = H / n_heads
     recall, density = oracle.recall_density(Qh, cache.K, cache.cnt, cache.len, sel, nsel, pipe.BQ, pipe.BK, pipe.scale,
                                             q_stride=97)
     info = {
         "value": round((t4 - t0) * 1e3 * scale, 1), "unit": "ms/chunk", "cores": threads, "kind": "oracle",
-        "sample": f"heads 0..{n_heads - 1} of {H}: the oracle's own rollout of the same frames, its last chunk step "
-                  f"timed; time scaled by {scale:g}",
+        "sample": f"heads 0..{n_heads - 1} of {H}: the oracle's own replay of the same chunks from the same starting "
+                  f"cache, its last chunk step timed ({(t4 - t0):.1f} s of CPU work; the compress stage runs one thread "
+                  f"per head, the other stages use all {threads}); time scaled by {scale:g} (extrapolated)",
         "stages_ms_scaled": {"compress": round((t1 - t0) * 1e3 * scale, 1), "encode+select": round((t2 - t1) * 1e3 * scale, 1),
                              "attn_self": round((t3 - t2) * 1e3 * scale, 1), "cross": round((t4 - t3) * 1e3 * scale, 1)},
         "parity_on_sample": {"sel_equal": sel_ok, "cross_sel_equal": csel_ok, "len_equal": len_ok,
+                             "merge_map_equal": mm_ok,
                              "attn_self_max_abs_err": err, "attn_cross_max_abs_err": errx},
+        "last_step_stats_head0": [int(x) for x in st_last[0][:5]],
         "selection_recall": round(recall, 4), "selection_density": round(density, 4),
     }
     return info
@@ -288,54 +304,35 @@ def attn_kernel_name(n_items, H, C, d=128):
     return "attn_bf16_d128_kernel<4>"
 
 
-def profiled_traffic_bytes():
-    """HBM bytes per launch of the self-attention kernel as recorded in profiles/ (rocprofv3 FETCH_SIZE +
-    WRITE_SIZE, scaled by a copy of known size), or None when the summary is absent."""
-    path = os.path.join(ROOT, "profiles", "cfg2_chunk_step_hbm_traffic.txt")
+TRAFFIC_FILES = {"cfg2": "cfg2_chunk_step_hbm_traffic.txt", "cfg5full": "cfg5full_chunk_step_hbm_traffic.txt"}
+
+
+def profiled_traffic(workload):
+    """HBM bytes per launch of the self-attention kernel for this workload as measured by the committed counter
+    summary in profiles/ (rocprofv3 FETCH_SIZE + WRITE_SIZE, scaled by a copy of known size): (bytes, file), or
+    (None, None) when no summary for this workload is there.  Lines: '<kernel name> ... <fetch MB> <write MB>'."""
+    name = TRAFFIC_FILES.get(workload)
+    if name is None:
+        return None, None
     best = None
     try:
-        for line in open(path):
-            if "attn_bf16_d128_pp_kernel<4" in line and not line.startswith("#"):
+        for line in open(os.path.join(ROOT, "profiles", name)):
+            if "attn_bf16_d128" in line and not line.startswith("#"):
                 f = line.split()
                 total = (float(f[-2]) + float(f[-1])) * 1e6
                 best = total if best is None else max(best, total)   # of several groups of launches: the self-attention ones
     except (OSError, ValueError):
-        pass
-    return best
+        return None, None
+    return best, ("profiles/" + name if best is not None else None)
 
 
-def main():
-    args = parse()
-    if args.gpus != 1:
-        print("bench.py: this build runs on one GPU only (the hot path is per head and needs no collective); "
-              "run with --gpus 1", file=sys.stderr)
-        sys.exit(2)
-    import numpy as np
-    import torch
-    import paper_2602_01801_amd as fa
+def build_host_rollout(args, workload, torch, fa, np, to_dev, n_chunks, n_cpu_heads):
+    """cfg2 / cfg5: frames generated on the host and merged into an empty cache through tempcache_compress."""
+    import oracle
     from workloads import CONFIGS, make_codec, make_sign_matrix
-
-    assert torch.cuda.is_available(), "bench.py needs a GPU"
-    torch.cuda.set_device(0)
-    fa.lib()
-
-    def to_dev(a):
-        a = np.ascontiguousarray(a)
-        if a.dtype == np.uint16:
-            return torch.from_numpy(a.view(np.int16)).cuda().view(torch.bfloat16)
-        return torch.from_numpy(a).cuda()
-
-    def to_host(t):
-        if t.dtype == torch.bfloat16:
-            return t.view(torch.int16).cpu().numpy().view(np.uint16)
-        return t.cpu().numpy()
-
-    if args.sweep:
-        return sweep(args, torch, fa, np, to_dev, to_host)
-
-    cfg = dict(CONFIGS[args.workload])
+    cfg = dict(CONFIGS[workload])
     T, cf = cfg["T"], cfg["chunk_frames"]
-    cap_frames = args.cap_frames or (24 if args.workload == "cfg2" else cfg["cache_frames"])
+    cap_frames = args.cap_frames or (24 if workload == "cfg2" else cfg["cache_frames"])
     n_prefill = args.prefill_frames if args.prefill_frames is not None else cfg["cache_frames"] - cf
     C = cap_frames * T
     n_kb_quoted = (cfg["cache_frames"] * T + cfg["BK"] - 1) // cfg["BK"]
@@ -344,23 +341,116 @@ def main():
     if args.code_shift is not None:
         codec_h.shift = args.code_shift
     codec = fa.Codec(to_dev(codec_h.R), float(codec_h.qscale), codec_h.shift)
-    n_chunks = args.warmup + args.steps + args.stage_steps
-    t_gen = time.perf_counter()
-    n_cpu_heads = min(args.cpu_heads, cfg["H"])
-    prefill, prefill_host, chunks, ps = gen_chunks(cfg, n_prefill, n_chunks, to_dev, n_cpu_heads)
+    prefill, chunks, ps = gen_chunks(cfg, n_prefill, n_chunks, n_cpu_heads)
     dev_chunks = [([(to_dev(K), to_dev(V)) for K, V in frames], to_dev(Q)) for frames, Q in chunks]
-    t_gen = time.perf_counter() - t_gen
     sign_h = make_sign_matrix(cfg["seed"], cfg["cfg_id"], cfg["d"], 128) if args.ann == "lsh" else None
     pipe = ChunkPipeline(cfg, C, args.tau, torch, fa, codec, (to_dev(ps.K), to_dev(ps.V)), n_sel,
                          sign_matrix=None if sign_h is None else to_dev(sign_h),
                          rep_mode=fa.REP_MEAN if args.rep == "mean" else fa.REP_LAST,
                          fused_cross=args.cross == "fused", ws_persistent=args.ws == "persistent")
     for K, V in prefill:
-        pipe.compress(K, V)
+        pipe.compress(to_dev(K), to_dev(V))
     torch.cuda.synchronize()
+    hs = slice(0, n_cpu_heads)
+    cut = lambda a: np.ascontiguousarray(a[hs])
+
+    def oracle_start():
+        # the oracle's own prefill from an empty cache, on its heads
+        cache = oracle.Cache.empty(n_cpu_heads, C, cfg["d"], cfg["r"], cfg["dtype"])
+        prev = None
+        for f, (K, V) in enumerate(prefill):
+            prev, _, _ = oracle.tempcache_compress(cache, codec_h.R, codec_h.qscale, codec_h.shift, cut(K), cut(V), cand=prev,
+                                                   tau2_q16=pipe.tau2, frame_id=f, rep_mode=pipe.rep_mode)
+        return cache, prev, len(prefill)
+    host_chunks = [([(cut(K), cut(V)) for K, V in frames], cut(Q)) for frames, Q in chunks]
+    label = (f"{workload}: {'Wan-1.3B-shaped' if workload == 'cfg2' else 'world-model-scale'} layer rollout, H {cfg['H']} d "
+             f"{cfg['d']}, chunk {cf}x{T} = {cf * T} queries, TempCache-bounded cache (cap {cap_frames} frames = {C} "
+             f"slots/head, tau {args.tau}) filled through tempcache_compress from empty, AnnSA {n_sel} of {n_kb_quoted} "
+             f"key blocks per query block (BQ {cfg['BQ']}, BK {cfg['BK']}), AnnCA {cfg['n_sel_cross']} of {cfg['n_p']} "
+             f"prompt tokens")
+    return dict(cfg=cfg, pipe=pipe, dev_chunks=dev_chunks, host_chunks=host_chunks, oracle_start=oracle_start,
+                ps_host=(cut(ps.K), cut(ps.V)), sign_h=sign_h, codec_h=codec_h, label=label, n_prefill=n_prefill,
+                cap_frames=cap_frames, n_sel=n_sel, n_kb_quoted=n_kb_quoted)
+
+
+def build_cfg5_full(args, torch, fa, np, to_dev, to_host, n_chunks, n_cpu_heads):
+    """The world-model layer on a full cache: 64 frames of the seeded device-side stream written into the cache as
+    plain concatenation (multiplicity 1, stamp = frame), then the stream goes on through tempcache_compress."""
+    import oracle
+    from workloads import CONFIGS, PromptSet, make_codec, make_sign_matrix
+    from workloads.synth_device import DeviceFrameStream
+    cfg = dict(CONFIGS["cfg5"])
+    H, d, r, T, cf = cfg["H"], cfg["d"], cfg["r"], cfg["T"], cfg["chunk_frames"]
+    n_fill = cfg["cache_frames"]
+    C = n_fill * T
+    n_kb = (C + cfg["BK"] - 1) // cfg["BK"]
+    n_sel = int(np.ceil(cfg["sel_frac"] * n_kb))
+    codec_h = make_codec(cfg["seed"], cfg["cfg_id"], d, r)
+    if args.code_shift is not None:
+        codec_h.shift = args.code_shift
+    codec = fa.Codec(to_dev(codec_h.R), float(codec_h.qscale), codec_h.shift)
+    stream = DeviceFrameStream(cfg["seed"], cfg["cfg_id"], H, d, T, cfg["n_c"], cfg["p"], cfg["sigma_d"], cfg["dtype"])
+    ps = PromptSet(cfg["seed"], cfg["cfg_id"], stream.centreK.cpu().numpy(), cfg["n_p"], cfg["n_pc"], cfg["n_near"],
+                   cfg["dtype"])
+    sign_h = make_sign_matrix(cfg["seed"], cfg["cfg_id"], d, 128) if args.ann == "lsh" else None
+    pipe = ChunkPipeline(cfg, C, args.tau, torch, fa, codec, (to_dev(ps.K), to_dev(ps.V)), n_sel,
+                         sign_matrix=None if sign_h is None else to_dev(sign_h),
+                         rep_mode=fa.REP_MEAN if args.rep == "mean" else fa.REP_LAST,
+                         fused_cross=args.cross == "fused", ws_persistent=args.ws == "persistent")
+    cache = pipe.cache
+    for f in range(n_fill):
+        K, V = stream.next_frame()
+        cache.K[:, f * T:(f + 1) * T] = K
+        cache.V[:, f * T:(f + 1) * T] = V
+        cache.stamp[:, f * T:(f + 1) * T] = f
+    cache.cnt.fill_(1)
+    cache.len.fill_(C)
+    fa.encode(cache.K, codec, out=cache.code)
+    last = torch.arange((n_fill - 1) * T, n_fill * T, dtype=torch.int32, device="cuda").repeat(H, 1).contiguous()
+    pipe.prev = last          # the slots the previous frame wrote
+    pipe.frame_id = n_fill
+    dev_chunks = []
+    for _ in range(n_chunks):
+        frames = [stream.next_frame() for _ in range(cf)]
+        dev_chunks.append((frames, stream.queries(cf)))
+    torch.cuda.synchronize()
+    hs = slice(0, n_cpu_heads)
+    host_chunks = [([(to_host(K[hs]), to_host(V[hs])) for K, V in frames], to_host(Q[hs])) for frames, Q in dev_chunks]
+    # the oracle's starting cache: the generator's keys and values of its heads, ITS OWN codes of them
+    K0, V0 = to_host(cache.K[hs]), to_host(cache.V[hs])
+    stamp0 = to_host(cache.stamp[hs])
+
+    def oracle_start():
+        oc = oracle.Cache(K=K0, V=V0, code=oracle.encode(K0, codec_h.R, codec_h.qscale, codec_h.shift),
+                          cnt=np.ones((n_cpu_heads, C), np.int32), stamp=stamp0, len=np.full(n_cpu_heads, C, np.int32))
+        return oc, to_host(last[hs]), n_fill
+    label = (f"cfg5full: world-model-scale layer at its full size, H {H} d {d}, chunk {cf}x{T} = {cf * T} queries, cache "
+             f"of {n_fill} frames = {C} live slots/head ({cache.nbytes() / 1e9:.2f} GB; seeded device-side generator, plain "
+             f"concatenation), every step TempCache-merges one frame into it (tau {args.tau}) and evicts for the rest, "
+             f"AnnSA {n_sel} of {n_kb} key blocks per query block (BQ {cfg['BQ']}, BK {cfg['BK']}), AnnCA "
+             f"{cfg['n_sel_cross']} of {cfg['n_p']} prompt tokens")
+    return dict(cfg=cfg, pipe=pipe, dev_chunks=dev_chunks, host_chunks=host_chunks, oracle_start=oracle_start,
+                ps_host=(np.ascontiguousarray(ps.K[hs]), np.ascontiguousarray(ps.V[hs])), sign_h=sign_h, codec_h=codec_h,
+                label=label, n_prefill=n_fill, cap_frames=n_fill, n_sel=n_sel, n_kb_quoted=n_kb)
+
+
+def run_layer(args, workload, torch, fa, np, to_dev, to_host, steps, warmup, stage_steps, with_cpu, with_dense):
+    """Build one workload, time `steps` chunk steps, return its record."""
+    n_chunks = warmup + steps + stage_steps
+    n_cpu_heads = min(args.cpu_heads, 40)
+    t_gen = time.perf_counter()
+    if workload == "cfg5full":
+        B = build_cfg5_full(args, torch, fa, np, to_dev, to_host, n_chunks, n_cpu_heads)
+    else:
+        B = build_host_rollout(args, workload, torch, fa, np, to_dev, n_chunks, n_cpu_heads)
+    t_gen = time.perf_counter() - t_gen
+    cfg, pipe, dev_chunks = B["cfg"], B["pipe"], B["dev_chunks"]
+    pipe.sorted_cand = args.cand == "sorted"
+    n_cpu_heads = min(n_cpu_heads, cfg["H"])
+    T, cf, C = cfg["T"], cfg["chunk_frames"], pipe.C
     len_prefill = to_host(pipe.cache.len).tolist()
 
-    for w in range(args.warmup):
+    for w in range(warmup):
         pipe.step(*dev_chunks[w])
     torch.cuda.synchronize()
 
@@ -368,7 +458,7 @@ def main():
     # queue has to drain to; seven per step cost about 15 us of a 0.3 ms step).
     attn_events = []
     t0 = time.perf_counter()
-    for s in range(args.steps):
+    for s in range(steps):
         evs = {}
 
         def mark(name, evs=evs):
@@ -376,25 +466,26 @@ def main():
                 e = torch.cuda.Event(enable_timing=True)
                 e.record()
                 evs[name] = e
-        pipe.step(*dev_chunks[args.warmup + s], ev=mark)
+        pipe.step(*dev_chunks[warmup + s], ev=mark)
         attn_events.append(evs)
     t_enqueued = time.perf_counter()
     torch.cuda.synchronize()
     t1 = time.perf_counter()
-    ms_per_step = (t1 - t0) * 1e3 / args.steps
-    attn_ms_timed = sum(e["select_self"].elapsed_time(e["attn_self"]) for e in attn_events) / args.steps
-    flops_timed = pipe.attended_flops()
+    ms_per_step = (t1 - t0) * 1e3 / steps
+    attn_ms = sum(e["select_self"].elapsed_time(e["attn_self"]) for e in attn_events) / steps
+    flops = pipe.attended_flops()
+    stats_timed = to_host(pipe.mm[(pipe.frame_id - 1) & 1][2])
     # Stage breakdown: a separate pass over the next chunks of the same rollout, an event after every stage.
     stage_names = ["compress", "encode", "select_self", "attn_self", "select_cross", "attn_cross"]
     events = []
-    for s in range(args.stage_steps):
+    for s in range(stage_steps):
         evs = []
 
         def mark(name, evs=evs):
             e = torch.cuda.Event(enable_timing=True)
             e.record()
             evs.append(e)
-        pipe.step(*dev_chunks[args.warmup + args.steps + s], ev=mark)
+        pipe.step(*dev_chunks[warmup + steps + s], ev=mark)
         events.append(evs)
     torch.cuda.synchronize()
     if args.calib_copy_mb > 0:
@@ -408,46 +499,123 @@ def main():
     for evs in events:
         for i, n in enumerate(stage_names):
             stage_ms[n] += evs[i].elapsed_time(evs[i + 1])
-    stage_ms = {n: v / max(args.stage_steps, 1) for n, v in stage_ms.items()}
-    attn_ms = attn_ms_timed
-    flops_last = flops_timed
-    tflops = flops_last / (attn_ms * 1e-3) / 1e12
+    stage_ms = {n: v / max(stage_steps, 1) for n, v in stage_ms.items()}
+    tflops = flops / (attn_ms * 1e-3) / 1e12
     len_final = to_host(pipe.cache.len).tolist()
-    dense = None if args.no_dense_equivalent else pipe.dense_equivalent_ms(dev_chunks[args.warmup + args.steps - 1][1])
+    dense = pipe.dense_equivalent_ms(dev_chunks[warmup + steps - 1][1]) if with_dense else None
+
+    # Algorithmic bytes of the bandwidth-bound stages (per chunk step), for their GB/s against the HBM peak:
+    #   encode: every query row in, its code out;  select: every live code once + the query codes;
+    #   compress, per frame and head: K and V rows of the frame in (2 rows), the matched slot's K row gathered, one V row
+    #   read-modified-written or K and V rows written (2 rows), about 40 B of records, plus the candidate window's codes.
+    H, d, r = cfg["H"], cfg["d"], cfg["r"]
+    es = 2 if cfg["dtype"] == "bf16" else 4
+    live = float(sum(len_final))
+    bytes_stage = {
+        "encode": H * pipe.n_q * (d * es + r),
+        "select_self": live * r + H * pipe.n_q * r + 4.0 * H * pipe.n_qb * pipe.n_sel,
+        "compress": cf * H * T * (5 * d * es + 40 + r) + cf * H * T * r,
+    }
+    stage_gbs = {k: round(v / (stage_ms[k] * 1e-3) / 1e9, 1) for k, v in bytes_stage.items() if stage_ms.get(k, 0) > 0}
+    traffic, traffic_src = profiled_traffic(workload)
 
     result = {
         "metric": "sparse-attn ms per generated chunk", "value": round(ms_per_step, 4), "unit": "ms/chunk",
-        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
+        "n_gpus": 1, "steps": steps, "warmup": warmup, "ms_per_step": round(ms_per_step, 4),
         "higher_is_better": False, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": f"{args.workload}: {'Wan-1.3B-shaped' if args.workload == 'cfg2' else 'world-model-scale'} layer rollout, H {cfg['H']} d {cfg['d']}, chunk "
-                               f"{cf}x{T} = {cf * T} queries, TempCache-bounded cache (cap {cap_frames} frames = {C} "
-                               f"slots/head, tau {args.tau}), AnnSA {n_sel} of {n_kb_quoted} key blocks per query block "
-                               f"(BQ {cfg['BQ']}, BK {cfg['BK']}), AnnCA {cfg['n_sel_cross']} of {cfg['n_p']} prompt tokens",
-                   "ann": f"int8 projection codes (r 32, shift {codec_h.shift})" if args.ann == "int8" else "sign codes, 128 hash bits (LSH variant)",
+        "config": {"workload": B["label"],
+                   "ann": f"int8 projection codes (r 32, shift {B['codec_h'].shift})" if args.ann == "int8" else "sign codes, 128 hash bits (LSH variant)",
                    "representative": args.rep + " key",
                    "tempcache_workspace": args.ws,
                    "cross_attention": "one launch (ann_cross_attn_fwd)" if args.cross == "fused" else "ann_select_cross + sparse_attn_fwd",
-                   "prefill_frames": n_prefill, "cache_len_per_head_start": [min(len_prefill), max(len_prefill)],
+                   "prefill_frames": B["n_prefill"], "cache_len_per_head_start": [min(len_prefill), max(len_prefill)],
                    "cache_len_per_head_end": [min(len_final), max(len_final)],
+                   "last_timed_compress_stats_head0": {k: int(v) for k, v in zip(
+                       ("len", "merged", "appended", "evicted", "dropped"), stats_timed[0][:5])},
                    "cache_bytes": pipe.cache.nbytes()},
         "stages_ms": {k: round(v, 4) for k, v in stage_ms.items()},
-        "stages_note": f"separate pass of {args.stage_steps} steps after the timed region, one event per stage",
+        "stages_note": f"separate pass of {stage_steps} steps after the timed region, one event per stage",
+        "stages_hbm": {"algorithmic_bytes": {k: int(v) for k, v in bytes_stage.items()}, "achieved_GBs": stage_gbs,
+                       "frac_of_peak": {k: round(v / PEAK_HBM_GBS, 4) for k, v in stage_gbs.items()},
+                       "peak_GBs": PEAK_HBM_GBS},
         "effective_tflops": round(tflops, 2), "pct_mfma_peak": round(100 * tflops / PEAK_BF16_TFLOPS, 2),
         "roofline": {"kernel": attn_kernel_name(cfg["H"] * pipe.n_qb, cfg["H"], C) + " (block-sparse self-attention)", "bound": "mfma",
                      "achieved": round(tflops, 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                      "frac": round(tflops / PEAK_BF16_TFLOPS, 4),
-                     "traffic": profiled_traffic_bytes() if args.workload == "cfg2" else None,
-                     "flops_per_launch": flops_last, "avg_launch_ms": round(attn_ms, 4)},
+                     "traffic": traffic, "traffic_source": traffic_src,
+                     "flops_per_launch": flops, "avg_launch_ms": round(attn_ms, 4)},
         "dense_equivalent": None if dense is None else {
             "ms": round(dense[0], 4), "key_blocks": dense[1], "speedup_of_sparse": round(dense[0] / attn_ms, 2),
             "note": "same kernel, every live key block of the final cache selected"},
         "host_gen_s": round(t_gen, 1),
-        "host_enqueue_ms_per_step": round((t_enqueued - t0) * 1e3 / args.steps, 4),
+        "host_enqueue_ms_per_step": round((t_enqueued - t0) * 1e3 / steps, 4),
     }
-    if not args.no_cpu_baseline:
-        result["cpu_baseline"] = cpu_baseline(cfg, pipe, prefill_host, chunks, ps, n_cpu_heads, to_host, sign_h, args.code_shift)
+    if with_cpu:
+        oc, oprev, ofid = B["oracle_start"]()
+        result["cpu_baseline"] = cpu_baseline(cfg, pipe, oc, oprev, ofid, B["host_chunks"], B["ps_host"], n_cpu_heads,
+                                              to_host, B["sign_h"], args.code_shift)
+    return result
+
+
+def sweep_ends(args, torch, fa, np, to_dev, to_host, n_frames=129):
+    """The two ends of the long-rollout sweep (cfg3, TempCache-bounded): chunk time right after the start and once
+    the cap of 24 frames of slots is reached and every call evicts."""
+    rows = sweep(args, torch, fa, np, to_dev, to_host, n_frames=n_frames, bounded_only=True, quiet=True)
+    first = rows[1]["tempcache"]
+    capped = [r_["tempcache"] for r_ in rows if r_["tempcache"]["evicted"] > 0]
+    out = {"first": dict(frames=rows[1]["frames"], **first)}
+    if capped:
+        last = capped[-3:]
+        out["capped"] = {"frames": rows[-1]["frames"], "ms": round(sum(x["ms"] for x in last) / len(last), 4),
+                         "compress_ms": round(sum(x["compress_ms"] for x in last) / len(last), 4),
+                         "attn_self_ms": round(sum(x["attn_self_ms"] for x in last) / len(last), 4),
+                         "len_max": last[-1]["len_max"], "evicted_per_call_head0": last[-1]["evicted"],
+                         "note": "mean of the last three evicting steps"}
+        out["capped_over_first"] = round(out["capped"]["ms"] / first["ms"], 3)
+    return out
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (the hot path is per head and needs no collective); "
+              "run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+    import numpy as np
+    import torch
+    import paper_2602_01801_amd as fa
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    fa.lib()
+    fa.init()
+
+    def to_dev(a):
+        a = np.ascontiguousarray(a)
+        if a.dtype == np.uint16:
+            return torch.from_numpy(a.view(np.int16)).cuda().view(torch.bfloat16)
+        return torch.from_numpy(a).cuda()
+
+    def to_host(t):
+        if t.dtype == torch.bfloat16:
+            return t.contiguous().view(torch.int16).cpu().numpy().view(np.uint16)
+        return t.contiguous().cpu().numpy()
+
+    if args.sweep:
+        return sweep(args, torch, fa, np, to_dev, to_host, n_frames=args.sweep_frames)
+
+    result = run_layer(args, args.workload, torch, fa, np, to_dev, to_host, args.steps, args.warmup, args.stage_steps,
+                       with_cpu=not args.no_cpu_baseline, with_dense=not args.no_dense_equivalent)
     result["peaks_measured"] = {"mfma_bf16_tflops": round(fa.probe_mfma_bf16(), 1),
                                 "stream_copy_gbs": round(fa.probe_copy(), 1)}
+    if args.workload == "cfg5full" and not args.no_extras:
+        torch.cuda.empty_cache()
+        r2 = run_layer(args, "cfg2", torch, fa, np, to_dev, to_host, 20, 3, 4, with_cpu=False, with_dense=False)
+        result["cfg2"] = {k: r2[k] for k in ("ms_per_step", "stages_ms", "stages_hbm", "effective_tflops", "roofline")}
+        result["cfg2"]["workload"] = r2["config"]["workload"]
+        result["cfg2"]["cache_len_per_head_end"] = r2["config"]["cache_len_per_head_end"]
+        torch.cuda.empty_cache()
+        result["cfg3_sweep_ends"] = sweep_ends(args, torch, fa, np, to_dev, to_host)
     line = json.dumps(result)
     print(line, flush=True)
     if args.out:
@@ -456,13 +624,12 @@ def main():
             f.write(line + "\n")
 
 
-def sweep(args, torch, fa, np, to_dev, to_host):
-    """Long-rollout sweep of the Wan-shaped layer: the cache grows 3 frames per step up to --sweep-frames;
+def sweep(args, torch, fa, np, to_dev, to_host, n_frames, bounded_only=False, quiet=False):
+    """Long-rollout sweep of the Wan-shaped layer: the cache grows 3 frames per step up to n_frames;
     each step is run TempCache-bounded (cap 24 frames of slots) and uncompressed (plain concatenation)."""
     from workloads import CONFIGS, FrameStream, PromptSet, make_codec
     cfg = dict(CONFIGS["cfg3"])
     T, cf, H, d, r = cfg["T"], cfg["chunk_frames"], cfg["H"], cfg["d"], cfg["r"]
-    n_frames = args.sweep_frames
     cap = cfg["cap_frames"] * T
     codec_h = make_codec(cfg["seed"], cfg["cfg_id"], d, r)
     codec = fa.Codec(to_dev(codec_h.R), float(codec_h.qscale), codec_h.shift)
@@ -472,7 +639,7 @@ def sweep(args, torch, fa, np, to_dev, to_host):
     n_kb_quoted = (21 * T + cfg["BK"] - 1) // cfg["BK"]
     n_sel = int(np.ceil(cfg["sel_frac"] * n_kb_quoted))
     bounded = ChunkPipeline(cfg, cap, args.tau, torch, fa, codec, prompt, n_sel)
-    plain = ChunkPipeline(cfg, n_frames * T, 2.0 ** 0.5, torch, fa, codec, prompt, n_sel)   # tau^2 = 2: never merges
+    plain = None if bounded_only else ChunkPipeline(cfg, n_frames * T, 2.0 ** 0.5, torch, fa, codec, prompt, n_sel)   # tau^2 = 2: never merges
     rows = []
     spacer = torch.zeros(64 << 20, dtype=torch.uint8, device="cuda")
     for step in range(n_frames // cf):
@@ -480,6 +647,8 @@ def sweep(args, torch, fa, np, to_dev, to_host):
         Q = to_dev(fs.queries(cf))
         row = {"frames": (step + 1) * cf}
         for name, pipe in (("tempcache", bounded), ("uncompressed", plain)):
+            if pipe is None:
+                continue
             evs = []
 
             def mark(nm, evs=evs):
@@ -499,14 +668,17 @@ def sweep(args, torch, fa, np, to_dev, to_host):
             row[name] = {"ms": round(ms, 3), "attn_self_ms": round(evs[3].elapsed_time(evs[4]), 4),
                          "select_self_ms": round(evs[2].elapsed_time(evs[3]), 4),
                          "compress_ms": round(evs[0].elapsed_time(evs[1]), 4),
-                         "len_max": int(L.max()), "live_cache_MB": round(live_bytes / 1e6, 1)}
+                         "len_max": int(L.max()), "live_cache_MB": round(live_bytes / 1e6, 1),
+                         "evicted": int(to_host(pipe.mm[(pipe.frame_id - 1) & 1][2])[0, 3])}
         rows.append(row)
-        print(json.dumps(row), flush=True)
-    if args.out:
+        if not quiet:
+            print(json.dumps(row), flush=True)
+    if args.out and not quiet:
         os.makedirs(os.path.dirname(os.path.abspath(args.out)), exist_ok=True)
         with open(args.out, "w") as f:
             for row in rows:
                 f.write(json.dumps(row) + "\n")
+    return rows
 
 
 if __name__ == "__main__":

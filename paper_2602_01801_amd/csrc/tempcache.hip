@@ -233,7 +233,10 @@ struct VerifyArgs {   // the verify step's arguments, for the launch that runs i
 // With VERIFY (workspaces that every call leaves clean, see tempcache_compress) the kernel is the verify step too: once
 // the arg-max of its 64 tokens is final it runs the cosine test for them and registers the joiners; nothing is cleared
 // here (records and plan scratch are clean on entry), and every workgroup adds its slice of the age histogram.
-template <int R, bool ENC, bool BF16, int D, bool VERIFY>
+// TOKS: tokens per workgroup.  64 (two groups of 32 tokens, four wavefronts share each group's window scan) when the
+// call is latency-bound; 256 (eight groups, one wavefront scans the whole window for its group) when there are many
+// more workgroups than the chip holds at once: staging the window is then paid a quarter as often.
+template <int R, bool ENC, bool BF16, int D, bool VERIFY, int TOKS>
 __global__ __launch_bounds__(WIN_THREADS) void tc_match_window_kernel(const int8_t *__restrict__ code,
                                                               const int32_t *__restrict__ len, int C,
                                                               const int8_t *__restrict__ cp, int n_new,
@@ -252,27 +255,35 @@ __global__ __launch_bounds__(WIN_THREADS) void tc_match_window_kernel(const int8
     i32x4 *ccode = (i32x4 *)wlds;                       // [NCH][n_pad]
     int *cslot = (int *)(wlds + (size_t)NCH * n_pad * 16);  // [n_pad]
     int *cpen = cslot + n_pad;                          // [n_pad]
-    constexpr int SPLIT = WIN_THREADS / 128;  // wavefronts sharing one group of 32 tokens, each on its share of the window
-    __shared__ u64 partbest[SPLIT][2][32];
+    constexpr int TG = TOKS / 32;                  // groups of 32 tokens
+    constexpr int SPLIT = (WIN_THREADS / 64) / TG; // wavefronts sharing one group of 32 tokens, each on its share of the window
+    static_assert(TG * SPLIT == WIN_THREADS / 64 && (TOKS == 64 || TOKS % 128 == 0), "token groups times window shares = wavefronts");
+    __shared__ u64 partbest[SPLIT][TG][32];
     const int h = blockIdx.y;
     const int L = min(len[h], C);
     const int tid = threadIdx.x, lane = lane_id(), wave = tid >> 6;
     const int col = lane & 31, g2 = lane >> 5;
-    const int tg = wave & 1, ch = wave >> 1;
-    const int tok = blockIdx.x * 64 + tg * 32 + col;
+    const int tg = wave % TG, ch = wave / TG;
+    const int tok = blockIdx.x * TOKS + tg * 32 + col;
     const int8_t *ch_code = code + (size_t)h * C * R;
-    __shared__ __attribute__((aligned(16))) int8_t pcode[ENC ? 64 * R : 16];
+    __shared__ __attribute__((aligned(16))) int8_t pcode[ENC ? TOKS * R : 16];
     i32x4 bfrag[KS];
     CodeMatrix<BF16, D, R> cm;
-    i32x4 xq[D / 64];
-    const int etok = blockIdx.x * 64 + 16 * wave + (lane & 15);  // token this lane helps to encode
+    // encoding: 16 tokens per wavefront and round; 64 tokens: wavefronts 0..3 once, 256 tokens: all eight twice
+    constexpr int EROUNDS = TOKS >= 128 ? TOKS / 128 : 1;
+    const bool enc_wave = ENC && (TOKS >= 128 || wave < 4);
+    i32x4 xq[EROUNDS][D / 64];
     if (ENC && !VERIFY)
         for (int k = blockIdx.x * WIN_THREADS + tid; k < ps_words; k += gridDim.x * WIN_THREADS) ps_all[(size_t)h * ps_words + k] = 0u;
-    if (ENC && wave < 4) {  // 16 tokens per wavefront
+    if (enc_wave) {
         cm.load(Rm, lane);
-        const char *row = (const char *)K_new + ((size_t)h * n_new + min(etok, n_new - 1)) * (size_t)D * (BF16 ? 2 : 4);
 #pragma unroll
-        for (int ks = 0; ks < D / 64; ++ks) xq[ks] = load_quantised<BF16>(row, ks, lane >> 4, qscale);
+        for (int er = 0; er < EROUNDS; ++er) {
+            const int etok = blockIdx.x * TOKS + 16 * (wave + 8 * er) + (lane & 15);  // token this lane helps to encode
+            const char *row = (const char *)K_new + ((size_t)h * n_new + min(etok, n_new - 1)) * (size_t)D * (BF16 ? 2 : 4);
+#pragma unroll
+            for (int ks = 0; ks < D / 64; ++ks) xq[er][ks] = load_quantised<BF16>(row, ks, lane >> 4, qscale);
+        }
     } else if (!ENC) {
         // probe codes of this wavefront's 32 tokens (B operand), in flight while the window is staged
         const int trow = min(tok, n_new - 1);
@@ -432,12 +443,16 @@ __global__ __launch_bounds__(WIN_THREADS) void tc_match_window_kernel(const int8
             }
         }
     }
-    if (ENC && wave < 4) {
+    if (enc_wave) {
 #pragma unroll
-        for (int cb = 0; cb < R / 16; ++cb) {
-            const unsigned w = cm.code_word(xq, cb, shift);
-            *(unsigned *)(pcode + (16 * wave + (lane & 15)) * R + cb * 16 + 4 * (lane >> 4)) = w;
-            if (etok < n_new) *(unsigned *)(ck + ((size_t)h * n_new + etok) * R + cb * 16 + 4 * (lane >> 4)) = w;
+        for (int er = 0; er < EROUNDS; ++er) {
+            const int etok = blockIdx.x * TOKS + 16 * (wave + 8 * er) + (lane & 15);
+#pragma unroll
+            for (int cb = 0; cb < R / 16; ++cb) {
+                const unsigned w = cm.code_word(xq[er], cb, shift);
+                *(unsigned *)(pcode + (16 * (wave + 8 * er) + (lane & 15)) * R + cb * 16 + 4 * (lane >> 4)) = w;
+                if (etok < n_new) *(unsigned *)(ck + ((size_t)h * n_new + etok) * R + cb * 16 + 4 * (lane >> 4)) = w;
+            }
         }
     }
     __syncthreads();
@@ -445,7 +460,11 @@ __global__ __launch_bounds__(WIN_THREADS) void tc_match_window_kernel(const int8
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) bfrag[ks] = *(const i32x4 *)(pcode + (tg * 32 + col) * R + ks * 32 + 16 * g2);
     }
-    LaneBest lb;
+    // Running arg-max of a lane over the 16 scores per group its accumulators hold: only the best score and the group
+    // it came from are kept in the loop (a maximum tree and one compare-select per group; a later group replaces the
+    // best only on a strictly higher score, so the earliest group wins among equals); which of the group's rows it was
+    // is looked up once, after the loop, by recomputing that group's 16 scores for this lane's token.
+    int bs = INT_MIN, bg = 0;
     const int n_groups = n_stage / 32;
     // Four groups of 32 candidates per step, their operand reads and matrix instructions issued together
     // (a group repeated at the ragged end changes nothing: only a strictly higher score replaces the best).
@@ -476,9 +495,37 @@ __global__ __launch_bounds__(WIN_THREADS) void tc_match_window_kernel(const int8
             }
         }
 #pragma unroll
-        for (int u = 0; u < UNR; ++u) lb.take(acc[u], min(g0 + u, n_groups - 1));
+        for (int u = 0; u < UNR; ++u) {
+            int mx = acc[u][0];
+#pragma unroll
+            for (int v = 1; v < 16; ++v) mx = max(mx, acc[u][v]);
+            const bool better = mx > bs;
+            bs = better ? mx : bs;
+            bg = better ? min(g0 + u, n_groups - 1) : bg;
+        }
     }
-    u64 mybest = lb.key(g2, 0);
+    u64 mybest = 0;
+    if (bs > MATCH_VALID) {   // some real candidate was seen: the earliest row of group bg that reaches the best score
+        i32x4 pc[NCH];
+        const int8_t *prow = ENC ? pcode + (tg * 32 + col) * R : cp + ((size_t)h * n_new + min(tok, n_new - 1)) * R;
+#pragma unroll
+        for (int c = 0; c < NCH; ++c) pc[c] = *(const i32x4 *)(prow + 16 * c);
+        int pos = -1;
+#pragma unroll
+        for (int v = 15; v >= 0; --v) {
+            const int row = bg * 32 + 8 * (v >> 2) + 4 * g2 + (v & 3);
+            int dot = 0;
+#pragma unroll
+            for (int c = 0; c < NCH; ++c) {
+                const i32x4 cc = ccode[c * n_pad + row];
+#pragma unroll
+                for (int m = 0; m < 4; ++m) dot = dot4_i8((unsigned)cc[m], (unsigned)pc[c][m], dot);
+            }
+            const int S = (metric == 0 ? 2 * dot : dot) + cpen[row];
+            pos = S == bs ? row : pos;
+        }
+        if (pos >= 0) mybest = ((u64)(unsigned)(bs + SCORE_BIAS) << 32) | (u64)(0xFFFFFFFFu - (unsigned)pos);
+    }
     {
         const unsigned lo = shfl_xor((unsigned)mybest, 32), hi = shfl_xor((unsigned)(mybest >> 32), 32);
         const u64 other = ((u64)hi << 32) | lo;
@@ -486,7 +533,7 @@ __global__ __launch_bounds__(WIN_THREADS) void tc_match_window_kernel(const int8
     }
     if (g2 == 0) partbest[ch][tg][col] = mybest;
     __syncthreads();
-    __shared__ int vj[64], vs[64];
+    __shared__ int vj[TOKS], vs[TOKS];
     if (ch == 0 && g2 == 0) {
         int j = -1, S = 0;
         if (tok < n_new) {
@@ -514,20 +561,24 @@ __global__ __launch_bounds__(WIN_THREADS) void tc_match_window_kernel(const int8
     if constexpr (VERIFY) {
         __shared__ unsigned lhist[AGE_BINS];
         __syncthreads();
-        constexpr int NPASS = 64 * 16 / WIN_THREADS;   // tokens per 16-lane group
-        VerifyRows<BF16, D> vr[NPASS];
+        constexpr int NPASS = TOKS * 16 / WIN_THREADS;   // tokens per 16-lane group
+        constexpr int PB = 2;                            // passes whose rows are loaded together (registers)
 #pragma unroll
-        for (int pass = 0; pass < NPASS; ++pass) {   // every row this group will need, in one round of loads
-            const int t = pass * (WIN_THREADS / 16) + (tid >> 4);
-            const int i = min(blockIdx.x * 64 + t, n_new - 1);
-            vr[pass].load(va.K, K_new, pcode + t * R, R, C, n_new, metric, h, i, tid & 15, vj[t]);
-        }
+        for (int p0 = 0; p0 < NPASS; p0 += PB) {
+            VerifyRows<BF16, D> vr[PB];
 #pragma unroll
-        for (int pass = 0; pass < NPASS; ++pass) {
-            const int t = pass * (WIN_THREADS / 16) + (tid >> 4);
-            const int i = blockIdx.x * 64 + t;
-            if (i < n_new)   // whole 16-lane groups
-                vr[pass].decide(C, n_new, qscale, metric, va.tau2_q16, win, grp, va.merged, h, i, tid & 15, vj[t], vs[t]);
+            for (int pass = 0; pass < PB; ++pass) {   // every row this group will need, in one round of loads
+                const int t = (p0 + pass) * (WIN_THREADS / 16) + (tid >> 4);
+                const int i = min(blockIdx.x * TOKS + t, n_new - 1);
+                vr[pass].load(va.K, K_new, pcode + t * R, R, C, n_new, metric, h, i, tid & 15, vj[t]);
+            }
+#pragma unroll
+            for (int pass = 0; pass < PB; ++pass) {
+                const int t = (p0 + pass) * (WIN_THREADS / 16) + (tid >> 4);
+                const int i = blockIdx.x * TOKS + t;
+                if (i < n_new)   // whole 16-lane groups
+                    vr[pass].decide(C, n_new, qscale, metric, va.tau2_q16, win, grp, va.merged, h, i, tid & 15, vj[t], vs[t]);
+            }
         }
         age_histogram_slice(len, va.stamp, C, n_new, va.frame_id, ps_all + (size_t)h * ps_words, va.hist_word, va.fut_word,
                             lhist);
@@ -537,10 +588,14 @@ static size_t match_window_lds(int n_cand, int r) { return (size_t)((n_cand + 31
 // dynamic LDS of the window kernel; with the static arrays of its largest instantiation (r = 64, fused verify: 10.6 KB)
 // it stays within the 160 KB of a compute unit
 constexpr size_t WINDOW_LDS_MAX = 148 * 1024;
-template <int R, bool ENC, bool BF16, int D, bool VERIFY>
+// static LDS of the wide (256 tokens per workgroup) instantiations: probe codes, verify hand-over, partial results,
+// age histogram, a few words; what is left of a compute unit's 160 KB is their window
+static constexpr size_t wide_window_lds_max(int r) { return (size_t)160 * 1024 - ((size_t)256 * r + 256 * 8 + 2048 + 4096 + 256); }
+template <int R, bool ENC, bool BF16, int D, bool VERIFY, int TOKS>
 static int allow_window_lds() {
-    return hipFuncSetAttribute((const void *)tc_match_window_kernel<R, ENC, BF16, D, VERIFY>,
-                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)WINDOW_LDS_MAX) == hipSuccess
+    const size_t lim = TOKS == 64 ? WINDOW_LDS_MAX : wide_window_lds_max(R);
+    return hipFuncSetAttribute((const void *)tc_match_window_kernel<R, ENC, BF16, D, VERIFY, TOKS>,
+                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)lim) == hipSuccess
                ? FASTAR_OK
                : FASTAR_ERR_HIP;
 }
@@ -551,20 +606,22 @@ int tempcache_setup() {
         int rc = FASTAR_OK;
 #define FASTAR_ALLOW(RR, BF, DD)                                                       \
     do {                                                                               \
-        if (rc == FASTAR_OK) rc = allow_window_lds<RR, true, BF, DD, true>();          \
-        if (rc == FASTAR_OK) rc = allow_window_lds<RR, true, BF, DD, false>();         \
+        if (rc == FASTAR_OK) rc = allow_window_lds<RR, true, BF, DD, true, 64>();      \
+        if (rc == FASTAR_OK) rc = allow_window_lds<RR, true, BF, DD, false, 64>();     \
+        if (rc == FASTAR_OK) rc = allow_window_lds<RR, true, BF, DD, true, 256>();     \
+        if (rc == FASTAR_OK) rc = allow_window_lds<RR, true, BF, DD, false, 256>();    \
     } while (0)
         FASTAR_ALLOW(32, true, 128); FASTAR_ALLOW(32, false, 128); FASTAR_ALLOW(32, true, 64); FASTAR_ALLOW(32, false, 64);
         FASTAR_ALLOW(64, true, 128); FASTAR_ALLOW(64, false, 128); FASTAR_ALLOW(64, true, 64); FASTAR_ALLOW(64, false, 64);
 #undef FASTAR_ALLOW
-        if (rc == FASTAR_OK) rc = allow_window_lds<32, false, true, 128, false>();
-        if (rc == FASTAR_OK) rc = allow_window_lds<64, false, true, 128, false>();
+        if (rc == FASTAR_OK) rc = allow_window_lds<32, false, true, 128, false, 64>();
+        if (rc == FASTAR_OK) rc = allow_window_lds<64, false, true, 128, false, 64>();
         return rc;
     });
 }
-template <int R, bool ENC, bool BF16, int D, bool VERIFY, typename... Args>
+template <int R, bool ENC, bool BF16, int D, bool VERIFY, int TOKS, typename... Args>
 static int launch_match_window(dim3 grid, size_t lds, hipStream_t s, Args... args) {
-    hipLaunchKernelGGL((tc_match_window_kernel<R, ENC, BF16, D, VERIFY>), grid, dim3(WIN_THREADS), lds, s, args...);
+    hipLaunchKernelGGL((tc_match_window_kernel<R, ENC, BF16, D, VERIFY, TOKS>), grid, dim3(WIN_THREADS), lds, s, args...);
     FASTAR_LAUNCH_CHECK();
     return FASTAR_OK;
 }
@@ -601,29 +658,58 @@ __device__ __forceinline__ void age_histogram_slice(const int32_t *__restrict__ 
     if (L + n_new <= C) return;  // uniform over the head: no eviction can be needed
     for (int k = threadIdx.x; k < AGE_BINS; k += blockDim.x) lhist[k] = 0;
     __syncthreads();
-    const int chunk = (L + gridDim.x - 1) / gridDim.x;
-    const int j0 = blockIdx.x * chunk, j1 = min(j0 + chunk, L);
+    // every workgroup takes a run of slots that starts on a multiple of four, four consecutive stamps per lane and load
+    // (16 bytes when the head's row is aligned), four such loads in flight before the first is used
+    const int chunk = ((L + gridDim.x - 1) / gridDim.x + 3) & ~3;
+    const int j0 = min((int)blockIdx.x * chunk, L), j1 = min(j0 + chunk, L);
     const int32_t *st = stamp + (size_t)h * C;
+    const bool vec = (((uintptr_t)st) & 15) == 0;
     bool future = false;
+    constexpr int UN = 4;
     // Neighbouring slots were mostly written by the same frame: when all of a wavefront's slots fall into one bin, one
-    // lane adds their number (64 additions to one LDS word would be served one after the other).
-    for (int jb = j0; jb < j1; jb += blockDim.x) {   // uniform trip count
-        const int j = jb + threadIdx.x;
-        const bool act = j < j1;
-        unsigned bin = 0;
-        if (act) {
-            const int sj = st[j];
-            if (sj > frame_id) future = true;
-            bin = min((unsigned)frame_id - (unsigned)sj, (unsigned)(AGE_BINS - 1));
+    // lane adds their number (hundreds of additions to one LDS word would be served one after the other).
+    for (int jb = j0; jb < j1; jb += (int)blockDim.x * 4 * UN) {   // uniform trip count
+        int sv[UN][4];
+#pragma unroll
+        for (int u = 0; u < UN; ++u) {
+            const int j = jb + (u * (int)blockDim.x + (int)threadIdx.x) * 4;
+            if (vec && j + 3 < j1) {
+                const i32x4 v = *(const i32x4 *)(st + j);
+                sv[u][0] = v[0]; sv[u][1] = v[1]; sv[u][2] = v[2]; sv[u][3] = v[3];
+            } else {
+#pragma unroll
+                for (int e = 0; e < 4; ++e) sv[u][e] = j + e < j1 ? st[j + e] : 0;
+            }
         }
-        const u64 m = __ballot(act);
-        if (m) {
-            const int first = __ffsll((unsigned long long)m) - 1;
-            const unsigned fbin = (unsigned)__shfl((int)bin, first);
-            if (__all(!act || bin == fbin)) {
-                if (lane_id() == first) atomicAdd(&lhist[fbin], (unsigned)__popcll(m));
-            } else if (act) {
-                atomicAdd(&lhist[bin], 1u);
+#pragma unroll
+        for (int u = 0; u < UN; ++u) {
+            const int j = jb + (u * (int)blockDim.x + (int)threadIdx.x) * 4;
+            unsigned bin[4];
+            int n_act = 0;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const bool act = j + e < j1;
+                if (act && sv[u][e] > frame_id) future = true;
+                bin[e] = min((unsigned)frame_id - (unsigned)sv[u][e], (unsigned)(AGE_BINS - 1));
+                n_act += act ? 1 : 0;
+            }
+            const u64 m = __ballot(n_act > 0);
+            if (m) {   // uniform
+                const int first = __ffsll((unsigned long long)m) - 1;
+                const unsigned fbin = (unsigned)__shfl((int)bin[0], first);   // an active lane's first slot is active
+                bool same = true;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) same = same && (j + e >= j1 || bin[e] == fbin);
+                if (__all(same)) {
+                    int tot = n_act;
+#pragma unroll
+                    for (int off = 32; off >= 1; off >>= 1) tot += shfl_xor(tot, off);
+                    if (lane_id() == first) atomicAdd(&lhist[fbin], (unsigned)tot);
+                } else {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e)
+                        if (j + e < j1) atomicAdd(&lhist[bin[e]], 1u);
+                }
             }
         }
     }
@@ -938,11 +1024,12 @@ struct BlockScan {
     }
 };
 
-constexpr int PLAN_TOK_MAX = 8;   // tokens per thread kept in registers (n_new <= 2048; more are re-read)
+// PLAN_TOK_MAX: tokens per thread kept in registers (8: frames up to 2048 tokens; 16: up to 4096; longer frames are
+// re-read from memory in dependent loads).
 
 // PLAN_PER_MAX: slots per thread kept in registers (longer runs are re-read from memory); 16 for caches up to
 // 16 * 256 * NB slots per head, 64 beyond (a 64-frame world-model cache: 57 slots per thread).
-template <int PLAN_PER_MAX>
+template <int PLAN_PER_MAX, int PLAN_TOK_MAX>
 __global__ __launch_bounds__(PLAN_THREADS) void tc_plan_kernel(const int32_t *__restrict__ len,
                                                                const int32_t *__restrict__ stamp, int C, int n_new,
                                                                int frame_id, const int32_t *__restrict__ jstar,
@@ -1299,15 +1386,26 @@ __global__ __launch_bounds__(PLAN_THREADS) void tc_plan_kernel(const int32_t *__
     }
 }
 
-// workgroups per head of tc_plan_kernel and its dynamic LDS (the touched bitmap of one workgroup's slot range)
+// workgroups per head of tc_plan_kernel and its dynamic LDS (the touched bitmap of one workgroup's slot range).
+// The workgroups of a head wait for each other, so the whole grid has to be resident at once: a compute unit holds
+// eight workgroups of 256 threads, fewer when their LDS (bitmap + about 5 KB of static arrays) does not fit eight times
+// into its 160 KB, and three when the kernel's widest instantiation (160 vector registers) is the one launched: three is
+// what is counted on; the grid (nb + 1) * H stays within what 256 compute units hold.
+static size_t plan_lds_bytes(int C, int nb) { return ((size_t)((C + nb - 1) / nb + 3 + 31) / 32 + 2) * 4; }
 static int plan_nb(int H, int C) {
     int nb = (C + 2047) / 2048;
-    const int cap = PLAN_MAX_GRID / H > 0 ? PLAN_MAX_GRID / H : 1;
-    if (nb > cap) nb = cap;
     if (nb > PLAN_NB_MAX) nb = PLAN_NB_MAX;
-    return nb < 1 ? 1 : nb;
+    if (nb < 1) nb = 1;
+    for (; nb > 1; --nb) {
+        const size_t lds = plan_lds_bytes(C, nb) + 5 * 1024;
+        size_t per_cu = (size_t)160 * 1024 / lds;
+        if (per_cu > 3) per_cu = 3;
+        size_t resident = per_cu * 256;
+        if (resident > (size_t)PLAN_MAX_GRID) resident = PLAN_MAX_GRID;
+        if ((size_t)(nb + 1) * (size_t)H <= resident) break;
+    }
+    return nb;
 }
-static size_t plan_lds_bytes(int C, int nb) { return ((size_t)((C + nb - 1) / nb + 3 + 31) / 32 + 2) * 4; }
 
 // ---- apply ---------------------------------------------------------------------------------------------
 template <bool BF16, int D>
@@ -1420,6 +1518,11 @@ __global__ __launch_bounds__(256) void tc_apply_kernel(void *__restrict__ K, voi
         }
     } else if (a < n_unm - n_dropped) {
         dst = a < n_victims ? victims[tb + a] : L + (a - n_victims);
+        // A plan whose bounded wait ran out (stats[7] = 1) may have left victim positions unwritten: whatever they
+        // hold, nothing is stored outside the cache; such a token counts as not placed.
+        if ((unsigned)dst >= (unsigned)C) dst = -1;
+    }
+    if (!mg && dst >= 0) {
         RP::store_raw(K, cb + dst, l16, kraw);
         RP::store_raw(V, cb + dst, l16, vraw);
         if (l16 < r / 4) ((unsigned *)(code + (cb + dst) * r))[l16] = cw;
@@ -1516,20 +1619,27 @@ extern "C" int tempcache_compress(const fastar_cache *cache, const fastar_codec 
     if (window) {
         // the whole candidate window fits one workgroup's LDS: final arg-max per token in one launch
         if (const int rc0 = tempcache_setup(); rc0 != FASTAR_OK) return rc0;
-        const dim3 grid((n_new + 63) / 64, H);
+        // 256 tokens per workgroup when 64 would give more than two rounds of workgroups over the chip (the window is
+        // staged once per workgroup) and the window leaves room for the wider static arrays
+        const size_t per_cu = (size_t)160 * 1024 / (win_lds + 9 * 1024);
+        const bool wide = fused_encode && win_lds <= wide_window_lds_max(r) &&
+                          (size_t)((n_new + 63) / 64) * (size_t)H > 2 * 256 * (per_cu > 0 ? per_cu : 1);
+        const dim3 grid(wide ? (n_new + 255) / 256 : (n_new + 63) / 64, H);
         const bool bf = dtype == FASTAR_BF16;
         const VerifyArgs va = {cache->K, tau2_q16, merged, cache->stamp, frame_id, PS_HIST, PS_FUT};
         int rc = FASTAR_OK;
-#define FASTAR_WIN(RR, ENC, BF, DD, VER)                                                                                  \
-    rc = launch_match_window<RR, ENC, BF, DD, VER>(grid, win_lds, s, cache->code, cache->len, C, cp, n_new, cand, n_cand, \
-                                                   metric, jstar, sbest, win, grp, K_new, codec->R, codec->qscale,         \
-                                                   codec->shift, ck, plan_scratch, (int)PS_STRIDE, va)
+#define FASTAR_WIN(RR, ENC, BF, DD, VER, TT)                                                                              \
+    rc = launch_match_window<RR, ENC, BF, DD, VER, TT>(grid, win_lds, s, cache->code, cache->len, C, cp, n_new, cand,      \
+                                                       n_cand, metric, jstar, sbest, win, grp, K_new, codec->R,            \
+                                                       codec->qscale, codec->shift, ck, plan_scratch, (int)PS_STRIDE, va)
 #define FASTAR_WIN_ENC(RR, BF, DD)                                                      \
     do {                                                                                \
-        if (fused_verify) FASTAR_WIN(RR, true, BF, DD, true);                           \
-        else FASTAR_WIN(RR, true, BF, DD, false);                                       \
+        if (fused_verify && wide) FASTAR_WIN(RR, true, BF, DD, true, 256);              \
+        else if (fused_verify) FASTAR_WIN(RR, true, BF, DD, true, 64);                  \
+        else if (wide) FASTAR_WIN(RR, true, BF, DD, false, 256);                        \
+        else FASTAR_WIN(RR, true, BF, DD, false, 64);                                   \
     } while (0)
-        if (!fused_encode) { if (r == 32) FASTAR_WIN(32, false, true, 128, false); else FASTAR_WIN(64, false, true, 128, false); }
+        if (!fused_encode) { if (r == 32) FASTAR_WIN(32, false, true, 128, false, 64); else FASTAR_WIN(64, false, true, 128, false, 64); }
         else if (r == 32 && d == 128) { if (bf) FASTAR_WIN_ENC(32, true, 128); else FASTAR_WIN_ENC(32, false, 128); }
         else if (r == 32) { if (bf) FASTAR_WIN_ENC(32, true, 64); else FASTAR_WIN_ENC(32, false, 64); }
         else if (d == 128) { if (bf) FASTAR_WIN_ENC(64, true, 128); else FASTAR_WIN_ENC(64, false, 128); }
@@ -1574,14 +1684,19 @@ extern "C" int tempcache_compress(const fastar_cache *cache, const fastar_codec 
                   grp, merged, cache->len, cache->stamp, frame_id, plan_scratch, PS_HIST, PS_FUT, PS_STRIDE);
         FASTAR_LAUNCH_CHECK();
     }
-    if (((C + nb - 1) / nb + PLAN_THREADS - 1) / PLAN_THREADS <= 16)
-        hipLaunchKernelGGL(tc_plan_kernel<16>, dim3(nb + 1, H), dim3(PLAN_THREADS), plan_lds_bytes(C, nb), s, cache->len,
-                           cache->stamp, C, n_new, frame_id, jstar, merged, win, rank, victims, hs, stats, plan_scratch,
-                           ws_persistent);
-    else
-        hipLaunchKernelGGL(tc_plan_kernel<64>, dim3(nb + 1, H), dim3(PLAN_THREADS), plan_lds_bytes(C, nb), s, cache->len,
-                           cache->stamp, C, n_new, frame_id, jstar, merged, win, rank, victims, hs, stats, plan_scratch,
-                           ws_persistent);
+    {
+        const bool long_runs = ((C + nb - 1) / nb + PLAN_THREADS - 1) / PLAN_THREADS > 16;
+        const bool long_frame = n_new > 8 * PLAN_THREADS;
+#define FASTAR_PLAN(PM, TM)                                                                                            \
+    hipLaunchKernelGGL((tc_plan_kernel<PM, TM>), dim3(nb + 1, H), dim3(PLAN_THREADS), plan_lds_bytes(C, nb), s, cache->len, \
+                       cache->stamp, C, n_new, frame_id, jstar, merged, win, rank, victims, hs, stats, plan_scratch,   \
+                       ws_persistent)
+        if (long_runs && long_frame) FASTAR_PLAN(64, 16);
+        else if (long_runs) FASTAR_PLAN(64, 8);
+        else if (long_frame) FASTAR_PLAN(16, 16);
+        else FASTAR_PLAN(16, 8);
+#undef FASTAR_PLAN
+    }
     FASTAR_LAUNCH_CHECK();
     FASTAR_TC(tc_apply_kernel, cache->K, cache->V, cache->code, cache->cnt, cache->stamp, C, r, K_new, V_new, ck, n_new,
               frame_id, jstar, merged, win, grp, rank, victims, hs, merge_map, cache->len, rep_mode, plan_scratch,

@@ -35,5 +35,8 @@ def test_roofline_kernel_name_follows_the_dispatch_rule():
 def test_traffic_figure_is_read_from_the_committed_profile():
     sys.path.insert(0, ROOT)
     import bench
-    t = bench.profiled_traffic_bytes()
+    t, src = bench.profiled_traffic("cfg2")
     assert t is not None and 50e6 < t < 400e6               # fetch + write of one self-attention launch at cfg2
+    assert src == "profiles/cfg2_chunk_step_hbm_traffic.txt"
+    # a workload without a committed counter summary reports no traffic rather than another workload's
+    assert bench.profiled_traffic("cfg5") == (None, None)

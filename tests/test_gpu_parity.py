@@ -35,9 +35,13 @@ def test_init_is_idempotent_and_optional():
 
 @pytest.mark.parametrize("dtype,d,r,n", [("fp32", 64, 32, 515), ("bf16", 128, 32, 4681), ("bf16", 64, 64, 33),
                                          ("fp32", 128, 64, 1000), ("bf16", 128, 32, 1), ("fp32", 64, 32, 16)])
-def test_encode_bit_exact(dtype, d, r, n):
+@pytest.mark.parametrize("shift", [4, 6, 8, 9, 1])
+def test_encode_bit_exact(dtype, d, r, n, shift):
+    # shift: the precision ladder of the quantisation ablation (4: the default, about 8 significant bits; 6; 8; 9:
+    # codes in {-1, 0, 1}; 1: nearly everything saturates)
     rng = np.random.default_rng(d * 1000 + r + n)
     codec = make_codec(0, 7, d, r)
+    codec.shift = shift
     x = (rng.standard_normal((n, d)) * 1.3).astype(np.float32)
     x[0, :4] = [100.0, -100.0, 0.0, 4.5]                       # saturation and exact grid points
     xs = to_storage(x, dtype)
@@ -481,7 +485,7 @@ def test_dense_limit_on_clustered_data_fp32_and_bf16():
 # ----------------------------------------------------------------------------------------- TempCache
 
 def run_rollout(name, n_frames, C, tau, dtype=None, H=None, windowed=True, metric=0, probe_queries=False, rep_mode=0,
-                persistent=False, r=None):
+                persistent=False, r=None, shift=None):
     over = {}
     if dtype:
         over["dtype"] = dtype
@@ -492,6 +496,8 @@ def run_rollout(name, n_frames, C, tau, dtype=None, H=None, windowed=True, metri
         c["H"] = H
     fs = FrameStream(c["seed"], c["cfg_id"], c["H"], c["d"], c["T"], c["n_c"], c["p"], c["sigma_d"], c["dtype"])
     codec = make_codec(c["seed"], c["cfg_id"], c["d"], c["r"])
+    if shift:
+        codec.shift = shift
     ref = oracle.Cache.empty(c["H"], C, c["d"], c["r"], c["dtype"])
     gpu = dev_cache(ref)
     dcodec = dev_codec(codec)
@@ -670,6 +676,53 @@ def test_tempcache_candidate_list_is_a_set_and_ties_go_to_the_smallest_slot(orde
     assert_cache_equal(host_cache(gpu), ref, VTOL["fp32"])
 
 
+@pytest.mark.parametrize("dtype,d,r,H,T,n_cand,persistent", [
+    ("bf16", 128, 32, 24, 1501, 3000, True), ("bf16", 128, 32, 24, 1501, 3000, False),
+    ("fp32", 64, 64, 22, 1530, 1800, True), ("bf16", 64, 32, 26, 1300, 3500, True)])
+def test_tempcache_many_workgroups_take_the_wide_window_kernel(dtype, d, r, H, T, n_cand, persistent):
+    # more than two rounds of 64-token workgroups over the chip with a window that fills a compute unit's LDS: the
+    # launcher takes the instantiation with 256 tokens per workgroup (ragged last workgroup, shuffled lists with
+    # repeats and dead ids, repeated keys, two calls on one workspace)
+    rng = np.random.default_rng(d + r + H + n_cand)
+    C = 5000
+    codec = make_codec(0, 9, d, r)
+    as_dt = lambda a: to_storage(a.astype(np.float32), dtype)
+    ref = oracle.Cache.empty(H, C, d, r, dtype)
+    ref.K[:] = as_dt(rng.standard_normal((H, C, d)))
+    ref.K[:, 2000:2600] = ref.K[:, 0:600]                        # repeated keys: equally scored candidates
+    ref.V[:] = as_dt(rng.standard_normal((H, C, d)))
+    ref.code[:] = oracle.encode(ref.K, codec.R, codec.qscale, codec.shift)
+    ref.cnt[:] = rng.integers(1, 4, size=(H, C))
+    ref.stamp[:] = rng.integers(0, 9, size=(H, C))
+    ref.len[:] = rng.integers(3800, 4400, size=H)
+    gpu = dev_cache(ref)
+    ws = torch.zeros(fa.workspace_bytes(fa.OP_COMPRESS, H, T, C, r), dtype=torch.uint8, device="cuda")
+    cand = None
+    for f in (9, 10):
+        K_new = as_dt(rng.standard_normal((H, T, d)))
+        src = rng.integers(0, 3700, size=(H, T))
+        for h in range(H):
+            K_new[h, :1000] = ref.K[h, src[h, :1000]]             # most of the frame repeats live slots
+        V_new = as_dt(rng.standard_normal((H, T, d)))
+        if cand is None:
+            cand = rng.integers(0, 4500, size=(H, n_cand)).astype(np.int32)
+            cand[:, :1000] = src[:, :1000]
+            cand[:, 1000:1400] = rng.integers(2000, 2600, size=(H, 400))
+            cand[:, ::19] = -1
+            cand = np.stack([row[rng.permutation(n_cand)] for row in cand])
+        args = dict(tau2_q16=TAU2(0.9), frame_id=f)
+        mm_r, mg_r, st_r = oracle.tempcache_compress(ref, codec.R, codec.qscale, codec.shift, K_new, V_new, cand=cand, **args)
+        mm_g, mg_g, st_g = fa.tempcache_compress(gpu, dev_codec(codec), to_dev(K_new), to_dev(V_new), cand=to_dev(cand),
+                                                 ws=ws, ws_persistent=persistent, **args)
+        sync()
+        assert mg_r.sum() > 100 * H
+        assert np.array_equal(to_host(st_g), st_r), f"stats, frame {f}"
+        assert np.array_equal(to_host(mg_g), mg_r), f"merged flags, frame {f}"
+        assert np.array_equal(to_host(mm_g), mm_r), f"merge map, frame {f}"
+        assert_cache_equal(host_cache(gpu), ref, VTOL[dtype])
+        cand = np.ascontiguousarray(np.concatenate([mm_r, mm_r[:, : n_cand - T]], axis=1)[:, :n_cand])
+
+
 @pytest.mark.parametrize("name,dtype,H,frames,C", [("cfg1", None, None, 6, 6 * 256), ("cfg1", "bf16", None, 6, 3 * 256),
                                                    ("cfg2", None, 2, 4, 3 * 1560)])
 def test_tempcache_mean_key_representative_bit_exact(name, dtype, H, frames, C):
@@ -777,6 +830,28 @@ def test_tempcache_rollout_on_a_persistent_workspace(name, dtype, H, frames, C, 
     # the workspace is zero-filled once and every call leaves it clean: the match launch goes straight on to the
     # threshold test (no clearing launch); merges, big groups, evictions and drops must come out bit for bit the same
     c, fs, codec, ref, gpu = run_rollout(name, frames, C, tau, dtype=dtype, H=H, rep_mode=rep, persistent=True)
+
+
+@pytest.mark.parametrize("shift", [4, 6, 8, 9])
+def test_code_precision_ladder_rollout_and_selection_bit_exact(shift):
+    # appendix ablation "Quantization precision for ANN matching": every code precision that the benchmark reports
+    # (bench.py --code-shift) runs the whole index path here: TempCache rollout (match, threshold, evictions: the
+    # coarser the codes, the more equally scored candidates), query codes, AnnSA and AnnCA selections
+    c, fs, codec, ref, gpu = run_rollout("cfg1", 6, 4 * 256, 0.98, dtype="bf16", persistent=True, shift=shift)
+    Q = fs.queries(1)
+    qc_r = oracle.encode(Q, codec.R, codec.qscale, codec.shift)
+    qc = fa.encode(to_dev(Q), dev_codec(codec))
+    assert np.array_equal(to_host(qc), qc_r)
+    sel_r, nsel_r = oracle.ann_select_self(qc_r, ref.code, ref.len, c["BQ"], c["n_rep"], c["BK"], 5)
+    sel, nsel = fa.ann_select_self(qc, gpu.code, gpu.len, c["BQ"], c["n_rep"], c["BK"], 5)
+    assert np.array_equal(to_host(sel), sel_r) and np.array_equal(to_host(nsel), nsel_r)
+    pk = to_storage(np.random.default_rng(shift).standard_normal((c["H"], 96, c["d"])).astype(np.float32), "bf16")
+    pc_r = oracle.encode(pk, codec.R, codec.qscale, codec.shift)
+    pc = fa.encode(to_dev(pk), dev_codec(codec))
+    assert np.array_equal(to_host(pc), pc_r)
+    csel_r, cnsel_r = oracle.ann_select_cross(qc_r, pc_r, c["BQ"], 16)
+    csel, cnsel = fa.ann_select_cross(qc, pc, c["BQ"], 16)
+    assert np.array_equal(to_host(csel), csel_r) and np.array_equal(to_host(cnsel), cnsel_r)
 
 
 @pytest.mark.parametrize("dtype,persistent", [("fp32", True), ("bf16", True), ("bf16", False)])
