@@ -15,9 +15,11 @@
 namespace fastar {
 
 constexpr int KB_PER_WG = 4;      // key blocks scored by one workgroup of score_self_kernel
-constexpr int KB_PER_WG_LONG = 16; // the same for long caches (at least 4096 such workgroups)
+constexpr int KB_PER_WG_LONG = 32; // the same for long caches (streaming kernel)
+constexpr size_t LONG_CACHE_BLOCKS = 16 * 4096;   // key blocks over all heads from which the streaming kernel pays
 constexpr int COL_CHUNK = 8;       // summary column blocks (of 32) kept in registers at a time
 constexpr int TOPK_LDS_CAP = 8192; // row entries cached in LDS by topk_kernel
+constexpr int TOPK_KPT = 16;       // rows of up to 256 * TOPK_KPT entries are selected from registers
 
 static inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
@@ -174,12 +176,14 @@ __global__ __launch_bounds__(256) void score_self_stream_kernel(const int8_t *__
     const int NR = n_qb * n_rep;
     const int NCB = (NR + 31) / 32;
     const int g = BQ / n_rep;
+    const int rep_shift = __ffs(n_rep) - 1;   // n_rep is a power of two
     const int8_t *kc = kcode + (size_t)h * C * R;
     const int8_t *rp = rep + (size_t)h * NR * R;
     // rounds of 64 keys (two groups of 32): key block wave + 4 * (it / rpk), keys 64 * (it % rpk) .. of it
     const int rpk = (BK + 63) / 64;
     const int n_it = ((KBW - wave + 3) / 4) * rpk;
     auto load_round = [&](int it, i32x4 (&a)[2][KS]) __attribute__((always_inline)) {
+        it = min(it, n_it - 1);   // rounds past the wavefront's share re-read its last one (cache hits), never other blocks
         const int kb = kb0 + wave + 4 * (it / rpk), sg0 = 64 * (it % rpk);
 #pragma unroll
         for (int q = 0; q < 2; ++q) {
@@ -204,6 +208,18 @@ __global__ __launch_bounds__(256) void score_self_stream_kernel(const int8_t *__
         // Four operand buffers in rotation, three rounds ahead: 6 KB of codes per wavefront are in flight while a
         // round is scored (the rotation is unrolled: copying a buffer would wait for its loads).
         int best[CC];
+        // what this lane's summary column of every column block stands for: its query block and whether it is the
+        // block's first summary; columns past the summaries or of a run without a query never count
+        int col_b[CC];
+        bool col_ok[CC], col_first[CC];
+#pragma unroll
+        for (int c = 0; c < CC; ++c) {
+            const int rc = (cb0 + c) * 32 + col;
+            col_b[c] = rc >> rep_shift;
+            const int u = rc & (n_rep - 1);
+            col_ok[c] = rc < NR && col_b[c] * BQ + u * g < n_q;
+            col_first[c] = rc < NR && u == 0 && g2 == 0;
+        }
         auto score_round = [&](int it, const i32x4 (&cur)[2][KS]) __attribute__((always_inline)) {
             const int kl = wave + 4 * (it / rpk), sg0 = 64 * (it % rpk);
             const int kb = kb0 + kl;
@@ -244,11 +260,9 @@ __global__ __launch_bounds__(256) void score_self_stream_kernel(const int8_t *__
                 for (int c = 0; c < CC; ++c) {
                     if (cb0 + c < NCB) {
                         int m = max(best[c], shfl_xor(best[c], 32));
-                        const int rc = (cb0 + c) * 32 + col;
-                        const int b = rc / n_rep, u = rc % n_rep;
-                        if (rc >= NR || b * BQ + u * g >= n_q) m = INT_MIN;
+                        if (!col_ok[c]) m = INT_MIN;
                         for (int off = 1; off < n_rep; off <<= 1) m = max(m, shfl_xor(m, off));
-                        if (g2 == 0 && u == 0 && rc < NR) tile[b * KBW + kl] = m;
+                        if (col_first[c]) tile[col_b[c] * KBW + kl] = m;
                     }
                 }
             }
@@ -300,6 +314,85 @@ __device__ __forceinline__ void topk_row(const int32_t *row, int n, int n_sel, i
         return;
     }
     auto to_key = [](int32_t sc) -> unsigned { return (unsigned)(max(sc, -(1 << 21)) + (1 << 21)); };
+    if (n > 1024 && n <= TOPK_KPT * 256) {
+        // Rows of 1025 to 4096 scores (shorter ones are done sooner by the three radix passes below, which take a
+        // barrier per 256 entries in their compaction; longer ones do not fit the registers): each thread owns a run of consecutive entries and keeps
+        // their keys in registers (key + 1, so that 0 stands for "no entry").  The k-th largest key is built bit by
+        // bit (23 rounds of "how many keys reach this value": one compare per key, the wavefront's count through
+        // scalar bit counts of the compare masks, one barrier per round), then one block scan of the per-thread
+        // (greater, equal) counts places every selected index: 26 barriers in all, no atomics.
+        const int kpt = (n + 255) / 256;
+        unsigned my[TOPK_KPT];
+        if (keys != nullptr) {   // row in global memory: coalesced loads, all in flight at once, staged through LDS
+            int32_t v[TOPK_KPT];
+#pragma unroll
+            for (int e = 0; e < TOPK_KPT; ++e) {
+                const int t = e * 256 + tid;
+                v[e] = t < n ? row[t] : 0;
+            }
+#pragma unroll
+            for (int e = 0; e < TOPK_KPT; ++e) {
+                const int t = e * 256 + tid;
+                if (t < n) keys[t] = to_key(v[e]);
+            }
+            __syncthreads();
+#pragma unroll
+            for (int e = 0; e < TOPK_KPT; ++e) {
+                const int i = tid * kpt + e;
+                my[e] = (e < kpt && i < n) ? keys[i] + 1u : 0u;
+            }
+        } else {
+#pragma unroll
+            for (int e = 0; e < TOPK_KPT; ++e) {
+                const int i = tid * kpt + e;
+                my[e] = (e < kpt && i < n) ? to_key(row[i]) + 1u : 0u;
+            }
+        }
+        __shared__ unsigned cnt_w[2][4];
+        auto count_ge = [&](unsigned cand, int buf) -> unsigned {   // entries with key + 1 >= cand, over the workgroup
+            unsigned c = 0;
+#pragma unroll
+            for (int e = 0; e < TOPK_KPT; ++e) c += (unsigned)__popcll(__ballot(my[e] >= cand));
+            if (lane == 0) cnt_w[buf][wave] = c;
+            __syncthreads();
+            return cnt_w[buf][0] + cnt_w[buf][1] + cnt_w[buf][2] + cnt_w[buf][3];
+        };
+        unsigned T = 0;
+        int round = 0;
+        for (int bit = 22; bit >= 0; --bit, ++round) {
+            const unsigned cand = T | (1u << bit);
+            if (count_ge(cand, round & 1) >= (unsigned)k) T = cand;
+        }
+        const unsigned need = (unsigned)k - count_ge(T + 1u, round & 1);   // ties at T that belong to the selection
+        unsigned n_gt = 0, n_eq = 0;
+#pragma unroll
+        for (int e = 0; e < TOPK_KPT; ++e) {
+            n_gt += my[e] > T ? 1u : 0u;
+            n_eq += my[e] == T ? 1u : 0u;
+        }
+        const unsigned packed = (n_gt << 16) | n_eq;   // both totals stay below 4097
+        unsigned incl = packed;
+#pragma unroll
+        for (int off = 1; off < 64; off <<= 1) {
+            const unsigned o = __shfl_up(incl, off, WAVE);
+            if (lane >= off) incl += o;
+        }
+        if (lane == 63) wtot_a[wave] = incl;
+        __syncthreads();
+        unsigned excl = incl - packed;
+#pragma unroll
+        for (int w = 0; w < 4; ++w)
+            if (w < wave) excl += wtot_a[w];
+        unsigned eq_rank = excl & 0xFFFFu;
+        unsigned pos = (excl >> 16) + min(eq_rank, need);
+#pragma unroll
+        for (int e = 0; e < TOPK_KPT; ++e) {
+            const bool take = my[e] > T || (my[e] == T && eq_rank < need);
+            if (my[e] == T) eq_rank += 1;
+            if (take) out[pos++] = tid * kpt + e;
+        }
+        return;
+    }
     const bool cached = keys != nullptr && n <= TOPK_LDS_CAP;
     if (cached) {
         for (int t0 = 0; t0 < n; t0 += 4 * 256) {   // four loads in flight per thread
@@ -822,7 +915,7 @@ static int select_self_impl(const int8_t *qcode, int n_q, const int8_t *kcode, c
     // the streaming kernel pays when there are thousands of its workgroups and the summaries fit four column blocks
     // (measured: 121 against 126 us at 40 heads x 3600 blocks; with fewer, wider workgroups the plain kernel wins)
     const bool few_cols = (n_qb * n_rep + 31) / 32 <= 4;
-    const int kbw = (few_cols && (size_t)n_kb_cap * H >= (size_t)KB_PER_WG_LONG * 4096) ? KB_PER_WG_LONG : KB_PER_WG;
+    const int kbw = (few_cols && (size_t)n_kb_cap * H >= LONG_CACHE_BLOCKS) ? KB_PER_WG_LONG : KB_PER_WG;
     const size_t tile_bytes = (size_t)n_qb * kbw * sizeof(int32_t);
     if (tile_bytes > 64 * 1024) return FASTAR_ERR_UNSUPPORTED;
     const SelfWs w = self_ws(H, n_q, C, r, BQ, BK, n_rep);
