@@ -38,7 +38,8 @@ def _load():
         _lib = ctypes.CDLL(_LIB)
         for name in ("oracle_encode", "oracle_tempcache_compress", "oracle_ann_select_self",
                      "oracle_ann_select_cross", "oracle_sparse_attn_fwd", "oracle_recall_density",
-                     "oracle_encode_sign", "oracle_ann_select_lsh"):
+                     "oracle_encode_sign", "oracle_ann_select_lsh", "oracle_fp8_encode", "oracle_fp8_decode",
+                     "oracle_kv_to_fp8", "oracle_sparse_attn_fwd_fp8"):
             getattr(_lib, name).restype = ctypes.c_int
     return _lib
 
@@ -250,3 +251,57 @@ def full_selection(H: int, n_q: int, BQ: int, length, BK: int):
         sel[h, :, :m] = np.arange(m, dtype=np.int32)
         nsel[h, :] = m
     return sel, nsel
+
+
+# ---------------------------------------------------------------------------------------------- fp8 K/V
+
+
+def fp8_encode(x: np.ndarray) -> np.ndarray:
+    """float32 values -> E4M3 codes (uint8), nearest with ties to even, saturating at 448."""
+    x = _c(x, np.float32)
+    code = np.empty(x.shape, np.uint8)
+    _check(_load().oracle_fp8_encode(_p(x), ctypes.c_int64(x.size), _p(code)), "oracle_fp8_encode")
+    return code
+
+
+def fp8_decode(code: np.ndarray) -> np.ndarray:
+    """E4M3 codes -> their exact values (float64)."""
+    code = _c(code, np.uint8)
+    x = np.empty(code.shape, np.float64)
+    _check(_load().oracle_fp8_decode(_p(code), ctypes.c_int64(code.size), _p(x)), "oracle_fp8_decode")
+    return x
+
+
+def kv8_empty(H: int, C: int, d: int):
+    """Zero-filled (K8 [H,Cp,d], V8T [H,Cp/64,d,64]) for a cache of capacity C."""
+    n_blk = (C + 63) // 64
+    return np.zeros((H, n_blk * 64, d), np.uint8), np.zeros((H, n_blk, d, 64), np.uint8)
+
+
+def kv_to_fp8(cache: Cache, K8: np.ndarray, V8T: np.ndarray, stamp_lo: int = -2 ** 31):
+    """(Re)write in place the blocks of the 8-bit cache copy that hold a live slot with stamp >= stamp_lo."""
+    H, C, d = cache.K.shape
+    n_blk = (C + 63) // 64
+    assert K8.shape == (H, n_blk * 64, d) and V8T.shape == (H, n_blk, d, 64)
+    assert K8.dtype == np.uint8 and V8T.dtype == np.uint8 and K8.flags.c_contiguous and V8T.flags.c_contiguous
+    rc = _load().oracle_kv_to_fp8(_p(_c(cache.K)), _p(_c(cache.V)), _p(_c(cache.stamp, np.int32)),
+                                  _p(_c(cache.len, np.int32)), H, C, d, _dtype_code(cache.K), ctypes.c_int32(stamp_lo),
+                                  _p(K8), _p(V8T))
+    _check(rc, "oracle_kv_to_fp8")
+
+
+def sparse_attn_fwd_fp8(Q, K8, V8T, cnt, length, C: int, sel, nsel, BQ: int, BK: int, scale: float):
+    """Attention over the 8-bit cache copy: (O [H,n_q,d] float64, lse [H,n_q] float64)."""
+    Q = _c(Q)
+    H, n_q, d = Q.shape
+    sel = _c(sel, np.int32)
+    nsel = _c(nsel, np.int32)
+    n_sel = sel.shape[2]
+    O = np.empty((H, n_q, d), np.float64)
+    lse = np.empty((H, n_q), np.float64)
+    rc = _load().oracle_sparse_attn_fwd_fp8(_p(Q), n_q, _p(_c(K8, np.uint8)), _p(_c(V8T, np.uint8)),
+                                            _p(None if cnt is None else _c(cnt, np.int32)), _p(_c(length, np.int32)), H, C,
+                                            d, _dtype_code(Q), _p(sel), _p(nsel), BQ, BK, n_sel, ctypes.c_double(scale),
+                                            _p(O), _p(lse))
+    _check(rc, "oracle_sparse_attn_fwd_fp8")
+    return O, lse

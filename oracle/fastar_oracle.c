@@ -31,6 +31,11 @@
  *   oracle_sparse_attn_fwd     Eq. (1) restricted to the candidate set (Sec. 5.1 display), with the
  *                              +log m_t logit shift of Lemma 1.
  *   oracle_recall_density      attention recall / density as defined in the Metrics paragraph.
+ *   oracle_fp8_encode/decode,  Sec. 5.1, quantised-search paragraph and the appendix ablation "Quantization precision for
+ *   oracle_kv_to_fp8,          ANN matching" name low-bit storage of keys; here the 8-bit floating-point format E4M3
+ *   oracle_sparse_attn_fwd_fp8 (OCP "FN": 4 exponent bits, bias 7, 3 mantissa bits, no infinities, largest finite 448) is
+ *                              the storage of K and V for the attention itself: the same attention on the exact
+ *                              values of the quantised keys, values and queries.
  *
  * Parity pins (tests/test_oracle_*.py): dense softmax attention written independently in
  * numpy, Lemma 1 on exact duplicates, brute-force nearest neighbours and top-k, closed-form
@@ -705,4 +710,124 @@ int oracle_recall_density(const void *Q, int n_q, const void *K, const int32_t *
     out[0] = n_queries ? recall_sum / (double)n_queries : 0.0;
     out[1] = pairs_all > 0 ? pairs_sel / pairs_all : 0.0;
     return 0;
+}
+
+/* ------------------------------------------------------------------ 8-bit floating-point K/V (E4M3) */
+
+/* Value of an E4M3 code (OCP FN variant): sign bit, 4 exponent bits with bias 7, 3 mantissa bits; exponent 0 holds
+ * the subnormals m/8 * 2^-6; the all-ones pattern of exponent and mantissa is NaN; there is no infinity. */
+static double fp8_value(uint8_t c) {
+    const int sign = c >> 7, e = (c >> 3) & 15, m = c & 7;
+    double v;
+    if (e == 15 && m == 7) return NAN;
+    if (e == 0)
+        v = ldexp((double)m / 8.0, -6);
+    else
+        v = ldexp(1.0 + (double)m / 8.0, e - 7);
+    return sign ? -v : v;
+}
+
+/* Nearest E4M3 code of a finite x, ties to the even mantissa, magnitudes beyond the largest finite value (448)
+ * saturate to it.  Found by plain search over the 127 non-negative finite codes, not by bit tricks. */
+static uint8_t fp8_code(float x) {
+    const double a = fabs((double)x);
+    int best = 0;
+    double best_err = a; /* code 0 = +0 */
+    for (int c = 1; c <= 0x7E; ++c) {
+        const double err = fabs(a - fp8_value((uint8_t)c));
+        if (err < best_err || (err == best_err && (c & 1) == 0 && (best & 1) == 1)) {
+            best = c;
+            best_err = err;
+        }
+    }
+    if (a >= 448.0) best = 0x7E;
+    return (uint8_t)(best | (signbit(x) ? 0x80 : 0));
+}
+
+int oracle_fp8_encode(const float *x, int64_t n, uint8_t *code) {
+    if (!x || !code) return -1;
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < n; ++i) code[i] = fp8_code(x[i]);
+    return 0;
+}
+
+int oracle_fp8_decode(const uint8_t *code, int64_t n, double *x) {
+    if (!x || !code) return -1;
+    for (int64_t i = 0; i < n; ++i) x[i] = fp8_value(code[i]);
+    return 0;
+}
+
+/*
+ * The 8-bit copy of the cache that the fp8 attention reads, in its layout:
+ *   K8  [H, Cp, d]            E4M3 code of every key coordinate, rows as in K (Cp = C rounded up to a multiple of 64)
+ *   V8T [H, Cp/64, d, 64]     per block of 64 slots the values transposed: element (h, blk, t, j) = V[h][64 blk + j][t]
+ * Only the blocks that hold a live slot whose stamp is >= stamp_lo are (re)written, whole: their live slots with the
+ * codes of the stored K / V, their dead slots (>= len) with zero.  stamp_lo <= the smallest stamp rewrites everything.
+ */
+int oracle_kv_to_fp8(const void *K, const void *V, const int32_t *stamp, const int32_t *len, int H, int C, int d,
+                     int dtype, int32_t stamp_lo, uint8_t *K8, uint8_t *V8T) {
+    if (!K || !V || !stamp || !len || !K8 || !V8T || H <= 0 || C <= 0 || d <= 0) return -1;
+    const int n_blk = (C + 63) / 64;
+    const int64_t Cp = (int64_t)n_blk * 64;
+#pragma omp parallel for collapse(2) schedule(static)
+    for (int h = 0; h < H; ++h) {
+        for (int blk = 0; blk < n_blk; ++blk) {
+            const int L = len[h] < C ? len[h] : C;
+            int dirty = 0;
+            for (int j = 0; j < 64; ++j) {
+                const int slot = blk * 64 + j;
+                if (slot < L && stamp[(int64_t)h * C + slot] >= stamp_lo) dirty = 1;
+            }
+            if (!dirty) continue;
+            for (int j = 0; j < 64; ++j) {
+                const int slot = blk * 64 + j;
+                for (int t = 0; t < d; ++t) {
+                    uint8_t ck = 0, cv = 0;
+                    if (slot < L) {
+                        ck = fp8_code(load_f32(K, dtype, ((int64_t)h * C + slot) * d + t));
+                        cv = fp8_code(load_f32(V, dtype, ((int64_t)h * C + slot) * d + t));
+                    }
+                    K8[((int64_t)h * Cp + slot) * d + t] = ck;
+                    V8T[(((int64_t)h * n_blk + blk) * d + t) * 64 + j] = cv;
+                }
+            }
+        }
+    }
+    return 0;
+}
+
+/*
+ * Attention over the 8-bit cache: oracle_sparse_attn_fwd on the exact values of the E4M3 codes of K and V and of
+ * the queries rounded to E4M3 (the kernel feeds both operands of the score product in that format); logits,
+ * softmax and the weighted sum in fp64 as everywhere.  Q [H,n_q,d] (dtype), K8 / V8T as oracle_kv_to_fp8 writes
+ * them, BK must be 64.
+ */
+int oracle_sparse_attn_fwd_fp8(const void *Q, int n_q, const uint8_t *K8, const uint8_t *V8T, const int32_t *cnt,
+                               const int32_t *len, int H, int C, int d, int dtype, const int32_t *sel,
+                               const int32_t *nsel, int BQ, int BK, int n_sel, double scale, double *O, double *lse) {
+    if (!Q || !K8 || !V8T || BK != 64) return -1;
+    const int n_blk = (C + 63) / 64;
+    const int64_t Cp = (int64_t)n_blk * 64;
+    float *Kf = malloc(sizeof(float) * (size_t)H * C * d);
+    float *Vf = malloc(sizeof(float) * (size_t)H * C * d);
+    float *Qf = malloc(sizeof(float) * (size_t)H * n_q * d);
+    if (!Kf || !Vf || !Qf) {
+        free(Kf);
+        free(Vf);
+        free(Qf);
+        return -5;
+    }
+    for (int h = 0; h < H; ++h)
+        for (int slot = 0; slot < C; ++slot)
+            for (int t = 0; t < d; ++t) {
+                Kf[((int64_t)h * C + slot) * d + t] = (float)fp8_value(K8[((int64_t)h * Cp + slot) * d + t]);
+                Vf[((int64_t)h * C + slot) * d + t] =
+                    (float)fp8_value(V8T[(((int64_t)h * n_blk + slot / 64) * d + t) * 64 + slot % 64]);
+            }
+    for (int64_t i = 0; i < (int64_t)H * n_q * d; ++i) Qf[i] = (float)fp8_value(fp8_code(load_f32(Q, dtype, i)));
+    const int rc = oracle_sparse_attn_fwd(Qf, n_q, Kf, Vf, cnt, len, H, C, d, 0, sel, nsel, BQ, BK, n_sel, scale, O, lse);
+    free(Kf);
+    free(Vf);
+    free(Qf);
+    return rc;
 }
