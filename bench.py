@@ -32,6 +32,7 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 matrix-core peak
+PEAK_FP8_TFLOPS = 5000.0    # MI355X dense 8-bit floating-point matrix-core peak
 PEAK_HBM_GBS = 8000.0       # MI355X HBM3E peak
 
 
@@ -60,6 +61,9 @@ def parse():
                     help="candidate list handed to tempcache_compress: the previous call's merge map as it is (the "
                          "kernel sorts it) or sorted ascending by the caller first (one torch sort per frame, untimed "
                          "work it is not: it runs inside the step)")
+    ap.add_argument("--kv", choices=["bf16", "fp8"], default="bf16",
+                    help="self-attention over the bf16 cache (default) or over its 8-bit floating-point (E4M3) copy, "
+                         "which fastar_kv_to_fp8 brings up to date after the chunk's TempCache calls")
     ap.add_argument("--rep", choices=["last", "mean"], default="last",
                     help="representative key of a merged group: the last key (the method) or the mean key (its ablation)")
     ap.add_argument("--prefill-frames", type=int, default=None, help="frames merged into the cache before timing")
@@ -85,6 +89,7 @@ class ChunkPipeline:
         self.t, self.fa, self.cfg = torch, fa, cfg
         self.ws_persistent = ws_persistent
         self.sorted_cand = False
+        self.kv8 = None        # (K8, V8T) when the self-attention runs over the 8-bit copy of the cache
         self.rep_mode = rep_mode
         self.fused_cross = fused_cross
         H, d, r, T = cfg["H"], cfg["d"], cfg["r"], cfg["T"]
@@ -143,9 +148,13 @@ class ChunkPipeline:
         fa = self.fa
         mark = ev if ev is not None else (lambda name: None)
         mark("start")
+        first_frame = self.frame_id
         for K, V in frames:
             self.compress(K, V)
         mark("compress")
+        if self.kv8 is not None:
+            fa.kv_to_fp8(self.cache, self.kv8[0], self.kv8[1], stamp_lo=first_frame)
+        mark("quantize")
         fa.encode(Q, self.codec, out=self.qcode)
         if self.Rb is not None:
             fa.encode_sign(Q, self.Rb, self.codec.qscale, out=self.qbits)
@@ -158,8 +167,12 @@ class ChunkPipeline:
             fa.ann_select_self(self.qcode, self.cache.code, self.cache.len, self.BQ, self.n_rep, self.BK, self.n_sel,
                                ws=self.ws_s, out=self.sel)
         mark("select_self")
-        fa.sparse_attn_fwd(Q, self.cache.K, self.cache.V, self.cache.cnt, self.cache.len, self.sel[0], self.sel[1],
-                           self.BQ, self.BK, self.scale, out=self.O)
+        if self.kv8 is not None:
+            fa.sparse_attn_fwd_fp8(Q, self.kv8[0], self.kv8[1], self.cache.cnt, self.cache.len, self.C, self.sel[0],
+                                   self.sel[1], self.BQ, self.BK, self.scale, out=self.O)
+        else:
+            fa.sparse_attn_fwd(Q, self.cache.K, self.cache.V, self.cache.cnt, self.cache.len, self.sel[0], self.sel[1],
+                               self.BQ, self.BK, self.scale, out=self.O)
         mark("attn_self")
         if self.fused_cross:   # selection and attention over it in one launch; the stage is booked under select_cross
             fa.ann_cross_attn_fwd(Q, self.qcode, self.pK, self.pV, self.pcode, self.BQ, self.n_sel_cross, self.scale,
@@ -180,13 +193,19 @@ class ChunkPipeline:
         nsel = t.full((self.H, self.n_qb), n_live, dtype=t.int32, device=Q.device)
         O = t.empty_like(Q)
         lse = t.empty(Q.shape[:2], dtype=t.float32, device=Q.device)
-        self.fa.sparse_attn_fwd(Q, self.cache.K, self.cache.V, self.cache.cnt, self.cache.len, sel, nsel, self.BQ,
-                                self.BK, self.scale, out=(O, lse))
+
+        def attend():
+            if self.kv8 is not None:
+                self.fa.sparse_attn_fwd_fp8(Q, self.kv8[0], self.kv8[1], self.cache.cnt, self.cache.len, self.C, sel, nsel,
+                                            self.BQ, self.BK, self.scale, out=(O, lse))
+            else:
+                self.fa.sparse_attn_fwd(Q, self.cache.K, self.cache.V, self.cache.cnt, self.cache.len, sel, nsel, self.BQ,
+                                        self.BK, self.scale, out=(O, lse))
+        attend()
         e0, e1 = t.cuda.Event(enable_timing=True), t.cuda.Event(enable_timing=True)
         e0.record()
         for _ in range(reps):
-            self.fa.sparse_attn_fwd(Q, self.cache.K, self.cache.V, self.cache.cnt, self.cache.len, sel, nsel, self.BQ,
-                                    self.BK, self.scale, out=(O, lse))
+            attend()
         e1.record()
         t.cuda.synchronize()
         return e0.elapsed_time(e1) / reps, n_live
@@ -259,7 +278,12 @@ def cpu_baseline(cfg, pipe, oracle_cache, oracle_prev, oracle_fid, host_chunks, 
     else:
         sel, nsel = oracle.ann_select_self(qc, cache.code, cache.len, pipe.BQ, pipe.n_rep, pipe.BK, pipe.n_sel)
     t2 = time.perf_counter()
-    O, _ = oracle.sparse_attn_fwd(Qh, cache.K, cache.V, cache.cnt, cache.len, sel, nsel, pipe.BQ, pipe.BK, pipe.scale)
+    if pipe.kv8 is not None:   # the oracle's own 8-bit copy of ITS cache
+        K8r, V8r = oracle.kv8_empty(n_heads, pipe.C, cfg["d"])
+        oracle.kv_to_fp8(cache, K8r, V8r)
+        O, _ = oracle.sparse_attn_fwd_fp8(Qh, K8r, V8r, cache.cnt, cache.len, pipe.C, sel, nsel, pipe.BQ, pipe.BK, pipe.scale)
+    else:
+        O, _ = oracle.sparse_attn_fwd(Qh, cache.K, cache.V, cache.cnt, cache.len, sel, nsel, pipe.BQ, pipe.BK, pipe.scale)
     t3 = time.perf_counter()
     pK, pV = ps_host
     pc = oracle.encode(pK, codec.R, codec.qscale, codec.shift)
@@ -446,6 +470,10 @@ def run_layer(args, workload, torch, fa, np, to_dev, to_host, steps, warmup, sta
     t_gen = time.perf_counter() - t_gen
     cfg, pipe, dev_chunks = B["cfg"], B["pipe"], B["dev_chunks"]
     pipe.sorted_cand = args.cand == "sorted"
+    fp8 = args.kv == "fp8"
+    if fp8:   # the 8-bit copy of the cache as it stands, kept up to date by every step
+        pipe.kv8 = fa.kv8_empty(cfg["H"], pipe.C, cfg["d"])
+        fa.kv_to_fp8(pipe.cache, pipe.kv8[0], pipe.kv8[1])
     n_cpu_heads = min(n_cpu_heads, cfg["H"])
     T, cf, C = cfg["T"], cfg["chunk_frames"], pipe.C
     len_prefill = to_host(pipe.cache.len).tolist()
@@ -476,7 +504,7 @@ def run_layer(args, workload, torch, fa, np, to_dev, to_host, steps, warmup, sta
     flops = pipe.attended_flops()
     stats_timed = to_host(pipe.mm[(pipe.frame_id - 1) & 1][2])
     # Stage breakdown: a separate pass over the next chunks of the same rollout, an event after every stage.
-    stage_names = ["compress", "encode", "select_self", "attn_self", "select_cross", "attn_cross"]
+    stage_names = ["compress", "quantize", "encode", "select_self", "attn_self", "select_cross", "attn_cross"]
     events = []
     for s in range(stage_steps):
         evs = []
@@ -501,6 +529,7 @@ def run_layer(args, workload, torch, fa, np, to_dev, to_host, steps, warmup, sta
             stage_ms[n] += evs[i].elapsed_time(evs[i + 1])
     stage_ms = {n: v / max(stage_steps, 1) for n, v in stage_ms.items()}
     tflops = flops / (attn_ms * 1e-3) / 1e12
+    peak_tf = PEAK_FP8_TFLOPS if fp8 else PEAK_BF16_TFLOPS
     len_final = to_host(pipe.cache.len).tolist()
     dense = pipe.dense_equivalent_ms(dev_chunks[warmup + steps - 1][1]) if with_dense else None
 
@@ -517,14 +546,16 @@ def run_layer(args, workload, torch, fa, np, to_dev, to_host, steps, warmup, sta
         "compress": cf * H * T * (5 * d * es + 40 + r) + cf * H * T * r,
     }
     stage_gbs = {k: round(v / (stage_ms[k] * 1e-3) / 1e9, 1) for k, v in bytes_stage.items() if stage_ms.get(k, 0) > 0}
-    traffic, traffic_src = profiled_traffic(workload)
+    traffic, traffic_src = (None, None) if fp8 else profiled_traffic(workload)
 
     result = {
         "metric": "sparse-attn ms per generated chunk", "value": round(ms_per_step, 4), "unit": "ms/chunk",
         "n_gpus": 1, "steps": steps, "warmup": warmup, "ms_per_step": round(ms_per_step, 4),
-        "higher_is_better": False, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "higher_is_better": False, "scaling": "weak", "vs_baseline": None, "dtype": "fp8 (E4M3 K/V/Q/P, fp32 accumulation)" if fp8 else "bf16",
+        "data": "synthetic",
         "config": {"workload": B["label"],
                    "ann": f"int8 projection codes (r 32, shift {B['codec_h'].shift})" if args.ann == "int8" else "sign codes, 128 hash bits (LSH variant)",
+                   "self_attention_kv": "8-bit floating-point (E4M3) copy of the cache, updated per chunk by fastar_kv_to_fp8" if fp8 else "bf16 cache",
                    "representative": args.rep + " key",
                    "tempcache_workspace": args.ws,
                    "cross_attention": "one launch (ann_cross_attn_fwd)" if args.cross == "fused" else "ann_select_cross + sparse_attn_fwd",
@@ -538,10 +569,10 @@ def run_layer(args, workload, torch, fa, np, to_dev, to_host, steps, warmup, sta
         "stages_hbm": {"algorithmic_bytes": {k: int(v) for k, v in bytes_stage.items()}, "achieved_GBs": stage_gbs,
                        "frac_of_peak": {k: round(v / PEAK_HBM_GBS, 4) for k, v in stage_gbs.items()},
                        "peak_GBs": PEAK_HBM_GBS},
-        "effective_tflops": round(tflops, 2), "pct_mfma_peak": round(100 * tflops / PEAK_BF16_TFLOPS, 2),
-        "roofline": {"kernel": attn_kernel_name(cfg["H"] * pipe.n_qb, cfg["H"], C) + " (block-sparse self-attention)", "bound": "mfma",
-                     "achieved": round(tflops, 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                     "frac": round(tflops / PEAK_BF16_TFLOPS, 4),
+        "effective_tflops": round(tflops, 2), "pct_mfma_peak": round(100 * tflops / peak_tf, 2),
+        "roofline": {"kernel": ("attn_fp8_d128_kernel" if fp8 else attn_kernel_name(cfg["H"] * pipe.n_qb, cfg["H"], C)) + " (block-sparse self-attention)", "bound": "mfma",
+                     "achieved": round(tflops, 2), "peak": peak_tf, "unit": "TFLOP/s",
+                     "frac": round(tflops / peak_tf, 4),
                      "traffic": traffic, "traffic_source": traffic_src,
                      "flops_per_launch": flops, "avg_launch_ms": round(attn_ms, 4)},
         "dense_equivalent": None if dense is None else {
@@ -665,8 +696,8 @@ def sweep(args, torch, fa, np, to_dev, to_host, n_frames, bounded_only=False, qu
             ms = evs[0].elapsed_time(evs[-1])
             L = to_host(pipe.cache.len)
             live_bytes = int(L.sum()) * (2 * d * 2 + r + 8)
-            row[name] = {"ms": round(ms, 3), "attn_self_ms": round(evs[3].elapsed_time(evs[4]), 4),
-                         "select_self_ms": round(evs[2].elapsed_time(evs[3]), 4),
+            row[name] = {"ms": round(ms, 3), "attn_self_ms": round(evs[4].elapsed_time(evs[5]), 4),
+                         "select_self_ms": round(evs[3].elapsed_time(evs[4]), 4),
                          "compress_ms": round(evs[0].elapsed_time(evs[1]), 4),
                          "len_max": int(L.max()), "live_cache_MB": round(live_bytes / 1e6, 1),
                          "evicted": int(to_host(pipe.mm[(pipe.frame_id - 1) & 1][2])[0, 3])}

@@ -269,6 +269,35 @@ int sparse_attn_fwd(const void *Q, int n_q, const void *K, const void *V, const 
                     const int32_t *len, int H, int C, int d, int dtype, const int32_t *sel, const int32_t *nsel,
                     int BQ, int BK, int n_sel, float scale, void *O, float *lse, void *stream);
 
+/*
+ * 8-bit floating-point K/V for the attention itself (Sec. 5.1, quantised-search paragraph; appendix ablation
+ * "Quantization precision for ANN matching" carried over from the retrieval codes to the attended keys and values).
+ * Format: E4M3 (OCP 8-bit floating point, "FN": bias 7, subnormals, no infinities, largest finite value 448); values
+ * beyond +-448 saturate; conversion rounds to nearest, ties to even.
+ *
+ * fastar_kv_to_fp8 keeps an 8-bit copy of a bf16 / fp32 cache (d = 128) up to date:
+ *   K8   [H, Cp, 128] uint8      codes of the keys, rows as in cache->K; Cp = C rounded up to a multiple of 64
+ *   V8T  [H, Cp/64, 128, 64]     codes of the values, every block of 64 slots transposed:
+ *                                element (h, blk, t, j) = code of V[h][64 blk + j][t]
+ * Every block of 64 slots that holds a live slot with stamp >= stamp_lo is rewritten whole (live slots with the codes
+ * of the stored rows, dead slots with zero); other blocks are not touched.  After tempcache_compress(frame_id = f),
+ * stamp_lo = f brings the copy up to date; stamp_lo = INT32_MIN rebuilds it.  The caller zero-fills K8 and V8T once:
+ * the attention reads whole blocks and a dead slot must hold a finite code.
+ */
+int fastar_kv_to_fp8(const fastar_cache *cache, int32_t stamp_lo, uint8_t *K8, uint8_t *V8T, void *stream);
+
+/*
+ * sparse_attn_fwd over that copy: the same definition (Eq. 1 restricted to the selected key blocks, +ln(cnt) bias of
+ * Lemma 1) on the exact values of the E4M3 codes of K and V and of Q rounded to E4M3.  Both products run on the 8-bit
+ * floating-point matrix instructions (fp32 accumulation); the softmax weights are rounded to E4M3 before the second
+ * product and the row sums are taken over the rounded weights, so every output is a convex combination of the stored
+ * values.  Q, O [H,n_q,128] bf16; cnt [H,C] or NULL; len [H]; sel / nsel as for sparse_attn_fwd; lse [H,n_q] or NULL.
+ * Supported: d = 128, BQ = 128, BK = 64 (one selection entry = one block of the copy); FASTAR_ERR_UNSUPPORTED otherwise.
+ */
+int sparse_attn_fwd_fp8(const void *Q, int n_q, const uint8_t *K8, const uint8_t *V8T, const int32_t *cnt,
+                        const int32_t *len, int H, int C, int d, const int32_t *sel, const int32_t *nsel, int BQ, int BK,
+                        int n_sel, float scale, void *O, float *lse, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

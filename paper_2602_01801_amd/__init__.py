@@ -25,10 +25,13 @@ from .binding import (  # noqa: F401
     encode,
     encode_sign,
     init,
+    kv8_empty,
+    kv_to_fp8,
     lib,
     probe_copy,
     probe_mfma_bf16,
     sparse_attn_fwd,
+    sparse_attn_fwd_fp8,
     tempcache_compress,
     workspace_bytes,
 )

@@ -83,6 +83,14 @@ def lib() -> ctypes.CDLL:
                                       ctypes.c_void_p, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int,
                                       ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int, ctypes.c_int, ctypes.c_int,
                                       ctypes.c_float, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
+        L.fastar_kv_to_fp8.restype = ctypes.c_int
+        L.fastar_kv_to_fp8.argtypes = [ctypes.POINTER(_CacheStruct), ctypes.c_int32, ctypes.c_void_p, ctypes.c_void_p,
+                                       ctypes.c_void_p]
+        L.sparse_attn_fwd_fp8.restype = ctypes.c_int
+        L.sparse_attn_fwd_fp8.argtypes = [ctypes.c_void_p, ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
+                                          ctypes.c_void_p, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_void_p,
+                                          ctypes.c_void_p, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_float,
+                                          ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
         L.fastar_encode_sign.restype = ctypes.c_int
         L.fastar_encode_sign.argtypes = [ctypes.c_void_p, ctypes.c_int, ctypes.c_int64, ctypes.c_int, ctypes.c_void_p,
                                          ctypes.c_float, ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p]
@@ -99,7 +107,8 @@ def lib() -> ctypes.CDLL:
 
 EXPORTS = ("fastar_init", "fastar_version", "fastar_strerror", "fastar_workspace_bytes", "fastar_encode", "tempcache_compress",
            "ann_cross_attn_fwd",
-           "ann_select_self", "ann_select_self_static", "ann_select_cross", "sparse_attn_fwd", "fastar_encode_sign", "ann_select_lsh",
+           "ann_select_self", "ann_select_self_static", "ann_select_cross", "sparse_attn_fwd", "fastar_kv_to_fp8",
+           "sparse_attn_fwd_fp8", "fastar_encode_sign", "ann_select_lsh",
            "fastar_probe_mfma_bf16", "fastar_probe_copy")
 
 
@@ -368,6 +377,51 @@ def sparse_attn_fwd(Q, K, V, cnt, length, sel, nsel, BQ: int, BK: int, scale: fl
     _check(lib().sparse_attn_fwd(Q.data_ptr(), n_q, K.data_ptr(), V.data_ptr(), _ptr(cnt), length.data_ptr(), H, C, d,
                                  _dtype_code(Q), sel.data_ptr(), nsel.data_ptr(), BQ, BK, n_sel, float(scale),
                                  O.data_ptr(), _ptr(lse), _stream()), "sparse_attn_fwd")
+    return O, lse
+
+
+def kv8_empty(H: int, C: int, d: int = 128, device="cuda"):
+    """Zero-filled 8-bit copy of a cache of capacity C: (K8 [H,Cp,d], V8T [H,Cp/64,d,64]) uint8, Cp = C rounded up to 64."""
+    n_blk = (C + 63) // 64
+    return (torch.zeros((H, n_blk * 64, d), dtype=torch.uint8, device=device),
+            torch.zeros((H, n_blk, d, 64), dtype=torch.uint8, device=device))
+
+
+def kv_to_fp8(cache: Cache, K8: torch.Tensor, V8T: torch.Tensor, stamp_lo: int = -2 ** 31) -> None:
+    """fastar_kv_to_fp8: rewrite the blocks of the 8-bit copy that hold a live slot with stamp >= stamp_lo."""
+    H, C, d, _ = cache.shape
+    n_blk = (C + 63) // 64
+    _dev(K8, torch.uint8)
+    _dev(V8T, torch.uint8)
+    if tuple(K8.shape) != (H, n_blk * 64, d) or tuple(V8T.shape) != (H, n_blk, d, 64):
+        raise ValueError("K8 must be [H,Cp,d] and V8T [H,Cp/64,d,64] with Cp = C rounded up to a multiple of 64")
+    cs = cache.struct()
+    _check(lib().fastar_kv_to_fp8(ctypes.byref(cs), int(stamp_lo), K8.data_ptr(), V8T.data_ptr(), _stream()),
+           "fastar_kv_to_fp8")
+
+
+def sparse_attn_fwd_fp8(Q, K8, V8T, cnt, length, C: int, sel, nsel, BQ: int, BK: int, scale: float, out=None,
+                        want_lse: bool = True):
+    """Block-sparse attention over the 8-bit cache copy.  Returns (O [H,n_q,d] bf16, lse [H,n_q] float32 or None)."""
+    _dev(Q, torch.bfloat16)
+    _dev(K8, torch.uint8)
+    _dev(V8T, torch.uint8)
+    _dev(length, torch.int32)
+    _dev(sel, torch.int32)
+    _dev(nsel, torch.int32)
+    if cnt is not None:
+        _dev(cnt, torch.int32)
+    H, n_q, d = Q.shape
+    n_blk = (C + 63) // 64
+    if tuple(K8.shape) != (H, n_blk * 64, d) or tuple(V8T.shape) != (H, n_blk, d, 64):
+        raise ValueError("K8 must be [H,Cp,d] and V8T [H,Cp/64,d,64] with Cp = C rounded up to a multiple of 64")
+    n_sel = sel.shape[2]
+    if out is None:
+        out = (torch.empty_like(Q), torch.empty((H, n_q), dtype=torch.float32, device=Q.device) if want_lse else None)
+    O, lse = out
+    _check(lib().sparse_attn_fwd_fp8(Q.data_ptr(), n_q, K8.data_ptr(), V8T.data_ptr(), _ptr(cnt), length.data_ptr(), H, C,
+                                     d, sel.data_ptr(), nsel.data_ptr(), BQ, BK, n_sel, float(scale), O.data_ptr(),
+                                     _ptr(lse), _stream()), "sparse_attn_fwd_fp8")
     return O, lse
 
 

@@ -9,7 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libfastar.so")
 SOURCES = ["api.hip", "encode.hip", "select.hip", "tempcache.hip", "attention.hip", "attention_d128.hip",
-           "attention_d128_pp.hip"]
+           "attention_d128_pp.hip", "attention_fp8.hip"]
 ASM_CHECKED = ["attention_d128.hip", "attention_d128_pp.hip"]  # kernels that read LDS through inline assembly
 # Integer matrix-core results that feed plain ALU epilogues (arg-max, top-k scores): keep them in ordinary vector
 # registers, not accumulation registers that every ALU instruction would first have to copy from.

@@ -60,6 +60,7 @@ extern "C" int fastar_init(void) {
     if (rc == FASTAR_OK) rc = fastar::attn_d128_setup();
     if (rc == FASTAR_OK) rc = fastar::select_setup();
     if (rc == FASTAR_OK) rc = fastar::tempcache_setup();
+    if (rc == FASTAR_OK) rc = fastar::attn_fp8_setup();
     return rc;
 }
 

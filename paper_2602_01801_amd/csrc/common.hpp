@@ -109,6 +109,7 @@ int attn_d128_pp_setup();
 int attn_d128_setup();
 int select_setup();
 int tempcache_setup();
+int attn_fp8_setup();
 
 // Host-side launch check shared by the entry points.
 #define FASTAR_LAUNCH_CHECK()                          \
