@@ -148,6 +148,13 @@ static int64_t dot_i8(const int8_t *a, const int8_t *b, int r) {
  *               decisions (codes, the cosine test), so its arithmetic is fixed: float32, cnt * K_old first, then the
  *               members' keys added in ascending token order, one float32 division, one rounding to the storage
  *               type; the slot's code is the code of that stored key.
+ *          2 => medoid key: of the group's members the one with the smallest total distance to the others.  A bounded
+ *               cache keeps no members, so the group seen by one call is the slot's current representative, standing
+ *               for the cnt tokens merged so far, and this frame's joiners (weight 1 each); distance = squared
+ *               Euclidean distance of the 8-bit codes (an exact integer); cost(x) = sum over members y of
+ *               weight(y) * dist(x, y); smallest cost wins, ties go to the current representative, then to the smaller
+ *               token.  The current representative winning leaves key and code as they are (value, multiplicity and
+ *               stamp are updated as always).
  * out:     merge_map [H,n_new] destination slot or -1 (dropped); merged [H,n_new] 0/1;
  *          stats [H,8] = len', n_merged, n_appended, n_evicted, n_dropped, 0, 0, 0
  */
@@ -159,7 +166,7 @@ int oracle_tempcache_compress(void *K, void *V, int8_t *code, int32_t *cnt, int3
     if (!K || !V || !code || !cnt || !stamp || !len || !R || !K_new || !V_new || !merge_map || !merged || !stats)
         return -1;
     if (H <= 0 || C <= 0 || d <= 0 || r <= 0 || n_new < 0 || (metric != 0 && metric != 1)) return -1;
-    if (rep_mode != 0 && rep_mode != 1) return -1;
+    if (rep_mode != 0 && rep_mode != 1 && rep_mode != 2) return -1;
     if (!P_new) P_new = K_new;
     int err = 0;
 #pragma omp parallel for schedule(dynamic, 1)
@@ -283,6 +290,35 @@ int oracle_tempcache_compress(void *K, void *V, int8_t *code, int32_t *cnt, int3
                 if (rep_mode == 0) {
                     copy_row(K, cb + j, K_new, nb + winner[j], d, dtype);
                     memcpy(code + (cb + j) * r, ck + (int64_t)winner[j] * r, (size_t)r);
+                } else if (rep_mode == 2) {
+                    /* medoid over {current representative (weight cnt)} and the joiners (weight 1), candidates in the
+                     * order representative, then tokens ascending; strict '<' keeps the earlier candidate on ties */
+                    const int8_t *cold = code + (cb + j) * r;
+                    int best = -1; /* -1 = the current representative */
+                    int64_t best_cost = 0;
+                    for (int i = 0; i < n_new; ++i)
+                        if (merged[nb + i] && jstar[i] == j) {
+                            const int8_t *ci = ck + (int64_t)i * r;
+                            best_cost += dot_i8(cold, cold, r) + dot_i8(ci, ci, r) - 2 * dot_i8(cold, ci, r);
+                        }
+                    for (int a = 0; a < n_new; ++a) {
+                        if (!(merged[nb + a] && jstar[a] == j)) continue;
+                        const int8_t *ca = ck + (int64_t)a * r;
+                        int64_t cost = (int64_t)cnt[cb + j] * (dot_i8(ca, ca, r) + dot_i8(cold, cold, r) - 2 * dot_i8(ca, cold, r));
+                        for (int i = 0; i < n_new; ++i)
+                            if (merged[nb + i] && jstar[i] == j) {
+                                const int8_t *ci = ck + (int64_t)i * r;
+                                cost += dot_i8(ca, ca, r) + dot_i8(ci, ci, r) - 2 * dot_i8(ca, ci, r);
+                            }
+                        if (cost < best_cost) {
+                            best = a;
+                            best_cost = cost;
+                        }
+                    }
+                    if (best >= 0) {
+                        copy_row(K, cb + j, K_new, nb + best, d, dtype);
+                        memcpy(code + (cb + j) * r, ck + (int64_t)best * r, (size_t)r);
+                    }
                 } else {
                     for (int t = 0; t < d; ++t) {
                         volatile float ksum = (float)cnt[cb + j] * load_f32(K, dtype, (cb + j) * d + t);

@@ -256,6 +256,73 @@ def test_mean_key_stays_inside_the_hull_of_its_group_and_its_code_is_the_code_of
     assert cache.cnt[:, :T].max() == 5
 
 
+def test_medoid_representative_hand_example_and_weight_of_the_stored_key():
+    # appendix, representative-selection ablation, medoid key.  Slot 0 holds `base`; three joiners lie on a line through
+    # it (base + 1, 2, 3 steps): with multiplicity 1 the medoid of {base, +1, +2, +3} is +1 (costs 14, 6, 6, 14 in units
+    # of step^2: the tie between +1 and +2 goes to the smaller token); with multiplicity 10 the stored key outweighs the
+    # joiners and stays.
+    d, r = 8, 4
+    R = np.array([[1, 1, 1, 1], [1, -1, 1, -1], [1, 1, -1, -1], [1, -1, -1, 1]] * 2, np.int8)
+    qscale, shift = 16.0, 1
+    base = np.array([1.0, 2.0, -1.0, 0.5, 3.0, -2.0, 1.5, 0.25], np.float32)
+    step = np.array([0.125, 0, 0, 0, 0, 0, 0, 0], np.float32)          # two code units along every column of R
+    far = -base[::-1].copy()
+    K0 = np.stack([base, far])[None]
+    V0 = np.zeros_like(K0)
+    K1 = np.stack([base + 3 * step, base + step, base + 2 * step])[None]   # tokens 0, 1, 2 = +3, +1, +2
+    for cnt0, expect in ((1, base + step), (10, base)):
+        c = oracle.Cache.empty(1, 8, d, r, "fp32")
+        oracle.tempcache_compress(c, R, qscale, shift, K0, V0, tau2_q16=NEVER, frame_id=0, rep_mode=2)
+        c.cnt[0, 0] = cnt0
+        codes = oracle.encode(np.concatenate([base[None], K1[0]]), R, qscale, shift).astype(np.int64)
+        assert len({tuple(x) for x in codes}) == 4                       # the four members have four different codes
+        mm, mg, _ = oracle.tempcache_compress(c, R, qscale, shift, K1, np.zeros_like(K1), tau2_q16=TAU2(0.9), frame_id=1,
+                                              rep_mode=2)
+        assert mg[0].tolist() == [1, 1, 1] and mm[0].tolist() == [0, 0, 0]
+        assert np.array_equal(c.K[0, 0], expect), cnt0
+        assert np.array_equal(c.code[0, 0], oracle.encode(expect[None], R, qscale, shift)[0])
+        assert c.cnt[0, 0] == cnt0 + 3 and c.stamp[0, 0] == 1
+
+
+def test_medoid_representative_is_the_brute_force_weighted_medoid_in_code_space():
+    # loose threshold: big groups.  Same decisions as the last-key mode within a call; the stored key is the member with
+    # the smallest weighted total squared code distance (stored key first, then tokens ascending, among equals).
+    c, fs, codec = stream_cfg1(p=1.0, sigma_d=0.3)
+    H, T, d = c["H"], c["T"], c["d"]
+    cache = oracle.Cache.empty(H, 2 * T, d, c["r"], "fp32")
+    twin = oracle.Cache.empty(H, 2 * T, d, c["r"], "fp32")
+    prev = None
+    groups_seen = moved = stayed = 0
+    shift_dir = np.sign(np.random.default_rng(2).standard_normal(d)).astype(np.float32)
+    for f in range(4):
+        K, V = fs.next_frame()
+        K = (K + 0.3 * f * shift_dir).astype(np.float32)      # the whole frame moves: joiners sit together, off the stored key
+        before = cache.copy()
+        mm, mg, st = compress(cache, codec, K, V, cand=prev, tau2_q16=TAU2(0.6), frame_id=f, rep_mode=2)
+        if f == 0:
+            compress(twin, codec, K, V, tau2_q16=TAU2(0.6), frame_id=f)
+            prev = mm
+            continue
+        ck = oracle.encode(K, codec.R, codec.qscale, codec.shift).astype(np.int64)
+        for h in range(H):
+            for j in np.unique(mm[h][mg[h] == 1]):
+                members = np.nonzero((mg[h] == 1) & (mm[h] == j))[0]
+                cold = before.code[h, j].astype(np.int64)
+                cand_codes = np.concatenate([cold[None], ck[h, members]])
+                w = np.concatenate([[before.cnt[h, j]], np.ones(members.size, np.int64)])
+                dist = ((cand_codes[:, None, :] - cand_codes[None, :, :]) ** 2).sum(axis=2)
+                cost = (dist * w[None, :]).sum(axis=1)
+                best = int(np.argmin(cost))                               # first minimum: stored key, then tokens ascending
+                want = before.K[h, j] if best == 0 else K[h, members[best - 1]]
+                assert np.array_equal(cache.K[h, j], want), (f, h, j)
+                assert np.array_equal(cache.code[h, j], cand_codes[best].astype(np.int8))
+                groups_seen += members.size > 1
+                moved += best != 0
+                stayed += best == 0
+        prev = mm
+    assert groups_seen > 20 and moved > 20 and stayed > 20               # the cases are all there
+
+
 def test_equally_scored_candidates_the_smallest_slot_wins():
     # slots 1, 3 and 4 hold the same key (same code, same score for any probe): the match goes to the smallest of them
     # that the candidate list names, whatever the order of the list and however often it repeats an id
