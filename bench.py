@@ -64,8 +64,8 @@ def parse():
     ap.add_argument("--kv", choices=["bf16", "fp8"], default="bf16",
                     help="self-attention over the bf16 cache (default) or over its 8-bit floating-point (E4M3) copy, "
                          "which fastar_kv_to_fp8 brings up to date after the chunk's TempCache calls")
-    ap.add_argument("--rep", choices=["last", "mean"], default="last",
-                    help="representative key of a merged group: the last key (the method) or the mean key (its ablation)")
+    ap.add_argument("--rep", choices=["last", "mean", "medoid"], default="last",
+                    help="representative key of a merged group: the last key (the method) or the mean / medoid key (its ablation)")
     ap.add_argument("--prefill-frames", type=int, default=None, help="frames merged into the cache before timing")
     ap.add_argument("--cap-frames", type=int, default=None, help="cache capacity in frames of slots")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -370,7 +370,7 @@ def build_host_rollout(args, workload, torch, fa, np, to_dev, n_chunks, n_cpu_he
     sign_h = make_sign_matrix(cfg["seed"], cfg["cfg_id"], cfg["d"], 128) if args.ann == "lsh" else None
     pipe = ChunkPipeline(cfg, C, args.tau, torch, fa, codec, (to_dev(ps.K), to_dev(ps.V)), n_sel,
                          sign_matrix=None if sign_h is None else to_dev(sign_h),
-                         rep_mode=fa.REP_MEAN if args.rep == "mean" else fa.REP_LAST,
+                         rep_mode={"last": fa.REP_LAST, "mean": fa.REP_MEAN, "medoid": fa.REP_MEDOID}[args.rep],
                          fused_cross=args.cross == "fused", ws_persistent=args.ws == "persistent")
     for K, V in prefill:
         pipe.compress(to_dev(K), to_dev(V))
@@ -419,7 +419,7 @@ def build_cfg5_full(args, torch, fa, np, to_dev, to_host, n_chunks, n_cpu_heads)
     sign_h = make_sign_matrix(cfg["seed"], cfg["cfg_id"], d, 128) if args.ann == "lsh" else None
     pipe = ChunkPipeline(cfg, C, args.tau, torch, fa, codec, (to_dev(ps.K), to_dev(ps.V)), n_sel,
                          sign_matrix=None if sign_h is None else to_dev(sign_h),
-                         rep_mode=fa.REP_MEAN if args.rep == "mean" else fa.REP_LAST,
+                         rep_mode={"last": fa.REP_LAST, "mean": fa.REP_MEAN, "medoid": fa.REP_MEDOID}[args.rep],
                          fused_cross=args.cross == "fused", ws_persistent=args.ws == "persistent")
     cache = pipe.cache
     for f in range(n_fill):

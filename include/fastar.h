@@ -63,6 +63,7 @@ extern "C" {
 /* representative key of a merged TempCache group (tempcache_compress, rep_mode) */
 #define FASTAR_REP_LAST 0
 #define FASTAR_REP_MEAN 1
+#define FASTAR_REP_MEDOID 2
 
 /*
  * Bounded per-head KV cache with multiplicities (Lemma 1 of the paper: a group of merged keys is
@@ -163,7 +164,11 @@ int ann_select_lsh(const uint32_t *qbits, int n_q, const uint32_t *kbits, const 
  *      rep_mode FASTAR_REP_MEAN (appendix ablation "Representative selection in KV merging") stores the
  *      multiplicity-weighted mean key instead: float32, multiplicity * old key, then the joiners' keys in
  *      ascending token order, one division, one rounding to dtype; the slot's code is the code of the
- *      stored key (one more launch).  FASTAR_REP_LAST is the method's own choice and the fast path.
+ *      stored key (one more launch).  FASTAR_REP_MEDOID stores the medoid key: of the slot's stored key (standing for
+ *      the multiplicity tokens merged so far) and this call's joiners (weight 1 each) the one with the smallest weighted
+ *      total squared distance to the others in code space (exact integers; ties to the stored key, then the smaller
+ *      token); the stored key winning leaves key and code as they are.  FASTAR_REP_LAST is the method's own choice and
+ *      the fast path.
  *   5. unmerged tokens are appended in token order.  If the cache would exceed C, the live slots
  *      that received no token in this call are evicted, smallest (stamp, slot) first, and refilled
  *      in ascending slot order; if there are too few of those, the last unmerged tokens are dropped.

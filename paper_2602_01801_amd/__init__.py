@@ -13,6 +13,7 @@ from .binding import (  # noqa: F401
     OP_SELECT_LSH,
     REP_LAST,
     REP_MEAN,
+    REP_MEDOID,
     OP_SELECT_SELF,
     Cache,
     Codec,

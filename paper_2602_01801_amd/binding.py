@@ -17,7 +17,7 @@ LIB_PATH = os.path.join(_HERE, "libfastar.so")
 
 F32, BF16 = 0, 1
 OP_COMPRESS, OP_SELECT_SELF, OP_SELECT_CROSS, OP_SELECT_LSH = 1, 2, 3, 4
-REP_LAST, REP_MEAN = 0, 1
+REP_LAST, REP_MEAN, REP_MEDOID = 0, 1, 2
 
 _lib = None
 

@@ -1507,6 +1507,69 @@ __global__ __launch_bounds__(256) void tc_apply_kernel(void *__restrict__ K, voi
 #pragma unroll
                 for (int e = 0; e < RP::EPL; ++e) kacc[e] = __fdiv_rn(kacc[e], (float)(m0 + gc));
                 RP::store(K, cb + j, l16, kacc);
+            } else if (rep_mode == 2) {
+                // Medoid key: of {stored key (weight m0), joiners (weight 1)} the member x with the smallest
+                // cost(x) = sum_y w_y |x - y|^2 in code space = W |x|^2 + S2 - 2 x . S1 (W = sum of the weights,
+                // S1 = weighted sum of the codes, S2 = weighted sum of their squared norms): exact integers, one pass to
+                // build the sums and one to evaluate the candidates (stored key first, then tokens ascending; a later
+                // candidate wins only on a strictly smaller cost).  Lane l16 owns code word l16 (r <= 64: 16 words).
+                // A single joiner never wins: cost(stored) = |d|^2 <= m0 |d|^2 = cost(joiner).
+                if (gc > 1) {
+                    const bool has_w = l16 < r / 4;
+                    const unsigned ow = has_w ? ((const unsigned *)(code + (cb + j) * r))[l16] : 0u;
+                    long long S1[4], S2 = (long long)m0 * dot4_i8(ow, ow, 0);
+#pragma unroll
+                    for (int k = 0; k < 4; ++k) S1[k] = (long long)m0 * (int)(signed char)(ow >> (8 * k));
+                    for (int base = 0; base < n_new; base += 16) {
+                        const int t = base + l16;
+                        const bool member = t < n_new && merged[tb + t] && jstar[tb + t] == j;
+                        unsigned mm = (unsigned)((__ballot(member) >> (16 * sub)) & 0xFFFFull);
+                        while (mm) {
+                            const int bit = __ffs(mm) - 1;
+                            mm &= mm - 1;
+                            const unsigned w = has_w ? ((const unsigned *)(ck + (tb + base + bit) * r))[l16] : 0u;
+                            S2 += dot4_i8(w, w, 0);
+#pragma unroll
+                            for (int k = 0; k < 4; ++k) S1[k] += (int)(signed char)(w >> (8 * k));
+                        }
+                    }
+                    const long long W = (long long)m0 + gc;
+                    auto group16_sum64 = [](long long v) -> long long {
+#pragma unroll
+                        for (int off = 1; off < 16; off <<= 1) {
+                            const unsigned lo = shfl_xor((unsigned)v, off), hi = shfl_xor((unsigned)((unsigned long long)v >> 32), off);
+                            v += (long long)(((unsigned long long)hi << 32) | lo);
+                        }
+                        return v;
+                    };
+                    auto cost_of = [&](unsigned w) -> long long {   // this lane's share of W |x|^2 + S2 - 2 x . S1
+                        long long c = W * dot4_i8(w, w, 0) + S2;
+#pragma unroll
+                        for (int k = 0; k < 4; ++k) c -= 2 * S1[k] * (int)(signed char)(w >> (8 * k));
+                        return c;
+                    };
+                    long long best_cost = group16_sum64(cost_of(ow));
+                    int best = -1;   // the stored key
+                    for (int base = 0; base < n_new; base += 16) {
+                        const int t = base + l16;
+                        const bool member = t < n_new && merged[tb + t] && jstar[tb + t] == j;
+                        unsigned mm = (unsigned)((__ballot(member) >> (16 * sub)) & 0xFFFFull);
+                        while (mm) {
+                            const int bit = __ffs(mm) - 1;
+                            mm &= mm - 1;
+                            const unsigned w = has_w ? ((const unsigned *)(ck + (tb + base + bit) * r))[l16] : 0u;
+                            const long long c = group16_sum64(cost_of(w));
+                            if (c < best_cost) {
+                                best_cost = c;
+                                best = base + bit;
+                            }
+                        }
+                    }
+                    if (best >= 0) {
+                        RP::copy(K, cb + j, K_new, tb + best, l16);
+                        if (has_w) ((unsigned *)(code + (cb + j) * r))[l16] = ((const unsigned *)(ck + (tb + best) * r))[l16];
+                    }
+                }
             } else {
                 RP::store_raw(K, cb + j, l16, kraw);
                 if (l16 < r / 4) ((unsigned *)(code + (cb + j) * r))[l16] = cw;
@@ -1576,7 +1639,7 @@ extern "C" int tempcache_compress(const fastar_cache *cache, const fastar_codec 
         return FASTAR_ERR_INVALID_ARG;
     const int H = cache->H, C = cache->C, d = cache->d, r = cache->r, dtype = cache->dtype;
     if (H <= 0 || C <= 0 || n_new <= 0 || (metric != 0 && metric != 1)) return FASTAR_ERR_INVALID_ARG;
-    if (rep_mode != FASTAR_REP_LAST && rep_mode != FASTAR_REP_MEAN) return FASTAR_ERR_INVALID_ARG;
+    if (rep_mode != FASTAR_REP_LAST && rep_mode != FASTAR_REP_MEAN && rep_mode != FASTAR_REP_MEDOID) return FASTAR_ERR_INVALID_ARG;
     if (ws_persistent != 0 && ws_persistent != 1) return FASTAR_ERR_INVALID_ARG;
     if (tau2_q16 < 0 || tau2_q16 > 131072) return FASTAR_ERR_INVALID_ARG;
     if (cand && n_cand <= 0) return FASTAR_ERR_INVALID_ARG;

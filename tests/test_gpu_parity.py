@@ -485,7 +485,7 @@ def test_dense_limit_on_clustered_data_fp32_and_bf16():
 # ----------------------------------------------------------------------------------------- TempCache
 
 def run_rollout(name, n_frames, C, tau, dtype=None, H=None, windowed=True, metric=0, probe_queries=False, rep_mode=0,
-                persistent=False, r=None, shift=None):
+                persistent=False, r=None, shift=None, frame_shift=0.0):
     over = {}
     if dtype:
         over["dtype"] = dtype
@@ -505,8 +505,11 @@ def run_rollout(name, n_frames, C, tau, dtype=None, H=None, windowed=True, metri
     ws = None
     if persistent:   # one workspace for the whole rollout, zero-filled once
         ws = torch.zeros(fa.workspace_bytes(fa.OP_COMPRESS, c["H"], c["T"], C, c["r"]), dtype=torch.uint8, device="cuda")
+    shift_dir = np.sign(np.random.default_rng(2).standard_normal(c["d"])).astype(np.float32)
     for f in range(n_frames):
         K, V = fs.next_frame()
+        if frame_shift:    # the whole frame moves: the joiners of a slot sit together, off the stored key
+            K = to_storage((to_f32(K) + frame_shift * f * shift_dir).astype(np.float32), c["dtype"])
         P = fs.queries(1) if probe_queries else None
         mm_r, mg_r, st_r = oracle.tempcache_compress(ref, codec.R, codec.qscale, codec.shift, K, V, P_new=P,
                                                      cand=prev_ref if windowed else None, metric=metric,
@@ -730,6 +733,18 @@ def test_tempcache_mean_key_representative_bit_exact(name, dtype, H, frames, C):
     # bit (assert_cache_equal compares keys and codes exactly), through merges of several tokens per slot and evictions
     c, fs, codec, ref, gpu = run_rollout(name, frames, C, 0.98, dtype=dtype, H=H, rep_mode=fa.REP_MEAN)
     assert ref.cnt.max() >= 4
+
+
+@pytest.mark.parametrize("name,dtype,H,frames,C,tau,fshift,r", [
+    ("cfg1", None, None, 5, 2 * 256, 0.6, 0.3, None),      # big groups that move: the medoid is often a joiner
+    ("cfg1", "bf16", None, 5, 2 * 256, 0.6, 0.3, 64),      # the same with 64-byte codes in bf16
+    ("cfg1", None, None, 6, 6 * 256, 0.98, 0.0, None),     # single joiners: the stored key always stays
+    ("cfg2", None, 2, 4, 3 * 1560, 0.9, 0.1, None)])
+def test_tempcache_medoid_key_representative_bit_exact(name, dtype, H, frames, C, tau, fshift, r):
+    # appendix ablation, medoid key: weighted medoid in code space, exact integers, so everything is bit-exact
+    c, fs, codec, ref, gpu = run_rollout(name, frames, C, tau, dtype=dtype, H=H, rep_mode=2, frame_shift=fshift, r=r,
+                                         persistent=True)
+    assert int(ref.cnt.max()) >= 3
 
 
 def test_tempcache_mean_key_with_many_joiners_per_slot():
