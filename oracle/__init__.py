@@ -39,7 +39,7 @@ def _load():
         for name in ("oracle_encode", "oracle_tempcache_compress", "oracle_ann_select_self",
                      "oracle_ann_select_cross", "oracle_sparse_attn_fwd", "oracle_recall_density",
                      "oracle_encode_sign", "oracle_ann_select_lsh", "oracle_fp8_encode", "oracle_fp8_decode",
-                     "oracle_kv_to_fp8", "oracle_sparse_attn_fwd_fp8"):
+                     "oracle_kv_to_fp8", "oracle_sparse_attn_fwd_fp8", "oracle_ann_select_self_forced"):
             getattr(_lib, name).restype = ctypes.c_int
     return _lib
 
@@ -138,8 +138,9 @@ def tempcache_compress(cache: Cache, R, qscale, shift, K_new, V_new, P_new=None,
     return merge_map, merged, stats
 
 
-def ann_select_self(qcode, kcode, length, BQ: int, n_rep: int, BK: int, n_sel: int):
-    """qcode [H,n_q,r], kcode [H,C,r], length [H] -> (sel [H,n_qb,n_sel] ascending / -1 padded, nsel [H,n_qb])."""
+def ann_select_self(qcode, kcode, length, BQ: int, n_rep: int, BK: int, n_sel: int, n_sink: int = 0, n_local: int = 0):
+    """qcode [H,n_q,r], kcode [H,C,r], length [H] -> (sel [H,n_qb,n_sel] ascending / -1 padded, nsel [H,n_qb]).
+    n_sink / n_local: first / last live key blocks that are always selected (they count against n_sel)."""
     qcode = _c(qcode, np.int8)
     kcode = _c(kcode, np.int8)
     length = _c(length, np.int32)
@@ -148,9 +149,9 @@ def ann_select_self(qcode, kcode, length, BQ: int, n_rep: int, BK: int, n_sel: i
     n_qb = (n_q + BQ - 1) // BQ
     sel = np.empty((H, n_qb, n_sel), np.int32)
     nsel = np.empty((H, n_qb), np.int32)
-    rc = _load().oracle_ann_select_self(_p(qcode), n_q, _p(kcode), _p(length), H, C, r, BQ, n_rep, BK, n_sel,
-                                        _p(sel), _p(nsel))
-    _check(rc, "oracle_ann_select_self")
+    rc = _load().oracle_ann_select_self_forced(_p(qcode), n_q, _p(kcode), _p(length), H, C, r, BQ, n_rep, BK, n_sel,
+                                               n_sink, n_local, _p(sel), _p(nsel))
+    _check(rc, "oracle_ann_select_self_forced")
     return sel, nsel
 
 

@@ -412,10 +412,18 @@ static void pick_top(const int64_t *score, int n, int n_out, uint8_t *picked) {
  * The min(n_sel, ceil(len/BK)) best key blocks are written in ascending order to
  * sel [H,n_qb,n_sel] (-1 padded), their number to nsel [H,n_qb].
  */
-int oracle_ann_select_self(const int8_t *qcode, int n_q, const int8_t *kcode, const int32_t *len, int H, int C, int r,
-                           int BQ, int n_rep, int BK, int n_sel, int32_t *sel, int32_t *nsel) {
+/*
+ * The same with forced blocks (Sec. 2: rolling-window generators keep the first frames as an attention sink; a local
+ * window is the usual companion): the first n_sink key blocks and the last n_local live key blocks of every head are
+ * always among the selected ones and count against the budget (n_sink + n_local <= n_sel); the rest of the budget goes
+ * to the best-scoring other blocks as before.  n_sink = n_local = 0 is oracle_ann_select_self.
+ */
+int oracle_ann_select_self_forced(const int8_t *qcode, int n_q, const int8_t *kcode, const int32_t *len, int H, int C,
+                                  int r, int BQ, int n_rep, int BK, int n_sel, int n_sink, int n_local, int32_t *sel,
+                                  int32_t *nsel) {
     if (!qcode || !kcode || !len || !sel || !nsel) return -1;
     if (H <= 0 || C <= 0 || r <= 0 || BQ <= 0 || n_rep <= 0 || BK <= 0 || n_sel <= 0 || BQ % n_rep != 0) return -1;
+    if (n_sink < 0 || n_local < 0 || n_sink + n_local > n_sel) return -1;
     const int n_qb = (n_q + BQ - 1) / BQ;
     const int g = BQ / n_rep;
     const int n_kb_cap = (C + BK - 1) / BK;
@@ -454,6 +462,7 @@ int oracle_ann_select_self(const int8_t *qcode, int n_q, const int8_t *kcode, co
                     }
                 }
                 score[kb] = best;
+                if (kb < n_sink || kb >= n_kb - n_local) score[kb] = INT64_MAX; /* forced: ahead of every real score */
             }
             int n_out = n_sel < n_kb ? n_sel : n_kb;
             pick_top(score, n_kb, n_out, picked);
@@ -470,6 +479,11 @@ int oracle_ann_select_self(const int8_t *qcode, int n_q, const int8_t *kcode, co
         }
     }
     return 0;
+}
+
+int oracle_ann_select_self(const int8_t *qcode, int n_q, const int8_t *kcode, const int32_t *len, int H, int C, int r,
+                           int BQ, int n_rep, int BK, int n_sel, int32_t *sel, int32_t *nsel) {
+    return oracle_ann_select_self_forced(qcode, n_q, kcode, len, H, C, r, BQ, n_rep, BK, n_sel, 0, 0, sel, nsel);
 }
 
 /*

@@ -140,3 +140,44 @@ def test_selection_finds_the_blocks_that_hold_the_exact_nearest_keys():
     sel, _ = oracle.ann_select_self(qc, kc, np.full(c["H"], c["T"], np.int32), BQ, 4, BK, 1)
     hit = (sel[:, :, 0] == np.arange(c["T"] // BQ)[None, :]).mean()
     assert hit == 1.0
+
+
+def test_forced_sink_and_local_blocks_are_always_selected_and_the_rest_is_the_plain_ranking():
+    # first n_sink and last n_local live key blocks always present (Sec. 2: the sink frames of rolling-window generators,
+    # and a local window); the rest of the budget = the plain top ranking restricted to the other blocks (brute force)
+    rng = np.random.default_rng(12)
+    H, n_q, C, r, BQ, n_rep, BK, n_sel = 2, 200, 64 * 30, 32, 64, 4, 64, 9
+    qc = rng.integers(-40, 41, size=(H, n_q, r)).astype(np.int8)
+    kc = rng.integers(-40, 41, size=(H, C, r)).astype(np.int8)
+    length = np.array([C, 64 * 17 + 5], np.int32)
+    plain, nplain = oracle.ann_select_self(qc, kc, length, BQ, n_rep, BK, n_sel)
+    same, nsame = oracle.ann_select_self(qc, kc, length, BQ, n_rep, BK, n_sel, 0, 0)
+    assert np.array_equal(plain, same) and np.array_equal(nplain, nsame)
+    for n_sink, n_local in ((2, 0), (0, 3), (2, 3), (4, 5)):
+        sel, nsel = oracle.ann_select_self(qc, kc, length, BQ, n_rep, BK, n_sel, n_sink, n_local)
+        for h in range(H):
+            n_kb = (int(length[h]) + BK - 1) // BK
+            forced = set(range(n_sink)) | set(range(n_kb - n_local, n_kb))
+            big, _ = oracle.ann_select_self(qc[h:h + 1], kc[h:h + 1], length[h:h + 1], BQ, n_rep, BK, n_kb)   # budget = all
+            for b in range(sel.shape[1]):
+                row = sel[h, b, :nsel[h, b]].tolist()
+                assert nsel[h, b] == n_sel and row == sorted(row) and forced <= set(row)
+                # ranking of the other blocks: recompute their scores by brute force
+                g = BQ // n_rep
+                reps = []
+                for u in range(n_rep):
+                    q0, q1 = b * BQ + u * g, min(b * BQ + (u + 1) * g, n_q)
+                    if q0 < n_q:
+                        reps.append(np.floor_divide(qc[h, q0:q1].astype(np.int64).sum(axis=0) + g // 2, g))
+                reps = np.array(reps)
+                L = int(length[h])
+                sc = np.array([(kc[h, kb * BK:min((kb + 1) * BK, L)].astype(np.int64) @ reps.T).max() for kb in range(n_kb)])
+                others = [kb for kb in range(n_kb) if kb not in forced]
+                order = sorted(others, key=lambda kb: (-sc[kb], kb))[: n_sel - len(forced)]
+                assert sorted(order + sorted(forced)) == row
+    # forced blocks fill the whole budget, or the cache has fewer blocks than the budget
+    sel, nsel = oracle.ann_select_self(qc, kc, length, BQ, n_rep, BK, 5, 2, 3)
+    assert sel[1, 0].tolist() == [0, 1, 15, 16, 17]
+    short = np.array([64 * 3, 64 * 2], np.int32)
+    sel, nsel = oracle.ann_select_self(qc, kc, short, BQ, n_rep, BK, 8, 2, 3)
+    assert sel[0, 0].tolist() == [0, 1, 2, -1, -1, -1, -1, -1] and nsel[1, 0] == 2
