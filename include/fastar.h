@@ -216,6 +216,17 @@ int ann_select_self(const int8_t *qcode, int n_q, const int8_t *kcode, const int
                     size_t ws_bytes, void *stream);
 
 /*
+ * AnnSA with forced key blocks (Sec. 2: rolling-window generators keep their first frames as an attention sink; a
+ * local window is the usual companion): as ann_select_self, but the first n_sink key blocks and the last n_local live
+ * key blocks of every head are always among the selected ones.  They count against the budget
+ * (n_sink + n_local <= n_sel, FASTAR_ERR_INVALID_ARG otherwise); the rest of it goes to the best-scoring other blocks.
+ * n_sink = n_local = 0 is ann_select_self.  Same workspace.
+ */
+int ann_select_self_forced(const int8_t *qcode, int n_q, const int8_t *kcode, const int32_t *len, int H, int C, int r,
+                           int BQ, int n_rep, int BK, int n_sel, int n_sink, int n_local, int32_t *sel, int32_t *nsel,
+                           void *ws, size_t ws_bytes, void *stream);
+
+/*
  * ann_select_self for callers that cannot allocate or bring a workspace: code under HIP graph capture, tight serving
  * loops, harnesses that forbid hipMalloc.  Same arguments, same kernels and bit-identical outputs as ann_select_self,
  * but the summaries and the score rows live in a static device array of FASTAR_STATIC_SCRATCH_BYTES inside the library

@@ -70,6 +70,9 @@ def lib() -> ctypes.CDLL:
                                       ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int,
                                       ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
                                       ctypes.c_size_t, ctypes.c_void_p]
+        L.ann_select_self_forced.restype = ctypes.c_int
+        L.ann_select_self_forced.argtypes = [ctypes.c_void_p, ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p] + \
+            [ctypes.c_int] * 9 + [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
         L.ann_select_self_static.restype = ctypes.c_int
         L.ann_select_self_static.argtypes = [ctypes.c_void_p, ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int,
                                              ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int,
@@ -107,7 +110,7 @@ def lib() -> ctypes.CDLL:
 
 EXPORTS = ("fastar_init", "fastar_version", "fastar_strerror", "fastar_workspace_bytes", "fastar_encode", "tempcache_compress",
            "ann_cross_attn_fwd",
-           "ann_select_self", "ann_select_self_static", "ann_select_cross", "sparse_attn_fwd", "fastar_kv_to_fp8",
+           "ann_select_self", "ann_select_self_forced", "ann_select_self_static", "ann_select_cross", "sparse_attn_fwd", "fastar_kv_to_fp8",
            "sparse_attn_fwd_fp8", "fastar_encode_sign", "ann_select_lsh",
            "fastar_probe_mfma_bf16", "fastar_probe_copy")
 
@@ -249,8 +252,10 @@ def tempcache_compress(cache: Cache, codec: Codec, K_new, V_new, P_new=None, can
     return merge_map, merged, stats
 
 
-def ann_select_self(qcode, kcode, length, BQ: int, n_rep: int, BK: int, n_sel: int, ws=None, out=None):
-    """AnnSA: (sel [H,n_qb,n_sel] int32 ascending / -1 padded, nsel [H,n_qb] int32)."""
+def ann_select_self(qcode, kcode, length, BQ: int, n_rep: int, BK: int, n_sel: int, ws=None, out=None, n_sink: int = 0,
+                    n_local: int = 0):
+    """AnnSA: (sel [H,n_qb,n_sel] int32 ascending / -1 padded, nsel [H,n_qb] int32).  n_sink / n_local > 0 calls
+    ann_select_self_forced (first / last live key blocks always selected)."""
     _dev(qcode, torch.int8)
     _dev(kcode, torch.int8)
     _dev(length, torch.int32)
@@ -262,6 +267,11 @@ def ann_select_self(qcode, kcode, length, BQ: int, n_rep: int, BK: int, n_sel: i
         out = (torch.empty((H, n_qb, n_sel), dtype=torch.int32, device=qcode.device),
                torch.empty((H, n_qb), dtype=torch.int32, device=qcode.device))
     sel, nsel = out
+    if n_sink or n_local:
+        _check(lib().ann_select_self_forced(qcode.data_ptr(), n_q, kcode.data_ptr(), length.data_ptr(), H, C, r, BQ, n_rep,
+                                            BK, n_sel, n_sink, n_local, sel.data_ptr(), nsel.data_ptr(), ws.data_ptr(),
+                                            ws.numel() * ws.element_size(), _stream()), "ann_select_self_forced")
+        return sel, nsel
     _check(lib().ann_select_self(qcode.data_ptr(), n_q, kcode.data_ptr(), length.data_ptr(), H, C, r, BQ, n_rep, BK,
                                  n_sel, sel.data_ptr(), nsel.data_ptr(), ws.data_ptr(),
                                  ws.numel() * ws.element_size(), _stream()), "ann_select_self")

@@ -295,8 +295,10 @@ __global__ __launch_bounds__(256) void score_self_stream_kernel(const int8_t *__
 // (ties: lowest index) and their indices written ascending to out[0..k), the rest of out[0..n_sel) padded with
 // -1; *nsel_out = k.  Called by all 256 threads of a workgroup.
 // keys: LDS staging for up to TOPK_LDS_CAP entries of a row in global memory, or nullptr (row read in place).
+// n_sink / n_local: the first / last entries of the row are forced (sink and local key blocks of AnnSA): they rank
+// ahead of every real score, so they are always among the selected ones while n_sink + n_local <= n_sel.
 __device__ __forceinline__ void topk_row(const int32_t *row, int n, int n_sel, int32_t *__restrict__ out,
-                                         int32_t *__restrict__ nsel_out, unsigned *keys) {
+                                         int32_t *__restrict__ nsel_out, unsigned *keys, int n_sink = 0, int n_local = 0) {
     // Scores are sums of at most 64 products of 8-bit codes (or counts of equal hash bits): |score| < 2^21, and
     // anything below (the INT_MIN of a block without a live key) is clamped there, so an order-preserving key has
     // 22 bits: three passes over 8-bit digits (the first has 6 significant bits) select exactly.
@@ -313,7 +315,11 @@ __device__ __forceinline__ void topk_row(const int32_t *row, int n, int n_sel, i
         for (int t = tid; t < n; t += 256) out[t] = t;
         return;
     }
-    auto to_key = [](int32_t sc) -> unsigned { return (unsigned)(max(sc, -(1 << 21)) + (1 << 21)); };
+    auto to_key0 = [](int32_t sc) -> unsigned { return (unsigned)(max(sc, -(1 << 21)) + (1 << 21)); };
+    // key of entry t with score sc: real scores stay below 2^22, forced entries sit exactly there
+    auto key_of = [&](int t, int32_t sc) -> unsigned {
+        return (t < n_sink || t >= n - n_local) ? (1u << 22) : to_key0(sc);
+    };
     if (n > 1024 && n <= TOPK_KPT * 256) {
         // Rows of 1025 to 4096 scores (shorter ones are done sooner by the three radix passes below, which take a
         // barrier per 256 entries in their compaction; longer ones do not fit the registers): each thread owns a run of consecutive entries and keeps
@@ -333,7 +339,7 @@ __device__ __forceinline__ void topk_row(const int32_t *row, int n, int n_sel, i
 #pragma unroll
             for (int e = 0; e < TOPK_KPT; ++e) {
                 const int t = e * 256 + tid;
-                if (t < n) keys[t] = to_key(v[e]);
+                if (t < n) keys[t] = key_of(t, v[e]);
             }
             __syncthreads();
 #pragma unroll
@@ -345,7 +351,7 @@ __device__ __forceinline__ void topk_row(const int32_t *row, int n, int n_sel, i
 #pragma unroll
             for (int e = 0; e < TOPK_KPT; ++e) {
                 const int i = tid * kpt + e;
-                my[e] = (e < kpt && i < n) ? to_key(row[i]) + 1u : 0u;
+                my[e] = (e < kpt && i < n) ? key_of(i, row[i]) + 1u : 0u;
             }
         }
         __shared__ unsigned cnt_w[2][4];
@@ -405,11 +411,11 @@ __device__ __forceinline__ void topk_row(const int32_t *row, int n, int n_sel, i
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
                 const int t = t0 + e * 256 + tid;
-                if (t < n) keys[t] = to_key(v[e]);
+                if (t < n) keys[t] = key_of(t, v[e]);
             }
         }
     }
-    auto key_at = [&](int i) -> unsigned { return cached ? keys[i] : to_key(row[i]); };
+    auto key_at = [&](int i) -> unsigned { return cached ? keys[i] : key_of(i, row[i]); };
 
     // radix select, most significant digit first: after the loop `prefix` is the k-th largest key and
     // `remaining` the number of entries equal to it that belong to the selection
@@ -723,14 +729,14 @@ __global__ __launch_bounds__(256) void cross_fused_kernel(const unsigned short *
 __global__ __launch_bounds__(256) void topk_kernel(const int32_t *__restrict__ score, int row_stride,
                                                    const int32_t *__restrict__ len, int len_cap, int BK, int n_fixed,
                                                    int n_qb, int n_sel, int32_t *__restrict__ sel,
-                                                   int32_t *__restrict__ nsel) {
+                                                   int32_t *__restrict__ nsel, int n_sink, int n_local) {
     __shared__ unsigned keys[TOPK_LDS_CAP];
     const int b = blockIdx.x, h = blockIdx.y;
     int n = n_fixed;
     if (len) n = (min(len[h], len_cap) + BK - 1) / BK;
     n = min(n, row_stride);
     topk_row(score + ((size_t)h * n_qb + b) * row_stride, n, n_sel, sel + ((size_t)h * n_qb + b) * n_sel,
-             nsel + (size_t)h * n_qb + b, keys);
+             nsel + (size_t)h * n_qb + b, keys, n_sink, n_local);
 }
 
 // ---- selection on sign codes (LSH family) -------------------------------------------------------------
@@ -904,8 +910,9 @@ using namespace fastar;
 
 static int select_self_impl(const int8_t *qcode, int n_q, const int8_t *kcode, const int32_t *len, int H, int C, int r,
                             int BQ, int n_rep, int BK, int n_sel, int32_t *sel, int32_t *nsel, void *ws,
-                            size_t ws_bytes, void *stream) {
+                            size_t ws_bytes, void *stream, int n_sink = 0, int n_local = 0) {
     if (!qcode || !kcode || !len || !sel || !nsel || !ws) return FASTAR_ERR_INVALID_ARG;
+    if (n_sink < 0 || n_local < 0 || n_sink + n_local > n_sel) return FASTAR_ERR_INVALID_ARG;
     if (H <= 0 || n_q <= 0 || C <= 0 || BQ <= 0 || n_rep <= 0 || BK <= 0 || n_sel <= 0) return FASTAR_ERR_INVALID_ARG;
     if (BQ % n_rep != 0) return FASTAR_ERR_INVALID_ARG;
     if (((uintptr_t)qcode & 15) || ((uintptr_t)kcode & 15) || ((uintptr_t)ws & 255)) return FASTAR_ERR_INVALID_ARG;
@@ -944,7 +951,7 @@ static int select_self_impl(const int8_t *qcode, int n_q, const int8_t *kcode, c
 #undef FASTAR_SCORE
     FASTAR_LAUNCH_CHECK();
     hipLaunchKernelGGL(topk_kernel, dim3(n_qb, H), dim3(256), 0, s, score, n_kb_cap, len, C, BK, 0, n_qb, n_sel, sel,
-                       nsel);
+                       nsel, n_sink, n_local);
     FASTAR_LAUNCH_CHECK();
     return FASTAR_OK;
 }
@@ -953,6 +960,13 @@ extern "C" int ann_select_self(const int8_t *qcode, int n_q, const int8_t *kcode
                                int r, int BQ, int n_rep, int BK, int n_sel, int32_t *sel, int32_t *nsel, void *ws,
                                size_t ws_bytes, void *stream) {
     return select_self_impl(qcode, n_q, kcode, len, H, C, r, BQ, n_rep, BK, n_sel, sel, nsel, ws, ws_bytes, stream);
+}
+
+extern "C" int ann_select_self_forced(const int8_t *qcode, int n_q, const int8_t *kcode, const int32_t *len, int H,
+                                      int C, int r, int BQ, int n_rep, int BK, int n_sel, int n_sink, int n_local,
+                                      int32_t *sel, int32_t *nsel, void *ws, size_t ws_bytes, void *stream) {
+    return select_self_impl(qcode, n_q, kcode, len, H, C, r, BQ, n_rep, BK, n_sel, sel, nsel, ws, ws_bytes, stream, n_sink,
+                            n_local);
 }
 
 // ---- the same selection on the library's own static scratch, for callers that cannot allocate ----------------------
@@ -1073,7 +1087,7 @@ extern "C" int ann_select_lsh(const uint32_t *qbits, int n_q, const uint32_t *kb
                            n_qb, n_kb_cap, lds_words, score);
     FASTAR_LAUNCH_CHECK();
     hipLaunchKernelGGL(topk_kernel, dim3(n_qb, H), dim3(256), 0, s, score, n_kb_cap, len, C, BK, 0, n_qb, n_sel, sel,
-                       nsel);
+                       nsel, 0, 0);
     FASTAR_LAUNCH_CHECK();
     return FASTAR_OK;
 }

@@ -90,6 +90,23 @@ def test_ann_select_self_bit_exact(H, n_q, C, r, BQ, n_rep, BK, n_sel, lens, spa
     assert np.array_equal(to_host(sel), ref_sel)
 
 
+@pytest.mark.parametrize("H,n_q,C,lens,n_sel,n_sink,n_local", [
+    (2, 300, 64 * 40, [2560, 1000], 9, 2, 3),            # rows of 40 / 16 blocks (three radix passes)
+    (3, 3600, 64 * 3600, [230400, 200001, 64], 360, 4, 56),   # world-model rows (selection from registers), one tiny head
+    (2, 200, 64 * 30, [1920, 130], 5, 2, 3),             # forced blocks fill the budget; a head with fewer blocks than that
+    (1, 128, 64 * 200, [12800], 20, 0, 7), (1, 128, 64 * 200, [12800], 20, 6, 0)])
+def test_ann_select_self_with_forced_sink_and_local_blocks(H, n_q, C, lens, n_sel, n_sink, n_local):
+    rng = np.random.default_rng(n_q + C + n_sink)
+    qc, kc = rand_codes(rng, -40, 40, H, n_q, 32), rand_codes(rng, -40, 40, H, C, 32)
+    length = np.array(lens, np.int32)
+    ref_sel, ref_nsel = oracle.ann_select_self(qc, kc, length, 128, 4, 64, n_sel, n_sink, n_local)
+    sel, nsel = fa.ann_select_self(to_dev(qc), to_dev(kc), to_dev(length), 128, 4, 64, n_sel, n_sink=n_sink, n_local=n_local)
+    assert np.array_equal(to_host(nsel), ref_nsel)
+    assert np.array_equal(to_host(sel), ref_sel)
+    with pytest.raises(fa.FastarError):
+        fa.ann_select_self(to_dev(qc), to_dev(kc), to_dev(length), 128, 4, 64, 4, n_sink=3, n_local=2)
+
+
 @pytest.mark.parametrize("H,n_q,n_p,r,BQ,n_sel,span", [
     (2, 256, 64, 32, 128, 16, 60), (2, 4680, 512, 32, 128, 64, 50), (1, 300, 2048, 32, 128, 64, 4),
     (2, 100, 97, 64, 64, 10, 30), (1, 50, 20, 32, 128, 64, 30),
