@@ -638,6 +638,7 @@ def main():
     result = run_layer(args, args.workload, torch, fa, np, to_dev, to_host, args.steps, args.warmup, args.stage_steps,
                        with_cpu=not args.no_cpu_baseline, with_dense=not args.no_dense_equivalent)
     result["peaks_measured"] = {"mfma_bf16_tflops": round(fa.probe_mfma_bf16(), 1),
+                                "mfma_bf16_tflops_random_operands": round(fa.probe_mfma_bf16(random_operands=True), 1),
                                 "stream_copy_gbs": round(fa.probe_copy(), 1)}
     if args.workload == "cfg5full" and not args.no_extras:
         torch.cuda.empty_cache()

@@ -15,12 +15,15 @@ extern "C" {
 
 /*
  *   fastar_probe_mfma_bf16  register-resident bf16 32x32x16 matrix-instruction loop on every SIMD;
+ *                           random_operands = 0: every operand element is 1.0 / 0.5; 1: operands drawn per lane, uniform
+ *                           in (-2, 2).  The instruction stream is the same; the chip holds a lower clock under the
+ *                           second (its power limit), so the two rates bracket what real data can reach;
  *                           *flops_out (host) receives the floating-point operations one launch performs;
  *                           sink is a device float the kernel may write (never does in practice).
  *   fastar_probe_copy       plain streaming copy of `bytes` (multiple of 16) from src to dst (device, 16-byte aligned).
  * Both enqueue one kernel on `stream`; the caller times them.
  */
-int fastar_probe_mfma_bf16(int iters, float *sink, double *flops_out, void *stream);
+int fastar_probe_mfma_bf16(int iters, int random_operands, float *sink, double *flops_out, void *stream);
 int fastar_probe_copy(const void *src, void *dst, size_t bytes, void *stream);
 
 #ifdef __cplusplus

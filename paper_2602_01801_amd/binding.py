@@ -101,7 +101,7 @@ def lib() -> ctypes.CDLL:
         L.ann_select_lsh.argtypes = [ctypes.c_void_p, ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p] + \
             [ctypes.c_int] * 7 + [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
         L.fastar_probe_mfma_bf16.restype = ctypes.c_int
-        L.fastar_probe_mfma_bf16.argtypes = [ctypes.c_int, ctypes.c_void_p, ctypes.POINTER(ctypes.c_double), ctypes.c_void_p]
+        L.fastar_probe_mfma_bf16.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_void_p, ctypes.POINTER(ctypes.c_double), ctypes.c_void_p]
         L.fastar_probe_copy.restype = ctypes.c_int
         L.fastar_probe_copy.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
         _lib = L
@@ -435,15 +435,17 @@ def sparse_attn_fwd_fp8(Q, K8, V8T, cnt, length, C: int, sel, nsel, BQ: int, BK:
     return O, lse
 
 
-def probe_mfma_bf16(iters: int = 20000) -> float:
-    """Measured register-resident bf16 matrix-core rate in TFLOP/s (times one probe launch with events)."""
+def probe_mfma_bf16(iters: int = 20000, random_operands: bool = False) -> float:
+    """Measured register-resident bf16 matrix-core rate in TFLOP/s (times one probe launch with events); with
+    random_operands the multipliers see data like real keys and queries and the chip holds a lower clock."""
     sink = torch.zeros(1, dtype=torch.float32, device="cuda")
     flops = ctypes.c_double(0.0)
-    _check(lib().fastar_probe_mfma_bf16(200, sink.data_ptr(), ctypes.byref(flops), _stream()), "fastar_probe_mfma_bf16")
+    ro = 1 if random_operands else 0
+    _check(lib().fastar_probe_mfma_bf16(200, ro, sink.data_ptr(), ctypes.byref(flops), _stream()), "fastar_probe_mfma_bf16")
     torch.cuda.synchronize()
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     e0.record()
-    _check(lib().fastar_probe_mfma_bf16(iters, sink.data_ptr(), ctypes.byref(flops), _stream()), "fastar_probe_mfma_bf16")
+    _check(lib().fastar_probe_mfma_bf16(iters, ro, sink.data_ptr(), ctypes.byref(flops), _stream()), "fastar_probe_mfma_bf16")
     e1.record()
     torch.cuda.synchronize()
     return flops.value / (e0.elapsed_time(e1) * 1e-3) / 1e12

@@ -11,13 +11,26 @@ size_t select_lsh_ws_bytes(int H, int n_q, int C, int n_bits, int BQ, int BK, in
 namespace fastar {
 
 // Register-resident matrix-core loop: four independent bf16 32x32x16 accumulators per wavefront, no memory traffic.
+// RANDOM = false: every operand element is 1.0 / 0.5 (the data path hardly toggles); true: operands drawn per lane from
+// a hash, uniform in (-2, 2), four different pairs per wavefront (what real keys and queries look like to the
+// multipliers).  The chip's clock under the two differs, which is what the second one is for.
+template <bool RANDOM>
 __global__ __launch_bounds__(256) void probe_mfma_kernel(int iters, float *sink) {
-    bf16x8 a, b;
+    bf16x8 a[4], b[4];
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
-        a[i] = (__bf16)1.0f;
-        b[i] = (__bf16)0.5f;
-    }
+    for (int j = 0; j < 4; ++j)
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            if (RANDOM) {
+                unsigned x = (threadIdx.x * 64u + j * 8u + i) + blockIdx.x * 7919u;
+                x ^= x >> 16; x *= 0x7feb352du; x ^= x >> 15; x *= 0x846ca68bu; x ^= x >> 16;
+                a[j][i] = (__bf16)(((int)(x & 0xFFFF) - 32768) / 16384.0f);
+                b[j][i] = (__bf16)(((int)(x >> 16) - 32768) / 16384.0f);
+            } else {
+                a[j][i] = (__bf16)1.0f;
+                b[j][i] = (__bf16)0.5f;
+            }
+        }
     f32x16 acc[4];
 #pragma unroll
     for (int j = 0; j < 4; ++j)
@@ -25,7 +38,7 @@ __global__ __launch_bounds__(256) void probe_mfma_kernel(int iters, float *sink)
         for (int v = 0; v < 16; ++v) acc[j][v] = 0.0f;
     for (int i = 0; i < iters; ++i) {
 #pragma unroll
-        for (int j = 0; j < 4; ++j) acc[j] = mfma_bf16_32x32x16(a, b, acc[j]);
+        for (int j = 0; j < 4; ++j) acc[j] = mfma_bf16_32x32x16(a[j], b[j], acc[j]);
     }
     if (acc[0][0] + acc[1][1] + acc[2][2] + acc[3][3] == 12345.0f) sink[0] = 1.0f;
 }
@@ -38,10 +51,13 @@ __global__ __launch_bounds__(256) void probe_copy_kernel(const u32x4 *__restrict
 
 }  // namespace fastar
 
-extern "C" int fastar_probe_mfma_bf16(int iters, float *sink, double *flops_out, void *stream) {
+extern "C" int fastar_probe_mfma_bf16(int iters, int random_operands, float *sink, double *flops_out, void *stream) {
     if (iters <= 0 || !sink) return FASTAR_ERR_INVALID_ARG;
     const int wgs = 256 * 8;
-    hipLaunchKernelGGL(fastar::probe_mfma_kernel, dim3(wgs), dim3(256), 0, (hipStream_t)stream, iters, sink);
+    if (random_operands)
+        hipLaunchKernelGGL(fastar::probe_mfma_kernel<true>, dim3(wgs), dim3(256), 0, (hipStream_t)stream, iters, sink);
+    else
+        hipLaunchKernelGGL(fastar::probe_mfma_kernel<false>, dim3(wgs), dim3(256), 0, (hipStream_t)stream, iters, sink);
     if (hipGetLastError() != hipSuccess) return FASTAR_ERR_HIP;
     if (flops_out) *flops_out = (double)wgs * 4.0 * (double)iters * 4.0 * 32768.0;
     return FASTAR_OK;

@@ -177,7 +177,6 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_bf16_d128_kernel(
     // running softmax state per query (lanes l and l+32 hold the two key halves of query column l%32):
     // m_ref = reference maximum in raw score units, neg_ms = -m_ref * scale (0 while m_ref = -inf), l0/l1 = sums of P
     float m_ref = -INFINITY, neg_ms = 0.0f, l0 = 0.0f, l1 = 0.0f;
-    const float tau_raw = 8.0f * inv_scale_log2;   // the reference may lag the true maximum by 8 octaves: P <= 256
     typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
 
     // direct global -> LDS loads of one tile: instruction i of this wavefront covers tile rows
@@ -241,8 +240,11 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_bf16_d128_kernel(
         vaddr[db] = vbuf_lds + vrow_in * ROWB +
                     (((4 * db + 2 * (grp & 1) + ((s16 & 3) >> 1)) ^ ((vrow_in & 7) << 1)) << 4) + (s16 & 1) * 8;
 
-    auto tile_step = [&](int t, auto stage_c) {
+    // A wavefront whose 32 queries all lie beyond n_q (the ragged last block of a head) still loads its share of every
+    // tile and meets the barriers, but reads no operands and computes nothing.
+    auto tile_step = [&](int t, auto stage_c, auto active_c) {
         constexpr int STAGE = decltype(stage_c)::value;
+        constexpr bool ACTIVE = decltype(active_c)::value;
         __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): this wavefront's share of tile t has landed
         __syncthreads();                     // ... and everyone else's; tile t-1 fully consumed
         // row table of tile t+2, first half: issue its loads now
@@ -255,9 +257,10 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_bf16_d128_kernel(
         __builtin_amdgcn_sched_barrier(0);
         // K operands of keys 0..31: in flight while the next tile's loads are set up
         bf16x8 ka[D / 16], kb2[D / 16];
-        read_k<STAGE * TILEB>(ka, kaddr);
+        if constexpr (ACTIVE) read_k<STAGE * TILEB>(ka, kaddr);
         if (t + 1 < nt) issue_loads(meta[(t + 1) % 3], STAGE ^ 1);
         const TileMeta &mt = meta[t % 3];
+        if constexpr (ACTIVE) {
 
         // The score accumulators start from the keys' bias (register v is key row 8(v/4)+4g+v%4 of its half),
         // in units of raw scores, so K Q^T lands on top of it: masking and multiplicity cost no vector instruction.
@@ -280,16 +283,49 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_bf16_d128_kernel(
         read_vt<STAGE * TILEB>(va, vaddr);
 #pragma unroll
         for (int s = 0; s < D / 16; ++s) s_acc[1] = mfma_bf16_32x32x16(kb2[s], qf[s], s_acc[1]);
-        // P = exp2(scale * (S - m_ref)) with a lazily updated reference: O and the sums are rescaled only when
-        // some query of the wavefront exceeds its reference by more than tau, which after the first tiles is
-        // rare; any reference cancels in O / l, P just ranges up to 2^8 instead of 1.
-        float mx = s_acc[0][0];
+        // P = exp2(scale * (S - m_ref)) with a lazily updated reference (any reference cancels in O / l).
+        // The row maximum is not taken per tile: P is computed against the reference as it stands and the tile's own
+        // row sums tell whether some score ran away from it (a sum beyond 2^15, or an overflow); only then, and
+        // while a query has no reference yet, is the maximum taken and O and the sums rescaled.  The reference is
+        // always the maximum over some prefix of the keys, so nothing underflows that the exact maximum would keep.
+        bf16x2 ones;
+        ones[0] = (__bf16)1.0f;
+        ones[1] = (__bf16)1.0f;
+        bf16x8 pf[2][2];
+        float lt0, lt1;
+        auto compute_p = [&]() {
+            lt0 = 0.0f;
+            lt1 = 0.0f;
 #pragma unroll
-        for (int v = 1; v < 16; ++v) mx = fmaxf(mx, s_acc[0][v]);
+            for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-        for (int v = 0; v < 16; ++v) mx = fmaxf(mx, s_acc[1][v]);
-        mx = fmaxf(mx, shfl_xor(mx, 32));
-        if (__any(mx > m_ref + tau_raw)) {   // wave-uniform
+                for (int hh = 0; hh < 2; ++hh) {
+                    bf16x2 pr[4];
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        const float p0 = __builtin_amdgcn_exp2f(fmaf(s_acc[kb][8 * hh + 2 * j], scale_log2, neg_ms));
+                        const float p1 = __builtin_amdgcn_exp2f(fmaf(s_acc[kb][8 * hh + 2 * j + 1], scale_log2, neg_ms));
+                        pr[j][0] = (__bf16)p0;
+                        pr[j][1] = (__bf16)p1;
+                        // the sums take the rounded P, the values the PV product sees
+                        if (j & 1) lt1 = __builtin_amdgcn_fdot2_f32_bf16(pr[j], ones, lt1, false);
+                        else lt0 = __builtin_amdgcn_fdot2_f32_bf16(pr[j], ones, lt0, false);
+                    }
+                    __builtin_memcpy(&pf[kb][hh], pr, 16);
+                }
+        };
+        bool renew = __any(m_ref == -INFINITY);   // wave-uniform
+        if (!renew) {
+            compute_p();
+            renew = __any(!(lt0 + lt1 <= 32768.0f));
+        }
+        if (renew) {
+            float mx = s_acc[0][0];
+#pragma unroll
+            for (int v = 1; v < 16; ++v) mx = fmaxf(mx, s_acc[0][v]);
+#pragma unroll
+            for (int v = 0; v < 16; ++v) mx = fmaxf(mx, s_acc[1][v]);
+            mx = fmaxf(mx, shfl_xor(mx, 32));
             const float m_new = fmaxf(m_ref, mx);
             const float alpha = m_ref == -INFINITY ? 0.0f : __builtin_amdgcn_exp2f((m_ref - m_new) * scale_log2);
             m_ref = m_new;
@@ -300,34 +336,17 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_bf16_d128_kernel(
             for (int db = 0; db < D / 32; ++db)
 #pragma unroll
                 for (int v = 0; v < 16; ++v) o_acc[db][v] *= alpha;
+            compute_p();
         }
-        bf16x2 ones;
-        ones[0] = (__bf16)1.0f;
-        ones[1] = (__bf16)1.0f;
-        bf16x8 pf[2][2];
-#pragma unroll
-        for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-            for (int hh = 0; hh < 2; ++hh) {
-                bf16x2 pr[4];
-#pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    const float p0 = __builtin_amdgcn_exp2f(fmaf(s_acc[kb][8 * hh + 2 * j], scale_log2, neg_ms));
-                    const float p1 = __builtin_amdgcn_exp2f(fmaf(s_acc[kb][8 * hh + 2 * j + 1], scale_log2, neg_ms));
-                    pr[j][0] = (__bf16)p0;
-                    pr[j][1] = (__bf16)p1;
-                    // the sums take the rounded P, the values the PV product sees
-                    if (j & 1) l1 = __builtin_amdgcn_fdot2_f32_bf16(pr[j], ones, l1, false);
-                    else l0 = __builtin_amdgcn_fdot2_f32_bf16(pr[j], ones, l0, false);
-                }
-                __builtin_memcpy(&pf[kb][hh], pr, 16);
-            }
+        l0 += lt0;
+        l1 += lt1;
 
         wait_vt(va);
         read_vt<STAGE * TILEB + 32 * ROWB>(vb, vaddr);  // keys 32..63, land during the first eight products
         pv_mfma(o_acc, va, pf[0]);
         wait_vt(vb);
         pv_mfma(o_acc, vb, pf[1]);
+        }
 
         // row table of tile t+2, second half
         __builtin_amdgcn_sched_barrier(0);
@@ -338,9 +357,16 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_bf16_d128_kernel(
         }
         kb_ahead = kb3;
     };
-    for (int t = 0; t < nt; t += 2) {
-        tile_step(t, std::integral_constant<int, 0>{});
-        if (t + 1 < nt) tile_step(t + 1, std::integral_constant<int, 1>{});
+    if (b * (NW * 32) + wave * 32 < n_q) {   // wave-uniform
+        for (int t = 0; t < nt; t += 2) {
+            tile_step(t, std::integral_constant<int, 0>{}, std::true_type{});
+            if (t + 1 < nt) tile_step(t + 1, std::integral_constant<int, 1>{}, std::true_type{});
+        }
+    } else {
+        for (int t = 0; t < nt; t += 2) {
+            tile_step(t, std::integral_constant<int, 0>{}, std::false_type{});
+            if (t + 1 < nt) tile_step(t + 1, std::integral_constant<int, 1>{}, std::false_type{});
+        }
     }
 
     // epilogue: normalise, transpose through LDS (K stages are free now), store rows coalesced
