@@ -39,7 +39,8 @@ def _load():
         for name in ("oracle_encode", "oracle_tempcache_compress", "oracle_ann_select_self",
                      "oracle_ann_select_cross", "oracle_sparse_attn_fwd", "oracle_recall_density",
                      "oracle_encode_sign", "oracle_ann_select_lsh", "oracle_fp8_encode", "oracle_fp8_decode",
-                     "oracle_kv_to_fp8", "oracle_sparse_attn_fwd_fp8", "oracle_ann_select_self_forced"):
+                     "oracle_kv_to_fp8", "oracle_sparse_attn_fwd_fp8", "oracle_ann_select_self_forced",
+                     "oracle_prompt_buckets", "oracle_ann_select_buckets"):
             getattr(_lib, name).restype = ctypes.c_int
     return _lib
 
@@ -152,6 +153,34 @@ def ann_select_self(qcode, kcode, length, BQ: int, n_rep: int, BK: int, n_sel: i
     rc = _load().oracle_ann_select_self_forced(_p(qcode), n_q, _p(kcode), _p(length), H, C, r, BQ, n_rep, BK, n_sel,
                                                n_sink, n_local, _p(sel), _p(nsel))
     _check(rc, "oracle_ann_select_self_forced")
+    return sel, nsel
+
+
+def prompt_buckets(code, pcode, m: int = 1):
+    """code [H,n,r], pcode [H,n_p,r] -> bucket [H,n,m]: the m nearest prompt tokens of every code (best first)."""
+    code = _c(code, np.int8)
+    pcode = _c(pcode, np.int8)
+    H, n, r = code.shape
+    n_p = pcode.shape[1]
+    bucket = np.empty((H, n, m), np.int32)
+    _check(_load().oracle_prompt_buckets(_p(code), n, _p(pcode), n_p, H, r, m, _p(bucket)), "oracle_prompt_buckets")
+    return bucket
+
+
+def ann_select_buckets(qbucket, kbucket, length, n_p: int, BQ: int, BK: int, n_sel: int, n_sink: int = 0,
+                       n_local: int = 0):
+    """qbucket [H,n_q,m], kbucket [H,C,m], length [H] -> (sel [H,n_qb,n_sel], nsel): key blocks that share a
+    prompt-induced bucket with the query block, the n_sel with the most shared buckets."""
+    qbucket = _c(qbucket, np.int32)
+    kbucket = _c(kbucket, np.int32)
+    length = _c(length, np.int32)
+    H, n_q, m = qbucket.shape
+    C = kbucket.shape[1]
+    n_qb = (n_q + BQ - 1) // BQ
+    sel = np.empty((H, n_qb, n_sel), np.int32)
+    nsel = np.empty((H, n_qb), np.int32)
+    _check(_load().oracle_ann_select_buckets(_p(qbucket), n_q, _p(kbucket), _p(length), H, C, m, n_p, BQ, BK, n_sel,
+                                             n_sink, n_local, _p(sel), _p(nsel)), "oracle_ann_select_buckets")
     return sel, nsel
 
 

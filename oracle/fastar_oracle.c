@@ -25,6 +25,8 @@
  *                              (appendix ablation "Representative selection in KV merging").
  *   oracle_ann_select_self     Sec. 5.4 (AnnSA): keys a query block attends to, ranked by code score.
  *   oracle_ann_select_cross    Sec. 5.3 (AnnCA): prompt tokens with a neighbouring query in the block.
+ *   oracle_prompt_buckets,     Sec. 5.4, first paragraph: self-attention restricted to the semantic buckets found by
+ *   oracle_ann_select_buckets  cross-attention pruning; the prompt tokens are the buckets, a code belongs to its nearest ones.
  *   oracle_encode_sign         Sec. 5.1, LSH paragraph: one hash bit per random projection (its sign).
  *   oracle_ann_select_lsh      Sec. 5.3 / 5.4 on those hash codes: candidates ranked by the number of hash
  *                              bits they share with the query side (AnnSA with key blocks, AnnCA with BK = 1).
@@ -521,6 +523,103 @@ int oracle_ann_select_cross(const int8_t *qcode, int n_q, const int8_t *pcode, i
                 if (picked[p]) out[w++] = p;
             nsel[(int64_t)h * n_qb + b] = w;
             for (; w < n_sel; ++w) out[w] = -1;
+            free(score);
+            free(picked);
+        }
+    }
+    return 0;
+}
+
+/* ------------------------------------------------------------------ prompt-induced buckets (AnnCA -> AnnSA) */
+/*
+ * Sec. 5.4: self-attention reuses the semantic buckets found during cross-attention pruning (Sec. 5.3); a query is
+ * assigned to one or more buckets and attends only to keys of the same bucket(s).  Reading: the prompt tokens are the
+ * buckets.  A code belongs to the m prompt tokens with the largest code inner product c . c_p (the same products
+ * AnnCA ranks prompt tokens by), ties to the smaller token id.
+ * code [H,n,r], pcode [H,n_p,r] -> bucket [H,n,m] (token ids, best first; -1 where n_p < m).
+ */
+int oracle_prompt_buckets(const int8_t *code, int n, const int8_t *pcode, int n_p, int H, int r, int m,
+                          int32_t *bucket) {
+    if (!code || !pcode || !bucket) return -1;
+    if (H <= 0 || n < 0 || n_p < 0 || r <= 0 || m <= 0) return -1;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int h = 0; h < H; ++h) {
+        int64_t *score = malloc(sizeof(int64_t) * (size_t)(n_p > 0 ? n_p : 1));
+        uint8_t *taken = malloc((size_t)(n_p > 0 ? n_p : 1));
+        for (int i = 0; i < n; ++i) {
+            const int8_t *c = code + ((int64_t)h * n + i) * r;
+            for (int p = 0; p < n_p; ++p) score[p] = dot_i8(c, pcode + ((int64_t)h * n_p + p) * r, r);
+            memset(taken, 0, (size_t)(n_p > 0 ? n_p : 1));
+            for (int j = 0; j < m; ++j) {
+                int best = -1;
+                for (int p = 0; p < n_p; ++p) {
+                    if (taken[p]) continue;
+                    if (best < 0 || score[p] > score[best]) best = p;
+                }
+                if (best >= 0) taken[best] = 1;
+                bucket[((int64_t)h * n + i) * m + j] = best;
+            }
+        }
+        free(score);
+        free(taken);
+    }
+    return 0;
+}
+
+/*
+ * AnnSA on those buckets.  qbucket [H,n_q,m], kbucket [H,C,m] (entries -1 are ignored), len [H].
+ * A query block owns the buckets of its queries, a key block those of its live keys; the score of a key block is the
+ * number of buckets the two share.  Only key blocks that share at least one bucket are candidates ("only keys within
+ * the same bucket(s)"); of these the n_sel with the largest score are kept (ties: smaller block), written ascending
+ * to sel [H,n_qb,n_sel] (-1 padded), their number to nsel.  The first n_sink and the last n_local live key blocks
+ * are always kept and count against the budget, as in oracle_ann_select_self_forced.
+ */
+int oracle_ann_select_buckets(const int32_t *qbucket, int n_q, const int32_t *kbucket, const int32_t *len, int H,
+                              int C, int m, int n_p, int BQ, int BK, int n_sel, int n_sink, int n_local,
+                              int32_t *sel, int32_t *nsel) {
+    if (!qbucket || !kbucket || !len || !sel || !nsel) return -1;
+    if (H <= 0 || C <= 0 || m <= 0 || n_p <= 0 || BQ <= 0 || BK <= 0 || n_sel <= 0) return -1;
+    if (n_sink < 0 || n_local < 0 || n_sink + n_local > n_sel) return -1;
+    const int n_qb = (n_q + BQ - 1) / BQ;
+    const int n_kb_cap = (C + BK - 1) / BK;
+#pragma omp parallel for collapse(2) schedule(dynamic, 1)
+    for (int h = 0; h < H; ++h) {
+        for (int b = 0; b < n_qb; ++b) {
+            const int L = len[h] < C ? len[h] : C;
+            const int n_kb = (L + BK - 1) / BK;
+            uint8_t *own = calloc((size_t)n_p, 1);
+            uint8_t *has = malloc((size_t)n_p);
+            int64_t *score = malloc(sizeof(int64_t) * (size_t)(n_kb_cap > 0 ? n_kb_cap : 1));
+            uint8_t *picked = malloc((size_t)(n_kb_cap > 0 ? n_kb_cap : 1));
+            for (int q = b * BQ; q < (b + 1) * BQ && q < n_q; ++q)
+                for (int j = 0; j < m; ++j) {
+                    const int32_t t = qbucket[((int64_t)h * n_q + q) * m + j];
+                    if (t >= 0 && t < n_p) own[t] = 1;
+                }
+            int n_cand = 0;
+            for (int kb = 0; kb < n_kb; ++kb) {
+                memset(has, 0, (size_t)n_p);
+                for (int k = kb * BK; k < (kb + 1) * BK && k < L; ++k)
+                    for (int j = 0; j < m; ++j) {
+                        const int32_t t = kbucket[((int64_t)h * C + k) * m + j];
+                        if (t >= 0 && t < n_p) has[t] = 1;
+                    }
+                int64_t shared = 0;
+                for (int t = 0; t < n_p; ++t) shared += own[t] && has[t];
+                const int forced = kb < n_sink || kb >= n_kb - n_local;
+                score[kb] = forced ? INT64_MAX : (shared > 0 ? shared : -1); /* -1: shares nothing, no candidate */
+                n_cand += forced || shared > 0;
+            }
+            const int n_out = n_sel < n_cand ? n_sel : n_cand;
+            pick_top(score, n_kb, n_out, picked);
+            int32_t *out = sel + ((int64_t)h * n_qb + b) * n_sel;
+            int w = 0;
+            for (int kb = 0; kb < n_kb; ++kb)
+                if (picked[kb]) out[w++] = kb;
+            nsel[(int64_t)h * n_qb + b] = w;
+            for (; w < n_sel; ++w) out[w] = -1;
+            free(own);
+            free(has);
             free(score);
             free(picked);
         }
