@@ -59,6 +59,7 @@ extern "C" {
 #define FASTAR_OP_SELECT_SELF 2
 #define FASTAR_OP_SELECT_CROSS 3
 #define FASTAR_OP_SELECT_LSH 4
+#define FASTAR_OP_SELECT_BUCKETS 5 /* pass the number of prompt tokens as r */
 
 /* representative key of a merged TempCache group (tempcache_compress, rep_mode) */
 #define FASTAR_REP_LAST 0
@@ -122,6 +123,34 @@ size_t fastar_workspace_bytes(int op, int H, int n_q, int n_k, int r, int BQ, in
  */
 int fastar_encode(const void *x, int dtype, int64_t n_vec, int d, const fastar_codec *codec, int r,
                   int8_t *code_out, void *stream);
+
+/*
+ * Prompt-induced buckets (Sec. 5.4, first paragraph: self-attention reuses the semantic buckets found by
+ * cross-attention pruning; a query is assigned to one or more buckets and attends only to keys of the same
+ * bucket(s)).  The prompt tokens are the buckets: a code belongs to the m prompt tokens with the largest code inner
+ * product (the products ann_select_cross ranks prompt tokens by), ties to the smaller token id.
+ *   code   [H,C,r] int8 (device), pcode [H,n_p,r] int8 (device), both 16-byte aligned
+ *   idx    [H,n] int32 rows to assign (device; entries < 0 or >= C are skipped, repeats are harmless), or NULL for
+ *          rows 0..n-1 (n <= C): a caller that keeps one bucket row per cache slot re-assigns only the slots
+ *          tempcache_compress wrote (its merge_map)
+ *   bucket [H,C,m] int32 out (device): token ids, best first; -1 where n_p < m; rows not named are left as they are
+ * Supported: r in {32, 64}, n_p <= 2048, m <= 8.
+ */
+int ann_prompt_buckets(const int8_t *code, int C, const int32_t *idx, int n, const int8_t *pcode, int n_p, int H, int r,
+                       int m, int32_t *bucket, void *stream);
+
+/*
+ * AnnSA on those buckets: a query block owns the buckets of its queries, a key block those of its live keys; a key
+ * block is a candidate only if the two share a bucket; of the candidates the n_sel that share the most are kept
+ * (ties: lowest index), written ascending to sel, -1 padded; nsel = their number (it can be 0).  The first n_sink and
+ * the last n_local live key blocks are always kept and count against the budget (n_sink + n_local <= n_sel).
+ *   qbucket [H,n_q,m], kbucket [H,C,m] int32 (entries outside [0, n_p) are ignored), len [H];
+ *   sel [H,n_qb,n_sel], nsel [H,n_qb] out;  ws of fastar_workspace_bytes(FASTAR_OP_SELECT_BUCKETS, H, n_q, C, n_p, BQ, BK, 0).
+ * Supported: n_p <= 2048; ceil(n_q/BQ) * ceil(n_p/32) * 4 bytes <= 48 KiB.
+ */
+int ann_select_buckets(const int32_t *qbucket, int n_q, const int32_t *kbucket, const int32_t *len, int H, int C, int m,
+                       int n_p, int BQ, int BK, int n_sel, int n_sink, int n_local, int32_t *sel, int32_t *nsel, void *ws,
+                       size_t ws_bytes, void *stream);
 
 /*
  * Sign codes, the hash of the LSH paragraph of Sec. 5.1: one bit per random projection, the side of the

@@ -16,7 +16,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libfastar.so")
 
 F32, BF16 = 0, 1
-OP_COMPRESS, OP_SELECT_SELF, OP_SELECT_CROSS, OP_SELECT_LSH = 1, 2, 3, 4
+OP_COMPRESS, OP_SELECT_SELF, OP_SELECT_CROSS, OP_SELECT_LSH, OP_SELECT_BUCKETS = 1, 2, 3, 4, 5
 REP_LAST, REP_MEAN, REP_MEDOID = 0, 1, 2
 
 _lib = None
@@ -73,6 +73,12 @@ def lib() -> ctypes.CDLL:
         L.ann_select_self_forced.restype = ctypes.c_int
         L.ann_select_self_forced.argtypes = [ctypes.c_void_p, ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p] + \
             [ctypes.c_int] * 9 + [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
+        L.ann_prompt_buckets.restype = ctypes.c_int
+        L.ann_prompt_buckets.argtypes = [ctypes.c_void_p, ctypes.c_int, ctypes.c_void_p, ctypes.c_int, ctypes.c_void_p] + \
+            [ctypes.c_int] * 4 + [ctypes.c_void_p, ctypes.c_void_p]
+        L.ann_select_buckets.restype = ctypes.c_int
+        L.ann_select_buckets.argtypes = [ctypes.c_void_p, ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p] + \
+            [ctypes.c_int] * 9 + [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
         L.ann_select_self_static.restype = ctypes.c_int
         L.ann_select_self_static.argtypes = [ctypes.c_void_p, ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int,
                                              ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int,
@@ -110,7 +116,7 @@ def lib() -> ctypes.CDLL:
 
 EXPORTS = ("fastar_init", "fastar_version", "fastar_strerror", "fastar_workspace_bytes", "fastar_encode", "tempcache_compress",
            "ann_cross_attn_fwd",
-           "ann_select_self", "ann_select_self_forced", "ann_select_self_static", "ann_select_cross", "sparse_attn_fwd", "fastar_kv_to_fp8",
+           "ann_select_self", "ann_select_self_forced", "ann_select_self_static", "ann_prompt_buckets", "ann_select_buckets", "ann_select_cross", "sparse_attn_fwd", "fastar_kv_to_fp8",
            "sparse_attn_fwd_fp8", "fastar_encode_sign", "ann_select_lsh",
            "fastar_probe_mfma_bf16", "fastar_probe_copy")
 
@@ -293,6 +299,43 @@ def ann_select_self_static(qcode, kcode, length, BQ: int, n_rep: int, BK: int, n
         raise ValueError("out must be (sel [H,n_qb,n_sel], nsel [H,n_qb])")
     _check(lib().ann_select_self_static(qcode.data_ptr(), n_q, kcode.data_ptr(), length.data_ptr(), H, C, r, BQ, n_rep,
                                         BK, n_sel, sel.data_ptr(), nsel.data_ptr(), _stream()), "ann_select_self_static")
+    return sel, nsel
+
+
+def prompt_buckets(code, pcode, m: int = 1, idx=None, out=None):
+    """The m nearest prompt tokens of every code row: bucket [H,C,m] int32.  idx [H,n] int32 names the rows to assign
+    (the others keep what `out` holds); without it every row is assigned."""
+    _dev(code, torch.int8)
+    _dev(pcode, torch.int8)
+    H, C, r = code.shape
+    n_p = pcode.shape[1]
+    if out is None:
+        out = torch.full((H, C, m), -1, dtype=torch.int32, device=code.device)
+    if idx is not None:
+        _dev(idx, torch.int32)
+    n = C if idx is None else idx.shape[1]
+    _check(lib().ann_prompt_buckets(code.data_ptr(), C, idx.data_ptr() if idx is not None else None, n, pcode.data_ptr(),
+                                    n_p, H, r, m, out.data_ptr(), _stream()), "ann_prompt_buckets")
+    return out
+
+
+def ann_select_buckets(qbucket, kbucket, length, n_p: int, BQ: int, BK: int, n_sel: int, n_sink: int = 0, n_local: int = 0,
+                       ws=None, out=None):
+    """AnnSA on prompt-induced buckets: (sel [H,n_qb,n_sel] int32 ascending / -1 padded, nsel [H,n_qb] int32)."""
+    _dev(qbucket, torch.int32)
+    _dev(kbucket, torch.int32)
+    _dev(length, torch.int32)
+    H, n_q, m = qbucket.shape
+    C = kbucket.shape[1]
+    n_qb = (n_q + BQ - 1) // BQ
+    ws = _workspace(ws, workspace_bytes(OP_SELECT_BUCKETS, H, n_q, C, n_p, BQ, BK, 0), qbucket.device)
+    if out is None:
+        out = (torch.empty((H, n_qb, n_sel), dtype=torch.int32, device=qbucket.device),
+               torch.empty((H, n_qb), dtype=torch.int32, device=qbucket.device))
+    sel, nsel = out
+    _check(lib().ann_select_buckets(qbucket.data_ptr(), n_q, kbucket.data_ptr(), length.data_ptr(), H, C, m, n_p, BQ, BK,
+                                    n_sel, n_sink, n_local, sel.data_ptr(), nsel.data_ptr(), ws.data_ptr(),
+                                    ws.numel() * ws.element_size(), _stream()), "ann_select_buckets")
     return sel, nsel
 
 

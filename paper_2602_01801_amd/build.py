@@ -9,11 +9,11 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libfastar.so")
 SOURCES = ["api.hip", "encode.hip", "select.hip", "tempcache.hip", "attention.hip", "attention_d128.hip",
-           "attention_d128_pp.hip", "attention_fp8.hip"]
+           "attention_d128_pp.hip", "attention_fp8.hip", "buckets.hip"]
 ASM_CHECKED = ["attention_d128.hip", "attention_d128_pp.hip"]  # kernels that read LDS through inline assembly
 # Integer matrix-core results that feed plain ALU epilogues (arg-max, top-k scores): keep them in ordinary vector
 # registers, not accumulation registers that every ALU instruction would first have to copy from.
-PER_SOURCE_FLAGS = {src: ["-mllvm", "-amdgpu-mfma-vgpr-form"] for src in ("tempcache.hip", "select.hip", "encode.hip")}
+PER_SOURCE_FLAGS = {src: ["-mllvm", "-amdgpu-mfma-vgpr-form"] for src in ("tempcache.hip", "select.hip", "encode.hip", "buckets.hip")}
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-fast-math", "-ffp-contract=on",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wno-unused-command-line-argument"]
 
