@@ -40,7 +40,7 @@ def _load():
                      "oracle_ann_select_cross", "oracle_sparse_attn_fwd", "oracle_recall_density",
                      "oracle_encode_sign", "oracle_ann_select_lsh", "oracle_fp8_encode", "oracle_fp8_decode",
                      "oracle_kv_to_fp8", "oracle_sparse_attn_fwd_fp8", "oracle_ann_select_self_forced",
-                     "oracle_prompt_buckets", "oracle_ann_select_buckets"):
+                     "oracle_prompt_buckets", "oracle_ann_select_buckets", "oracle_encode_packed", "oracle_unpack_codes"):
             getattr(_lib, name).restype = ctypes.c_int
     return _lib
 
@@ -81,6 +81,29 @@ def encode(x: np.ndarray, R: np.ndarray, qscale, shift: int) -> np.ndarray:
     rc = _load().oracle_encode(_p(x), _dtype_code(x), ctypes.c_int64(n_vec), d, _p(R), r,
                                ctypes.c_float(float(np.float32(qscale))), int(shift), _p(code))
     _check(rc, "oracle_encode")
+    return code
+
+
+def encode_packed(x: np.ndarray, R: np.ndarray, qscale, shift: int, bits: int) -> np.ndarray:
+    """x [..., d] (storage form) -> packed codes [..., r*bits/8] uint8, `bits` per entry (2, 4 or 8)."""
+    x = _c(x)
+    R = _c(R, np.int8)
+    d, r = R.shape
+    assert x.shape[-1] == d
+    n_vec = x.size // d
+    packed = np.empty(x.shape[:-1] + (r * bits // 8,), dtype=np.uint8)
+    rc = _load().oracle_encode_packed(_p(x), _dtype_code(x), ctypes.c_int64(n_vec), d, _p(R), r,
+                                      ctypes.c_float(float(np.float32(qscale))), int(shift), int(bits), _p(packed))
+    _check(rc, "oracle_encode_packed")
+    return packed
+
+
+def unpack_codes(packed: np.ndarray, r: int, bits: int) -> np.ndarray:
+    """packed [..., r*bits/8] uint8 -> int8 entries [..., r]."""
+    packed = _c(packed, np.uint8)
+    n_vec = packed.size // (r * bits // 8)
+    code = np.empty(packed.shape[:-1] + (r,), dtype=np.int8)
+    _check(_load().oracle_unpack_codes(_p(packed), ctypes.c_int64(n_vec), r, int(bits), _p(code)), "oracle_unpack_codes")
     return code
 
 

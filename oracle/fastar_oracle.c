@@ -17,6 +17,8 @@
  *   oracle_encode              Sec. 5.1 "Attention as approximate nearest neighbour search":
  *                              shared low-dimensional random projection (LSH paragraph) of
  *                              low-bit quantised vectors (quantised-search paragraph, 8 bit).
+ *   oracle_encode_packed,      the same codes at 2 or 4 bits per entry, packed (appendix ablation "Quantization precision
+ *   oracle_unpack_codes        for ANN matching"); selection on them is oracle_ann_select_self on the unpacked entries.
  *   oracle_tempcache_compress  Sec. 5.2 "KV cache compression using temporal correspondence":
  *                              top-1 neighbour of every new token among cached keys, merge when
  *                              the key similarity passes a threshold, keep the most recent key,
@@ -120,6 +122,47 @@ int oracle_encode(const void *x, int dtype, int64_t n_vec, int d, const int8_t *
     if (!x || !R || !code || d <= 0 || r <= 0 || shift < 1) return -1;
 #pragma omp parallel for schedule(static)
     for (int64_t v = 0; v < n_vec; ++v) encode_vec(x, dtype, v * d, d, R, r, qscale, shift, code + v * r);
+    return 0;
+}
+
+/*
+ * Codes that are really `bits` wide (appendix, "Quantization precision for ANN matching": the retrieval codes' bit
+ * width is varied; narrower codes are cheaper to store and to stream).  Same projection; the last step saturates to
+ * the range of a `bits`-bit two's complement number without its most negative value, +-(2^(bits-1) - 1), and entry j
+ * of a vector occupies bits [bits*(j mod 8/bits), +bits) of byte j / (8/bits).  bits in {2, 4, 8}; 8 is oracle_encode.
+ * x [n_vec, d] -> packed [n_vec, r*bits/8] bytes.
+ */
+int oracle_encode_packed(const void *x, int dtype, int64_t n_vec, int d, const int8_t *R, int r, float qscale,
+                         int shift, int bits, uint8_t *packed) {
+    if (!x || !R || !packed || d <= 0 || r <= 0 || shift < 1) return -1;
+    if ((bits != 2 && bits != 4 && bits != 8) || (r * bits) % 8 != 0) return -1;
+    const int lim = (1 << (bits - 1)) - 1, per = 8 / bits;
+    const int64_t row = (int64_t)r * bits / 8;
+#pragma omp parallel for schedule(static)
+    for (int64_t v = 0; v < n_vec; ++v) {
+        memset(packed + v * row, 0, (size_t)row);
+        for (int j = 0; j < r; ++j) {
+            int64_t y = 0;
+            for (int t = 0; t < d; ++t)
+                y += (int64_t)R[(int64_t)t * r + j] * quant8(load_f32(x, dtype, v * d + t), qscale);
+            const int c = clampi(floor_div(y + ((int64_t)1 << (shift - 1)), (int64_t)1 << shift), -lim, lim);
+            packed[v * row + j / per] |= (uint8_t)(((unsigned)c & ((1u << bits) - 1u)) << (bits * (j % per)));
+        }
+    }
+    return 0;
+}
+
+/* packed [n_vec, r*bits/8] -> code [n_vec, r] int8: the entries of oracle_encode_packed, sign-extended. */
+int oracle_unpack_codes(const uint8_t *packed, int64_t n_vec, int r, int bits, int8_t *code) {
+    if (!packed || !code || r <= 0 || (bits != 2 && bits != 4 && bits != 8) || (r * bits) % 8 != 0) return -1;
+    const int per = 8 / bits;
+    const int64_t row = (int64_t)r * bits / 8;
+    for (int64_t v = 0; v < n_vec; ++v)
+        for (int j = 0; j < r; ++j) {
+            int c = (packed[v * row + j / per] >> (bits * (j % per))) & ((1 << bits) - 1);
+            if (c >= 1 << (bits - 1)) c -= 1 << bits;
+            code[v * r + j] = (int8_t)c;
+        }
     return 0;
 }
 

@@ -94,3 +94,49 @@ def test_scores_are_integers_below_2_pow_24():
     # |2 c.c' - c'.c'| <= 3 r 127^2 both stay below 2^24 for r <= 64
     for r in (32, 64):
         assert 3 * r * 127 * 127 < 2 ** 24
+
+
+# ------------------------------------------------------------------ codes of 2 and 4 bits per entry, packed
+# (appendix, "Quantization precision for ANN matching": the bit width of the retrieval codes is varied)
+
+def _np_unpack(packed, r, bits):
+    per = 8 // bits
+    j = np.arange(r)
+    c = (packed[..., j // per].astype(np.int32) >> (bits * (j % per))) & ((1 << bits) - 1)
+    return np.where(c >= 1 << (bits - 1), c - (1 << bits), c).astype(np.int8)
+
+
+@pytest.mark.parametrize("bits", [2, 4, 8])
+@pytest.mark.parametrize("dtype", ["fp32", "bf16"])
+def test_packed_codes_are_the_8_bit_codes_saturated_to_the_narrow_range(bits, dtype):
+    from workloads import make_codec, to_storage
+    rng = np.random.default_rng(bits)
+    d, r = 128, 32
+    codec = make_codec(0, 1, d, r)
+    x = to_storage((1.2 * rng.standard_normal((3, 50, d))).astype(np.float32), dtype)
+    lim = (1 << (bits - 1)) - 1
+    for shift in (4, 6, 8, 9):
+        wide = oracle.encode(x, codec.R, codec.qscale, shift)
+        packed = oracle.encode_packed(x, codec.R, codec.qscale, shift, bits)
+        assert packed.shape == (3, 50, r * bits // 8) and packed.dtype == np.uint8
+        got = _np_unpack(packed, r, bits)
+        assert np.array_equal(got, np.clip(wide, -lim, lim))
+        assert np.array_equal(oracle.unpack_codes(packed, r, bits), got)
+        if bits == 8:
+            assert np.array_equal(packed.view(np.int8), wide)
+        elif shift == 4:
+            assert (np.abs(got) == lim).any() and (np.abs(wide) > lim).any()      # the narrow range does saturate here
+
+
+def test_packed_layout_by_hand():
+    # d = 4, r = 4, R = identity-like signs: y = +-xq, shift 1: c = floor((y + 1) / 2)
+    R = np.array([[1, 0, 0, 0], [0, 1, 0, 0], [0, 0, -1, 0], [0, 0, 0, 1]], np.int8)
+    x = np.array([[2.0, -2.0, 9.0, 100.0]], np.float32)          # xq = 2, -2, 9, 100 -> y = 2, -2, -9, 100
+    # c8 = floor(3/2), floor(-1/2), floor(-8/2), floor(101/2) = 1, -1, -4, 50
+    assert oracle.encode(x, R, 1.0, 1).tolist() == [[1, -1, -4, 50]]
+    # 4 bits: 1, -1, -4, 7 -> nibbles 0x1, 0xF, 0xC, 0x7 -> bytes 0xF1, 0x7C
+    assert oracle.encode_packed(x, R, 1.0, 1, 4).tolist() == [[0xF1, 0x7C]]
+    # 2 bits: 1, -1, -1, 1 -> 01, 11, 11, 01 from the low end -> 0b01111101
+    assert oracle.encode_packed(x, R, 1.0, 1, 2).tolist() == [[0b01111101]]
+    assert oracle.unpack_codes(np.array([[0xF1, 0x7C]], np.uint8), 4, 4).tolist() == [[1, -1, -4, 7]]
+    assert oracle.unpack_codes(np.array([[0b01111101]], np.uint8), 4, 2).tolist() == [[1, -1, -1, 1]]
