@@ -153,6 +153,26 @@ int ann_select_buckets(const int32_t *qbucket, int n_q, const int32_t *kbucket, 
                        size_t ws_bytes, void *stream);
 
 /*
+ * Codes that are really `bits` wide (appendix, "Quantization precision for ANN matching": the bit width of the
+ * retrieval codes is varied; narrower codes are cheaper to store and to stream).  As fastar_encode, but the last step
+ * saturates to +-(2^(bits-1) - 1) and entry j of a vector occupies bits [bits*(j mod 8/bits), +bits) of byte
+ * j / (8/bits): packed_out [n_vec, r*bits/8] uint8 (device, 4-byte aligned).  bits in {2, 4, 8}; 8 is fastar_encode.
+ * Supported for bits < 8: r = 32.
+ */
+int fastar_encode_packed(const void *x, int dtype, int64_t n_vec, int d, const fastar_codec *codec, int r, int bits,
+                         uint8_t *packed_out, void *stream);
+
+/*
+ * ann_select_self_forced on such packed codes: qcode [H,n_q,r*bits/8], kcode [H,C,r*bits/8]; the result is that of
+ * ann_select_self_forced on the unpacked entries.  The key codes are streamed as they are stored (r*bits/8 bytes per
+ * key) and widened in registers.  Same workspace as ann_select_self (the summaries are kept one byte per entry).
+ * Supported for bits < 8: r = 32.
+ */
+int ann_select_self_packed(const int8_t *qcode, int n_q, const int8_t *kcode, const int32_t *len, int H, int C, int r,
+                           int bits, int BQ, int n_rep, int BK, int n_sel, int n_sink, int n_local, int32_t *sel,
+                           int32_t *nsel, void *ws, size_t ws_bytes, void *stream);
+
+/*
  * Sign codes, the hash of the LSH paragraph of Sec. 5.1: one bit per random projection, the side of the
  * hyperplane the quantised vector lies on.  bit j = 1 iff sum_t R[t][j] * xq[t] >= 0, xq as in fastar_codec.
  *   x        [n_vec, d] dtype (device), d in {64, 128}

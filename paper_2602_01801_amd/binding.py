@@ -79,6 +79,12 @@ def lib() -> ctypes.CDLL:
         L.ann_select_buckets.restype = ctypes.c_int
         L.ann_select_buckets.argtypes = [ctypes.c_void_p, ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p] + \
             [ctypes.c_int] * 9 + [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
+        L.fastar_encode_packed.restype = ctypes.c_int
+        L.fastar_encode_packed.argtypes = [ctypes.c_void_p, ctypes.c_int, ctypes.c_int64, ctypes.c_int,
+                                           ctypes.POINTER(_CodecStruct), ctypes.c_int, ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p]
+        L.ann_select_self_packed.restype = ctypes.c_int
+        L.ann_select_self_packed.argtypes = [ctypes.c_void_p, ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p] + \
+            [ctypes.c_int] * 10 + [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
         L.ann_select_self_static.restype = ctypes.c_int
         L.ann_select_self_static.argtypes = [ctypes.c_void_p, ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int,
                                              ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int,
@@ -116,7 +122,7 @@ def lib() -> ctypes.CDLL:
 
 EXPORTS = ("fastar_init", "fastar_version", "fastar_strerror", "fastar_workspace_bytes", "fastar_encode", "tempcache_compress",
            "ann_cross_attn_fwd",
-           "ann_select_self", "ann_select_self_forced", "ann_select_self_static", "ann_prompt_buckets", "ann_select_buckets", "ann_select_cross", "sparse_attn_fwd", "fastar_kv_to_fp8",
+           "ann_select_self", "ann_select_self_forced", "ann_select_self_static", "ann_prompt_buckets", "ann_select_buckets", "fastar_encode_packed", "ann_select_self_packed", "ann_select_cross", "sparse_attn_fwd", "fastar_kv_to_fp8",
            "sparse_attn_fwd_fp8", "fastar_encode_sign", "ann_select_lsh",
            "fastar_probe_mfma_bf16", "fastar_probe_copy")
 
@@ -223,6 +229,40 @@ def encode(x: torch.Tensor, codec: Codec, out: torch.Tensor | None = None) -> to
     _check(lib().fastar_encode(x.data_ptr(), _dtype_code(x), n_vec, d, ctypes.byref(cs), r, out.data_ptr(), _stream()),
            "fastar_encode")
     return out
+
+
+def encode_packed(x: torch.Tensor, codec: Codec, bits: int, out: torch.Tensor | None = None) -> torch.Tensor:
+    """x [..., d] -> codes of `bits` (2, 4 or 8) bits per entry, packed: uint8 [..., r*bits/8]."""
+    _dev(x)
+    d, r = codec.R.shape
+    n_vec = x.numel() // d
+    if out is None:
+        out = torch.empty(x.shape[:-1] + (r * bits // 8,), dtype=torch.uint8, device=x.device)
+    cs = codec.struct()
+    _check(lib().fastar_encode_packed(x.data_ptr(), _dtype_code(x), n_vec, d, ctypes.byref(cs), r, bits, out.data_ptr(),
+                                      _stream()), "fastar_encode_packed")
+    return out
+
+
+def ann_select_self_packed(qcode, kcode, length, bits: int, BQ: int, n_rep: int, BK: int, n_sel: int, n_sink: int = 0,
+                           n_local: int = 0, ws=None, out=None):
+    """AnnSA on packed codes (uint8 [H,n,r*bits/8]): the selection ann_select_self makes on the unpacked entries."""
+    _dev(qcode, torch.uint8)
+    _dev(kcode, torch.uint8)
+    _dev(length, torch.int32)
+    H, n_q, rb = qcode.shape
+    r = rb * 8 // bits
+    C = kcode.shape[1]
+    n_qb = (n_q + BQ - 1) // BQ
+    ws = _workspace(ws, workspace_bytes(OP_SELECT_SELF, H, n_q, C, r, BQ, BK, n_rep), qcode.device)
+    if out is None:
+        out = (torch.empty((H, n_qb, n_sel), dtype=torch.int32, device=qcode.device),
+               torch.empty((H, n_qb), dtype=torch.int32, device=qcode.device))
+    sel, nsel = out
+    _check(lib().ann_select_self_packed(qcode.data_ptr(), n_q, kcode.data_ptr(), length.data_ptr(), H, C, r, bits, BQ,
+                                        n_rep, BK, n_sel, n_sink, n_local, sel.data_ptr(), nsel.data_ptr(), ws.data_ptr(),
+                                        ws.numel() * ws.element_size(), _stream()), "ann_select_self_packed")
+    return sel, nsel
 
 
 def tempcache_compress(cache: Cache, codec: Codec, K_new, V_new, P_new=None, cand=None, metric: int = 0,

@@ -78,6 +78,41 @@ int encode_launch(const void *x, int dtype, int64_t n_vec, int d, const fastar_c
     return FASTAR_OK;
 }
 
+// ---- codes of 2 or 4 bits per entry, packed (appendix, "Quantization precision for ANN matching") -------------------
+// Same operands as encode_kernel; a lane ends with four entries of one vector = BITS / 2 bytes.
+template <bool BF16, int D, int R, int BITS>
+__global__ __launch_bounds__(256) void encode_packed_kernel(const void *__restrict__ x, int64_t n_vec,
+                                                            const int8_t *__restrict__ Rm, float qscale, int shift,
+                                                            uint8_t *__restrict__ packed) {
+    constexpr int KS = D / 64, CB = R / 16;
+    constexpr int ROWB = R * BITS / 8;
+    const int lane = lane_id();
+    const int col = lane & 15, g = lane >> 4;
+    CodeMatrix<BF16, D, R> cm;
+    cm.load(Rm, lane);
+    const int64_t gtid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int64_t wave = gtid >> 6, n_waves = ((int64_t)gridDim.x * blockDim.x) >> 6;
+    const int64_t n_groups = (n_vec + 15) >> 4;
+    const size_t row_bytes = (size_t)D * (BF16 ? 2 : 4);
+    for (int64_t grp = wave; grp < n_groups; grp += n_waves) {
+        const int64_t vec = grp * 16 + col;
+        const int64_t vload = vec < n_vec ? vec : n_vec - 1;
+        const char *row = (const char *)x + (size_t)vload * row_bytes;
+        i32x4 b[KS];
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) b[ks] = load_quantised<BF16>(row, ks, g, qscale);
+#pragma unroll
+        for (int cb = 0; cb < CB; ++cb) {
+            const unsigned w = cm.template code_bits<BITS>(b, cb, shift);
+            if (vec < n_vec) {
+                uint8_t *dst = packed + vec * ROWB + (cb * 16 + 4 * g) * BITS / 8;
+                if (BITS == 4) *(unsigned short *)dst = (unsigned short)w;
+                else *dst = (uint8_t)w;
+            }
+        }
+    }
+}
+
 // ---- sign codes (LSH paragraph of Sec. 5.1): bit j = [ (R^T xq)_j >= 0 ] --------------------------------------
 // Same operand layout as encode_kernel; NB hash bits = NB/16 blocks of 16 rows of R^T.  A lane ends with the 4 sign
 // bits (rows 4g+v of a block) of one vector per block; two blocks and the four quarters g make one 32-bit word,
@@ -151,6 +186,36 @@ static void launch_encode_sign(const void *x, int64_t n_vec, const int8_t *R, fl
 extern "C" int fastar_encode(const void *x, int dtype, int64_t n_vec, int d, const fastar_codec *codec, int r,
                              int8_t *code_out, void *stream) {
     return fastar::encode_launch(x, dtype, n_vec, d, codec, r, code_out, nullptr, 0, (hipStream_t)stream);
+}
+
+extern "C" int fastar_encode_packed(const void *x, int dtype, int64_t n_vec, int d, const fastar_codec *codec, int r,
+                                    int bits, uint8_t *packed_out, void *stream) {
+    using namespace fastar;
+    if (bits == 8) return encode_launch(x, dtype, n_vec, d, codec, r, (int8_t *)packed_out, nullptr, 0, (hipStream_t)stream);
+    if (!x || !codec || !codec->R || !packed_out || n_vec < 0) return FASTAR_ERR_INVALID_ARG;
+    if (dtype != FASTAR_F32 && dtype != FASTAR_BF16) return FASTAR_ERR_INVALID_ARG;
+    if (bits != 2 && bits != 4) return FASTAR_ERR_INVALID_ARG;
+    if (codec->shift < 1 || codec->shift > 16) return FASTAR_ERR_INVALID_ARG;
+    if ((d != 64 && d != 128) || r != 32) return FASTAR_ERR_UNSUPPORTED;
+    if (((uintptr_t)x & 15) || ((uintptr_t)packed_out & 3)) return FASTAR_ERR_INVALID_ARG;
+    if (n_vec == 0) return FASTAR_OK;
+    hipStream_t s = (hipStream_t)stream;
+    int64_t blocks = ((n_vec + 15) / 16 + 3) / 4;
+    if (blocks > 4096) blocks = 4096;
+#define FASTAR_ENCP(B, DD, BB)                                                                                       \
+    hipLaunchKernelGGL((encode_packed_kernel<B, DD, 32, BB>), dim3((unsigned)blocks), dim3(256), 0, s, x, n_vec, codec->R, \
+                       codec->qscale, codec->shift, packed_out)
+    const bool bf = dtype == FASTAR_BF16;
+    if (d == 64) {
+        if (bits == 4) { if (bf) FASTAR_ENCP(true, 64, 4); else FASTAR_ENCP(false, 64, 4); }
+        else { if (bf) FASTAR_ENCP(true, 64, 2); else FASTAR_ENCP(false, 64, 2); }
+    } else {
+        if (bits == 4) { if (bf) FASTAR_ENCP(true, 128, 4); else FASTAR_ENCP(false, 128, 4); }
+        else { if (bf) FASTAR_ENCP(true, 128, 2); else FASTAR_ENCP(false, 128, 2); }
+    }
+#undef FASTAR_ENCP
+    FASTAR_LAUNCH_CHECK();
+    return FASTAR_OK;
 }
 
 extern "C" int fastar_encode_sign(const void *x, int dtype, int64_t n_vec, int d, const int8_t *R, float qscale,

@@ -76,6 +76,21 @@ struct CodeMatrix {
         for (int ks = 0; ks < KS; ++ks) acc = mfma_i8_16x16x64(a[ks][cb], b[ks], acc);
         return pack_i8x4(requant(acc[0], shift), requant(acc[1], shift), requant(acc[2], shift), requant(acc[3], shift));
     }
+    // The same four entries at BITS (2 or 4) bits each, saturated to +-(2^(BITS-1) - 1), entry v in bits [BITS*v, +BITS).
+    template <int BITS>
+    __device__ __forceinline__ unsigned code_bits(const i32x4 (&b)[KS], int cb, int shift) const {
+        i32x4 acc = {0, 0, 0, 0};
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) acc = mfma_i8_16x16x64(a[ks][cb], b[ks], acc);
+        constexpr int LIM = (1 << (BITS - 1)) - 1;
+        unsigned w = 0;
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+            const int c = min(max((acc[v] + (1 << (shift - 1))) >> shift, -LIM), LIM);
+            w |= ((unsigned)c & ((1u << BITS) - 1u)) << (BITS * v);
+        }
+        return w;
+    }
 };
 
 }  // namespace fastar

@@ -22,39 +22,80 @@ constexpr int COL_CHUNK = 8;       // summary column blocks (of 32) kept in regi
 
 static inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
+// ---- codes narrower than a byte -----------------------------------------------------------------------
+// Codes of BITS (2, 4 or 8) bits per entry, packed from the low end of each byte (appendix, "Quantization precision for
+// ANN matching").  Key codes stay packed in memory and are widened in registers, as the matrix operand of one lane half
+// (16 entries): an entry is moved to the TOP bits of its byte, i.e. multiplied by 2^(8-BITS) - the same factor on every
+// score of a call, so no ranking changes - which needs one shift and one mask per four entries and no sign extension.
+// Byte i of output word t then holds entry (8/BITS) * i' + t of its word; the summaries are stored in the same order.
+template <int BITS>
+__device__ __forceinline__ i32x4 load_key_codes(const int8_t *p) {   // p: the lane half's 16 * BITS / 8 bytes
+    i32x4 a;
+    if constexpr (BITS == 8) {
+        a = *(const i32x4 *)p;
+    } else if constexpr (BITS == 4) {
+        const u32x2 w = *(const u32x2 *)p;
+        a[0] = (int)((w[0] << 4) & 0xF0F0F0F0u);
+        a[1] = (int)(w[0] & 0xF0F0F0F0u);
+        a[2] = (int)((w[1] << 4) & 0xF0F0F0F0u);
+        a[3] = (int)(w[1] & 0xF0F0F0F0u);
+    } else {
+        const unsigned w = *(const unsigned *)p;
+        a[0] = (int)((w << 6) & 0xC0C0C0C0u);
+        a[1] = (int)((w << 4) & 0xC0C0C0C0u);
+        a[2] = (int)((w << 2) & 0xC0C0C0C0u);
+        a[3] = (int)(w & 0xC0C0C0C0u);
+    }
+    return a;
+}
+// position, inside its group of 16, at which entry e of a summary is stored so that it meets the widened key entries
+template <int BITS>
+__device__ __forceinline__ int summary_slot(int e) {
+    if constexpr (BITS == 8) return e;
+    else if constexpr (BITS == 4) return (e & 8) + ((e & 1) << 2) + ((e & 7) >> 1);
+    else return ((e & 3) << 2) + (e >> 2);
+}
+
 // ---- query-block summaries ------------------------------------------------------------------------
 // rep[h][b*n_rep + u][j] = floor((sum over the u-th run of g queries of block b of qcode[.][j] + g/2) / g)
+template <int BITS>
 __global__ void rep_kernel(const int8_t *__restrict__ qcode, int n_q, int r, int BQ, int n_rep, int n_qb,
                            int8_t *__restrict__ rep) {
     const int b = blockIdx.x, h = blockIdx.y;
     const int g = BQ / n_rep;
+    constexpr int PER = 8 / BITS;
+    const int rb = r / PER;   // bytes per query row
     for (int t = threadIdx.x; t < n_rep * r; t += blockDim.x) {
         const int u = t / r, j = t % r;
         const int q0 = b * BQ + u * g;
         const int q1 = min(q0 + g, n_q);
         int s = 0;
-        const int8_t *col = qcode + ((size_t)h * n_q + q0) * r + j;
+        const int8_t *col = qcode + ((size_t)h * n_q + q0) * rb + j / PER;
+        const int up = 32 - BITS * (j % PER + 1);   // shift that puts the entry at the top of a word, then arithmetic shift down
         const int n = q1 - q0;
         int q = 0;
         for (; q + 8 <= n; q += 8) {   // eight independent loads in flight
             int v[8];
 #pragma unroll
-            for (int e = 0; e < 8; ++e) v[e] = col[(size_t)(q + e) * r];
+            for (int e = 0; e < 8; ++e) v[e] = col[(size_t)(q + e) * rb];
 #pragma unroll
-            for (int e = 0; e < 8; ++e) s += v[e];
+            for (int e = 0; e < 8; ++e) s += BITS == 8 ? v[e] : ((int)((unsigned)v[e] << up) >> (32 - BITS));
         }
-        for (; q < n; ++q) s += col[(size_t)q * r];
+        for (; q < n; ++q) {
+            const int v = col[(size_t)q * rb];
+            s += BITS == 8 ? v : ((int)((unsigned)v << up) >> (32 - BITS));
+        }
         s += g / 2;
         int m = s / g;
         if (s % g != 0 && s < 0) m -= 1;
-        rep[((size_t)h * n_qb * n_rep + (size_t)b * n_rep + u) * r + j] = (int8_t)m;
+        rep[((size_t)h * n_qb * n_rep + (size_t)b * n_rep + u) * r + (j & ~15) + summary_slot<BITS>(j & 15)] = (int8_t)m;
     }
 }
 
 // ---- AnnSA scoring -----------------------------------------------------------------------------------
 // out[h][b][kb] = max over the summaries u of block b (whose run holds a query) and the live keys k of
 // key block kb of rep[b,u] . kcode[k].   D = A x B with A rows = 32 keys, B columns = 32 summaries.
-template <int R>
+template <int R, int BITS>
 __global__ __launch_bounds__(256) void score_self_kernel(const int8_t *__restrict__ kcode, const int32_t *__restrict__ len,
                                                          const int8_t *__restrict__ rep, int C, int n_q, int BQ,
                                                          int n_rep, int BK, int n_qb, int n_kb_cap,
@@ -71,7 +112,8 @@ __global__ __launch_bounds__(256) void score_self_kernel(const int8_t *__restric
     const int NR = n_qb * n_rep;
     const int NCB = (NR + 31) / 32;
     const int g = BQ / n_rep;
-    const int8_t *kc = kcode + (size_t)h * C * R;
+    constexpr int RB = R * BITS / 8;   // bytes per key row
+    const int8_t *kc = kcode + (size_t)h * C * RB;
     const int8_t *rp = rep + (size_t)h * NR * R;
 
     for (int cb0 = 0; cb0 < NCB; cb0 += COL_CHUNK) {
@@ -103,7 +145,7 @@ __global__ __launch_bounds__(256) void score_self_kernel(const int8_t *__restric
 #pragma unroll
                     for (int ks = 0; ks < KS; ++ks) {
                         i32x4 a = {0, 0, 0, 0};
-                        if (have[q]) a = *(const i32x4 *)(kc + (size_t)krow * R + ks * 32 + 16 * g2);
+                        if (have[q]) a = load_key_codes<BITS>(kc + (size_t)krow * RB + (ks * 32 + 16 * g2) * BITS / 8);
                         afrag[q][ks] = a;
                     }
                 }
@@ -158,7 +200,7 @@ __global__ __launch_bounds__(256) void score_self_kernel(const int8_t *__restric
 // The same scores for long caches (at least 4096 workgroups of KBW = 16 key blocks): wavefront w streams blocks w, w+4,
 // ... with the codes of the next three rounds in flight while it scores the current one, and the workgroup writes
 // 64-byte pieces of the score rows.  CC: summary column blocks (of 32) kept in registers at a time.
-template <int R, int KBW, int CC>
+template <int R, int KBW, int CC, int BITS>
 __global__ __launch_bounds__(256) void score_self_stream_kernel(const int8_t *__restrict__ kcode, const int32_t *__restrict__ len,
                                                          const int8_t *__restrict__ rep, int C, int n_q, int BQ,
                                                          int n_rep, int BK, int n_qb, int n_kb_cap,
@@ -176,7 +218,8 @@ __global__ __launch_bounds__(256) void score_self_stream_kernel(const int8_t *__
     const int NCB = (NR + 31) / 32;
     const int g = BQ / n_rep;
     const int rep_shift = __ffs(n_rep) - 1;   // n_rep is a power of two
-    const int8_t *kc = kcode + (size_t)h * C * R;
+    constexpr int RB = R * BITS / 8;   // bytes per key row
+    const int8_t *kc = kcode + (size_t)h * C * RB;
     const int8_t *rp = rep + (size_t)h * NR * R;
     // rounds of 64 keys (two groups of 32): key block wave + 4 * (it / rpk), keys 64 * (it % rpk) .. of it
     const int rpk = (BK + 63) / 64;
@@ -192,7 +235,7 @@ __global__ __launch_bounds__(256) void score_self_stream_kernel(const int8_t *__
             // the compiler can wait for exactly the buffer it needs; rows past the block or the cache are never scored
             const int krow = min(kbase + col, C - 1);
 #pragma unroll
-            for (int ks = 0; ks < KS; ++ks) a[q][ks] = *(const i32x4 *)(kc + (size_t)krow * R + ks * 32 + 16 * g2);
+            for (int ks = 0; ks < KS; ++ks) a[q][ks] = load_key_codes<BITS>(kc + (size_t)krow * RB + (ks * 32 + 16 * g2) * BITS / 8);
         }
     };
 
@@ -683,13 +726,14 @@ using namespace fastar;
 
 static int select_self_impl(const int8_t *qcode, int n_q, const int8_t *kcode, const int32_t *len, int H, int C, int r,
                             int BQ, int n_rep, int BK, int n_sel, int32_t *sel, int32_t *nsel, void *ws,
-                            size_t ws_bytes, void *stream, int n_sink = 0, int n_local = 0) {
+                            size_t ws_bytes, void *stream, int n_sink = 0, int n_local = 0, int bits = 8) {
     if (!qcode || !kcode || !len || !sel || !nsel || !ws) return FASTAR_ERR_INVALID_ARG;
     if (n_sink < 0 || n_local < 0 || n_sink + n_local > n_sel) return FASTAR_ERR_INVALID_ARG;
     if (H <= 0 || n_q <= 0 || C <= 0 || BQ <= 0 || n_rep <= 0 || BK <= 0 || n_sel <= 0) return FASTAR_ERR_INVALID_ARG;
     if (BQ % n_rep != 0) return FASTAR_ERR_INVALID_ARG;
     if (((uintptr_t)qcode & 15) || ((uintptr_t)kcode & 15) || ((uintptr_t)ws & 255)) return FASTAR_ERR_INVALID_ARG;
     if ((r != 32 && r != 64) || !pow2_le32(n_rep) || BK % 32 != 0) return FASTAR_ERR_UNSUPPORTED;
+    if (bits != 8 && !((bits == 4 || bits == 2) && r == 32)) return FASTAR_ERR_UNSUPPORTED;
     const int n_qb = (n_q + BQ - 1) / BQ;
     const int n_kb_cap = (C + BK - 1) / BK;
     // the streaming kernel pays when there are thousands of its workgroups and the summaries fit four column blocks
@@ -703,25 +747,23 @@ static int select_self_impl(const int8_t *qcode, int n_q, const int8_t *kcode, c
     hipStream_t s = (hipStream_t)stream;
     int8_t *rep = (int8_t *)ws + w.rep_off;
     int32_t *score = (int32_t *)((char *)ws + w.score_off);
-    hipLaunchKernelGGL(rep_kernel, dim3(n_qb, H), dim3(128), 0, s, qcode, n_q, r, BQ, n_rep, n_qb, rep);
-    FASTAR_LAUNCH_CHECK();
-    dim3 grid((n_kb_cap + kbw - 1) / kbw, H);
-#define FASTAR_SCORE(RR, CCC)                                                                                        \
-    hipLaunchKernelGGL((score_self_stream_kernel<RR, KB_PER_WG_LONG, CCC>), grid, dim3(256), tile_bytes, s, kcode, len, \
-                       rep, C, n_q, BQ, n_rep, BK, n_qb, n_kb_cap, score)
-    if (kbw == KB_PER_WG) {
-        if (r == 32)
-            hipLaunchKernelGGL(score_self_kernel<32>, grid, dim3(256), tile_bytes, s, kcode, len, rep, C, n_q, BQ, n_rep,
-                               BK, n_qb, n_kb_cap, score);
-        else
-            hipLaunchKernelGGL(score_self_kernel<64>, grid, dim3(256), tile_bytes, s, kcode, len, rep, C, n_q, BQ, n_rep,
-                               BK, n_qb, n_kb_cap, score);
-    } else if (r == 32) {
-        FASTAR_SCORE(32, 4);
-    } else {
-        FASTAR_SCORE(64, 4);
-    }
-#undef FASTAR_SCORE
+    const dim3 grid((n_kb_cap + kbw - 1) / kbw, H);
+#define FASTAR_SELF(RR, BB)                                                                                            \
+    do {                                                                                                               \
+        hipLaunchKernelGGL(rep_kernel<BB>, dim3(n_qb, H), dim3(128), 0, s, qcode, n_q, r, BQ, n_rep, n_qb, rep);       \
+        FASTAR_LAUNCH_CHECK();                                                                                         \
+        if (kbw == KB_PER_WG)                                                                                          \
+            hipLaunchKernelGGL((score_self_kernel<RR, BB>), grid, dim3(256), tile_bytes, s, kcode, len, rep, C, n_q, BQ, \
+                               n_rep, BK, n_qb, n_kb_cap, score);                                                      \
+        else                                                                                                           \
+            hipLaunchKernelGGL((score_self_stream_kernel<RR, KB_PER_WG_LONG, 4, BB>), grid, dim3(256), tile_bytes, s,  \
+                               kcode, len, rep, C, n_q, BQ, n_rep, BK, n_qb, n_kb_cap, score);                         \
+    } while (0)
+    if (bits == 4) FASTAR_SELF(32, 4);
+    else if (bits == 2) FASTAR_SELF(32, 2);
+    else if (r == 32) FASTAR_SELF(32, 8);
+    else FASTAR_SELF(64, 8);
+#undef FASTAR_SELF
     FASTAR_LAUNCH_CHECK();
     hipLaunchKernelGGL(topk_kernel, dim3(n_qb, H), dim3(256), 0, s, score, n_kb_cap, len, C, BK, 0, n_qb, n_sel, sel,
                        nsel, n_sink, n_local);
@@ -740,6 +782,14 @@ extern "C" int ann_select_self_forced(const int8_t *qcode, int n_q, const int8_t
                                       int32_t *sel, int32_t *nsel, void *ws, size_t ws_bytes, void *stream) {
     return select_self_impl(qcode, n_q, kcode, len, H, C, r, BQ, n_rep, BK, n_sel, sel, nsel, ws, ws_bytes, stream, n_sink,
                             n_local);
+}
+
+extern "C" int ann_select_self_packed(const int8_t *qcode, int n_q, const int8_t *kcode, const int32_t *len, int H,
+                                      int C, int r, int bits, int BQ, int n_rep, int BK, int n_sel, int n_sink,
+                                      int n_local, int32_t *sel, int32_t *nsel, void *ws, size_t ws_bytes, void *stream) {
+    if (bits != 2 && bits != 4 && bits != 8) return FASTAR_ERR_INVALID_ARG;
+    return select_self_impl(qcode, n_q, kcode, len, H, C, r, BQ, n_rep, BK, n_sel, sel, nsel, ws, ws_bytes, stream, n_sink,
+                            n_local, bits);
 }
 
 // ---- the same selection on the library's own static scratch, for callers that cannot allocate ----------------------
