@@ -40,7 +40,7 @@ def _load():
                      "oracle_ann_select_cross", "oracle_sparse_attn_fwd", "oracle_recall_density",
                      "oracle_encode_sign", "oracle_ann_select_lsh", "oracle_fp8_encode", "oracle_fp8_decode",
                      "oracle_kv_to_fp8", "oracle_sparse_attn_fwd_fp8", "oracle_ann_select_self_forced",
-                     "oracle_prompt_buckets", "oracle_ann_select_buckets", "oracle_encode_packed", "oracle_unpack_codes"):
+                     "oracle_prompt_buckets", "oracle_ann_select_buckets", "oracle_encode_packed", "oracle_unpack_codes", "oracle_ann_select_lsh_buckets"):
             getattr(_lib, name).restype = ctypes.c_int
     return _lib
 
@@ -248,6 +248,24 @@ def ann_select_lsh(qbits, kbits, length, BQ: int, n_rep: int, BK: int, n_sel: in
     rc = _load().oracle_ann_select_lsh(_p(qbits), n_q, _p(kbits), _p(length), H, C, 32 * W, BQ, n_rep, BK, n_sel,
                                        _p(sel), _p(nsel))
     _check(rc, "oracle_ann_select_lsh")
+    return sel, nsel
+
+
+def ann_select_lsh_buckets(qbits, kbits, length, band_bits: int, radius: int, BQ: int, n_rep: int, BK: int, n_sel: int,
+                           n_sink: int = 0, n_local: int = 0):
+    """Hash-table form of ann_select_lsh: bands of band_bits bits are the tables, a pair collides in a table when its
+    buckets differ in at most `radius` bits; key blocks without a collision are no candidates."""
+    qbits = _c(qbits, np.uint32)
+    kbits = _c(kbits, np.uint32)
+    length = _c(length, np.int32)
+    H, n_q, W = qbits.shape
+    C = kbits.shape[1]
+    n_qb = (n_q + BQ - 1) // BQ
+    sel = np.empty((H, n_qb, n_sel), np.int32)
+    nsel = np.empty((H, n_qb), np.int32)
+    rc = _load().oracle_ann_select_lsh_buckets(_p(qbits), n_q, _p(kbits), _p(length), H, C, 32 * W, band_bits, radius,
+                                               BQ, n_rep, BK, n_sel, n_sink, n_local, _p(sel), _p(nsel))
+    _check(rc, "oracle_ann_select_lsh_buckets")
     return sel, nsel
 
 

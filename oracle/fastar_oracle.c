@@ -32,6 +32,9 @@
  *   oracle_encode_sign         Sec. 5.1, LSH paragraph: one hash bit per random projection (its sign).
  *   oracle_ann_select_lsh      Sec. 5.3 / 5.4 on those hash codes: candidates ranked by the number of hash
  *                              bits they share with the query side (AnnSA with key blocks, AnnCA with BK = 1).
+ *   oracle_ann_select_lsh_buckets  the same with hash tables: the code cut into bands, a pair scored by the tables in which
+ *                              it falls into the same (or, multi-probe, a neighbouring) bucket; blocks without a collision
+ *                              are no candidates (Sec. 5.1 LSH paragraph "same bucket(s)"; Sec. 2 multi-table probing).
  *   oracle_sparse_attn_fwd     Eq. (1) restricted to the candidate set (Sec. 5.1 display), with the
  *                              +log m_t logit shift of Lemma 1.
  *   oracle_recall_density      attention recall / density as defined in the Metrics paragraph.
@@ -715,12 +718,30 @@ static int equal_bits(const uint32_t *a, const uint32_t *b, int W) {
  * order to sel [H,n_qb,n_sel] (-1 padded), their number to nsel [H,n_qb].
  * n_rep = BQ and BK = 1 give the cross-attention form: a key is scored by its best-matching query of the block.
  */
-int oracle_ann_select_lsh(const uint32_t *qbits, int n_q, const uint32_t *kbits, const int32_t *len, int H, int C,
-                          int n_bits, int BQ, int n_rep, int BK, int n_sel, int32_t *sel, int32_t *nsel) {
+/* Tables in which two hash codes fall into the same bucket, or into buckets at most `radius` bits apart: the code is
+ * cut into bands of band_bits consecutive bits, one band per table. */
+static int colliding_tables(const uint32_t *a, const uint32_t *b, int n_bits, int band_bits, int radius) {
+    int n = 0;
+    for (int t = 0; t < n_bits / band_bits; ++t) {
+        int diff = 0;
+        for (int j = t * band_bits; j < (t + 1) * band_bits; ++j)
+            diff += (int)(((a[j / 32] ^ b[j / 32]) >> (j % 32)) & 1u);
+        n += diff <= radius;
+    }
+    return n;
+}
+
+/* band_bits = 0: pairs are scored by their equal bits and every key block is a candidate (oracle_ann_select_lsh);
+ * band_bits > 0: pairs are scored by their colliding tables and only key blocks with a collision are candidates. */
+static int lsh_select(const uint32_t *qbits, int n_q, const uint32_t *kbits, const int32_t *len, int H, int C,
+                      int n_bits, int band_bits, int radius, int BQ, int n_rep, int BK, int n_sel, int n_sink,
+                      int n_local, int32_t *sel, int32_t *nsel) {
     if (!qbits || !kbits || !len || !sel || !nsel) return -1;
     if (H <= 0 || C <= 0 || n_bits <= 0 || n_bits % 32 != 0 || BQ <= 0 || n_rep <= 0 || BK <= 0 || n_sel <= 0 ||
         BQ % n_rep != 0)
         return -1;
+    if (band_bits < 0 || (band_bits > 0 && n_bits % band_bits != 0) || radius < 0) return -1;
+    if (n_sink < 0 || n_local < 0 || n_sink + n_local > n_sel) return -1;
     const int W = n_bits / 32;
     const int n_qb = (n_q + BQ - 1) / BQ;
     const int g = BQ / n_rep;
@@ -745,17 +766,23 @@ int oracle_ann_select_lsh(const uint32_t *qbits, int n_q, const uint32_t *kbits,
                     if (2 * ones >= q1 - q0) rep[(int64_t)u * W + j / 32] |= (uint32_t)1 << (j % 32);
                 }
             }
+            int n_cand = 0;
             for (int kb = 0; kb < n_kb; ++kb) {
                 int64_t best = -1;
                 for (int k = kb * BK; k < (kb + 1) * BK && k < L; ++k)
                     for (int u = 0; u < n_rep; ++u) {
                         if (!rep_ok[u]) continue;
-                        int64_t s = equal_bits(rep + (int64_t)u * W, kbits + ((int64_t)h * C + k) * W, W);
+                        const uint32_t *ck = kbits + ((int64_t)h * C + k) * W;
+                        int64_t s = band_bits ? colliding_tables(rep + (int64_t)u * W, ck, n_bits, band_bits, radius)
+                                              : equal_bits(rep + (int64_t)u * W, ck, W);
                         if (s > best) best = s;
                     }
-                score[kb] = best;
+                const int forced = kb < n_sink || kb >= n_kb - n_local;
+                if (band_bits && best < 1) best = -1; /* no table in common: not a candidate */
+                n_cand += forced || !band_bits || best >= 1;
+                score[kb] = forced ? INT64_MAX : best;
             }
-            int n_out = n_sel < n_kb ? n_sel : n_kb;
+            int n_out = n_sel < n_cand ? n_sel : n_cand;
             pick_top(score, n_kb, n_out, picked);
             int32_t *out = sel + ((int64_t)h * n_qb + b) * n_sel;
             int w = 0;
@@ -770,6 +797,28 @@ int oracle_ann_select_lsh(const uint32_t *qbits, int n_q, const uint32_t *kbits,
         }
     }
     return 0;
+}
+
+int oracle_ann_select_lsh(const uint32_t *qbits, int n_q, const uint32_t *kbits, const int32_t *len, int H, int C,
+                          int n_bits, int BQ, int n_rep, int BK, int n_sel, int32_t *sel, int32_t *nsel) {
+    return lsh_select(qbits, n_q, kbits, len, H, C, n_bits, 0, 0, BQ, n_rep, BK, n_sel, 0, 0, sel, nsel);
+}
+
+/*
+ * Bucket form of the same selection (Sec. 5.1, LSH paragraph: a query only compares against keys that land in the same
+ * bucket(s); Sec. 2 names multi-table bucket probing).  The n_bits hash bits are cut into n_bits / band_bits bands,
+ * one hash table each; a vector's bucket in a table is its band.  A summary and a key collide in a table when their
+ * buckets are equal (radius 0) or differ in at most `radius` bits (multi-probe: the query side also looks into the
+ * neighbouring buckets).  Score of a pair = number of tables in which it collides; score of a key block = best pair
+ * over the block's summaries and its live keys; a key block without any collision is no candidate; of the candidates
+ * the n_sel best are kept (ties: lowest index).  The first n_sink / last n_local live blocks are always kept.
+ */
+int oracle_ann_select_lsh_buckets(const uint32_t *qbits, int n_q, const uint32_t *kbits, const int32_t *len, int H,
+                                  int C, int n_bits, int band_bits, int radius, int BQ, int n_rep, int BK, int n_sel,
+                                  int n_sink, int n_local, int32_t *sel, int32_t *nsel) {
+    if (band_bits <= 0) return -1;
+    return lsh_select(qbits, n_q, kbits, len, H, C, n_bits, band_bits, radius, BQ, n_rep, BK, n_sel, n_sink, n_local,
+                      sel, nsel);
 }
 
 /* ------------------------------------------------------------------ sparse attention */

@@ -171,3 +171,106 @@ def test_neighbours_in_angle_are_what_the_hash_selects():
     ks = oracle.encode_sign(K, R, 127 / 4.5)
     sel, nsel = oracle.ann_select_lsh(qs, ks, np.array([64], np.int32), 16, 4, BK, 1)
     assert sel.tolist() == [[[5]]]
+
+
+# ------------------------------------------------------------------ hash tables: same bucket(s), multi-probe
+# (Sec. 5.1, LSH paragraph: a query only compares against keys that land in the same bucket(s); Sec. 2: multi-table
+# bucket probing)
+
+def brute_select_buckets(qbits, kbits, length, n_bits, band, radius, BQ, n_rep, BK, n_sel, n_sink=0, n_local=0):
+    """Python integers and sets: bucket ids per table, probe sets by explicit bit flips."""
+    from itertools import combinations
+    H, n_q, W = qbits.shape
+    C = kbits.shape[1]
+    n_qb = (n_q + BQ - 1) // BQ
+    g = BQ // n_rep
+    T = n_bits // band
+    as_int = lambda words: sum(int(w) << (32 * i) for i, w in enumerate(words))
+    bucket = lambda code, t: (code >> (t * band)) & ((1 << band) - 1)
+
+    def probes(bk):   # the bucket itself and every bucket at most `radius` bit flips away
+        out = {bk}
+        for k in range(1, radius + 1):
+            for pos in combinations(range(band), k):
+                x = bk
+                for p in pos:
+                    x ^= 1 << p
+                out.add(x)
+        return out
+
+    sel = -np.ones((H, n_qb, n_sel), np.int32)
+    nsel = np.zeros((H, n_qb), np.int32)
+    for h in range(H):
+        L = min(int(length[h]), C)
+        n_kb = (L + BK - 1) // BK
+        keys = [as_int(kbits[h, k]) for k in range(L)]
+        for b in range(n_qb):
+            reps = []
+            for u in range(n_rep):
+                qs = [as_int(qbits[h, q]) for q in range(b * BQ + u * g, min(b * BQ + (u + 1) * g, n_q))]
+                if qs:
+                    reps.append(sum(1 << j for j in range(n_bits) if 2 * sum((q >> j) & 1 for q in qs) >= len(qs)))
+            probe_sets = [[probes(bucket(r, t)) for t in range(T)] for r in reps]
+            cand = []
+            for kb in range(n_kb):
+                best = max(sum(bucket(keys[k], t) in ps[t] for t in range(T))
+                           for k in range(kb * BK, min((kb + 1) * BK, L)) for ps in probe_sets)
+                forced = kb < n_sink or kb >= n_kb - n_local
+                if forced or best >= 1:
+                    cand.append((0 if forced else 1, -best, kb))
+            chosen = sorted(kb for _, _, kb in sorted(cand)[:n_sel])
+            sel[h, b, :len(chosen)] = chosen
+            nsel[h, b] = len(chosen)
+    return sel, nsel
+
+
+@pytest.mark.parametrize("n_q,C,lens,n_bits,band,radius,BQ,n_rep,BK,n_sel,sink,local", [
+    (20, 37, [37, 20], 64, 8, 0, 8, 2, 4, 3, 0, 0),
+    (20, 37, [37, 20], 64, 8, 1, 8, 2, 4, 3, 0, 0),
+    (9, 16, [16, 0], 32, 4, 0, 4, 4, 1, 20, 0, 0),      # single keys and queries, budget beyond the candidates
+    (16, 48, [48, 41], 128, 16, 2, 16, 1, 8, 4, 1, 1),  # wide bands, two flips, forced blocks
+    (12, 40, [40, 40], 64, 32, 3, 4, 2, 2, 6, 0, 0),
+    (10, 30, [30, 7], 64, 2, 0, 5, 5, 3, 4, 0, 0)])
+def test_bucket_selection_matches_brute_force_on_probe_sets(n_q, C, lens, n_bits, band, radius, BQ, n_rep, BK, n_sel, sink, local):
+    rng = np.random.default_rng(n_q + C + band + radius)
+    H, W = 2, n_bits // 32
+    qbits = rng.integers(0, 2 ** 32, size=(H, n_q, W), dtype=np.uint64).astype(np.uint32)
+    kbits = rng.integers(0, 2 ** 32, size=(H, C, W), dtype=np.uint64).astype(np.uint32)
+    kbits[:, ::3] = kbits[:, 1:2]
+    kbits[:, 5::7] = qbits[:, :1] ^ np.uint32(1 << 3)                  # near copies of a query: collide in most tables
+    length = np.array(lens, np.int32)
+    got = oracle.ann_select_lsh_buckets(qbits, kbits, length, band, radius, BQ, n_rep, BK, n_sel, sink, local)
+    ref = brute_select_buckets(qbits, kbits, length, n_bits, band, radius, BQ, n_rep, BK, n_sel, sink, local)
+    assert np.array_equal(got[1], ref[1]) and np.array_equal(got[0], ref[0])
+
+
+def test_one_table_of_all_bits_is_bucket_equality_and_one_bit_tables_count_equal_bits():
+    rng = np.random.default_rng(11)
+    qbits = rng.integers(0, 4, size=(1, 6, 1), dtype=np.uint64).astype(np.uint32)       # 2 significant bits: many equal codes
+    kbits = rng.integers(0, 4, size=(1, 40, 1), dtype=np.uint64).astype(np.uint32)
+    length = np.array([40], np.int32)
+    # one table over the whole code, single queries and keys, budget beyond the cache: exactly the keys with the query's code
+    sel, nsel = oracle.ann_select_lsh_buckets(qbits, kbits, length, 32, 0, 1, 1, 1, 40)
+    for i in range(6):
+        same = np.flatnonzero(kbits[0, :, 0] == qbits[0, i, 0])
+        assert nsel[0, i] == len(same) and np.array_equal(sel[0, i, :len(same)], same)
+    # one-bit tables: a pair's collisions are its equal bits, so the ranking is that of ann_select_lsh whenever every
+    # block has a collision (always, with 32 one-bit tables of codes that agree in their 30 high bits)
+    a = oracle.ann_select_lsh_buckets(qbits, kbits, length, 1, 0, 2, 1, 4, 3)
+    b = oracle.ann_select_lsh(qbits, kbits, length, 2, 1, 4, 3)
+    assert np.array_equal(a[0], b[0]) and np.array_equal(a[1], b[1])
+
+
+def test_probing_more_buckets_only_adds_candidates_and_full_radius_admits_everything():
+    rng = np.random.default_rng(12)
+    qbits = rng.integers(0, 2 ** 32, size=(1, 8, 2), dtype=np.uint64).astype(np.uint32)
+    kbits = rng.integers(0, 2 ** 32, size=(1, 64, 2), dtype=np.uint64).astype(np.uint32)
+    length = np.array([64], np.int32)
+    prev = None
+    for radius in range(0, 9):
+        sel, nsel = oracle.ann_select_lsh_buckets(qbits, kbits, length, 8, radius, 8, 2, 4, 16)
+        cur = set(sel[0, 0, :nsel[0, 0]].tolist())
+        if prev is not None:
+            assert prev <= cur
+        prev = cur
+    assert cur == set(range(16))          # radius = band width: every bucket is probed
