@@ -197,6 +197,20 @@ int ann_select_lsh(const uint32_t *qbits, int n_q, const uint32_t *kbits, const 
                    size_t ws_bytes, void *stream);
 
 /*
+ * Hash-table form of ann_select_lsh (Sec. 5.1, LSH paragraph: a query only compares against keys that land in the same
+ * bucket(s); Sec. 2: multi-table bucket probing).  The hash bits are cut into n_bits / band_bits bands, one table each;
+ * a vector's bucket in a table is its band.  A summary and a key collide in a table when their buckets differ in at
+ * most `radius` bits (0: the same bucket; more: the neighbouring buckets are probed as well).  A pair scores its
+ * colliding tables, a key block its best (summary, live key) pair; key blocks without a collision are no candidates;
+ * of the candidates the n_sel best are kept (ties: lowest index), -1 padded; nsel = their number (it can be 0).  The
+ * first n_sink / last n_local live key blocks are always kept (n_sink + n_local <= n_sel).
+ * Same arrays and workspace as ann_select_lsh.  Supported: band_bits in {4, 8, 16, 32}.
+ */
+int ann_select_lsh_buckets(const uint32_t *qbits, int n_q, const uint32_t *kbits, const int32_t *len, int H, int C,
+                           int n_bits, int band_bits, int radius, int BQ, int n_rep, int BK, int n_sel, int n_sink,
+                           int n_local, int32_t *sel, int32_t *nsel, void *ws, size_t ws_bytes, void *stream);
+
+/*
  * TempCache (Sec. 5.2 and Lemma 1): merge one frame of n_new tokens per head into the cache.  Every
  * decision is taken against the cache as it is at entry; a chunk of several frames is several calls.
  *   1. probe code cp_i = code(P_new[i]) (P_new NULL => K_new), key code ck_i = code(K_new[i]).

@@ -85,6 +85,9 @@ def lib() -> ctypes.CDLL:
         L.ann_select_self_packed.restype = ctypes.c_int
         L.ann_select_self_packed.argtypes = [ctypes.c_void_p, ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p] + \
             [ctypes.c_int] * 10 + [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
+        L.ann_select_lsh_buckets.restype = ctypes.c_int
+        L.ann_select_lsh_buckets.argtypes = [ctypes.c_void_p, ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p] + \
+            [ctypes.c_int] * 11 + [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
         L.ann_select_self_static.restype = ctypes.c_int
         L.ann_select_self_static.argtypes = [ctypes.c_void_p, ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int,
                                              ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int,
@@ -123,7 +126,7 @@ def lib() -> ctypes.CDLL:
 EXPORTS = ("fastar_init", "fastar_version", "fastar_strerror", "fastar_workspace_bytes", "fastar_encode", "tempcache_compress",
            "ann_cross_attn_fwd",
            "ann_select_self", "ann_select_self_forced", "ann_select_self_static", "ann_prompt_buckets", "ann_select_buckets", "fastar_encode_packed", "ann_select_self_packed", "ann_select_cross", "sparse_attn_fwd", "fastar_kv_to_fp8",
-           "sparse_attn_fwd_fp8", "fastar_encode_sign", "ann_select_lsh",
+           "sparse_attn_fwd_fp8", "fastar_encode_sign", "ann_select_lsh", "ann_select_lsh_buckets",
            "fastar_probe_mfma_bf16", "fastar_probe_copy")
 
 
@@ -428,6 +431,27 @@ def ann_select_lsh(qbits, kbits, length, BQ: int, n_rep: int, BK: int, n_sel: in
     _check(lib().ann_select_lsh(qbits.data_ptr(), n_q, kbits.data_ptr(), length.data_ptr(), H, C, 32 * W, BQ, n_rep,
                                 BK, n_sel, sel.data_ptr(), nsel.data_ptr(), ws.data_ptr(),
                                 ws.numel() * ws.element_size(), _stream()), "ann_select_lsh")
+    return sel, nsel
+
+
+def ann_select_lsh_buckets(qbits, kbits, length, band_bits: int, radius: int, BQ: int, n_rep: int, BK: int, n_sel: int,
+                           n_sink: int = 0, n_local: int = 0, ws=None, out=None):
+    """Hash-table form of ann_select_lsh (bands = tables, buckets at most `radius` bits apart collide)."""
+    _dev(qbits, torch.int32)
+    _dev(kbits, torch.int32)
+    _dev(length, torch.int32)
+    H, n_q, W = qbits.shape
+    C = kbits.shape[1]
+    n_qb = (n_q + BQ - 1) // BQ
+    ws = _workspace(ws, workspace_bytes(OP_SELECT_LSH, H, n_q, C, 32 * W, BQ, BK, n_rep), qbits.device)
+    if out is None:
+        out = (torch.empty((H, n_qb, n_sel), dtype=torch.int32, device=qbits.device),
+               torch.empty((H, n_qb), dtype=torch.int32, device=qbits.device))
+    sel, nsel = out
+    _check(lib().ann_select_lsh_buckets(qbits.data_ptr(), n_q, kbits.data_ptr(), length.data_ptr(), H, C, 32 * W,
+                                        band_bits, radius, BQ, n_rep, BK, n_sel, n_sink, n_local, sel.data_ptr(),
+                                        nsel.data_ptr(), ws.data_ptr(), ws.numel() * ws.element_size(), _stream()),
+           "ann_select_lsh_buckets")
     return sel, nsel
 
 

@@ -162,19 +162,10 @@ __global__ __launch_bounds__(256) void bucket_topk_kernel(const int32_t *__restr
                                                           int n_sel, int n_sink, int n_local, int32_t *__restrict__ sel,
                                                           int32_t *__restrict__ nsel) {
     __shared__ unsigned keys[TOPK_LDS_CAP];
-    __shared__ int cand_w[4];
     const int b = blockIdx.x, h = blockIdx.y;
     const int n = min((min(len[h], C) + BK - 1) / BK, n_kb_cap);
     const int32_t *row = score + ((size_t)h * n_qb + b) * n_kb_cap;
-    int c = 0;
-    for (int base = 0; base < n; base += 256) {   // uniform trip count
-        const int t = base + threadIdx.x;
-        const bool is_cand = t < n && (row[t] > 0 || t < n_sink || t >= n - n_local);
-        c += __popcll(__ballot(is_cand));
-    }
-    if (lane_id() == 0) cand_w[threadIdx.x >> 6] = c;
-    __syncthreads();
-    const int n_cand = cand_w[0] + cand_w[1] + cand_w[2] + cand_w[3];
+    const int n_cand = count_candidates(row, n, n_sink, n_local, 1);
     topk_row(row, n, n_sel, sel + ((size_t)h * n_qb + b) * n_sel, nsel + (size_t)h * n_qb + b, keys, n_sink, n_local,
              n_cand);
 }

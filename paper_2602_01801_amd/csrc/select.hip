@@ -545,14 +545,17 @@ __global__ __launch_bounds__(256) void cross_fused_kernel(const unsigned short *
 __global__ __launch_bounds__(256) void topk_kernel(const int32_t *__restrict__ score, int row_stride,
                                                    const int32_t *__restrict__ len, int len_cap, int BK, int n_fixed,
                                                    int n_qb, int n_sel, int32_t *__restrict__ sel,
-                                                   int32_t *__restrict__ nsel, int n_sink, int n_local) {
+                                                   int32_t *__restrict__ nsel, int n_sink, int n_local, int cand_min) {
     __shared__ unsigned keys[TOPK_LDS_CAP];
     const int b = blockIdx.x, h = blockIdx.y;
     int n = n_fixed;
     if (len) n = (min(len[h], len_cap) + BK - 1) / BK;
     n = min(n, row_stride);
-    topk_row(score + ((size_t)h * n_qb + b) * row_stride, n, n_sel, sel + ((size_t)h * n_qb + b) * n_sel,
-             nsel + (size_t)h * n_qb + b, keys, n_sink, n_local);
+    const int32_t *row = score + ((size_t)h * n_qb + b) * row_stride;
+    // cand_min > INT_MIN: only entries that score at least that much (or are forced) may be selected
+    const int k_cap = cand_min > INT_MIN ? count_candidates(row, n, n_sink, n_local, cand_min) : INT_MAX;
+    topk_row(row, n, n_sel, sel + ((size_t)h * n_qb + b) * n_sel, nsel + (size_t)h * n_qb + b, keys, n_sink, n_local,
+             k_cap);
 }
 
 // ---- selection on sign codes (LSH family) -------------------------------------------------------------
@@ -587,11 +590,39 @@ __global__ __launch_bounds__(256) void lsh_summary_kernel(const uint32_t *__rest
 // <= 64) or over several 64-key rounds of a wavefront (BK a multiple of 64).
 constexpr int LSH_QB = 8;  // query blocks whose scores a lane carries at a time
 
-template <int W>
+// Score of one 32-bit word of a (summary, key) pair, d = summary ^ key.
+// BAND = 0: equal bits.  BAND in {4, 8, 16, 32}: the word holds 32/BAND hash tables (bands); a table counts when the
+// two buckets differ in at most `radius` bits (0: same bucket; more: the neighbouring buckets are probed too).  Bits
+// set per band by the usual pairwise sums, then one add per word whose carry into each band's top bit says "more than
+// radius"; rc = that addend (see lsh_radius_addend).
+template <int BAND>
+__device__ __forceinline__ int lsh_word_score(unsigned d, unsigned rc, int radius) {
+    if constexpr (BAND == 0) {
+        return __popc(~d);
+    } else {
+        unsigned c = d - ((d >> 1) & 0x55555555u);
+        c = (c & 0x33333333u) + ((c >> 2) & 0x33333333u);
+        if constexpr (BAND == 4) return 8 - __popc((c + rc) & 0x88888888u);
+        c = (c + (c >> 4)) & 0x0F0F0F0Fu;
+        if constexpr (BAND == 8) return 4 - __popc((c + rc) & 0x80808080u);
+        c = (c + (c >> 8)) & 0x00FF00FFu;
+        if constexpr (BAND == 16) return 2 - __popc((c + rc) & 0x80008000u);
+        c = (c + (c >> 16)) & 0xFFFFu;
+        return (int)c <= radius ? 1 : 0;
+    }
+}
+static inline unsigned lsh_radius_addend(int band, int radius) {
+    if (band == 4) return (unsigned)(7 - radius) * 0x11111111u;
+    if (band == 8) return (unsigned)(0x7F - radius) * 0x01010101u;
+    if (band == 16) return (unsigned)(0x7FFF - radius) * 0x00010001u;
+    return 0u;
+}
+
+template <int W, int BAND>
 __global__ __launch_bounds__(256) void lsh_score_kernel(const uint32_t *__restrict__ kbits, const int32_t *__restrict__ len,
                                                         const uint32_t *__restrict__ rep, int C, int n_q, int BQ,
                                                         int n_rep, int BK, int n_qb, int n_kb_cap, int lds_words,
-                                                        int32_t *__restrict__ out) {
+                                                        unsigned rc, int radius, int32_t *__restrict__ out) {
     const int h = blockIdx.y;
     const int L = min(len[h], C);
     const int n_kb = (L + BK - 1) / BK;
@@ -640,7 +671,7 @@ __global__ __launch_bounds__(256) void lsh_score_kernel(const uint32_t *__restri
                         const uint32_t *r = rp + ((size_t)b * n_rep + u) * W;
                         int eq = 0;
 #pragma unroll
-                        for (int w = 0; w < W; ++w) eq += __popc(~(r[w] ^ kw[w]));
+                        for (int w = 0; w < W; ++w) eq += lsh_word_score<BAND>(r[w] ^ kw[w], rc, radius);
                         if (live) best[i] = max(best[i], eq);
                     }
                 }
@@ -766,7 +797,7 @@ static int select_self_impl(const int8_t *qcode, int n_q, const int8_t *kcode, c
 #undef FASTAR_SELF
     FASTAR_LAUNCH_CHECK();
     hipLaunchKernelGGL(topk_kernel, dim3(n_qb, H), dim3(256), 0, s, score, n_kb_cap, len, C, BK, 0, n_qb, n_sel, sel,
-                       nsel, n_sink, n_local);
+                       nsel, n_sink, n_local, INT_MIN);
     FASTAR_LAUNCH_CHECK();
     return FASTAR_OK;
 }
@@ -873,14 +904,17 @@ extern "C" int ann_cross_attn_fwd(const void *Q, const int8_t *qcode, int n_q, c
     return FASTAR_OK;
 }
 
-extern "C" int ann_select_lsh(const uint32_t *qbits, int n_q, const uint32_t *kbits, const int32_t *len, int H, int C,
-                              int n_bits, int BQ, int n_rep, int BK, int n_sel, int32_t *sel, int32_t *nsel, void *ws,
-                              size_t ws_bytes, void *stream) {
+static int select_lsh_impl(const uint32_t *qbits, int n_q, const uint32_t *kbits, const int32_t *len, int H, int C,
+                           int n_bits, int band, int radius, int BQ, int n_rep, int BK, int n_sel, int n_sink, int n_local,
+                           int32_t *sel, int32_t *nsel, void *ws, size_t ws_bytes, void *stream) {
     if (!qbits || !kbits || !len || !sel || !nsel || !ws) return FASTAR_ERR_INVALID_ARG;
     if (H <= 0 || n_q <= 0 || C <= 0 || BQ <= 0 || n_rep <= 0 || BK <= 0 || n_sel <= 0) return FASTAR_ERR_INVALID_ARG;
     if (BQ % n_rep != 0 || ((uintptr_t)ws & 255)) return FASTAR_ERR_INVALID_ARG;
+    if (radius < 0 || n_sink < 0 || n_local < 0 || n_sink + n_local > n_sel) return FASTAR_ERR_INVALID_ARG;
     if (n_bits != 64 && n_bits != 128 && n_bits != 256) return FASTAR_ERR_UNSUPPORTED;
+    if (band != 0 && band != 4 && band != 8 && band != 16 && band != 32) return FASTAR_ERR_UNSUPPORTED;
     if (!((BK <= 64 && (BK & (BK - 1)) == 0) || BK % 64 == 0)) return FASTAR_ERR_UNSUPPORTED;
+    if (band && radius > band) radius = band;   // every bucket of a table is probed from there on
     const int W = n_bits / 32;
     const int n_qb = (n_q + BQ - 1) / BQ;
     const int n_kb_cap = (C + BK - 1) / BK;
@@ -899,18 +933,43 @@ extern "C" int ann_select_lsh(const uint32_t *qbits, int n_q, const uint32_t *kb
     int lds_words = n_qb * n_rep * W;
     if ((size_t)lds_words * 4 > 48 * 1024) lds_words = 0;  // too many summaries (per-query form): read them from memory
     const size_t lds_bytes = (size_t)lds_words * 4;
-    if (W == 2)
-        hipLaunchKernelGGL(lsh_score_kernel<2>, grid, dim3(256), lds_bytes, s, kbits, len, rep, C, n_q, BQ, n_rep, BK,
-                           n_qb, n_kb_cap, lds_words, score);
-    else if (W == 4)
-        hipLaunchKernelGGL(lsh_score_kernel<4>, grid, dim3(256), lds_bytes, s, kbits, len, rep, C, n_q, BQ, n_rep, BK,
-                           n_qb, n_kb_cap, lds_words, score);
-    else
-        hipLaunchKernelGGL(lsh_score_kernel<8>, grid, dim3(256), lds_bytes, s, kbits, len, rep, C, n_q, BQ, n_rep, BK,
-                           n_qb, n_kb_cap, lds_words, score);
+    const unsigned rc = lsh_radius_addend(band, radius);
+#define FASTAR_LSH(WW, BB)                                                                                             \
+    hipLaunchKernelGGL((lsh_score_kernel<WW, BB>), grid, dim3(256), lds_bytes, s, kbits, len, rep, C, n_q, BQ, n_rep, BK, \
+                       n_qb, n_kb_cap, lds_words, rc, radius, score)
+#define FASTAR_LSH_W(BB)                        \
+    do {                                        \
+        if (W == 2) FASTAR_LSH(2, BB);          \
+        else if (W == 4) FASTAR_LSH(4, BB);     \
+        else FASTAR_LSH(8, BB);                 \
+    } while (0)
+    if (band == 0) FASTAR_LSH_W(0);
+    else if (band == 4) FASTAR_LSH_W(4);
+    else if (band == 8) FASTAR_LSH_W(8);
+    else if (band == 16) FASTAR_LSH_W(16);
+    else FASTAR_LSH_W(32);
+#undef FASTAR_LSH_W
+#undef FASTAR_LSH
     FASTAR_LAUNCH_CHECK();
+    // with tables only key blocks with a collision are candidates
     hipLaunchKernelGGL(topk_kernel, dim3(n_qb, H), dim3(256), 0, s, score, n_kb_cap, len, C, BK, 0, n_qb, n_sel, sel,
-                       nsel, 0, 0);
+                       nsel, n_sink, n_local, band ? 1 : INT_MIN);
     FASTAR_LAUNCH_CHECK();
     return FASTAR_OK;
+}
+
+extern "C" int ann_select_lsh(const uint32_t *qbits, int n_q, const uint32_t *kbits, const int32_t *len, int H, int C,
+                              int n_bits, int BQ, int n_rep, int BK, int n_sel, int32_t *sel, int32_t *nsel, void *ws,
+                              size_t ws_bytes, void *stream) {
+    return select_lsh_impl(qbits, n_q, kbits, len, H, C, n_bits, 0, 0, BQ, n_rep, BK, n_sel, 0, 0, sel, nsel, ws, ws_bytes,
+                           stream);
+}
+
+extern "C" int ann_select_lsh_buckets(const uint32_t *qbits, int n_q, const uint32_t *kbits, const int32_t *len, int H,
+                                      int C, int n_bits, int band_bits, int radius, int BQ, int n_rep, int BK, int n_sel,
+                                      int n_sink, int n_local, int32_t *sel, int32_t *nsel, void *ws, size_t ws_bytes,
+                                      void *stream) {
+    if (band_bits <= 0) return FASTAR_ERR_INVALID_ARG;
+    return select_lsh_impl(qbits, n_q, kbits, len, H, C, n_bits, band_bits, radius, BQ, n_rep, BK, n_sel, n_sink, n_local,
+                           sel, nsel, ws, ws_bytes, stream);
 }

@@ -238,4 +238,18 @@ __device__ __forceinline__ void topk_row(const int32_t *row, int n, int n_sel, i
     }
 }
 
+// Entries of a row that are candidates: score >= cand_min, or forced (first n_sink / last n_local).  All 256 threads.
+__device__ __forceinline__ int count_candidates(const int32_t *row, int n, int n_sink, int n_local, int cand_min) {
+    __shared__ int cand_w[4];
+    int c = 0;
+    for (int base = 0; base < n; base += 256) {   // uniform trip count
+        const int t = base + threadIdx.x;
+        const bool is_cand = t < n && (row[t] >= cand_min || t < n_sink || t >= n - n_local);
+        c += __popcll(__ballot(is_cand));
+    }
+    if (lane_id() == 0) cand_w[threadIdx.x >> 6] = c;
+    __syncthreads();
+    return cand_w[0] + cand_w[1] + cand_w[2] + cand_w[3];
+}
+
 }  // namespace fastar

@@ -221,6 +221,34 @@ def test_ann_select_lsh_bit_exact(H, n_q, C, n_bits, BQ, n_rep, BK, n_sel, lens,
     assert np.array_equal(to_host(sel), ref_sel)
 
 
+@pytest.mark.parametrize("band,radius", [(4, 0), (8, 0), (8, 1), (16, 2), (32, 5), (8, 9), (16, 0)])
+@pytest.mark.parametrize("H,n_q,C,n_bits,BQ,n_rep,BK,n_sel,lens,flip,sink,local", [
+    (2, 256, 1280, 128, 128, 4, 64, 5, [1280, 546], 0.3, 0, 0),
+    (3, 300, 64 * 40, 64, 128, 4, 64, 7, [2560, 2000, 0], 0.02, 1, 2),   # heavy ties, empty head, forced blocks
+    (2, 200, 640, 256, 64, 8, 16, 30, [640, 333], 0.45, 0, 0),            # nearly random codes: few collisions, budget > candidates
+    (2, 300, 97, 128, 128, 128, 1, 20, [97, 50], 0.1, 0, 0),              # cross-attention form
+])
+def test_ann_select_lsh_buckets_bit_exact(band, radius, H, n_q, C, n_bits, BQ, n_rep, BK, n_sel, lens, flip, sink, local):
+    rng = np.random.default_rng(n_q + C + n_bits + band + radius)
+    W = n_bits // 32
+    proto = rng.integers(0, 2, size=(8, n_bits))
+    def draw(n):
+        b = proto[rng.integers(0, 8, size=n)] ^ (rng.random((n, n_bits)) < flip)
+        words = np.zeros((n, W), np.uint32)
+        for j in range(n_bits):
+            words[:, j // 32] |= (b[:, j].astype(np.uint32) << np.uint32(j % 32))
+        return words
+    qb = np.stack([draw(n_q) for _ in range(H)])
+    kb = np.stack([draw(C) for _ in range(H)])
+    length = np.array(lens, np.int32)
+    ref_sel, ref_nsel = oracle.ann_select_lsh_buckets(qb, kb, length, band, radius, BQ, n_rep, BK, n_sel, sink, local)
+    sel, nsel = fa.ann_select_lsh_buckets(to_dev(qb.view(np.int32)), to_dev(kb.view(np.int32)), to_dev(length), band,
+                                          radius, BQ, n_rep, BK, n_sel, sink, local)
+    sync()
+    assert np.array_equal(to_host(nsel), ref_nsel)
+    assert np.array_equal(to_host(sel), ref_sel)
+
+
 def test_sign_codes_select_then_attend_end_to_end():
     """Hash the cache keys and the queries, select on shared bits, attend: the whole variant against the oracle."""
     c = dict(CONFIGS["cfg1"])
