@@ -10,13 +10,14 @@
 //                       the tail of the scoring kernel for AnnCA, where one workgroup owns a whole row)
 #include <limits.h>
 
+#include <algorithm>
+
 #include "common.hpp"
 #include "topk_dev.hpp"
 
 namespace fastar {
 
 constexpr int KB_PER_WG = 4;      // key blocks scored by one workgroup of score_self_kernel
-constexpr int KB_PER_WG_LONG = 32; // the same for long caches (streaming kernel)
 constexpr size_t LONG_CACHE_BLOCKS = 16 * 4096;   // key blocks over all heads from which the streaming kernel pays
 constexpr int COL_CHUNK = 8;       // summary column blocks (of 32) kept in registers at a time
 
@@ -197,36 +198,51 @@ __global__ __launch_bounds__(256) void score_self_kernel(const int8_t *__restric
     }
 }
 
-// The same scores for long caches (at least 4096 workgroups of KBW = 16 key blocks): wavefront w streams blocks w, w+4,
-// ... with the codes of the next three rounds in flight while it scores the current one, and the workgroup writes
-// 64-byte pieces of the score rows.  CC: summary column blocks (of 32) kept in registers at a time.
-template <int R, int KBW, int CC, int BITS>
-__global__ __launch_bounds__(256) void score_self_stream_kernel(const int8_t *__restrict__ kcode, const int32_t *__restrict__ len,
+// Lane exchanges of the scoring epilogue without a trip through LDS.
+__device__ __forceinline__ int max_across_halves_i32(int x) {   // max with lane ^ 32
+    const auto r = __builtin_amdgcn_permlane32_swap((unsigned)x, (unsigned)x, false, false);
+    return max((int)r[0], (int)r[1]);
+}
+__device__ __forceinline__ int max_over_quad_i32(int x) {       // max over the four lanes 4k .. 4k+3
+    x = max(x, __builtin_amdgcn_update_dpp(x, x, 0xB1, 0xF, 0xF, false));   // quad_perm [1,0,3,2]
+    return max(x, __builtin_amdgcn_update_dpp(x, x, 0x4E, 0xF, 0xF, false));   // quad_perm [2,3,0,1]
+}
+
+// The same scores for long caches.  What bounds this kernel is how the memory system is addressed: workgroups that
+// each own a contiguous run of key blocks read at large, equal strides from each other and reach only about
+// 2.8 TB/s on this chip, whatever they compute; workgroups that together sweep a dense window reach 5 TB/s and more.
+// So the grid walks the head's key blocks in steps: in step s workgroup x takes blocks 4(sG + x) .. +3, one per
+// wavefront, G = gridDim.x; a wavefront keeps the codes of its next three rounds in flight while it scores the current
+// one (four operand buffers in an unrolled rotation: copying a buffer would wait for its loads) and writes its block's
+// scores straight to the rows of the score matrix.  CC: summary column blocks (of 32) kept in registers at a time.
+template <int R, int CC, int BITS>
+__global__ __launch_bounds__(256, 3) void score_self_stream_kernel(const int8_t *__restrict__ kcode, const int32_t *__restrict__ len,
                                                          const int8_t *__restrict__ rep, int C, int n_q, int BQ,
                                                          int n_rep, int BK, int n_qb, int n_kb_cap,
                                                          int32_t *__restrict__ out) {
     constexpr int KS = R / 32;
-    extern __shared__ int32_t tile[];  // [n_qb][KBW]
+    constexpr int RB = R * BITS / 8;   // bytes per key row
     const int h = blockIdx.y;
     const int L = min(len[h], C);
     const int n_kb = (L + BK - 1) / BK;
-    const int kb0 = blockIdx.x * KBW;
-    if (kb0 >= n_kb) return;  // whole workgroup beyond the live cache (uniform)
-    const int lane = lane_id(), wave = threadIdx.x >> 6;
+    const int lane = lane_id();
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // wave-uniform, kept in a scalar register
     const int col = lane & 31, g2 = lane >> 5;
     const int NR = n_qb * n_rep;
     const int NCB = (NR + 31) / 32;
     const int g = BQ / n_rep;
     const int rep_shift = __ffs(n_rep) - 1;   // n_rep is a power of two
-    constexpr int RB = R * BITS / 8;   // bytes per key row
     const int8_t *kc = kcode + (size_t)h * C * RB;
     const int8_t *rp = rep + (size_t)h * NR * R;
-    // rounds of 64 keys (two groups of 32): key block wave + 4 * (it / rpk), keys 64 * (it % rpk) .. of it
+    const int first = blockIdx.x * 4 + wave;          // this wavefront's first key block
+    const int stride = gridDim.x * 4;                 // ... and the distance to its next one
+    if (first >= n_kb) return;                        // nothing for this wavefront (no barrier follows)
+    // rounds of 64 keys (two groups of 32): key block first + stride * (it / rpk), keys 64 * (it % rpk) .. of it
     const int rpk = (BK + 63) / 64;
-    const int n_it = ((KBW - wave + 3) / 4) * rpk;
+    const int n_it = ((n_kb - first + stride - 1) / stride) * rpk;
     auto load_round = [&](int it, i32x4 (&a)[2][KS]) __attribute__((always_inline)) {
         it = min(it, n_it - 1);   // rounds past the wavefront's share re-read its last one (cache hits), never other blocks
-        const int kb = kb0 + wave + 4 * (it / rpk), sg0 = 64 * (it % rpk);
+        const int kb = first + stride * (it / rpk), sg0 = 64 * (it % rpk);
 #pragma unroll
         for (int q = 0; q < 2; ++q) {
             const int sg = sg0 + 32 * q;
@@ -247,53 +263,70 @@ __global__ __launch_bounds__(256) void score_self_stream_kernel(const int8_t *__
 #pragma unroll
             for (int ks = 0; ks < KS; ++ks) bfrag[c][ks] = *(const i32x4 *)(rp + (size_t)rc * R + ks * 32 + 16 * g2);
         }
-        // Four operand buffers in rotation, three rounds ahead: 6 KB of codes per wavefront are in flight while a
-        // round is scored (the rotation is unrolled: copying a buffer would wait for its loads).
         int best[CC];
-        // what this lane's summary column of every column block stands for: its query block and whether it is the
+        // what this lane's summary column of every column block stands for: its score row and whether it is the
         // block's first summary; columns past the summaries or of a run without a query never count
-        int col_b[CC];
+        int32_t *col_out[CC];
         bool col_ok[CC], col_first[CC];
 #pragma unroll
         for (int c = 0; c < CC; ++c) {
             const int rc = (cb0 + c) * 32 + col;
-            col_b[c] = rc >> rep_shift;
+            const int b = rc >> rep_shift;
             const int u = rc & (n_rep - 1);
-            col_ok[c] = rc < NR && col_b[c] * BQ + u * g < n_q;
+            col_ok[c] = rc < NR && b * BQ + u * g < n_q;
             col_first[c] = rc < NR && u == 0 && g2 == 0;
+            col_out[c] = out + ((size_t)h * n_qb + min(b, n_qb - 1)) * n_kb_cap;
         }
+        const bool full_cols = cb0 + CC <= NCB;
         auto score_round = [&](int it, const i32x4 (&cur)[2][KS]) __attribute__((always_inline)) {
-            const int kl = wave + 4 * (it / rpk), sg0 = 64 * (it % rpk);
-            const int kb = kb0 + kl;
-            if (it >= n_it || kb >= n_kb) return;   // uniform
+            if (it >= n_it) return;   // uniform
+            const int kb = first + stride * (it / rpk), sg0 = 64 * (it % rpk);
             if (sg0 == 0) {
 #pragma unroll
                 for (int c = 0; c < CC; ++c) best[c] = INT_MIN;
             }
-#pragma unroll
-            for (int q = 0; q < 2; ++q) {
-                const int sg = sg0 + 32 * q;
-                const int kbase = kb * BK + sg;
-                if (!(sg < BK && kbase < L)) continue;   // uniform
-                const bool partial = kbase + 32 > L || sg + 32 > BK;
+            if (full_cols && kb * BK + sg0 + 64 <= L && sg0 + 64 <= BK) {
+                // the common round, straight line: 64 live keys, every column block in use
 #pragma unroll
                 for (int c = 0; c < CC; ++c) {
-                    if (cb0 + c < NCB) {
-                        i32x16 acc = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+                    i32x16 acc0 = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+                    i32x16 acc1 = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
 #pragma unroll
-                        for (int ks = 0; ks < KS; ++ks) acc = mfma_i8_32x32x32(cur[q][ks], bfrag[c][ks], acc);
-                        int m = best[c];
-                        if (partial) {
+                    for (int ks = 0; ks < KS; ++ks) {
+                        acc0 = mfma_i8_32x32x32(cur[0][ks], bfrag[c][ks], acc0);
+                        acc1 = mfma_i8_32x32x32(cur[1][ks], bfrag[c][ks], acc1);
+                    }
+                    int m = best[c];
 #pragma unroll
-                            for (int v = 0; v < 16; ++v) {
-                                const int kloc = 8 * (v >> 2) + 4 * g2 + (v & 3);
-                                if (kbase + kloc < L && sg + kloc < BK) m = max(m, acc[v]);
+                    for (int v = 0; v < 16; ++v) m = max(max(m, acc0[v]), acc1[v]);   // one three-operand maximum each
+                    best[c] = m;
+                }
+            } else {
+#pragma unroll
+                for (int q = 0; q < 2; ++q) {
+                    const int sg = sg0 + 32 * q;
+                    const int kbase = kb * BK + sg;
+                    if (!(sg < BK && kbase < L)) continue;   // uniform
+                    const bool partial = kbase + 32 > L || sg + 32 > BK;
+#pragma unroll
+                    for (int c = 0; c < CC; ++c) {
+                        if (cb0 + c < NCB) {
+                            i32x16 acc = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+#pragma unroll
+                            for (int ks = 0; ks < KS; ++ks) acc = mfma_i8_32x32x32(cur[q][ks], bfrag[c][ks], acc);
+                            int m = best[c];
+                            if (partial) {
+#pragma unroll
+                                for (int v = 0; v < 16; ++v) {
+                                    const int kloc = 8 * (v >> 2) + 4 * g2 + (v & 3);
+                                    if (kbase + kloc < L && sg + kloc < BK) m = max(m, acc[v]);
+                                }
+                            } else {
+#pragma unroll
+                                for (int v = 0; v < 16; ++v) m = max(m, acc[v]);
                             }
-                        } else {
-#pragma unroll
-                            for (int v = 0; v < 16; ++v) m = max(m, acc[v]);
+                            best[c] = m;
                         }
-                        best[c] = m;
                     }
                 }
             }
@@ -301,10 +334,11 @@ __global__ __launch_bounds__(256) void score_self_stream_kernel(const int8_t *__
 #pragma unroll
                 for (int c = 0; c < CC; ++c) {
                     if (cb0 + c < NCB) {
-                        int m = max(best[c], shfl_xor(best[c], 32));
+                        int m = max_across_halves_i32(best[c]);
                         if (!col_ok[c]) m = INT_MIN;
-                        for (int off = 1; off < n_rep; off <<= 1) m = max(m, shfl_xor(m, off));
-                        if (col_first[c]) tile[col_b[c] * KBW + kl] = m;
+                        if (n_rep == 4) m = max_over_quad_i32(m);   // uniform
+                        else for (int off = 1; off < n_rep; off <<= 1) m = max(m, shfl_xor(m, off));
+                        if (col_first[c]) col_out[c][kb] = m;
                     }
                 }
             }
@@ -323,12 +357,6 @@ __global__ __launch_bounds__(256) void score_self_stream_kernel(const int8_t *__
             load_round(it + 6, b2);
             score_round(it + 3, b3);
         }
-    }
-    __syncthreads();
-    const int n_here = min(KBW, n_kb - kb0);
-    for (int t = threadIdx.x; t < n_qb * KBW; t += blockDim.x) {
-        const int b = t / KBW, kl = t % KBW;
-        if (kl < n_here) out[((size_t)h * n_qb + b) * n_kb_cap + kb0 + kl] = tile[t];
     }
 }
 
@@ -767,28 +795,30 @@ static int select_self_impl(const int8_t *qcode, int n_q, const int8_t *kcode, c
     if (bits != 8 && !((bits == 4 || bits == 2) && r == 32)) return FASTAR_ERR_UNSUPPORTED;
     const int n_qb = (n_q + BQ - 1) / BQ;
     const int n_kb_cap = (C + BK - 1) / BK;
-    // the streaming kernel pays when there are thousands of its workgroups and the summaries fit four column blocks
-    // (measured: 121 against 126 us at 40 heads x 3600 blocks; with fewer, wider workgroups the plain kernel wins)
+    // long caches whose summaries fit four column blocks take the streaming kernel: about 2048 workgroups that
+    // sweep each head's key blocks together
     const bool few_cols = (n_qb * n_rep + 31) / 32 <= 4;
-    const int kbw = (few_cols && (size_t)n_kb_cap * H >= LONG_CACHE_BLOCKS) ? KB_PER_WG_LONG : KB_PER_WG;
-    const size_t tile_bytes = (size_t)n_qb * kbw * sizeof(int32_t);
-    if (tile_bytes > 64 * 1024) return FASTAR_ERR_UNSUPPORTED;
+    const bool stream_kernel = few_cols && (size_t)n_kb_cap * H >= LONG_CACHE_BLOCKS;
+    const size_t tile_bytes = (size_t)n_qb * KB_PER_WG * sizeof(int32_t);
+    if (!stream_kernel && tile_bytes > 64 * 1024) return FASTAR_ERR_UNSUPPORTED;
     const SelfWs w = self_ws(H, n_q, C, r, BQ, BK, n_rep);
     if (ws_bytes < w.total) return FASTAR_ERR_WORKSPACE;
     hipStream_t s = (hipStream_t)stream;
     int8_t *rep = (int8_t *)ws + w.rep_off;
     int32_t *score = (int32_t *)((char *)ws + w.score_off);
-    const dim3 grid((n_kb_cap + kbw - 1) / kbw, H);
+    const dim3 grid((n_kb_cap + KB_PER_WG - 1) / KB_PER_WG, H);
+    constexpr int stream_wgs = 768;   // three resident workgroups per CU (the kernel is built for 168 registers)
+    const dim3 grid_stream((unsigned)std::max(1, std::min(std::max(1, stream_wgs / H), (n_kb_cap + 3) / 4)), H);
 #define FASTAR_SELF(RR, BB)                                                                                            \
     do {                                                                                                               \
         hipLaunchKernelGGL(rep_kernel<BB>, dim3(n_qb, H), dim3(128), 0, s, qcode, n_q, r, BQ, n_rep, n_qb, rep);       \
         FASTAR_LAUNCH_CHECK();                                                                                         \
-        if (kbw == KB_PER_WG)                                                                                          \
+        if (!stream_kernel)                                                                                            \
             hipLaunchKernelGGL((score_self_kernel<RR, BB>), grid, dim3(256), tile_bytes, s, kcode, len, rep, C, n_q, BQ, \
                                n_rep, BK, n_qb, n_kb_cap, score);                                                      \
         else                                                                                                           \
-            hipLaunchKernelGGL((score_self_stream_kernel<RR, KB_PER_WG_LONG, 4, BB>), grid, dim3(256), tile_bytes, s,  \
-                               kcode, len, rep, C, n_q, BQ, n_rep, BK, n_qb, n_kb_cap, score);                         \
+            hipLaunchKernelGGL((score_self_stream_kernel<RR, 4, BB>), grid_stream, dim3(256), 0, s, kcode, len, rep, C, \
+                               n_q, BQ, n_rep, BK, n_qb, n_kb_cap, score);                                             \
     } while (0)
     if (bits == 4) FASTAR_SELF(32, 4);
     else if (bits == 2) FASTAR_SELF(32, 2);
