@@ -60,6 +60,7 @@ extern "C" {
 #define FASTAR_OP_SELECT_CROSS 3
 #define FASTAR_OP_SELECT_LSH 4
 #define FASTAR_OP_SELECT_BUCKETS 5 /* pass the number of prompt tokens as r */
+#define FASTAR_OP_ATTN 6           /* sparse_attn_fwd_ws: a fixed amount, whatever the shape */
 
 /* representative key of a merged TempCache group (tempcache_compress, rep_mode) */
 #define FASTAR_REP_LAST 0
@@ -347,6 +348,18 @@ int ann_cross_attn_fwd(const void *Q, const int8_t *qcode, int n_q, const void *
 int sparse_attn_fwd(const void *Q, int n_q, const void *K, const void *V, const int32_t *cnt,
                     const int32_t *len, int H, int C, int d, int dtype, const int32_t *sel, const int32_t *nsel,
                     int BQ, int BK, int n_sel, float scale, void *O, float *lse, void *stream);
+
+/*
+ * sparse_attn_fwd with a workspace: same arguments, same result (to the tolerance of the attention itself: a block
+ * that two workgroups share is put together from two partial sums).  With more query blocks than the chip holds at
+ * once (bf16, d = 128, BQ = 128) the persistent kernel is used: every resident workgroup takes an equal share of all
+ * tiles, query blocks cut by a share's boundary leave fragments in `ws`, a second small launch combines them.  Other
+ * shapes run exactly as sparse_attn_fwd and leave `ws` untouched.
+ *   ws / ws_bytes  fastar_workspace_bytes(FASTAR_OP_ATTN, ...) bytes, 256-byte aligned; contents need not be kept
+ */
+int sparse_attn_fwd_ws(const void *Q, int n_q, const void *K, const void *V, const int32_t *cnt, const int32_t *len,
+                       int H, int C, int d, int dtype, const int32_t *sel, const int32_t *nsel, int BQ, int BK, int n_sel,
+                       float scale, void *O, float *lse, void *ws, size_t ws_bytes, void *stream);
 
 /*
  * 8-bit floating-point K/V for the attention itself (Sec. 5.1, quantised-search paragraph; appendix ablation

@@ -16,7 +16,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libfastar.so")
 
 F32, BF16 = 0, 1
-OP_COMPRESS, OP_SELECT_SELF, OP_SELECT_CROSS, OP_SELECT_LSH, OP_SELECT_BUCKETS = 1, 2, 3, 4, 5
+OP_COMPRESS, OP_SELECT_SELF, OP_SELECT_CROSS, OP_SELECT_LSH, OP_SELECT_BUCKETS, OP_ATTN = 1, 2, 3, 4, 5, 6
 REP_LAST, REP_MEAN, REP_MEDOID = 0, 1, 2
 
 _lib = None
@@ -101,6 +101,8 @@ def lib() -> ctypes.CDLL:
                                       ctypes.c_void_p, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int,
                                       ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int, ctypes.c_int, ctypes.c_int,
                                       ctypes.c_float, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
+        L.sparse_attn_fwd_ws.restype = ctypes.c_int
+        L.sparse_attn_fwd_ws.argtypes = L.sparse_attn_fwd.argtypes[:-1] + [ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
         L.fastar_kv_to_fp8.restype = ctypes.c_int
         L.fastar_kv_to_fp8.argtypes = [ctypes.POINTER(_CacheStruct), ctypes.c_int32, ctypes.c_void_p, ctypes.c_void_p,
                                        ctypes.c_void_p]
@@ -125,7 +127,7 @@ def lib() -> ctypes.CDLL:
 
 EXPORTS = ("fastar_init", "fastar_version", "fastar_strerror", "fastar_workspace_bytes", "fastar_encode", "tempcache_compress",
            "ann_cross_attn_fwd",
-           "ann_select_self", "ann_select_self_forced", "ann_select_self_static", "ann_prompt_buckets", "ann_select_buckets", "fastar_encode_packed", "ann_select_self_packed", "ann_select_cross", "sparse_attn_fwd", "fastar_kv_to_fp8",
+           "ann_select_self", "ann_select_self_forced", "ann_select_self_static", "ann_prompt_buckets", "ann_select_buckets", "fastar_encode_packed", "ann_select_self_packed", "ann_select_cross", "sparse_attn_fwd", "sparse_attn_fwd_ws", "fastar_kv_to_fp8",
            "sparse_attn_fwd_fp8", "fastar_encode_sign", "ann_select_lsh", "ann_select_lsh_buckets",
            "fastar_probe_mfma_bf16", "fastar_probe_copy")
 
@@ -475,8 +477,10 @@ def ann_cross_attn_fwd(Q, qcode, Kp, Vp, pcode, BQ: int, n_sel: int, scale: floa
     return sel, nsel, O
 
 
-def sparse_attn_fwd(Q, K, V, cnt, length, sel, nsel, BQ: int, BK: int, scale: float, out=None, want_lse: bool = True):
-    """Block-sparse attention.  Returns (O [H,n_q,d] in Q's dtype, lse [H,n_q] float32 or None)."""
+def sparse_attn_fwd(Q, K, V, cnt, length, sel, nsel, BQ: int, BK: int, scale: float, out=None, want_lse: bool = True,
+                    ws=None):
+    """Block-sparse attention.  Returns (O [H,n_q,d] in Q's dtype, lse [H,n_q] float32 or None).
+    ws: uint8 device workspace of workspace_bytes(OP_ATTN, ...) -> sparse_attn_fwd_ws (persistent kernel where it pays)."""
     _dev(Q)
     _dev(K, Q.dtype)
     _dev(V, Q.dtype)
@@ -491,6 +495,13 @@ def sparse_attn_fwd(Q, K, V, cnt, length, sel, nsel, BQ: int, BK: int, scale: fl
     if out is None:
         out = (torch.empty_like(Q), torch.empty((H, n_q), dtype=torch.float32, device=Q.device) if want_lse else None)
     O, lse = out
+    if ws is not None:
+        _dev(ws, torch.uint8)
+        _check(lib().sparse_attn_fwd_ws(Q.data_ptr(), n_q, K.data_ptr(), V.data_ptr(), _ptr(cnt), length.data_ptr(), H, C,
+                                        d, _dtype_code(Q), sel.data_ptr(), nsel.data_ptr(), BQ, BK, n_sel, float(scale),
+                                        O.data_ptr(), _ptr(lse), ws.data_ptr(), ws.numel(), _stream()),
+               "sparse_attn_fwd_ws")
+        return O, lse
     _check(lib().sparse_attn_fwd(Q.data_ptr(), n_q, K.data_ptr(), V.data_ptr(), _ptr(cnt), length.data_ptr(), H, C, d,
                                  _dtype_code(Q), sel.data_ptr(), nsel.data_ptr(), BQ, BK, n_sel, float(scale),
                                  O.data_ptr(), _ptr(lse), _stream()), "sparse_attn_fwd")

@@ -7,6 +7,7 @@ size_t select_self_ws_bytes(int H, int n_q, int C, int r, int BQ, int BK, int n_
 size_t select_cross_ws_bytes(int H, int n_q, int n_p, int BQ);
 size_t select_lsh_ws_bytes(int H, int n_q, int C, int n_bits, int BQ, int BK, int n_rep);
 size_t select_buckets_ws_bytes(int H, int n_q, int C, int n_p, int BQ, int BK);
+size_t attn_sk_ws_bytes();
 }  // namespace fastar
 
 namespace fastar {
@@ -102,6 +103,7 @@ extern "C" size_t fastar_workspace_bytes(int op, int H, int n_q, int n_k, int r,
         case FASTAR_OP_SELECT_CROSS: return fastar::select_cross_ws_bytes(H, n_q, n_k, BQ);
         case FASTAR_OP_SELECT_LSH: return fastar::select_lsh_ws_bytes(H, n_q, n_k, r, BQ, BK, n_rep);
         case FASTAR_OP_SELECT_BUCKETS: return fastar::select_buckets_ws_bytes(H, n_q, n_k, r, BQ, BK);
+        case FASTAR_OP_ATTN: return fastar::attn_sk_ws_bytes();
         default: return 0;
     }
 }

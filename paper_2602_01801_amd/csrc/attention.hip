@@ -374,14 +374,43 @@ int launch_attn_bf16_d128_pp(const void *Q, int n_q, const void *K, const void *
                              const int32_t *len, int H, int C, const int32_t *sel, const int32_t *nsel, int bk_shift,
                              int n_sel, float scale_log2, void *O, float *lse, hipStream_t s);
 
+size_t attn_sk_ws_bytes();
+int launch_attn_bf16_d128_sk(const void *Q, int n_q, const void *K, const void *V, const int32_t *cnt, const int32_t *len,
+                             int H, int C, const int32_t *sel, const int32_t *nsel, int bk_shift, int n_sel,
+                             float scale_log2, void *O, float *lse, void *ws, hipStream_t s);
+
 }  // namespace fastar
 
 using namespace fastar;
+
+static int sparse_attn_impl(const void *Q, int n_q, const void *K, const void *V, const int32_t *cnt,
+                            const int32_t *len, int H, int C, int d, int dtype, const int32_t *sel,
+                            const int32_t *nsel, int BQ, int BK, int n_sel, float scale, void *O, float *lse,
+                            void *ws, size_t ws_bytes, void *stream);
 
 extern "C" int sparse_attn_fwd(const void *Q, int n_q, const void *K, const void *V, const int32_t *cnt,
                                const int32_t *len, int H, int C, int d, int dtype, const int32_t *sel,
                                const int32_t *nsel, int BQ, int BK, int n_sel, float scale, void *O, float *lse,
                                void *stream) {
+    return sparse_attn_impl(Q, n_q, K, V, cnt, len, H, C, d, dtype, sel, nsel, BQ, BK, n_sel, scale, O, lse, nullptr, 0,
+                            stream);
+}
+
+extern "C" int sparse_attn_fwd_ws(const void *Q, int n_q, const void *K, const void *V, const int32_t *cnt,
+                                  const int32_t *len, int H, int C, int d, int dtype, const int32_t *sel,
+                                  const int32_t *nsel, int BQ, int BK, int n_sel, float scale, void *O, float *lse,
+                                  void *ws, size_t ws_bytes, void *stream) {
+    if (!ws || ((uintptr_t)ws & 255)) return FASTAR_ERR_INVALID_ARG;
+    if (ws_bytes < attn_sk_ws_bytes()) return FASTAR_ERR_WORKSPACE;
+    return sparse_attn_impl(Q, n_q, K, V, cnt, len, H, C, d, dtype, sel, nsel, BQ, BK, n_sel, scale, O, lse, ws, ws_bytes,
+                            stream);
+}
+
+static int sparse_attn_impl(const void *Q, int n_q, const void *K, const void *V, const int32_t *cnt,
+                               const int32_t *len, int H, int C, int d, int dtype, const int32_t *sel,
+                               const int32_t *nsel, int BQ, int BK, int n_sel, float scale, void *O, float *lse,
+                               void *ws, size_t ws_bytes, void *stream) {
+    (void)ws_bytes;
     if (!Q || !K || !V || !len || !sel || !nsel || !O) return FASTAR_ERR_INVALID_ARG;
     if (H <= 0 || n_q <= 0 || C <= 0 || BQ <= 0 || BK <= 0 || n_sel <= 0) return FASTAR_ERR_INVALID_ARG;
     if (dtype != FASTAR_F32 && dtype != FASTAR_BF16) return FASTAR_ERR_INVALID_ARG;
@@ -406,6 +435,10 @@ extern "C" int sparse_attn_fwd(const void *Q, int n_q, const void *K, const void
         // work comes in rounds of 512 query blocks: when the last round would be less than half full, the kernel with
         // one block per workgroup (two workgroups per CU, started as slots free up) finishes earlier.
         const int n_items = n_qb * H;
+        // With a workspace, and more query blocks than fit the chip at once, the persistent kernel: equal shares of
+        // the tiles for every resident workgroup, whatever the block count (long enough shares to pay for the fragments).
+        if (ws && d == 128 && BQ == 128 && n_items > 512 && (long long)n_items * ((n_sel * BK + 63) / 64) >= 512ll * 128)
+            return launch_attn_bf16_d128_sk(Q, n_q, K, V, cnt, len, H, C, sel, nsel, bk_shift, n_sel, scale_log2, O, lse, ws, s);
         if (d == 128 && BQ == 128 && (n_items <= 512 || n_items % 512 == 0 || n_items % 512 >= 256))
             return launch_attn_bf16_d128_pp(Q, n_q, K, V, cnt, len, H, C, sel, nsel, bk_shift, n_sel, scale_log2, O, lse, s);
         if (d == 128)  // tuned path: direct-to-LDS tiles, LDS transpose loads

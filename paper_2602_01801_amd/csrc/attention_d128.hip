@@ -15,6 +15,8 @@
 //   * masked rows (padding of the selection list, slots beyond len) fetch row 0 of the head, which
 //     is live, and carry a -inf bias, so they contribute exactly zero;
 //   * the running-maximum rescale of O is skipped when no lane of the wavefront saw a new maximum.
+#include <limits.h>
+
 #include <type_traits>
 
 #include "common.hpp"
@@ -127,30 +129,25 @@ __device__ __forceinline__ void pv_mfma(f32x16 (&o_acc)[D / 32], const s16x4 (&f
 // dynamic LDS layout: [K stage 0][K stage 1][V stage 0][V stage 1][meta x3]
 constexpr int LDS_BYTES = 4 * TILEB + 3 * (int)sizeof(TileMeta);
 
+constexpr int PART_O_FLOATS = (D / 32) * 16 * 64;              // O^T accumulators of one wavefront
+constexpr int PART_FLOATS = 4 * (PART_O_FLOATS + 2 * 64);      // one fragment of a query block (4 wavefronts)
+constexpr int SK_WORKGROUPS = 512;                             // two resident workgroups per CU
+
+// One query block (h, b) over the tiles [t_begin, t_end) of its selection list (t_end may lie beyond the list: it is
+// clipped).  part == nullptr: the block's output rows and lse are written.  Otherwise the fragment's unnormalised
+// result goes to `part`: O^T accumulators as they sit in registers ([wave][db][v][lane] floats), then the reference
+// maxima and the row sums ([wave][lane] each), for attn_combine_kernel.  All NW * 64 threads of a workgroup.
 template <int NW>
-__global__ __launch_bounds__(NW * 64, 2) void attn_bf16_d128_kernel(
+__device__ __forceinline__ void attend_item(
     const unsigned short *__restrict__ Q, const unsigned short *__restrict__ K, const unsigned short *__restrict__ V,
     const int32_t *__restrict__ cnt, const int32_t *__restrict__ len, const int32_t *__restrict__ sel,
-    const int32_t *__restrict__ nsel, int n_q, int C, int bk_shift, int n_sel, int n_qb, int H, float scale_log2, float inv_scale_log2,
-    unsigned short *__restrict__ O, float *__restrict__ lse) {
-    extern __shared__ __attribute__((aligned(1024))) unsigned char lds[];
+    const int32_t *__restrict__ nsel, int n_q, int C, int bk_shift, int n_sel, int n_qb, float scale_log2,
+    float inv_scale_log2, unsigned short *__restrict__ O, float *__restrict__ lse, unsigned char *lds, int h, int b,
+    int t_begin, int t_end, float *__restrict__ part) {
     unsigned char *kbuf = lds;
     unsigned char *vbuf = lds + 2 * TILEB;
     TileMeta *meta = (TileMeta *)(lds + 4 * TILEB);
     constexpr int IPW = (TK / 4) / NW;  // 1-KiB direct-load instructions per wavefront and tensor
-
-    // workgroup -> (head, query block): each XCD (workgroups are dealt round-robin to 8 of them) gets a
-    // contiguous range of (head, block) pairs, so neighbouring query blocks share one L2.
-    int h, b;
-    {
-        const int total = n_qb * H;
-        const int wg = blockIdx.x;
-        const int per = (total + 7) / 8;
-        const int item = (wg & 7) * per + (wg >> 3);
-        if (item >= total) return;
-        h = item / n_qb;
-        b = item % n_qb;
-    }
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform, kept in a scalar register
     const int col = lane & 31, g = lane >> 5;
@@ -160,7 +157,8 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_bf16_d128_kernel(
     const int32_t *cnt_h = cnt ? cnt + (size_t)h * C : nullptr;
     const unsigned short *Kh = K + (size_t)h * C * D;
     const unsigned short *Vh = V + (size_t)h * C * D;
-    const int nt = ((n_listed << bk_shift) + TK - 1) / TK;
+    const int nt = min(((n_listed << bk_shift) + TK - 1) / TK, t_end);   // end of this fragment
+    const int t0 = min(t_begin, nt);
 
     const int q_idx = b * (NW * 32) + wave * 32 + col;
     bf16x8 qf[D / 16];
@@ -214,12 +212,12 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_bf16_d128_kernel(
         return key;
     };
     int kb_ahead = -1;  // selection entry of this thread's position in tile t+2
-    if (nt > 0) {
-        fill_meta(meta[0], 0, sel_row, n_listed, bk_shift, L, cnt_h, inv_scale_log2);
-        if (nt > 1) fill_meta(meta[1], 1, sel_row, n_listed, bk_shift, L, cnt_h, inv_scale_log2);
-        if (nt > 2) kb_ahead = sel_entry(2);
+    if (nt > t0) {
+        fill_meta(meta[t0 % 3], t0, sel_row, n_listed, bk_shift, L, cnt_h, inv_scale_log2);
+        if (nt > t0 + 1) fill_meta(meta[(t0 + 1) % 3], t0 + 1, sel_row, n_listed, bk_shift, L, cnt_h, inv_scale_log2);
+        if (nt > t0 + 2) kb_ahead = sel_entry(t0 + 2);
         __syncthreads();
-        issue_loads(meta[0], 0);
+        issue_loads(meta[t0 % 3], 0);
     }
     // Per-lane LDS byte offsets that do not depend on the tile.  XOR with a per-lane constant permutes
     // aligned groups of chunks, so every fragment address is (per-lane register) + (compile-time offset).
@@ -358,20 +356,30 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_bf16_d128_kernel(
         kb_ahead = kb3;
     };
     if (b * (NW * 32) + wave * 32 < n_q) {   // wave-uniform
-        for (int t = 0; t < nt; t += 2) {
+        for (int t = t0; t < nt; t += 2) {
             tile_step(t, std::integral_constant<int, 0>{}, std::true_type{});
             if (t + 1 < nt) tile_step(t + 1, std::integral_constant<int, 1>{}, std::true_type{});
         }
     } else {
-        for (int t = 0; t < nt; t += 2) {
+        for (int t = t0; t < nt; t += 2) {
             tile_step(t, std::integral_constant<int, 0>{}, std::false_type{});
             if (t + 1 < nt) tile_step(t + 1, std::integral_constant<int, 1>{}, std::false_type{});
         }
     }
 
-    // epilogue: normalise, transpose through LDS (K stages are free now), store rows coalesced
     const float l_lane = l0 + l1;
     const float l_tot = l_lane + shfl_xor(l_lane, 32);
+    if (part) {   // a fragment of the block: everything a later combination needs, as it sits in the registers
+#pragma unroll
+        for (int db = 0; db < D / 32; ++db)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) part[((wave * (D / 32) + db) * 16 + v) * 64 + lane] = o_acc[db][v];
+        part[NW * PART_O_FLOATS + wave * 64 + lane] = m_ref;
+        part[NW * PART_O_FLOATS + NW * 64 + wave * 64 + lane] = l_tot;
+        __syncthreads();   // the tile stages and row tables are free for the next block
+        return;
+    }
+    // epilogue: normalise, transpose through LDS (K stages are free now), store rows coalesced
     const float inv = l_tot > 0.0f ? 1.0f / l_tot : 0.0f;
     __syncthreads();
     constexpr int OSTR = D + 8;  // bf16 elements per staged row (16-byte pad)
@@ -400,6 +408,123 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_bf16_d128_kernel(
     }
     if (lse && g == 0 && q_idx < n_q)
         lse[(size_t)h * n_q + q_idx] = l_tot > 0.0f ? (m_ref * scale_log2 + __log2f(l_tot)) * LN2 : -INFINITY;
+    __syncthreads();   // the staged output rows have been read: the tile stages are free for the next block
+}
+
+
+// One query block per workgroup; two workgroups per CU, started as slots free up.
+template <int NW>
+__global__ __launch_bounds__(NW * 64, 2) void attn_bf16_d128_kernel(
+    const unsigned short *__restrict__ Q, const unsigned short *__restrict__ K, const unsigned short *__restrict__ V,
+    const int32_t *__restrict__ cnt, const int32_t *__restrict__ len, const int32_t *__restrict__ sel,
+    const int32_t *__restrict__ nsel, int n_q, int C, int bk_shift, int n_sel, int n_qb, int H, float scale_log2, float inv_scale_log2,
+    unsigned short *__restrict__ O, float *__restrict__ lse) {
+    extern __shared__ __attribute__((aligned(1024))) unsigned char lds[];
+    // workgroup -> (head, query block): each XCD (workgroups are dealt round-robin to 8 of them) gets a
+    // contiguous range of (head, block) pairs, so neighbouring query blocks share one L2.
+    const int total = n_qb * H;
+    const int wg = blockIdx.x;
+    const int per = (total + 7) / 8;
+    const int item = (wg & 7) * per + (wg >> 3);
+    if (item >= total) return;
+    attend_item<NW>(Q, K, V, cnt, len, sel, nsel, n_q, C, bk_shift, n_sel, n_qb, scale_log2, inv_scale_log2, O, lse, lds,
+                    item / n_qb, item % n_qb, 0, INT_MAX, nullptr);
+}
+
+// The persistent form (BQ = 128).  Every query block stands for NT tiles (its list may be shorter), the blocks in
+// (head, block) order make one sequence of n_qb * H * NT tiles, and each of the P resident workgroups takes an equal,
+// contiguous share of it: whole blocks are finished in place, a block cut by a share's boundary leaves one fragment per
+// share that touches it (slot 0 of a workgroup: a block begun by an earlier workgroup; slot 1: a block it begins but
+// does not finish), and attn_combine_kernel puts the fragments together.  However the block count compares with the
+// number of resident workgroups, every workgroup does the same amount of work.
+__global__ __launch_bounds__(256, 2) void attn_bf16_d128_sk_kernel(
+    const unsigned short *__restrict__ Q, const unsigned short *__restrict__ K, const unsigned short *__restrict__ V,
+    const int32_t *__restrict__ cnt, const int32_t *__restrict__ len, const int32_t *__restrict__ sel,
+    const int32_t *__restrict__ nsel, int n_q, int C, int bk_shift, int n_sel, int n_qb, int H, int NT, float scale_log2,
+    float inv_scale_log2, unsigned short *__restrict__ O, float *__restrict__ lse, float *__restrict__ ws) {
+    extern __shared__ __attribute__((aligned(1024))) unsigned char lds[];
+    const int P = gridDim.x;                                       // a multiple of 8
+    const int i = (blockIdx.x & 7) * (P >> 3) + (blockIdx.x >> 3);   // neighbouring shares on one XCD
+    const long long W = (long long)n_qb * H * NT;
+    long long v = i * W / P;
+    const long long v_end = (i + 1) * W / P;
+    while (v < v_end) {
+        const int item = (int)(v / NT);
+        const int t_begin = (int)(v - (long long)item * NT);
+        const int t_end = (int)min((long long)NT, v_end - (long long)item * NT);
+        float *part = nullptr;
+        if (t_begin > 0 || t_end < NT) part = ws + ((size_t)i * 2 + (t_begin > 0 ? 0 : 1)) * PART_FLOATS;
+        attend_item<4>(Q, K, V, cnt, len, sel, nsel, n_q, C, bk_shift, n_sel, n_qb, scale_log2, inv_scale_log2, O, lse, lds,
+                       item / n_qb, item % n_qb, t_begin, t_end, part);
+        v = (long long)item * NT + t_end;
+    }
+}
+
+// Fragments of the query blocks that attn_bf16_d128_sk_kernel cut: workgroup i of this launch puts together the block
+// that share i begins but does not finish (its slot 1, then slot 0 of the following shares while they lie inside the
+// block).  Same wavefront / lane layout as the fragments; any reference maximum is as good as the true one.
+__global__ __launch_bounds__(256) void attn_combine_kernel(const float *__restrict__ ws, int P, int n_q, int n_qb, int H,
+                                                           int NT, float scale_log2, unsigned short *__restrict__ O,
+                                                           float *__restrict__ lse) {
+    extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
+    const int i = blockIdx.x;
+    const long long W = (long long)n_qb * H * NT;
+    const long long start = i * W / P, end = (i + 1) * W / P;
+    if (end >= W || end % NT == 0) return;          // share i ends with a whole block
+    const int item = (int)(end / NT);
+    if ((long long)item * NT < start) return;       // the block began in an earlier share: that one combines it
+    const long long item_end = (long long)(item + 1) * NT;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int col = lane & 31, g = lane >> 5;
+    const int h = item / n_qb, b = item % n_qb;
+    // fragments: (i, slot 1), then (k, slot 0) for k = i + 1 .. while share k starts inside the block
+    int n_frag = 1;
+    while (i + n_frag < P && (i + n_frag) * W / P < item_end) ++n_frag;
+    auto frag = [&](int f) -> const float * { return ws + ((size_t)(i + f) * 2 + (f == 0 ? 1 : 0)) * PART_FLOATS; };
+    float m_all = -INFINITY;
+    for (int f = 0; f < n_frag; ++f) m_all = fmaxf(m_all, frag(f)[4 * PART_O_FLOATS + wave * 64 + lane]);
+    float o[D / 32][16];
+#pragma unroll
+    for (int db = 0; db < D / 32; ++db)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) o[db][v] = 0.0f;
+    float l_tot = 0.0f;
+    for (int f = 0; f < n_frag; ++f) {
+        const float *p = frag(f);
+        const float m_f = p[4 * PART_O_FLOATS + wave * 64 + lane];
+        const float w = m_f == -INFINITY ? 0.0f : __builtin_amdgcn_exp2f((m_f - m_all) * scale_log2);
+        l_tot += w * p[4 * PART_O_FLOATS + 4 * 64 + wave * 64 + lane];
+        if (w > 0.0f) {
+#pragma unroll
+            for (int db = 0; db < D / 32; ++db)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) o[db][v] += w * p[((wave * (D / 32) + db) * 16 + v) * 64 + lane];
+        }
+    }
+    const float inv = l_tot > 0.0f ? 1.0f / l_tot : 0.0f;
+    constexpr int OSTR = D + 8;
+    unsigned short *Os = (unsigned short *)lds + (size_t)wave * 32 * OSTR;
+#pragma unroll
+    for (int db = 0; db < D / 32; ++db)
+#pragma unroll
+        for (int q4 = 0; q4 < 4; ++q4) {
+            typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
+            bf16x4 wv;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) wv[e] = (__bf16)(o[db][4 * q4 + e] * inv);
+            *(bf16x4 *)(Os + col * OSTR + 32 * db + 8 * q4 + 4 * g) = wv;
+        }
+    __syncthreads();
+    const int rr = lane >> 4, cc = lane & 15;
+#pragma unroll
+    for (int it = 0; it < 8; ++it) {
+        const int r = it * 4 + rr;
+        const int qi = b * 128 + wave * 32 + r;
+        if (qi < n_q) *(u32x4 *)(O + ((size_t)h * n_q + qi) * D + cc * 8) = *(const u32x4 *)(Os + r * OSTR + cc * 8);
+    }
+    const int q_idx = b * 128 + wave * 32 + col;
+    if (lse && g == 0 && q_idx < n_q)
+        lse[(size_t)h * n_q + q_idx] = l_tot > 0.0f ? (m_all * scale_log2 + __log2f(l_tot)) * LN2 : -INFINITY;
 }
 
 }  // namespace d128
@@ -412,6 +537,8 @@ int attn_d128_setup() {
         if (hipFuncSetAttribute((const void *)attn_bf16_d128_kernel<4>, hipFuncAttributeMaxDynamicSharedMemorySize,
                                 LDS_BYTES) != hipSuccess ||
             hipFuncSetAttribute((const void *)attn_bf16_d128_kernel<2>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                LDS_BYTES) != hipSuccess ||
+            hipFuncSetAttribute((const void *)attn_bf16_d128_sk_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
                                 LDS_BYTES) != hipSuccess)
             return FASTAR_ERR_HIP;
         return FASTAR_OK;
@@ -434,6 +561,27 @@ int launch_attn_bf16_d128(const void *Q, int n_q, const void *K, const void *V, 
         hipLaunchKernelGGL(attn_bf16_d128_kernel<2>, grid, dim3(128), LDS_BYTES, s, (const unsigned short *)Q,
                            (const unsigned short *)K, (const unsigned short *)V, cnt, len, sel, nsel, n_q, C, bk_shift,
                            n_sel, n_qb, H, scale_log2, 1.0f / scale_log2, (unsigned short *)O, lse);
+    if (hipGetLastError() != hipSuccess) return FASTAR_ERR_HIP;
+    return FASTAR_OK;
+}
+
+// The persistent form of the same attention (BQ = 128): every resident workgroup gets an equal share of the tiles.
+// ws: SK_WORKGROUPS * 2 fragments (attn_sk_ws_bytes()).
+size_t attn_sk_ws_bytes() { return (size_t)d128::SK_WORKGROUPS * 2 * d128::PART_FLOATS * sizeof(float); }
+
+int launch_attn_bf16_d128_sk(const void *Q, int n_q, const void *K, const void *V, const int32_t *cnt, const int32_t *len,
+                             int H, int C, const int32_t *sel, const int32_t *nsel, int bk_shift, int n_sel,
+                             float scale_log2, void *O, float *lse, void *ws, hipStream_t s) {
+    using namespace d128;
+    if (const int rc = attn_d128_setup(); rc != FASTAR_OK) return rc;
+    const int n_qb = (n_q + 127) / 128;
+    const int NT = (int)((((long long)n_sel << bk_shift) + TK - 1) / TK);
+    hipLaunchKernelGGL(attn_bf16_d128_sk_kernel, dim3(SK_WORKGROUPS), dim3(256), LDS_BYTES, s, (const unsigned short *)Q,
+                       (const unsigned short *)K, (const unsigned short *)V, cnt, len, sel, nsel, n_q, C, bk_shift, n_sel,
+                       n_qb, H, NT, scale_log2, 1.0f / scale_log2, (unsigned short *)O, lse, (float *)ws);
+    if (hipGetLastError() != hipSuccess) return FASTAR_ERR_HIP;
+    hipLaunchKernelGGL(attn_combine_kernel, dim3(SK_WORKGROUPS), dim3(256), 4 * 32 * (D + 8) * 2, s, (const float *)ws,
+                       SK_WORKGROUPS, n_q, n_qb, H, NT, scale_log2, (unsigned short *)O, lse);
     if (hipGetLastError() != hipSuccess) return FASTAR_ERR_HIP;
     return FASTAR_OK;
 }

@@ -1150,3 +1150,74 @@ def test_bad_arguments_are_rejected_on_the_host():
         fa.sparse_attn_fwd(Qf, Qf, Qf, None, length, sel, nsel, 128, 96, 0.1)  # fp32: BK beyond 64
     with pytest.raises(fa.FastarError, match="unsupported"):
         fa.sparse_attn_fwd(Qf, Qf, Qf, None, length, sel, nsel, 256, 64, 0.1)  # fp32: BQ beyond 128
+
+
+# ----------------------------------------------------------------------------------------- persistent attention
+
+@pytest.mark.parametrize("H,n_q,C,n_sel,lens_cut,with_cnt", [
+    (20, 3600, 64 * 400, 200, 0, True),      # 580 query blocks, ragged last block of every head, shares of 226.6 tiles
+    (9, 7700, 64 * 300, 150, 1, True),       # 549 blocks; one head short, one empty: lists shorter than the share arithmetic assumes
+    (33, 2048, 64 * 256, 128, 0, False),     # 528 blocks, no multiplicities
+])
+def test_persistent_attention_matches_the_oracle_and_the_plain_launch(H, n_q, C, n_sel, lens_cut, with_cnt):
+    # sparse_attn_fwd_ws takes the persistent kernel here (more than 512 query blocks, long shares): blocks cut by share
+    # boundaries are combined from fragments.  Oracle on sampled (head, query block) pairs incl. cut and whole ones.
+    rng = np.random.default_rng(H + n_q)
+    g = torch.Generator(device="cuda").manual_seed(H * 1000 + n_sel)
+    Q = torch.randn(H, n_q, 128, device="cuda", generator=g).bfloat16()
+    K = torch.randn(H, C, 128, device="cuda", generator=g).bfloat16()
+    V = torch.randn(H, C, 128, device="cuda", generator=g).bfloat16()
+    Q[:, ::7] *= 3.0                                           # some peaked rows
+    cnt = torch.randint(1, 6, (H, C), device="cuda", generator=g, dtype=torch.int32) if with_cnt else None
+    lens = np.full(H, C, np.int32)
+    if lens_cut:
+        lens[3], lens[5] = C // 3 + 17, 0
+    n_qb, n_kb = -(-n_q // 128), C // 64
+    sel = np.stack([np.stack([np.sort(rng.choice(n_kb, n_sel, replace=False)) for _ in range(n_qb)]) for _ in range(H)]).astype(np.int32)
+    nsel = np.full((H, n_qb), n_sel, np.int32)
+    nsel[0, 1], nsel[1, 0] = n_sel // 3, 0                     # short and empty lists
+    sel[0, 1, n_sel // 3:] = -1
+    sel[1, 0, :] = -1
+    ws = torch.empty(fa.workspace_bytes(fa.OP_ATTN, H, n_q, C), dtype=torch.uint8, device="cuda")
+    args = (Q, K, V, cnt, to_dev(lens), to_dev(sel), to_dev(nsel), 128, 64, 128 ** -0.5)
+    O_ws, lse_ws = fa.sparse_attn_fwd(*args, ws=ws)
+    O_pl, lse_pl = fa.sparse_attn_fwd(*args)
+    sync()
+    O_ws_h, O_pl_h = to_host(O_ws), to_host(O_pl)
+    assert np.abs(to_f32(O_ws_h).astype(np.float64) - to_f32(O_pl_h)).max() <= 2e-2
+    lw, lp = to_host(lse_ws), to_host(lse_pl)
+    fin = np.isfinite(lp)
+    assert np.array_equal(fin, np.isfinite(lw)) and np.abs(lw[fin] - lp[fin]).max() <= 1e-2   # sums of rounded P against different references
+    # the oracle on a sample of blocks: the first ones, the special ones, and blocks around share boundaries
+    NT = n_sel
+    W = n_qb * H * NT
+    cut_items = sorted({(i * W // 512) // NT for i in range(1, 512) if (i * W // 512) % NT})
+    sample = sorted(set([0, 1, n_qb, n_qb - 1, H * n_qb - 1] + cut_items[:3] + cut_items[-2:] + [cut_items[len(cut_items) // 2]]))
+    Kh, Vh, Qh = to_host(K), to_host(V), to_host(Q)
+    cnt_h = to_host(cnt) if with_cnt else None
+    for item in sample:
+        h, b = divmod(item, n_qb)
+        q0, q1 = b * 128, min((b + 1) * 128, n_q)
+        O_r, lse_r = oracle.sparse_attn_fwd(Qh[h:h + 1, q0:q1], Kh[h:h + 1], Vh[h:h + 1], None if cnt_h is None else cnt_h[h:h + 1],
+                                            lens[h:h + 1], sel[h:h + 1, b:b + 1], nsel[h:h + 1, b:b + 1], 128, 64, 128 ** -0.5)
+        err = np.abs(to_f32(O_ws_h[h, q0:q1]).astype(np.float64) - O_r[0]).max()
+        assert err <= ATOL["bf16"], f"item {item}: {err}"
+        lr = lse_r[0]
+        ok = np.isfinite(lr)
+        assert np.array_equal(ok, np.isfinite(lw[h, q0:q1])) and np.abs(lw[h, q0:q1][ok] - lr[ok]).max(initial=0.0) <= 2e-2
+
+
+def test_attention_with_a_workspace_runs_small_shapes_as_before_and_rejects_a_short_workspace():
+    rng = np.random.default_rng(5)
+    H, n_q, C, n_sel = 2, 300, 640, 4
+    Q, K, V = (to_dev(to_storage(rng.standard_normal((H, n, 128)).astype(np.float32), "bf16")) for n in (n_q, C, C))
+    lens = to_dev(np.array([640, 300], np.int32))
+    sel = to_dev(np.stack([np.stack([np.sort(rng.choice(10, n_sel, replace=False)) for _ in range(3)]) for _ in range(H)]).astype(np.int32))
+    nsel = to_dev(np.full((H, 3), n_sel, np.int32))
+    ws = torch.empty(fa.workspace_bytes(fa.OP_ATTN, H, n_q, C), dtype=torch.uint8, device="cuda")
+    a = fa.sparse_attn_fwd(Q, K, V, None, lens, sel, nsel, 128, 64, 0.1, ws=ws)
+    b = fa.sparse_attn_fwd(Q, K, V, None, lens, sel, nsel, 128, 64, 0.1)
+    sync()
+    assert torch.equal(a[0], b[0]) and torch.equal(a[1], b[1])
+    with pytest.raises(fa.FastarError):
+        fa.sparse_attn_fwd(Q, K, V, None, lens, sel, nsel, 128, 64, 0.1, ws=ws[:1024])
