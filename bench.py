@@ -224,6 +224,72 @@ class ChunkPipeline:
         return 4.0 * self.d * float(pairs.item())
 
 
+def selection_variants(pipe, Q, cfg, torch, fa, np, to_dev, reps=3):
+    """The other selection forms on the cache as the run left it, each timed on its own (events around `reps` calls, a
+    warm-up call first): codes of 4 and 2 bits per entry, hash tables over sign codes, prompt-induced buckets.  What a
+    variant needs beside the per-chunk call (packed codes / hash bits / bucket ids of the whole cache) is built once,
+    outside the timing, as a cache that kept such metadata per slot would have it."""
+    from workloads import make_sign_matrix
+    H, C, d, r = pipe.H, pipe.C, pipe.d, pipe.r
+    BQ, BK, n_rep, n_sel = pipe.BQ, pipe.BK, pipe.n_rep, pipe.n_sel
+
+    def timed(fn):
+        fn()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return round(e0.elapsed_time(e1) / reps, 4)
+
+    def density(nsel):
+        live_blocks = torch.clamp((pipe.cache.len + BK - 1) // BK, min=1).to(torch.float32)
+        return round(float((nsel.to(torch.float32) / live_blocks[:, None]).mean().item()), 4)
+
+    out = {"note": "per-chunk cost of the query side + the selection; ms; density = selected / live key blocks"}
+    out["int8_r32"] = {"ms": timed(lambda: (fa.encode(Q, pipe.codec, out=pipe.qcode),
+                                             fa.ann_select_self(pipe.qcode, pipe.cache.code, pipe.cache.len, BQ, n_rep, BK,
+                                                                n_sel, ws=pipe.ws_s, out=pipe.sel))),
+                       "bytes_per_key": r}
+    for bits, shift in ((4, 8), (2, 9)):
+        codec = fa.Codec(pipe.codec.R, pipe.codec.qscale, shift)
+        kp = fa.encode_packed(pipe.cache.K, codec, bits)
+        qp = fa.encode_packed(Q, codec, bits)
+        sel = (torch.empty_like(pipe.sel[0]), torch.empty_like(pipe.sel[1]))
+        out[f"packed_{bits}bit"] = {"ms": timed(lambda: (fa.encode_packed(Q, codec, bits, out=qp),
+                                                        fa.ann_select_self_packed(qp, kp, pipe.cache.len, bits, BQ, n_rep,
+                                                                                  BK, n_sel, ws=pipe.ws_s, out=sel))),
+                                     "bytes_per_key": r * bits // 8, "shift": shift}
+        del kp, qp
+    Rb = to_dev(make_sign_matrix(cfg["seed"], cfg["cfg_id"], d, 128))
+    kbits = fa.encode_sign(pipe.cache.K, Rb, pipe.codec.qscale)
+    qbits = fa.encode_sign(Q, Rb, pipe.codec.qscale)
+    ws_l = torch.empty(fa.workspace_bytes(fa.OP_SELECT_LSH, H, pipe.n_q, C, 128, BQ, BK, n_rep), dtype=torch.uint8, device="cuda")
+    sel = (torch.empty_like(pipe.sel[0]), torch.empty_like(pipe.sel[1]))
+    out["lsh_equal_bits_128"] = {"ms": timed(lambda: (fa.encode_sign(Q, Rb, pipe.codec.qscale, out=qbits),
+                                                      fa.ann_select_lsh(qbits, kbits, pipe.cache.len, BQ, n_rep, BK, n_sel,
+                                                                        ws=ws_l, out=sel))), "bytes_per_key": 16}
+    for band, radius in ((8, 0), (8, 1)):
+        ms = timed(lambda: (fa.encode_sign(Q, Rb, pipe.codec.qscale, out=qbits),
+                            fa.ann_select_lsh_buckets(qbits, kbits, pipe.cache.len, band, radius, BQ, n_rep, BK, n_sel,
+                                                      ws=ws_l, out=sel)))
+        out[f"lsh_tables_16x{band}bit_radius{radius}"] = {"ms": ms, "bytes_per_key": 16, "density": density(sel[1])}
+    del kbits, qbits, ws_l
+    m = 2
+    kb = fa.prompt_buckets(pipe.cache.code, pipe.pcode, m)
+    assign_all = timed(lambda: fa.prompt_buckets(pipe.cache.code, pipe.pcode, m, out=kb))
+    idx = pipe.prev if pipe.prev is not None else None
+    assign_frame = timed(lambda: fa.prompt_buckets(pipe.cache.code, pipe.pcode, m, idx=idx, out=kb)) if idx is not None else None
+    qb = fa.prompt_buckets(pipe.qcode, pipe.pcode, m)
+    ws_b = torch.empty(fa.workspace_bytes(fa.OP_SELECT_BUCKETS, H, pipe.n_q, C, pipe.n_p, BQ, BK, 0), dtype=torch.uint8, device="cuda")
+    ms = timed(lambda: (fa.prompt_buckets(pipe.qcode, pipe.pcode, m, out=qb),
+                        fa.ann_select_buckets(qb, kb, pipe.cache.len, pipe.n_p, BQ, BK, n_sel, ws=ws_b, out=sel)))
+    out["prompt_buckets_m2"] = {"ms": ms, "density": density(sel[1]), "bucket_ids_of_the_frames_slots_ms": assign_frame,
+                                "bucket_ids_of_the_whole_cache_ms": assign_all, "bytes_per_key": 4 * m}
+    return out
+
+
 def gen_chunks(cfg, n_prefill, n_chunks, cpu_heads):
     """Host-side generation of the whole rollout (uploaded once by the caller).  Returns the prefill frames, the
     chunks [(frames, Q)], the prompt set; host arrays in storage form."""
@@ -458,7 +524,8 @@ def build_cfg5_full(args, torch, fa, np, to_dev, to_host, n_chunks, n_cpu_heads)
                 label=label, n_prefill=n_fill, cap_frames=n_fill, n_sel=n_sel, n_kb_quoted=n_kb)
 
 
-def run_layer(args, workload, torch, fa, np, to_dev, to_host, steps, warmup, stage_steps, with_cpu, with_dense):
+def run_layer(args, workload, torch, fa, np, to_dev, to_host, steps, warmup, stage_steps, with_cpu, with_dense,
+              with_variants=False):
     """Build one workload, time `steps` chunk steps, return its record."""
     n_chunks = warmup + steps + stage_steps
     n_cpu_heads = min(args.cpu_heads, 40)
@@ -585,6 +652,8 @@ def run_layer(args, workload, torch, fa, np, to_dev, to_host, steps, warmup, sta
         oc, oprev, ofid = B["oracle_start"]()
         result["cpu_baseline"] = cpu_baseline(cfg, pipe, oc, oprev, ofid, B["host_chunks"], B["ps_host"], n_cpu_heads,
                                               to_host, B["sign_h"], args.code_shift)
+    if with_variants:
+        result["selection_variants"] = selection_variants(pipe, dev_chunks[-1][1], cfg, torch, fa, np, to_dev)
     return result
 
 
@@ -636,7 +705,8 @@ def main():
         return sweep(args, torch, fa, np, to_dev, to_host, n_frames=args.sweep_frames)
 
     result = run_layer(args, args.workload, torch, fa, np, to_dev, to_host, args.steps, args.warmup, args.stage_steps,
-                       with_cpu=not args.no_cpu_baseline, with_dense=not args.no_dense_equivalent)
+                       with_cpu=not args.no_cpu_baseline, with_dense=not args.no_dense_equivalent,
+                       with_variants=not args.no_extras and args.ann == "int8" and args.code_shift is None)
     result["peaks_measured"] = {"mfma_bf16_tflops": round(fa.probe_mfma_bf16(), 1),
                                 "mfma_bf16_tflops_random_operands": round(fa.probe_mfma_bf16(random_operands=True), 1),
                                 "stream_copy_gbs": round(fa.probe_copy(), 1)}
