@@ -14,6 +14,8 @@
 // All decisions are integer and order-independent (max / count), so the merge map is reproducible.
 #include <limits.h>
 
+#include <algorithm>
+
 #include "encode_dev.hpp"
 
 namespace fastar {
@@ -264,8 +266,8 @@ __global__ __launch_bounds__(WIN_THREADS) void tc_match_window_kernel(const int8
     const int tid = threadIdx.x, lane = lane_id(), wave = tid >> 6;
     const int col = lane & 31, g2 = lane >> 5;
     const int tg = wave % TG, ch = wave / TG;
-    const int tok = blockIdx.x * TOKS + tg * 32 + col;
     const int8_t *ch_code = code + (size_t)h * C * R;
+    const int n_tb = (n_new + TOKS - 1) / TOKS;   // blocks of TOKS tokens; this workgroup takes blockIdx.x, + gridDim.x, ...
     __shared__ __attribute__((aligned(16))) int8_t pcode[ENC ? TOKS * R : 16];
     i32x4 bfrag[KS];
     CodeMatrix<BF16, D, R> cm;
@@ -275,21 +277,25 @@ __global__ __launch_bounds__(WIN_THREADS) void tc_match_window_kernel(const int8
     i32x4 xq[EROUNDS][D / 64];
     if (ENC && !VERIFY)
         for (int k = blockIdx.x * WIN_THREADS + tid; k < ps_words; k += gridDim.x * WIN_THREADS) ps_all[(size_t)h * ps_words + k] = 0u;
-    if (enc_wave) {
-        cm.load(Rm, lane);
+    if (enc_wave) cm.load(Rm, lane);
+    // what a block of tokens needs before the window can be scanned for it: the rows to encode (ENC) or the probe
+    // codes (B operand); for the workgroup's first block these loads are in flight while the window is staged
+    auto load_block = [&](int tb) {
+        if (enc_wave) {
 #pragma unroll
-        for (int er = 0; er < EROUNDS; ++er) {
-            const int etok = blockIdx.x * TOKS + 16 * (wave + 8 * er) + (lane & 15);  // token this lane helps to encode
-            const char *row = (const char *)K_new + ((size_t)h * n_new + min(etok, n_new - 1)) * (size_t)D * (BF16 ? 2 : 4);
+            for (int er = 0; er < EROUNDS; ++er) {
+                const int etok = tb * TOKS + 16 * (wave + 8 * er) + (lane & 15);  // token this lane helps to encode
+                const char *row = (const char *)K_new + ((size_t)h * n_new + min(etok, n_new - 1)) * (size_t)D * (BF16 ? 2 : 4);
 #pragma unroll
-            for (int ks = 0; ks < D / 64; ++ks) xq[er][ks] = load_quantised<BF16>(row, ks, lane >> 4, qscale);
+                for (int ks = 0; ks < D / 64; ++ks) xq[er][ks] = load_quantised<BF16>(row, ks, lane >> 4, qscale);
+            }
+        } else if (!ENC) {
+            const int trow = min(tb * TOKS + tg * 32 + col, n_new - 1);
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) bfrag[ks] = *(const i32x4 *)(cp + ((size_t)h * n_new + trow) * R + ks * 32 + 16 * g2);
         }
-    } else if (!ENC) {
-        // probe codes of this wavefront's 32 tokens (B operand), in flight while the window is staged
-        const int trow = min(tok, n_new - 1);
-#pragma unroll
-        for (int ks = 0; ks < KS; ++ks) bfrag[ks] = *(const i32x4 *)(cp + ((size_t)h * n_new + trow) * R + ks * 32 + 16 * g2);
-    }
+    };
+    load_block(blockIdx.x);
     // The candidate list is a SET of slots and ties go to the smallest slot, so the window is staged in ascending
     // slot order without repeats: position order then is slot order, which is all the arg-max below needs.
     //   1. every thread reads its entries of the list (ids outside [0, L) do not count) and whether the list already
@@ -443,10 +449,17 @@ __global__ __launch_bounds__(WIN_THREADS) void tc_match_window_kernel(const int8
             }
         }
     }
+    __shared__ int vj[TOKS], vs[TOKS];
+    for (int tb = blockIdx.x; tb < n_tb; tb += gridDim.x) {
+    const int tok = tb * TOKS + tg * 32 + col;
+    if (tb != (int)blockIdx.x) {
+        __syncthreads();   // the previous block's probe codes and arg-maxima have been read
+        load_block(tb);
+    }
     if (enc_wave) {
 #pragma unroll
         for (int er = 0; er < EROUNDS; ++er) {
-            const int etok = blockIdx.x * TOKS + 16 * (wave + 8 * er) + (lane & 15);
+            const int etok = tb * TOKS + 16 * (wave + 8 * er) + (lane & 15);
 #pragma unroll
             for (int cb = 0; cb < R / 16; ++cb) {
                 const unsigned w = cm.code_word(xq[er], cb, shift);
@@ -533,7 +546,6 @@ __global__ __launch_bounds__(WIN_THREADS) void tc_match_window_kernel(const int8
     }
     if (g2 == 0) partbest[ch][tg][col] = mybest;
     __syncthreads();
-    __shared__ int vj[TOKS], vs[TOKS];
     if (ch == 0 && g2 == 0) {
         int j = -1, S = 0;
         if (tok < n_new) {
@@ -559,27 +571,31 @@ __global__ __launch_bounds__(WIN_THREADS) void tc_match_window_kernel(const int8
         }
     }
     if constexpr (VERIFY) {
-        __shared__ unsigned lhist[AGE_BINS];
         __syncthreads();
         constexpr int NPASS = TOKS * 16 / WIN_THREADS;   // tokens per 16-lane group
-        constexpr int PB = 2;                            // passes whose rows are loaded together (registers)
+        constexpr int PB = TOKS >= 256 ? 4 : 2;          // passes whose rows are loaded together (registers)
 #pragma unroll
         for (int p0 = 0; p0 < NPASS; p0 += PB) {
             VerifyRows<BF16, D> vr[PB];
 #pragma unroll
             for (int pass = 0; pass < PB; ++pass) {   // every row this group will need, in one round of loads
                 const int t = (p0 + pass) * (WIN_THREADS / 16) + (tid >> 4);
-                const int i = min(blockIdx.x * TOKS + t, n_new - 1);
+                const int i = min(tb * TOKS + t, n_new - 1);
                 vr[pass].load(va.K, K_new, pcode + t * R, R, C, n_new, metric, h, i, tid & 15, vj[t]);
             }
 #pragma unroll
             for (int pass = 0; pass < PB; ++pass) {
                 const int t = (p0 + pass) * (WIN_THREADS / 16) + (tid >> 4);
-                const int i = blockIdx.x * TOKS + t;
+                const int i = tb * TOKS + t;
                 if (i < n_new)   // whole 16-lane groups
                     vr[pass].decide(C, n_new, qscale, metric, va.tau2_q16, win, grp, va.merged, h, i, tid & 15, vj[t], vs[t]);
             }
         }
+    }
+    }   // blocks of tokens
+    if constexpr (VERIFY) {
+        __shared__ unsigned lhist[AGE_BINS];
+        __syncthreads();
         age_histogram_slice(len, va.stamp, C, n_new, va.frame_id, ps_all + (size_t)h * ps_words, va.hist_word, va.fut_word,
                             lhist);
     }
@@ -1687,7 +1703,12 @@ extern "C" int tempcache_compress(const fastar_cache *cache, const fastar_codec 
         const size_t per_cu = (size_t)160 * 1024 / (win_lds + 9 * 1024);
         const bool wide = fused_encode && win_lds <= wide_window_lds_max(r) &&
                           (size_t)((n_new + 63) / 64) * (size_t)H > 2 * 256 * (per_cu > 0 ? per_cu : 1);
-        const dim3 grid(wide ? (n_new + 255) / 256 : (n_new + 63) / 64, H);
+        // With 256 tokens per workgroup a workgroup takes several blocks of tokens, one after the other, once it has
+        // staged the window: as many workgroups as the chip holds at once (the staging is then paid once per resident
+        // workgroup, and no round of workgroups waits for the one before it).
+        int gx = wide ? (n_new + 255) / 256 : (n_new + 63) / 64;
+        if (wide) gx = std::min(gx, std::max(1, (int)(256 * (per_cu > 0 ? per_cu : 1)) / H));
+        const dim3 grid(gx, H);
         const bool bf = dtype == FASTAR_BF16;
         const VerifyArgs va = {cache->K, tau2_q16, merged, cache->stamp, frame_id, PS_HIST, PS_FUT};
         int rc = FASTAR_OK;
