@@ -592,6 +592,7 @@ __global__ __launch_bounds__(WIN_THREADS) void tc_match_window_kernel(const int8
             }
         }
     }
+    if constexpr (TOKS < 256) break;   // one block per workgroup: the grid covers the tokens (and the compiler sees no loop)
     }   // blocks of tokens
     if constexpr (VERIFY) {
         __shared__ unsigned lhist[AGE_BINS];

@@ -38,5 +38,8 @@ def test_traffic_figure_is_read_from_the_committed_profile():
     t, src = bench.profiled_traffic("cfg2")
     assert t is not None and 50e6 < t < 400e6               # fetch + write of one self-attention launch at cfg2
     assert src == "profiles/cfg2_chunk_step_hbm_traffic.txt"
+    t5, src5 = bench.profiled_traffic("cfg5full")
+    assert t5 is not None and 5e9 < t5 < 14e9             # the world-model launch gathers 13.7 GB, most of it from HBM
+    assert src5 == "profiles/cfg5full_chunk_step_hbm_traffic.txt"
     # a workload without a committed counter summary reports no traffic rather than another workload's
     assert bench.profiled_traffic("cfg5") == (None, None)
