@@ -47,7 +47,9 @@ def parse():
     ap.add_argument("--stage-steps", type=int, default=4,
                     help="extra steps after the timed region, instrumented with an event after every stage")
     ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--warmup", type=int, default=6,
+                    help="untimed steps first; the first four or five launches after an idle queue run 5-25 %% slower "
+                         "than the steady state on this chip (clock and power settling)")
     ap.add_argument("--workload", default="cfg5full", choices=["cfg5full", "cfg2", "cfg5"])
     ap.add_argument("--no-extras", action="store_true",
                     help="headline workload only: skip the short cfg2 leg and the sweep ends of the default run")
@@ -55,6 +57,11 @@ def parse():
     ap.add_argument("--ws", choices=["persistent", "scratch"], default="persistent",
                     help="TempCache workspace: kept by the caller across calls (zero-filled once; one launch less per "
                          "frame) or scratch that may hold anything")
+    ap.add_argument("--streams", type=int, choices=[1, 2], default=1,
+                    help="2: the query codes and the cross-attention path run on a second stream beside the compress "
+                         "calls.  Measured: no gain at either layer (the window-match, scoring and attention kernels "
+                         "each fill the register files of the compute units they run on, so the second stream's "
+                         "kernels wait for them anyway; at the Wan-shaped layer the extra enqueue cost shows)")
     ap.add_argument("--cross", choices=["fused", "separate"], default="fused",
                     help="AnnCA as one launch (selection + attention) or as ann_select_cross followed by sparse_attn_fwd")
     ap.add_argument("--cand", choices=["as-is", "sorted"], default="as-is",
@@ -114,6 +121,8 @@ class ChunkPipeline:
         self.O = (e((H, self.n_q, d), dt), e((H, self.n_q), torch.float32))
         self.prev = None
         self.frame_id = 0
+        self.side = None       # second stream for the work that depends on Q and the prompt only (set by the caller)
+        self.ev_q = None
         # cross-attention: prompt K/V and their codes are fixed for the rollout
         self.pK, self.pV = prompt
         self.n_p = self.pK.shape[1]
@@ -147,6 +156,8 @@ class ChunkPipeline:
         """frames: list of (K, V) device tensors of the chunk; Q [H,n_q,d].  ev: optional event recorder."""
         fa = self.fa
         mark = ev if ev is not None else (lambda name: None)
+        if self.side is not None and self.Rb is None and self.fused_cross:
+            return self.step_two_streams(frames, Q, mark)
         mark("start")
         first_frame = self.frame_id
         for K, V in frames:
@@ -183,6 +194,42 @@ class ChunkPipeline:
             mark("select_cross")
             fa.sparse_attn_fwd(Q, self.pK, self.pV, None, self.plen, self.csel[0], self.csel[1], self.BQ, 1, self.scale,
                                out=self.Ox, want_lse=False)
+        mark("attn_cross")
+
+    def step_two_streams(self, frames, Q, mark):
+        """The same step with the query codes and the whole cross-attention path (they depend on Q and the prompt only) on a
+        second stream of the same priority, beside the compress calls: chains of dependent launches that leave most of
+        the chip idle.  The step ends when both streams have: the main stream waits for the second one."""
+        fa, t = self.fa, self.t
+        main, side = t.cuda.current_stream(), self.side
+        mark("start")
+        first_frame = self.frame_id
+        side.wait_stream(main)   # after the previous step's readers of the query codes and of the cross outputs
+        with t.cuda.stream(side):
+            fa.encode(Q, self.codec, out=self.qcode)
+            self.ev_q.record(side)
+            fa.ann_cross_attn_fwd(Q, self.qcode, self.pK, self.pV, self.pcode, self.BQ, self.n_sel_cross, self.scale,
+                                  out=(self.csel[0], self.csel[1], self.Ox[0]))
+        for K, V in frames:
+            self.compress(K, V)
+        mark("compress")
+        if self.kv8 is not None:
+            fa.kv_to_fp8(self.cache, self.kv8[0], self.kv8[1], stamp_lo=first_frame)
+        mark("quantize")
+        main.wait_event(self.ev_q)
+        mark("encode")
+        fa.ann_select_self(self.qcode, self.cache.code, self.cache.len, self.BQ, self.n_rep, self.BK, self.n_sel,
+                           ws=self.ws_s, out=self.sel)
+        mark("select_self")
+        if self.kv8 is not None:
+            fa.sparse_attn_fwd_fp8(Q, self.kv8[0], self.kv8[1], self.cache.cnt, self.cache.len, self.C, self.sel[0],
+                                   self.sel[1], self.BQ, self.BK, self.scale, out=self.O)
+        else:
+            fa.sparse_attn_fwd(Q, self.cache.K, self.cache.V, self.cache.cnt, self.cache.len, self.sel[0], self.sel[1],
+                               self.BQ, self.BK, self.scale, out=self.O)
+        mark("attn_self")
+        main.wait_stream(side)
+        mark("select_cross")
         mark("attn_cross")
 
     def dense_equivalent_ms(self, Q, reps=3):
@@ -539,7 +586,8 @@ def build_cfg5_full(args, torch, fa, np, to_dev, to_host, n_chunks, n_cpu_heads)
 def run_layer(args, workload, torch, fa, np, to_dev, to_host, steps, warmup, stage_steps, with_cpu, with_dense,
               with_variants=False):
     """Build one workload, time `steps` chunk steps, return its record."""
-    n_chunks = warmup + steps + stage_steps
+    stage_lead = 3 if stage_steps > 0 else 0   # plain steps between the host's synchronisation and the instrumented ones
+    n_chunks = warmup + steps + stage_lead + stage_steps
     n_cpu_heads = min(args.cpu_heads, 40)
     t_gen = time.perf_counter()
     if workload == "cfg5full":
@@ -549,6 +597,10 @@ def run_layer(args, workload, torch, fa, np, to_dev, to_host, steps, warmup, sta
     t_gen = time.perf_counter() - t_gen
     cfg, pipe, dev_chunks = B["cfg"], B["pipe"], B["dev_chunks"]
     pipe.sorted_cand = args.cand == "sorted"
+    n_streams = args.streams
+    if n_streams == 2:
+        pipe.side = torch.cuda.Stream()   # default priority
+        pipe.ev_q = torch.cuda.Event()
     fp8 = args.kv == "fp8"
     if fp8:   # the 8-bit copy of the cache as it stands, kept up to date by every step
         pipe.kv8 = fa.kv8_empty(cfg["H"], pipe.C, cfg["d"])
@@ -585,6 +637,9 @@ def run_layer(args, workload, torch, fa, np, to_dev, to_host, steps, warmup, sta
     # Stage breakdown: a separate pass over the next chunks of the same rollout, an event after every stage.
     stage_names = ["compress", "quantize", "encode", "select_self", "attn_self", "select_cross", "attn_cross"]
     events = []
+    side_saved, pipe.side = pipe.side, None   # the breakdown is taken with every stage on one stream, one after the other
+    for s in range(stage_lead):
+        pipe.step(*dev_chunks[warmup + steps + s])
     for s in range(stage_steps):
         evs = []
 
@@ -592,9 +647,10 @@ def run_layer(args, workload, torch, fa, np, to_dev, to_host, steps, warmup, sta
             e = torch.cuda.Event(enable_timing=True)
             e.record()
             evs.append(e)
-        pipe.step(*dev_chunks[warmup + steps + s], ev=mark)
+        pipe.step(*dev_chunks[warmup + steps + stage_lead + s], ev=mark)
         events.append(evs)
     torch.cuda.synchronize()
+    pipe.side = side_saved
     if args.calib_copy_mb > 0:
         src = torch.ones(args.calib_copy_mb << 20, dtype=torch.uint8, device="cuda")
         dst = torch.empty_like(src)
@@ -645,13 +701,16 @@ def run_layer(args, workload, torch, fa, np, to_dev, to_host, steps, warmup, sta
                    "representative": args.rep + " key",
                    "tempcache_workspace": args.ws,
                    "cross_attention": "one launch (ann_cross_attn_fwd)" if args.cross == "fused" else "ann_select_cross + sparse_attn_fwd",
+                   "streams": "2: query codes + cross-attention on a second stream beside the compress calls, joined before "
+                              "the step ends" if n_streams == 2 else "1",
                    "prefill_frames": B["n_prefill"], "cache_len_per_head_start": [min(len_prefill), max(len_prefill)],
                    "cache_len_per_head_end": [min(len_final), max(len_final)],
                    "last_timed_compress_stats_head0": {k: int(v) for k, v in zip(
                        ("len", "merged", "appended", "evicted", "dropped"), stats_timed[0][:5])},
                    "cache_bytes": pipe.cache.nbytes()},
         "stages_ms": {k: round(v, 4) for k, v in stage_ms.items()},
-        "stages_note": f"separate pass of {stage_steps} steps after the timed region, one event per stage",
+        "stages_note": f"separate pass of {stage_steps} steps after the timed region (and {stage_lead} plain steps, so that the "
+                       f"queue is back in its steady state), one event per stage, all stages on one stream",
         "stages_hbm": {"algorithmic_bytes": {k: int(v) for k, v in bytes_stage.items()}, "achieved_GBs": stage_gbs,
                        "frac_of_peak": {k: round(v / PEAK_HBM_GBS, 4) for k, v in stage_gbs.items()},
                        "peak_GBs": PEAK_HBM_GBS},

@@ -221,6 +221,7 @@ constexpr int WIN_THREADS = 512;
 template <bool BF16, int D>
 struct VerifyRows;
 constexpr int AGE_BINS = 1024;
+template <int UN>
 __device__ __forceinline__ void age_histogram_slice(const int32_t *__restrict__ len, const int32_t *__restrict__ stamp,
                                                     int C, int n_new, int frame_id, unsigned *__restrict__ ps,
                                                     int hist_word, int fut_word, unsigned *lhist);
@@ -267,7 +268,10 @@ __global__ __launch_bounds__(WIN_THREADS) void tc_match_window_kernel(const int8
     const int col = lane & 31, g2 = lane >> 5;
     const int tg = wave % TG, ch = wave / TG;
     const int8_t *ch_code = code + (size_t)h * C * R;
-    const int n_tb = (n_new + TOKS - 1) / TOKS;   // blocks of TOKS tokens; this workgroup takes blockIdx.x, + gridDim.x, ...
+    // Tokens of this workgroup: [t0, t1).  64 tokens: its block.  256: an equal share of the frame (whole groups of 32
+    // tokens), taken in blocks of 256 once the window is staged; the launcher sizes the grid so that no share is empty.
+    const int per = TOKS < 256 ? TOKS : ((((n_new + (int)gridDim.x - 1) / (int)gridDim.x) + 31) & ~31);
+    const int t0 = min((int)blockIdx.x * per, n_new), t1 = min(t0 + per, n_new);
     __shared__ __attribute__((aligned(16))) int8_t pcode[ENC ? TOKS * R : 16];
     i32x4 bfrag[KS];
     CodeMatrix<BF16, D, R> cm;
@@ -280,22 +284,22 @@ __global__ __launch_bounds__(WIN_THREADS) void tc_match_window_kernel(const int8
     if (enc_wave) cm.load(Rm, lane);
     // what a block of tokens needs before the window can be scanned for it: the rows to encode (ENC) or the probe
     // codes (B operand); for the workgroup's first block these loads are in flight while the window is staged
-    auto load_block = [&](int tb) {
+    auto load_block = [&](int base) {   // base: first token of the block
         if (enc_wave) {
 #pragma unroll
             for (int er = 0; er < EROUNDS; ++er) {
-                const int etok = tb * TOKS + 16 * (wave + 8 * er) + (lane & 15);  // token this lane helps to encode
+                const int etok = base + 16 * (wave + 8 * er) + (lane & 15);  // token this lane helps to encode
                 const char *row = (const char *)K_new + ((size_t)h * n_new + min(etok, n_new - 1)) * (size_t)D * (BF16 ? 2 : 4);
 #pragma unroll
                 for (int ks = 0; ks < D / 64; ++ks) xq[er][ks] = load_quantised<BF16>(row, ks, lane >> 4, qscale);
             }
         } else if (!ENC) {
-            const int trow = min(tb * TOKS + tg * 32 + col, n_new - 1);
+            const int trow = min(base + tg * 32 + col, n_new - 1);
 #pragma unroll
             for (int ks = 0; ks < KS; ++ks) bfrag[ks] = *(const i32x4 *)(cp + ((size_t)h * n_new + trow) * R + ks * 32 + 16 * g2);
         }
     };
-    load_block(blockIdx.x);
+    load_block(t0);
     // The candidate list is a SET of slots and ties go to the smallest slot, so the window is staged in ascending
     // slot order without repeats: position order then is slot order, which is all the arg-max below needs.
     //   1. every thread reads its entries of the list (ids outside [0, L) do not count) and whether the list already
@@ -450,21 +454,22 @@ __global__ __launch_bounds__(WIN_THREADS) void tc_match_window_kernel(const int8
         }
     }
     __shared__ int vj[TOKS], vs[TOKS];
-    for (int tb = blockIdx.x; tb < n_tb; tb += gridDim.x) {
-    const int tok = tb * TOKS + tg * 32 + col;
-    if (tb != (int)blockIdx.x) {
+    for (int base = t0; base < t1; base += TOKS) {
+    const int lim = min(base + TOKS, t1);   // this block's tokens: [base, lim)
+    const int tok = base + tg * 32 + col;
+    if (base != t0) {
         __syncthreads();   // the previous block's probe codes and arg-maxima have been read
-        load_block(tb);
+        load_block(base);
     }
     if (enc_wave) {
 #pragma unroll
         for (int er = 0; er < EROUNDS; ++er) {
-            const int etok = tb * TOKS + 16 * (wave + 8 * er) + (lane & 15);
+            const int etok = base + 16 * (wave + 8 * er) + (lane & 15);
 #pragma unroll
             for (int cb = 0; cb < R / 16; ++cb) {
                 const unsigned w = cm.code_word(xq[er], cb, shift);
                 *(unsigned *)(pcode + (16 * (wave + 8 * er) + (lane & 15)) * R + cb * 16 + 4 * (lane >> 4)) = w;
-                if (etok < n_new) *(unsigned *)(ck + ((size_t)h * n_new + etok) * R + cb * 16 + 4 * (lane >> 4)) = w;
+                if (etok < lim) *(unsigned *)(ck + ((size_t)h * n_new + etok) * R + cb * 16 + 4 * (lane >> 4)) = w;
             }
         }
     }
@@ -478,7 +483,78 @@ __global__ __launch_bounds__(WIN_THREADS) void tc_match_window_kernel(const int8
     // best only on a strictly higher score, so the earliest group wins among equals); which of the group's rows it was
     // is looked up once, after the loop, by recomputing that group's 16 scores for this lane's token.
     int bs = INT_MIN, bg = 0;
-    const int n_groups = n_stage / 32;
+    // a wavefront whose 32 tokens all lie beyond the block's end scans nothing (uniform over the wavefront)
+    const int n_groups = base + tg * 32 < lim ? n_stage / 32 : 0;
+    // squared distance: 2 * dot, the product is accumulated twice; inner product: the second product is with zero
+    i32x4 bfrag2[KS];
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) bfrag2[ks][e] = metric == 0 ? bfrag[ks][e] : 0;
+    if constexpr (TOKS >= 256) {
+        // Long scans (one wavefront, the whole window): two groups of 32 candidates per step in three rotating operand
+        // sets, so that the reads of step t + 2, the matrix instructions of step t + 1 and the maxima of step t are in
+        // flight together (a wavefront issues in order: without the rotation its matrix and vector phases alternate).
+        // Steps past the end repeat the last group, which changes nothing: only a strictly higher score replaces the best.
+        constexpr int UNR = 2;
+        struct ScanSet {
+            i32x4 a[UNR][KS];
+            i32x16 acc[UNR];
+        };
+        const int n_it = n_groups > ch * UNR ? (n_groups - ch * UNR + SPLIT * UNR - 1) / (SPLIT * UNR) : 0;
+        auto group_of = [&](int it, int u) { return min((ch + it * SPLIT) * UNR + u, n_groups - 1); };
+        auto rd = [&](ScanSet &s, int it) {
+#pragma unroll
+            for (int u = 0; u < UNR; ++u) {
+                const int gi = group_of(it, u);
+#pragma unroll
+                for (int ks = 0; ks < KS; ++ks) s.a[u][ks] = ccode[(2 * ks + g2) * n_pad + gi * 32 + col];
+#pragma unroll
+                for (int q4 = 0; q4 < 4; ++q4) {   // minus the penalty of the accumulator's rows
+                    const i32x4 np = *(const i32x4 *)(&cpen[gi * 32 + 8 * q4 + 4 * g2]);
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) s.acc[u][4 * q4 + e] = np[e];
+                }
+            }
+        };
+        auto mm = [&](ScanSet &s) {
+#pragma unroll
+            for (int u = 0; u < UNR; ++u) {
+#pragma unroll
+                for (int ks = 0; ks < KS; ++ks) s.acc[u] = mfma_i8_32x32x32(s.a[u][ks], bfrag[ks], s.acc[u]);
+#pragma unroll
+                for (int ks = 0; ks < KS; ++ks) s.acc[u] = mfma_i8_32x32x32(s.a[u][ks], bfrag2[ks], s.acc[u]);
+            }
+        };
+        auto red = [&](const ScanSet &s, int it) {
+#pragma unroll
+            for (int u = 0; u < UNR; ++u) {
+                int mx = s.acc[u][0];
+#pragma unroll
+                for (int v = 1; v < 16; ++v) mx = max(mx, s.acc[u][v]);
+                const bool better = mx > bs;
+                bs = better ? mx : bs;
+                bg = better ? group_of(it, u) : bg;
+            }
+        };
+        if (n_it > 0) {
+            ScanSet s0, s1, s2;
+            rd(s0, 0);
+            rd(s1, 1);
+            mm(s0);
+            for (int it = 0; it < n_it; it += 3) {
+                rd(s2, it + 2);
+                mm(s1);
+                red(s0, it);
+                rd(s0, it + 3);
+                mm(s2);
+                red(s1, it + 1);
+                rd(s1, it + 4);
+                mm(s0);
+                red(s2, it + 2);
+            }
+        }
+    } else {
     // Four groups of 32 candidates per step, their operand reads and matrix instructions issued together
     // (a group repeated at the ragged end changes nothing: only a strictly higher score replaces the best).
     constexpr int UNR = 4;
@@ -502,10 +578,8 @@ __global__ __launch_bounds__(WIN_THREADS) void tc_match_window_kernel(const int8
         for (int u = 0; u < UNR; ++u) {
 #pragma unroll
             for (int ks = 0; ks < KS; ++ks) acc[u] = mfma_i8_32x32x32(afrag[u][ks], bfrag[ks], acc[u]);
-            if (metric == 0) {  // 2 * dot: the product is accumulated twice
 #pragma unroll
-                for (int ks = 0; ks < KS; ++ks) acc[u] = mfma_i8_32x32x32(afrag[u][ks], bfrag[ks], acc[u]);
-            }
+            for (int ks = 0; ks < KS; ++ks) acc[u] = mfma_i8_32x32x32(afrag[u][ks], bfrag2[ks], acc[u]);
         }
 #pragma unroll
         for (int u = 0; u < UNR; ++u) {
@@ -516,6 +590,7 @@ __global__ __launch_bounds__(WIN_THREADS) void tc_match_window_kernel(const int8
             bs = better ? mx : bs;
             bg = better ? min(g0 + u, n_groups - 1) : bg;
         }
+    }
     }
     u64 mybest = 0;
     if (bs > MATCH_VALID) {   // some real candidate was seen: the earliest row of group bg that reaches the best score
@@ -548,7 +623,7 @@ __global__ __launch_bounds__(WIN_THREADS) void tc_match_window_kernel(const int8
     __syncthreads();
     if (ch == 0 && g2 == 0) {
         int j = -1, S = 0;
-        if (tok < n_new) {
+        if (tok < lim) {
 #pragma unroll
             for (int c = 1; c < SPLIT; ++c) {
                 const u64 other = partbest[c][tg][col];
@@ -573,21 +648,21 @@ __global__ __launch_bounds__(WIN_THREADS) void tc_match_window_kernel(const int8
     if constexpr (VERIFY) {
         __syncthreads();
         constexpr int NPASS = TOKS * 16 / WIN_THREADS;   // tokens per 16-lane group
-        constexpr int PB = TOKS >= 256 ? 4 : 2;          // passes whose rows are loaded together (registers)
+        constexpr int PB = TOKS >= 256 ? 8 : 2;          // passes whose rows are loaded together (registers)
 #pragma unroll
         for (int p0 = 0; p0 < NPASS; p0 += PB) {
             VerifyRows<BF16, D> vr[PB];
 #pragma unroll
             for (int pass = 0; pass < PB; ++pass) {   // every row this group will need, in one round of loads
                 const int t = (p0 + pass) * (WIN_THREADS / 16) + (tid >> 4);
-                const int i = min(tb * TOKS + t, n_new - 1);
+                const int i = min(base + t, n_new - 1);
                 vr[pass].load(va.K, K_new, pcode + t * R, R, C, n_new, metric, h, i, tid & 15, vj[t]);
             }
 #pragma unroll
             for (int pass = 0; pass < PB; ++pass) {
                 const int t = (p0 + pass) * (WIN_THREADS / 16) + (tid >> 4);
-                const int i = tb * TOKS + t;
-                if (i < n_new)   // whole 16-lane groups
+                const int i = base + t;
+                if (i < lim)   // whole 16-lane groups
                     vr[pass].decide(C, n_new, qscale, metric, va.tau2_q16, win, grp, va.merged, h, i, tid & 15, vj[t], vs[t]);
             }
         }
@@ -597,8 +672,8 @@ __global__ __launch_bounds__(WIN_THREADS) void tc_match_window_kernel(const int8
     if constexpr (VERIFY) {
         __shared__ unsigned lhist[AGE_BINS];
         __syncthreads();
-        age_histogram_slice(len, va.stamp, C, n_new, va.frame_id, ps_all + (size_t)h * ps_words, va.hist_word, va.fut_word,
-                            lhist);
+        age_histogram_slice<(TOKS >= 256 ? 20 : 4)>(len, va.stamp, C, n_new, va.frame_id, ps_all + (size_t)h * ps_words,
+                                                    va.hist_word, va.fut_word, lhist);
     }
 }
 static size_t match_window_lds(int n_cand, int r) { return (size_t)((n_cand + 31) & ~31) * (size_t)(r + 8); }
@@ -667,11 +742,14 @@ __global__ __launch_bounds__(256) void tc_prep_kernel(const u64 *__restrict__ be
 // Per head, a histogram of the live slots' ages (frame_id - stamp, 1024 bins, the last one collecting everything
 // older) for the eviction plan: the verify launch, a whole grid, reads the stamps, where the plan has few
 // workgroups per head.  Every workgroup of the launch adds its slice of the slots.  Called by whole workgroups.
+// UN: 16-byte loads per lane in flight before the first is used (a slice read in one round trip when it fits).
+template <int UN>
 __device__ __forceinline__ void age_histogram_slice(const int32_t *__restrict__ len, const int32_t *__restrict__ stamp,
                                                     int C, int n_new, int frame_id, unsigned *__restrict__ ps,
                                                     int hist_word, int fut_word, unsigned *lhist) {
     const int h = blockIdx.y;
     const int L = min(len[h], C);
+    if (hist_word < 0) return;   // uniform over the launch: the plan counts the ages itself
     if (L + n_new <= C) return;  // uniform over the head: no eviction can be needed
     for (int k = threadIdx.x; k < AGE_BINS; k += blockDim.x) lhist[k] = 0;
     __syncthreads();
@@ -682,7 +760,6 @@ __device__ __forceinline__ void age_histogram_slice(const int32_t *__restrict__ 
     const int32_t *st = stamp + (size_t)h * C;
     const bool vec = (((uintptr_t)st) & 15) == 0;
     bool future = false;
-    constexpr int UN = 4;
     // Neighbouring slots were mostly written by the same frame: when all of a wavefront's slots fall into one bin, one
     // lane adds their number (hundreds of additions to one LDS word would be served one after the other).
     for (int jb = j0; jb < j1; jb += (int)blockDim.x * 4 * UN) {   // uniform trip count
@@ -875,7 +952,7 @@ __global__ __launch_bounds__(256) void tc_verify_kernel(const void *__restrict__
     const int i = blockIdx.x * (blockDim.x / 16) + (threadIdx.x >> 4);
     if (i < n_new) verify_token<BF16, D>(K, K_new, cp, r, C, n_new, qscale, metric, tau2_q16, jstar, sbest, win, grp,
                                          merged, h, i, l16);  // whole 16-lane groups
-    age_histogram_slice(len, stamp, C, n_new, frame_id, plan_scratch + (size_t)h * scratch_words, hist_word, fut_word,
+    age_histogram_slice<4>(len, stamp, C, n_new, frame_id, plan_scratch + (size_t)h * scratch_words, hist_word, fut_word,
                         lhist);
 }
 
@@ -883,14 +960,14 @@ __global__ __launch_bounds__(256) void tc_verify_kernel(const void *__restrict__
 // Two halves, so that a caller with several tokens per lane group can issue all their loads first.  Whole 16-lane groups.
 template <bool BF16, int D>
 struct VerifyRows {
-    float a[RowPiece<BF16, D>::EPL], b[RowPiece<BF16, D>::EPL];
+    typename RowPiece<BF16, D>::Raw ra, rb;   // raw bits: half the registers of the float values while the loads are in flight
     unsigned cw;
     __device__ __forceinline__ void load(const void *__restrict__ K, const void *__restrict__ K_new, const int8_t *cprow,
                                          int r, int C, int n_new, int metric, int h, int i, int l16, int j) {
         typedef RowPiece<BF16, D> RP;
-        RP::load(K_new, (size_t)h * n_new + i, l16, a);
+        ra = RP::load_raw(K_new, (size_t)h * n_new + i, l16);
         cw = (metric == 0 && l16 < r / 4) ? ((const unsigned *)cprow)[l16] : 0u;
-        if (j >= 0) RP::load(K, (size_t)h * C + j, l16, b);
+        if (j >= 0) rb = RP::load_raw(K, (size_t)h * C + j, l16);
     }
     __device__ __forceinline__ void decide(int C, int n_new, float qscale, int metric, int tau2_q16, u64 *__restrict__ win,
                                            int32_t *__restrict__ grp, uint8_t *__restrict__ merged, int h, int i,
@@ -899,6 +976,9 @@ struct VerifyRows {
         const int nn = group16_sum(dot4_i8(cw, cw, 0));  // |probe code|^2 (r <= 64: at most 16 words)
         bool is_merged = false;
         if (j >= 0) {
+            float a[RP::EPL], b[RP::EPL];
+            RP::unpack(ra, a);
+            RP::unpack(rb, b);
             int dot = 0, na = 0, nb = 0;
 #pragma unroll
             for (int e = 0; e < RP::EPL; ++e) {
@@ -1054,7 +1134,7 @@ __global__ __launch_bounds__(PLAN_THREADS) void tc_plan_kernel(const int32_t *__
                                                                const u64 *__restrict__ win, int32_t *__restrict__ rank,
                                                                int32_t *__restrict__ victims, int32_t *__restrict__ hs,
                                                                int32_t *__restrict__ stats, unsigned *__restrict__ ps_all,
-                                                               int ws_persistent) {
+                                                               int ws_persistent, int self_hist) {
     extern __shared__ unsigned touched[];  // bitmap over this workgroup's slot range
     __shared__ unsigned lhist[PLAN_BINS];
     __shared__ unsigned wtot[PLAN_WAVES];
@@ -1137,8 +1217,10 @@ __global__ __launch_bounds__(PLAN_THREADS) void tc_plan_kernel(const int32_t *__
 #pragma unroll
             for (int k = 0; k < PLAN_PER_MAX; ++k) sreg[k] = j0 + k < j1 ? st[j0 + k] : 0;
         }
+        if (!self_hist) {
 #pragma unroll
-        for (int q = 0; q < 4; ++q) hreg[q] = ps[PS_HIST + 4 * tid + q];   // written by the previous kernel
+            for (int q = 0; q < 4; ++q) hreg[q] = ps[PS_HIST + 4 * tid + q];   // written by the previous kernel
+        }
     }
     n_unm = scan.sum(n_unm);
     int e = L + (int)n_unm - C;
@@ -1159,7 +1241,7 @@ __global__ __launch_bounds__(PLAN_THREADS) void tc_plan_kernel(const int32_t *__
         // second round of loads: for the merged tokens, the record of their slot's group and the slot's stamp
         u64 wrec[PLAN_TOK_MAX];
         int wst[PLAN_TOK_MAX];
-        if (tok_cached) {
+        if (tok_cached && !self_hist) {
 #pragma unroll
             for (int k = 0; k < PLAN_TOK_MAX; ++k) {
                 wrec[k] = tj[k] >= 0 ? win[cb + tj[k]] : 0ull;
@@ -1176,12 +1258,12 @@ __global__ __launch_bounds__(PLAN_THREADS) void tc_plan_kernel(const int32_t *__
         });
         __syncthreads();
         u64 elig = 0;  // bit k: slot j0 + k is live and untouched
-        if (cached) {
-#pragma unroll
-            for (int k = 0; k < PLAN_PER_MAX; ++k) {
-                const int j = j0 + k;
-                if (j < j1 && !((touched[(j - s0) >> 5] >> ((j - s0) & 31)) & 1u)) elig |= 1ull << k;
-            }
+        if (cached && j0 < j1) {   // the run's bits of the bitmap: 64 bits from bit j0 - s0 on, out of three words
+            const int o = j0 - s0, w0 = o >> 5, sh = o & 31;
+            u64 t = (u64)touched[w0] | ((u64)touched[w0 + 1] << 32);
+            if (sh) t = (t >> sh) | ((u64)touched[w0 + 2] << (64 - sh));
+            const int n = j1 - j0;
+            elig = ~t & (n >= 64 ? ~0ull : ((1ull << n) - 1ull));
         }
         // visit(f): f(slot, key) for the eligible slots of this thread's run, ascending; key: larger = older
         auto visit = [&](auto &&f) {
@@ -1222,8 +1304,37 @@ __global__ __launch_bounds__(PLAN_THREADS) void tc_plan_kernel(const int32_t *__
         // frame (each counted once, by the token that represents its group) and read the threshold off it.  Every
         // workgroup does this on the same data, so no meeting is needed.  It does not apply when a stamp lies in
         // the future or the threshold falls into the last bin (ages >= 1023 lumped together).
-        bool fast = ps[PS_FUT] == 0u;   // written by the previous kernel
+        // With self_hist the launch before left no histogram (a long cache: reading every stamp there as well costs more
+        // than one meeting here): every workgroup counts the ages of its eligible slots from the stamps it holds, a run of
+        // equal ages with one addition, the head's workgroups add their bins up in global memory and meet once.
+        bool fast = self_hist ? true : ps[PS_FUT] == 0u;   // written by the previous kernel
+        unsigned c4[4] = {0u, 0u, 0u, 0u};
         if (fast) {
+            if (self_hist) {
+                bool future = false;
+                unsigned run_bin = 0u, run_n = 0u;
+                visit([&](int, unsigned u) {
+                    const int sv = (int)(~u ^ 0x80000000u);   // the stamp behind the key
+                    future = future || sv > frame_id;
+                    const unsigned bin = min((unsigned)frame_id - (unsigned)sv, (unsigned)(PLAN_BINS - 1));
+                    if (bin != run_bin && run_n) {
+                        atomicAdd(&lhist[run_bin], run_n);
+                        run_n = 0u;
+                    }
+                    run_bin = bin;
+                    run_n += 1u;
+                });
+                if (run_n) atomicAdd(&lhist[run_bin], run_n);
+                __syncthreads();
+#pragma unroll
+                for (int q = 0; q < 4; ++q)
+                    if (lhist[4 * tid + q]) atomicAdd(&ps[PS_HIST + 4 * tid + q], lhist[4 * tid + q]);
+                if (__any(future) && lane == 0) atomicOr(&ps[PS_FUT], 1u);
+                head_barrier(&ps[PS_BAR + 3], NB, &ps[PS_ERR]);
+#pragma unroll
+                for (int q = 0; q < 4; ++q) c4[q] = ld_agent(&ps[PS_HIST + PLAN_BINS - 1 - (4 * tid + q)]);
+                fast = ld_agent(&ps[PS_FUT]) == 0u;   // uniform over the head
+            } else {
             if (tok_cached) {
 #pragma unroll
                 for (int k = 0; k < PLAN_TOK_MAX; ++k)
@@ -1240,9 +1351,11 @@ __global__ __launch_bounds__(PLAN_THREADS) void tc_plan_kernel(const int32_t *__
                 });
             }
             __syncthreads();
-            unsigned c4[4];
 #pragma unroll
             for (int q = 0; q < 4; ++q) c4[q] = lhist[PLAN_BINS - 1 - (4 * tid + q)];
+            }
+        }
+        if (fast) {
             unsigned bin, above;
             search(c4, (unsigned)e, cnt_el, bin, above);
             take_all = cnt_el <= (unsigned)e;
@@ -1665,6 +1778,14 @@ extern "C" int tempcache_compress(const fastar_cache *cache, const fastar_codec 
     if ((d != 64 && d != 128) || (r != 32 && r != 64)) return FASTAR_ERR_UNSUPPORTED;
     const int nb = plan_nb(H, C);
     if (plan_lds_bytes(C, nb) > 48 * 1024) return FASTAR_ERR_UNSUPPORTED;  // eviction bitmap of a slot range lives in LDS
+    // Who counts the live slots' ages for the eviction threshold.  Short caches: the verify step, whose whole grid reads
+    // the stamps while the plan's few workgroups would meet for it.  Long caches (a plan thread holds more than 16 stamps,
+    // and all of its run, in registers): the plan itself, from the stamps it reads anyway: a second sweep over every
+    // stamp costs more than one meeting of the head's workgroups.
+    const int plan_span = (((C + nb - 1) / nb) + 3) & ~3;
+    const int plan_per = (((plan_span + PLAN_THREADS - 1) / PLAN_THREADS) + 3) & ~3;
+    const bool long_runs = ((C + nb - 1) / nb + PLAN_THREADS - 1) / PLAN_THREADS > 16;   // the plan's instantiation with 64 stamps per thread
+    const bool self_hist = long_runs && plan_per <= 64;
     if (((uintptr_t)cache->K & 15) || ((uintptr_t)cache->V & 15) || ((uintptr_t)cache->code & 15) ||
         ((uintptr_t)K_new & 15) || ((uintptr_t)V_new & 15) || ((uintptr_t)P_new & 15) || ((uintptr_t)ws & 255))
         return FASTAR_ERR_INVALID_ARG;
@@ -1708,10 +1829,14 @@ extern "C" int tempcache_compress(const fastar_cache *cache, const fastar_codec 
         // staged the window: as many workgroups as the chip holds at once (the staging is then paid once per resident
         // workgroup, and no round of workgroups waits for the one before it).
         int gx = wide ? (n_new + 255) / 256 : (n_new + 63) / 64;
-        if (wide) gx = std::min(gx, std::max(1, (int)(256 * (per_cu > 0 ? per_cu : 1)) / H));
+        if (wide) {   // equal shares of whole groups of 32 tokens, none of them empty
+            gx = std::min(gx, std::max(1, (int)(256 * (per_cu > 0 ? per_cu : 1)) / H));
+            const int per = (((n_new + gx - 1) / gx) + 31) & ~31;
+            gx = (n_new + per - 1) / per;
+        }
         const dim3 grid(gx, H);
         const bool bf = dtype == FASTAR_BF16;
-        const VerifyArgs va = {cache->K, tau2_q16, merged, cache->stamp, frame_id, PS_HIST, PS_FUT};
+        const VerifyArgs va = {cache->K, tau2_q16, merged, cache->stamp, frame_id, self_hist ? -1 : PS_HIST, PS_FUT};
         int rc = FASTAR_OK;
 #define FASTAR_WIN(RR, ENC, BF, DD, VER, TT)                                                                              \
     rc = launch_match_window<RR, ENC, BF, DD, VER, TT>(grid, win_lds, s, cache->code, cache->len, C, cp, n_new, cand,      \
@@ -1766,16 +1891,15 @@ extern "C" int tempcache_compress(const fastar_cache *cache, const fastar_codec 
     } while (0)
     if (!fused_verify) {
         FASTAR_TC(tc_verify_kernel, cache->K, K_new, cp, r, C, n_new, codec->qscale, metric, tau2_q16, jstar, sbest, win,
-                  grp, merged, cache->len, cache->stamp, frame_id, plan_scratch, PS_HIST, PS_FUT, PS_STRIDE);
+                  grp, merged, cache->len, cache->stamp, frame_id, plan_scratch, self_hist ? -1 : PS_HIST, PS_FUT, PS_STRIDE);
         FASTAR_LAUNCH_CHECK();
     }
     {
-        const bool long_runs = ((C + nb - 1) / nb + PLAN_THREADS - 1) / PLAN_THREADS > 16;
         const bool long_frame = n_new > 8 * PLAN_THREADS;
 #define FASTAR_PLAN(PM, TM)                                                                                            \
     hipLaunchKernelGGL((tc_plan_kernel<PM, TM>), dim3(nb + 1, H), dim3(PLAN_THREADS), plan_lds_bytes(C, nb), s, cache->len, \
                        cache->stamp, C, n_new, frame_id, jstar, merged, win, rank, victims, hs, stats, plan_scratch,   \
-                       ws_persistent)
+                       ws_persistent, self_hist ? 1 : 0)
         if (long_runs && long_frame) FASTAR_PLAN(64, 16);
         else if (long_runs) FASTAR_PLAN(64, 8);
         else if (long_frame) FASTAR_PLAN(16, 16);
