@@ -119,6 +119,9 @@ class ChunkPipeline:
         self.qcode = e((H, self.n_q, r), torch.int8)
         self.sel = (e((H, self.n_qb, self.n_sel), torch.int32), e((H, self.n_qb), torch.int32))
         self.O = (e((H, self.n_q, d), dt), e((H, self.n_q), torch.float32))
+        # workspace of the self-attention call: with it, a launch that would end in a short last round is split (whole
+        # rounds of one-block workgroups, then equal shares of the blocks left over)
+        self.ws_a = e((fa.workspace_bytes(fa.OP_ATTN, H, self.n_q, C),), torch.uint8) if dt == torch.bfloat16 and d == 128 else None
         self.prev = None
         self.frame_id = 0
         self.side = None       # second stream for the work that depends on Q and the prompt only (set by the caller)
@@ -183,7 +186,7 @@ class ChunkPipeline:
                                    self.sel[1], self.BQ, self.BK, self.scale, out=self.O)
         else:
             fa.sparse_attn_fwd(Q, self.cache.K, self.cache.V, self.cache.cnt, self.cache.len, self.sel[0], self.sel[1],
-                               self.BQ, self.BK, self.scale, out=self.O)
+                               self.BQ, self.BK, self.scale, out=self.O, ws=self.ws_a)
         mark("attn_self")
         if self.fused_cross:   # selection and attention over it in one launch; the stage is booked under select_cross
             fa.ann_cross_attn_fwd(Q, self.qcode, self.pK, self.pV, self.pcode, self.BQ, self.n_sel_cross, self.scale,
@@ -226,7 +229,7 @@ class ChunkPipeline:
                                    self.sel[1], self.BQ, self.BK, self.scale, out=self.O)
         else:
             fa.sparse_attn_fwd(Q, self.cache.K, self.cache.V, self.cache.cnt, self.cache.len, self.sel[0], self.sel[1],
-                               self.BQ, self.BK, self.scale, out=self.O)
+                               self.BQ, self.BK, self.scale, out=self.O, ws=self.ws_a)
         mark("attn_self")
         main.wait_stream(side)
         mark("select_cross")
@@ -444,9 +447,14 @@ def cpu_baseline(cfg, pipe, oracle_cache, oracle_prev, oracle_fid, host_chunks, 
     return info
 
 
-def attn_kernel_name(n_items, H, C, d=128):
+def attn_kernel_name(n_items, H, C, d=128, n_tiles=None):
     """Which bf16 d = 128, BQ = 128, BK = 64 kernel sparse_attn_fwd launches for this many (head, query block) pairs
-    and this cache capacity (K and V of all heads within 256 MB: bias rows written in the matrix phase)."""
+    and this cache capacity (K and V of all heads within 256 MB: bias rows written in the matrix phase).  n_tiles: 64-key
+    tiles per query block when the call carries a workspace (then a launch with a short last round is split)."""
+    per_xcd = (n_items + 7) // 8
+    tail = per_xcd % 64
+    if n_tiles is not None and per_xcd > 64 and 0 < tail <= 24 and n_tiles * (1.2 - 0.0375 * tail) > 30.0:
+        return "attn_bf16_d128_sk_kernel + attn_combine_kernel"
     if n_items <= 512 or n_items % 512 == 0 or n_items % 512 >= 256:
         resident = H * C * d * 2 * 2 <= (256 << 20)
         return "attn_bf16_d128_pp_kernel<4, true, %s>" % ("true" if resident else "false")
@@ -715,7 +723,7 @@ def run_layer(args, workload, torch, fa, np, to_dev, to_host, steps, warmup, sta
                        "frac_of_peak": {k: round(v / PEAK_HBM_GBS, 4) for k, v in stage_gbs.items()},
                        "peak_GBs": PEAK_HBM_GBS},
         "effective_tflops": round(tflops, 2), "pct_mfma_peak": round(100 * tflops / peak_tf, 2),
-        "roofline": {"kernel": ("attn_fp8_d128_kernel" if fp8 else attn_kernel_name(cfg["H"] * pipe.n_qb, cfg["H"], C)) + " (block-sparse self-attention)",
+        "roofline": {"kernel": ("attn_fp8_d128_kernel" if fp8 else attn_kernel_name(cfg["H"] * pipe.n_qb, cfg["H"], C, n_tiles=(pipe.n_sel * pipe.BK + 63) // 64 if pipe.ws_a is not None else None)) + " (block-sparse self-attention)",
                      "bound": "hbm" if hbm_bound else "mfma",
                      "achieved": round(gbs, 1) if hbm_bound else round(tflops, 2),
                      "peak": PEAK_HBM_GBS if hbm_bound else peak_tf, "unit": "GB/s" if hbm_bound else "TFLOP/s",

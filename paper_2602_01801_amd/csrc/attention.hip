@@ -377,7 +377,7 @@ int launch_attn_bf16_d128_pp(const void *Q, int n_q, const void *K, const void *
 size_t attn_sk_ws_bytes();
 int launch_attn_bf16_d128_sk(const void *Q, int n_q, const void *K, const void *V, const int32_t *cnt, const int32_t *len,
                              int H, int C, const int32_t *sel, const int32_t *nsel, int bk_shift, int n_sel,
-                             float scale_log2, void *O, float *lse, void *ws, hipStream_t s);
+                             float scale_log2, void *O, float *lse, void *ws, int full_per, hipStream_t s);
 
 }  // namespace fastar
 
@@ -435,10 +435,19 @@ static int sparse_attn_impl(const void *Q, int n_q, const void *K, const void *V
         // work comes in rounds of 512 query blocks: when the last round would be less than half full, the kernel with
         // one block per workgroup (two workgroups per CU, started as slots free up) finishes earlier.
         const int n_items = n_qb * H;
-        // With a workspace, and more query blocks than fit the chip at once, the persistent kernel: equal shares of
-        // the tiles for every resident workgroup, whatever the block count (long enough shares to pay for the fragments).
-        if (ws && d == 128 && BQ == 128 && n_items > 512 && (long long)n_items * ((n_sel * BK + 63) / 64) >= 512ll * 128)
-            return launch_attn_bf16_d128_sk(Q, n_q, K, V, cnt, len, H, C, sel, nsel, bk_shift, n_sel, scale_log2, O, lse, ws, s);
+        // With a workspace, and more query blocks than the chip holds at once in a number that leaves a short last
+        // round (an XCD holds 64 workgroups of the one-block kernel; a round that only a few of them take part in lasts
+        // half as long as a full one, with most of the chip idle): the one-block kernel on whole rounds, then the query
+        // blocks left over cut into equal shares of their tiles for all resident workgroups (long enough shares to pay for
+        // the fragments and their combination).
+        const int per_xcd = (n_items + 7) / 8, tail_per = per_xcd % 64;
+        const int n_tiles = (int)(((long long)n_sel * BK + 63) / 64);
+        // What the split saves: a last round of n_tiles tiles at a lone workgroup's pace (about 1.2 us per tile) against
+        // tail_per / 64 of a round at the pace of a full chip (2.4 us per tile) plus about 30 us of fragments and launches.
+        if (ws && d == 128 && BQ == 128 && per_xcd > 64 && tail_per > 0 && tail_per <= 24 &&
+            (float)n_tiles * (1.2f - 0.0375f * (float)tail_per) > 30.0f)
+            return launch_attn_bf16_d128_sk(Q, n_q, K, V, cnt, len, H, C, sel, nsel, bk_shift, n_sel, scale_log2, O, lse, ws,
+                                            per_xcd - tail_per, s);
         if (d == 128 && BQ == 128 && (n_items <= 512 || n_items % 512 == 0 || n_items % 512 >= 256))
             return launch_attn_bf16_d128_pp(Q, n_q, K, V, cnt, len, H, C, sel, nsel, bk_shift, n_sel, scale_log2, O, lse, s);
         if (d == 128)  // tuned path: direct-to-LDS tiles, LDS transpose loads

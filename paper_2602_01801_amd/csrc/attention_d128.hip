@@ -431,49 +431,68 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_bf16_d128_kernel(
                     item / n_qb, item % n_qb, 0, INT_MAX, nullptr);
 }
 
-// The persistent form (BQ = 128).  Every query block stands for NT tiles (its list may be shorter), the blocks in
-// (head, block) order make one sequence of n_qb * H * NT tiles, and each of the P resident workgroups takes an equal,
+// The persistent form (BQ = 128) for the query blocks that whole rounds of one-block workgroups leave over.  The
+// (head, block) pairs are dealt to the 8 XCDs in contiguous ranges of `per`, as in the plain kernel; the first `full_per`
+// pairs of every range (whole rounds of the workgroups an XCD holds at once) are taken by one workgroup each, and the
+// other per - full_per of every range (all of them when full_per is 0) as follows.  Every such query block stands for NT tiles (its list may be shorter), the
+// blocks, range after range, make one sequence of tiles, and each of the P resident workgroups takes an equal,
 // contiguous share of it: whole blocks are finished in place, a block cut by a share's boundary leaves one fragment per
 // share that touches it (slot 0 of a workgroup: a block begun by an earlier workgroup; slot 1: a block it begins but
-// does not finish), and attn_combine_kernel puts the fragments together.  However the block count compares with the
-// number of resident workgroups, every workgroup does the same amount of work.
+// does not finish), and attn_combine_kernel puts the fragments together.  However the number of blocks left over
+// compares with the number of resident workgroups, every workgroup does the same amount of work.
+struct TailMap {
+    int per, full_per, total;   // pairs per XCD range, of them done by the plain launch, pairs in all
+    __device__ __forceinline__ int tail_per() const { return per - full_per; }
+    __device__ __forceinline__ long long tiles(int NT) const { return (long long)8 * tail_per() * NT; }
+    // position in the sequence -> (head, block) pair; pairs >= total do not exist (the last range may be short)
+    __device__ __forceinline__ int item(int vi) const { return (vi / tail_per()) * per + full_per + vi % tail_per(); }
+};
 __global__ __launch_bounds__(256, 2) void attn_bf16_d128_sk_kernel(
     const unsigned short *__restrict__ Q, const unsigned short *__restrict__ K, const unsigned short *__restrict__ V,
     const int32_t *__restrict__ cnt, const int32_t *__restrict__ len, const int32_t *__restrict__ sel,
-    const int32_t *__restrict__ nsel, int n_q, int C, int bk_shift, int n_sel, int n_qb, int H, int NT, float scale_log2,
-    float inv_scale_log2, unsigned short *__restrict__ O, float *__restrict__ lse, float *__restrict__ ws) {
+    const int32_t *__restrict__ nsel, int n_q, int C, int bk_shift, int n_sel, int n_qb, TailMap tm, int n_plain, int NT,
+    float scale_log2, float inv_scale_log2, unsigned short *__restrict__ O, float *__restrict__ lse, float *__restrict__ ws) {
     extern __shared__ __attribute__((aligned(1024))) unsigned char lds[];
-    const int P = gridDim.x;                                       // a multiple of 8
-    const int i = (blockIdx.x & 7) * (P >> 3) + (blockIdx.x >> 3);   // neighbouring shares on one XCD
-    const long long W = (long long)n_qb * H * NT;
-    long long v = i * W / P;
-    const long long v_end = (i + 1) * W / P;
+    // The first 8 * full_per workgroups of the launch are the plain kernel's (range wg & 7, pair wg >> 3 of it, the whole
+    // block): one launch, so that the shares start as soon as workgroups of the last whole round finish.
+    const int P = (int)gridDim.x - n_plain;                        // a multiple of 8
+    const int wg = (int)blockIdx.x - n_plain;
+    const int i = (wg & 7) * (P >> 3) + (wg >> 3);                 // neighbouring shares on one XCD: those of its own range
+    const int direct = wg < 0 ? ((int)blockIdx.x & 7) * tm.per + ((int)blockIdx.x >> 3) : -1;
+    const long long W = tm.tiles(NT);
+    long long v = wg < 0 ? 0 : i * W / P;
+    const long long v_end = wg < 0 ? NT : (i + 1) * W / P;
     while (v < v_end) {
-        const int item = (int)(v / NT);
-        const int t_begin = (int)(v - (long long)item * NT);
-        const int t_end = (int)min((long long)NT, v_end - (long long)item * NT);
-        float *part = nullptr;
-        if (t_begin > 0 || t_end < NT) part = ws + ((size_t)i * 2 + (t_begin > 0 ? 0 : 1)) * PART_FLOATS;
-        attend_item<4>(Q, K, V, cnt, len, sel, nsel, n_q, C, bk_shift, n_sel, n_qb, scale_log2, inv_scale_log2, O, lse, lds,
-                       item / n_qb, item % n_qb, t_begin, t_end, part);
-        v = (long long)item * NT + t_end;
+        const int vi = (int)(v / NT);
+        const int t_begin = (int)(v - (long long)vi * NT);
+        const int t_end = (int)min((long long)NT, v_end - (long long)vi * NT);
+        const int item = direct >= 0 ? direct : tm.item(vi);
+        if (item < tm.total) {   // uniform over the workgroup
+            float *part = nullptr;
+            if (t_begin > 0 || t_end < NT) part = ws + ((size_t)i * 2 + (t_begin > 0 ? 0 : 1)) * PART_FLOATS;
+            attend_item<4>(Q, K, V, cnt, len, sel, nsel, n_q, C, bk_shift, n_sel, n_qb, scale_log2, inv_scale_log2, O, lse,
+                           lds, item / n_qb, item % n_qb, t_begin, t_end, part);
+        }
+        v = (long long)vi * NT + t_end;
     }
 }
 
 // Fragments of the query blocks that attn_bf16_d128_sk_kernel cut: workgroup i of this launch puts together the block
 // that share i begins but does not finish (its slot 1, then slot 0 of the following shares while they lie inside the
 // block).  Same wavefront / lane layout as the fragments; any reference maximum is as good as the true one.
-__global__ __launch_bounds__(256) void attn_combine_kernel(const float *__restrict__ ws, int P, int n_q, int n_qb, int H,
+__global__ __launch_bounds__(256) void attn_combine_kernel(const float *__restrict__ ws, int P, int n_q, int n_qb, TailMap tm,
                                                            int NT, float scale_log2, unsigned short *__restrict__ O,
                                                            float *__restrict__ lse) {
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
     const int i = blockIdx.x;
-    const long long W = (long long)n_qb * H * NT;
+    const long long W = tm.tiles(NT);
     const long long start = i * W / P, end = (i + 1) * W / P;
     if (end >= W || end % NT == 0) return;          // share i ends with a whole block
-    const int item = (int)(end / NT);
-    if ((long long)item * NT < start) return;       // the block began in an earlier share: that one combines it
-    const long long item_end = (long long)(item + 1) * NT;
+    const int vi = (int)(end / NT);
+    if ((long long)vi * NT < start) return;         // the block began in an earlier share: that one combines it
+    const int item = tm.item(vi);
+    if (item >= tm.total) return;                   // no such block: nothing was written for it
+    const long long item_end = (long long)(vi + 1) * NT;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int col = lane & 31, g = lane >> 5;
     const int h = item / n_qb, b = item % n_qb;
@@ -569,19 +588,24 @@ int launch_attn_bf16_d128(const void *Q, int n_q, const void *K, const void *V, 
 // ws: SK_WORKGROUPS * 2 fragments (attn_sk_ws_bytes()).
 size_t attn_sk_ws_bytes() { return (size_t)d128::SK_WORKGROUPS * 2 * d128::PART_FLOATS * sizeof(float); }
 
+// full_per: (head, block) pairs per XCD range that the plain kernel takes first, in whole rounds of the 64 workgroups an
+// XCD holds (0: the persistent kernel takes everything); the rest of every range goes to the persistent kernel.
 int launch_attn_bf16_d128_sk(const void *Q, int n_q, const void *K, const void *V, const int32_t *cnt, const int32_t *len,
                              int H, int C, const int32_t *sel, const int32_t *nsel, int bk_shift, int n_sel,
-                             float scale_log2, void *O, float *lse, void *ws, hipStream_t s) {
+                             float scale_log2, void *O, float *lse, void *ws, int full_per, hipStream_t s) {
     using namespace d128;
     if (const int rc = attn_d128_setup(); rc != FASTAR_OK) return rc;
     const int n_qb = (n_q + 127) / 128;
     const int NT = (int)((((long long)n_sel << bk_shift) + TK - 1) / TK);
-    hipLaunchKernelGGL(attn_bf16_d128_sk_kernel, dim3(SK_WORKGROUPS), dim3(256), LDS_BYTES, s, (const unsigned short *)Q,
+    const TailMap tm = {(n_qb * H + 7) / 8, full_per, n_qb * H};
+    if (full_per < 0 || full_per >= tm.per) return FASTAR_ERR_INVALID_ARG;
+    const int n_plain = 8 * full_per;
+    hipLaunchKernelGGL(attn_bf16_d128_sk_kernel, dim3(n_plain + SK_WORKGROUPS), dim3(256), LDS_BYTES, s, (const unsigned short *)Q,
                        (const unsigned short *)K, (const unsigned short *)V, cnt, len, sel, nsel, n_q, C, bk_shift, n_sel,
-                       n_qb, H, NT, scale_log2, 1.0f / scale_log2, (unsigned short *)O, lse, (float *)ws);
+                       n_qb, tm, n_plain, NT, scale_log2, 1.0f / scale_log2, (unsigned short *)O, lse, (float *)ws);
     if (hipGetLastError() != hipSuccess) return FASTAR_ERR_HIP;
     hipLaunchKernelGGL(attn_combine_kernel, dim3(SK_WORKGROUPS), dim3(256), 4 * 32 * (D + 8) * 2, s, (const float *)ws,
-                       SK_WORKGROUPS, n_q, n_qb, H, NT, scale_log2, (unsigned short *)O, lse);
+                       SK_WORKGROUPS, n_q, n_qb, tm, NT, scale_log2, (unsigned short *)O, lse);
     if (hipGetLastError() != hipSuccess) return FASTAR_ERR_HIP;
     return FASTAR_OK;
 }

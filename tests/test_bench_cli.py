@@ -23,6 +23,8 @@ def test_roofline_kernel_name_follows_the_dispatch_rule():
     assert bench.attn_kernel_name(37 * 12, 12, 196608) == "attn_bf16_d128_pp_kernel<4, true, false>"
     # cfg5: 29 x 40 = 1160 = 2 rounds of 512 + 136 (< 256): one block per workgroup
     assert bench.attn_kernel_name(29 * 40, 40, 230400) == "attn_bf16_d128_kernel<4>"
+    assert bench.attn_kernel_name(29 * 40, 40, 230400, n_tiles=360).startswith("attn_bf16_d128_sk_kernel")   # with a workspace: split launch
+    assert bench.attn_kernel_name(37 * 12, 12, 37440, n_tiles=52) == "attn_bf16_d128_pp_kernel<4, true, true>"
     assert bench.attn_kernel_name(1024, 40, 230400).startswith("attn_bf16_d128_pp_kernel<4, true, false")
     assert bench.attn_kernel_name(1024 + 256, 8, 1000).startswith("attn_bf16_d128_pp_kernel")
     # the same rule as the launcher's source states it

@@ -144,12 +144,15 @@ def test_dense_limit_uncompressed_wan_cache():
     select_and_attend(c, fs, codec, dcodec, gpu, ref, heads, n_kb)
 
 
-def test_world_model_attention_on_a_full_cache():
-    # cfg5 at the size bench.py --workload cfg5 reaches once its cache is full: 40 heads x 230400 live slots (64 frames
-    # of 3600), 3600 queries, 360 of 3600 key blocks per query block; 29 x 40 = 1160 query blocks, so the kernel with
-    # one block per workgroup is the one launched, on K and V far beyond the memory-side cache.  The cache is synthetic
-    # (seeded normal keys and values, multiplicities 1..6, two heads not quite full); the oracle recomputes three heads
-    # and, of each, the first, a middle and the ragged last query block.
+@pytest.mark.parametrize("with_ws", [True, False])
+def test_world_model_attention_on_a_full_cache(with_ws):
+    # cfg5 at the size bench.py's default run holds: 40 heads x 230400 live slots (64 frames of 3600), 3600 queries, 360 of
+    # 3600 key blocks per query block; 29 x 40 = 1160 query blocks on K and V far beyond the memory-side cache.  Without
+    # a workspace the kernel with one block per workgroup is launched; with one (as bench.py calls it) the launch is
+    # split: 128 of the 145 (head, block) pairs of every XCD range by one workgroup each, the other 17 in equal shares
+    # of their tiles.  The cache is synthetic (seeded normal keys and values, multiplicities 1..6, two heads not quite
+    # full); the oracle recomputes, of three heads, the first, a middle and the ragged last query block, and three blocks
+    # of head 4, whose blocks 12..28 are pairs 128..144: the first range's left-over ones.
     c = CONFIGS["cfg5"]
     H, d, BQ, BK = c["H"], c["d"], c["BQ"], c["BK"]
     n_q, C, n_sel = c["T"], 64 * c["T"], 360
@@ -168,12 +171,13 @@ def test_world_model_attention_on_a_full_cache():
         for b in range(n_qb):
             sel[h, b] = np.sort(rng.choice(n_kb, n_sel, replace=False))   # the last blocks of heads 17, 39: partly / wholly dead
     nsel = np.full((H, n_qb), n_sel, np.int32)
-    O, lse = fa.sparse_attn_fwd(Q, K, V, cnt, to_dev(lens), to_dev(sel), to_dev(nsel), BQ, BK, d ** -0.5)
+    ws = torch.empty(fa.workspace_bytes(fa.OP_ATTN, H, n_q, C), dtype=torch.uint8, device="cuda") if with_ws else None
+    O, lse = fa.sparse_attn_fwd(Q, K, V, cnt, to_dev(lens), to_dev(sel), to_dev(nsel), BQ, BK, d ** -0.5, ws=ws)
     torch.cuda.synchronize()
     assert bool(torch.isfinite(O.float()).all())
-    for h in (0, 17, 39):
+    for h, blocks in ((0, (0, 13, n_qb - 1)), (17, (0, 13, n_qb - 1)), (39, (0, 13, n_qb - 1)), (4, (12, 20, n_qb - 1))):
         Kh, Vh, ch = to_host(K[h:h + 1]), to_host(V[h:h + 1]), to_host(cnt[h:h + 1])
-        for b in (0, 13, n_qb - 1):
+        for b in blocks:
             q0, q1 = b * BQ, min((b + 1) * BQ, n_q)
             O_r, lse_r = oracle.sparse_attn_fwd(to_host(Q[h:h + 1, q0:q1]), Kh, Vh, ch, lens[h:h + 1],
                                                 np.ascontiguousarray(sel[h:h + 1, b:b + 1]), nsel[h:h + 1, b:b + 1],

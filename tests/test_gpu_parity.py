@@ -1160,8 +1160,9 @@ def test_bad_arguments_are_rejected_on_the_host():
     (33, 2048, 64 * 256, 128, 0, False),     # 528 blocks, no multiplicities
 ])
 def test_persistent_attention_matches_the_oracle_and_the_plain_launch(H, n_q, C, n_sel, lens_cut, with_cnt):
-    # sparse_attn_fwd_ws takes the persistent kernel here (more than 512 query blocks, long shares): blocks cut by share
-    # boundaries are combined from fragments.  Oracle on sampled (head, query block) pairs incl. cut and whole ones.
+    # sparse_attn_fwd_ws splits the launch here (more query blocks than the chip holds at once, a short last round): the
+    # query blocks left over by the whole rounds go to the persistent kernel in equal shares of their tiles, blocks cut by
+    # share boundaries are combined from fragments.  Oracle on sampled (head, query block) pairs incl. cut and whole ones.
     rng = np.random.default_rng(H + n_q)
     g = torch.Generator(device="cuda").manual_seed(H * 1000 + n_sel)
     Q = torch.randn(H, n_q, 128, device="cuda", generator=g).bfloat16()
@@ -1190,9 +1191,15 @@ def test_persistent_attention_matches_the_oracle_and_the_plain_launch(H, n_q, C,
     assert np.array_equal(fin, np.isfinite(lw)) and np.abs(lw[fin] - lp[fin]).max() <= 1e-2   # sums of rounded P against different references
     # the oracle on a sample of blocks: the first ones, the special ones, and blocks around share boundaries
     NT = n_sel
-    W = n_qb * H * NT
-    cut_items = sorted({(i * W // 512) // NT for i in range(1, 512) if (i * W // 512) % NT})
-    sample = sorted(set([0, 1, n_qb, n_qb - 1, H * n_qb - 1] + cut_items[:3] + cut_items[-2:] + [cut_items[len(cut_items) // 2]]))
+    total = n_qb * H
+    per = -(-total // 8)
+    tail_per = per % 64
+    assert per > 64 and 0 < tail_per <= 24, "the shape is meant to take the split launch"
+    W = 8 * tail_per * NT
+    to_item = lambda vi: (vi // tail_per) * per + (per - tail_per) + vi % tail_per   # position in the left-over sequence -> pair
+    cut_items = sorted({to_item((i * W // 512) // NT) for i in range(1, 512) if (i * W // 512) % NT} - set(range(total, 8 * per)))
+    whole_tail = sorted({to_item(vi) for vi in range(8 * tail_per)} - set(cut_items) - set(range(total, 8 * per)))
+    sample = sorted(set([0, 1, n_qb, n_qb - 1, total - 1] + cut_items[:3] + cut_items[-2:] + [cut_items[len(cut_items) // 2]] + whole_tail[:1]))
     Kh, Vh, Qh = to_host(K), to_host(V), to_host(Q)
     cnt_h = to_host(cnt) if with_cnt else None
     for item in sample:
