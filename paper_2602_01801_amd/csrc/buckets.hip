@@ -9,6 +9,8 @@
 //                          that the scoring reads them coalesced
 //   bucket_score_kernel    shared buckets of every (query block, key block) pair: AND + bit count
 //   bucket_topk_kernel     candidates (at least one shared bucket, or forced) counted, then the exact top-k of select.hip
+#include <algorithm>
+
 #include "common.hpp"
 #include "topk_dev.hpp"
 
@@ -161,7 +163,7 @@ __global__ __launch_bounds__(256) void bucket_topk_kernel(const int32_t *__restr
                                                           const int32_t *__restrict__ len, int C, int BK, int n_qb,
                                                           int n_sel, int n_sink, int n_local, int32_t *__restrict__ sel,
                                                           int32_t *__restrict__ nsel) {
-    __shared__ unsigned keys[TOPK_LDS_CAP];
+    extern __shared__ unsigned keys[];   // min(n_kb_cap, TOPK_LDS_CAP) words: staging of the row's keys
     const int b = blockIdx.x, h = blockIdx.y;
     const int n = min((min(len[h], C) + BK - 1) / BK, n_kb_cap);
     const int32_t *row = score + ((size_t)h * n_qb + b) * n_kb_cap;
@@ -240,8 +242,8 @@ extern "C" int ann_select_buckets(const int32_t *qbucket, int n_q, const int32_t
     hipLaunchKernelGGL(bucket_score_kernel, dim3((n_kb_cap + 255) / 256, H), dim3(256), own_bytes, s, qmask, kmask, W,
                        n_qb, n_kb_cap, score);
     FASTAR_LAUNCH_CHECK();
-    hipLaunchKernelGGL(bucket_topk_kernel, dim3(n_qb, H), dim3(256), 0, s, score, n_kb_cap, len, C, BK, n_qb, n_sel,
-                       n_sink, n_local, sel, nsel);
+    hipLaunchKernelGGL(bucket_topk_kernel, dim3(n_qb, H), dim3(256), (size_t)std::min(n_kb_cap, TOPK_LDS_CAP) * 4, s, score,
+                       n_kb_cap, len, C, BK, n_qb, n_sel, n_sink, n_local, sel, nsel);
     FASTAR_LAUNCH_CHECK();
     return FASTAR_OK;
 }

@@ -574,7 +574,9 @@ __global__ __launch_bounds__(256) void topk_kernel(const int32_t *__restrict__ s
                                                    const int32_t *__restrict__ len, int len_cap, int BK, int n_fixed,
                                                    int n_qb, int n_sel, int32_t *__restrict__ sel,
                                                    int32_t *__restrict__ nsel, int n_sink, int n_local, int cand_min) {
-    __shared__ unsigned keys[TOPK_LDS_CAP];
+    // staging of the row's keys: min(row_stride, TOPK_LDS_CAP) words of dynamic LDS (a static array of the full size
+    // would hold the kernel to four workgroups per compute unit whatever the row length)
+    extern __shared__ unsigned keys[];
     const int b = blockIdx.x, h = blockIdx.y;
     int n = n_fixed;
     if (len) n = (min(len[h], len_cap) + BK - 1) / BK;
@@ -826,8 +828,8 @@ static int select_self_impl(const int8_t *qcode, int n_q, const int8_t *kcode, c
     else FASTAR_SELF(64, 8);
 #undef FASTAR_SELF
     FASTAR_LAUNCH_CHECK();
-    hipLaunchKernelGGL(topk_kernel, dim3(n_qb, H), dim3(256), 0, s, score, n_kb_cap, len, C, BK, 0, n_qb, n_sel, sel,
-                       nsel, n_sink, n_local, INT_MIN);
+    hipLaunchKernelGGL(topk_kernel, dim3(n_qb, H), dim3(256), (size_t)std::min(n_kb_cap, TOPK_LDS_CAP) * 4, s, score, n_kb_cap,
+                       len, C, BK, 0, n_qb, n_sel, sel, nsel, n_sink, n_local, INT_MIN);
     FASTAR_LAUNCH_CHECK();
     return FASTAR_OK;
 }
@@ -982,8 +984,8 @@ static int select_lsh_impl(const uint32_t *qbits, int n_q, const uint32_t *kbits
 #undef FASTAR_LSH
     FASTAR_LAUNCH_CHECK();
     // with tables only key blocks with a collision are candidates
-    hipLaunchKernelGGL(topk_kernel, dim3(n_qb, H), dim3(256), 0, s, score, n_kb_cap, len, C, BK, 0, n_qb, n_sel, sel,
-                       nsel, n_sink, n_local, band ? 1 : INT_MIN);
+    hipLaunchKernelGGL(topk_kernel, dim3(n_qb, H), dim3(256), (size_t)std::min(n_kb_cap, TOPK_LDS_CAP) * 4, s, score, n_kb_cap,
+                       len, C, BK, 0, n_qb, n_sel, sel, nsel, n_sink, n_local, band ? 1 : INT_MIN);
     FASTAR_LAUNCH_CHECK();
     return FASTAR_OK;
 }
