@@ -351,10 +351,12 @@ int sparse_attn_fwd(const void *Q, int n_q, const void *K, const void *V, const 
 
 /*
  * sparse_attn_fwd with a workspace: same arguments, same result (to the tolerance of the attention itself: a block
- * that two workgroups share is put together from two partial sums).  With more query blocks than the chip holds at
- * once (bf16, d = 128, BQ = 128) the persistent kernel is used: every resident workgroup takes an equal share of all
- * tiles, query blocks cut by a share's boundary leave fragments in `ws`, a second small launch combines them.  Other
- * shapes run exactly as sparse_attn_fwd and leave `ws` untouched.
+ * that several workgroups share is put together from their partial sums).  With more query blocks than the chip holds
+ * at once, in a number that would leave a short last round of workgroups (bf16, d = 128, BQ = 128; the rule is in
+ * attention.hip), the launch is split: whole rounds of query blocks are taken by one workgroup each, the blocks left
+ * over are cut into equal shares of their tiles for all resident workgroups, blocks cut by a share's boundary leave
+ * fragments in `ws`, and a second small launch combines them.  Other shapes run exactly as sparse_attn_fwd and leave
+ * `ws` untouched.
  *   ws / ws_bytes  fastar_workspace_bytes(FASTAR_OP_ATTN, ...) bytes, 256-byte aligned; contents need not be kept
  */
 int sparse_attn_fwd_ws(const void *Q, int n_q, const void *K, const void *V, const int32_t *cnt, const int32_t *len,
