@@ -241,11 +241,15 @@ int ann_select_lsh_buckets(const uint32_t *qbits, int n_q, const uint32_t *kbits
  *   merge_map [H,n_new] int32  destination slot of each token, -1 if dropped
  *   merged    [H,n_new] uint8  1 if the token joined an existing slot
  *   stats     [H,8]     int32  {len after, n_merged, n_appended, n_evicted, n_dropped, 0, 0, status}
- *                              status 0; 1 if a bounded wait inside the eviction plan ran out, 2 if the stamps of
- *                              the evictable slots span 2^20 frames or more: the choice of victims is then not
+ *                              status 0; 1 if a bounded wait inside the eviction plan ran out (its workgroups, which
+ *                              meet through global memory, were not all running at once): nothing of this call is
+ *                              applied to the head then, its K, V, code, cnt, stamp and len stay as they were, every
+ *                              token of the head is reported dropped (merge_map -1, merged 0, n_dropped = n_new), and a
+ *                              persistent workspace has to be zero-filled again before its next use; 2 if the stamps
+ *                              of the evictable slots span 2^20 frames or more: the choice of victims is then not
  *                              guaranteed to be the oldest-first one
  *                              3 if ws_persistent was set for a workspace that is neither zero-filled nor left by
- *                              a finished call
+ *                              a finished call: nothing is applied either (as for status 1)
  *   ws / ws_bytes              workspace of fastar_workspace_bytes(FASTAR_OP_COMPRESS, ...), 256-byte aligned
  *   ws_persistent              0: the workspace may hold anything (the call clears what it needs: one launch more).
  *                              1: the caller zero-filled the workspace once and since then only calls of this

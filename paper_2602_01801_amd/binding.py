@@ -121,6 +121,8 @@ def lib() -> ctypes.CDLL:
         L.fastar_probe_mfma_bf16.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_void_p, ctypes.POINTER(ctypes.c_double), ctypes.c_void_p]
         L.fastar_probe_copy.restype = ctypes.c_int
         L.fastar_probe_copy.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
+        L.fastar_debug_plan_wait.restype = ctypes.c_int
+        L.fastar_debug_plan_wait.argtypes = [ctypes.c_int, ctypes.c_int]
         _lib = L
     return _lib
 
@@ -129,7 +131,7 @@ EXPORTS = ("fastar_init", "fastar_version", "fastar_strerror", "fastar_workspace
            "ann_cross_attn_fwd",
            "ann_select_self", "ann_select_self_forced", "ann_select_self_static", "ann_prompt_buckets", "ann_select_buckets", "fastar_encode_packed", "ann_select_self_packed", "ann_select_cross", "sparse_attn_fwd", "sparse_attn_fwd_ws", "fastar_kv_to_fp8",
            "sparse_attn_fwd_fp8", "fastar_encode_sign", "ann_select_lsh", "ann_select_lsh_buckets",
-           "fastar_probe_mfma_bf16", "fastar_probe_copy")
+           "fastar_probe_mfma_bf16", "fastar_probe_copy", "fastar_debug_plan_wait")
 
 
 def init() -> None:
@@ -567,6 +569,11 @@ def probe_mfma_bf16(iters: int = 20000, random_operands: bool = False) -> float:
     e1.record()
     torch.cuda.synchronize()
     return flops.value / (e0.elapsed_time(e1) * 1e-3) / 1e12
+
+
+def debug_plan_wait(spin_limit: int = -1, extra_arrivals: int = 0) -> None:
+    """Test hook (fastar_debug_plan_wait): bound the eviction plan's waits and add arrivals that never come."""
+    _check(lib().fastar_debug_plan_wait(spin_limit, extra_arrivals), "fastar_debug_plan_wait")
 
 
 def probe_copy(mib: int = 1024, reps: int = 5) -> float:

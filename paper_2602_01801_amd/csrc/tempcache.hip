@@ -25,8 +25,9 @@ int encode_launch(const void *x, int dtype, int64_t n_vec, int d, const fastar_c
 
 constexpr int SCORE_BIAS = 1 << 23;      // makes every score positive inside the packed arg-max key
 constexpr int PLAN_SCRATCH_WORDS = 64 + 3 * 1024;  // per-head scratch of tc_plan_kernel (PS_STRIDE)
-constexpr int HS_STRIDE = 8;             // per-head scalars: oldL, n_unmerged, e, n_victims, n_dropped, newL, -, clean mark
+constexpr int HS_STRIDE = 8;             // per-head scalars: oldL, n_unmerged, e, n_victims, n_dropped, newL, 3 if the workspace is not clean, clean mark
 constexpr int WS_CLEAN = 0x5A17C1EA;     // hs word 7 after a call: group records and plan scratch are all zero again
+constexpr int WS_FAILED = 0x0BADC0DE;    // hs word 7 after a call whose plan gave up for the head: records and scratch are left as they are
 
 typedef unsigned long long u64;
 
@@ -1055,16 +1056,23 @@ __device__ __forceinline__ unsigned ld_agent(const unsigned *p) {
     return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
-// All NB workgroups of a head arrive at counter *ctr; returns when all have (or the bounded wait ran out).
-__device__ __forceinline__ void head_barrier(unsigned *ctr, unsigned nb, unsigned *err) {
+// How long the plan's workgroups wait for each other, and for how many arrivals: normally PLAN_SPIN_LIMIT rounds for the
+// head's own workgroups; the test hook fastar_debug_plan_wait shortens the wait and adds arrivals that never come, so
+// that the exit of a wait that runs out can be exercised while every workgroup still finishes.
+struct PlanWait {
+    int spin_limit;
+    unsigned extra_arrivals;
+};
+// All NB workgroups of a head arrive at counter *ctr; returns when all have (or the bounded wait ran out: bit 0 of *err).
+__device__ __forceinline__ void head_barrier(unsigned *ctr, unsigned nb, unsigned *err, PlanWait pw) {
     __syncthreads();
     if (nb > 1 && threadIdx.x == 0) {
         __threadfence();
         atomicAdd(ctr, 1u);
         int spins = 0;
-        while (ld_agent(ctr) < nb) {
-            if (++spins > PLAN_SPIN_LIMIT) {
-                atomicExch(err, 1u);
+        while (ld_agent(ctr) < nb + pw.extra_arrivals) {
+            if (++spins > pw.spin_limit) {
+                atomicOr(err, 1u);
                 break;
             }
             __builtin_amdgcn_s_sleep(4);
@@ -1134,7 +1142,7 @@ __global__ __launch_bounds__(PLAN_THREADS) void tc_plan_kernel(const int32_t *__
                                                                const u64 *__restrict__ win, int32_t *__restrict__ rank,
                                                                int32_t *__restrict__ victims, int32_t *__restrict__ hs,
                                                                int32_t *__restrict__ stats, unsigned *__restrict__ ps_all,
-                                                               int ws_persistent, int self_hist) {
+                                                               int ws_persistent, int self_hist, PlanWait pw) {
     extern __shared__ unsigned touched[];  // bitmap over this workgroup's slot range
     __shared__ unsigned lhist[PLAN_BINS];
     __shared__ unsigned wtot[PLAN_WAVES];
@@ -1330,7 +1338,7 @@ __global__ __launch_bounds__(PLAN_THREADS) void tc_plan_kernel(const int32_t *__
                 for (int q = 0; q < 4; ++q)
                     if (lhist[4 * tid + q]) atomicAdd(&ps[PS_HIST + 4 * tid + q], lhist[4 * tid + q]);
                 if (__any(future) && lane == 0) atomicOr(&ps[PS_FUT], 1u);
-                head_barrier(&ps[PS_BAR + 3], NB, &ps[PS_ERR]);
+                head_barrier(&ps[PS_BAR + 3], NB, &ps[PS_ERR], pw);
 #pragma unroll
                 for (int q = 0; q < 4; ++q) c4[q] = ld_agent(&ps[PS_HIST + PLAN_BINS - 1 - (4 * tid + q)]);
                 fast = ld_agent(&ps[PS_FUT]) == 0u;   // uniform over the head
@@ -1401,7 +1409,7 @@ __global__ __launch_bounds__(PLAN_THREADS) void tc_plan_kernel(const int32_t *__
                     atomicAdd(&ps[PS_TOT], c);
                 }
             }
-            head_barrier(&ps[PS_BAR + 0], NB, &ps[PS_ERR]);
+            head_barrier(&ps[PS_BAR + 0], NB, &ps[PS_ERR], pw);
             const unsigned umax = ld_agent(&ps[PS_MAXK]), umin = ~ld_agent(&ps[PS_MAXNK]);
             cnt_el = ld_agent(&ps[PS_TOT]);
             take_all = cnt_el <= (unsigned)e;  // fewer eligible slots than evictions needed: take them all
@@ -1421,7 +1429,7 @@ __global__ __launch_bounds__(PLAN_THREADS) void tc_plan_kernel(const int32_t *__
                     unsigned *gh = ps + PS_HIST + (1 + which) * PLAN_BINS;
                     for (int k = tid; k < PLAN_BINS; k += PLAN_THREADS)
                         if (lhist[k]) atomicAdd(&gh[k], lhist[k]);
-                    head_barrier(&ps[PS_BAR + 1 + which], NB, &ps[PS_ERR]);
+                    head_barrier(&ps[PS_BAR + 1 + which], NB, &ps[PS_ERR], pw);
                     unsigned c4[4], total;
 #pragma unroll
                     for (int q = 0; q < 4; ++q) c4[q] = ld_agent(&gh[PLAN_BINS - 1 - (4 * tid + q)]);
@@ -1438,7 +1446,7 @@ __global__ __launch_bounds__(PLAN_THREADS) void tc_plan_kernel(const int32_t *__
                 } else {  // resolve inside the coarse bin (ranges up to 2^20 frames; wider ones are not resolved exactly)
                     const unsigned lo2 = umin + (bin << sh);
                     const int sh2 = sh > 10 ? sh - 10 : 0;
-                    if (sh2 > 0 && tid == 0) atomicExch(&ps[PS_ERR], 2u);
+                    if (sh2 > 0 && tid == 0) atomicOr(&ps[PS_ERR], 2u);
                     unsigned bin2, above2;
                     level(lo2, 1u << sh, sh2, (unsigned)e - above, 1, bin2, above2);
                     T = lo2 + (bin2 << sh2);
@@ -1466,8 +1474,8 @@ __global__ __launch_bounds__(PLAN_THREADS) void tc_plan_kernel(const int32_t *__
             u64 v = 0;
             int spins = 0;
             while (!((v = __hip_atomic_load(&blk[tid], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) >> 63)) {
-                if (++spins > PLAN_SPIN_LIMIT) {
-                    atomicExch(&ps[PS_ERR], 1u);
+                if (++spins > pw.spin_limit) {
+                    atomicOr(&ps[PS_ERR], 1u);
                     break;
                 }
                 __builtin_amdgcn_s_sleep(2);
@@ -1509,9 +1517,13 @@ __global__ __launch_bounds__(PLAN_THREADS) void tc_plan_kernel(const int32_t *__
         o[0] = L; o[1] = (int)n_unm; o[2] = e; o[3] = n_victims; o[4] = n_dropped; o[5] = newL;
         int32_t *s = stats + (size_t)h * 8;
         s[0] = newL; s[1] = n_new - (int)n_unm; s[2] = n_app; s[3] = n_victims; s[4] = n_dropped;
-        int status = e > 0 ? (int)ld_agent(&ps[PS_ERR]) : 0;
+        // bit 0 of the error word (a wait ran out) may still be raised by a workgroup that finishes later: the apply
+        // launch looks again and, if it is set, leaves the head's cache as it was
+        const unsigned err = e > 0 ? ld_agent(&ps[PS_ERR]) : 0u;
+        int status = (err & 1u) ? 1 : (err & 2u) ? 2 : 0;
         // a workspace declared persistent must be a zero-filled one or one a finished call left behind
         if (ws_persistent && mark != 0 && mark != WS_CLEAN) status = 3;
+        o[6] = status == 3 ? 3 : 0;   // for the apply launch: records and scratch of this workspace mean nothing
         s[5] = 0; s[6] = 0; s[7] = status;
     }
 }
@@ -1548,9 +1560,30 @@ __global__ __launch_bounds__(256) void tc_apply_kernel(void *__restrict__ K, voi
                                                        const int32_t *__restrict__ rank,
                                                        const int32_t *__restrict__ victims, int32_t *hs,
                                                        int32_t *__restrict__ merge_map, int32_t *__restrict__ len,
-                                                       int rep_mode, unsigned *__restrict__ ps_all, int ps_words) {
+                                                       int rep_mode, unsigned *__restrict__ ps_all, int ps_words,
+                                                       int32_t *__restrict__ stats) {
     typedef RowPiece<BF16, D> RP;
     const int h = blockIdx.y;
+    // A wait of the plan ran out for this head (bit 0 of its error word; every workgroup of this launch sees it, because
+    // none clears the scratch words then): the victims are not to be trusted, so nothing of the head is applied.  Its
+    // cache stays as it was before the call, every token counts as dropped, and the workspace is marked as not clean.
+    // The same when the workspace was declared persistent but is neither zero-filled nor left by a finished call
+    // (status 3, word 6 of the head's scalars): its records mean nothing.
+    const bool ws_dirty = hs[(size_t)h * HS_STRIDE + 6] == 3;
+    if (ws_dirty || (ps_all[(size_t)h * ps_words + PS_ERR] & 1u)) {
+        if (blockIdx.x == 0 && threadIdx.x == 0) {
+            int32_t *s = stats + (size_t)h * 8;
+            s[0] = hs[(size_t)h * HS_STRIDE + 0]; s[1] = 0; s[2] = 0; s[3] = 0; s[4] = n_new; s[5] = 0; s[6] = 0;
+            s[7] = ws_dirty ? 3 : 1;
+            if (!ws_dirty) hs[(size_t)h * HS_STRIDE + 7] = WS_FAILED;
+        }
+        const int i = blockIdx.x * (blockDim.x / 16) + (threadIdx.x >> 4);
+        if (i < n_new && (threadIdx.x & 15) == 0) {
+            merge_map[(size_t)h * n_new + i] = -1;
+            const_cast<uint8_t *>(merged)[(size_t)h * n_new + i] = 0;
+        }
+        return;
+    }
     // the new length is published here and not by the plan: its workgroups read len[h] at different times
     if (blockIdx.x == 0 && threadIdx.x == 0) {
         len[h] = hs[(size_t)h * HS_STRIDE + 5];
@@ -1758,6 +1791,16 @@ __global__ __launch_bounds__(256) void tc_recode_kernel(const void *__restrict__
 
 using namespace fastar;
 
+// what tc_plan_kernel's waits are bounded by (test hook below; the default is what every caller gets)
+static PlanWait g_plan_wait = {PLAN_SPIN_LIMIT, 0u};
+
+extern "C" int fastar_debug_plan_wait(int spin_limit, int extra_arrivals) {
+    if (extra_arrivals < 0) return FASTAR_ERR_INVALID_ARG;
+    g_plan_wait.spin_limit = spin_limit < 0 ? PLAN_SPIN_LIMIT : spin_limit;
+    g_plan_wait.extra_arrivals = (unsigned)extra_arrivals;
+    return FASTAR_OK;
+}
+
 extern "C" int tempcache_compress(const fastar_cache *cache, const fastar_codec *codec, const void *K_new,
                                   const void *V_new, const void *P_new, int n_new, const int32_t *cand, int n_cand,
                                   int metric, int32_t tau2_q16, int32_t frame_id, int rep_mode, int32_t *merge_map,
@@ -1899,7 +1942,7 @@ extern "C" int tempcache_compress(const fastar_cache *cache, const fastar_codec 
 #define FASTAR_PLAN(PM, TM)                                                                                            \
     hipLaunchKernelGGL((tc_plan_kernel<PM, TM>), dim3(nb + 1, H), dim3(PLAN_THREADS), plan_lds_bytes(C, nb), s, cache->len, \
                        cache->stamp, C, n_new, frame_id, jstar, merged, win, rank, victims, hs, stats, plan_scratch,   \
-                       ws_persistent, self_hist ? 1 : 0)
+                       ws_persistent, self_hist ? 1 : 0, g_plan_wait)
         if (long_runs && long_frame) FASTAR_PLAN(64, 16);
         else if (long_runs) FASTAR_PLAN(64, 8);
         else if (long_frame) FASTAR_PLAN(16, 16);
@@ -1909,7 +1952,7 @@ extern "C" int tempcache_compress(const fastar_cache *cache, const fastar_codec 
     FASTAR_LAUNCH_CHECK();
     FASTAR_TC(tc_apply_kernel, cache->K, cache->V, cache->code, cache->cnt, cache->stamp, C, r, K_new, V_new, ck, n_new,
               frame_id, jstar, merged, win, grp, rank, victims, hs, merge_map, cache->len, rep_mode, plan_scratch,
-              (int)PS_STRIDE);
+              (int)PS_STRIDE, stats);
     FASTAR_LAUNCH_CHECK();
 #undef FASTAR_TC
     if (rep_mode == FASTAR_REP_MEAN) {

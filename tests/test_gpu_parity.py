@@ -771,6 +771,69 @@ def test_tempcache_many_workgroups_take_the_wide_window_kernel(dtype, d, r, H, T
         cand = np.ascontiguousarray(np.concatenate([mm_r, mm_r[:, : n_cand - T]], axis=1)[:, :n_cand])
 
 
+@pytest.mark.parametrize("path,H,T,C,persistent", [
+    ("own_histogram", 2, 700, 16 * 256 * 17, True),    # long cache: the plan's workgroups meet for the age histogram
+    ("general", 3, 300, 4 * 2048, False),              # a stamp in the future: the general path, three meetings
+])
+def test_tempcache_plan_that_gives_up_leaves_the_cache_untouched_and_says_so(path, H, T, C, persistent):
+    # The eviction plan's workgroups wait for each other through global memory, bounded.  The test hook makes those
+    # waits run out (they expect one arrival more than will ever come, for 50 polls): the call must finish, report
+    # status 1 for every head, apply nothing (cache bit for bit as before, every token reported dropped), and the same
+    # call on a fresh workspace with the normal waits must equal the oracle.
+    rng = np.random.default_rng(C + T)
+    d, r, dtype = 128, 32, "bf16"
+    codec = make_codec(0, 9, d, r)
+    as_dt = lambda a: to_storage(a.astype(np.float32), dtype)
+    ref = oracle.Cache.empty(H, C, d, r, dtype)
+    ref.K[:] = as_dt(rng.standard_normal((H, C, d)))
+    ref.V[:] = as_dt(rng.standard_normal((H, C, d)))
+    ref.code[:] = oracle.encode(ref.K, codec.R, codec.qscale, codec.shift)
+    ref.cnt[:] = rng.integers(1, 4, size=(H, C))
+    ref.stamp[:] = rng.integers(0, 9, size=(H, C))
+    if path == "general":
+        ref.stamp[:, 17] = 40                                      # above the call's frame id
+    ref.len[:] = C                                                 # full: every unmerged token needs a victim
+    gpu = dev_cache(ref)
+    before = host_cache(gpu)
+    K_new = as_dt(rng.standard_normal((H, T, d)))
+    src = rng.integers(0, C, size=(H, T))
+    for h in range(H):
+        K_new[h, : T // 2] = ref.K[h, src[h, : T // 2]]            # half of the frame repeats live slots
+    V_new = as_dt(rng.standard_normal((H, T, d)))
+    cand = np.ascontiguousarray(src[:, rng.permutation(T)]).astype(np.int32)
+    args = dict(tau2_q16=TAU2(0.9), frame_id=9)
+    n_ws = fa.workspace_bytes(fa.OP_COMPRESS, H, T, C, r)
+    ws = torch.zeros(n_ws, dtype=torch.uint8, device="cuda")
+    fa.debug_plan_wait(50, 1)
+    try:
+        mm_g, mg_g, st_g = fa.tempcache_compress(gpu, dev_codec(codec), to_dev(K_new), to_dev(V_new), cand=to_dev(cand),
+                                                 ws=ws, ws_persistent=persistent, **args)
+        sync()
+    finally:
+        fa.debug_plan_wait(-1, 0)
+    st = to_host(st_g)
+    assert (st[:, 7] == 1).all() and (st[:, 0] == C).all() and (st[:, 4] == T).all() and (st[:, 1:4] == 0).all()
+    assert (to_host(mm_g) == -1).all() and (to_host(mg_g) == 0).all()
+    after = host_cache(gpu)
+    for name in ("K", "V", "code", "cnt", "stamp", "len"):
+        assert np.array_equal(getattr(after, name), getattr(before, name)), name
+    # the same call with the normal waits, on a fresh workspace
+    ws2 = torch.zeros(n_ws, dtype=torch.uint8, device="cuda")
+    mm_r, mg_r, st_r = oracle.tempcache_compress(ref, codec.R, codec.qscale, codec.shift, K_new, V_new, cand=cand, **args)
+    mm_g, mg_g, st_g = fa.tempcache_compress(gpu, dev_codec(codec), to_dev(K_new), to_dev(V_new), cand=to_dev(cand),
+                                             ws=ws2, ws_persistent=persistent, **args)
+    sync()
+    assert (st_r[:, 3] > 0).all() and (st_r[:, 7] == 0).all() and mg_r.sum() > H * T // 4      # evictions and merges
+    assert np.array_equal(to_host(st_g), st_r) and np.array_equal(to_host(mg_g), mg_r) and np.array_equal(to_host(mm_g), mm_r)
+    assert_cache_equal(host_cache(gpu), ref, VTOL[dtype])
+    if persistent:   # the workspace of the call that gave up is not clean: a further call on it says so and applies nothing
+        _, _, st3 = fa.tempcache_compress(gpu, dev_codec(codec), to_dev(K_new), to_dev(V_new), cand=to_dev(cand),
+                                          ws=ws, ws_persistent=True, tau2_q16=TAU2(0.9), frame_id=10)
+        sync()
+        assert (to_host(st3)[:, 7] != 0).all()
+        assert_cache_equal(host_cache(gpu), ref, VTOL[dtype])
+
+
 @pytest.mark.parametrize("name,dtype,H,frames,C", [("cfg1", None, None, 6, 6 * 256), ("cfg1", "bf16", None, 6, 3 * 256),
                                                    ("cfg2", None, 2, 4, 3 * 1560)])
 def test_tempcache_mean_key_representative_bit_exact(name, dtype, H, frames, C):
