@@ -692,8 +692,12 @@ static int allow_window_lds() {
                ? FASTAR_OK
                : FASTAR_ERR_HIP;
 }
+struct PlanResidency;
+static int plan_residency(PlanResidency *out);
+static int plan_residency_setup();
 // every instantiation of the window kernel may use more than the default 64 KB of dynamic LDS: requested once per device
 int tempcache_setup() {
+    if (const int rc = plan_residency_setup(); rc != FASTAR_OK) return rc;
     static DeviceOnce once;
     return once.run([](int) {
         int rc = FASTAR_OK;
@@ -1529,20 +1533,50 @@ __global__ __launch_bounds__(PLAN_THREADS) void tc_plan_kernel(const int32_t *__
 }
 
 // workgroups per head of tc_plan_kernel and its dynamic LDS (the touched bitmap of one workgroup's slot range).
-// The workgroups of a head wait for each other, so the whole grid has to be resident at once: a compute unit holds
-// eight workgroups of 256 threads, fewer when their LDS (bitmap + about 5 KB of static arrays) does not fit eight times
-// into its 160 KB, and three when the kernel's widest instantiation (160 vector registers) is the one launched: three is
-// what is counted on; the grid (nb + 1) * H stays within what 256 compute units hold.
+// The workgroups of a head wait for each other, so the whole grid has to be resident at once.  What a compute unit
+// holds of the kernel's instantiations without dynamic LDS (registers, wavefront slots) and the number of compute units
+// are asked of the runtime once per device; with LDS (bitmap + about 5 KB of static arrays) fewer may fit its 160 KB.
+// The grid (nb + 1) * H stays within that (and within PLAN_MAX_GRID).
+struct PlanResidency {
+    int per_cu, n_cu;
+};
+static int plan_residency(PlanResidency *out) {
+    static DeviceOnce once;
+    static PlanResidency table[DeviceOnce::MAX_DEVICES];
+    const int rc = once.run([](int dev) {
+        int least = INT_MAX, n_cu = 0;
+        const void *kernels[4] = {(const void *)tc_plan_kernel<64, 16>, (const void *)tc_plan_kernel<64, 8>,
+                                  (const void *)tc_plan_kernel<16, 16>, (const void *)tc_plan_kernel<16, 8>};
+        for (const void *k : kernels) {
+            int n = 0;
+            if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, k, PLAN_THREADS, 0) != hipSuccess) return FASTAR_ERR_HIP;
+            least = std::min(least, n);
+        }
+        if (hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return FASTAR_ERR_HIP;
+        if (least < 1 || n_cu < 1) return FASTAR_ERR_HIP;
+        table[dev] = {least, n_cu};
+        return FASTAR_OK;
+    });
+    if (rc != FASTAR_OK) return rc;
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return FASTAR_ERR_HIP;
+    *out = table[dev];
+    return FASTAR_OK;
+}
+static int plan_residency_setup() {
+    PlanResidency pr;
+    return plan_residency(&pr);
+}
 static size_t plan_lds_bytes(int C, int nb) { return ((size_t)((C + nb - 1) / nb + 3 + 31) / 32 + 2) * 4; }
-static int plan_nb(int H, int C) {
+static int plan_nb(int H, int C, PlanResidency pr) {
     int nb = (C + 2047) / 2048;
     if (nb > PLAN_NB_MAX) nb = PLAN_NB_MAX;
     if (nb < 1) nb = 1;
     for (; nb > 1; --nb) {
         const size_t lds = plan_lds_bytes(C, nb) + 5 * 1024;
         size_t per_cu = (size_t)160 * 1024 / lds;
-        if (per_cu > 3) per_cu = 3;
-        size_t resident = per_cu * 256;
+        if (per_cu > (size_t)pr.per_cu) per_cu = (size_t)pr.per_cu;
+        size_t resident = per_cu * (size_t)pr.n_cu;
         if (resident > (size_t)PLAN_MAX_GRID) resident = PLAN_MAX_GRID;
         if ((size_t)(nb + 1) * (size_t)H <= resident) break;
     }
@@ -1819,7 +1853,9 @@ extern "C" int tempcache_compress(const fastar_cache *cache, const fastar_codec 
     if (codec->shift < 1 || codec->shift > 16) return FASTAR_ERR_INVALID_ARG;
     if (dtype != FASTAR_F32 && dtype != FASTAR_BF16) return FASTAR_ERR_INVALID_ARG;
     if ((d != 64 && d != 128) || (r != 32 && r != 64)) return FASTAR_ERR_UNSUPPORTED;
-    const int nb = plan_nb(H, C);
+    PlanResidency pr;
+    if (const int rc0 = plan_residency(&pr); rc0 != FASTAR_OK) return rc0;
+    const int nb = plan_nb(H, C, pr);
     if (plan_lds_bytes(C, nb) > 48 * 1024) return FASTAR_ERR_UNSUPPORTED;  // eviction bitmap of a slot range lives in LDS
     // Who counts the live slots' ages for the eviction threshold.  Short caches: the verify step, whose whole grid reads
     // the stamps while the plan's few workgroups would meet for it.  Long caches (a plan thread holds more than 16 stamps,
