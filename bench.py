@@ -183,7 +183,7 @@ class ChunkPipeline:
         mark("select_self")
         if self.kv8 is not None:
             fa.sparse_attn_fwd_fp8(Q, self.kv8[0], self.kv8[1], self.cache.cnt, self.cache.len, self.C, self.sel[0],
-                                   self.sel[1], self.BQ, self.BK, self.scale, out=self.O)
+                                   self.sel[1], self.BQ, self.BK, self.scale, out=self.O, ws=self.ws_a)
         else:
             fa.sparse_attn_fwd(Q, self.cache.K, self.cache.V, self.cache.cnt, self.cache.len, self.sel[0], self.sel[1],
                                self.BQ, self.BK, self.scale, out=self.O, ws=self.ws_a)
@@ -226,7 +226,7 @@ class ChunkPipeline:
         mark("select_self")
         if self.kv8 is not None:
             fa.sparse_attn_fwd_fp8(Q, self.kv8[0], self.kv8[1], self.cache.cnt, self.cache.len, self.C, self.sel[0],
-                                   self.sel[1], self.BQ, self.BK, self.scale, out=self.O)
+                                   self.sel[1], self.BQ, self.BK, self.scale, out=self.O, ws=self.ws_a)
         else:
             fa.sparse_attn_fwd(Q, self.cache.K, self.cache.V, self.cache.cnt, self.cache.len, self.sel[0], self.sel[1],
                                self.BQ, self.BK, self.scale, out=self.O, ws=self.ws_a)
@@ -594,7 +594,7 @@ def build_cfg5_full(args, torch, fa, np, to_dev, to_host, n_chunks, n_cpu_heads)
 def run_layer(args, workload, torch, fa, np, to_dev, to_host, steps, warmup, stage_steps, with_cpu, with_dense,
               with_variants=False):
     """Build one workload, time `steps` chunk steps, return its record."""
-    stage_lead = 3 if stage_steps > 0 else 0   # plain steps between the host's synchronisation and the instrumented ones
+    stage_lead = 6 if stage_steps > 0 else 0   # plain steps between the host's synchronisation and the instrumented ones
     n_chunks = warmup + steps + stage_lead + stage_steps
     n_cpu_heads = min(args.cpu_heads, 40)
     t_gen = time.perf_counter()

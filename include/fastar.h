@@ -60,7 +60,7 @@ extern "C" {
 #define FASTAR_OP_SELECT_CROSS 3
 #define FASTAR_OP_SELECT_LSH 4
 #define FASTAR_OP_SELECT_BUCKETS 5 /* pass the number of prompt tokens as r */
-#define FASTAR_OP_ATTN 6           /* sparse_attn_fwd_ws: a fixed amount, whatever the shape */
+#define FASTAR_OP_ATTN 6           /* sparse_attn_fwd_ws, sparse_attn_fwd_fp8_ws: a fixed amount, whatever the shape */
 
 /* representative key of a merged TempCache group (tempcache_compress, rep_mode) */
 #define FASTAR_REP_LAST 0
@@ -395,6 +395,17 @@ int fastar_kv_to_fp8(const fastar_cache *cache, int32_t stamp_lo, uint8_t *K8, u
 int sparse_attn_fwd_fp8(const void *Q, int n_q, const uint8_t *K8, const uint8_t *V8T, const int32_t *cnt,
                         const int32_t *len, int H, int C, int d, const int32_t *sel, const int32_t *nsel, int BQ, int BK,
                         int n_sel, float scale, void *O, float *lse, void *stream);
+
+/*
+ * sparse_attn_fwd_fp8 with a workspace, as sparse_attn_fwd_ws is to sparse_attn_fwd: same arguments, same result (to the
+ * tolerance of the attention itself); a launch that would end in a short last round of workgroups is split, the query
+ * blocks left over are cut into equal shares of their tiles, and a second small launch combines the fragments.  Other
+ * shapes run exactly as sparse_attn_fwd_fp8 and leave `ws` untouched.
+ *   ws / ws_bytes  fastar_workspace_bytes(FASTAR_OP_ATTN, ...) bytes, 256-byte aligned; contents need not be kept
+ */
+int sparse_attn_fwd_fp8_ws(const void *Q, int n_q, const uint8_t *K8, const uint8_t *V8T, const int32_t *cnt,
+                           const int32_t *len, int H, int C, int d, const int32_t *sel, const int32_t *nsel, int BQ,
+                           int BK, int n_sel, float scale, void *O, float *lse, void *ws, size_t ws_bytes, void *stream);
 
 #ifdef __cplusplus
 }

@@ -111,6 +111,8 @@ def lib() -> ctypes.CDLL:
                                           ctypes.c_void_p, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_void_p,
                                           ctypes.c_void_p, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_float,
                                           ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
+        L.sparse_attn_fwd_fp8_ws.restype = ctypes.c_int
+        L.sparse_attn_fwd_fp8_ws.argtypes = L.sparse_attn_fwd_fp8.argtypes[:-1] + [ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
         L.fastar_encode_sign.restype = ctypes.c_int
         L.fastar_encode_sign.argtypes = [ctypes.c_void_p, ctypes.c_int, ctypes.c_int64, ctypes.c_int, ctypes.c_void_p,
                                          ctypes.c_float, ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p]
@@ -130,7 +132,7 @@ def lib() -> ctypes.CDLL:
 EXPORTS = ("fastar_init", "fastar_version", "fastar_strerror", "fastar_workspace_bytes", "fastar_encode", "tempcache_compress",
            "ann_cross_attn_fwd",
            "ann_select_self", "ann_select_self_forced", "ann_select_self_static", "ann_prompt_buckets", "ann_select_buckets", "fastar_encode_packed", "ann_select_self_packed", "ann_select_cross", "sparse_attn_fwd", "sparse_attn_fwd_ws", "fastar_kv_to_fp8",
-           "sparse_attn_fwd_fp8", "fastar_encode_sign", "ann_select_lsh", "ann_select_lsh_buckets",
+           "sparse_attn_fwd_fp8", "sparse_attn_fwd_fp8_ws", "fastar_encode_sign", "ann_select_lsh", "ann_select_lsh_buckets",
            "fastar_probe_mfma_bf16", "fastar_probe_copy", "fastar_debug_plan_wait")
 
 
@@ -531,8 +533,9 @@ def kv_to_fp8(cache: Cache, K8: torch.Tensor, V8T: torch.Tensor, stamp_lo: int =
 
 
 def sparse_attn_fwd_fp8(Q, K8, V8T, cnt, length, C: int, sel, nsel, BQ: int, BK: int, scale: float, out=None,
-                        want_lse: bool = True):
-    """Block-sparse attention over the 8-bit cache copy.  Returns (O [H,n_q,d] bf16, lse [H,n_q] float32 or None)."""
+                        want_lse: bool = True, ws=None):
+    """Block-sparse attention over the 8-bit cache copy.  Returns (O [H,n_q,d] bf16, lse [H,n_q] float32 or None).
+    ws: workspace of workspace_bytes(OP_ATTN, ...) -> sparse_attn_fwd_fp8_ws."""
     _dev(Q, torch.bfloat16)
     _dev(K8, torch.uint8)
     _dev(V8T, torch.uint8)
@@ -549,6 +552,13 @@ def sparse_attn_fwd_fp8(Q, K8, V8T, cnt, length, C: int, sel, nsel, BQ: int, BK:
     if out is None:
         out = (torch.empty_like(Q), torch.empty((H, n_q), dtype=torch.float32, device=Q.device) if want_lse else None)
     O, lse = out
+    if ws is not None:
+        _dev(ws, torch.uint8)
+        _check(lib().sparse_attn_fwd_fp8_ws(Q.data_ptr(), n_q, K8.data_ptr(), V8T.data_ptr(), _ptr(cnt), length.data_ptr(),
+                                            H, C, d, sel.data_ptr(), nsel.data_ptr(), BQ, BK, n_sel, float(scale),
+                                            O.data_ptr(), _ptr(lse), ws.data_ptr(), ws.numel(), _stream()),
+               "sparse_attn_fwd_fp8_ws")
+        return O, lse
     _check(lib().sparse_attn_fwd_fp8(Q.data_ptr(), n_q, K8.data_ptr(), V8T.data_ptr(), _ptr(cnt), length.data_ptr(), H, C,
                                      d, sel.data_ptr(), nsel.data_ptr(), BQ, BK, n_sel, float(scale), O.data_ptr(),
                                      _ptr(lse), _stream()), "sparse_attn_fwd_fp8")

@@ -440,14 +440,11 @@ static int sparse_attn_impl(const void *Q, int n_q, const void *K, const void *V
         // half as long as a full one, with most of the chip idle): the one-block kernel on whole rounds, then the query
         // blocks left over cut into equal shares of their tiles for all resident workgroups (long enough shares to pay for
         // the fragments and their combination).
-        const int per_xcd = (n_items + 7) / 8, tail_per = per_xcd % 64;
         const int n_tiles = (int)(((long long)n_sel * BK + 63) / 64);
-        // What the split saves: a last round of n_tiles tiles at a lone workgroup's pace (about 1.2 us per tile) against
-        // tail_per / 64 of a round at the pace of a full chip (2.4 us per tile) plus about 30 us of fragments and launches.
-        if (ws && d == 128 && BQ == 128 && per_xcd > 64 && tail_per > 0 && tail_per <= 24 &&
-            (float)n_tiles * (1.2f - 0.0375f * (float)tail_per) > 30.0f)
+        const int full_per = attn_split_full_per(n_items, n_tiles);
+        if (ws && d == 128 && BQ == 128 && full_per > 0)
             return launch_attn_bf16_d128_sk(Q, n_q, K, V, cnt, len, H, C, sel, nsel, bk_shift, n_sel, scale_log2, O, lse, ws,
-                                            per_xcd - tail_per, s);
+                                            full_per, s);
         if (d == 128 && BQ == 128 && (n_items <= 512 || n_items % 512 == 0 || n_items % 512 >= 256))
             return launch_attn_bf16_d128_pp(Q, n_q, K, V, cnt, len, H, C, sel, nsel, bk_shift, n_sel, scale_log2, O, lse, s);
         if (d == 128)  // tuned path: direct-to-LDS tiles, LDS transpose loads

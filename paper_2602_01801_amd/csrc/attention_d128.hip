@@ -132,6 +132,8 @@ constexpr int LDS_BYTES = 4 * TILEB + 3 * (int)sizeof(TileMeta);
 constexpr int PART_O_FLOATS = (D / 32) * 16 * 64;              // O^T accumulators of one wavefront
 constexpr int PART_FLOATS = 4 * (PART_O_FLOATS + 2 * 64);      // one fragment of a query block (4 wavefronts)
 constexpr int SK_WORKGROUPS = 512;                             // two resident workgroups per CU
+static_assert(PART_O_FLOATS == ATTN_PART_O_FLOATS && PART_FLOATS == ATTN_PART_FLOATS && SK_WORKGROUPS == ATTN_SHARE_WORKGROUPS,
+              "fragment layout shared with the 8-bit kernel");
 
 // One query block (h, b) over the tiles [t_begin, t_end) of its selection list (t_end may lie beyond the list: it is
 // clipped).  part == nullptr: the block's output rows and lse are written.  Otherwise the fragment's unnormalised
@@ -440,13 +442,6 @@ __global__ __launch_bounds__(NW * 64, 2) void attn_bf16_d128_kernel(
 // share that touches it (slot 0 of a workgroup: a block begun by an earlier workgroup; slot 1: a block it begins but
 // does not finish), and attn_combine_kernel puts the fragments together.  However the number of blocks left over
 // compares with the number of resident workgroups, every workgroup does the same amount of work.
-struct TailMap {
-    int per, full_per, total;   // pairs per XCD range, of them done by the plain launch, pairs in all
-    __device__ __forceinline__ int tail_per() const { return per - full_per; }
-    __device__ __forceinline__ long long tiles(int NT) const { return (long long)8 * tail_per() * NT; }
-    // position in the sequence -> (head, block) pair; pairs >= total do not exist (the last range may be short)
-    __device__ __forceinline__ int item(int vi) const { return (vi / tail_per()) * per + full_per + vi % tail_per(); }
-};
 __global__ __launch_bounds__(256, 2) void attn_bf16_d128_sk_kernel(
     const unsigned short *__restrict__ Q, const unsigned short *__restrict__ K, const unsigned short *__restrict__ V,
     const int32_t *__restrict__ cnt, const int32_t *__restrict__ len, const int32_t *__restrict__ sel,
@@ -480,9 +475,10 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_d128_sk_kernel(
 // Fragments of the query blocks that attn_bf16_d128_sk_kernel cut: workgroup i of this launch puts together the block
 // that share i begins but does not finish (its slot 1, then slot 0 of the following shares while they lie inside the
 // block).  Same wavefront / lane layout as the fragments; any reference maximum is as good as the true one.
+// lse_offset: added to the base-2 logarithm (the 8-bit kernel's probabilities carry a fixed power of two).
 __global__ __launch_bounds__(256) void attn_combine_kernel(const float *__restrict__ ws, int P, int n_q, int n_qb, TailMap tm,
-                                                           int NT, float scale_log2, unsigned short *__restrict__ O,
-                                                           float *__restrict__ lse) {
+                                                           int NT, float scale_log2, float lse_offset,
+                                                           unsigned short *__restrict__ O, float *__restrict__ lse) {
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
     const int i = blockIdx.x;
     const long long W = tm.tiles(NT);
@@ -543,10 +539,20 @@ __global__ __launch_bounds__(256) void attn_combine_kernel(const float *__restri
     }
     const int q_idx = b * 128 + wave * 32 + col;
     if (lse && g == 0 && q_idx < n_q)
-        lse[(size_t)h * n_q + q_idx] = l_tot > 0.0f ? (m_all * scale_log2 + __log2f(l_tot)) * LN2 : -INFINITY;
+        lse[(size_t)h * n_q + q_idx] = l_tot > 0.0f ? (m_all * scale_log2 + lse_offset + __log2f(l_tot)) * LN2 : -INFINITY;
 }
 
 }  // namespace d128
+
+// The combination launch for any kernel that leaves fragments in the layout above (the bf16 and the 8-bit one).
+int launch_attn_combine(const void *ws, int n_q, int n_qb, TailMap tm, int NT, float scale_log2, float lse_offset, void *O,
+                        float *lse, hipStream_t s) {
+    using namespace d128;
+    hipLaunchKernelGGL(attn_combine_kernel, dim3(SK_WORKGROUPS), dim3(256), 4 * 32 * (D + 8) * 2, s, (const float *)ws,
+                       SK_WORKGROUPS, n_q, n_qb, tm, NT, scale_log2, lse_offset, (unsigned short *)O, lse);
+    if (hipGetLastError() != hipSuccess) return FASTAR_ERR_HIP;
+    return FASTAR_OK;
+}
 
 // more than 64 KiB of LDS per workgroup has to be requested once per kernel and device
 int attn_d128_setup() {
@@ -604,10 +610,7 @@ int launch_attn_bf16_d128_sk(const void *Q, int n_q, const void *K, const void *
                        (const unsigned short *)K, (const unsigned short *)V, cnt, len, sel, nsel, n_q, C, bk_shift, n_sel,
                        n_qb, tm, n_plain, NT, scale_log2, 1.0f / scale_log2, (unsigned short *)O, lse, (float *)ws);
     if (hipGetLastError() != hipSuccess) return FASTAR_ERR_HIP;
-    hipLaunchKernelGGL(attn_combine_kernel, dim3(SK_WORKGROUPS), dim3(256), 4 * 32 * (D + 8) * 2, s, (const float *)ws,
-                       SK_WORKGROUPS, n_q, n_qb, tm, NT, scale_log2, (unsigned short *)O, lse);
-    if (hipGetLastError() != hipSuccess) return FASTAR_ERR_HIP;
-    return FASTAR_OK;
+    return launch_attn_combine(ws, n_q, n_qb, tm, NT, scale_log2, 0.0f, O, lse, s);
 }
 
 }  // namespace fastar

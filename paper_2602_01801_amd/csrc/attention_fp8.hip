@@ -146,34 +146,28 @@ __device__ __forceinline__ f32x16 mfma_f8(i32x8 a, i32x8 b, f32x16 c) {
     return __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a, b, c, 0, 0, 0, 0, 0, 0);   // both operands E4M3, no scales
 }
 
-__global__ __launch_bounds__(256, 2) void attn_fp8_d128_kernel(
+// Query block b of head h over the entries t_begin <= t < t_end of its list (one entry = one tile).  part == nullptr:
+// normalised output rows and lse are written (the range must then be the whole list).  part != nullptr: the unnormalised
+// O^T accumulators ([wave][32-row block of d][register][lane]), then the reference maxima and the row sums
+// ([wave][lane] each): the fragment layout that the combination launch of the split bf16 kernel reads.
+// All 256 threads of a workgroup; may be called again by the same workgroup for another block.
+__device__ __forceinline__ void attend_item_fp8(
     const unsigned short *__restrict__ Q, const uint8_t *__restrict__ K8, const uint8_t *__restrict__ V8T,
     const int32_t *__restrict__ cnt, const int32_t *__restrict__ len, const int32_t *__restrict__ sel,
-    const int32_t *__restrict__ nsel, int n_q, int C, int n_blk, int n_sel, int n_qb, int H, float scale_log2,
-    float inv_scale_log2, unsigned short *__restrict__ O, float *__restrict__ lse) {
-    extern __shared__ __attribute__((aligned(1024))) unsigned char lds[];
+    const int32_t *__restrict__ nsel, int n_q, int C, int n_blk, int n_sel, int n_qb, float scale_log2,
+    float inv_scale_log2, unsigned short *__restrict__ O, float *__restrict__ lse, unsigned char *lds, int h, int b,
+    int t_begin, int t_end, float *__restrict__ part) {
     unsigned char *kbuf = lds;
     unsigned char *vbuf = lds + 2 * TILEB;
     TileMeta *meta = (TileMeta *)(lds + META_OFF);
-
-    // workgroup -> (head, query block): each XCD gets a contiguous range of (head, block) pairs
-    int h, b;
-    {
-        const int total = n_qb * H;
-        const int wg = blockIdx.x;
-        const int per = (total + 7) / 8;
-        const int item = (wg & 7) * per + (wg >> 3);
-        if (item >= total) return;
-        h = item / n_qb;
-        b = item % n_qb;
-    }
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int col = lane & 31, g = lane >> 5;
     const int L = min(len[h], C);
     const int n_live_blk = (L + TK - 1) / TK;
-    const int nt = L > 0 ? min(nsel[(size_t)h * n_qb + b], n_sel) : 0;   // one selection entry = one tile
-    const int32_t *sel_row = sel + ((size_t)h * n_qb + b) * n_sel;
+    const int nt_all = L > 0 ? min(nsel[(size_t)h * n_qb + b], n_sel) : 0;   // one selection entry = one tile
+    const int nt = max(0, min(nt_all, t_end) - t_begin);                     // tiles of this call: entries t_begin .. t_begin + nt - 1
+    const int32_t *sel_row = sel + ((size_t)h * n_qb + b) * n_sel + t_begin;
     const int32_t *cnt_h = cnt ? cnt + (size_t)h * C : nullptr;
     const uint8_t *Kh = K8 + (size_t)h * n_blk * TK * D;
     const uint8_t *Vh = V8T + (size_t)h * n_blk * TILEB;
@@ -339,8 +333,18 @@ __global__ __launch_bounds__(256, 2) void attn_fp8_d128_kernel(
         if (t + 1 < nt) tile_step(t + 1, std::integral_constant<int, 1>{});
     }
 
-    // epilogue: normalise, transpose through LDS, store rows coalesced
     const float l_tot = l_acc[0];
+    if (part) {   // a fragment: the combination launch normalises
+#pragma unroll
+        for (int db = 0; db < D / 32; ++db)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) part[((wave * (D / 32) + db) * 16 + v) * 64 + lane] = o_acc[db][v];
+        part[4 * ATTN_PART_O_FLOATS + wave * 64 + lane] = m_ref;
+        part[4 * ATTN_PART_O_FLOATS + 4 * 64 + wave * 64 + lane] = l_tot;
+        __syncthreads();   // the tile stages and the bookkeeping are free for the next block
+        return;
+    }
+    // epilogue: normalise, transpose through LDS, store rows coalesced
     const float inv = l_tot > 0.0f ? 1.0f / l_tot : 0.0f;
     __syncthreads();
     unsigned short *Os = (unsigned short *)lds + (size_t)wave * 32 * OSTR;
@@ -366,6 +370,54 @@ __global__ __launch_bounds__(256, 2) void attn_fp8_d128_kernel(
     }
     if (lse && g == 0 && q_idx < n_q)
         lse[(size_t)h * n_q + q_idx] = l_tot > 0.0f ? (m_ref * scale_log2 - 6.0f + __log2f(l_tot)) * LN2 : -INFINITY;
+    __syncthreads();   // the staged output rows have been read: the tile stages are free for the next block
+}
+
+// One query block per workgroup; two workgroups per CU, started as slots free up.
+__global__ __launch_bounds__(256, 2) void attn_fp8_d128_kernel(
+    const unsigned short *__restrict__ Q, const uint8_t *__restrict__ K8, const uint8_t *__restrict__ V8T,
+    const int32_t *__restrict__ cnt, const int32_t *__restrict__ len, const int32_t *__restrict__ sel,
+    const int32_t *__restrict__ nsel, int n_q, int C, int n_blk, int n_sel, int n_qb, int H, float scale_log2,
+    float inv_scale_log2, unsigned short *__restrict__ O, float *__restrict__ lse) {
+    extern __shared__ __attribute__((aligned(1024))) unsigned char lds[];
+    // workgroup -> (head, query block): each XCD gets a contiguous range of (head, block) pairs
+    const int total = n_qb * H;
+    const int wg = blockIdx.x;
+    const int per = (total + 7) / 8;
+    const int item = (wg & 7) * per + (wg >> 3);
+    if (item >= total) return;
+    attend_item_fp8(Q, K8, V8T, cnt, len, sel, nsel, n_q, C, n_blk, n_sel, n_qb, scale_log2, inv_scale_log2, O, lse, lds,
+                    item / n_qb, item % n_qb, 0, INT_MAX, nullptr);
+}
+
+// The split launch (see the bf16 kernel of the same structure in attention_d128.hip): the first n_plain workgroups take one
+// whole query block each, in the plain kernel's order; the others take equal shares of the tiles of the blocks left over.
+__global__ __launch_bounds__(256, 2) void attn_fp8_d128_sk_kernel(
+    const unsigned short *__restrict__ Q, const uint8_t *__restrict__ K8, const uint8_t *__restrict__ V8T,
+    const int32_t *__restrict__ cnt, const int32_t *__restrict__ len, const int32_t *__restrict__ sel,
+    const int32_t *__restrict__ nsel, int n_q, int C, int n_blk, int n_sel, int n_qb, TailMap tm, int n_plain, int NT,
+    float scale_log2, float inv_scale_log2, unsigned short *__restrict__ O, float *__restrict__ lse, float *__restrict__ ws) {
+    extern __shared__ __attribute__((aligned(1024))) unsigned char lds[];
+    const int P = (int)gridDim.x - n_plain;                        // a multiple of 8
+    const int wg = (int)blockIdx.x - n_plain;
+    const int i = (wg & 7) * (P >> 3) + (wg >> 3);                 // neighbouring shares on one XCD: those of its own range
+    const int direct = wg < 0 ? ((int)blockIdx.x & 7) * tm.per + ((int)blockIdx.x >> 3) : -1;
+    const long long W = tm.tiles(NT);
+    long long v = wg < 0 ? 0 : i * W / P;
+    const long long v_end = wg < 0 ? NT : (i + 1) * W / P;
+    while (v < v_end) {
+        const int vi = (int)(v / NT);
+        const int t_begin = (int)(v - (long long)vi * NT);
+        const int t_end = (int)min((long long)NT, v_end - (long long)vi * NT);
+        const int item = direct >= 0 ? direct : tm.item(vi);
+        if (item < tm.total) {   // uniform over the workgroup
+            float *part = nullptr;
+            if (t_begin > 0 || t_end < NT) part = ws + ((size_t)i * 2 + (t_begin > 0 ? 0 : 1)) * ATTN_PART_FLOATS;
+            attend_item_fp8(Q, K8, V8T, cnt, len, sel, nsel, n_q, C, n_blk, n_sel, n_qb, scale_log2, inv_scale_log2, O, lse,
+                            lds, item / n_qb, item % n_qb, t_begin, t_end, part);
+        }
+        v = (long long)vi * NT + t_end;
+    }
 }
 
 }  // namespace f8
@@ -374,7 +426,9 @@ int attn_fp8_setup() {
     static DeviceOnce once;
     return once.run([](int) {
         return hipFuncSetAttribute((const void *)f8::attn_fp8_d128_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                   f8::LDS_BYTES) == hipSuccess
+                                   f8::LDS_BYTES) == hipSuccess &&
+                       hipFuncSetAttribute((const void *)f8::attn_fp8_d128_sk_kernel,
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, f8::LDS_BYTES) == hipSuccess
                    ? FASTAR_OK
                    : FASTAR_ERR_HIP;
     });
@@ -405,9 +459,28 @@ extern "C" int fastar_kv_to_fp8(const fastar_cache *cache, int32_t stamp_lo, uin
     return FASTAR_OK;
 }
 
+static int sparse_attn_fp8_impl(const void *Q, int n_q, const uint8_t *K8, const uint8_t *V8T, const int32_t *cnt,
+                                const int32_t *len, int H, int C, int d, const int32_t *sel, const int32_t *nsel, int BQ,
+                                int BK, int n_sel, float scale, void *O, float *lse, void *ws, void *stream);
+
 extern "C" int sparse_attn_fwd_fp8(const void *Q, int n_q, const uint8_t *K8, const uint8_t *V8T, const int32_t *cnt,
                                    const int32_t *len, int H, int C, int d, const int32_t *sel, const int32_t *nsel,
                                    int BQ, int BK, int n_sel, float scale, void *O, float *lse, void *stream) {
+    return sparse_attn_fp8_impl(Q, n_q, K8, V8T, cnt, len, H, C, d, sel, nsel, BQ, BK, n_sel, scale, O, lse, nullptr, stream);
+}
+
+extern "C" int sparse_attn_fwd_fp8_ws(const void *Q, int n_q, const uint8_t *K8, const uint8_t *V8T, const int32_t *cnt,
+                                      const int32_t *len, int H, int C, int d, const int32_t *sel, const int32_t *nsel,
+                                      int BQ, int BK, int n_sel, float scale, void *O, float *lse, void *ws,
+                                      size_t ws_bytes, void *stream) {
+    if (!ws || ((uintptr_t)ws & 255)) return FASTAR_ERR_INVALID_ARG;
+    if (ws_bytes < (size_t)ATTN_SHARE_WORKGROUPS * 2 * ATTN_PART_FLOATS * sizeof(float)) return FASTAR_ERR_WORKSPACE;
+    return sparse_attn_fp8_impl(Q, n_q, K8, V8T, cnt, len, H, C, d, sel, nsel, BQ, BK, n_sel, scale, O, lse, ws, stream);
+}
+
+static int sparse_attn_fp8_impl(const void *Q, int n_q, const uint8_t *K8, const uint8_t *V8T, const int32_t *cnt,
+                                const int32_t *len, int H, int C, int d, const int32_t *sel, const int32_t *nsel, int BQ,
+                                int BK, int n_sel, float scale, void *O, float *lse, void *ws, void *stream) {
     if (!Q || !K8 || !V8T || !len || !sel || !nsel || !O) return FASTAR_ERR_INVALID_ARG;
     if (H <= 0 || n_q <= 0 || C <= 0 || n_sel <= 0) return FASTAR_ERR_INVALID_ARG;
     if (!(scale > 0.0f) || !(scale < INFINITY)) return FASTAR_ERR_INVALID_ARG;
@@ -418,6 +491,18 @@ extern "C" int sparse_attn_fwd_fp8(const void *Q, int n_q, const uint8_t *K8, co
     const int n_qb = (n_q + 127) / 128;
     const int n_blk = (C + f8::TK - 1) / f8::TK;
     const float scale_log2 = scale * 1.4426950408889634f;
+    // with a workspace, a launch that would end in a short last round of workgroups is split (one entry = one tile)
+    const int full_per = ws ? attn_split_full_per(n_qb * H, n_sel) : 0;
+    if (full_per > 0) {
+        const TailMap tm = {(n_qb * H + 7) / 8, full_per, n_qb * H};
+        const int n_plain = 8 * full_per;
+        hipLaunchKernelGGL(f8::attn_fp8_d128_sk_kernel, dim3(n_plain + ATTN_SHARE_WORKGROUPS), dim3(256), f8::LDS_BYTES,
+                           (hipStream_t)stream, (const unsigned short *)Q, K8, V8T, cnt, len, sel, nsel, n_q, C, n_blk,
+                           n_sel, n_qb, tm, n_plain, n_sel, scale_log2, 1.0f / scale_log2, (unsigned short *)O, lse,
+                           (float *)ws);
+        FASTAR_LAUNCH_CHECK();
+        return launch_attn_combine(ws, n_q, n_qb, tm, n_sel, scale_log2, -6.0f, O, lse, (hipStream_t)stream);
+    }
     const dim3 grid((unsigned)(((n_qb * H + 7) / 8) * 8));
     hipLaunchKernelGGL(f8::attn_fp8_d128_kernel, grid, dim3(256), f8::LDS_BYTES, (hipStream_t)stream,
                        (const unsigned short *)Q, K8, V8T, cnt, len, sel, nsel, n_q, C, n_blk, n_sel, n_qb, H, scale_log2,

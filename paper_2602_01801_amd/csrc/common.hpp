@@ -104,6 +104,32 @@ struct DeviceOnce {
     }
 };
 
+// ---- split attention launches (sparse_attn_fwd_ws, sparse_attn_fwd_fp8_ws) ---------------------------------------
+// The (head, query block) pairs are dealt to the 8 XCDs in contiguous ranges of `per`; the first `full_per` pairs of every
+// range are taken by one workgroup each, the others are cut into equal shares of their tiles (attention_d128.hip).
+struct TailMap {
+    int per, full_per, total;   // pairs per XCD range, of them taken whole, pairs in all
+    __host__ __device__ __forceinline__ int tail_per() const { return per - full_per; }
+    __host__ __device__ __forceinline__ long long tiles(int NT) const { return (long long)8 * tail_per() * NT; }
+    // position in the left-over sequence -> (head, block) pair; pairs >= total do not exist (the last range may be short)
+    __host__ __device__ __forceinline__ int item(int vi) const { return (vi / tail_per()) * per + full_per + vi % tail_per(); }
+};
+constexpr int ATTN_SHARE_WORKGROUPS = 512;                      // resident workgroups that take the shares: two per CU
+constexpr int ATTN_PART_O_FLOATS = (128 / 32) * 16 * 64;        // O^T accumulators of one wavefront (d = 128)
+constexpr int ATTN_PART_FLOATS = 4 * (ATTN_PART_O_FLOATS + 2 * 64);   // one fragment of a query block: four wavefronts' accumulators, reference maxima, row sums
+// Whether a launch of n_items pairs with n_tiles 64-key tiles each is split, and how many pairs per range are taken
+// whole then (0: not split).  What the split saves: a last round of n_tiles tiles at a lone workgroup's pace (about 1.2 us
+// per tile) against tail_per / 64 of a round at the pace of a full chip (2.4 us per tile) plus about 30 us of fragments and
+// launches (an XCD holds 64 workgroups of the one-block kernels).
+inline int attn_split_full_per(int n_items, int n_tiles) {
+    const int per_xcd = (n_items + 7) / 8, tail_per = per_xcd % 64;
+    if (per_xcd > 64 && tail_per > 0 && tail_per <= 24 && (float)n_tiles * (1.2f - 0.0375f * (float)tail_per) > 30.0f)
+        return per_xcd - tail_per;
+    return 0;
+}
+int launch_attn_combine(const void *ws, int n_q, int n_qb, TailMap tm, int NT, float scale_log2, float lse_offset, void *O,
+                        float *lse, hipStream_t s);
+
 // Per-file set-up, all of it run by fastar_init() (api.hip) and each lazily by the first launch that needs it.
 int attn_d128_pp_setup();
 int attn_d128_setup();

@@ -120,6 +120,67 @@ def test_fp8_attention_matches_the_oracle(H, n_q, C, lens, n_sel, seed):
     check_fp8_attention(Q, c, sel, nsel, d ** -0.5, use_cnt=False)
 
 
+@pytest.mark.parametrize("H,n_q,C,n_sel", [
+    (20, 3600, 64 * 300, 150),     # 580 query blocks: 73 per XCD range, 9 of them left over by the whole round
+    (33, 2048, 64 * 256, 128),     # 528 blocks: 2 per range left over
+])
+def test_fp8_attention_with_a_workspace_splits_the_launch_and_matches_the_plain_one_and_the_oracle(H, n_q, C, n_sel):
+    # sparse_attn_fwd_fp8_ws: the query blocks that whole rounds of workgroups leave over are cut into equal shares of
+    # their tiles and combined from fragments.  Against the plain launch everywhere, against the oracle on sampled
+    # (head, query block) pairs: whole ones, cut ones, a short and an empty list, a head that is not full.
+    rng = np.random.default_rng(H + n_sel)
+    d = 128
+    g = torch.Generator(device="cuda").manual_seed(H * 7 + n_sel)
+    Q = (torch.randn(H, n_q, d, device="cuda", generator=g) * 1.1).bfloat16()
+    K = torch.randn(H, C, d, device="cuda", generator=g).bfloat16()
+    V = torch.randn(H, C, d, device="cuda", generator=g).bfloat16()
+    cnt = torch.randint(1, 6, (H, C), device="cuda", generator=g, dtype=torch.int32)
+    lens = np.full(H, C, np.int32)
+    lens[3] = C // 2 + 17
+    gpu = fa.Cache.empty(H, C, d, 32, torch.bfloat16)
+    gpu.K.copy_(K); gpu.V.copy_(V); gpu.cnt.copy_(cnt); gpu.stamp.zero_(); gpu.len.copy_(to_dev(lens))
+    K8, V8 = fa.kv8_empty(H, C, d)
+    fa.kv_to_fp8(gpu, K8, V8)
+    n_qb, n_kb = -(-n_q // 128), C // 64
+    sel = np.stack([np.stack([np.sort(rng.choice(n_kb, n_sel, replace=False)) for _ in range(n_qb)]) for _ in range(H)]).astype(np.int32)
+    nsel = np.full((H, n_qb), n_sel, np.int32)
+    total = n_qb * H
+    per = -(-total // 8)
+    tail_per = per % 64
+    assert per > 64 and 0 < tail_per <= 24, "the shape is meant to take the split launch"
+    to_item = lambda vi: (vi // tail_per) * per + (per - tail_per) + vi % tail_per
+    W = 8 * tail_per * n_sel
+    cut = sorted({to_item((i * W // 512) // n_sel) for i in range(1, 512) if (i * W // 512) % n_sel} - set(range(total, 8 * per)))
+    short_item, empty_item = cut[1], to_item(1) if to_item(1) not in cut[:3] else to_item(2)
+    nsel.reshape(-1)[short_item] = n_sel // 3
+    sel.reshape(total, n_sel)[short_item, n_sel // 3:] = -1
+    nsel.reshape(-1)[empty_item] = 0
+    sel.reshape(total, n_sel)[empty_item, :] = -1
+    ws = torch.empty(fa.workspace_bytes(fa.OP_ATTN, H, n_q, C), dtype=torch.uint8, device="cuda")
+    args = (Q, K8, V8, cnt, to_dev(lens), C, to_dev(sel), to_dev(nsel), 128, 64, d ** -0.5)
+    O_ws, lse_ws = fa.sparse_attn_fwd_fp8(*args, ws=ws)
+    O_pl, lse_pl = fa.sparse_attn_fwd_fp8(*args)
+    torch.cuda.synchronize()
+    a, b = storage_to_f64(to_host(O_ws)), storage_to_f64(to_host(O_pl))
+    # a fragment rounds its weights to E4M3 against its own reference maximum: the two launches differ like either does from the oracle
+    assert np.isfinite(a).all() and np.abs(a - b).max() <= ATOL_MAX and np.abs(a - b).mean() <= ATOL_MEAN
+    lw, lp = to_host(lse_ws).astype(np.float64), to_host(lse_pl).astype(np.float64)
+    fin = np.isfinite(lp)
+    assert np.array_equal(fin, np.isfinite(lw)) and np.abs(lw[fin] - lp[fin]).max() <= 0.05
+    Kc, Vc = to_host(K8), to_host(V8)
+    sample = sorted(set([0, n_qb - 1, total - 1, short_item, empty_item, 3 * n_qb] + cut[:2] + cut[-1:]))
+    for item in sample:
+        h, bq = divmod(item, n_qb)
+        q0, q1 = bq * 128, min((bq + 1) * 128, n_q)
+        O_r, lse_r = oracle.sparse_attn_fwd_fp8(to_host(Q[h:h + 1, q0:q1]), Kc[h:h + 1], Vc[h:h + 1], to_host(cnt[h:h + 1]),
+                                                lens[h:h + 1], C, sel[h:h + 1, bq:bq + 1], nsel[h:h + 1, bq:bq + 1], 128, 64,
+                                                d ** -0.5)
+        err = np.abs(a[h, q0:q1] - O_r[0])
+        assert err.max() <= ATOL_MAX and err.mean() <= ATOL_MEAN, f"item {item}: {err.max()} {err.mean()}"
+        ok = np.isfinite(lse_r[0])
+        assert np.array_equal(ok, np.isfinite(lw[h, q0:q1])) and np.abs(lw[h, q0:q1][ok] - lse_r[0][ok]).max(initial=0.0) <= 0.05
+
+
 def test_fp8_attention_with_steadily_climbing_logits_and_a_dominant_key():
     # the reference maximum is updated lazily: scores that climb along the key list, and one key that dominates a row
     rng = np.random.default_rng(9)
