@@ -472,15 +472,17 @@ __global__ __launch_bounds__(256, 2) void attn_bf16_d128_sk_kernel(
     }
 }
 
-// Fragments of the query blocks that attn_bf16_d128_sk_kernel cut: workgroup i of this launch puts together the block
-// that share i begins but does not finish (its slot 1, then slot 0 of the following shares while they lie inside the
-// block).  Same wavefront / lane layout as the fragments; any reference maximum is as good as the true one.
+// Fragments of the query blocks that attn_bf16_d128_sk_kernel cut: workgroup (i, db) of this launch puts together, for the
+// 32 coordinates db of d, the block that share i begins but does not finish (its slot 1, then slot 0 of the following
+// shares while they lie inside the block).  Same wavefront / lane layout as the fragments; any reference maximum is as good
+// as the true one.  One workgroup per block and quarter of d: the rows of four fragments are in flight together, so a
+// block costs one or two memory round trips.
 // lse_offset: added to the base-2 logarithm (the 8-bit kernel's probabilities carry a fixed power of two).
 __global__ __launch_bounds__(256) void attn_combine_kernel(const float *__restrict__ ws, int P, int n_q, int n_qb, TailMap tm,
                                                            int NT, float scale_log2, float lse_offset,
                                                            unsigned short *__restrict__ O, float *__restrict__ lse) {
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
-    const int i = blockIdx.x;
+    const int i = blockIdx.x, db = blockIdx.y;
     const long long W = tm.tiles(NT);
     const long long start = i * W / P, end = (i + 1) * W / P;
     if (end >= W || end % NT == 0) return;          // share i ends with a whole block
@@ -498,47 +500,50 @@ __global__ __launch_bounds__(256) void attn_combine_kernel(const float *__restri
     auto frag = [&](int f) -> const float * { return ws + ((size_t)(i + f) * 2 + (f == 0 ? 1 : 0)) * PART_FLOATS; };
     float m_all = -INFINITY;
     for (int f = 0; f < n_frag; ++f) m_all = fmaxf(m_all, frag(f)[4 * PART_O_FLOATS + wave * 64 + lane]);
-    float o[D / 32][16];
+    float o[16];
 #pragma unroll
-    for (int db = 0; db < D / 32; ++db)
-#pragma unroll
-        for (int v = 0; v < 16; ++v) o[db][v] = 0.0f;
+    for (int v = 0; v < 16; ++v) o[v] = 0.0f;
     float l_tot = 0.0f;
-    for (int f = 0; f < n_frag; ++f) {
-        const float *p = frag(f);
-        const float m_f = p[4 * PART_O_FLOATS + wave * 64 + lane];
-        const float w = m_f == -INFINITY ? 0.0f : __builtin_amdgcn_exp2f((m_f - m_all) * scale_log2);
-        l_tot += w * p[4 * PART_O_FLOATS + 4 * 64 + wave * 64 + lane];
-        if (w > 0.0f) {
+    constexpr int FB = 4;   // fragments whose rows are loaded together
+    for (int f0 = 0; f0 < n_frag; f0 += FB) {
+        float mf[FB], lf[FB], of[FB][16];
 #pragma unroll
-            for (int db = 0; db < D / 32; ++db)
+        for (int u = 0; u < FB; ++u) {
+            const float *p = frag(min(f0 + u, n_frag - 1));
+            mf[u] = p[4 * PART_O_FLOATS + wave * 64 + lane];
+            lf[u] = p[4 * PART_O_FLOATS + 4 * 64 + wave * 64 + lane];
 #pragma unroll
-                for (int v = 0; v < 16; ++v) o[db][v] += w * p[((wave * (D / 32) + db) * 16 + v) * 64 + lane];
+            for (int v = 0; v < 16; ++v) of[u][v] = p[((wave * (D / 32) + db) * 16 + v) * 64 + lane];
+        }
+#pragma unroll
+        for (int u = 0; u < FB; ++u) {
+            const float w = (f0 + u >= n_frag || mf[u] == -INFINITY) ? 0.0f : __builtin_amdgcn_exp2f((mf[u] - m_all) * scale_log2);
+            l_tot += w * lf[u];
+#pragma unroll
+            for (int v = 0; v < 16; ++v) o[v] += w * of[u][v];
         }
     }
     const float inv = l_tot > 0.0f ? 1.0f / l_tot : 0.0f;
-    constexpr int OSTR = D + 8;
-    unsigned short *Os = (unsigned short *)lds + (size_t)wave * 32 * OSTR;
+    constexpr int OS = 32 + 8;   // bf16 elements per staged row (this quarter of d, padded)
+    unsigned short *Os = (unsigned short *)lds + (size_t)wave * 32 * OS;
 #pragma unroll
-    for (int db = 0; db < D / 32; ++db)
+    for (int q4 = 0; q4 < 4; ++q4) {
+        typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
+        bf16x4 wv;
 #pragma unroll
-        for (int q4 = 0; q4 < 4; ++q4) {
-            typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
-            bf16x4 wv;
-#pragma unroll
-            for (int e = 0; e < 4; ++e) wv[e] = (__bf16)(o[db][4 * q4 + e] * inv);
-            *(bf16x4 *)(Os + col * OSTR + 32 * db + 8 * q4 + 4 * g) = wv;
-        }
+        for (int e = 0; e < 4; ++e) wv[e] = (__bf16)(o[4 * q4 + e] * inv);
+        *(bf16x4 *)(Os + col * OS + 8 * q4 + 4 * g) = wv;
+    }
     __syncthreads();
-    const int rr = lane >> 4, cc = lane & 15;
+    const int rr = lane >> 2, cc = lane & 3;
 #pragma unroll
-    for (int it = 0; it < 8; ++it) {
-        const int r = it * 4 + rr;
+    for (int it = 0; it < 2; ++it) {
+        const int r = it * 16 + rr;
         const int qi = b * 128 + wave * 32 + r;
-        if (qi < n_q) *(u32x4 *)(O + ((size_t)h * n_q + qi) * D + cc * 8) = *(const u32x4 *)(Os + r * OSTR + cc * 8);
+        if (qi < n_q) *(u32x4 *)(O + ((size_t)h * n_q + qi) * D + 32 * db + cc * 8) = *(const u32x4 *)(Os + r * OS + cc * 8);
     }
     const int q_idx = b * 128 + wave * 32 + col;
-    if (lse && g == 0 && q_idx < n_q)
+    if (db == 0 && lse && g == 0 && q_idx < n_q)
         lse[(size_t)h * n_q + q_idx] = l_tot > 0.0f ? (m_all * scale_log2 + lse_offset + __log2f(l_tot)) * LN2 : -INFINITY;
 }
 
@@ -548,7 +553,7 @@ __global__ __launch_bounds__(256) void attn_combine_kernel(const float *__restri
 int launch_attn_combine(const void *ws, int n_q, int n_qb, TailMap tm, int NT, float scale_log2, float lse_offset, void *O,
                         float *lse, hipStream_t s) {
     using namespace d128;
-    hipLaunchKernelGGL(attn_combine_kernel, dim3(SK_WORKGROUPS), dim3(256), 4 * 32 * (D + 8) * 2, s, (const float *)ws,
+    hipLaunchKernelGGL(attn_combine_kernel, dim3(SK_WORKGROUPS, D / 32), dim3(256), 4 * 32 * (32 + 8) * 2, s, (const float *)ws,
                        SK_WORKGROUPS, n_q, n_qb, tm, NT, scale_log2, lse_offset, (unsigned short *)O, lse);
     if (hipGetLastError() != hipSuccess) return FASTAR_ERR_HIP;
     return FASTAR_OK;
