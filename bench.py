@@ -621,8 +621,8 @@ def run_layer(args, workload, torch, fa, np, to_dev, to_host, steps, warmup, sta
         pipe.step(*dev_chunks[w])
     torch.cuda.synchronize()
 
-    # Timed region: K steps, only the self-attention launch bracketed by events (every event is a marker the
-    # queue has to drain to; seven per step cost about 15 us of a 0.3 ms step).
+    # Timed region: K steps; the self-attention launch of every fourth step is bracketed by events (every event is a
+    # marker the queue has to drain to: about 6 us of idle chip each, so not every step carries them).
     attn_events = []
     t0 = time.perf_counter()
     for s in range(steps):
@@ -633,13 +633,16 @@ def run_layer(args, workload, torch, fa, np, to_dev, to_host, steps, warmup, sta
                 e = torch.cuda.Event(enable_timing=True)
                 e.record()
                 evs[name] = e
-        pipe.step(*dev_chunks[warmup + s], ev=mark)
-        attn_events.append(evs)
+        if s % 4 == 0:
+            pipe.step(*dev_chunks[warmup + s], ev=mark)
+            attn_events.append(evs)
+        else:
+            pipe.step(*dev_chunks[warmup + s])
     t_enqueued = time.perf_counter()
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     ms_per_step = (t1 - t0) * 1e3 / steps
-    attn_ms = sum(e["select_self"].elapsed_time(e["attn_self"]) for e in attn_events) / steps
+    attn_ms = sum(e["select_self"].elapsed_time(e["attn_self"]) for e in attn_events) / len(attn_events)
     flops = pipe.attended_flops()
     stats_timed = to_host(pipe.mm[(pipe.frame_id - 1) & 1][2])
     # Stage breakdown: a separate pass over the next chunks of the same rollout, an event after every stage.
@@ -730,10 +733,11 @@ def run_layer(args, workload, torch, fa, np, to_dev, to_host, steps, warmup, sta
                      "frac": round(gbs / PEAK_HBM_GBS, 4) if hbm_bound else round(tflops / peak_tf, 4),
                      "traffic": traffic, "traffic_source": traffic_src,
                      "algorithmic_bytes_per_launch": gathered, "flops_per_launch": flops, "avg_launch_ms": round(attn_ms, 4),
+                     "launches_timed": len(attn_events),
                      "mfma_view": {"achieved": round(tflops, 2), "peak": peak_tf, "unit": "TFLOP/s", "frac": round(tflops / peak_tf, 4)},
                      "hbm_view": {"achieved": round(gbs, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": round(gbs / PEAK_HBM_GBS, 4),
                                   "measured_traffic_GBs": None if traffic is None else round(traffic / (attn_ms * 1e-3) / 1e9, 1)},
-                     "note": "bound = hbm when the committed counter summary of this workload shows at least half of the gathered K/V bytes coming from HBM (no reuse in cache), else mfma"},
+                     "note": "avg_launch_ms: HIP events around the self-attention call of every fourth timed step; bound = hbm when the committed counter summary of this workload shows at least half of the gathered K/V bytes coming from HBM (no reuse in cache), else mfma"},
         "dense_equivalent": None if dense is None else {
             "ms": round(dense[0], 4), "key_blocks": dense[1], "speedup_of_sparse": round(dense[0] / attn_ms, 2),
             "note": "same kernel, every live key block of the final cache selected"},
