@@ -1207,9 +1207,12 @@ __global__ __launch_bounds__(PLAN_THREADS) void tc_plan_kernel(const int32_t *__
         // the loads below do not depend on the count: issued before the reduction waits for the ones above
         n_unm = c;
     }
-    // Long runs (PLAN_PER_MAX 64) start on multiples of four slots so that their stamps can be read 16 bytes at a time:
-    // lanes of one load touch different cache lines either way, a quarter of the loads touches them a quarter as often.
+    // Long runs (PLAN_PER_MAX 64) start on multiples of four slots so that their stamps can be read 16 bytes at a time.
+    // A thread's run is contiguous, so a load in which every lane reads from its own run touches 64 cache lines: the runs
+    // of a wavefront (contiguous too) are instead read in four pieces of 16 runs each, consecutive lanes consecutive
+    // 16 bytes, and handed to their owners through a piece of LDS that belongs to the wavefront.
     constexpr bool QUADS = PLAN_PER_MAX > 16;
+    __shared__ __attribute__((aligned(16))) int stage[QUADS ? PLAN_WAVES * 16 * PLAN_PER_MAX : 4];
     const int span = QUADS ? (((L + NB - 1) / NB + 3) & ~3) : (L + NB - 1) / NB;
     const int s0 = min(b * span, L), s1 = min(s0 + span, L);
     const int per_raw = (span + PLAN_THREADS - 1) / PLAN_THREADS;
@@ -1221,15 +1224,53 @@ __global__ __launch_bounds__(PLAN_THREADS) void tc_plan_kernel(const int32_t *__
     unsigned hreg[4] = {0, 0, 0, 0};
     if (maybe) {
         if (cached && QUADS && (((uintptr_t)st & 15) == 0)) {
+            int *wst = stage + wave * (16 * PLAN_PER_MAX);   // this wavefront's piece: 16 runs
+            const int piece = 16 * per;                       // slots of 16 runs: at most 1024, i.e. four 16-byte loads per lane
+            const int wbase = s0 + wave * 64 * per;           // first slot of the wavefront's runs (may lie beyond s1)
+            auto load_piece = [&](int c, i32x4 (&v)[4]) {
 #pragma unroll
-            for (int k = 0; k < PLAN_PER_MAX; k += 4) {
-                if (j0 + k + 3 < j1) {
-                    const i32x4 v = *(const i32x4 *)(st + j0 + k);
-                    sreg[k] = v[0]; sreg[k + 1] = v[1]; sreg[k + 2] = v[2]; sreg[k + 3] = v[3];
-                } else {
+                for (int u = 0; u < 4; ++u) {
+                    const int q = u * 64 + lane;              // quad of the piece
+                    const int slot = wbase + c * piece + 4 * q;
+                    v[u] = i32x4{0, 0, 0, 0};
+                    if (4 * q < piece) {
+                        if (slot + 3 < s1) {
+                            v[u] = *(const i32x4 *)(st + slot);
+                        } else {
 #pragma unroll
-                    for (int q = 0; q < 4; ++q) sreg[k + q] = j0 + k + q < j1 ? st[j0 + k + q] : 0;
+                            for (int e = 0; e < 4; ++e) v[u][e] = slot + e < s1 ? st[slot + e] : 0;
+                        }
+                    }
                 }
+            };
+            i32x4 cur[4], nxt[4];
+            load_piece(0, cur);
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                if (c + 1 < 4) load_piece(c + 1, nxt);        // in flight while this piece is handed over
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const int q = u * 64 + lane;
+                    if (4 * q < piece) *(i32x4 *)(wst + 4 * q) = cur[u];
+                }
+                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+                __builtin_amdgcn_wave_barrier();
+                __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+                if ((lane >> 4) == c) {                       // the owners of this piece's runs
+                    const int *mine = wst + (lane & 15) * per;
+#pragma unroll
+                    for (int k = 0; k < PLAN_PER_MAX; k += 4) {
+                        if (k < per) {
+                            const i32x4 w = *(const i32x4 *)(mine + k);
+                            sreg[k] = w[0]; sreg[k + 1] = w[1]; sreg[k + 2] = w[2]; sreg[k + 3] = w[3];
+                        }
+                    }
+                }
+                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+                __builtin_amdgcn_wave_barrier();
+                __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+#pragma unroll
+                for (int u = 0; u < 4; ++u) cur[u] = nxt[u];
             }
         } else if (cached) {
 #pragma unroll
@@ -1579,7 +1620,9 @@ static int plan_nb(int H, int C, PlanResidency pr) {
     if (nb > PLAN_NB_MAX) nb = PLAN_NB_MAX;
     if (nb < 1) nb = 1;
     for (; nb > 1; --nb) {
-        const size_t lds = plan_lds_bytes(C, nb) + 5 * 1024;
+        // static arrays: about 5 KB, and 16 KB more in the instantiation for long runs (the hand-over area of the stamps)
+        const bool long_runs = ((C + nb - 1) / nb + PLAN_THREADS - 1) / PLAN_THREADS > 16;
+        const size_t lds = plan_lds_bytes(C, nb) + (long_runs ? 21 : 5) * 1024;
         size_t per_cu = (size_t)160 * 1024 / lds;
         if (per_cu > (size_t)pr.per_cu) per_cu = (size_t)pr.per_cu;
         size_t resident = per_cu * (size_t)pr.n_cu;
