@@ -57,11 +57,12 @@ def parse():
     ap.add_argument("--ws", choices=["persistent", "scratch"], default="persistent",
                     help="TempCache workspace: kept by the caller across calls (zero-filled once; one launch less per "
                          "frame) or scratch that may hold anything")
-    ap.add_argument("--streams", type=int, choices=[1, 2], default=1,
-                    help="2: the query codes and the cross-attention path run on a second stream beside the compress "
-                         "calls.  Measured: no gain at either layer (the window-match, scoring and attention kernels "
-                         "each fill the register files of the compute units they run on, so the second stream's "
-                         "kernels wait for them anyway; at the Wan-shaped layer the extra enqueue cost shows)")
+    ap.add_argument("--streams", type=int, choices=[1, 2], default=None,
+                    help="2: the query codes and the cross-attention path (they depend on Q and the prompt only) run on a "
+                         "second stream of the same priority beside the compress calls and are joined before the step "
+                         "ends.  Default at the world-model layer (measured: -0.9 %%; the window-match and plan launches "
+                         "fill the register files of their compute units, so the second stream's kernels mostly run "
+                         "beside the apply launch); 1 at the Wan-shaped layer, where the extra enqueue cost shows")
     ap.add_argument("--cross", choices=["fused", "separate"], default="fused",
                     help="AnnCA as one launch (selection + attention) or as ann_select_cross followed by sparse_attn_fwd")
     ap.add_argument("--cand", choices=["as-is", "sorted"], default="as-is",
@@ -605,7 +606,7 @@ def run_layer(args, workload, torch, fa, np, to_dev, to_host, steps, warmup, sta
     t_gen = time.perf_counter() - t_gen
     cfg, pipe, dev_chunks = B["cfg"], B["pipe"], B["dev_chunks"]
     pipe.sorted_cand = args.cand == "sorted"
-    n_streams = args.streams
+    n_streams = args.streams if args.streams is not None else (2 if workload.startswith("cfg5") else 1)
     if n_streams == 2:
         pipe.side = torch.cuda.Stream()   # default priority
         pipe.ev_q = torch.cuda.Event()
